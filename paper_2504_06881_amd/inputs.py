@@ -1,0 +1,164 @@
+"""Seeded synthetic inputs for the tropical-convolution hot path.
+
+This module only draws random tensors of the shapes and value distributions of
+the benchmark layer configurations; it contains none of the operator's
+arithmetic and imports neither the HIP binding nor the CPU oracle, so both
+sides of a parity test can consume exactly the same host buffers.
+
+The tensors stand in for the image-classification and segmentation feature maps
+of the paper's experiments (CIFAR-sized 32x32 maps, ImageNet-style ResNet-18
+stage shapes, segmentation-encoder maps; paper Sec. 5): activations ~ N(0, 1),
+kernels uniform in a small symmetric range, upstream gradients ~ N(0, 1).
+Draw order is fixed: x, W1, [W2 for parallel], gy, [alpha, beta].
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class LayerCfg:
+    name: str
+    N: int
+    C_in: int
+    H: int
+    W: int
+    C_out: int
+    KH: int = 3
+    KW: int = 3
+    stride: int = 1
+    pad: int = 1
+    dil: int = 1
+    mode: str = "max"          # max | min | compound | parallel
+    dtype: str = "f32"         # f32 | bf16 (storage of x, w, y)
+    seed: int = 0
+    w_range: float = 1.0       # kernels ~ U(-w_range, w_range)
+
+    @property
+    def K(self) -> int:
+        return self.C_in * self.KH * self.KW
+
+    @property
+    def out_hw(self):
+        ho = (self.H + 2 * self.pad - self.dil * (self.KH - 1) - 1) // self.stride + 1
+        wo = (self.W + 2 * self.pad - self.dil * (self.KW - 1) - 1) // self.stride + 1
+        return ho, wo
+
+    @property
+    def branches(self) -> int:
+        return 2 if self.mode in ("compound", "parallel") else 1
+
+    @property
+    def candidates(self) -> int:
+        ho, wo = self.out_hw
+        return self.N * self.C_out * ho * wo * self.K
+
+    @property
+    def pairs(self) -> int:
+        """add+compare pairs, dense count (padded taps included), one per candidate per branch."""
+        return self.candidates * self.branches
+
+    def with_(self, **kw) -> "LayerCfg":
+        return replace(self, **kw)
+
+
+# The benchmark layer configurations (single tropical conv layers).
+CONFIGS: Dict[str, LayerCfg] = {c.name: c for c in [
+    LayerCfg("cfg1", 2, 3, 16, 16, 8, mode="max", seed=0, w_range=1.0),
+    LayerCfg("cfg2_main", 128, 64, 32, 32, 64, mode="compound", seed=1, w_range=0.1),
+    LayerCfg("cfg2_stem", 128, 3, 32, 32, 16, mode="compound", seed=1, w_range=0.1),
+    LayerCfg("cfg3a", 64, 64, 56, 56, 64, mode="parallel", seed=2, w_range=0.05),
+    LayerCfg("cfg3b", 64, 128, 28, 28, 256, stride=2, mode="parallel", seed=2, w_range=0.05),
+    LayerCfg("cfg3c", 64, 256, 14, 14, 256, mode="parallel", seed=2, w_range=0.05),
+    LayerCfg("cfg4a", 8, 128, 128, 128, 128, mode="compound", seed=3, w_range=0.1),
+    LayerCfg("cfg4b", 8, 256, 64, 64, 256, pad=2, dil=2, mode="compound", seed=3, w_range=0.1),
+]}
+
+
+def resnet20_layers(batch: int = 256, seed: int = 4):
+    """The 19 tropical conv layers of a ResNet-20-style net on [batch, 3, 32, 32], all parallel mode."""
+    layers = [LayerCfg("r20_stem", batch, 3, 32, 32, 16, mode="parallel", seed=seed, w_range=0.1)]
+    spec = [(16, 32, 6), (32, 16, 6), (64, 8, 6)]
+    c_prev, hw_prev = 16, 32
+    li = 0
+    for c, hw, n in spec:
+        for b in range(n):
+            first = (b == 0 and c != c_prev)
+            layers.append(LayerCfg(f"r20_conv{li}", batch, c_prev if first else c,
+                                   hw_prev if first else hw, hw_prev if first else hw, c,
+                                   stride=2 if first else 1, mode="parallel", seed=seed + 1 + li,
+                                   w_range=0.1))
+            li += 1
+        c_prev, hw_prev = c, hw
+    return layers
+
+
+def to_bf16_grid(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16-representable fp32 (ties to even)."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def _no_neg_zero(a: np.ndarray) -> np.ndarray:
+    return (a + np.float32(0.0)).astype(np.float32)
+
+
+def make_inputs(cfg: LayerCfg, alpha_beta: Optional[str] = None, integer: bool = False,
+                seed: Optional[int] = None) -> Dict[str, Optional[np.ndarray]]:
+    """Draw x, w_min, w_max, gy, alpha, beta (numpy, host) for one layer configuration.
+
+    alpha_beta: None -> alpha = beta = None (all ones); "random" -> U(-1, 1) per output
+    channel; "half" -> 0.5 each; "contrast" -> (1, -1).
+    integer: integer-valued x and w in [-4, 4] (every add exact, massive ties).
+    Weight tensors: max mode fills w_max, min mode w_min, compound one tensor returned
+    as both, parallel two independent tensors (W1 -> w_min, W2 -> w_max).
+    """
+    rng = np.random.Generator(np.random.PCG64(cfg.seed if seed is None else seed))
+    ho, wo = cfg.out_hw
+    xs = (cfg.N, cfg.C_in, cfg.H, cfg.W)
+    ws = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+
+    def draw_x():
+        if integer:
+            return rng.integers(-4, 5, size=xs).astype(np.float32)
+        return rng.standard_normal(size=xs, dtype=np.float32)
+
+    def draw_w():
+        if integer:
+            return rng.integers(-4, 5, size=ws).astype(np.float32)
+        return ((rng.random(size=ws, dtype=np.float32) * 2 - 1) * np.float32(cfg.w_range)).astype(np.float32)
+
+    x = draw_x()
+    w1 = draw_w()
+    w2 = draw_w() if cfg.mode == "parallel" else None
+    gy = rng.standard_normal(size=(cfg.N, cfg.C_out, ho, wo), dtype=np.float32)
+    alpha = beta = None
+    if alpha_beta == "random":
+        alpha = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+        beta = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+    elif alpha_beta == "half":
+        alpha = np.full(cfg.C_out, 0.5, np.float32)
+        beta = np.full(cfg.C_out, 0.5, np.float32)
+    elif alpha_beta == "contrast":
+        alpha = np.full(cfg.C_out, 1.0, np.float32)
+        beta = np.full(cfg.C_out, -1.0, np.float32)
+    elif alpha_beta is not None:
+        raise ValueError(alpha_beta)
+    if cfg.dtype == "bf16":
+        x, w1 = to_bf16_grid(x), to_bf16_grid(w1)
+        w2 = to_bf16_grid(w2) if w2 is not None else None
+    x, w1 = _no_neg_zero(x), _no_neg_zero(w1)
+    w2 = _no_neg_zero(w2) if w2 is not None else None
+    if cfg.mode == "max":
+        w_min, w_max = None, w1
+    elif cfg.mode == "min":
+        w_min, w_max = w1, None
+    elif cfg.mode == "compound":
+        w_min = w_max = w1
+    else:
+        w_min, w_max = w1, w2
+    return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)
