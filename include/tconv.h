@@ -1,0 +1,129 @@
+/*
+ * tconv.h - C ABI of the MI355X (gfx950) tropical convolution library.
+ *
+ * Operator family (paper Sec. 3.1 and 3.3).  For every output element
+ * (n, c_out, oh, ow) and every live branch the library reduces over all
+ * K = C_in*KH*KW taps of the window
+ *
+ *     y_max = max_k ( x[n, c, ih, iw] + w_max[c_out, c, i, j] )     max-plus, layer (v) MaxPlus-Max-Conv2d
+ *     y_min = min_k ( x[n, c, ih, iw] + w_min[c_out, c, i, j] )     min-plus, layer (iv) MinPlus-Min-Conv2d
+ *
+ * with k = (c*KH + i)*KW + j, ih = oh*stride_h - pad_h + i*dil_h, iw likewise
+ * (cross-correlation, as the discrete operators of Sec. 3.1 are written), and
+ *
+ *     compound:  y = alpha[c_out]*y_min + beta[c_out]*y_max,  ONE kernel feeds both branches
+ *     parallel:  y = alpha[c_out]*y_min + beta[c_out]*y_max,  kernel g1 = w_min, g2 = w_max
+ *
+ * (Sec. 3.3, Definitions "compound" and "parallel"; alpha = beta = 1 gives the
+ * direct-summation variants of App. B.4).  Padding holds the semiring identity
+ * (-inf for max-plus, +inf for min-plus, Sec. 3.1): a padded tap never wins.
+ * Ties keep the lowest k.  Every x + w is one rounded fp32 add; the combine is
+ * two rounded fp32 products and one rounded fp32 sum (no fused multiply-add).
+ * Backward routes the whole output gradient of a branch through its winning
+ * tap (the saved idx), scaled by alpha (min branch) / beta (max branch) in
+ * compound and parallel mode and unscaled in max / min mode.
+ *
+ * Conventions shared by every entry point
+ *   - Tensors are contiguous, x / grad_x NCHW, kernels OIHW, outputs NCHW
+ *     [N, C_out, H_out, W_out].  All tensor pointers are DEVICE pointers owned by
+ *     the caller; `desc` and the size outputs are HOST pointers.  The library
+ *     allocates nothing and keeps no state between calls.
+ *   - dtype selects the storage type of x, kernels, y, y_min, y_max (fp32 or
+ *     bf16; bf16 is widened exactly, all arithmetic and the index decision are
+ *     fp32, results are rounded to nearest-even on store).  gy, grad_x, grad_w,
+ *     alpha, beta are always fp32; idx_* are int32 in [0, K).
+ *   - Domain: finite values, no negative zero in x or the kernels.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on that stream and return; outputs are overwritten.
+ *   - Return value: TCONV_OK (0) or a negative tconv_status.  The library never
+ *     aborts, throws or prints.  On error nothing has been enqueued.
+ */
+#ifndef TCONV_H
+#define TCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum tconv_mode { TCONV_MAX = 0, TCONV_MIN = 1, TCONV_COMPOUND = 2, TCONV_PARALLEL = 3 };
+enum tconv_dtype { TCONV_F32 = 0, TCONV_BF16 = 1 };
+enum tconv_op { TCONV_OP_FORWARD = 0, TCONV_OP_BACKWARD_INPUT = 1, TCONV_OP_BACKWARD_WEIGHT = 2 };
+
+enum tconv_status {
+  TCONV_OK = 0,
+  TCONV_E_INVAL = -1,       /* NULL required pointer, non-positive dim, stride < 1, dil < 1, pad < 0, bad mode / dtype / op */
+  TCONV_E_SHAPE = -2,       /* H_out or W_out < 1, pad > dil*(k-1) (a window could be all padding), a tensor with >= 2^31 elements */
+  TCONV_E_WORKSPACE = -3,   /* workspace NULL or smaller than tconv_workspace_bytes() reports */
+  TCONV_E_UNSUPPORTED = -4, /* valid request this build has no kernel for */
+  TCONV_E_LAUNCH = -5       /* the HIP runtime refused a launch (hipGetLastError) */
+};
+
+typedef struct tconv_desc {
+  int32_t N, C_in, H, W;    /* input  [N, C_in, H, W]                 */
+  int32_t C_out, KH, KW;    /* kernel [C_out, C_in, KH, KW]           */
+  int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+  int32_t mode;             /* enum tconv_mode                        */
+  int32_t dtype;            /* enum tconv_dtype                       */
+} tconv_desc;
+
+/* H_out = floor((H + 2*pad_h - dil_h*(KH-1) - 1)/stride_h) + 1, W_out likewise.  Host only. */
+int tconv_out_shape(const tconv_desc* desc, int32_t* H_out, int32_t* W_out);
+
+/* Scratch bytes `op` (enum tconv_op) needs for this descriptor (may be 0).  Host only. */
+int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes);
+
+/*
+ * Forward (Sec. 3.1 layers (iv), (v); Sec. 3.3 compound / parallel).
+ *   x        [N, C_in, H, W], dtype.
+ *   w_min    kernel of the min-plus branch, w_max of the max-plus branch, dtype.
+ *            max: w_max required (w_min ignored); min: w_min required;
+ *            compound: the one shared kernel through either pointer (w_min wins if both set);
+ *            parallel: both required (g1 = w_min, g2 = w_max).
+ *   alpha, beta  fp32 [C_out] or NULL (= all ones); ignored in max / min mode.
+ *   y        required; combined output (max / min: the single branch), dtype.
+ *   y_min, y_max  optional branch outputs (NULL = not written), dtype.
+ *   idx_min, idx_max  int32, required for every live branch: lowest winning tap k.
+ *   workspace  device scratch of at least tconv_workspace_bytes(desc, TCONV_OP_FORWARD) bytes,
+ *            256-byte aligned (may be NULL when that is 0).
+ */
+int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                  const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                  int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
+/*
+ * Backward w.r.t. the input: grad_x[n, c*, ih*, iw*] += g_b for every output and
+ * live branch b, (c*, i*, j*) = unflatten(idx_b); g_min = alpha*gy, g_max = beta*gy
+ * (compound / parallel), g = gy (max / min).  grad_x fp32 [N, C_in, H, W] is
+ * overwritten.  Sums are fp32 in an unspecified order (hardware atomics).
+ */
+int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* alpha,
+                         const float* beta, const int32_t* idx_min, const int32_t* idx_max,
+                         float* grad_x, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward w.r.t. the kernel(s): grad_w_b[c_out, k*] += g_b summed over (n, oh, ow).
+ * max: grad_w_max; min: grad_w_min; parallel: both; compound: both branches add
+ * into ONE tensor, grad_w_min if non-NULL else grad_w_max.  fp32 OIHW, overwritten.
+ */
+int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* alpha,
+                          const float* beta, const int32_t* idx_min, const int32_t* idx_max,
+                          float* grad_w_min, float* grad_w_max, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/* Static, NUL-terminated description of a tconv_status value.  Host only. */
+const char* tconv_status_string(int status);
+
+/*
+ * Name of the forward kernel tconv_forward would launch for this descriptor
+ * ("tiled3x3" or "generic"), for tests and benchmarks.  Host only; NULL on a bad descriptor.
+ */
+const char* tconv_forward_kernel_name(const tconv_desc* desc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCONV_H */

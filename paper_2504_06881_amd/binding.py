@@ -1,0 +1,157 @@
+"""Thin ctypes binding of libtconv.so: argument marshalling only.
+
+Function names mirror the C ABI in ``include/tconv.h``.  Tensors are torch CUDA
+(ROCm) tensors used purely as device buffers; the launches go to torch's current
+stream.  There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtconv.so")
+
+MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3}
+DTYPES = {"f32": 0, "bf16": 1}
+OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
+SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",
+           "tconv_backward_weight", "tconv_status_string", "tconv_forward_kernel_name")
+
+
+class TconvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class tconv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "N", "C_in", "H", "W", "C_out", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
+        "dil_h", "dil_w", "mode", "dtype")]
+
+
+@dataclass(frozen=True)
+class Desc:
+    N: int
+    C_in: int
+    H: int
+    W: int
+    C_out: int
+    KH: int
+    KW: int
+    stride: Tuple[int, int] = (1, 1)
+    pad: Tuple[int, int] = (0, 0)
+    dil: Tuple[int, int] = (1, 1)
+    mode: str = "max"
+    dtype: str = "f32"
+
+    def c(self) -> tconv_desc:
+        return tconv_desc(self.N, self.C_in, self.H, self.W, self.C_out, self.KH, self.KW,
+                          self.stride[0], self.stride[1], self.pad[0], self.pad[1],
+                          self.dil[0], self.dil[1], MODES[self.mode], DTYPES[self.dtype])
+
+    @staticmethod
+    def from_cfg(cfg, mode: Optional[str] = None, dtype: Optional[str] = None) -> "Desc":
+        """From an inputs.LayerCfg (square stride / pad / dilation)."""
+        return Desc(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW,
+                    (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), (cfg.dil, cfg.dil),
+                    mode or cfg.mode, dtype or cfg.dtype)
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libtconv.so; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2504_06881_amd.build "
+                "or __graft_entry__.build()); the library has no CPU fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        D, P, I32P = ctypes.POINTER(tconv_desc), ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
+        lib.tconv_out_shape.argtypes = [D, I32P, I32P]
+        lib.tconv_workspace_bytes.argtypes = [D, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        lib.tconv_forward.argtypes = [D] + [P] * 11 + [ctypes.c_size_t, P]
+        lib.tconv_backward_input.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
+        lib.tconv_backward_weight.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv_status_string.argtypes = [ctypes.c_int]
+        lib.tconv_status_string.restype = ctypes.c_char_p
+        lib.tconv_forward_kernel_name.argtypes = [D]
+        lib.tconv_forward_kernel_name.restype = ctypes.c_char_p
+        for f in ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward",
+                  "tconv_backward_input", "tconv_backward_weight"):
+            getattr(lib, f).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().tconv_status_string(int(status)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise TconvError(rc, where)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+def tconv_out_shape(desc: Desc) -> Tuple[int, int]:
+    ho, wo = ctypes.c_int32(), ctypes.c_int32()
+    cd = desc.c()
+    _check(load().tconv_out_shape(ctypes.byref(cd), ctypes.byref(ho), ctypes.byref(wo)), "tconv_out_shape")
+    return int(ho.value), int(wo.value)
+
+
+def tconv_workspace_bytes(desc: Desc, op: str) -> int:
+    n = ctypes.c_size_t()
+    cd = desc.c()
+    _check(load().tconv_workspace_bytes(ctypes.byref(cd), OPS[op], ctypes.byref(n)), "tconv_workspace_bytes")
+    return int(n.value)
+
+
+def tconv_forward_kernel_name(desc: Desc) -> str:
+    cd = desc.c()
+    r = load().tconv_forward_kernel_name(ctypes.byref(cd))
+    if r is None:
+        raise TconvError(-1, "tconv_forward_kernel_name")
+    return r.decode()
+
+
+def tconv_forward(desc: Desc, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max,
+                  workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_forward(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha),
+                                _ptr(beta), _ptr(y), _ptr(y_min), _ptr(y_max), _ptr(idx_min),
+                                _ptr(idx_max), _ptr(workspace), wsz, _stream()), "tconv_forward")
+
+
+def tconv_backward_input(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_x, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward_input(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta),
+                                       _ptr(idx_min), _ptr(idx_max), _ptr(grad_x), _ptr(workspace),
+                                       wsz, _stream()), "tconv_backward_input")
+
+
+def tconv_backward_weight(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max,
+                          workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta),
+                                        _ptr(idx_min), _ptr(idx_max), _ptr(grad_w_min),
+                                        _ptr(grad_w_max), _ptr(workspace), wsz, _stream()),
+           "tconv_backward_weight")

@@ -1,0 +1,148 @@
+// C-ABI entry points of libtconv: argument validation and kernel selection only.
+// Every step of the hot path runs in the HIP kernels of this library; there is
+// no host-side or CPU implementation behind these calls.
+#include <stdlib.h>
+#include <string.h>
+
+#include "tconv_internal.h"
+
+using namespace tconv;
+
+namespace {
+
+// Validates the descriptor and fills the launch-time view.
+int make_params(const tconv_desc* d, Params* p) {
+  if (!d) return TCONV_E_INVAL;
+  if (d->N < 1 || d->C_in < 1 || d->H < 1 || d->W < 1 || d->C_out < 1 || d->KH < 1 || d->KW < 1)
+    return TCONV_E_INVAL;
+  if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1 || d->pad_h < 0 ||
+      d->pad_w < 0)
+    return TCONV_E_INVAL;
+  if (d->mode < TCONV_MAX || d->mode > TCONV_PARALLEL) return TCONV_E_INVAL;
+  if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16) return TCONV_E_INVAL;
+  const long long eh = (long long)d->dil_h * (d->KH - 1), ew = (long long)d->dil_w * (d->KW - 1);
+  // a window must never lie wholly in the padding
+  if (d->pad_h > eh || d->pad_w > ew) return TCONV_E_SHAPE;
+  const long long nh = (long long)d->H + 2LL * d->pad_h - eh - 1;
+  const long long nw = (long long)d->W + 2LL * d->pad_w - ew - 1;
+  if (nh < 0 || nw < 0) return TCONV_E_SHAPE;
+  const long long Ho = nh / d->stride_h + 1, Wo = nw / d->stride_w + 1;
+  const long long K = (long long)d->C_in * d->KH * d->KW;
+  const long long lim = 0x7fffffffLL;
+  if (K > lim || (long long)d->N * d->C_in * d->H * d->W > lim ||
+      (long long)d->N * d->C_out * Ho * Wo > lim || (long long)d->C_out * K > lim)
+    return TCONV_E_SHAPE;
+  p->N = d->N; p->C_in = d->C_in; p->H = d->H; p->W = d->W;
+  p->C_out = d->C_out; p->KH = d->KH; p->KW = d->KW;
+  p->sh = d->stride_h; p->sw = d->stride_w; p->ph = d->pad_h; p->pw = d->pad_w;
+  p->dh = d->dil_h; p->dw = d->dil_w;
+  p->Ho = (int)Ho; p->Wo = (int)Wo; p->K = (int)K; p->mode = d->mode;
+  return TCONV_OK;
+}
+
+// TCONV_FORWARD_KERNEL=generic forces the generic kernel (tuning / testing aid).
+bool use_tiled(const Params& p, int dtype) {
+  if (!forward_tiled3x3_supported(p, dtype)) return false;
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  return !(e && strcmp(e, "generic") == 0);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tconv_out_shape(const tconv_desc* desc, int32_t* H_out, int32_t* W_out) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!H_out || !W_out) return TCONV_E_INVAL;
+  *H_out = p.Ho;
+  *W_out = p.Wo;
+  return TCONV_OK;
+}
+
+int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_WEIGHT) return TCONV_E_INVAL;
+  *bytes = 0;  // no kernel of this build stages anything outside its inputs and outputs
+  return TCONV_OK;
+}
+
+int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                  const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                  int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                  void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!x || !y) return TCONV_E_INVAL;
+  FwdArgs a = {x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (w_min ? w_min : w_max);
+  const bool do_min = p.mode != TCONV_MAX, do_max = p.mode != TCONV_MIN;
+  if (do_min && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
+  if (do_max && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hipError_t e = use_tiled(p, desc->dtype) ? launch_forward_tiled3x3(p, desc->dtype, a, s)
+                                                 : launch_forward_generic(p, desc->dtype, a, s);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* alpha,
+                         const float* beta, const int32_t* idx_min, const int32_t* idx_max,
+                         float* grad_x, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !grad_x) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  const hipError_t e = launch_backward_input(p, a, grad_x, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* alpha,
+                          const float* beta, const int32_t* idx_min, const int32_t* idx_max,
+                          float* grad_w_min, float* grad_w_max, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  switch (p.mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+const char* tconv_status_string(int status) {
+  switch (status) {
+    case TCONV_OK: return "ok";
+    case TCONV_E_INVAL: return "invalid argument (NULL required pointer, non-positive size, bad mode, dtype or op)";
+    case TCONV_E_SHAPE: return "unsupported shape (empty output, padding larger than the dilated kernel extent, or a tensor of 2^31 or more elements)";
+    case TCONV_E_WORKSPACE: return "workspace missing or too small";
+    case TCONV_E_UNSUPPORTED: return "no kernel for this request in this build";
+    case TCONV_E_LAUNCH: return "HIP kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* tconv_forward_kernel_name(const tconv_desc* desc) {
+  Params p;
+  if (make_params(desc, &p) != TCONV_OK) return nullptr;
+  return use_tiled(p, desc->dtype) ? "tiled3x3" : "generic";
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// Internal declarations shared by the HIP translation units of libtconv (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tconv.h"
+
+namespace tconv {
+
+// Launch-time view of a validated descriptor.
+struct Params {
+  int N, C_in, H, W;
+  int C_out, KH, KW;
+  int sh, sw, ph, pw, dh, dw;
+  int Ho, Wo;
+  int K;     // C_in*KH*KW
+  int mode;  // enum tconv_mode
+};
+
+struct FwdArgs {
+  const void* x;
+  const void* w_min;  // kernel of the min-plus branch (compound: the shared kernel)
+  const void* w_max;  // kernel of the max-plus branch (compound: the shared kernel)
+  const float* alpha;
+  const float* beta;
+  void* y;
+  void* y_min;
+  void* y_max;
+  int32_t* idx_min;
+  int32_t* idx_max;
+};
+
+struct BwdArgs {
+  const float* gy;
+  const float* alpha;
+  const float* beta;
+  const int32_t* idx_min;
+  const int32_t* idx_max;
+};
+
+// bf16 storage helpers: exact widening, round-to-nearest-even narrowing.
+typedef unsigned short bf16_t;
+
+__device__ __forceinline__ float ld_f32(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const bf16_t* p, size_t i) {
+  return __uint_as_float(((unsigned)p[i]) << 16);
+}
+__device__ __forceinline__ void st_f32(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_f32(bf16_t* p, size_t i, float v) {
+  unsigned u = __float_as_uint(v);
+  if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+  p[i] = (bf16_t)(u >> 16);
+}
+
+// alpha*y_min + beta*y_max with each product and the sum rounded separately (no FMA).
+__device__ __forceinline__ float combine(float a, float ymin, float b, float ymax) {
+  return __fadd_rn(__fmul_rn(a, ymin), __fmul_rn(b, ymax));
+}
+
+// Kernel launchers (each returns hipGetLastError() after its launches).
+hipError_t launch_forward_generic(const Params& p, int dtype, const FwdArgs& a, hipStream_t s);
+bool forward_tiled3x3_supported(const Params& p, int dtype);
+hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, hipStream_t s);
+hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);
+hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad_w_min,
+                                  float* grad_w_max, hipStream_t s);
+
+}  // namespace tconv

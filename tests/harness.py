@@ -1,0 +1,132 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, run the oracle, compare.
+
+The HIP side and the oracle side only meet here, on numpy arrays; both consume the
+same seeded host buffers from ``paper_2504_06881_amd.inputs``.
+"""
+import numpy as np
+
+from oracle import tconv_oracle as orc
+from paper_2504_06881_amd import binding as tb
+
+GRAD_RTOL = 1e-5  # spec tolerance for fp32 gradients
+
+
+def oracle_shape(cfg):
+    return orc.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+
+
+def run_oracle(cfg, inp, backward=True):
+    s = oracle_shape(cfg)
+    m = cfg.mode
+    r = orc.forward(s, m, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"],
+                    out_bf16=(cfg.dtype == "bf16"))
+    if backward:
+        kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"], alpha=inp["alpha"], beta=inp["beta"])
+        r["grad_x"] = orc.backward_input(s, m, inp["gy"], **kw)
+        r["grad_w_min"], r["grad_w_max"] = orc.backward_weight(s, m, inp["gy"], **kw)
+        # magnitude of the summands of every gradient element: the scale of the tolerance
+        ab = {k: (None if inp[k] is None else np.abs(inp[k])) for k in ("alpha", "beta")}
+        kwa = dict(idx_min=r["idx_min"], idx_max=r["idx_max"], alpha=ab["alpha"], beta=ab["beta"])
+        r["grad_x_scale"] = orc.backward_input(s, m, np.abs(inp["gy"]), **kwa)
+        r["grad_w_min_scale"], r["grad_w_max_scale"] = orc.backward_weight(s, m, np.abs(inp["gy"]), **kwa)
+    return r
+
+
+def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
+    """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32)."""
+    import torch
+    dev = torch.device(device)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    d = tb.Desc.from_cfg(cfg)
+    ho, wo = tb.tconv_out_shape(d)
+    assert (ho, wo) == cfg.out_hw
+
+    def up(a, dt=torch.float32):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
+
+    x = up(inp["x"], tdt)
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"], tdt)
+    else:
+        w_min, w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
+    alpha, beta, gy = up(inp["alpha"]), up(inp["beta"]), up(inp["gy"])
+    oshape = (cfg.N, cfg.C_out, ho, wo)
+    do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+
+    def poison(dt):  # outputs start from garbage: the library must overwrite, never accumulate
+        t = torch.empty(oshape, device=dev, dtype=dt)
+        if dt == torch.int32:
+            t.fill_(-12345)
+        else:
+            t.fill_(float("nan"))
+        return t
+
+    y = poison(tdt)
+    y_min = poison(tdt) if (do_min and branch_outputs) else None
+    y_max = poison(tdt) if (do_max and branch_outputs) else None
+    idx_min = poison(torch.int32) if do_min else None
+    idx_max = poison(torch.int32) if do_max else None
+    wsz = tb.tconv_workspace_bytes(d, "forward")
+    ws = torch.empty(max(wsz, 1), device=dev, dtype=torch.uint8) if wsz else None
+    tb.tconv_forward(d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max, ws)
+    out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
+    if backward:
+        gx = torch.full((cfg.N, cfg.C_in, cfg.H, cfg.W), float("nan"), device=dev)
+        tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+        wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+        gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel") else None
+        tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
+    torch.cuda.synchronize()
+    res = {}
+    for k, v in out.items():
+        if v is None:
+            res[k] = None
+        elif v.dtype == torch.bfloat16:
+            res[k] = v.float().cpu().numpy()
+        else:
+            res[k] = v.cpu().numpy()
+    return res
+
+
+def bits(a):
+    return np.ascontiguousarray(a, np.float32).view(np.int32)
+
+
+def assert_forward_bit_exact(hip, ref, keys=("y", "y_min", "y_max", "idx_min", "idx_max"), what=""):
+    for k in keys:
+        if ref.get(k) is None:
+            assert hip.get(k) is None or k in ("y_min", "y_max"), f"{what}{k}: HIP wrote a dead branch"
+            continue
+        if hip.get(k) is None:
+            continue  # optional output not requested
+        a, b = hip[k], ref[k]
+        assert a.shape == b.shape, f"{what}{k}: shape {a.shape} vs {b.shape}"
+        same = np.array_equal(a, b) if a.dtype == np.int32 else np.array_equal(bits(a), bits(b))
+        if not same:
+            bad = np.argwhere((a != b) | (np.isnan(a.astype(np.float64)) != np.isnan(b.astype(np.float64))))
+            first = tuple(bad[0])
+            raise AssertionError(f"{what}{k}: {len(bad)} of {a.size} elements differ; first at {first}: "
+                                 f"hip={a[first]!r} oracle={b[first]!r}")
+
+
+def assert_grad_close(a, b, scale, name, rtol=GRAD_RTOL):
+    """|a - b| <= rtol * max(1, sum of |summands|) per element, and the same bound in the max norm of b."""
+    assert a.shape == b.shape, f"{name}: shape {a.shape} vs {b.shape}"
+    assert np.isfinite(a).all(), f"{name}: non-finite values (output not overwritten?)"
+    err = np.abs(a.astype(np.float64) - b)
+    bound = rtol * np.maximum(1.0, scale)
+    if not (err <= bound).all():
+        i = tuple(np.argwhere(err > bound)[0])
+        raise AssertionError(f"{name}: element {i} hip={a[i]!r} oracle={b[i]!r} |err|={err[i]:.3e} "
+                             f"> {bound[i]:.3e}")
+    assert err.max() <= rtol * max(1.0, np.abs(b).max()), f"{name}: max-norm error {err.max():.3e}"
+
+
+def assert_backward_close(hip, ref, what=""):
+    assert_grad_close(hip["grad_x"], ref["grad_x"], ref["grad_x_scale"], what + "grad_x")
+    for k in ("grad_w_min", "grad_w_max"):
+        if ref[k] is None:
+            continue
+        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)

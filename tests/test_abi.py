@@ -1,0 +1,74 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/tconv.h declares,
+and its host-only entry points validate descriptors.  No compute call is made (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2504_06881_amd import binding as tb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "tconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tconv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = tb.load()
+    names = _declared()
+    assert set(names) == set(tb.SYMBOLS), names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_out_shape_and_validation():
+    d = tb.Desc(2, 3, 16, 16, 8, 3, 3, pad=(1, 1))
+    assert tb.tconv_out_shape(d) == (16, 16)
+    assert tb.tconv_out_shape(tb.Desc(64, 128, 28, 28, 256, 3, 3, stride=(2, 2), pad=(1, 1))) == (14, 14)
+    assert tb.tconv_out_shape(tb.Desc(8, 256, 64, 64, 256, 3, 3, pad=(2, 2), dil=(2, 2))) == (64, 64)
+    assert tb.tconv_out_shape(tb.Desc(1, 1, 7, 9, 1, 2, 5, stride=(2, 3), pad=(1, 2))) == (4, 3)
+    for bad, code in [
+        (tb.Desc(0, 3, 16, 16, 8, 3, 3), -1),
+        (tb.Desc(1, 3, 16, 16, 8, 3, 3, stride=(0, 1)), -1),
+        (tb.Desc(1, 3, 16, 16, 8, 3, 3, dil=(1, 0)), -1),
+        (tb.Desc(1, 3, 16, 16, 8, 3, 3, pad=(-1, 0)), -1),
+        (tb.Desc(1, 3, 2, 2, 8, 3, 3), -2),                 # kernel larger than the input
+        (tb.Desc(1, 3, 16, 16, 8, 3, 3, pad=(3, 3)), -2),   # a window could be all padding
+        (tb.Desc(1, 3, 16, 16, 8, 1, 1, pad=(1, 1)), -2),
+        (tb.Desc(4096, 1024, 64, 64, 8, 3, 3, pad=(1, 1)), -2),  # >= 2^31 input elements
+    ]:
+        with pytest.raises(tb.TconvError) as e:
+            tb.tconv_out_shape(bad)
+        assert e.value.status == code, bad
+    cd = d.c()
+    cd.mode = 7
+    assert tb.load().tconv_out_shape(ctypes.byref(cd), None, None) == -1
+    cd = d.c()
+    assert tb.load().tconv_out_shape(ctypes.byref(cd), None, None) == -1  # NULL outputs
+
+
+def test_workspace_status_and_kernel_name():
+    d = tb.Desc(2, 3, 16, 16, 8, 3, 3, pad=(1, 1))
+    for op in ("forward", "backward_input", "backward_weight"):
+        assert tb.tconv_workspace_bytes(d, op) >= 0
+    n = ctypes.c_size_t()
+    cd = d.c()
+    assert tb.load().tconv_workspace_bytes(ctypes.byref(cd), 9, ctypes.byref(n)) == -1
+    assert tb.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -5, -99):
+        assert len(tb.status_string(s)) > 3
+    assert tb.tconv_forward_kernel_name(d) in ("tiled3x3", "generic")
+    assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2))) == "generic"
+
+
+def test_compute_entry_points_reject_null_before_touching_the_gpu():
+    lib = tb.load()
+    cd = tb.Desc(2, 3, 16, 16, 8, 3, 3, pad=(1, 1)).c()
+    assert lib.tconv_forward(ctypes.byref(cd), *([None] * 11), 0, None) == -1
+    assert lib.tconv_backward_input(ctypes.byref(cd), *([None] * 7), 0, None) == -1
+    assert lib.tconv_backward_weight(ctypes.byref(cd), *([None] * 8), 0, None) == -1
+    assert lib.tconv_forward(None, *([None] * 11), 0, None) == -1

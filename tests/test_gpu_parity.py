@@ -1,0 +1,185 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Forward outputs and indices must match bit for bit; gradients within 1e-5 of the
+magnitude of their summands (fp32 atomics sum in an unspecified order).
+"""
+import os
+
+import numpy as np
+import pytest
+
+import harness as hs
+from paper_2504_06881_amd import binding as tb
+from paper_2504_06881_amd.inputs import CONFIGS, LayerCfg, make_inputs, resnet20_layers
+
+pytestmark = pytest.mark.gpu
+
+MODES = ("max", "min", "compound", "parallel")
+
+
+def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None, seed=None):
+    inp = make_inputs(cfg, alpha_beta=alpha_beta, integer=integer, seed=seed)
+    ref = hs.run_oracle(cfg, inp)
+    old = os.environ.pop("TCONV_FORWARD_KERNEL", None)
+    try:
+        if kernel:
+            os.environ["TCONV_FORWARD_KERNEL"] = kernel
+        hip = hs.run_hip(cfg, inp, branch_outputs=branch_outputs)
+    finally:
+        os.environ.pop("TCONV_FORWARD_KERNEL", None)
+        if old is not None:
+            os.environ["TCONV_FORWARD_KERNEL"] = old
+    what = f"[{cfg.name} {cfg.mode} {cfg.dtype} ab={alpha_beta} int={integer} k={kernel}] "
+    hs.assert_forward_bit_exact(hip, ref, what=what)
+    hs.assert_backward_close(hip, ref, what=what)
+    return hip, ref
+
+
+@pytest.mark.parametrize("kernel", [None, "generic"])
+@pytest.mark.parametrize("mode", MODES)
+def test_cfg1_all_modes(mode, kernel):
+    cfg = CONFIGS["cfg1"].with_(mode=mode)
+    for ab in (None, "random", "half", "contrast"):
+        if ab and mode in ("max", "min") and ab != "random":
+            continue
+        _check(cfg, alpha_beta=ab, kernel=kernel)
+    _check(cfg, integer=True, kernel=kernel)
+    _check(cfg, branch_outputs=False, kernel=kernel)
+
+
+# Shapes chosen to span several tiles with ragged tails in every dimension the kernels block over
+# (W_out not a multiple of 8, odd C_in, C_out not a multiple of 4, odd H_out) and to cover stride,
+# dilation and padding combinations, 1x1 and non-3x3 kernels, and degenerate sizes.
+RAGGED = [
+    LayerCfg("r_3x3_s1", 3, 5, 19, 23, 7, seed=11),
+    LayerCfg("r_3x3_s1_even", 2, 6, 17, 40, 12, seed=12),
+    LayerCfg("r_3x3_s2", 3, 4, 21, 27, 6, stride=2, seed=13),
+    LayerCfg("r_3x3_s2_even", 2, 7, 32, 32, 9, stride=2, seed=14),
+    LayerCfg("r_3x3_d2", 2, 5, 18, 26, 5, pad=2, dil=2, seed=15),
+    LayerCfg("r_3x3_p0", 2, 3, 12, 20, 4, pad=0, seed=16),
+    LayerCfg("r_3x3_d2_p1", 2, 3, 15, 19, 4, pad=1, dil=2, seed=17),
+    LayerCfg("r_3x3_p2", 1, 2, 9, 13, 3, pad=2, seed=18),
+    LayerCfg("r_3x3_s2_d2", 2, 3, 20, 25, 5, stride=2, pad=2, dil=2, seed=19),
+    LayerCfg("r_1x1", 2, 9, 7, 11, 5, KH=1, KW=1, pad=0, seed=20),
+    LayerCfg("r_5x5", 2, 3, 14, 15, 4, KH=5, KW=5, pad=2, seed=21),
+    LayerCfg("r_2x3", 2, 3, 9, 10, 3, KH=2, KW=3, pad=1, seed=22),
+    LayerCfg("r_narrow", 4, 6, 8, 5, 8, seed=23),          # W_out < one 8-pixel segment
+    LayerCfg("r_w8", 4, 16, 8, 8, 16, seed=24),
+    LayerCfg("r_one", 1, 1, 1, 1, 1, KH=1, KW=1, pad=0, seed=25),
+    LayerCfg("r_one3", 1, 1, 1, 1, 1, seed=26),            # 3x3 on a single pixel: 8 of 9 taps are padding
+    LayerCfg("r_c1", 5, 1, 16, 16, 1, seed=27),
+    LayerCfg("r_wide_cout", 1, 8, 12, 16, 70, seed=28),
+    LayerCfg("r_14", 6, 10, 14, 14, 20, seed=29),          # 14x14 maps (ResNet stage shape)
+    LayerCfg("r_7", 6, 10, 7, 7, 8, seed=30),
+]
+
+
+@pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
+def test_ragged_shapes(cfg):
+    for mode in MODES:
+        c = cfg.with_(mode=mode)
+        _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+    _check(cfg.with_(mode="compound"), integer=True)
+    _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
+
+
+@pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10]], ids=lambda c: c.name)
+def test_generic_kernel_on_ragged_shapes(cfg):
+    for mode in MODES:
+        _check(cfg.with_(mode=mode), kernel="generic")
+    _check(cfg.with_(mode="compound"), integer=True, kernel="generic")
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_bf16_storage(mode):
+    for base in (RAGGED[0], RAGGED[2], RAGGED[4], CONFIGS["cfg1"]):
+        cfg = base.with_(mode=mode, dtype="bf16")
+        _check(cfg, alpha_beta="random" if mode in ("compound", "parallel") else None)
+        _check(cfg, integer=True)
+
+
+def test_forward_is_deterministic_and_stream_ordered():
+    import torch
+    cfg = RAGGED[1].with_(mode="compound")
+    inp = make_inputs(cfg)
+    a = hs.run_hip(cfg, inp, backward=False)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        b = hs.run_hip(cfg, inp, backward=False)
+    for k in ("y", "y_min", "y_max", "idx_min", "idx_max"):
+        assert np.array_equal(a[k], b[k])
+
+
+def test_error_paths_return_codes():
+    import torch
+    cfg = CONFIGS["cfg1"].with_(mode="parallel")
+    d = tb.Desc.from_cfg(cfg)
+    z = torch.zeros(16, device="cuda")
+    zi = torch.zeros(16, device="cuda", dtype=torch.int32)
+    with pytest.raises(tb.TconvError) as e:   # parallel needs both kernels
+        tb.tconv_forward(d, z, z, None, None, None, z, None, None, zi, zi)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:   # missing index output
+        tb.tconv_forward(d, z, z, z, None, None, z, None, None, None, zi)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_backward_input(d, z, None, None, zi, zi, None)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_backward_weight(d, z, None, None, zi, zi, z, None)
+    assert e.value.status == -1
+    bad = tb.Desc(1, 1, 4, 4, 1, 3, 3, pad=(3, 3))
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_out_shape(bad)
+    assert e.value.status == -2
+
+
+# ---------------------------------------------------------------- benchmark configurations, full size
+
+@pytest.mark.parametrize("name", ["cfg2_stem", "cfg2_main", "cfg3a", "cfg3b", "cfg3c"])
+def test_full_size_configs(name):
+    """Every output of the full-size layer against the oracle (the OpenMP oracle takes seconds here)."""
+    cfg = CONFIGS[name]
+    print(f"[full] {name} {cfg.mode} pairs={cfg.pairs:.3e}", flush=True)
+    _check(cfg)
+
+
+@pytest.mark.parametrize("name,dtype", [("cfg4a", "f32"), ("cfg4a", "bf16"), ("cfg4b", "f32"), ("cfg4b", "bf16")])
+def test_segmentation_configs_sampled(name, dtype):
+    """Full-size launch; images 0 and N-1 are compared output by output with the oracle, and the
+    remaining images through properties that hold at any size (index validity, gradient mass)."""
+    cfg = CONFIGS[name].with_(dtype=dtype)
+    print(f"[sampled] {name} {dtype} pairs={cfg.pairs:.3e}", flush=True)
+    inp = make_inputs(cfg)
+    hip = hs.run_hip(cfg, inp)
+    for n in (0, cfg.N - 1):
+        sub = cfg.with_(N=1)
+        sinp = dict(inp, x=inp["x"][n:n + 1], gy=inp["gy"][n:n + 1])
+        ref = hs.run_oracle(sub, sinp)
+        part = {k: (None if v is None else v[n:n + 1]) for k, v in hip.items() if not k.startswith("grad_w")}
+        hs.assert_forward_bit_exact(part, ref, what=f"[{name} {dtype} n={n}] ")
+        hs.assert_grad_close(part["grad_x"], ref["grad_x"], ref["grad_x_scale"], f"[{name} n={n}] grad_x")
+    for k in ("idx_min", "idx_max"):
+        assert hip[k].min() >= 0 and hip[k].max() < cfg.K
+    tot = 2.0 * inp["gy"].astype(np.float64).sum()
+    scale = 2.0 * np.abs(inp["gy"]).astype(np.float64).sum()
+    assert abs(hip["grad_x"].astype(np.float64).sum() - tot) <= 1e-5 * scale
+    assert abs(hip["grad_w_min"].astype(np.float64).sum() - tot) <= 1e-5 * scale
+
+
+def test_segmentation_weight_gradient_on_a_slice():
+    """grad_w needs every image, so it is compared on a two-image slice of the segmentation layers."""
+    for name in ("cfg4a", "cfg4b"):
+        cfg = CONFIGS[name].with_(N=2)
+        _check(cfg)
+
+
+def test_resnet20_layers_one_each():
+    """One layer of each distinct shape of the all-parallel ResNet-20-style stack, batch 32."""
+    seen = set()
+    for cfg in resnet20_layers(batch=32):
+        key = (cfg.C_in, cfg.H, cfg.C_out, cfg.stride)
+        if key in seen:
+            continue
+        seen.add(key)
+        _check(cfg)
