@@ -66,7 +66,9 @@ int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_WEIGHT) return TCONV_E_INVAL;
-  *bytes = 0;  // no kernel of this build stages anything outside its inputs and outputs
+  *bytes = 0;
+  // only the tiled forward kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
+  if (op == TCONV_OP_FORWARD && use_tiled(p, desc->dtype)) *bytes = forward_tiled3x3_workspace(p, desc->dtype);
   return TCONV_OK;
 }
 
@@ -74,7 +76,6 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
                   const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
                   int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
                   void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
@@ -85,8 +86,15 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
   if (do_min && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
   if (do_max && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
   hipStream_t s = (hipStream_t)hip_stream;
-  const hipError_t e = use_tiled(p, desc->dtype) ? launch_forward_tiled3x3(p, desc->dtype, a, s)
-                                                 : launch_forward_generic(p, desc->dtype, a, s);
+  hipError_t e;
+  if (use_tiled(p, desc->dtype)) {
+    const size_t need = forward_tiled3x3_workspace(p, desc->dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)))
+      return TCONV_E_WORKSPACE;
+    e = launch_forward_tiled3x3(p, desc->dtype, a, workspace, s);
+  } else {
+    e = launch_forward_generic(p, desc->dtype, a, s);
+  }
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 

@@ -1,199 +1,63 @@
-// Tiled forward kernel for 3x3 tropical convolutions on gfx950: a VALU "semiring GEMM".
+// Tiled forward kernel for 3x3, stride-1 tropical convolutions on gfx950: a VALU "semiring GEMM".
 //
-// Operator: paper Sec. 3.1 layers (iv) / (v) (one min / max over all C_in*9 taps of
-// x + w) and the Sec. 3.3 compound (one shared add feeds both reductions, Sec. 3.5
-// closing remark) and parallel combinations.  The semiring has no multiply, so the
-// matrix cores do not apply; the kernel is built for the vector ALUs instead:
+// Operator: paper Sec. 3.1 layers (iv) / (v) (one min / max over all C_in*9 taps of x + w) and the
+// Sec. 3.3 compound (one shared add feeds both reductions, Sec. 3.5 closing remark) and parallel
+// combinations.  The semiring has no multiply, so the matrix cores do not apply; the kernel is
+// built for the vector ALUs:
 //
-//  * One lane owns a row segment of 8 consecutive output pixels and TN output
-//    channels: 8*TN running extrema (x2 branches) live in VGPRs for the whole K loop.
-//  * The TN*18 kernel values of a channel pair are wave-uniform: they are fetched
-//    with scalar loads straight from the OIHW tensor (k is contiguous per c_out) into
-//    SGPRs and enter v_add_f32 as the scalar operand - no LDS, no VGPRs, no repacking.
-//  * The 3 x (7S+2D+1) input values a lane needs per channel are loaded once into
-//    VGPRs (implicit im2col: unaligned 16-byte loads over the always-valid core
-//    columns, clamped single loads for the halo columns) and reused for all 9 taps,
-//    8 pixels and TN channels.  Out-of-image taps are turned into NaN with one OR per
-//    loaded value; fmaxf / fminf / ordered compares ignore NaN, so a padded tap can
-//    never win in either branch and costs nothing in the inner loop.
-//  * Inner loop per pair of consecutive taps ("step"): 2 adds, then per branch
-//    v_max3_f32 / v_min3_f32 (two candidates per instruction), one compare and one
-//    select that records the STEP number.  The exact tap (first or second of the
-//    step) is recovered after the K loop by re-evaluating the step's first tap and
-//    comparing it with the extremum: equal -> that tap (lowest index wins ties),
-//    else the second.  Steps partition k in ascending order and updates are strict,
-//    so the recorded step is the one holding the lowest winning k.
-//  * The 4 waves of a workgroup share the pixel segments and differ in c_out group,
-//    so their x loads hit the same L1 lines; there is no LDS use and no barrier.
-#include "tconv_internal.h"
+//  * A lane owns a row segment of 8 consecutive output pixels and 4 output channels: 32 running
+//    extrema per branch stay in VGPRs for the whole K loop.  The 4 waves of a workgroup share the
+//    pixel segments (same x lines in L1) and differ in output-channel group.  No LDS, no barrier.
+//  * Kernel values are wave-uniform: scalar loads straight from the OIHW tensor (k is contiguous
+//    per c_out) put the 18 values of a channel pair in SGPRs, where they are the scalar operand
+//    of v_add_f32 - no repacking pass, no VGPRs, no LDS.
+//  * Implicit im2col: per channel a lane loads 3 rows x (8 + 2*dil) input values once (raw buffer
+//    loads: wave-uniform descriptor + 32-bit lane offset + uniform channel offset) and reuses them
+//    for 9 taps x 8 pixels x 4 channels.  Padding becomes NaN with one OR per loaded value;
+//    v_max/v_min/v_max3/v_min3 return the non-NaN operand, so a padded tap never wins in either
+//    branch and costs nothing in the inner loop.
+//  * Inner blocks (tile_blocks_gfx950.h, hand-scheduled): one accumulator walks two channels
+//    (18 taps) with 18 adds, v_max3/v_min3 chains, and 2 compares + 2 selects per branch that
+//    record the winning CHANNEL.  After the K loop the epilogue re-evaluates the 9 taps of that
+//    channel and takes the first that equals the extremum: exactly the lowest winning tap.
+//  * Register-resident software pipeline: the six x rows of a channel pair occupy six register
+//    slots.  Pixels are walked left to right, so the low columns of every slot die first; they
+//    are re-loaded for the NEXT channel pair in the middle of the current one, the high columns
+//    at its end, and each half is masked just before its first use.
+#include <stdlib.h>
+
+#include "tile_common.h"
+// after tile_common.h: the blocks header relies on the HIP runtime declarations included there
+#include <tile_blocks_gfx950.h>
 
 namespace tconv {
 namespace {
 
-constexpr int PX = 8;     // output pixels per lane
-constexpr int WAVES = 4;  // waves per workgroup, each a different c_out group
+using namespace tile;
 
-typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
-typedef float f2u __attribute__((ext_vector_type(2), aligned(4)));
-typedef unsigned u4u __attribute__((ext_vector_type(4), aligned(2)));
-typedef unsigned u2u __attribute__((ext_vector_type(2), aligned(2)));
+constexpr int TN = 4;  // output channels per lane
 
-__device__ __forceinline__ float nan_or(float v, unsigned m) {
-  return __uint_as_float(__float_as_uint(v) | m);
+// 9 x values of pixel q for the 3x3 taps of one channel: rows[i][q + j*D]
+template <int D, int XR>
+__device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][XR], int ch, int q) {
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+#pragma unroll
+    for (int j = 0; j < 3; ++j) out[i * 3 + j] = rows[ch * 3 + i][q + j * D];
 }
 
-// ---- contiguous run of N input values starting at p (4-byte aligned only) -> fp32 registers
-template <int N>
-__device__ __forceinline__ void load_run(float* dst, const float* p) {
-  if constexpr (N >= 4) {
-    const f4u v = *(const f4u*)p;
-    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-    load_run<N - 4>(dst + 4, p + 4);
-  } else if constexpr (N >= 2) {
-    const f2u v = *(const f2u*)p;
-    dst[0] = v.x; dst[1] = v.y;
-    load_run<N - 2>(dst + 2, p + 2);
-  } else if constexpr (N == 1) {
-    dst[0] = *p;
-  }
-}
-
-// bf16 storage: the run is loaded as raw 16-bit values (2-byte aligned) and widened exactly.
-template <int N>
-__device__ __forceinline__ void load_run(float* dst, const bf16_t* p) {
-#pragma unroll
-  for (int i = 0; i < N; ++i) dst[i] = __uint_as_float(((unsigned)p[i]) << 16);
-}
-
-__device__ __forceinline__ float ld1(const float* p) { return *p; }
-__device__ __forceinline__ float ld1(const bf16_t* p) { return __uint_as_float(((unsigned)*p) << 16); }
-
-template <int MODE, int S, int D, int TN, typename T>
-struct Tile {
-  static constexpr bool DO_MIN = (MODE != TCONV_MAX);
-  static constexpr bool DO_MAX = (MODE != TCONV_MIN);
-  static constexpr bool TWO_W = (MODE == TCONV_PARALLEL);
-  static constexpr int XR = 7 * S + 2 * D + 1;  // input columns a lane touches per row
-  static constexpr int NC = 7 * S + 1;          // core columns [D, D+NC): always inside the row
-
-  float bmax[TN][PX], bmin[TN][PX];
-  int imax[TN][PX], imin[TN][PX];
-
-  __device__ __forceinline__ void init() {
-#pragma unroll
-    for (int c = 0; c < TN; ++c)
-#pragma unroll
-      for (int q = 0; q < PX; ++q) {
-        bmax[c][q] = -INFINITY; bmin[c][q] = INFINITY;
-        imax[c][q] = 0; imin[c][q] = 0;
-      }
-  }
-
-  // One row of one channel: core run + clamped halo singles, then NaN out what is padding.
-  // cb + ro addresses the first core column (iw0 + D) of the (clamped) row: cb is the wave-uniform
-  // channel base, ro the lane's byte offset; hoff[h] are the clamped byte offsets of the 2D halo
-  // columns relative to that (possibly negative; the 32-bit sum ro + hoff[h] never is);
-  // mrow / mhalo are all-ones where the row / halo column is padding.
-  __device__ __forceinline__ void load_row(float (&xr)[XR], const char* cb, unsigned ro,
-                                           const int (&hoff)[2 * D], unsigned mrow,
-                                           const unsigned (&mhalo)[2 * D]) {
-    load_run<NC>(&xr[D], (const T*)(cb + ro));
-#pragma unroll
-    for (int h = 0; h < D; ++h) {
-      xr[h] = ld1((const T*)(cb + (ro + (unsigned)hoff[h])));
-      xr[D + NC + h] = ld1((const T*)(cb + (ro + (unsigned)hoff[D + h])));
-    }
-#pragma unroll
-    for (int o = 0; o < XR; ++o) {
-      unsigned m = mrow;
-      if (o < D) m |= mhalo[o];
-      if (o >= D + NC) m |= mhalo[o - NC];
-      xr[o] = nan_or(xr[o], m);
-    }
-  }
-
-  // One step = two consecutive taps (a, b) for all pixels and channels of the lane.
-  __device__ __forceinline__ void step(const float (&xa)[PX], const float (&xb)[PX],
-                                       const float (&wa_min)[TN], const float (&wb_min)[TN],
-                                       const float (&wa_max)[TN], const float (&wb_max)[TN], int t) {
-#pragma unroll
-    for (int c = 0; c < TN; ++c)
-#pragma unroll
-      for (int q = 0; q < PX; ++q) {
-        if (TWO_W) {
-          const float sa1 = xa[q] + wa_min[c], sb1 = xb[q] + wb_min[c];
-          const float sa2 = xa[q] + wa_max[c], sb2 = xb[q] + wb_max[c];
-          const float nmn = fminf(fminf(bmin[c][q], sa1), sb1);
-          imin[c][q] = (nmn < bmin[c][q]) ? t : imin[c][q];
-          bmin[c][q] = nmn;
-          const float nmx = fmaxf(fmaxf(bmax[c][q], sa2), sb2);
-          imax[c][q] = (nmx > bmax[c][q]) ? t : imax[c][q];
-          bmax[c][q] = nmx;
-        } else {
-          const float sa = xa[q] + (DO_MAX ? wa_max[c] : wa_min[c]);
-          const float sb = xb[q] + (DO_MAX ? wb_max[c] : wb_min[c]);
-          if (DO_MAX) {
-            const float nmx = fmaxf(fmaxf(bmax[c][q], sa), sb);
-            imax[c][q] = (nmx > bmax[c][q]) ? t : imax[c][q];
-            bmax[c][q] = nmx;
-          }
-          if (DO_MIN) {
-            const float nmn = fminf(fminf(bmin[c][q], sa), sb);
-            imin[c][q] = (nmn < bmin[c][q]) ? t : imin[c][q];
-            bmin[c][q] = nmn;
-          }
-        }
-      }
-  }
-
-  // Last tap of an odd K: a step with a single candidate.
-  __device__ __forceinline__ void step1(const float (&xa)[PX], const float (&wa_min)[TN],
-                                        const float (&wa_max)[TN], int t) {
-#pragma unroll
-    for (int c = 0; c < TN; ++c)
-#pragma unroll
-      for (int q = 0; q < PX; ++q) {
-        if (DO_MIN) {
-          const float s = xa[q] + ((TWO_W || !DO_MAX) ? wa_min[c] : wa_max[c]);  // compound: shared kernel
-          const float nmn = fminf(bmin[c][q], s);
-          imin[c][q] = (nmn < bmin[c][q]) ? t : imin[c][q];
-          bmin[c][q] = nmn;
-        }
-        if (DO_MAX) {
-          const float s = xa[q] + wa_max[c];
-          const float nmx = fmaxf(bmax[c][q], s);
-          imax[c][q] = (nmx > bmax[c][q]) ? t : imax[c][q];
-          bmax[c][q] = nmx;
-        }
-      }
-  }
-};
-
-// The 8 x values of tap (i, j) within a channel's three row registers.
-template <int S, int D, int XR>
-__device__ __forceinline__ void tap_x(float (&out)[PX], const float (&row)[XR], int j) {
-#pragma unroll
-  for (int q = 0; q < PX; ++q) out[q] = row[q * S + j * D];
-}
-
-template <typename T>
-__device__ __forceinline__ float wld(const T* w, int k);
-template <>
-__device__ __forceinline__ float wld<float>(const float* w, int k) { return w[k]; }
-template <>
-__device__ __forceinline__ float wld<bf16_t>(const bf16_t* w, int k) {
-  return __uint_as_float(((unsigned)w[k]) << 16);
-}
-
-template <int MODE, int S, int D, int TN, typename T>
-__global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
-    Params p, const T* __restrict__ x, const T* __restrict__ w_min, const T* __restrict__ w_max,
-    const float* __restrict__ alpha, const float* __restrict__ beta, T* __restrict__ y,
-    T* __restrict__ y_min, T* __restrict__ y_max, int32_t* __restrict__ idx_min,
-    int32_t* __restrict__ idx_max, int segs, int n_units, int n_groups) {
-  using TL = Tile<MODE, S, D, TN, T>;
-  constexpr bool DO_MIN = TL::DO_MIN, DO_MAX = TL::DO_MAX, TWO_W = TL::TWO_W;
-  constexpr int XR = TL::XR, NC = TL::NC;
+template <int MODE, int D, typename TO>
+__global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
+    Params p, const float* __restrict__ x, const float* __restrict__ w_min,
+    const float* __restrict__ w_max, const float* __restrict__ alpha,
+    const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
+    TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
+    int n_units, int n_groups, int dbg) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr int XR = 8 + 2 * D;  // input columns a lane touches per row
+  constexpr int H1 = D + 4;      // columns [0, H1): left halo + first half of the core
+  constexpr int P1 = D + 3;      // first-half columns are dead once pixel P1 is done
+  constexpr int P2 = 4 - D;      // second-half columns are first read by pixel P2
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
@@ -213,37 +77,34 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   // pixels it shares with its neighbour are computed twice and stored once
   const int ow_nom = seg * PX;
   const int ow0 = min(ow_nom, p.Wo - PX);
-  const int first_q = ow_nom - ow0;  // pixels q < first_q belong to the previous segment
+  const int first_q = ow_nom - ow0;
 
   // ---- channel-independent addressing and padding masks
-  const int iw0 = ow0 * S - p.pw;
+  const int iw0 = ow0 - p.pw;  // input column of register column 0
   const size_t HW = (size_t)p.H * p.W;
-  // per-lane byte offsets (32-bit: the tensor is below 4 GiB) added to a wave-uniform channel base
-  unsigned roff[3];
-  unsigned mrow[3];
+  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
+  unsigned roff[3];  // byte offset of the first core column (iw0 + D >= 0) of each (clamped) row
+  unsigned mrow[3];  // all-ones where the row is padding
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
-    const int ih = oh * S - p.ph + i * D;
-    const bool v = (ih >= 0 && ih < p.H);
-    mrow[i] = v ? 0u : 0xffffffffu;
+    const int ih = oh - p.ph + i * D;
+    mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
     const int ihc = min(max(ih, 0), p.H - 1);
-    // offset of the lane's first CORE column (iw0 + D >= 0 because pad_w <= D): never negative
-    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(T));
+    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(float));
   }
-  int hoff[2 * D];
-  unsigned mhalo[2 * D];
+  int hoff[2 * D];         // clamped byte offsets of the halo columns relative to roff
+  unsigned mhalo[2 * D];   // all-ones where the halo column is padding
 #pragma unroll
   for (int h = 0; h < 2 * D; ++h) {
-    const int o = (h < D) ? h : h + NC;
+    const int o = (h < D) ? h : h + 8;
     const int iw = iw0 + o;
-    const bool v = (iw >= 0 && iw < p.W);
-    mhalo[h] = v ? 0u : 0xffffffffu;
-    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(T);  // relative to the core start
+    mhalo[h] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
+    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
   }
 
-  // ---- kernel rows of this wave's TN output channels (wave-uniform pointers)
-  const T* wr_min[TN];
-  const T* wr_max[TN];
+  // ---- kernel rows of this wave's output channels (wave-uniform)
+  const float* wr_min[TN];
+  const float* wr_max[TN];
 #pragma unroll
   for (int c = 0; c < TN; ++c) {
     const int co = min(co0 + c, p.C_out - 1);
@@ -251,173 +112,239 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     wr_max[c] = DO_MAX ? w_max + (size_t)co * p.K : nullptr;
   }
 
-  TL acc;
-  acc.init();
+  float bmax[TN][PX], bmin[TN][PX];
+  int imax[TN][PX], imin[TN][PX];
+#pragma unroll
+  for (int c = 0; c < TN; ++c)
+#pragma unroll
+    for (int q = 0; q < PX; ++q) {
+      bmax[c][q] = -INFINITY; bmin[c][q] = INFINITY;
+      imax[c][q] = 0; imin[c][q] = 0;
+    }
 
-  // ---- main loop over channel pairs: 18 taps = 9 steps.  Software pipeline, in program order:
-  //  * the six input rows of a pair (2 channels x 3 kernel rows; tap t lives in row slot t/3)
-  //    sit in six register slots; a slot is re-loaded for the NEXT pair right after the step
-  //    that last reads it, and its padding mask is applied just before its first use;
-  //  * the kernel values of a step (2 taps x TN channels, SGPRs) are fetched one step ahead.
-  const int npairs = p.C_in >> 1;
-  constexpr int WMN = (TWO_W || !DO_MAX) ? TN : 1;
-  constexpr int WMX = DO_MAX ? TN : 1;
-  float xs[6][XR];
-  auto issue_row = [&](int slot, int cp) {
-    const char* cb = (const char*)(x + (size_t)(2 * cp + slot / 3) * HW);  // wave-uniform
-    const unsigned ro = roff[slot % 3];
-    load_run<NC>(&xs[slot][D], (const T*)(cb + ro));
+  // ---- main loop over channel pairs (cA = 2*du, cB = 2*du + 1; an odd C_in gets a virtual last
+  // channel whose x is all NaN)
+  const int ndu = (dbg & 2) ? 0 : (p.C_in + 1) >> 1;
+  float xs[6][XR];  // slot = 3*(channel parity) + kernel row
+
+  auto chan_soff = [&](int c) -> unsigned {  // wave-uniform byte offset of channel c (clamped)
+    return (unsigned)((size_t)min(c, p.C_in - 1) * HW * sizeof(float));
+  };
+  auto issue_first = [&](int du) {  // left halo + first 4 core columns of all six rows
 #pragma unroll
-    for (int h = 0; h < D; ++h) {
-      xs[slot][h] = ld1((const T*)(cb + (ro + (unsigned)hoff[h])));
-      xs[slot][D + NC + h] = ld1((const T*)(cb + (ro + (unsigned)hoff[D + h])));
+    for (int sl = 0; sl < 6; ++sl) {
+      const unsigned soff = chan_soff(2 * du + sl / 3);
+      const unsigned ro = roff[sl % 3];
+      load_run<4, float>(&xs[sl][D], xres, ro, soff);
+#pragma unroll
+      for (int h = 0; h < D; ++h) xs[sl][h] = load_one<float>(xres, ro + (unsigned)hoff[h], soff);
     }
   };
-  auto finalize_row = [&](int slot) {
-    const unsigned mr = mrow[slot % 3];
+  auto issue_second = [&](int du) {  // last 4 core columns + right halo
 #pragma unroll
-    for (int o = 0; o < XR; ++o) {
-      unsigned m = mr;
-      if (o < D) m |= mhalo[o];
-      if (o >= D + NC) m |= mhalo[o - NC];
-      xs[slot][o] = nan_or(xs[slot][o], m);
+    for (int sl = 0; sl < 6; ++sl) {
+      const unsigned soff = chan_soff(2 * du + sl / 3);
+      const unsigned ro = roff[sl % 3];
+      load_run<4, float>(&xs[sl][D + 4], xres, ro + 16u, soff);
+#pragma unroll
+      for (int h = 0; h < D; ++h) xs[sl][D + 8 + h] = load_one<float>(xres, ro + (unsigned)hoff[D + h], soff);
     }
   };
-  auto load_w = [&](float (&wmn)[WMN][2], float (&wmx)[WMX][2], int k) {
+  auto mask_cols = [&](int lo, int hi, unsigned mB) {  // padding -> NaN for columns [lo, hi)
 #pragma unroll
-    for (int c = 0; c < TN; ++c) {
-      if (DO_MAX) { wmx[c][0] = wld<T>(wr_max[c], k); wmx[c][1] = wld<T>(wr_max[c], k + 1); }
-      if (TWO_W || !DO_MAX) { wmn[c][0] = wld<T>(wr_min[c], k); wmn[c][1] = wld<T>(wr_min[c], k + 1); }
+    for (int sl = 0; sl < 6; ++sl) {
+      const unsigned mr = mrow[sl % 3] | (sl >= 3 ? mB : 0u);
+#pragma unroll
+      for (int o = 0; o < XR; ++o) {
+        if (o < lo || o >= hi) continue;
+        unsigned m = mr;
+        if (o < D) m |= mhalo[o];
+        if (o >= D + 8) m |= mhalo[o - 8];
+        xs[sl][o] = nan_or(xs[sl][o], m);
+      }
     }
   };
-  float wc_mn[WMN][2], wc_mx[WMX][2];
-  if (npairs > 0) {
+  // 18 kernel values (channels cA, cB) of output channel slot c; the offsets are laundered so that
+  // every block re-loads them (SGPRs are too few to keep all four channels' values live)
+  auto load_w = [&](float (&wv)[18], const float* row, int cA, int cB) {
+    const float* pa = row + launder_uniform(cA * 9);
+    const float* pb = row + launder_uniform(cB * 9);
 #pragma unroll
-    for (int r = 0; r < 6; ++r) issue_row(r, 0);
-    load_w(wc_mn, wc_mx, 0);
+    for (int t = 0; t < 9; ++t) { wv[t] = pa[t]; wv[9 + t] = pb[t]; }
+  };
+
+  if (ndu > 0) {
+    issue_first(0);
+    issue_second(0);
   }
-  for (int cp = 0; cp < npairs; ++cp) {
-    const int cpn = min(cp + 1, npairs - 1);  // past the end: re-load the last pair (unused, in bounds)
-    const int t0 = cp * 9;
+  for (int du = 0; du < ndu; ++du) {
+    const int dn = min(du + 1, ndu - 1);  // past the end: re-load the last pair (unused, in bounds)
+    const int cA = 2 * du, cBv = 2 * du + 1;
+    const int cB = min(cBv, p.C_in - 1);
+    const unsigned mB = (cBv < p.C_in) ? 0u : 0xffffffffu;
+    const int tA = cA, tB = cBv;
+    mask_cols(0, H1, mB);
+    if (MODE == TCONV_COMPOUND) {
+      float wc[18], wn[18];
+      load_w(wc, wr_max[0], cA, cB);
 #pragma unroll
-    for (int s = 0; s < 9; ++s) {
-      const int ta = 2 * s, tb = 2 * s + 1;
-      float wn_mn[WMN][2], wn_mx[WMX][2];
-      load_w(wn_mn, wn_mx, (s < 8) ? cp * 18 + 2 * s + 2 : cpn * 18);
-#pragma unroll
-      for (int r = 0; r < 6; ++r)
-        if ((3 * r) / 2 == s) finalize_row(r);
-      float xa[PX], xb[PX];
-      tap_x<S, D, XR>(xa, xs[ta / 3], ta % 3);
-      tap_x<S, D, XR>(xb, xs[tb / 3], tb % 3);
-      float wa1[TN], wb1[TN], wa2[TN], wb2[TN];
-#pragma unroll
-      for (int c = 0; c < TN; ++c) {
-        wa2[c] = DO_MAX ? wc_mx[DO_MAX ? c : 0][0] : 0.f;
-        wb2[c] = DO_MAX ? wc_mx[DO_MAX ? c : 0][1] : 0.f;
-        wa1[c] = (TWO_W || !DO_MAX) ? wc_mn[(TWO_W || !DO_MAX) ? c : 0][0] : 0.f;
-        wb1[c] = (TWO_W || !DO_MAX) ? wc_mn[(TWO_W || !DO_MAX) ? c : 0][1] : 0.f;
-      }
-      acc.step(xa, xb, wa1, wb1, wa2, wb2, t0 + s);
-#pragma unroll
-      for (int r = 0; r < 6; ++r)
-        if ((3 * r + 2) / 2 == s) issue_row(r, cpn);
-      __builtin_amdgcn_sched_barrier(0);  // keep the hand-made pipeline: nothing moves across a step
-#pragma unroll
-      for (int c = 0; c < TN; ++c) {
-        if (DO_MAX) { wc_mx[c][0] = wn_mx[c][0]; wc_mx[c][1] = wn_mx[c][1]; }
-        if (TWO_W || !DO_MAX) { wc_mn[c][0] = wn_mn[c][0]; wc_mn[c][1] = wn_mn[c][1]; }
-      }
-    }
-  }
-  if (p.C_in & 1) {  // odd C_in: the last channel alone, 4 full steps and a single-candidate step
-    const int cl = p.C_in - 1;
-    float wmn[TWO_W || !DO_MAX ? TN : 1][9], wmx[DO_MAX ? TN : 1][9];
-#pragma unroll
-    for (int c = 0; c < TN; ++c)
-#pragma unroll
-      for (int t = 0; t < 9; ++t) {
-        if (DO_MAX) wmx[c][t] = wld<T>(wr_max[c], cl * 9 + t);
-        if (TWO_W || !DO_MAX) wmn[c][t] = wld<T>(wr_min[c], cl * 9 + t);
-      }
-    float xs1[3][XR];
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-      acc.load_row(xs1[i], (const char*)(x + (size_t)cl * HW), roff[i], hoff, mrow[i], mhalo);
-    const int t0 = npairs * 9;
-#pragma unroll
-    for (int s = 0; s < 5; ++s) {
-      const int ta = 2 * s, tb = 2 * s + 1;
-      float xa[PX], xb[PX];
-      float wa1[TN], wb1[TN], wa2[TN], wb2[TN];
-      tap_x<S, D, XR>(xa, xs1[ta / 3], ta % 3);
-#pragma unroll
-      for (int c = 0; c < TN; ++c) {
-        wa2[c] = DO_MAX ? wmx[c][ta] : 0.f;
-        wa1[c] = (TWO_W || !DO_MAX) ? wmn[TWO_W || !DO_MAX ? c : 0][ta] : 0.f;
-      }
-      if (s < 4) {
-        tap_x<S, D, XR>(xb, xs1[tb / 3], tb % 3);
+      for (int q = 0; q < PX; ++q) {
+        if (q == P2) mask_cols(H1, XR, mB);
+        float xA[9], xB[9];
+        taps_of<D, XR>(xA, xs, 0, q);
+        taps_of<D, XR>(xB, xs, 1, q);
 #pragma unroll
         for (int c = 0; c < TN; ++c) {
-          wb2[c] = DO_MAX ? wmx[c][tb] : 0.f;
-          wb1[c] = (TWO_W || !DO_MAX) ? wmn[TWO_W || !DO_MAX ? c : 0][tb] : 0.f;
+          load_w(wn, wr_max[(c + 1) % TN], cA, cB);
+          float wA[9], wB[9];
+#pragma unroll
+          for (int t = 0; t < 9; ++t) { wA[t] = wc[t]; wB[t] = wc[9 + t]; }
+          blk_both(bmax[c][q], bmin[c][q], imax[c][q], imin[c][q], xA, xB, wA, wB, tA, tB);
+#pragma unroll
+          for (int t = 0; t < 18; ++t) wc[t] = wn[t];
         }
-        acc.step(xa, xb, wa1, wb1, wa2, wb2, t0 + s);
-      } else {
-        acc.step1(xa, wa1, wa2, t0 + s);
+        if (q == P1) issue_first(dn);
+      }
+    } else {
+      // single-branch blocks cover two pixels; parallel mode runs a max block and a min block
+      constexpr int NB = (MODE == TCONV_PARALLEL) ? 2 : 1;
+      float wc[18], wn[18];
+      load_w(wc, DO_MAX ? wr_max[0] : wr_min[0], cA, cB);
+#pragma unroll
+      for (int q = 0; q < PX; q += 2) {
+        if (q == (P2 & ~1)) mask_cols(H1, XR, mB);
+        float xA0[9], xB0[9], xA1[9], xB1[9];
+        taps_of<D, XR>(xA0, xs, 0, q);
+        taps_of<D, XR>(xB0, xs, 1, q);
+        taps_of<D, XR>(xA1, xs, 0, q + 1);
+        taps_of<D, XR>(xB1, xs, 1, q + 1);
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const bool is_max = (MODE == TCONV_MAX) || (MODE == TCONV_PARALLEL && b == 0);
+            // next block in program order: other branch of the same channel, or next channel
+            const int cn = (b == NB - 1) ? (c + 1) % TN : c;
+            const bool next_is_max = (MODE == TCONV_MAX) || (MODE == TCONV_PARALLEL && ((b + 1) % NB) == 0);
+            load_w(wn, next_is_max ? wr_max[cn] : wr_min[cn], cA, cB);
+            float wA[9], wB[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) { wA[t] = wc[t]; wB[t] = wc[9 + t]; }
+            if (is_max)
+              blk_max2(bmax[c][q], imax[c][q], bmax[c][q + 1], imax[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
+            else
+              blk_min2(bmin[c][q], imin[c][q], bmin[c][q + 1], imin[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
+#pragma unroll
+            for (int t = 0; t < 18; ++t) wc[t] = wn[t];
+          }
+        if (q == (P1 & ~1)) issue_first(dn);
       }
     }
+    issue_second(dn);
   }
 
-  // ---- epilogue: exact tap index of every extremum, combine, store
+  // ---- epilogue: exact tap of every extremum (first tap of the winning channel, in k order, whose
+  // sum equals it), combine, store.  Each lane writes its 8 consecutive outputs with 16-byte stores.
   if (!unit_ok) return;
-  const T* xn = x + (size_t)n * p.C_in * HW;
-  const int ih_base = oh * S - p.ph;
-  auto refine = [&](int t, float best, const T* wrow, int q) -> int {
-    const int ka = 2 * t, kb = ka + 1;
-    if (kb >= p.K) return ka;
-    const int c = ka / 9, r = ka - 9 * c, i = r / 3, j = r - 3 * i;
-    const int ih = ih_base + i * D, iw = (ow0 + q) * S - p.pw + j * D;
-    const bool v = (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W);
-    const int ihc = min(max(ih, 0), p.H - 1), iwc = min(max(iw, 0), p.W - 1);
-    const float xv = ld1(xn + (size_t)c * HW + (size_t)ihc * p.W + iwc);
-    const float sa = __fadd_rn(xv, wld<T>(wrow, ka));
-    return (v && sa == best) ? ka : kb;
+  const size_t wbytes = (size_t)p.C_out * p.K * sizeof(float);
+  const rsrc_t wres_min = make_rsrc(DO_MIN ? w_min : w_max, (unsigned)wbytes);
+  const rsrc_t wres_max = make_rsrc(DO_MAX ? w_max : w_min, (unsigned)wbytes);
+  const size_t xn_off = (size_t)n * p.C_in * HW;
+  int ihc[3];
+  bool rv[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int ih = oh - p.ph + i * D;
+    rv[i] = (ih >= 0 && ih < p.H);
+    ihc[i] = min(max(ih, 0), p.H - 1);
+  }
+  auto refine = [&](int cs, float best, rsrc_t wres, int co, int q) -> int {
+    if (dbg & 1) return cs * 9;
+    cs = min(cs, p.C_in - 1);  // a virtual channel never wins; keep the address in range regardless
+    float wv[9];
+    load_run<9, float>(wv, wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
+    const int iwq = ow0 + q - p.pw;
+    int res = cs * 9;
+#pragma unroll
+    for (int i = 2; i >= 0; --i) {
+      const size_t rbase = xn_off + (size_t)cs * HW + (size_t)ihc[i] * p.W;
+      float xv[3];
+      bool cv[3];
+      if (q >= D && q <= 7 - D) {  // every tap column of this pixel lies inside the row
+        float run[2 * D + 1];
+        load_run<2 * D + 1, float>(run, xres, (unsigned)((rbase + iwq) * sizeof(float)), 0u);
+#pragma unroll
+        for (int j = 0; j < 3; ++j) { xv[j] = run[j * D]; cv[j] = true; }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+          const int iw = iwq + j * D;
+          cv[j] = (iw >= 0 && iw < p.W);
+          xv[j] = load_one<float>(xres, (unsigned)((rbase + min(max(iw, 0), p.W - 1)) * sizeof(float)), 0u);
+        }
+      }
+#pragma unroll
+      for (int j = 2; j >= 0; --j) {
+        const float s = __fadd_rn(xv[j], wv[i * 3 + j]);
+        res = (rv[i] && cv[j] && s == best) ? cs * 9 + i * 3 + j : res;
+      }
+    }
+    return res;
   };
   const size_t plane = (size_t)p.Ho * p.Wo;
 #pragma unroll
   for (int c = 0; c < TN; ++c) {
     const int co = co0 + c;
-    if (co >= p.C_out) break;
+    if (co >= p.C_out) break;  // wave-uniform
     const size_t ob = ((size_t)n * p.C_out + co) * plane + (size_t)oh * p.Wo + ow0;
     float ca = 1.f, cb = 1.f;
     if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
       if (alpha) ca = alpha[co];
       if (beta) cb = beta[co];
     }
+    int ridx[PX];
+    float out[PX];
+    if (DO_MIN) {
+#pragma unroll
+      for (int q = 0; q < PX; ++q) ridx[q] = refine(imin[c][q], bmin[c][q], wres_min, co, q);
+      store_row(idx_min + ob, ridx, first_q);
+      if (y_min) store_row(y_min + ob, bmin[c], first_q);
+    }
+    if (DO_MAX) {
+#pragma unroll
+      for (int q = 0; q < PX; ++q) ridx[q] = refine(imax[c][q], bmax[c][q], wres_max, co, q);
+      store_row(idx_max + ob, ridx, first_q);
+      if (y_max) store_row(y_max + ob, bmax[c], first_q);
+    }
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
-      if (q < first_q) continue;
-      float out;
-      if (DO_MIN) {
-        idx_min[ob + q] = refine(acc.imin[c][q], acc.bmin[c][q], wr_min[c], q);
-        if (y_min) st_f32(y_min, ob + q, acc.bmin[c][q]);
-      }
-      if (DO_MAX) {
-        idx_max[ob + q] = refine(acc.imax[c][q], acc.bmax[c][q], wr_max[c], q);
-        if (y_max) st_f32(y_max, ob + q, acc.bmax[c][q]);
-      }
-      if (MODE == TCONV_MAX) out = acc.bmax[c][q];
-      else if (MODE == TCONV_MIN) out = acc.bmin[c][q];
-      else out = combine(ca, acc.bmin[c][q], cb, acc.bmax[c][q]);
-      st_f32(y, ob + q, out);
+      if (MODE == TCONV_MAX) out[q] = bmax[c][q];
+      else if (MODE == TCONV_MIN) out[q] = bmin[c][q];
+      else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
     }
+    store_row(y + ob, out, first_q);
   }
 }
 
-template <int MODE, int S, int D, int TN, typename T>
-hipError_t launch_one(const Params& p, const FwdArgs& a, hipStream_t s) {
+// bf16 storage is widened to fp32 once, into the workspace, so that the main kernel always reads fp32
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restrict__ src,
+                                                          float* __restrict__ dst, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    dst[i] = __uint_as_float(((unsigned)src[i]) << 16);
+}
+
+void widen(const void* src, float* dst, size_t n, hipStream_t s) {
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)src, dst, n);
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+template <int MODE, int D, typename TO>
+hipError_t launch_one(const Params& p, const float* x, const float* w_min, const float* w_max,
+                      const FwdArgs& a, hipStream_t s) {
   const int segs = (p.Wo + PX - 1) / PX;
   const long long n_units = (long long)p.N * p.Ho * segs;
   const int n_groups = (p.C_out + TN - 1) / TN;
@@ -425,52 +352,78 @@ hipError_t launch_one(const Params& p, const FwdArgs& a, hipStream_t s) {
   const long long gblocks = (n_groups + WAVES - 1) / WAVES;
   const long long blocks = ublocks * gblocks;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, T>), dim3((unsigned)blocks),
-                     dim3(WAVES * 64), 0, s, p, (const T*)a.x, (const T*)a.w_min,
-                     (const T*)a.w_max, a.alpha, a.beta, (T*)a.y, (T*)a.y_min, (T*)a.y_max,
-                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups);
+  const char* e = getenv("TCONV_DEBUG_FLAGS");
+  const int dbg = e ? atoi(e) : 0;
+  hipLaunchKernelGGL((fwd_tiled3x3_s1_kernel<MODE, D, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
+                     0, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
+                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, dbg);
   return hipGetLastError();
 }
 
-template <int MODE, typename T>
-hipError_t launch_geo(const Params& p, const FwdArgs& a, hipStream_t s) {
-  constexpr int TN = 4;
-  if (p.sh == 1 && p.dh == 1) return launch_one<MODE, 1, 1, TN, T>(p, a, s);
-  if (p.sh == 2 && p.dh == 1) return launch_one<MODE, 2, 1, TN, T>(p, a, s);
-  if (p.sh == 1 && p.dh == 2) return launch_one<MODE, 1, 2, TN, T>(p, a, s);
-  return hipErrorNotSupported;
+template <int MODE, typename TO>
+hipError_t launch_dil(const Params& p, const float* x, const float* w_min, const float* w_max,
+                      const FwdArgs& a, hipStream_t s) {
+  return p.dh == 1 ? launch_one<MODE, 1, TO>(p, x, w_min, w_max, a, s)
+                   : launch_one<MODE, 2, TO>(p, x, w_min, w_max, a, s);
 }
 
-template <typename T>
-hipError_t launch_mode(const Params& p, const FwdArgs& a, hipStream_t s) {
+template <typename TO>
+hipError_t launch_mode(const Params& p, const float* x, const float* w_min, const float* w_max,
+                       const FwdArgs& a, hipStream_t s) {
   switch (p.mode) {
-    case TCONV_MAX: return launch_geo<TCONV_MAX, T>(p, a, s);
-    case TCONV_MIN: return launch_geo<TCONV_MIN, T>(p, a, s);
-    case TCONV_COMPOUND: return launch_geo<TCONV_COMPOUND, T>(p, a, s);
-    default: return launch_geo<TCONV_PARALLEL, T>(p, a, s);
+    case TCONV_MAX: return launch_dil<TCONV_MAX, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_MIN: return launch_dil<TCONV_MIN, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_COMPOUND: return launch_dil<TCONV_COMPOUND, TO>(p, x, w_min, w_max, a, s);
+    default: return launch_dil<TCONV_PARALLEL, TO>(p, x, w_min, w_max, a, s);
   }
+}
+
+bool stride1_supported(const Params& p) {
+  if (p.KH != 3 || p.KW != 3) return false;
+  if (p.sh != 1 || p.sw != 1 || p.dh != p.dw || (p.dh != 1 && p.dh != 2)) return false;
+  if (p.pw > p.dw) return false;  // the 8 core columns of every lane must lie inside the row
+  if (p.Wo < PX) return false;    // at least one full 8-pixel segment per output row
+  // lanes address x and the kernels (as fp32) with 32-bit byte offsets
+  if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
+  if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
+  return true;
 }
 
 }  // namespace
 
-// 3x3 kernels with equal stride and dilation on both axes, (stride, dilation) in
-// {(1,1), (2,1), (1,2)}, horizontal padding at most the dilation (so the core columns of
-// every lane lie inside the row), and at least one full 8-pixel segment per output row.
 bool forward_tiled3x3_supported(const Params& p, int dtype) {
-  if (p.KH != 3 || p.KW != 3) return false;
-  if (p.sh != p.sw || p.dh != p.dw) return false;
-  const bool geo = (p.sh == 1 && p.dh == 1) || (p.sh == 2 && p.dh == 1) || (p.sh == 1 && p.dh == 2);
-  if (!geo) return false;
-  if (p.pw > p.dw) return false;
-  if (p.Wo < PX) return false;
-  // lanes address x with 32-bit byte offsets
-  const size_t esz = (dtype == TCONV_BF16) ? 2 : 4;
-  if ((size_t)p.N * p.C_in * p.H * p.W * esz >= 0xfffff000ull) return false;
-  return true;
+  return stride1_supported(p) || forward_tiled_strided_supported(p, dtype);
 }
 
-hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, hipStream_t s) {
-  return dtype == TCONV_BF16 ? launch_mode<bf16_t>(p, a, s) : launch_mode<float>(p, a, s);
+// Workspace of the tiled path: only bf16 storage with the stride-1 kernel needs one (fp32 copies
+// of x and of the kernel tensors).
+size_t forward_tiled3x3_workspace(const Params& p, int dtype) {
+  if (dtype != TCONV_BF16 || !stride1_supported(p)) return 0;
+  const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;
+  return align256(nx * 4) + align256(nw * 4) * (p.mode == TCONV_PARALLEL ? 2 : 1);
+}
+
+hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, void* workspace,
+                                   hipStream_t s) {
+  if (!stride1_supported(p)) return launch_forward_tiled_strided(p, dtype, a, s);
+  if (dtype != TCONV_BF16)
+    return launch_mode<float>(p, (const float*)a.x, (const float*)a.w_min, (const float*)a.w_max, a, s);
+  const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;
+  float* xf = (float*)workspace;
+  float* wa = (float*)((char*)workspace + align256(nx * 4));
+  float* wb = (float*)((char*)wa + align256(nw * 4));
+  widen(a.x, xf, nx, s);
+  const float* wmin_f = nullptr;
+  const float* wmax_f = nullptr;
+  if (p.mode == TCONV_PARALLEL) {
+    widen(a.w_min, wa, nw, s);
+    widen(a.w_max, wb, nw, s);
+    wmin_f = wa; wmax_f = wb;
+  } else {
+    widen(p.mode == TCONV_MIN ? a.w_min : a.w_max, wa, nw, s);
+    wmin_f = wmax_f = wa;
+  }
+  return launch_mode<bf16_t>(p, xf, wmin_f, wmax_f, a, s);
 }
 
 }  // namespace tconv

@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Writes tile_blocks_gfx950.h: the hand-scheduled gfx950 inner blocks of the tiled forward kernel.
+
+A block advances ONE running extremum (per branch) over TWO consecutive input channels
+(2 x 9 taps of a 3x3 kernel) entirely in registers:
+
+    channel A:  tmp  = max(best, s0 .. s8)      4 x v_max3_f32 + 1 x v_max_f32, result in a temporary
+                mA   = tmp  > best               "channel A holds a new extremum"
+    channel B:  best = max(tmp, s0' .. s8')     written back in place
+                mB   = best > tmp
+                idx  = mA ? cA : idx ;  idx = mB ? cB : idx
+
+with s = x + w one v_add_f32 per tap (the kernel value is the SGPR operand).  Going
+through the temporary and back keeps every accumulator in its own register with no
+copy, and the winning CHANNEL is recorded with 2 compares + 2 selects per 18 taps; the
+exact tap inside that channel is recovered after the K loop.  Strict compares in
+ascending channel order keep the lowest winning channel.
+
+Instruction order is fixed by hand because gfx950 needs two independent instructions
+between a VALU write of a lane mask (v_cmp -> VCC / SGPR pair) and the VALU read of it
+(v_cndmask); the compiler neither sees nor pads inside an asm block.  Four masks
+(three SGPR pairs and VCC) are live at the end of a block so that every select has at
+least three other instructions between it and its compare.
+
+Run:  python3 gen_tile_blocks.py > tile_blocks_gfx950.h
+"""
+
+PAIRS = [(0, 1), (2, 3), (4, 5), (6, 7)]
+
+
+def chain(lines, ch, dst_of, src_first, both):
+    """One channel (9 taps) for one accumulator.  dst_of/src_first: dict branch -> operand name."""
+    first = True
+    for a, b in PAIRS:
+        lines.append(f"v_add_f32 %[sa], %[w{ch}{a}], %[x{ch}{a}]")
+        lines.append(f"v_add_f32 %[sb], %[w{ch}{b}], %[x{ch}{b}]")
+        for br, op in both:
+            src = src_first[br] if first else dst_of[br]
+            lines.append(f"v_{op}3_f32 %[{dst_of[br]}], %[{src}], %[sa], %[sb]")
+        first = False
+    lines.append(f"v_add_f32 %[sa], %[w{ch}8], %[x{ch}8]")
+    for br, op in both:
+        lines.append(f"v_{op}_f32 %[{dst_of[br]}], %[{dst_of[br]}], %[sa]")
+
+
+def emit_asm(lines):
+    return "\n".join(f'      "{l}\\n\\t"' for l in lines)
+
+
+def gen_both():
+    both = [("mx", "max"), ("mn", "min")]
+    L = []
+    chain(L, "A", {"mx": "tmx", "mn": "tmn"}, {"mx": "bmax", "mn": "bmin"}, both)
+    L.append("v_cmp_gt_f32 %[m1], %[tmx], %[bmax]")
+    L.append("v_cmp_lt_f32 %[m2], %[tmn], %[bmin]")
+    chain(L, "B", {"mx": "bmax", "mn": "bmin"}, {"mx": "tmx", "mn": "tmn"}, both)
+    L.append("v_cmp_gt_f32 vcc, %[bmax], %[tmx]")
+    L.append("v_cmp_lt_f32 %[m3], %[bmin], %[tmn]")
+    L.append("v_cndmask_b32 %[imax], %[imax], %[tA], %[m1]")
+    L.append("v_cndmask_b32 %[imin], %[imin], %[tA], %[m2]")
+    L.append("v_cndmask_b32 %[imax], %[imax], %[tB], vcc")
+    L.append("v_cndmask_b32 %[imin], %[imin], %[tB], %[m3]")
+    ins = []
+    for ch in "AB":
+        ins += [f'[x{ch}{i}] "v"(x{ch}[{i}])' for i in range(9)]
+        ins += [f'[w{ch}{i}] "s"(w{ch}[{i}])' for i in range(9)]
+    ins += ['[tA] "v"(tA)', '[tB] "v"(tB)']
+    return f"""
+// Compound mode: one shared add per tap feeds both reductions (paper Sec. 3.5, closing remark).
+// 46 VALU instructions for 18 candidates x 2 branches.
+__device__ __forceinline__ void blk_both(float& bmax, float& bmin, int& imax, int& imin,
+                                         const float (&xA)[9], const float (&xB)[9],
+                                         const float (&wA)[9], const float (&wB)[9], int tA, int tB) {{
+  float tmx, tmn, sa, sb;
+  unsigned long long m1, m2, m3;
+  asm(
+{emit_asm(L)}
+      : [tmx] "=&v"(tmx), [tmn] "=&v"(tmn), [sa] "=&v"(sa), [sb] "=&v"(sb),
+        [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+        [bmax] "+v"(bmax), [bmin] "+v"(bmin), [imax] "+v"(imax), [imin] "+v"(imin)
+      : {", ".join(ins)}
+      : "vcc");
+}}
+"""
+
+
+def gen_one2(name, op, cmp):
+    """Single branch, two accumulators (two pixels of one output channel) per block."""
+    L = []
+    # channel A of both accumulators, then their compares
+    for p in "01":
+        first = True
+        for a, b in PAIRS:
+            L.append(f"v_add_f32 %[sa], %[wA{a}], %[xA{p}_{a}]")
+            L.append(f"v_add_f32 %[sb], %[wA{b}], %[xA{p}_{b}]")
+            src = f"b{p}" if first else f"t{p}"
+            L.append(f"v_{op}3_f32 %[t{p}], %[{src}], %[sa], %[sb]")
+            first = False
+        L.append(f"v_add_f32 %[sa], %[wA8], %[xA{p}_8]")
+        L.append(f"v_{op}_f32 %[t{p}], %[t{p}], %[sa]")
+    L.append(f"v_cmp_{cmp}_f32 %[m1], %[t0], %[b0]")
+    L.append(f"v_cmp_{cmp}_f32 %[m2], %[t1], %[b1]")
+    for p in "01":
+        first = True
+        for a, b in PAIRS:
+            L.append(f"v_add_f32 %[sa], %[wB{a}], %[xB{p}_{a}]")
+            L.append(f"v_add_f32 %[sb], %[wB{b}], %[xB{p}_{b}]")
+            src = f"t{p}" if first else f"b{p}"
+            L.append(f"v_{op}3_f32 %[b{p}], %[{src}], %[sa], %[sb]")
+            first = False
+        L.append(f"v_add_f32 %[sa], %[wB8], %[xB{p}_8]")
+        L.append(f"v_{op}_f32 %[b{p}], %[b{p}], %[sa]")
+    L.append(f"v_cmp_{cmp}_f32 vcc, %[b0], %[t0]")
+    L.append(f"v_cmp_{cmp}_f32 %[m3], %[b1], %[t1]")
+    L.append("v_cndmask_b32 %[i0], %[i0], %[tA], %[m1]")
+    L.append("v_cndmask_b32 %[i1], %[i1], %[tA], %[m2]")
+    L.append("v_cndmask_b32 %[i0], %[i0], %[tB], vcc")
+    L.append("v_cndmask_b32 %[i1], %[i1], %[tB], %[m3]")
+    ins = []
+    for ch in "AB":
+        for p in "01":
+            ins += [f'[x{ch}{p}_{i}] "v"(x{ch}{p}[{i}])' for i in range(9)]
+        ins += [f'[w{ch}{i}] "s"(w{ch}[{i}])' for i in range(9)]
+    ins += ['[tA] "v"(tA)', '[tB] "v"(tB)']
+    return f"""
+// One branch ({op}-plus), two pixels of one output channel.  64 VALU instructions for 2 x 18 candidates.
+__device__ __forceinline__ void {name}(float& b0, int& i0, float& b1, int& i1,
+                                       const float (&xA0)[9], const float (&xB0)[9],
+                                       const float (&xA1)[9], const float (&xB1)[9],
+                                       const float (&wA)[9], const float (&wB)[9], int tA, int tB) {{
+  float t0, t1, sa, sb;
+  unsigned long long m1, m2, m3;
+  asm(
+{emit_asm(L)}
+      : [t0] "=&v"(t0), [t1] "=&v"(t1), [sa] "=&v"(sa), [sb] "=&v"(sb),
+        [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+        [b0] "+v"(b0), [i0] "+v"(i0), [b1] "+v"(b1), [i1] "+v"(i1)
+      : {", ".join(ins)}
+      : "vcc");
+}}
+"""
+
+
+HEADER = """// GENERATED by gen_tile_blocks.py - do not edit by hand.
+//
+// Hand-scheduled gfx950 inner blocks of the tiled 3x3 tropical-convolution forward kernel
+// (paper Sec. 3.1 layers (iv)/(v): one max / min over all taps of x + w; Sec. 3.3 compound).
+// See the generator for the scheme and for why the instruction order is fixed.
+#pragma once
+
+namespace tconv {
+
+// Makes the compiler forget the value of a wave-uniform integer (it stays in an SGPR), so that
+// loads addressed through it are re-issued instead of being kept live across the whole loop body.
+__device__ __forceinline__ int launder_uniform(int v) {
+  asm volatile("" : "+s"(v));
+  return v;
+}
+"""
+
+if __name__ == "__main__":
+    out = HEADER + gen_both() + gen_one2("blk_max2", "max", "gt") + gen_one2("blk_min2", "min", "lt")
+    out += "\n}  // namespace tconv\n"
+    print(out, end="")

@@ -1,0 +1,118 @@
+// Helpers shared by the tiled 3x3 forward kernels (gfx950): lane geometry constants, raw buffer
+// loads of x, and the vectorised row stores of the epilogue.
+#pragma once
+#include "tconv_internal.h"
+
+namespace tconv {
+namespace tile {
+
+constexpr int PX = 8;     // output pixels per lane
+constexpr int WAVES = 4;  // waves per workgroup, each a different c_out group
+
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f2u __attribute__((ext_vector_type(2), aligned(4)));
+
+__device__ __forceinline__ float nan_or(float v, unsigned m) {
+  return __uint_as_float(__float_as_uint(v) | m);
+}
+
+// ---- input loads go through a raw buffer resource: a wave-uniform 128-bit descriptor of the whole x
+// tensor in SGPRs, a per-lane 32-bit byte offset in a VGPR and a wave-uniform channel offset in an SGPR
+// (buffer_load ... offen).  No 64-bit per-lane address arithmetic, and nothing loop-invariant for
+// the compiler to hoist into VGPR pairs.
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// contiguous run of N values starting at byte offset voff (+ uniform soff) -> fp32 registers
+template <int N, typename T>
+__device__ __forceinline__ void load_run(float* dst, rsrc_t r, unsigned voff, unsigned soff) {
+  if constexpr (sizeof(T) == 4) {  // fp32 storage, 4-byte aligned
+    if constexpr (N >= 4) {
+      const u4v v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+      dst[0] = __uint_as_float(v.x); dst[1] = __uint_as_float(v.y);
+      dst[2] = __uint_as_float(v.z); dst[3] = __uint_as_float(v.w);
+      load_run<N - 4, T>(dst + 4, r, voff + 16, soff);
+    } else if constexpr (N >= 2) {
+      const u2v v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+      dst[0] = __uint_as_float(v.x); dst[1] = __uint_as_float(v.y);
+      load_run<N - 2, T>(dst + 2, r, voff + 8, soff);
+    } else if constexpr (N == 1) {
+      dst[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+    }
+  } else {  // bf16 storage: 2-byte aligned, widened exactly
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      dst[i] = __uint_as_float(((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff + 2 * i, soff, 0)) << 16);
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ float load_one(rsrc_t r, unsigned voff, unsigned soff) {
+  if constexpr (sizeof(T) == 4)
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+  else
+    return __uint_as_float(((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0)) << 16);
+}
+
+// ---- a lane's 8 consecutive outputs -> memory.  Pixels q < first_q belong to the neighbouring
+// lane (shifted last segment of a row): then single predicated stores, else two 16-byte stores.
+typedef int i4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));
+
+__device__ __forceinline__ void store_row(float* p, const float (&v)[PX], int first_q) {
+  if (first_q == 0) {
+    f4u a, b;
+    a.x = v[0]; a.y = v[1]; a.z = v[2]; a.w = v[3];
+    b.x = v[4]; b.y = v[5]; b.z = v[6]; b.w = v[7];
+    *(f4u*)p = a;
+    *(f4u*)(p + 4) = b;
+  } else {
+#pragma unroll
+    for (int q = 0; q < PX; ++q)
+      if (q >= first_q) p[q] = v[q];
+  }
+}
+
+__device__ __forceinline__ void store_row(int32_t* p, const int (&v)[PX], int first_q) {
+  if (first_q == 0) {
+    i4u a, b;
+    a.x = v[0]; a.y = v[1]; a.z = v[2]; a.w = v[3];
+    b.x = v[4]; b.y = v[5]; b.z = v[6]; b.w = v[7];
+    *(i4u*)p = a;
+    *(i4u*)(p + 4) = b;
+  } else {
+#pragma unroll
+    for (int q = 0; q < PX; ++q)
+      if (q >= first_q) p[q] = v[q];
+  }
+}
+
+__device__ __forceinline__ unsigned bf16_bits(float v) {  // round to nearest even
+  unsigned u = __float_as_uint(v);
+  if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ void store_row(bf16_t* p, const float (&v)[PX], int first_q) {
+  if (first_q == 0) {
+    u4h a;
+    a.x = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+    a.y = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+    a.z = bf16_bits(v[4]) | (bf16_bits(v[5]) << 16);
+    a.w = bf16_bits(v[6]) | (bf16_bits(v[7]) << 16);
+    *(u4h*)p = a;
+  } else {
+#pragma unroll
+    for (int q = 0; q < PX; ++q)
+      if (q >= first_q) p[q] = (bf16_t)bf16_bits(v[q]);
+  }
+}
+
+
+}  // namespace tile
+}  // namespace tconv
