@@ -3,7 +3,7 @@
 // x element and the one kernel element that produced the extremum).  Neither does
 // any arithmetic beyond adds, so both are bound by reading gy and idx from HBM.
 //
-//   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (scatter, hardware fp32 atomics)
+//   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (input tile in LDS, LDS fp32 atomics, plain stores)
 //   backward_weight: grad_w_b[c_out, k*]    += g_b   (per-c_out LDS histogram, then flush)
 //
 // g_min = alpha[c_out]*gy and g_max = beta[c_out]*gy in compound / parallel mode
@@ -72,19 +72,143 @@ __global__ __launch_bounds__(256) void bwd_input_scatter_kernel(Params p, BwdArg
   }
 }
 
+// Tiled backward-input: no global atomics.  One workgroup owns an INPUT tile (CC channels x TH x TW
+// pixels of one image) in LDS, scans every output whose window can reach the tile (the tile grown by
+// the kernel extent, all C_out channels, every live branch), adds the gradients that land inside
+// with LDS atomics and finally writes the tile to grad_x with plain coalesced stores.  Every input
+// element belongs to exactly one workgroup, so grad_x needs no zero fill.  The price is re-reading
+// gy / idx for the halo: (TH+e)(TW+e)/(TH*TW) times the algorithmic bytes (times the number of
+// channel chunks when C_in*TH*TW does not fit in LDS); neighbouring tiles share those lines in L2.
+template <int MODE, bool K3>
+__global__ __launch_bounds__(256) void bwd_input_tile_kernel(Params p, BwdArgs a,
+                                                             float* __restrict__ grad_x, int TH,
+                                                             int TW, int CC, int tiles_h,
+                                                             int tiles_w, int chunks) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX);
+  constexpr bool DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  extern __shared__ float tile[];  // [CC][TH][TW]
+  int b = blockIdx.x;
+  const int ch = b % chunks; b /= chunks;
+  const int tw = b % tiles_w; b /= tiles_w;
+  const int th = b % tiles_h;
+  const int n = b / tiles_h;
+  const int h0 = th * TH, w0 = tw * TW, c0 = ch * CC;
+  const int tsz = CC * TH * TW;
+  for (int e = threadIdx.x; e < tsz; e += 256) tile[e] = 0.f;
+  __syncthreads();
+
+  // outputs whose window can reach the tile
+  const int KHs = K3 ? 3 : p.KH, KWs = K3 ? 3 : p.KW, KK = KHs * KWs;
+  const int nh = h0 + p.ph - (KHs - 1) * p.dh, nw = w0 + p.pw - (KWs - 1) * p.dw;
+  const int oh_lo = nh <= 0 ? 0 : (nh + p.sh - 1) / p.sh;
+  const int ow_lo = nw <= 0 ? 0 : (nw + p.sw - 1) / p.sw;
+  const int oh_hi = min(p.Ho - 1, (h0 + TH - 1 + p.ph) / p.sh);
+  const int ow_hi = min(p.Wo - 1, (w0 + TW - 1 + p.pw) / p.sw);
+  const int RH = oh_hi - oh_lo + 1, RW = ow_hi - ow_lo + 1;
+  const int plane = p.Ho * p.Wo;
+  if (RH > 0 && RW > 0) {
+    for (int px = threadIdx.x; px < RH * RW; px += 256) {
+      const int oh = oh_lo + px / RW, ow = ow_lo + px % RW;
+      // position of tap (0, 0) of this output relative to the tile
+      const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw - w0;
+      size_t o = ((size_t)n * p.C_out) * plane + (size_t)oh * p.Wo + ow;
+#pragma unroll 4
+      for (int co = 0; co < p.C_out; ++co, o += plane) {
+        const float g = a.gy[o];
+        if (DO_MIN) {
+          const int k = a.idx_min[o];
+          const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
+          const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
+          if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
+            atomicAdd(&tile[(cc * TH + ih) * TW + iw], SCALED ? __fmul_rn(a.alpha ? a.alpha[co] : 1.0f, g) : g);
+        }
+        if (DO_MAX) {
+          const int k = a.idx_max[o];
+          const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
+          const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
+          if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
+            atomicAdd(&tile[(cc * TH + ih) * TW + iw], SCALED ? __fmul_rn(a.beta ? a.beta[co] : 1.0f, g) : g);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const size_t HW = (size_t)p.H * p.W;
+  float* gxn = grad_x + (size_t)n * p.C_in * HW;
+  for (int e = threadIdx.x; e < tsz; e += 256) {
+    const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
+    if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
+      gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = tile[e];
+  }
+}
+
+// Tile shape for bwd_input_tile_kernel: minimise (channel chunks) x (halo re-read factor) under the
+// LDS budget, with a penalty for rows too short to coalesce.
+struct BwdInTile { int TH, TW, CC, tiles_h, tiles_w, chunks; };
+
+static BwdInTile choose_bwd_input_tile(const Params& p, int lds_floats) {
+  BwdInTile best = {0, 0, 0, 0, 0, 0};
+  double best_cost = 1e30;
+  const int eh = (p.KH - 1) * p.dh, ew = (p.KW - 1) * p.dw;
+  for (int chunks = 1; chunks <= p.C_in; chunks *= 2) {
+    const int CC = (p.C_in + chunks - 1) / chunks;
+    for (int TWc = 8; TWc <= 128; TWc *= 2) {
+      const int TW = TWc < p.W ? TWc : p.W;
+      int TH = lds_floats / (CC * TW);
+      if (TH > p.H) TH = p.H;
+      if (TH > 64) TH = 64;
+      if (TH < 1) continue;
+      const int real_chunks = (p.C_in + CC - 1) / CC;
+      double cost = (double)real_chunks * (TH + eh) / TH * (TW + ew) / TW;
+      if (TW + ew < 16) cost *= 1.5;
+      const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
+      const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
+      if (wgs < 512) cost *= 1.0 + (512 - wgs) / 512;  // too few workgroups to fill 256 CUs
+      if (cost < best_cost) {
+        best_cost = cost;
+        best = {TH, TW, CC, tiles_h, tiles_w, real_chunks};
+      }
+      if (TW == p.W) break;
+    }
+    if (CC == 1) break;
+  }
+  return best;
+}
+
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
+  constexpr int LDS_FLOATS = 16 * 1024;  // 64 KB per workgroup: two workgroups share a CU's LDS
+  const BwdInTile t = choose_bwd_input_tile(p, LDS_FLOATS);
+  const long long blocks = (long long)p.N * t.tiles_h * t.tiles_w * t.chunks;
+  if (t.TH >= 1 && blocks <= 0x7fffffffLL) {
+    const size_t lds = (size_t)t.CC * t.TH * t.TW * sizeof(float);
+    const bool k3 = (p.KH == 3 && p.KW == 3);
+#define TCONV_LAUNCH_BWD_IN(M, K3)                                                              \
+  hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)blocks), dim3(256), lds, s, p, a, \
+                     grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks)
+    switch (p.mode) {
+      case TCONV_MAX: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MAX, true); else TCONV_LAUNCH_BWD_IN(TCONV_MAX, false); break;
+      case TCONV_MIN: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MIN, true); else TCONV_LAUNCH_BWD_IN(TCONV_MIN, false); break;
+      default:  // compound and parallel route gradients identically
+        if (k3) TCONV_LAUNCH_BWD_IN(TCONV_COMPOUND, true); else TCONV_LAUNCH_BWD_IN(TCONV_COMPOUND, false);
+        break;
+    }
+#undef TCONV_LAUNCH_BWD_IN
+    return hipGetLastError();
+  }
+  // fallback: zero fill + global atomics
   fill_zero(grad_x, (size_t)p.N * p.C_in * p.H * p.W, s);
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
-  const unsigned blocks = (unsigned)((total + 255) / 256);
+  const unsigned sblocks = (unsigned)((total + 255) / 256);
   switch (p.mode) {
     case TCONV_MAX:
-      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_MAX>, dim3(blocks), dim3(256), 0, s, p, a, grad_x);
+      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_MAX>, dim3(sblocks), dim3(256), 0, s, p, a, grad_x);
       break;
     case TCONV_MIN:
-      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_MIN>, dim3(blocks), dim3(256), 0, s, p, a, grad_x);
+      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_MIN>, dim3(sblocks), dim3(256), 0, s, p, a, grad_x);
       break;
-    default:  // compound and parallel route gradients identically
-      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_COMPOUND>, dim3(blocks), dim3(256), 0, s, p, a, grad_x);
+    default:
+      hipLaunchKernelGGL(bwd_input_scatter_kernel<TCONV_COMPOUND>, dim3(sblocks), dim3(256), 0, s, p, a, grad_x);
       break;
   }
   return hipGetLastError();
