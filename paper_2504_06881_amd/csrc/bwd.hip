@@ -5,12 +5,38 @@
 //
 //   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (input tile in LDS, LDS fp32 atomics, plain stores)
 //   backward_weight: grad_w_b[c_out, k*]    += g_b   (per-c_out LDS histogram, then flush)
+// Both accumulate in 64-bit fixed point (see fixed_shift below).
 //
 // g_min = alpha[c_out]*gy and g_max = beta[c_out]*gy in compound / parallel mode
 // (paper Sec. 3.3 definitions), g = gy in max / min mode.
 #include "tconv_internal.h"
 
 namespace tconv {
+
+// ---- fixed-point accumulation.  On gfx950 an LDS fp32 atomic add (ds_add_f32) runs about 12x slower
+// than the integer LDS atomics (measured: ~190 cycles against ~16 per wave instruction with random
+// addresses), so both backward kernels accumulate in 64-bit fixed point with ds_add_u64.  The scale
+// 2^S is chosen per workgroup from the largest |term| it will add and the number of terms, so that
+// no sum can overflow 62 bits whatever the magnitude of the inputs; a term is the exact double product
+// coef*gy rounded once to a multiple of 2^-S (relative to the largest term: below 2^-40 for fewer
+// than 2^20 terms).  Integer adds commute, so the per-workgroup sums are bit-reproducible, and each
+// is rounded to fp32 once at the end.
+__device__ __forceinline__ int fixed_shift(float gmax, unsigned items) {
+  if (!(gmax > 0.f)) return 0;
+  int e;
+  frexpf(gmax, &e);                         // gmax < 2^e
+  const int lg = 32 - __clz((int)items);    // items < 2^lg
+  return 62 - e - lg;
+}
+__device__ __forceinline__ long long to_fixed(float coef, float g, double scale) {
+  return __double2ll_rn((double)coef * (double)g * scale);
+}
+// max over the workgroup of non-negative floats: wave reduction, then one LDS integer max per wave
+__device__ __forceinline__ void block_max_nonneg(float v, unsigned* slot) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  if ((threadIdx.x & 63) == 0) atomicMax(slot, __float_as_uint(v));
+}
 
 // Zero n floats: float4 stores over the 16-byte-aligned body, scalar stores for the ragged ends.
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, size_t n) {
@@ -75,19 +101,22 @@ __global__ __launch_bounds__(256) void bwd_input_scatter_kernel(Params p, BwdArg
 // Tiled backward-input: no global atomics.  One workgroup owns an INPUT tile (CC channels x TH x TW
 // pixels of one image) in LDS, scans every output whose window can reach the tile (the tile grown by
 // the kernel extent, all C_out channels, every live branch), adds the gradients that land inside
-// with LDS atomics and finally writes the tile to grad_x with plain coalesced stores.  Every input
+// with 64-bit fixed-point LDS atomics and finally writes the tile to grad_x with plain coalesced stores.  Every input
 // element belongs to exactly one workgroup, so grad_x needs no zero fill.  The price is re-reading
 // gy / idx for the halo: (TH+e)(TW+e)/(TH*TW) times the algorithmic bytes (times the number of
 // channel chunks when C_in*TH*TW does not fit in LDS); neighbouring tiles share those lines in L2.
 template <int MODE, bool K3>
-__global__ __launch_bounds__(256) void bwd_input_tile_kernel(Params p, BwdArgs a,
-                                                             float* __restrict__ grad_x, int TH,
-                                                             int TW, int CC, int tiles_h,
-                                                             int tiles_w, int chunks) {
+__global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs a,
+                                                              float* __restrict__ grad_x, int TH,
+                                                              int TW, int CC, int tiles_h,
+                                                              int tiles_w, int chunks) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  extern __shared__ float tile[];  // [CC][TH][TW]
+  // [CC][TH][TW] 64-bit fixed-point sums, then one int2 per output pixel of the scanned region
+  extern __shared__ long long tile[];
+  __shared__ unsigned s_gmax;
+  const int bd = blockDim.x;
   int b = blockIdx.x;
   const int ch = b % chunks; b /= chunks;
   const int tw = b % tiles_w; b /= tiles_w;
@@ -95,8 +124,9 @@ __global__ __launch_bounds__(256) void bwd_input_tile_kernel(Params p, BwdArgs a
   const int n = b / tiles_h;
   const int h0 = th * TH, w0 = tw * TW, c0 = ch * CC;
   const int tsz = CC * TH * TW;
-  for (int e = threadIdx.x; e < tsz; e += 256) tile[e] = 0.f;
-  __syncthreads();
+  int2* tab = (int2*)(tile + tsz);
+  for (int e = threadIdx.x; e < tsz; e += bd) tile[e] = 0;
+  if (threadIdx.x == 0) s_gmax = 0u;
 
   // outputs whose window can reach the tile
   const int KHs = K3 ? 3 : p.KH, KWs = K3 ? 3 : p.KW, KK = KHs * KWs;
@@ -105,41 +135,105 @@ __global__ __launch_bounds__(256) void bwd_input_tile_kernel(Params p, BwdArgs a
   const int ow_lo = nw <= 0 ? 0 : (nw + p.sw - 1) / p.sw;
   const int oh_hi = min(p.Ho - 1, (h0 + TH - 1 + p.ph) / p.sh);
   const int ow_hi = min(p.Wo - 1, (w0 + TW - 1 + p.pw) / p.sw);
-  const int RH = oh_hi - oh_lo + 1, RW = ow_hi - ow_lo + 1;
+  const int RH = max(oh_hi - oh_lo + 1, 0), RW = max(ow_hi - ow_lo + 1, 0);
+  const int P = RH * RW;  // output pixels scanned per output channel
   const int plane = p.Ho * p.Wo;
-  if (RH > 0 && RW > 0) {
-    for (int px = threadIdx.x; px < RH * RW; px += 256) {
-      const int oh = oh_lo + px / RW, ow = ow_lo + px % RW;
-      // position of tap (0, 0) of this output relative to the tile
-      const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw - w0;
-      size_t o = ((size_t)n * p.C_out) * plane + (size_t)oh * p.Wo + ow;
-#pragma unroll 4
-      for (int co = 0; co < p.C_out; ++co, o += plane) {
-        const float g = a.gy[o];
+  // per scanned pixel: position of its tap (0, 0) relative to the tile, and its offset in a plane
+  for (int px = threadIdx.x; px < P; px += bd) {
+    const int oh = oh_lo + px / RW, ow = ow_lo + px % RW;
+    const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw - w0;
+    tab[px] = make_int2((bh & 0xffff) | (bw << 16), oh * p.Wo + ow);
+  }
+  __syncthreads();
+
+  if (P > 0) {
+    const size_t nbase = (size_t)n * p.C_out * plane;
+    const int co_start = threadIdx.x / P, px_start = threadIdx.x - co_start * P;
+    const int dco = bd / P, dpx = bd - dco * P;
+    // ---- pass 1: the largest |term| this workgroup can add fixes the fixed-point scale
+    {
+      float m = 0.f;
+      int co = co_start, px = px_start;
+      while (co < p.C_out) {
+        float cm = 1.f;
+        if (SCALED) cm = fmaxf(a.alpha ? fabsf(a.alpha[co]) : 1.f, a.beta ? fabsf(a.beta[co]) : 1.f);
+        m = fmaxf(m, fabsf(a.gy[nbase + (size_t)co * plane + tab[px].y]) * cm);
+        px += dpx;
+        co += dco;
+        if (px >= P) { px -= P; ++co; }
+      }
+      block_max_nonneg(m, &s_gmax);
+    }
+    __syncthreads();
+    // |coef*gy| <= the fp32 product bound above up to one rounding: double it for safety
+    const int S = fixed_shift(2.f * __uint_as_float(s_gmax), (unsigned)p.C_out * (unsigned)P * 2u);
+    const double scale = ldexp(1.0, S);
+    // ---- pass 2: items (co, px) in px-major order (consecutive threads read consecutive pixels of a
+    // plane row); four items per thread in flight (12 independent loads)
+    constexpr int UB = 4;
+    int co = co_start, px = px_start;
+    while (co < p.C_out) {
+      int cov[UB], tx[UB];
+      size_t ov[UB];
+      float gv[UB];
+      int kmn[UB], kmx[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        cov[u] = co;
+        const bool ok = co < p.C_out;
+        const int2 t = tab[px];
+        tx[u] = t.x;
+        ov[u] = nbase + (size_t)(ok ? co : 0) * plane + t.y;
+        px += dpx;
+        co += dco;
+        if (px >= P) { px -= P; ++co; }
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        gv[u] = a.gy[ov[u]];
+        if (DO_MIN) kmn[u] = a.idx_min[ov[u]];
+        if (DO_MAX) kmx[u] = a.idx_max[ov[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (cov[u] >= p.C_out) continue;
+        const int bh = (int)(short)(tx[u] & 0xffff), bw = tx[u] >> 16;
+        const float g = gv[u];
         if (DO_MIN) {
-          const int k = a.idx_min[o];
+          const int k = kmn[u];
           const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd(&tile[(cc * TH + ih) * TW + iw], SCALED ? __fmul_rn(a.alpha ? a.alpha[co] : 1.0f, g) : g);
+            atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
+                      (unsigned long long)to_fixed((SCALED && a.alpha) ? a.alpha[cov[u]] : 1.0f, g, scale));
         }
         if (DO_MAX) {
-          const int k = a.idx_max[o];
+          const int k = kmx[u];
           const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd(&tile[(cc * TH + ih) * TW + iw], SCALED ? __fmul_rn(a.beta ? a.beta[co] : 1.0f, g) : g);
+            atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
+                      (unsigned long long)to_fixed((SCALED && a.beta) ? a.beta[cov[u]] : 1.0f, g, scale));
         }
       }
     }
-  }
-  __syncthreads();
-  const size_t HW = (size_t)p.H * p.W;
-  float* gxn = grad_x + (size_t)n * p.C_in * HW;
-  for (int e = threadIdx.x; e < tsz; e += 256) {
-    const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
-    if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
-      gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = tile[e];
+    __syncthreads();
+    const double inv = ldexp(1.0, -S);
+    const size_t HW = (size_t)p.H * p.W;
+    float* gxn = grad_x + (size_t)n * p.C_in * HW;
+    for (int e = threadIdx.x; e < tsz; e += bd) {
+      const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
+      if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
+        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = (float)((double)tile[e] * inv);
+    }
+  } else {  // no output reaches this tile: its gradient is zero
+    const size_t HW = (size_t)p.H * p.W;
+    float* gxn = grad_x + (size_t)n * p.C_in * HW;
+    for (int e = threadIdx.x; e < tsz; e += bd) {
+      const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
+      if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
+        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = 0.f;
+    }
   }
 }
 
@@ -147,7 +241,14 @@ __global__ __launch_bounds__(256) void bwd_input_tile_kernel(Params p, BwdArgs a
 // LDS budget, with a penalty for rows too short to coalesce.
 struct BwdInTile { int TH, TW, CC, tiles_h, tiles_w, chunks; };
 
-static BwdInTile choose_bwd_input_tile(const Params& p, int lds_floats) {
+// LDS bytes of a candidate: the tile plus one int2 per scanned output pixel (bounded by the tile grown
+// by the kernel extent).
+static size_t bwd_input_lds_bytes(const Params& p, int CC, int TH, int TW) {
+  const size_t region = (size_t)(TH + (p.KH - 1) * p.dh + p.sh) * (TW + (p.KW - 1) * p.dw + p.sw);
+  return (size_t)CC * TH * TW * sizeof(long long) + region * sizeof(int2);
+}
+
+static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
   BwdInTile best = {0, 0, 0, 0, 0, 0};
   double best_cost = 1e30;
   const int eh = (p.KH - 1) * p.dh, ew = (p.KW - 1) * p.dw;
@@ -155,19 +256,19 @@ static BwdInTile choose_bwd_input_tile(const Params& p, int lds_floats) {
     const int CC = (p.C_in + chunks - 1) / chunks;
     for (int TWc = 8; TWc <= 128; TWc *= 2) {
       const int TW = TWc < p.W ? TWc : p.W;
-      int TH = lds_floats / (CC * TW);
-      if (TH > p.H) TH = p.H;
-      if (TH > 64) TH = 64;
-      if (TH < 1) continue;
-      const int real_chunks = (p.C_in + CC - 1) / CC;
-      double cost = (double)real_chunks * (TH + eh) / TH * (TW + ew) / TW;
-      if (TW + ew < 16) cost *= 1.5;
-      const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
-      const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
-      if (wgs < 512) cost *= 1.0 + (512 - wgs) / 512;  // too few workgroups to fill 256 CUs
-      if (cost < best_cost) {
-        best_cost = cost;
-        best = {TH, TW, CC, tiles_h, tiles_w, real_chunks};
+      int TH = p.H < 64 ? p.H : 64;
+      while (TH >= 1 && bwd_input_lds_bytes(p, CC, TH, TW) > lds_budget) --TH;
+      if (TH >= 1) {
+        const int real_chunks = (p.C_in + CC - 1) / CC;
+        double cost = (double)real_chunks * (TH + eh) / TH * (TW + ew) / TW;
+        if (TW + ew < 16) cost *= 1.5;
+        const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
+        const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
+        if (wgs < 512) cost *= 1.0 + (512 - wgs) / 512;  // too few workgroups to fill 256 CUs
+        if (cost < best_cost) {
+          best_cost = cost;
+          best = {TH, TW, CC, tiles_h, tiles_w, real_chunks};
+        }
       }
       if (TW == p.W) break;
     }
@@ -177,14 +278,14 @@ static BwdInTile choose_bwd_input_tile(const Params& p, int lds_floats) {
 }
 
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
-  constexpr int LDS_FLOATS = 16 * 1024;  // 64 KB per workgroup: two workgroups share a CU's LDS
-  const BwdInTile t = choose_bwd_input_tile(p, LDS_FLOATS);
+  constexpr size_t LDS_BUDGET = 78 * 1024;  // per workgroup: two workgroups share a CU's 160 KB of LDS
+  const BwdInTile t = choose_bwd_input_tile(p, LDS_BUDGET);
   const long long blocks = (long long)p.N * t.tiles_h * t.tiles_w * t.chunks;
   if (t.TH >= 1 && blocks <= 0x7fffffffLL) {
-    const size_t lds = (size_t)t.CC * t.TH * t.TW * sizeof(float);
+    const size_t lds = bwd_input_lds_bytes(p, t.CC, t.TH, t.TW);
     const bool k3 = (p.KH == 3 && p.KW == 3);
 #define TCONV_LAUNCH_BWD_IN(M, K3)                                                              \
-  hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)blocks), dim3(256), lds, s, p, a, \
+  hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)blocks), dim3(1024), lds, s, p, a, \
                      grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks)
     switch (p.mode) {
       case TCONV_MAX: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MAX, true); else TCONV_LAUNCH_BWD_IN(TCONV_MAX, false); break;
@@ -214,13 +315,13 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
   return hipGetLastError();
 }
 
-// One block = one output channel x one slice of the batch.  The block keeps a K-bin
-// fp32 histogram per destination tensor in LDS, adds every (n, oh, ow) item of its
-// slice with LDS atomics, then flushes the non-zero bins with global atomics.
+// One block = one output channel x one slice of the batch.  The block keeps a K-bin 64-bit
+// fixed-point histogram per destination tensor in LDS, adds every (n, oh, ow) item of its slice with
+// integer LDS atomics, then flushes the non-zero bins (rounded to fp32 once) with global atomics.
 // NHIST = 1: a single destination (max, min, and compound where both branches share
 // one grad_w); NHIST = 2: parallel (min branch -> grad_w_min, max branch -> grad_w_max).
 template <int MODE>
-__global__ __launch_bounds__(256) void bwd_weight_hist_kernel(Params p, BwdArgs a,
+__global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ gw_min,
                                                               float* __restrict__ gw_max,
                                                               int n_per_block) {
@@ -228,40 +329,81 @@ __global__ __launch_bounds__(256) void bwd_weight_hist_kernel(Params p, BwdArgs 
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NHIST = (MODE == TCONV_PARALLEL) ? 2 : 1;
-  extern __shared__ float hist[];  // NHIST * K floats
+  extern __shared__ long long hist[];  // NHIST * K fixed-point sums
+  __shared__ unsigned s_gmax;
   const int co = blockIdx.x;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
   const int K = p.K;
-  for (int k = threadIdx.x; k < NHIST * K; k += blockDim.x) hist[k] = 0.f;
+  const int bd = blockDim.x;
+  for (int k = threadIdx.x; k < NHIST * K; k += bd) hist[k] = 0;
+  if (threadIdx.x == 0) s_gmax = 0u;
   __syncthreads();
-  float* hmin = hist;
-  float* hmax = hist + (NHIST - 1) * K;
+  long long* hmin = hist;
+  long long* hmax = hist + (NHIST - 1) * K;
   const float ca = SCALED ? (a.alpha ? a.alpha[co] : 1.0f) : 1.0f;
   const float cb = SCALED ? (a.beta ? a.beta[co] : 1.0f) : 1.0f;
   const int plane = p.Ho * p.Wo;
-  for (int n = n0; n < n1; ++n) {
-    const size_t base = ((size_t)n * p.C_out + co) * plane;
-    for (int q = threadIdx.x; q < plane; q += blockDim.x) {
-      const float g = a.gy[base + q];
-      if (DO_MIN) {
-        const int k = a.idx_min[base + q];
-        if ((unsigned)k < (unsigned)K) atomicAdd(hmin + k, SCALED ? __fmul_rn(ca, g) : g);
+  const int n_start = n0 + threadIdx.x / plane, q_start = threadIdx.x % plane;
+  const int dn = bd / plane, dq = bd % plane;
+  // ---- pass 1: largest |gy| of the slice fixes the fixed-point scale
+  {
+    float m = 0.f;
+    int n = n_start, q = q_start;
+    while (n < n1) {
+      m = fmaxf(m, fabsf(a.gy[((size_t)n * p.C_out + co) * plane + q]));
+      q += dq;
+      n += dn;
+      if (q >= plane) { q -= plane; ++n; }
+    }
+    block_max_nonneg(m, &s_gmax);
+  }
+  __syncthreads();
+  const float cmax = fmaxf(fabsf(ca), fabsf(cb));
+  const int S = fixed_shift(2.f * cmax * __uint_as_float(s_gmax), (unsigned)(n1 - n0) * (unsigned)plane * 2u);
+  const double scale = ldexp(1.0, S);
+  // ---- pass 2: items (image, pixel) of this slice, pixel-major; four per thread in flight
+  {
+    constexpr int UB = 4;
+    int n = n_start, q = q_start;
+    while (n < n1) {
+      size_t ov[UB];
+      bool okv[UB];
+      float gv[UB];
+      int kmn[UB], kmx[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        okv[u] = n < n1;
+        ov[u] = ((size_t)(okv[u] ? n : n0) * p.C_out + co) * plane + q;
+        q += dq;
+        n += dn;
+        if (q >= plane) { q -= plane; ++n; }
       }
-      if (DO_MAX) {
-        const int k = a.idx_max[base + q];
-        if ((unsigned)k < (unsigned)K) atomicAdd(hmax + k, SCALED ? __fmul_rn(cb, g) : g);
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        gv[u] = a.gy[ov[u]];
+        if (DO_MIN) kmn[u] = a.idx_min[ov[u]];
+        if (DO_MAX) kmx[u] = a.idx_max[ov[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (!okv[u]) continue;
+        if (DO_MIN && (unsigned)kmn[u] < (unsigned)K)
+          atomicAdd((unsigned long long*)(hmin + kmn[u]), (unsigned long long)to_fixed(ca, gv[u], scale));
+        if (DO_MAX && (unsigned)kmx[u] < (unsigned)K)
+          atomicAdd((unsigned long long*)(hmax + kmx[u]), (unsigned long long)to_fixed(cb, gv[u], scale));
       }
     }
   }
   __syncthreads();
+  const double inv = ldexp(1.0, -S);
   float* dmin = (MODE == TCONV_MAX) ? gw_max : gw_min;  // NHIST == 1: the single destination
-  for (int k = threadIdx.x; k < K; k += blockDim.x) {
-    const float v = hist[k];
-    if (v != 0.f) atomicAdd(dmin + (size_t)co * K + k, v);
+  for (int k = threadIdx.x; k < K; k += bd) {
+    const long long v = hist[k];
+    if (v != 0) atomicAdd(dmin + (size_t)co * K + k, (float)((double)v * inv));
     if (NHIST == 2) {
-      const float v2 = hmax[k];
-      if (v2 != 0.f) atomicAdd(gw_max + (size_t)co * K + k, v2);
+      const long long v2 = hmax[k];
+      if (v2 != 0) atomicAdd(gw_max + (size_t)co * K + k, (float)((double)v2 * inv));
     }
   }
 }
@@ -301,10 +443,10 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
   if (p.mode == TCONV_MAX || p.mode == TCONV_PARALLEL) fill_zero(gmax, wn, s);
 
   const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
-  const size_t lds = (size_t)nhist * p.K * sizeof(float);
+  const size_t lds = (size_t)nhist * p.K * sizeof(long long);
   if (lds <= 64 * 1024) {
-    // enough blocks to fill 256 CUs several times over, but at least one image per block
-    int slices = (4096 + p.C_out - 1) / p.C_out;
+    // two 1024-thread workgroups per CU; few slices keep the number of flush atomics small
+    int slices = (512 + p.C_out - 1) / p.C_out;
     if (slices > p.N) slices = p.N;
     if (slices < 1) slices = 1;
     const int n_per_block = (p.N + slices - 1) / slices;
@@ -312,16 +454,16 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
     dim3 grid(p.C_out, slices);
     switch (p.mode) {
       case TCONV_MAX:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MAX>, grid, dim3(256), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MAX>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
         break;
       case TCONV_MIN:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MIN>, grid, dim3(256), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MIN>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
         break;
       case TCONV_COMPOUND:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_COMPOUND>, grid, dim3(256), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_COMPOUND>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
         break;
       default:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_PARALLEL>, grid, dim3(256), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_PARALLEL>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
         break;
     }
   } else {
