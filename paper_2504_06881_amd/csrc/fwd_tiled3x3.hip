@@ -245,6 +245,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
 
   // ---- epilogue: exact tap of every extremum (first tap of the winning channel, in k order, whose
   // sum equals it), combine, store.  Each lane writes its 8 consecutive outputs with 16-byte stores.
+  // The winning-channel ids are parked in LDS (a private 16-byte-per-lane slot per row: no barrier)
+  // so that the gather batches below have registers to land in.
+  constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
+  __shared__ int4 stash[WAVES][NBR][TN][2][64];
+#pragma unroll
+  for (int c = 0; c < TN; ++c)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (DO_MIN) stash[wave][0][c][h][lane] = make_int4(imin[c][4 * h], imin[c][4 * h + 1], imin[c][4 * h + 2], imin[c][4 * h + 3]);
+      if (DO_MAX) stash[wave][NBR - 1][c][h][lane] = make_int4(imax[c][4 * h], imax[c][4 * h + 1], imax[c][4 * h + 2], imax[c][4 * h + 3]);
+    }
+  auto unstash = [&](int br, int c, int (&ids)[PX]) {
+    const int4 a0 = stash[wave][br][c][0][lane], a1 = stash[wave][br][c][1][lane];
+    ids[0] = a0.x; ids[1] = a0.y; ids[2] = a0.z; ids[3] = a0.w;
+    ids[4] = a1.x; ids[5] = a1.y; ids[6] = a1.z; ids[7] = a1.w;
+  };
   if (!unit_ok) return;
   const size_t wbytes = (size_t)p.C_out * p.K * sizeof(float);
   const rsrc_t wres_min = make_rsrc(DO_MIN ? w_min : w_max, (unsigned)wbytes);
@@ -258,38 +274,62 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
     rv[i] = (ih >= 0 && ih < p.H);
     ihc[i] = min(max(ih, 0), p.H - 1);
   }
-  auto refine = [&](int cs, float best, rsrc_t wres, int co, int q) -> int {
-    if (dbg & 1) return cs * 9;
-    cs = min(cs, p.C_in - 1);  // a virtual channel never wins; keep the address in range regardless
-    float wv[9];
-    load_run<9, float>(wv, wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
-    const int iwq = ow0 + q - p.pw;
-    int res = cs * 9;
+  // Exact taps for RB pixels of one (channel, branch) row at a time: first ALL gathers of the batch
+  // are issued (9 kernel values and a 3 x (2D+1) input patch per item), only then any is consumed,
+  // so the batch pays one memory latency instead of one per item.  Border pixels load their patch
+  // from a start clamped into the row and pick the taps with a per-lane shift.
+  constexpr int L = 2 * D + 1;           // contiguous input columns spanned by the 3 taps of a row
+  constexpr int RB = (D == 1) ? 4 : 2;   // items per batch (register budget)
+  auto refine_batch = [&](const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co, int q0,
+                          int (&res)[PX]) {
+    float wv[RB][9];
+    float run[RB][3][L];
+    int csv[RB], shv[RB];
 #pragma unroll
-    for (int i = 2; i >= 0; --i) {
-      const size_t rbase = xn_off + (size_t)cs * HW + (size_t)ihc[i] * p.W;
-      float xv[3];
-      bool cv[3];
-      if (q >= D && q <= 7 - D) {  // every tap column of this pixel lies inside the row
-        float run[2 * D + 1];
-        load_run<2 * D + 1, float>(run, xres, (unsigned)((rbase + iwq) * sizeof(float)), 0u);
+    for (int u = 0; u < RB; ++u) {
+      const int q = q0 + u;
+      const int cs = min(cs_row[q], p.C_in - 1);  // a virtual channel never wins; keep the address in range
+      csv[u] = cs;
+      load_run<9, float>(wv[u], wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
+      const int iwq = ow0 + q - p.pw;
+      const bool inner = (q >= D && q <= 7 - D);  // every tap column of this pixel lies inside the row
+      const int start = inner ? iwq : min(max(iwq, 0), p.W - L);
+      shv[u] = iwq - start;
 #pragma unroll
-        for (int j = 0; j < 3; ++j) { xv[j] = run[j * D]; cv[j] = true; }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 3; ++j) {
-          const int iw = iwq + j * D;
-          cv[j] = (iw >= 0 && iw < p.W);
-          xv[j] = load_one<float>(xres, (unsigned)((rbase + min(max(iw, 0), p.W - 1)) * sizeof(float)), 0u);
-        }
-      }
-#pragma unroll
-      for (int j = 2; j >= 0; --j) {
-        const float s = __fadd_rn(xv[j], wv[i * 3 + j]);
-        res = (rv[i] && cv[j] && s == best) ? cs * 9 + i * 3 + j : res;
+      for (int i = 0; i < 3; ++i) {
+        const size_t rbase = xn_off + (size_t)cs * HW + (size_t)ihc[i] * p.W;
+        load_run<L, float>(run[u][i], xres, (unsigned)((rbase + start) * sizeof(float)), 0u);
       }
     }
-    return res;
+    __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the batch ahead of every use
+#pragma unroll
+    for (int u = 0; u < RB; ++u) {
+      const int q = q0 + u;
+      const bool inner = (q >= D && q <= 7 - D);
+      const int iwq = ow0 + q - p.pw;
+      int r = csv[u] * 9;
+#pragma unroll
+      for (int i = 2; i >= 0; --i)
+#pragma unroll
+        for (int j = 2; j >= 0; --j) {
+          float xv;
+          bool ok = rv[i];
+          if (inner) {
+            xv = run[u][i][j * D];
+          } else {
+            const int col = j * D + shv[u];  // position of the tap inside the loaded run
+            xv = run[u][i][0];
+#pragma unroll
+            for (int t = 1; t < L; ++t) xv = (col == t) ? run[u][i][t] : xv;
+            const int iw = iwq + j * D;
+            ok = ok && (iw >= 0 && iw < p.W);
+          }
+          const float sum = __fadd_rn(xv, wv[u][i * 3 + j]);
+          r = (ok && sum == best_row[q]) ? csv[u] * 9 + i * 3 + j : r;
+        }
+      res[q] = (dbg & 1) ? csv[u] * 9 : r;
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the next batch starts after this one has retired its registers
   };
   const size_t plane = (size_t)p.Ho * p.Wo;
 #pragma unroll
@@ -302,17 +342,19 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
       if (alpha) ca = alpha[co];
       if (beta) cb = beta[co];
     }
-    int ridx[PX];
+    int ridx[PX], cids[PX];
     float out[PX];
     if (DO_MIN) {
+      unstash(0, c, cids);
 #pragma unroll
-      for (int q = 0; q < PX; ++q) ridx[q] = refine(imin[c][q], bmin[c][q], wres_min, co, q);
+      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmin[c], wres_min, co, q, ridx);
       store_row(idx_min + ob, ridx, first_q);
       if (y_min) store_row(y_min + ob, bmin[c], first_q);
     }
     if (DO_MAX) {
+      unstash(NBR - 1, c, cids);
 #pragma unroll
-      for (int q = 0; q < PX; ++q) ridx[q] = refine(imax[c][q], bmax[c][q], wres_max, co, q);
+      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmax[c], wres_max, co, q, ridx);
       store_row(idx_max + ob, ridx, first_q);
       if (y_max) store_row(y_max + ob, bmax[c], first_q);
     }
