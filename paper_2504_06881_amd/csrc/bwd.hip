@@ -9,6 +9,8 @@
 //
 // g_min = alpha[c_out]*gy and g_max = beta[c_out]*gy in compound / parallel mode
 // (paper Sec. 3.3 definitions), g = gy in max / min mode.
+#include <stdlib.h>
+
 #include "tconv_internal.h"
 
 namespace tconv {
@@ -17,8 +19,8 @@ namespace tconv {
 // than the integer LDS atomics (measured: ~190 cycles against ~16 per wave instruction with random
 // addresses), so both backward kernels accumulate in 64-bit fixed point with ds_add_u64.  The scale
 // 2^S is chosen per workgroup from the largest |term| it will add and the number of terms, so that
-// no sum can overflow 62 bits whatever the magnitude of the inputs; a term is the exact double product
-// coef*gy rounded once to a multiple of 2^-S (relative to the largest term: below 2^-40 for fewer
+// no sum can overflow 62 bits whatever the magnitude of the inputs; a term is the fp32 product
+// fl(coef*gy) rounded once to a multiple of 2^-S (relative to the largest term: below 2^-37 for fewer
 // than 2^20 terms).  Integer adds commute, so the per-workgroup sums are bit-reproducible, and each
 // is rounded to fp32 once at the end.
 __device__ __forceinline__ int fixed_shift(float gmax, unsigned items) {
@@ -26,10 +28,20 @@ __device__ __forceinline__ int fixed_shift(float gmax, unsigned items) {
   int e;
   frexpf(gmax, &e);                         // gmax < 2^e
   const int lg = 32 - __clz((int)items);    // items < 2^lg
-  return 62 - e - lg;
+  const int S = 62 - e - lg;
+  return S > 188 ? 188 : S;                 // keeps the shift of a denormal term within 39 bits
 }
-__device__ __forceinline__ long long to_fixed(float coef, float g, double scale) {
-  return __double2ll_rn((double)coef * (double)g * scale);
+// t * 2^S as a 64-bit integer (round half away from zero), in integer arithmetic: the 24-bit
+// significand shifted by the exponent.  |t| * 2^S < 2^62 by the choice of S, so the shift is <= 38.
+__device__ __forceinline__ long long to_fixed(float t, int S) {
+  const unsigned b = __float_as_uint(t);
+  const int e = (int)((b >> 23) & 0xffu);
+  const unsigned m = (b & 0x7fffffu) | (e ? 0x800000u : 0u);
+  const int sh = (e ? e : 1) - 150 + S;  // t = +-m * 2^(sh - S)
+  unsigned long long mag;
+  if (sh >= 0) mag = (unsigned long long)m << (sh > 39 ? 39 : sh);
+  else mag = (sh > -26) ? (unsigned long long)((m + (1u << (-sh - 1))) >> (-sh)) : 0ull;
+  return (b >> 31) ? -(long long)mag : (long long)mag;
 }
 // max over the workgroup of non-negative floats: wave reduction, then one LDS integer max per wave
 __device__ __forceinline__ void block_max_nonneg(float v, unsigned* slot) {
@@ -117,7 +129,12 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   extern __shared__ long long tile[];
   __shared__ unsigned s_gmax;
   const int bd = blockDim.x;
-  int b = blockIdx.x;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a contiguous
+  // run of tiles, so that the tiles of one image (which share halo rows of gy / idx) meet in one L2.
+  const int nblk = p.N * tiles_h * tiles_w * chunks;
+  const int per_xcd = (nblk + 7) / 8;
+  int b = (int)(blockIdx.x % 8u) * per_xcd + (int)(blockIdx.x / 8u);
+  if (b >= nblk || (int)(blockIdx.x / 8u) >= per_xcd) return;  // whole workgroup leaves before any barrier
   const int ch = b % chunks; b /= chunks;
   const int tw = b % tiles_w; b /= tiles_w;
   const int th = b % tiles_h;
@@ -167,7 +184,6 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
     __syncthreads();
     // |coef*gy| <= the fp32 product bound above up to one rounding: double it for safety
     const int S = fixed_shift(2.f * __uint_as_float(s_gmax), (unsigned)p.C_out * (unsigned)P * 2u);
-    const double scale = ldexp(1.0, S);
     // ---- pass 2: items (co, px) in px-major order (consecutive threads read consecutive pixels of a
     // plane row); four items per thread in flight (12 independent loads)
     constexpr int UB = 4;
@@ -205,7 +221,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
             atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
-                      (unsigned long long)to_fixed((SCALED && a.alpha) ? a.alpha[cov[u]] : 1.0f, g, scale));
+                      (unsigned long long)to_fixed((SCALED && a.alpha) ? __fmul_rn(a.alpha[cov[u]], g) : g, S));
         }
         if (DO_MAX) {
           const int k = kmx[u];
@@ -213,7 +229,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
             atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
-                      (unsigned long long)to_fixed((SCALED && a.beta) ? a.beta[cov[u]] : 1.0f, g, scale));
+                      (unsigned long long)to_fixed((SCALED && a.beta) ? __fmul_rn(a.beta[cov[u]], g) : g, S));
         }
       }
     }
@@ -278,14 +294,16 @@ static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
 }
 
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
-  constexpr size_t LDS_BUDGET = 78 * 1024;  // per workgroup: two workgroups share a CU's 160 KB of LDS
+  size_t LDS_BUDGET = 78 * 1024;  // per workgroup: two workgroups share a CU's 160 KB of LDS
+  if (const char* e = getenv("TCONV_BWD_LDS_KB")) LDS_BUDGET = (size_t)atoi(e) * 1024;
   const BwdInTile t = choose_bwd_input_tile(p, LDS_BUDGET);
   const long long blocks = (long long)p.N * t.tiles_h * t.tiles_w * t.chunks;
   if (t.TH >= 1 && blocks <= 0x7fffffffLL) {
     const size_t lds = bwd_input_lds_bytes(p, t.CC, t.TH, t.TW);
+    const long long grid_blocks = ((blocks + 7) / 8) * 8;  // the kernel remaps blockIdx per XCD
     const bool k3 = (p.KH == 3 && p.KW == 3);
 #define TCONV_LAUNCH_BWD_IN(M, K3)                                                              \
-  hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)blocks), dim3(1024), lds, s, p, a, \
+  hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)grid_blocks), dim3(1024), lds, s, p, a, \
                      grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks)
     switch (p.mode) {
       case TCONV_MAX: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MAX, true); else TCONV_LAUNCH_BWD_IN(TCONV_MAX, false); break;
@@ -361,7 +379,6 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
   __syncthreads();
   const float cmax = fmaxf(fabsf(ca), fabsf(cb));
   const int S = fixed_shift(2.f * cmax * __uint_as_float(s_gmax), (unsigned)(n1 - n0) * (unsigned)plane * 2u);
-  const double scale = ldexp(1.0, S);
   // ---- pass 2: items (image, pixel) of this slice, pixel-major; four per thread in flight
   {
     constexpr int UB = 4;
@@ -389,9 +406,9 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
       for (int u = 0; u < UB; ++u) {
         if (!okv[u]) continue;
         if (DO_MIN && (unsigned)kmn[u] < (unsigned)K)
-          atomicAdd((unsigned long long*)(hmin + kmn[u]), (unsigned long long)to_fixed(ca, gv[u], scale));
+          atomicAdd((unsigned long long*)(hmin + kmn[u]), (unsigned long long)to_fixed(SCALED ? __fmul_rn(ca, gv[u]) : gv[u], S));
         if (DO_MAX && (unsigned)kmx[u] < (unsigned)K)
-          atomicAdd((unsigned long long*)(hmax + kmx[u]), (unsigned long long)to_fixed(cb, gv[u], scale));
+          atomicAdd((unsigned long long*)(hmax + kmx[u]), (unsigned long long)to_fixed(SCALED ? __fmul_rn(cb, gv[u]) : gv[u], S));
       }
     }
   }
