@@ -5,7 +5,7 @@
 //
 //   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (input tile in LDS, LDS fp32 atomics, plain stores)
 //   backward_weight: grad_w_b[c_out, k*]    += g_b   (per-c_out LDS histogram, then flush)
-// Both accumulate in 64-bit fixed point (see fixed_shift below).
+// Both accumulate in fp64 in LDS (see below).
 //
 // g_min = alpha[c_out]*gy and g_max = beta[c_out]*gy in compound / parallel mode
 // (paper Sec. 3.3 definitions), g = gy in max / min mode.
@@ -15,40 +15,11 @@
 
 namespace tconv {
 
-// ---- fixed-point accumulation.  On gfx950 an LDS fp32 atomic add (ds_add_f32) runs about 12x slower
-// than the integer LDS atomics (measured: ~190 cycles against ~16 per wave instruction with random
-// addresses), so both backward kernels accumulate in 64-bit fixed point with ds_add_u64.  The scale
-// 2^S is chosen per workgroup from the largest |term| it will add and the number of terms, so that
-// no sum can overflow 62 bits whatever the magnitude of the inputs; a term is the fp32 product
-// fl(coef*gy) rounded once to a multiple of 2^-S (relative to the largest term: below 2^-37 for fewer
-// than 2^20 terms).  Integer adds commute, so the per-workgroup sums are bit-reproducible, and each
-// is rounded to fp32 once at the end.
-__device__ __forceinline__ int fixed_shift(float gmax, unsigned items) {
-  if (!(gmax > 0.f)) return 0;
-  int e;
-  frexpf(gmax, &e);                         // gmax < 2^e
-  const int lg = 32 - __clz((int)items);    // items < 2^lg
-  const int S = 62 - e - lg;
-  return S > 188 ? 188 : S;                 // keeps the shift of a denormal term within 39 bits
-}
-// t * 2^S as a 64-bit integer (round half away from zero), in integer arithmetic: the 24-bit
-// significand shifted by the exponent.  |t| * 2^S < 2^62 by the choice of S, so the shift is <= 38.
-__device__ __forceinline__ long long to_fixed(float t, int S) {
-  const unsigned b = __float_as_uint(t);
-  const int e = (int)((b >> 23) & 0xffu);
-  const unsigned m = (b & 0x7fffffu) | (e ? 0x800000u : 0u);
-  const int sh = (e ? e : 1) - 150 + S;  // t = +-m * 2^(sh - S)
-  unsigned long long mag;
-  if (sh >= 0) mag = (unsigned long long)m << (sh > 39 ? 39 : sh);
-  else mag = (sh > -26) ? (unsigned long long)((m + (1u << (-sh - 1))) >> (-sh)) : 0ull;
-  return (b >> 31) ? -(long long)mag : (long long)mag;
-}
-// max over the workgroup of non-negative floats: wave reduction, then one LDS integer max per wave
-__device__ __forceinline__ void block_max_nonneg(float v, unsigned* slot) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  if ((threadIdx.x & 63) == 0) atomicMax(slot, __float_as_uint(v));
-}
+// ---- accumulation in LDS.  On gfx950 an LDS fp32 atomic add (ds_add_f32) runs about 9-12x slower than
+// the 64-bit LDS atomics (measured with random addresses, cycles per wave instruction: ds_add_f32 ~190,
+// ds_add_u64 ~16, ds_add_f64 ~22).  Both backward kernels therefore accumulate in fp64 with ds_add_f64:
+// every term is the exact double product coef*gy, the order-dependence of the sum is at the 1e-16
+// level, and each sum is rounded to fp32 once at the end.
 
 // Zero n floats: float4 stores over the 16-byte-aligned body, scalar stores for the ragged ends.
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, size_t n) {
@@ -113,7 +84,7 @@ __global__ __launch_bounds__(256) void bwd_input_scatter_kernel(Params p, BwdArg
 // Tiled backward-input: no global atomics.  One workgroup owns an INPUT tile (CC channels x TH x TW
 // pixels of one image) in LDS, scans every output whose window can reach the tile (the tile grown by
 // the kernel extent, all C_out channels, every live branch), adds the gradients that land inside
-// with 64-bit fixed-point LDS atomics and finally writes the tile to grad_x with plain coalesced stores.  Every input
+// with fp64 LDS atomics and finally writes the tile to grad_x with plain coalesced stores.  Every input
 // element belongs to exactly one workgroup, so grad_x needs no zero fill.  The price is re-reading
 // gy / idx for the halo: (TH+e)(TW+e)/(TH*TW) times the algorithmic bytes (times the number of
 // channel chunks when C_in*TH*TW does not fit in LDS); neighbouring tiles share those lines in L2.
@@ -125,9 +96,8 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  // [CC][TH][TW] 64-bit fixed-point sums, then one int2 per output pixel of the scanned region
-  extern __shared__ long long tile[];
-  __shared__ unsigned s_gmax;
+  // [CC][TH][TW] fp64 sums, then one int2 per output pixel of the scanned region
+  extern __shared__ double tile[];
   const int bd = blockDim.x;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a contiguous
   // run of tiles, so that the tiles of one image (which share halo rows of gy / idx) meet in one L2.
@@ -142,8 +112,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   const int h0 = th * TH, w0 = tw * TW, c0 = ch * CC;
   const int tsz = CC * TH * TW;
   int2* tab = (int2*)(tile + tsz);
-  for (int e = threadIdx.x; e < tsz; e += bd) tile[e] = 0;
-  if (threadIdx.x == 0) s_gmax = 0u;
+  for (int e = threadIdx.x; e < tsz; e += bd) tile[e] = 0.0;
 
   // outputs whose window can reach the tile
   const int KHs = K3 ? 3 : p.KH, KWs = K3 ? 3 : p.KW, KK = KHs * KWs;
@@ -167,24 +136,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
     const size_t nbase = (size_t)n * p.C_out * plane;
     const int co_start = threadIdx.x / P, px_start = threadIdx.x - co_start * P;
     const int dco = bd / P, dpx = bd - dco * P;
-    // ---- pass 1: the largest |term| this workgroup can add fixes the fixed-point scale
-    {
-      float m = 0.f;
-      int co = co_start, px = px_start;
-      while (co < p.C_out) {
-        float cm = 1.f;
-        if (SCALED) cm = fmaxf(a.alpha ? fabsf(a.alpha[co]) : 1.f, a.beta ? fabsf(a.beta[co]) : 1.f);
-        m = fmaxf(m, fabsf(a.gy[nbase + (size_t)co * plane + tab[px].y]) * cm);
-        px += dpx;
-        co += dco;
-        if (px >= P) { px -= P; ++co; }
-      }
-      block_max_nonneg(m, &s_gmax);
-    }
-    __syncthreads();
-    // |coef*gy| <= the fp32 product bound above up to one rounding: double it for safety
-    const int S = fixed_shift(2.f * __uint_as_float(s_gmax), (unsigned)p.C_out * (unsigned)P * 2u);
-    // ---- pass 2: items (co, px) in px-major order (consecutive threads read consecutive pixels of a
+    // items (co, px) in px-major order (consecutive threads read consecutive pixels of a
     // plane row); four items per thread in flight (12 independent loads)
     constexpr int UB = 4;
     int co = co_start, px = px_start;
@@ -220,27 +172,26 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
           const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
-                      (unsigned long long)to_fixed((SCALED && a.alpha) ? __fmul_rn(a.alpha[cov[u]], g) : g, S));
+            atomicAdd(&tile[(cc * TH + ih) * TW + iw],
+                      (SCALED && a.alpha) ? (double)a.alpha[cov[u]] * (double)g : (double)g);
         }
         if (DO_MAX) {
           const int k = kmx[u];
           const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd((unsigned long long*)&tile[(cc * TH + ih) * TW + iw],
-                      (unsigned long long)to_fixed((SCALED && a.beta) ? __fmul_rn(a.beta[cov[u]], g) : g, S));
+            atomicAdd(&tile[(cc * TH + ih) * TW + iw],
+                      (SCALED && a.beta) ? (double)a.beta[cov[u]] * (double)g : (double)g);
         }
       }
     }
     __syncthreads();
-    const double inv = ldexp(1.0, -S);
     const size_t HW = (size_t)p.H * p.W;
     float* gxn = grad_x + (size_t)n * p.C_in * HW;
     for (int e = threadIdx.x; e < tsz; e += bd) {
       const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
       if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
-        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = (float)((double)tile[e] * inv);
+        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = (float)tile[e];
     }
   } else {  // no output reaches this tile: its gradient is zero
     const size_t HW = (size_t)p.H * p.W;
@@ -261,7 +212,7 @@ struct BwdInTile { int TH, TW, CC, tiles_h, tiles_w, chunks; };
 // by the kernel extent).
 static size_t bwd_input_lds_bytes(const Params& p, int CC, int TH, int TW) {
   const size_t region = (size_t)(TH + (p.KH - 1) * p.dh + p.sh) * (TW + (p.KW - 1) * p.dw + p.sw);
-  return (size_t)CC * TH * TW * sizeof(long long) + region * sizeof(int2);
+  return (size_t)CC * TH * TW * sizeof(double) + region * sizeof(int2);
 }
 
 static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
@@ -333,9 +284,9 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
   return hipGetLastError();
 }
 
-// One block = one output channel x one slice of the batch.  The block keeps a K-bin 64-bit
-// fixed-point histogram per destination tensor in LDS, adds every (n, oh, ow) item of its slice with
-// integer LDS atomics, then flushes the non-zero bins (rounded to fp32 once) with global atomics.
+// One block = one output channel x one slice of the batch.  The block keeps a K-bin fp64 histogram
+// per destination tensor in LDS, adds every (n, oh, ow) item of its slice with LDS atomics, then
+// flushes the non-zero bins (rounded to fp32 once) with global atomics.
 // NHIST = 1: a single destination (max, min, and compound where both branches share
 // one grad_w); NHIST = 2: parallel (min branch -> grad_w_min, max branch -> grad_w_max).
 template <int MODE>
@@ -347,39 +298,22 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NHIST = (MODE == TCONV_PARALLEL) ? 2 : 1;
-  extern __shared__ long long hist[];  // NHIST * K fixed-point sums
-  __shared__ unsigned s_gmax;
+  extern __shared__ double hist[];  // NHIST * K sums
   const int co = blockIdx.x;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
   const int K = p.K;
   const int bd = blockDim.x;
-  for (int k = threadIdx.x; k < NHIST * K; k += bd) hist[k] = 0;
-  if (threadIdx.x == 0) s_gmax = 0u;
+  for (int k = threadIdx.x; k < NHIST * K; k += bd) hist[k] = 0.0;
   __syncthreads();
-  long long* hmin = hist;
-  long long* hmax = hist + (NHIST - 1) * K;
+  double* hmin = hist;
+  double* hmax = hist + (NHIST - 1) * K;
   const float ca = SCALED ? (a.alpha ? a.alpha[co] : 1.0f) : 1.0f;
   const float cb = SCALED ? (a.beta ? a.beta[co] : 1.0f) : 1.0f;
   const int plane = p.Ho * p.Wo;
   const int n_start = n0 + threadIdx.x / plane, q_start = threadIdx.x % plane;
   const int dn = bd / plane, dq = bd % plane;
-  // ---- pass 1: largest |gy| of the slice fixes the fixed-point scale
-  {
-    float m = 0.f;
-    int n = n_start, q = q_start;
-    while (n < n1) {
-      m = fmaxf(m, fabsf(a.gy[((size_t)n * p.C_out + co) * plane + q]));
-      q += dq;
-      n += dn;
-      if (q >= plane) { q -= plane; ++n; }
-    }
-    block_max_nonneg(m, &s_gmax);
-  }
-  __syncthreads();
-  const float cmax = fmaxf(fabsf(ca), fabsf(cb));
-  const int S = fixed_shift(2.f * cmax * __uint_as_float(s_gmax), (unsigned)(n1 - n0) * (unsigned)plane * 2u);
-  // ---- pass 2: items (image, pixel) of this slice, pixel-major; four per thread in flight
+  // items (image, pixel) of this slice, pixel-major; four per thread in flight
   {
     constexpr int UB = 4;
     int n = n_start, q = q_start;
@@ -406,21 +340,20 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
       for (int u = 0; u < UB; ++u) {
         if (!okv[u]) continue;
         if (DO_MIN && (unsigned)kmn[u] < (unsigned)K)
-          atomicAdd((unsigned long long*)(hmin + kmn[u]), (unsigned long long)to_fixed(SCALED ? __fmul_rn(ca, gv[u]) : gv[u], S));
+          atomicAdd(hmin + kmn[u], SCALED ? (double)ca * (double)gv[u] : (double)gv[u]);
         if (DO_MAX && (unsigned)kmx[u] < (unsigned)K)
-          atomicAdd((unsigned long long*)(hmax + kmx[u]), (unsigned long long)to_fixed(SCALED ? __fmul_rn(cb, gv[u]) : gv[u], S));
+          atomicAdd(hmax + kmx[u], SCALED ? (double)cb * (double)gv[u] : (double)gv[u]);
       }
     }
   }
   __syncthreads();
-  const double inv = ldexp(1.0, -S);
   float* dmin = (MODE == TCONV_MAX) ? gw_max : gw_min;  // NHIST == 1: the single destination
   for (int k = threadIdx.x; k < K; k += bd) {
-    const long long v = hist[k];
-    if (v != 0) atomicAdd(dmin + (size_t)co * K + k, (float)((double)v * inv));
+    const double v = hist[k];
+    if (v != 0.0) atomicAdd(dmin + (size_t)co * K + k, (float)v);
     if (NHIST == 2) {
-      const long long v2 = hmax[k];
-      if (v2 != 0) atomicAdd(gw_max + (size_t)co * K + k, (float)((double)v2 * inv));
+      const double v2 = hmax[k];
+      if (v2 != 0.0) atomicAdd(gw_max + (size_t)co * K + k, (float)v2);
     }
   }
 }
@@ -460,7 +393,7 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
   if (p.mode == TCONV_MAX || p.mode == TCONV_PARALLEL) fill_zero(gmax, wn, s);
 
   const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
-  const size_t lds = (size_t)nhist * p.K * sizeof(long long);
+  const size_t lds = (size_t)nhist * p.K * sizeof(double);
   if (lds <= 64 * 1024) {
     // two 1024-thread workgroups per CU; few slices keep the number of flush atomics small
     int slices = (512 + p.C_out - 1) / p.C_out;
