@@ -1,29 +1,31 @@
-// Tiled forward kernel for 3x3, stride-1 tropical convolutions on gfx950: a VALU "semiring GEMM".
+// Tiled forward kernel for 3x3 tropical convolutions on gfx950: a VALU "semiring GEMM".
 //
 // Operator: paper Sec. 3.1 layers (iv) / (v) (one min / max over all C_in*9 taps of x + w) and the
 // Sec. 3.3 compound (one shared add feeds both reductions, Sec. 3.5 closing remark) and parallel
 // combinations.  The semiring has no multiply, so the matrix cores do not apply; the kernel is
 // built for the vector ALUs:
 //
-//  * A lane owns a row segment of 8 consecutive output pixels and 4 output channels: 32 running
-//    extrema per branch stay in VGPRs for the whole K loop.  The 4 waves of a workgroup share the
-//    pixel segments (same x lines in L1) and differ in output-channel group.  No LDS, no barrier.
+//  * A lane owns a row segment of PX consecutive output pixels (8 at stride 1, 4 at stride 2) and 4
+//    output channels: 4*PX running extrema per branch stay in VGPRs for the whole K loop.  The 4
+//    waves of a workgroup share the pixel segments (same x lines in L1) and differ in output-channel
+//    group.  The main loop uses no LDS and no barrier.
 //  * Kernel values are wave-uniform: scalar loads straight from the OIHW tensor (k is contiguous
 //    per c_out) put the 18 values of a channel pair in SGPRs, where they are the scalar operand
 //    of v_add_f32 - no repacking pass, no VGPRs, no LDS.
-//  * Implicit im2col: per channel a lane loads 3 rows x (8 + 2*dil) input values once (raw buffer
-//    loads: wave-uniform descriptor + 32-bit lane offset + uniform channel offset) and reuses them
-//    for 9 taps x 8 pixels x 4 channels.  Padding becomes NaN with one OR per loaded value;
-//    v_max/v_min/v_max3/v_min3 return the non-NaN operand, so a padded tap never wins in either
-//    branch and costs nothing in the inner loop.
+//  * Implicit im2col: per channel a lane loads 3 rows x ((PX-1)*stride + 2*dil + 1) input values
+//    once (raw buffer loads: wave-uniform descriptor + 32-bit lane offset + uniform channel offset)
+//    and reuses them for 9 taps x PX pixels x 4 channels.  Padding becomes NaN with one OR per loaded
+//    value; v_max/v_min/v_max3/v_min3 return the non-NaN operand, so a padded tap never wins in
+//    either branch and costs nothing in the inner loop.
 //  * Inner blocks (tile_blocks_gfx950.h, hand-scheduled): one accumulator walks two channels
 //    (18 taps) with 18 adds, v_max3/v_min3 chains, and 2 compares + 2 selects per branch that
 //    record the winning CHANNEL.  After the K loop the epilogue re-evaluates the 9 taps of that
 //    channel and takes the first that equals the extremum: exactly the lowest winning tap.
-//  * Register-resident software pipeline: the six x rows of a channel pair occupy six register
-//    slots.  Pixels are walked left to right, so the low columns of every slot die first; they
-//    are re-loaded for the NEXT channel pair in the middle of the current one, the high columns
-//    at its end, and each half is masked just before its first use.
+//  * Register-resident software pipeline for the six x rows of a channel pair.  Stride 1: six slots;
+//    pixels are walked left to right, so the low columns of every slot die first and are re-loaded
+//    for the NEXT channel pair in the middle of the current one, the high columns at its end.
+//    Stride 2: the rows are short, two full sets of slots alternate (the pair loop is unrolled by two).
+//    Masks are applied just before the first use.
 #include <stdlib.h>
 
 #include "tile_common.h"
@@ -37,27 +39,26 @@ using namespace tile;
 
 constexpr int TN = 4;  // output channels per lane
 
-// 9 x values of pixel q for the 3x3 taps of one channel: rows[i][q + j*D]
-template <int D, int XR>
+// 9 x values of pixel q for the 3x3 taps of one channel: rows[3*ch + i][q*S + j*D]
+template <int S, int D, int XR>
 __device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][XR], int ch, int q) {
 #pragma unroll
   for (int i = 0; i < 3; ++i)
 #pragma unroll
-    for (int j = 0; j < 3; ++j) out[i * 3 + j] = rows[ch * 3 + i][q + j * D];
+    for (int j = 0; j < 3; ++j) out[i * 3 + j] = rows[ch * 3 + i][q * S + j * D];
 }
 
-template <int MODE, int D, typename TO>
-__global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
+template <int MODE, int S, int D, typename TO>
+__global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
     int n_units, int n_groups, int dbg) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
-  constexpr int XR = 8 + 2 * D;  // input columns a lane touches per row
-  constexpr int H1 = D + 4;      // columns [0, H1): left halo + first half of the core
-  constexpr int P1 = D + 3;      // first-half columns are dead once pixel P1 is done
-  constexpr int P2 = 4 - D;      // second-half columns are first read by pixel P2
+  constexpr int PX = (S == 1) ? 8 : 4;          // output pixels per lane
+  constexpr int NC = (PX - 1) * S + 1;          // core columns [D, D+NC): always inside the row
+  constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
@@ -73,30 +74,31 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
   const int seg = unit % segs;
   const int oh = (unit / segs) % p.Ho;
   const int n = unit / (segs * p.Ho);
-  // the last segment of a row is shifted left so that every lane owns 8 real pixels;
+  // the last segment of a row is shifted left so that every lane owns PX real pixels;
   // pixels it shares with its neighbour are computed twice and stored once
   const int ow_nom = seg * PX;
   const int ow0 = min(ow_nom, p.Wo - PX);
   const int first_q = ow_nom - ow0;
 
   // ---- channel-independent addressing and padding masks
-  const int iw0 = ow0 - p.pw;  // input column of register column 0
+  const int iw0 = ow0 * S - p.pw;  // input column of register column 0
   const size_t HW = (size_t)p.H * p.W;
   const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
   unsigned roff[3];  // byte offset of the first core column (iw0 + D >= 0) of each (clamped) row
   unsigned mrow[3];  // all-ones where the row is padding
+  int ihc[3];        // clamped input rows of the three kernel rows
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
-    const int ih = oh - p.ph + i * D;
+    const int ih = oh * S - p.ph + i * D;
     mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
-    const int ihc = min(max(ih, 0), p.H - 1);
-    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(float));
+    ihc[i] = min(max(ih, 0), p.H - 1);
+    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc[i] * p.W + (size_t)(iw0 + D)) * sizeof(float));
   }
   int hoff[2 * D];         // clamped byte offsets of the halo columns relative to roff
   unsigned mhalo[2 * D];   // all-ones where the halo column is padding
 #pragma unroll
   for (int h = 0; h < 2 * D; ++h) {
-    const int o = (h < D) ? h : h + 8;
+    const int o = (h < D) ? h : h + NC;
     const int iw = iw0 + o;
     mhalo[h] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
     hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
@@ -125,32 +127,35 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
   // ---- main loop over channel pairs (cA = 2*du, cB = 2*du + 1; an odd C_in gets a virtual last
   // channel whose x is all NaN)
   const int ndu = (dbg & 2) ? 0 : (p.C_in + 1) >> 1;
-  float xs[6][XR];  // slot = 3*(channel parity) + kernel row
 
   auto chan_soff = [&](int c) -> unsigned {  // wave-uniform byte offset of channel c (clamped)
     return (unsigned)((size_t)min(c, p.C_in - 1) * HW * sizeof(float));
   };
-  auto issue_first = [&](int du) {  // left halo + first 4 core columns of all six rows
+  // loads of columns [lo, hi) of all six rows of channel pair du; lo / hi fall on the boundaries
+  // {0, D, D+4, D+NC, XR} so that every piece is a halo single or a run of the core
+  auto issue_cols = [&](float (&xs)[6][XR], int du, int lo, int hi) {
 #pragma unroll
     for (int sl = 0; sl < 6; ++sl) {
       const unsigned soff = chan_soff(2 * du + sl / 3);
       const unsigned ro = roff[sl % 3];
-      load_run<4, float>(&xs[sl][D], xres, ro, soff);
+      if (lo == 0) {
 #pragma unroll
-      for (int h = 0; h < D; ++h) xs[sl][h] = load_one<float>(xres, ro + (unsigned)hoff[h], soff);
+        for (int h = 0; h < D; ++h) xs[sl][h] = load_one<float>(xres, ro + (unsigned)hoff[h], soff);
+      }
+      if (lo <= D && hi >= D + NC) {
+        load_run<NC, float>(&xs[sl][D], xres, ro, soff);
+      } else if (lo <= D) {
+        load_run<4, float>(&xs[sl][D], xres, ro, soff);                    // first 4 core columns
+      } else {
+        load_run<NC - 4, float>(&xs[sl][D + 4], xres, ro + 16u, soff);      // the rest of the core
+      }
+      if (hi == XR) {
+#pragma unroll
+        for (int h = 0; h < D; ++h) xs[sl][D + NC + h] = load_one<float>(xres, ro + (unsigned)hoff[D + h], soff);
+      }
     }
   };
-  auto issue_second = [&](int du) {  // last 4 core columns + right halo
-#pragma unroll
-    for (int sl = 0; sl < 6; ++sl) {
-      const unsigned soff = chan_soff(2 * du + sl / 3);
-      const unsigned ro = roff[sl % 3];
-      load_run<4, float>(&xs[sl][D + 4], xres, ro + 16u, soff);
-#pragma unroll
-      for (int h = 0; h < D; ++h) xs[sl][D + 8 + h] = load_one<float>(xres, ro + (unsigned)hoff[D + h], soff);
-    }
-  };
-  auto mask_cols = [&](int lo, int hi, unsigned mB) {  // padding -> NaN for columns [lo, hi)
+  auto mask_cols = [&](float (&xs)[6][XR], int lo, int hi, unsigned mB) {  // padding -> NaN, columns [lo, hi)
 #pragma unroll
     for (int sl = 0; sl < 6; ++sl) {
       const unsigned mr = mrow[sl % 3] | (sl >= 3 ? mB : 0u);
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
         if (o < lo || o >= hi) continue;
         unsigned m = mr;
         if (o < D) m |= mhalo[o];
-        if (o >= D + 8) m |= mhalo[o - 8];
+        if (o >= D + NC) m |= mhalo[o - NC];
         xs[sl][o] = nan_or(xs[sl][o], m);
       }
     }
@@ -172,29 +177,19 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
 #pragma unroll
     for (int t = 0; t < 9; ++t) { wv[t] = pa[t]; wv[9 + t] = pb[t]; }
   };
-
-  if (ndu > 0) {
-    issue_first(0);
-    issue_second(0);
-  }
-  for (int du = 0; du < ndu; ++du) {
-    const int dn = min(du + 1, ndu - 1);  // past the end: re-load the last pair (unused, in bounds)
-    const int cA = 2 * du, cBv = 2 * du + 1;
-    const int cB = min(cBv, p.C_in - 1);
-    const unsigned mB = (cBv < p.C_in) ? 0u : 0xffffffffu;
-    const int tA = cA, tB = cBv;
-    mask_cols(0, H1, mB);
-    if (MODE == TCONV_COMPOUND) {
-      float wc[18], wn[18];
-      load_w(wc, wr_max[0], cA, cB);
+  // the blocks of pixels [q_lo, q_hi) for all four channels; wc carries the kernel values of the
+  // next block to run (they are fetched one block ahead)
+  constexpr int QSTEP = (MODE == TCONV_COMPOUND) ? 1 : 2;  // single-branch blocks cover two pixels
+  auto do_pixels = [&](float (&xs)[6][XR], float (&wc)[18], int q_lo, int q_hi, int cA, int cB, int tA, int tB) {
 #pragma unroll
-      for (int q = 0; q < PX; ++q) {
-        if (q == P2) mask_cols(H1, XR, mB);
+    for (int q = q_lo; q < q_hi; q += QSTEP) {
+      if (MODE == TCONV_COMPOUND) {
         float xA[9], xB[9];
-        taps_of<D, XR>(xA, xs, 0, q);
-        taps_of<D, XR>(xB, xs, 1, q);
+        taps_of<S, D, XR>(xA, xs, 0, q);
+        taps_of<S, D, XR>(xB, xs, 1, q);
 #pragma unroll
         for (int c = 0; c < TN; ++c) {
+          float wn[18];
           load_w(wn, wr_max[(c + 1) % TN], cA, cB);
           float wA[9], wB[9];
 #pragma unroll
@@ -203,21 +198,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
 #pragma unroll
           for (int t = 0; t < 18; ++t) wc[t] = wn[t];
         }
-        if (q == P1) issue_first(dn);
-      }
-    } else {
-      // single-branch blocks cover two pixels; parallel mode runs a max block and a min block
-      constexpr int NB = (MODE == TCONV_PARALLEL) ? 2 : 1;
-      float wc[18], wn[18];
-      load_w(wc, DO_MAX ? wr_max[0] : wr_min[0], cA, cB);
-#pragma unroll
-      for (int q = 0; q < PX; q += 2) {
-        if (q == (P2 & ~1)) mask_cols(H1, XR, mB);
+      } else {
+        // parallel mode runs a max block and a min block per pixel pair
+        constexpr int NB = (MODE == TCONV_PARALLEL) ? 2 : 1;
         float xA0[9], xB0[9], xA1[9], xB1[9];
-        taps_of<D, XR>(xA0, xs, 0, q);
-        taps_of<D, XR>(xB0, xs, 1, q);
-        taps_of<D, XR>(xA1, xs, 0, q + 1);
-        taps_of<D, XR>(xB1, xs, 1, q + 1);
+        taps_of<S, D, XR>(xA0, xs, 0, q);
+        taps_of<S, D, XR>(xB0, xs, 1, q);
+        taps_of<S, D, XR>(xA1, xs, 0, q + 1);
+        taps_of<S, D, XR>(xB1, xs, 1, q + 1);
 #pragma unroll
         for (int c = 0; c < TN; ++c)
 #pragma unroll
@@ -226,6 +214,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
             // next block in program order: other branch of the same channel, or next channel
             const int cn = (b == NB - 1) ? (c + 1) % TN : c;
             const bool next_is_max = (MODE == TCONV_MAX) || (MODE == TCONV_PARALLEL && ((b + 1) % NB) == 0);
+            float wn[18];
             load_w(wn, next_is_max ? wr_max[cn] : wr_min[cn], cA, cB);
             float wA[9], wB[9];
 #pragma unroll
@@ -237,47 +226,91 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
 #pragma unroll
             for (int t = 0; t < 18; ++t) wc[t] = wn[t];
           }
-        if (q == (P1 & ~1)) issue_first(dn);
       }
     }
-    issue_second(dn);
+  };
+  const float* w_first = DO_MAX ? wr_max[0] : wr_min[0];  // kernel row of the first block of a pair
+
+  if constexpr (S == 1) {
+    // six slots, column-phased: columns [0, H1) are dead once pixel P1 is done and are first needed
+    // again at pixel 0; columns [H1, XR) are first read by pixel P2
+    constexpr int H1 = D + 4;
+    constexpr int QA = (4 - D) & ~(QSTEP - 1);            // first pixel (block start) reading column H1
+    constexpr int QB = ((D + 3) | (QSTEP - 1)) + 1;       // first pixel after the last reader of column H1 - 1
+    float xs[6][XR];
+    if (ndu > 0) issue_cols(xs, 0, 0, XR);
+    for (int du = 0; du < ndu; ++du) {
+      const int dn = min(du + 1, ndu - 1);  // past the end: re-load the last pair (unused, in bounds)
+      const int cA = 2 * du, cBv = 2 * du + 1, cB = min(cBv, p.C_in - 1);
+      const unsigned mB = (cBv < p.C_in) ? 0u : 0xffffffffu;
+      float wc[18];
+      load_w(wc, w_first, cA, cB);
+      mask_cols(xs, 0, H1, mB);
+      do_pixels(xs, wc, 0, QA, cA, cB, cA, cBv);
+      mask_cols(xs, H1, XR, mB);
+      do_pixels(xs, wc, QA, QB, cA, cB, cA, cBv);
+      issue_cols(xs, dn, 0, H1);
+      do_pixels(xs, wc, QB, PX, cA, cB, cA, cBv);
+      issue_cols(xs, dn, H1, XR);
+    }
+  } else {
+    // two sets of six slots: the rows of the next pair are loaded while the current pair runs
+    float xs0[6][XR], xs1[6][XR];
+    if (ndu > 0) issue_cols(xs0, 0, 0, XR);
+    for (int du = 0; du < ndu; du += 2) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int d = du + half;
+        if (d < ndu) {  // wave-uniform
+          const int dn = min(d + 1, ndu - 1);
+          const int cA = 2 * d, cBv = 2 * d + 1, cB = min(cBv, p.C_in - 1);
+          const unsigned mB = (cBv < p.C_in) ? 0u : 0xffffffffu;
+          float wc[18];
+          load_w(wc, w_first, cA, cB);
+          if (half == 0) {
+            issue_cols(xs1, dn, 0, XR);
+            mask_cols(xs0, 0, XR, mB);
+            do_pixels(xs0, wc, 0, PX, cA, cB, cA, cBv);
+          } else {
+            issue_cols(xs0, dn, 0, XR);
+            mask_cols(xs1, 0, XR, mB);
+            do_pixels(xs1, wc, 0, PX, cA, cB, cA, cBv);
+          }
+        }
+      }
+    }
   }
 
   // ---- epilogue: exact tap of every extremum (first tap of the winning channel, in k order, whose
-  // sum equals it), combine, store.  Each lane writes its 8 consecutive outputs with 16-byte stores.
+  // sum equals it), combine, store.  Each lane writes its PX consecutive outputs with 16-byte stores.
   // The winning-channel ids are parked in LDS (a private 16-byte-per-lane slot per row: no barrier)
   // so that the gather batches below have registers to land in.
   constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
-  __shared__ int4 stash[WAVES][NBR][TN][2][64];
+  constexpr int NQ4 = PX / 4;
+  __shared__ int4 stash[WAVES][NBR][TN][NQ4][64];
 #pragma unroll
   for (int c = 0; c < TN; ++c)
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NQ4; ++h) {
       if (DO_MIN) stash[wave][0][c][h][lane] = make_int4(imin[c][4 * h], imin[c][4 * h + 1], imin[c][4 * h + 2], imin[c][4 * h + 3]);
       if (DO_MAX) stash[wave][NBR - 1][c][h][lane] = make_int4(imax[c][4 * h], imax[c][4 * h + 1], imax[c][4 * h + 2], imax[c][4 * h + 3]);
     }
   auto unstash = [&](int br, int c, int (&ids)[PX]) {
-    const int4 a0 = stash[wave][br][c][0][lane], a1 = stash[wave][br][c][1][lane];
-    ids[0] = a0.x; ids[1] = a0.y; ids[2] = a0.z; ids[3] = a0.w;
-    ids[4] = a1.x; ids[5] = a1.y; ids[6] = a1.z; ids[7] = a1.w;
+#pragma unroll
+    for (int h = 0; h < NQ4; ++h) {
+      const int4 a4 = stash[wave][br][c][h][lane];
+      ids[4 * h] = a4.x; ids[4 * h + 1] = a4.y; ids[4 * h + 2] = a4.z; ids[4 * h + 3] = a4.w;
+    }
   };
   if (!unit_ok) return;
   const size_t wbytes = (size_t)p.C_out * p.K * sizeof(float);
   const rsrc_t wres_min = make_rsrc(DO_MIN ? w_min : w_max, (unsigned)wbytes);
   const rsrc_t wres_max = make_rsrc(DO_MAX ? w_max : w_min, (unsigned)wbytes);
   const size_t xn_off = (size_t)n * p.C_in * HW;
-  int ihc[3];
-  bool rv[3];
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int ih = oh - p.ph + i * D;
-    rv[i] = (ih >= 0 && ih < p.H);
-    ihc[i] = min(max(ih, 0), p.H - 1);
-  }
   // Exact taps for RB pixels of one (channel, branch) row at a time: first ALL gathers of the batch
   // are issued (9 kernel values and a 3 x (2D+1) input patch per item), only then any is consumed,
-  // so the batch pays one memory latency instead of one per item.  Border pixels load their patch
-  // from a start clamped into the row and pick the taps with a per-lane shift.
+  // so the batch pays one memory latency instead of one per item.  A pixel whose taps may leave the
+  // row loads its patch from a start clamped into the row and picks the taps with a per-lane shift.
   constexpr int L = 2 * D + 1;           // contiguous input columns spanned by the 3 taps of a row
   constexpr int RB = (D == 1) ? 4 : 2;   // items per batch (register budget)
   auto refine_batch = [&](const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co, int q0,
@@ -291,8 +324,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
       const int cs = min(cs_row[q], p.C_in - 1);  // a virtual channel never wins; keep the address in range
       csv[u] = cs;
       load_run<9, float>(wv[u], wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
-      const int iwq = ow0 + q - p.pw;
-      const bool inner = (q >= D && q <= 7 - D);  // every tap column of this pixel lies inside the row
+      const int iwq = (ow0 + q) * S - p.pw;
+      // stride 1: pixels D .. PX-1-D have every tap column inside the row whatever the padding
+      const bool inner = (S == 1) && (q >= D && q <= PX - 1 - D);
       const int start = inner ? iwq : min(max(iwq, 0), p.W - L);
       shv[u] = iwq - start;
 #pragma unroll
@@ -305,15 +339,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
 #pragma unroll
     for (int u = 0; u < RB; ++u) {
       const int q = q0 + u;
-      const bool inner = (q >= D && q <= 7 - D);
-      const int iwq = ow0 + q - p.pw;
+      const bool inner = (S == 1) && (q >= D && q <= PX - 1 - D);
+      const int iwq = (ow0 + q) * S - p.pw;
       int r = csv[u] * 9;
 #pragma unroll
       for (int i = 2; i >= 0; --i)
 #pragma unroll
         for (int j = 2; j >= 0; --j) {
           float xv;
-          bool ok = rv[i];
+          bool ok = (mrow[i] == 0u);
           if (inner) {
             xv = run[u][i][j * D];
           } else {
@@ -348,15 +382,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
       unstash(0, c, cids);
 #pragma unroll
       for (int q = 0; q < PX; q += RB) refine_batch(cids, bmin[c], wres_min, co, q, ridx);
-      store_row(idx_min + ob, ridx, first_q);
-      if (y_min) store_row(y_min + ob, bmin[c], first_q);
+      store_row<PX>(idx_min + ob, ridx, first_q);
+      if (y_min) store_row<PX>(y_min + ob, bmin[c], first_q);
     }
     if (DO_MAX) {
       unstash(NBR - 1, c, cids);
 #pragma unroll
       for (int q = 0; q < PX; q += RB) refine_batch(cids, bmax[c], wres_max, co, q, ridx);
-      store_row(idx_max + ob, ridx, first_q);
-      if (y_max) store_row(y_max + ob, bmax[c], first_q);
+      store_row<PX>(idx_max + ob, ridx, first_q);
+      if (y_max) store_row<PX>(y_max + ob, bmax[c], first_q);
     }
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
@@ -364,7 +398,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_s1_kernel(
       else if (MODE == TCONV_MIN) out[q] = bmin[c][q];
       else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
     }
-    store_row(y + ob, out, first_q);
+    store_row<PX>(y + ob, out, first_q);
   }
 }
 
@@ -384,9 +418,10 @@ void widen(const void* src, float* dst, size_t n, hipStream_t s) {
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-template <int MODE, int D, typename TO>
+template <int MODE, int S, int D, typename TO>
 hipError_t launch_one(const Params& p, const float* x, const float* w_min, const float* w_max,
                       const FwdArgs& a, hipStream_t s) {
+  constexpr int PX = (S == 1) ? 8 : 4;
   const int segs = (p.Wo + PX - 1) / PX;
   const long long n_units = (long long)p.N * p.Ho * segs;
   const int n_groups = (p.C_out + TN - 1) / TN;
@@ -396,58 +431,59 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   const char* e = getenv("TCONV_DEBUG_FLAGS");
   const int dbg = e ? atoi(e) : 0;
-  hipLaunchKernelGGL((fwd_tiled3x3_s1_kernel<MODE, D, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
+  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
                      0, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
                      a.idx_min, a.idx_max, segs, (int)n_units, n_groups, dbg);
   return hipGetLastError();
 }
 
 template <int MODE, typename TO>
-hipError_t launch_dil(const Params& p, const float* x, const float* w_min, const float* w_max,
+hipError_t launch_geo(const Params& p, const float* x, const float* w_min, const float* w_max,
                       const FwdArgs& a, hipStream_t s) {
-  return p.dh == 1 ? launch_one<MODE, 1, TO>(p, x, w_min, w_max, a, s)
-                   : launch_one<MODE, 2, TO>(p, x, w_min, w_max, a, s);
+  if (p.sh == 2) return launch_one<MODE, 2, 1, TO>(p, x, w_min, w_max, a, s);
+  return p.dh == 1 ? launch_one<MODE, 1, 1, TO>(p, x, w_min, w_max, a, s)
+                   : launch_one<MODE, 1, 2, TO>(p, x, w_min, w_max, a, s);
 }
 
 template <typename TO>
 hipError_t launch_mode(const Params& p, const float* x, const float* w_min, const float* w_max,
                        const FwdArgs& a, hipStream_t s) {
   switch (p.mode) {
-    case TCONV_MAX: return launch_dil<TCONV_MAX, TO>(p, x, w_min, w_max, a, s);
-    case TCONV_MIN: return launch_dil<TCONV_MIN, TO>(p, x, w_min, w_max, a, s);
-    case TCONV_COMPOUND: return launch_dil<TCONV_COMPOUND, TO>(p, x, w_min, w_max, a, s);
-    default: return launch_dil<TCONV_PARALLEL, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_MAX: return launch_geo<TCONV_MAX, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_MIN: return launch_geo<TCONV_MIN, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_COMPOUND: return launch_geo<TCONV_COMPOUND, TO>(p, x, w_min, w_max, a, s);
+    default: return launch_geo<TCONV_PARALLEL, TO>(p, x, w_min, w_max, a, s);
   }
 }
 
-bool stride1_supported(const Params& p) {
+}  // namespace
+
+// 3x3 kernels with equal stride and dilation on both axes, (stride, dilation) in {(1,1), (1,2), (2,1)},
+// horizontal padding at most the dilation (so that the core columns of every lane lie inside the row),
+// at least one full pixel segment per output row, tensors addressable with 32-bit byte offsets.
+bool forward_tiled3x3_supported(const Params& p, int dtype) {
+  (void)dtype;
   if (p.KH != 3 || p.KW != 3) return false;
-  if (p.sh != 1 || p.sw != 1 || p.dh != p.dw || (p.dh != 1 && p.dh != 2)) return false;
-  if (p.pw > p.dw) return false;  // the 8 core columns of every lane must lie inside the row
-  if (p.Wo < PX) return false;    // at least one full 8-pixel segment per output row
-  // lanes address x and the kernels (as fp32) with 32-bit byte offsets
+  if (p.sh != p.sw || p.dh != p.dw) return false;
+  const bool geo = (p.sh == 1 && (p.dh == 1 || p.dh == 2)) || (p.sh == 2 && p.dh == 1);
+  if (!geo) return false;
+  if (p.pw > p.dw) return false;
+  if (p.Wo < (p.sh == 1 ? 8 : 4)) return false;
+  if (p.W < 2 * p.dw + 1) return false;  // the epilogue loads 2*dil + 1 consecutive columns of a row
   if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
   if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
   return true;
 }
 
-}  // namespace
-
-bool forward_tiled3x3_supported(const Params& p, int dtype) {
-  return stride1_supported(p) || forward_tiled_strided_supported(p, dtype);
-}
-
-// Workspace of the tiled path: only bf16 storage with the stride-1 kernel needs one (fp32 copies
-// of x and of the kernel tensors).
+// Workspace of the tiled path: only bf16 storage needs one (fp32 copies of x and the kernel tensors).
 size_t forward_tiled3x3_workspace(const Params& p, int dtype) {
-  if (dtype != TCONV_BF16 || !stride1_supported(p)) return 0;
+  if (dtype != TCONV_BF16) return 0;
   const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;
   return align256(nx * 4) + align256(nw * 4) * (p.mode == TCONV_PARALLEL ? 2 : 1);
 }
 
 hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, void* workspace,
                                    hipStream_t s) {
-  if (!stride1_supported(p)) return launch_forward_tiled_strided(p, dtype, a, s);
   if (dtype != TCONV_BF16)
     return launch_mode<float>(p, (const float*)a.x, (const float*)a.w_min, (const float*)a.w_max, a, s);
   const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;

@@ -6,7 +6,6 @@
 namespace tconv {
 namespace tile {
 
-constexpr int PX = 8;     // output pixels per lane
 constexpr int WAVES = 4;  // waves per workgroup, each a different c_out group
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
@@ -59,35 +58,40 @@ __device__ __forceinline__ float load_one(rsrc_t r, unsigned voff, unsigned soff
     return __uint_as_float(((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0)) << 16);
 }
 
-// ---- a lane's 8 consecutive outputs -> memory.  Pixels q < first_q belong to the neighbouring
-// lane (shifted last segment of a row): then single predicated stores, else two 16-byte stores.
+// ---- a lane's NP (4 or 8) consecutive outputs -> memory.  Pixels q < first_q belong to the
+// neighbouring lane (shifted last segment of a row): then single predicated stores, else 16-byte stores.
 typedef int i4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));
+typedef unsigned u2h __attribute__((ext_vector_type(2), aligned(2)));
 
-__device__ __forceinline__ void store_row(float* p, const float (&v)[PX], int first_q) {
+template <int NP>
+__device__ __forceinline__ void store_row(float* p, const float (&v)[NP], int first_q) {
   if (first_q == 0) {
-    f4u a, b;
-    a.x = v[0]; a.y = v[1]; a.z = v[2]; a.w = v[3];
-    b.x = v[4]; b.y = v[5]; b.z = v[6]; b.w = v[7];
-    *(f4u*)p = a;
-    *(f4u*)(p + 4) = b;
+#pragma unroll
+    for (int h = 0; h < NP / 4; ++h) {
+      f4u a;
+      a.x = v[4 * h]; a.y = v[4 * h + 1]; a.z = v[4 * h + 2]; a.w = v[4 * h + 3];
+      *(f4u*)(p + 4 * h) = a;
+    }
   } else {
 #pragma unroll
-    for (int q = 0; q < PX; ++q)
+    for (int q = 0; q < NP; ++q)
       if (q >= first_q) p[q] = v[q];
   }
 }
 
-__device__ __forceinline__ void store_row(int32_t* p, const int (&v)[PX], int first_q) {
+template <int NP>
+__device__ __forceinline__ void store_row(int32_t* p, const int (&v)[NP], int first_q) {
   if (first_q == 0) {
-    i4u a, b;
-    a.x = v[0]; a.y = v[1]; a.z = v[2]; a.w = v[3];
-    b.x = v[4]; b.y = v[5]; b.z = v[6]; b.w = v[7];
-    *(i4u*)p = a;
-    *(i4u*)(p + 4) = b;
+#pragma unroll
+    for (int h = 0; h < NP / 4; ++h) {
+      i4u a;
+      a.x = v[4 * h]; a.y = v[4 * h + 1]; a.z = v[4 * h + 2]; a.w = v[4 * h + 3];
+      *(i4u*)(p + 4 * h) = a;
+    }
   } else {
 #pragma unroll
-    for (int q = 0; q < PX; ++q)
+    for (int q = 0; q < NP; ++q)
       if (q >= first_q) p[q] = v[q];
   }
 }
@@ -98,21 +102,22 @@ __device__ __forceinline__ unsigned bf16_bits(float v) {  // round to nearest ev
   return u >> 16;
 }
 
-__device__ __forceinline__ void store_row(bf16_t* p, const float (&v)[PX], int first_q) {
+template <int NP>
+__device__ __forceinline__ void store_row(bf16_t* p, const float (&v)[NP], int first_q) {
   if (first_q == 0) {
-    u4h a;
-    a.x = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
-    a.y = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
-    a.z = bf16_bits(v[4]) | (bf16_bits(v[5]) << 16);
-    a.w = bf16_bits(v[6]) | (bf16_bits(v[7]) << 16);
-    *(u4h*)p = a;
+#pragma unroll
+    for (int h = 0; h < NP / 4; ++h) {
+      u2h a;
+      a.x = bf16_bits(v[4 * h]) | (bf16_bits(v[4 * h + 1]) << 16);
+      a.y = bf16_bits(v[4 * h + 2]) | (bf16_bits(v[4 * h + 3]) << 16);
+      *(u2h*)(p + 4 * h) = a;
+    }
   } else {
 #pragma unroll
-    for (int q = 0; q < PX; ++q)
+    for (int q = 0; q < NP; ++q)
       if (q >= first_q) p[q] = (bf16_t)bf16_bits(v[q]);
   }
 }
-
 
 }  // namespace tile
 }  // namespace tconv
