@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
-    int n_units, int n_groups, int dbg) {
+    int n_units, int n_groups, int wrps, int dbg) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr int PX = (S == 1) ? 8 : 4;          // output pixels per lane
   constexpr int NC = (PX - 1) * S + 1;          // core columns [D, D+NC): always inside the row
@@ -283,38 +283,65 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
 
   // ---- epilogue: exact tap of every extremum (first tap of the winning channel, in k order, whose
   // sum equals it), combine, store.  Each lane writes its PX consecutive outputs with 16-byte stores.
-  // The winning-channel ids are parked in LDS (a private 16-byte-per-lane slot per row: no barrier)
+  // The winning-channel ids are parked in LDS (16 bits each, a private slot per lane: no barrier)
   // so that the gather batches below have registers to land in.
   constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
-  constexpr int NQ4 = PX / 4;
-  __shared__ int4 stash[WAVES][NBR][TN][NQ4][64];
+  __shared__ int stash[WAVES][NBR][TN][PX / 2][64];
 #pragma unroll
   for (int c = 0; c < TN; ++c)
 #pragma unroll
-    for (int h = 0; h < NQ4; ++h) {
-      if (DO_MIN) stash[wave][0][c][h][lane] = make_int4(imin[c][4 * h], imin[c][4 * h + 1], imin[c][4 * h + 2], imin[c][4 * h + 3]);
-      if (DO_MAX) stash[wave][NBR - 1][c][h][lane] = make_int4(imax[c][4 * h], imax[c][4 * h + 1], imax[c][4 * h + 2], imax[c][4 * h + 3]);
+    for (int h = 0; h < PX / 2; ++h) {
+      if (DO_MIN) stash[wave][0][c][h][lane] = imin[c][2 * h] | (imin[c][2 * h + 1] << 16);
+      if (DO_MAX) stash[wave][NBR - 1][c][h][lane] = imax[c][2 * h] | (imax[c][2 * h + 1] << 16);
     }
   auto unstash = [&](int br, int c, int (&ids)[PX]) {
 #pragma unroll
-    for (int h = 0; h < NQ4; ++h) {
-      const int4 a4 = stash[wave][br][c][h][lane];
-      ids[4 * h] = a4.x; ids[4 * h + 1] = a4.y; ids[4 * h + 2] = a4.z; ids[4 * h + 3] = a4.w;
+    for (int h = 0; h < PX / 2; ++h) {
+      const unsigned a2 = (unsigned)stash[wave][br][c][h][lane];
+      ids[2 * h] = (int)(a2 & 0xffffu); ids[2 * h + 1] = (int)(a2 >> 16);
     }
   };
-  if (!unit_ok) return;
+  const int first_qs = unit_ok ? first_q : PX;  // surplus lanes store nothing (they still help with the copies below)
   const size_t wbytes = (size_t)p.C_out * p.K * sizeof(float);
   const rsrc_t wres_min = make_rsrc(DO_MIN ? w_min : w_max, (unsigned)wbytes);
   const rsrc_t wres_max = make_rsrc(DO_MAX ? w_max : w_min, (unsigned)wbytes);
   const size_t xn_off = (size_t)n * p.C_in * HW;
+  // The kernel values the gathers need are one K-float row per (output channel, branch); a gather
+  // straight from global memory costs the texture addresser one address per lane, so the wave first
+  // copies wrps such rows (as many as fit its share of LDS; 0: none fit) with coalesced loads and
+  // gathers from LDS.  Rows are numbered in the order they are used: c * NT + t.
+  constexpr int NT = (MODE == TCONV_PARALLEL) ? 2 : 1;  // kernel tensors
+  HIP_DYNAMIC_SHARED(float, wstage_all)
+  const int KS = (p.K + 3) & ~3;  // row stride in LDS
+  float* const wstage = wstage_all + wave * (wrps * KS);
+  auto stage_rows = [&](int s0) {
+    wave_lds_fence();  // every lane is done with the rows staged before
+    for (int r = 0; r < wrps; ++r) {
+      const int s = s0 + r;
+      if (s >= TN * NT) break;
+      const int co = min(co0 + s / NT, p.C_out - 1);
+      const bool use_max = DO_MAX && (NT == 1 || (s % NT) == 1);
+      const unsigned rbase = (unsigned)((size_t)co * p.K * sizeof(float));
+      float* const dst = wstage + r * KS;
+      // 4 floats per lane and trip; the last chunk of the row is moved back so that it ends with the row
+      for (int f = lane * 4; f < p.K; f += 256) {
+        const int fs = min(f, p.K - 4);
+        float v[4];
+        load_run<4, float>(v, use_max ? wres_max : wres_min, rbase + (unsigned)fs * 4u, 0u);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dst[fs + t] = v[t];
+      }
+    }
+    wave_lds_fence();
+  };
   // Exact taps for RB pixels of one (channel, branch) row at a time: first ALL gathers of the batch
   // are issued (9 kernel values and a 3 x (2D+1) input patch per item), only then any is consumed,
   // so the batch pays one memory latency instead of one per item.  A pixel whose taps may leave the
   // row loads its patch from a start clamped into the row and picks the taps with a per-lane shift.
   constexpr int L = 2 * D + 1;           // contiguous input columns spanned by the 3 taps of a row
   constexpr int RB = (D == 1) ? 4 : 2;   // items per batch (register budget)
-  auto refine_batch = [&](const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co, int q0,
-                          int (&res)[PX]) {
+  auto refine_batch = [&](const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co,
+                          const float* wl, int q0, int (&res)[PX]) {
     float wv[RB][9];
     float run[RB][3][L];
     int csv[RB], shv[RB];
@@ -323,7 +350,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       const int q = q0 + u;
       const int cs = min(cs_row[q], p.C_in - 1);  // a virtual channel never wins; keep the address in range
       csv[u] = cs;
-      load_run<9, float>(wv[u], wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
+      if (wl) {  // uniform
+#pragma unroll
+        for (int t = 0; t < 9; ++t) wv[u][t] = wl[cs * 9 + t];
+      } else {
+        load_run<9, float>(wv[u], wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
+      }
       const int iwq = (ow0 + q) * S - p.pw;
       // stride 1: pixels D .. PX-1-D have every tap column inside the row whatever the padding
       const bool inner = (S == 1) && (q >= D && q <= PX - 1 - D);
@@ -378,19 +410,25 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     }
     int ridx[PX], cids[PX];
     float out[PX];
+    // rows of this channel in use order: parallel: min row, then max row; else the one row
+    const int s_min = c * NT, s_max = c * NT + (NT - 1);
     if (DO_MIN) {
+      if (wrps > 0 && s_min % wrps == 0) stage_rows(s_min);
+      const float* wl = wrps > 0 ? wstage + (s_min % wrps) * KS : nullptr;
       unstash(0, c, cids);
 #pragma unroll
-      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmin[c], wres_min, co, q, ridx);
-      store_row<PX>(idx_min + ob, ridx, first_q);
-      if (y_min) store_row<PX>(y_min + ob, bmin[c], first_q);
+      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmin[c], wres_min, co, wl, q, ridx);
+      store_row<PX>(idx_min + ob, ridx, first_qs);
+      if (y_min) store_row<PX>(y_min + ob, bmin[c], first_qs);
     }
     if (DO_MAX) {
+      if (wrps > 0 && s_max % wrps == 0 && !(DO_MIN && NT == 1)) stage_rows(s_max);
+      const float* wl = wrps > 0 ? wstage + (s_max % wrps) * KS : nullptr;
       unstash(NBR - 1, c, cids);
 #pragma unroll
-      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmax[c], wres_max, co, q, ridx);
-      store_row<PX>(idx_max + ob, ridx, first_q);
-      if (y_max) store_row<PX>(y_max + ob, bmax[c], first_q);
+      for (int q = 0; q < PX; q += RB) refine_batch(cids, bmax[c], wres_max, co, wl, q, ridx);
+      store_row<PX>(idx_max + ob, ridx, first_qs);
+      if (y_max) store_row<PX>(y_max + ob, bmax[c], first_qs);
     }
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
@@ -398,7 +436,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       else if (MODE == TCONV_MIN) out[q] = bmin[c][q];
       else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
     }
-    store_row<PX>(y + ob, out, first_q);
+    store_row<PX>(y + ob, out, first_qs);
   }
 }
 
@@ -431,9 +469,18 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   const char* e = getenv("TCONV_DEBUG_FLAGS");
   const int dbg = e ? atoi(e) : 0;
+  // kernel rows a wave stages in LDS for the epilogue gathers: as many (a power of two) as fit its
+  // 12 KB share (32 KB of static LDS + 4 x 12 KB leave room for two workgroups per compute unit)
+  constexpr int NT = (MODE == TCONV_PARALLEL) ? 2 : 1;
+  const int KS = (p.K + 3) & ~3;
+  int wrps = 0;
+  for (int r = TN * NT; r >= 1; r >>= 1)
+    if ((long long)r * KS <= 3072) { wrps = r; break; }
+  if (dbg & 16) wrps = 0;
+  const size_t lds = (size_t)WAVES * wrps * KS * sizeof(float);
   hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
-                     0, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
-                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, dbg);
+                     lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
+                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, wrps, dbg);
   return hipGetLastError();
 }
 
@@ -470,6 +517,7 @@ bool forward_tiled3x3_supported(const Params& p, int dtype) {
   if (p.pw > p.dw) return false;
   if (p.Wo < (p.sh == 1 ? 8 : 4)) return false;
   if (p.W < 2 * p.dw + 1) return false;  // the epilogue loads 2*dil + 1 consecutive columns of a row
+  if (p.C_in > 65535) return false;      // winning channels are parked as 16-bit values
   if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
   if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
   return true;

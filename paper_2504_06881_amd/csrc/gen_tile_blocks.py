@@ -156,6 +156,11 @@ __device__ __forceinline__ int launder_uniform(int v) {
   asm volatile("" : "+s"(v));
   return v;
 }
+
+// Between a wave's LDS writes and its reads of what other lanes of the SAME wave wrote: the lanes of a
+// wave run in lockstep and LDS executes a wave's operations in order, so only the compiler has to
+// be kept from moving memory operations across this point.
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
 """
 
 if __name__ == "__main__":
