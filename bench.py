@@ -11,6 +11,8 @@ Prints ONE JSON line:
   roofline       : the forward kernel against the fp32 vector-ALU peak, measured live with HIP events
   cpu_baseline   : the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
 Extra keys give the forward-only rate and the achieved HBM GB/s of the two backward calls.
+--workload takes any single-layer configuration name (cfg2_main, cfg3a, cfg4b, ...) or cfg5, the 19
+layers of a ResNet-20-style net run back to back (one step = all layers, forward and backward).
 """
 from __future__ import annotations
 
@@ -61,42 +63,65 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     tb.load()  # fails loudly if libtconv.so has not been built
-    cfg = CONFIGS[args.workload]
-    dev = torch.device("cuda:0")
-    inp = make_inputs(cfg)
-    d = tb.Desc.from_cfg(cfg)
-    ho, wo = tb.tconv_out_shape(d)
-    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-
-    def up(a, dt=torch.float32):
-        return None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
-
-    x = up(inp["x"], tdt)
-    if cfg.mode == "compound":
-        w_min = w_max = up(inp["w_min"], tdt)
+    from paper_2504_06881_amd.inputs import resnet20_layers
+    if args.workload == "cfg5":
+        # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (benchmark configs[4]);
+        # the batch-norm / residual glue of the net is not part of the hot path and is not run
+        cfgs = resnet20_layers(256)
+        wl_name = "cfg5: the 19 parallel-mode 3x3 layers of a ResNet-20-style net on x[256,3,32,32], f32"
     else:
-        w_min, w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
-    gy = up(inp["gy"])
-    oshape = (cfg.N, cfg.C_out, ho, wo)
-    do_min, do_max = cfg.mode != "max", cfg.mode != "min"
-    y = torch.empty(oshape, device=dev, dtype=tdt)
-    y_min = torch.empty(oshape, device=dev, dtype=tdt) if do_min else None
-    y_max = torch.empty(oshape, device=dev, dtype=tdt) if do_max else None
-    idx_min = torch.empty(oshape, device=dev, dtype=torch.int32) if do_min else None
-    idx_max = torch.empty(oshape, device=dev, dtype=torch.int32) if do_max else None
-    gx = torch.empty(tuple(inp["x"].shape), device=dev)
-    wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
-    gw_min = torch.empty(wshape, device=dev) if do_min else None
-    gw_max = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel") else None
+        cfgs = [CONFIGS[args.workload]]
+        c0 = cfgs[0]
+        wl_name = (f"{c0.name}: x[{c0.N},{c0.C_in},{c0.H},{c0.W}] -> {c0.C_out}ch 3x3 s{c0.stride} p{c0.pad} "
+                   f"d{c0.dil} {c0.mode} {c0.dtype}")
+    dev = torch.device("cuda:0")
 
-    def fwd():
-        tb.tconv_forward(d, x, w_min, w_max, None, None, y, y_min, y_max, idx_min, idx_max)
+    class Layer:
+        """Device buffers and the three calls of one layer."""
 
-    def bwd_in():
-        tb.tconv_backward_input(d, gy, None, None, idx_min, idx_max, gx)
+        def __init__(self, cfg):
+            self.cfg = cfg
+            self.inp = inp = make_inputs(cfg)
+            self.d = d = tb.Desc.from_cfg(cfg)
+            ho, wo = tb.tconv_out_shape(d)
+            tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
 
-    def bwd_w():
-        tb.tconv_backward_weight(d, gy, None, None, idx_min, idx_max, gw_min, gw_max)
+            def up(a, dt=torch.float32):
+                return None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
+
+            self.x = up(inp["x"], tdt)
+            if cfg.mode == "compound":
+                self.w_min = self.w_max = up(inp["w_min"], tdt)
+            else:
+                self.w_min, self.w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
+            self.gy = up(inp["gy"])
+            osh = (cfg.N, cfg.C_out, ho, wo)
+            do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+            self.y = torch.empty(osh, device=dev, dtype=tdt)
+            self.y_min = torch.empty(osh, device=dev, dtype=tdt) if do_min else None
+            self.y_max = torch.empty(osh, device=dev, dtype=tdt) if do_max else None
+            self.idx_min = torch.empty(osh, device=dev, dtype=torch.int32) if do_min else None
+            self.idx_max = torch.empty(osh, device=dev, dtype=torch.int32) if do_max else None
+            self.gx = torch.empty(tuple(inp["x"].shape), device=dev)
+            wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+            self.gw_min = torch.empty(wshape, device=dev) if do_min else None
+            self.gw_max = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel") else None
+            self.n_out = cfg.N * cfg.C_out * ho * wo
+            # algorithmic HBM bytes of the backward calls: gy + idx per output per branch, grad written once
+            self.bytes_bi = self.n_out * (4 + 4 * cfg.branches) + inp["x"].size * 4
+            self.bytes_bw = self.n_out * (4 + 4 * cfg.branches) + cfg.C_out * cfg.K * 4 * (2 if cfg.mode == "parallel" else 1)
+
+        def fwd(self):
+            tb.tconv_forward(self.d, self.x, self.w_min, self.w_max, None, None, self.y, self.y_min, self.y_max,
+                             self.idx_min, self.idx_max)
+
+        def bwd_in(self):
+            tb.tconv_backward_input(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gx)
+
+        def bwd_w(self):
+            tb.tconv_backward_weight(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gw_min, self.gw_max)
+
+    layers = [Layer(c) for c in cfgs]
 
     # HIP events on the stream the kernels are launched on (torch's current stream)
     def ev():
@@ -111,30 +136,32 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        fwd(); bwd_in(); bwd_w()
+        for L in layers:
+            L.fwd(); L.bwd_in(); L.bwd_w()
     torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e = [ev() for _ in range(4)]
-        e[0].record(); fwd(); e[1].record(); bwd_in(); e[2].record(); bwd_w(); e[3].record()
-        marks.append(e)
+        for L in layers:
+            e = [ev() for _ in range(4)]
+            e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); e[2].record(); L.bwd_w(); e[3].record()
+            marks.append((L, e))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps   # ms
-    t_bi = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
-    t_bw = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    t_f = sum(m[0].elapsed_time(m[1]) for _, m in marks) / args.steps   # ms per step, all layers
+    t_bi = sum(m[1].elapsed_time(m[2]) for _, m in marks) / args.steps
+    t_bw = sum(m[2].elapsed_time(m[3]) for _, m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
 
-    pairs = cfg.pairs
+    pairs = sum(L.cfg.pairs for L in layers)
     value = pairs / (ms_step * 1e-3) / 1e9
     fwd_pairs_s = pairs / (t_f * 1e-3)
-    peak = alu_peak_pairs_per_s(cfg.mode)
-    n_out = cfg.N * cfg.C_out * ho * wo
-    br = cfg.branches
-    # algorithmic HBM bytes of the backward calls: gy + idx per output per branch, grad written once
-    bytes_bi = n_out * (4 + 4 * br) + inp["x"].size * 4
-    bytes_bw = n_out * (4 + 4 * br) + cfg.C_out * cfg.K * 4 * (2 if cfg.mode == "parallel" else 1)
+    # plain-form lane operations of the forward pass (2 per pair; compound 1.5) against the VALU issue rate
+    lane_ops = sum(L.cfg.pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(L.cfg.mode)) for L in layers)
+    achieved = lane_ops / (t_f * 1e-3)
+    bytes_bi = sum(L.bytes_bi for L in layers)
+    bytes_bw = sum(L.bytes_bw for L in layers)
+    dtypes = {L.cfg.dtype for L in layers}
 
     out = {
         "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step",
@@ -147,54 +174,57 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if cfg.dtype == "f32" else "bf16-storage/f32-arith",
+        "dtype": "f32" if dtypes == {"f32"} else "bf16-storage/f32-arith",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: x[{cfg.N},{cfg.C_in},{cfg.H},{cfg.W}] -> {cfg.C_out}ch 3x3 "
-                               f"s{cfg.stride} p{cfg.pad} d{cfg.dil} {cfg.mode} {cfg.dtype}, fwd+bwd_input+bwd_weight",
-                   "pairs_per_step": pairs, "forward_kernel": tb.tconv_forward_kernel_name(d)},
+        "config": {"workload": wl_name + ", fwd+bwd_input+bwd_weight", "pairs_per_step": pairs,
+                   "forward_kernel": tb.tconv_forward_kernel_name(layers[-1].d)},
         "forward_gops": round(fwd_pairs_s / 1e9, 2),
         "ms_forward": round(t_f, 4),
         "ms_backward_input": round(t_bi, 4),
         "ms_backward_weight": round(t_bw, 4),
         "backward_input_gbs": round(bytes_bi / (t_bi * 1e-3) / 1e9, 1),
         "backward_weight_gbs": round(bytes_bw / (t_bw * 1e-3) / 1e9, 1),
-        # algorithmic lane-operations (one fp32 add or compare each) against the chip's fp32 VALU issue rate
+        # algorithmic lane-operations (one fp32 add or compare each) against the chip's fp32 VALU issue rate;
+        # frac_best prices the same work at one packed add + one 3-operand compare per two pairs
         "roofline": {"bound": "alu", "kernel": "forward",
-                     "achieved": round(fwd_pairs_s * (LANE_OPS_PER_S / peak) / 1e12, 3),
+                     "achieved": round(achieved / 1e12, 3),
                      "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
-                     "frac": round(fwd_pairs_s / peak, 4), "traffic": None},
+                     "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
+                     "traffic": None},
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline([(L.cfg, L.inp) for L in layers], args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0
 
 
-def cpu_baseline(cfg, inp, target_s: float):
+def cpu_baseline(layers, target_s: float):
     """The CPU oracle, as it stands, on a batch slice sized for about target_s seconds of CPU work."""
     from oracle import tconv_oracle as orc
     threads = orc.num_threads()
-    per_image = cfg.pairs / cfg.N
+    n_full = layers[0][0].N
+    per_image = sum(cfg.pairs for cfg, _ in layers) / n_full
 
     def run(n_img):
-        s = orc.Shape(n_img, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
-        xs, gys = inp["x"][:n_img], inp["gy"][:n_img]
         t0 = time.perf_counter()
-        r = orc.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"])
-        orc.backward_input(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
-        orc.backward_weight(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
+        for cfg, inp in layers:
+            s = orc.Shape(n_img, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+            xs, gys = inp["x"][:n_img], inp["gy"][:n_img]
+            r = orc.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"])
+            orc.backward_input(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
+            orc.backward_weight(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
         return time.perf_counter() - t0
 
     t1 = run(1)  # calibrate on one image
-    n_img = int(max(1, min(cfg.N, target_s / max(t1, 1e-6))))
+    n_img = int(max(1, min(n_full, target_s / max(t1, 1e-6))))
     # repeat the slice until about target_s seconds of CPU work have been timed
     reps, total = 0, 0.0
     while reps == 0 or (total < target_s and reps < 50):
         total += run(n_img)
         reps += 1
     return {"value": round(per_image * n_img * reps / total / 1e9, 3), "unit": "GOPS", "cores": threads,
-            "kind": "oracle", "sample": f"first {n_img} of {cfg.N} images of the same workload, forward + both "
+            "kind": "oracle", "sample": f"first {n_img} of {n_full} images of the same workload, forward + both "
                                         f"backward passes, {reps} repetitions, {total:.1f} s of wall time"}
 
 

@@ -71,6 +71,13 @@ RAGGED = [
     LayerCfg("r_wide_cout", 1, 8, 12, 16, 70, seed=28),
     LayerCfg("r_14", 6, 10, 14, 14, 20, seed=29),          # 14x14 maps (ResNet stage shape)
     LayerCfg("r_7", 6, 10, 7, 7, 8, seed=30),
+    # deep inputs: the forward epilogue stages 4, 2, 1 or no kernel rows per wave in LDS (K = 9 * C_in
+    # against its 3072-float share), and none at all beyond that
+    LayerCfg("r_cin70", 1, 70, 9, 12, 6, seed=31),
+    LayerCfg("r_cin130", 1, 130, 8, 9, 5, seed=32),
+    LayerCfg("r_cin300", 1, 300, 6, 8, 5, seed=33),
+    LayerCfg("r_cin350", 1, 350, 6, 8, 3, seed=34),
+    LayerCfg("r_cin131_s2", 1, 131, 9, 10, 6, stride=2, seed=35),
 ]
 
 
