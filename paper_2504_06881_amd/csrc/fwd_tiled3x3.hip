@@ -37,7 +37,6 @@ namespace {
 
 using namespace tile;
 
-constexpr int TN = 4;  // output channels per lane
 
 // 9 x values of pixel q for the 3x3 taps of one channel: rows[3*ch + i][q*S + j*D]
 template <int S, int D, int XR>
@@ -48,7 +47,8 @@ __device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][
     for (int j = 0; j < 3; ++j) out[i * 3 + j] = rows[ch * 3 + i][q * S + j * D];
 }
 
-template <int MODE, int S, int D, typename TO>
+// TN: output channels per lane (4; 2 for layers too small to fill the chip with 4)
+template <int MODE, int S, int D, int TN, typename TO>
 __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha,
@@ -456,9 +456,9 @@ void widen(const void* src, float* dst, size_t n, hipStream_t s) {
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-template <int MODE, int S, int D, typename TO>
-hipError_t launch_one(const Params& p, const float* x, const float* w_min, const float* w_max,
-                      const FwdArgs& a, hipStream_t s) {
+template <int MODE, int S, int D, int TN, typename TO>
+hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const float* w_max,
+                     const FwdArgs& a, hipStream_t s) {
   constexpr int PX = (S == 1) ? 8 : 4;
   const int segs = (p.Wo + PX - 1) / PX;
   const long long n_units = (long long)p.N * p.Ho * segs;
@@ -478,10 +478,37 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
     if ((long long)r * KS <= 3072) { wrps = r; break; }
   if (dbg & 16) wrps = 0;
   const size_t lds = (size_t)WAVES * wrps * KS * sizeof(float);
-  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
+  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
                      lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
                      a.idx_min, a.idx_max, segs, (int)n_units, n_groups, wrps, dbg);
   return hipGetLastError();
+}
+
+// workgroups the chip holds at once (two per compute unit)
+long long resident_workgroups() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  return 2LL * cus;
+}
+
+template <int MODE, int S, int D, typename TO>
+hipError_t launch_one(const Params& p, const float* x, const float* w_min, const float* w_max,
+                      const FwdArgs& a, hipStream_t s) {
+  // 4 output channels per lane reuse every loaded input value twice as often as 2, but a layer whose
+  // grid leaves half of the wave slots empty runs faster on twice as many, half as long waves
+  // (measured: not so at stride 2, whose loads per arithmetic instruction are already twice as many,
+  // unless three quarters are empty)
+  constexpr int PX = (S == 1) ? 8 : 4;
+  const long long n_units = (long long)p.N * p.Ho * ((p.Wo + PX - 1) / PX);
+  const long long blocks4 = ((n_units + 63) / 64) * ((((long long)p.C_out + 3) / 4 + WAVES - 1) / WAVES);
+  int tn = (blocks4 * (S == 1 ? 2 : 4) <= resident_workgroups() && p.C_out > 2) ? 2 : 4;
+  if (const char* e = getenv("TCONV_FWD_TN")) {  // tuning aid
+    if (atoi(e) == 2 || atoi(e) == 4) tn = atoi(e);
+  }
+  return tn == 2 ? launch_tn<MODE, S, D, 2, TO>(p, x, w_min, w_max, a, s)
+                 : launch_tn<MODE, S, D, 4, TO>(p, x, w_min, w_max, a, s);
 }
 
 template <int MODE, typename TO>
