@@ -253,3 +253,32 @@ int oracle_tconv_backward_weight(const oracle_shape* s, int mode, const float* g
         }
   return 0;
 }
+
+/*
+ * Gradient of the combine step (paper Sec. 3.3: y = alpha*y_min + beta*y_max, alpha and beta
+ * learnable; here one pair per output channel): the step is linear in alpha and beta, so
+ *   grad_alpha[c] = sum over (n, oh, ow) of gy * y_min,   grad_beta[c] = the same with y_max.
+ * y_min, y_max are the branch outputs of the forward pass (fp32 values).  Compound and parallel
+ * mode only.  Either output may be NULL.  Outputs (double, [C_out]) are overwritten.
+ */
+int oracle_tconv_backward_alpha_beta(const oracle_shape* s, int mode, const float* gy,
+                                     const float* y_min, const float* y_max, double* grad_alpha,
+                                     double* grad_beta) {
+  int32_t Ho, Wo;
+  if (oracle_out_shape(s, &Ho, &Wo) != 0) return -1;
+  if (mode != ORACLE_COMPOUND && mode != ORACLE_PARALLEL) return -1;
+  if (!gy || (grad_alpha && !y_min) || (grad_beta && !y_max)) return -1;
+  for (int co = 0; co < s->C_out; ++co) {
+    double ga = 0.0, gb = 0.0;
+    for (int n = 0; n < s->N; ++n)
+      for (int oh = 0; oh < Ho; ++oh)
+        for (int ow = 0; ow < Wo; ++ow) {
+          size_t o = (((size_t)n * s->C_out + co) * Ho + oh) * Wo + ow;
+          if (grad_alpha) ga += (double)gy[o] * (double)y_min[o];
+          if (grad_beta) gb += (double)gy[o] * (double)y_max[o];
+        }
+    if (grad_alpha) grad_alpha[co] = ga;
+    if (grad_beta) grad_beta[co] = gb;
+  }
+  return 0;
+}

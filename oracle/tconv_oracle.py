@@ -83,6 +83,7 @@ def _load():
         lib.oracle_tconv_forward.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 10 + [ctypes.c_int]
         lib.oracle_tconv_backward_input.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 6
         lib.oracle_tconv_backward_weight.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 7
+        lib.oracle_tconv_backward_alpha_beta.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 5
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -184,3 +185,18 @@ def backward_weight(s: Shape, mode: str, gy, idx_min=None, idx_max=None, alpha=N
     if rc != 0:
         raise ValueError(f"oracle_tconv_backward_weight rejected the arguments (rc={rc})")
     return g_min, g_max
+
+
+def backward_alpha_beta(s: Shape, mode: str, gy, y_min, y_max):
+    """(grad_alpha, grad_beta) as float64 [C_out]: sums of gy*y_min and gy*y_max over (n, oh, ow)."""
+    ho, wo = out_shape(s)
+    oshape = (s.N, s.C_out, ho, wo)
+    gy, y_min, y_max = _f32(gy, oshape), _f32(y_min, oshape), _f32(y_max, oshape)
+    ga = np.empty((s.C_out,), np.float64)
+    gb = np.empty((s.C_out,), np.float64)
+    cs = s.c()
+    rc = _load().oracle_tconv_backward_alpha_beta(ctypes.byref(cs), MODES[mode], _p(gy), _p(y_min),
+                                                  _p(y_max), _p(ga), _p(gb))
+    if rc != 0:
+        raise ValueError(f"oracle_tconv_backward_alpha_beta rejected the arguments (rc={rc})")
+    return ga, gb

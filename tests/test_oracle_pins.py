@@ -439,3 +439,52 @@ def test_pair_count_formula():
     assert c.out_hw == (14, 14) and c.candidates == 64 * 1152 * 256 * 14 * 14
     assert CONFIGS["cfg4b"].out_hw == (64, 64)
     assert CONFIGS["cfg1"].pairs == 2 * 8 * 16 * 16 * 27
+
+
+# ---------------------------------------------------------------- gradient of the combine step
+
+@pytest.mark.parametrize("mode", ["compound", "parallel"])
+def test_alpha_beta_gradient_against_finite_differences(mode):
+    """L = sum(gy * (alpha*y_min + beta*y_max)) is linear in alpha and beta (Sec. 3.3), so a central
+    difference of the fp64 brute-force forward in one alpha[c] / beta[c] is the exact gradient."""
+    s, x, w, w2, rng = _rand_layer(41, N=2, C=2, H=5, W=4, CO=3)
+    wmn, wmx = (w, w2) if mode == "parallel" else (w, w)
+    alpha = rng.uniform(-1, 1, s.C_out)
+    beta = rng.uniform(-1, 1, s.C_out)
+    r = orc.forward(s, mode, x, w_min=wmn, w_max=wmx)
+    gy = rng.standard_normal(r["y"].shape).astype(np.float32)
+    ga, gb = orc.backward_alpha_beta(s, mode, gy, r["y_min"], r["y_max"])
+    ymn, _ = brute.forward(x.astype(np.float64), wmn.astype(np.float64), False, 1, 1, 1, dtype=np.float64)
+    ymx, _ = brute.forward(x.astype(np.float64), wmx.astype(np.float64), True, 1, 1, 1, dtype=np.float64)
+
+    def loss(a, b):
+        return (gy.astype(np.float64) * (a[None, :, None, None] * ymn + b[None, :, None, None] * ymx)).sum()
+
+    h = 0.125
+    for c in range(s.C_out):
+        e = np.zeros(s.C_out)
+        e[c] = h
+        assert abs((loss(alpha + e, beta) - loss(alpha - e, beta)) / (2 * h) - ga[c]) < 1e-5
+        assert abs((loss(alpha, beta + e) - loss(alpha, beta - e)) / (2 * h) - gb[c]) < 1e-5
+
+
+def test_alpha_beta_gradient_special_cases():
+    """gy == 1 turns the gradients into plain per-channel sums of the branch outputs (library sum);
+    a gy that is non-zero in one channel only leaves every other channel's gradient at zero; and the
+    gradients of the degenerate pairs (1, 0) / (0, 1) of Sec. 3.3 are those of the single branches."""
+    s, x, w, _, rng = _rand_layer(42, N=3, C=2, H=6, W=5, CO=4, integer=True)
+    r = orc.forward(s, "compound", x, w_min=w, w_max=w)
+    ones = np.ones(r["y"].shape, np.float32)
+    ga, gb = orc.backward_alpha_beta(s, "compound", ones, r["y_min"], r["y_max"])
+    assert np.array_equal(ga, r["y_min"].astype(np.float64).sum(axis=(0, 2, 3)))   # integers: exact
+    assert np.array_equal(gb, r["y_max"].astype(np.float64).sum(axis=(0, 2, 3)))
+    gy = np.zeros(r["y"].shape, np.float32)
+    gy[:, 2] = rng.standard_normal(gy[:, 2].shape).astype(np.float32)
+    ga, gb = orc.backward_alpha_beta(s, "compound", gy, r["y_min"], r["y_max"])
+    assert ga[2] != 0 and gb[2] != 0
+    assert not ga[[0, 1, 3]].any() and not gb[[0, 1, 3]].any()
+    # y_min, y_max do not depend on alpha / beta: swapping the two branch tensors swaps the two gradients
+    ga2, gb2 = orc.backward_alpha_beta(s, "compound", gy, r["y_max"], r["y_min"])
+    assert np.array_equal(ga2, gb) and np.array_equal(gb2, ga)
+    with pytest.raises(ValueError):
+        orc.backward_alpha_beta(s, "max", gy, r["y_min"], r["y_max"])
