@@ -50,7 +50,12 @@ extern "C" {
 
 enum tconv_mode { TCONV_MAX = 0, TCONV_MIN = 1, TCONV_COMPOUND = 2, TCONV_PARALLEL = 3 };
 enum tconv_dtype { TCONV_F32 = 0, TCONV_BF16 = 1 };
-enum tconv_op { TCONV_OP_FORWARD = 0, TCONV_OP_BACKWARD_INPUT = 1, TCONV_OP_BACKWARD_WEIGHT = 2 };
+enum tconv_op {
+  TCONV_OP_FORWARD = 0,
+  TCONV_OP_BACKWARD_INPUT = 1,
+  TCONV_OP_BACKWARD_WEIGHT = 2,
+  TCONV_OP_BACKWARD_ALPHA_BETA = 3
+};
 
 enum tconv_status {
   TCONV_OK = 0,
@@ -98,7 +103,8 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
  * Backward w.r.t. the input: grad_x[n, c*, ih*, iw*] += g_b for every output and
  * live branch b, (c*, i*, j*) = unflatten(idx_b); g_min = alpha*gy, g_max = beta*gy
  * (compound / parallel), g = gy (max / min).  grad_x fp32 [N, C_in, H, W] is
- * overwritten.  Sums are fp32 in an unspecified order (hardware atomics).
+ * overwritten.  The sums are accumulated in fp64 in an unspecified order and rounded
+ * to fp32 once.
  */
 int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* alpha,
                          const float* beta, const int32_t* idx_min, const int32_t* idx_max,
@@ -113,6 +119,21 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
                           const float* beta, const int32_t* idx_min, const int32_t* idx_max,
                           float* grad_w_min, float* grad_w_max, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward w.r.t. the combine coefficients (Sec. 3.3: y = alpha*y_min + beta*y_max with learnable
+ * alpha, beta; one pair per output channel): grad_alpha[c] = sum over (n, oh, ow) of gy*y_min,
+ * grad_beta[c] = the same with y_max.  Compound and parallel mode only (TCONV_E_INVAL otherwise).
+ *   gy       fp32 [N, C_out, H_out, W_out].
+ *   y_min, y_max  the branch outputs of tconv_forward, dtype; y_min is required when grad_alpha is
+ *            requested, y_max when grad_beta is.
+ *   grad_alpha, grad_beta  fp32 [C_out], overwritten; either may be NULL (not computed), not both.
+ * Partial sums are fp64; the per-workgroup partial results are added in fp32 in an unspecified order.
+ * No workspace is needed (tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_ALPHA_BETA) is 0).
+ */
+int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const void* y_min,
+                              const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
 
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */
 const char* tconv_status_string(int status);

@@ -18,7 +18,8 @@ MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3}
 DTYPES = {"f32": 0, "bf16": 1}
 OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",
-           "tconv_backward_weight", "tconv_status_string", "tconv_forward_kernel_name")
+           "tconv_backward_weight", "tconv_backward_alpha_beta", "tconv_status_string",
+           "tconv_forward_kernel_name")
 
 
 class TconvError(RuntimeError):
@@ -79,12 +80,13 @@ def load() -> ctypes.CDLL:
         lib.tconv_forward.argtypes = [D] + [P] * 11 + [ctypes.c_size_t, P]
         lib.tconv_backward_input.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_backward_weight.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv_backward_alpha_beta.argtypes = [D] + [P] * 6 + [ctypes.c_size_t, P]
         lib.tconv_status_string.argtypes = [ctypes.c_int]
         lib.tconv_status_string.restype = ctypes.c_char_p
         lib.tconv_forward_kernel_name.argtypes = [D]
         lib.tconv_forward_kernel_name.restype = ctypes.c_char_p
         for f in ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward",
-                  "tconv_backward_input", "tconv_backward_weight"):
+                  "tconv_backward_input", "tconv_backward_weight", "tconv_backward_alpha_beta"):
             getattr(lib, f).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -155,3 +157,12 @@ def tconv_backward_weight(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_w_
                                         _ptr(idx_min), _ptr(idx_max), _ptr(grad_w_min),
                                         _ptr(grad_w_max), _ptr(workspace), wsz, _stream()),
            "tconv_backward_weight")
+
+
+def tconv_backward_alpha_beta(desc: Desc, gy, y_min, y_max, grad_alpha, grad_beta, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward_alpha_beta(ctypes.byref(cd), _ptr(gy), _ptr(y_min), _ptr(y_max),
+                                            _ptr(grad_alpha), _ptr(grad_beta), _ptr(workspace), wsz,
+                                            _stream()),
+           "tconv_backward_alpha_beta")

@@ -65,7 +65,7 @@ int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
-  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_WEIGHT) return TCONV_E_INVAL;
+  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_ALPHA_BETA) return TCONV_E_INVAL;
   *bytes = 0;
   // only the tiled forward kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
   if (op == TCONV_OP_FORWARD && use_tiled(p, desc->dtype)) *bytes = forward_tiled3x3_workspace(p, desc->dtype);
@@ -132,6 +132,21 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
   }
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
   const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const void* y_min,
+                              const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (p.mode != TCONV_COMPOUND && p.mode != TCONV_PARALLEL) return TCONV_E_INVAL;
+  if (!gy || (!grad_alpha && !grad_beta)) return TCONV_E_INVAL;
+  if ((grad_alpha && !y_min) || (grad_beta && !y_max)) return TCONV_E_INVAL;
+  const hipError_t e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta,
+                                                  (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 

@@ -434,4 +434,65 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
   return hipGetLastError();
 }
 
+// ---- gradient of the combine step (paper Sec. 3.3: y = alpha*y_min + beta*y_max with learnable alpha,
+// beta, one pair per output channel here): grad_alpha[c] = sum over (n, oh, ow) of gy*y_min, grad_beta[c]
+// the same with y_max.  HBM bound: gy and the branch outputs are read once.  Workgroup = one output
+// channel x a slice of the batch; fp64 partial sums per thread, reduced through LDS, one fp32 atomic per
+// workgroup and output into the zero-filled result.
+template <typename TY>
+__global__ __launch_bounds__(256) void bwd_alpha_beta_kernel(Params p, const float* __restrict__ gy,
+                                                             const TY* __restrict__ y_min,
+                                                             const TY* __restrict__ y_max,
+                                                             float* __restrict__ grad_alpha,
+                                                             float* __restrict__ grad_beta, int n_per_block) {
+  const int co = blockIdx.x;
+  const int n0 = blockIdx.y * n_per_block;
+  const int n1 = min(n0 + n_per_block, p.N);
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  double sa = 0.0, sb = 0.0;
+  for (int n = n0; n < n1; ++n) {
+    const size_t base = ((size_t)n * p.C_out + co) * plane;
+    for (size_t i = threadIdx.x; i < plane; i += blockDim.x) {
+      const float g = gy[base + i];
+      if (grad_alpha) sa += (double)g * (double)ld_f32(y_min, base + i);
+      if (grad_beta) sb += (double)g * (double)ld_f32(y_max, base + i);
+    }
+  }
+  __shared__ double red[2][256];
+  red[0][threadIdx.x] = sa;
+  red[1][threadIdx.x] = sb;
+  __syncthreads();
+  for (int h = 128; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h) {
+      red[0][threadIdx.x] += red[0][threadIdx.x + h];
+      red[1][threadIdx.x] += red[1][threadIdx.x + h];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (grad_alpha) atomicAdd(grad_alpha + co, (float)red[0][0]);
+    if (grad_beta) atomicAdd(grad_beta + co, (float)red[1][0]);
+  }
+}
+
+hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
+                                      const void* y_max, float* grad_alpha, float* grad_beta,
+                                      hipStream_t s) {
+  if (grad_alpha) fill_zero(grad_alpha, (size_t)p.C_out, s);
+  if (grad_beta) fill_zero(grad_beta, (size_t)p.C_out, s);
+  // about two workgroups per compute unit, each with at least one image
+  int slices = (512 + p.C_out - 1) / p.C_out;
+  if (slices > p.N) slices = p.N;
+  if (slices > 65535) slices = 65535;
+  const int n_per_block = (p.N + slices - 1) / slices;
+  const dim3 grid((unsigned)p.C_out, (unsigned)((p.N + n_per_block - 1) / n_per_block));
+  if (dtype == TCONV_BF16)
+    hipLaunchKernelGGL(bwd_alpha_beta_kernel<bf16_t>, grid, dim3(256), 0, s, p, gy, (const bf16_t*)y_min,
+                       (const bf16_t*)y_max, grad_alpha, grad_beta, n_per_block);
+  else
+    hipLaunchKernelGGL(bwd_alpha_beta_kernel<float>, grid, dim3(256), 0, s, p, gy, (const float*)y_min,
+                       (const float*)y_max, grad_alpha, grad_beta, n_per_block);
+  return hipGetLastError();
+}
+
 }  // namespace tconv

@@ -66,5 +66,8 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);
 hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad_w_min,
                                   float* grad_w_max, hipStream_t s);
+hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
+                                      const void* y_max, float* grad_alpha, float* grad_beta,
+                                      hipStream_t s);
 
 }  // namespace tconv

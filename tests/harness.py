@@ -29,6 +29,10 @@ def run_oracle(cfg, inp, backward=True):
         kwa = dict(idx_min=r["idx_min"], idx_max=r["idx_max"], alpha=ab["alpha"], beta=ab["beta"])
         r["grad_x_scale"] = orc.backward_input(s, m, np.abs(inp["gy"]), **kwa)
         r["grad_w_min_scale"], r["grad_w_max_scale"] = orc.backward_weight(s, m, np.abs(inp["gy"]), **kwa)
+        if m in ("compound", "parallel"):  # gradient of the combine step, from the branch outputs
+            r["grad_alpha"], r["grad_beta"] = orc.backward_alpha_beta(s, m, inp["gy"], r["y_min"], r["y_max"])
+            r["grad_alpha_scale"], r["grad_beta_scale"] = orc.backward_alpha_beta(
+                s, m, np.abs(inp["gy"]), np.abs(r["y_min"]), np.abs(r["y_max"]))
     return r
 
 
@@ -78,6 +82,11 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
         gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel") else None
         tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
+        if cfg.mode in ("compound", "parallel") and branch_outputs:
+            ga = torch.full((cfg.C_out,), float("nan"), device=dev)
+            gb = torch.full((cfg.C_out,), float("nan"), device=dev)
+            tb.tconv_backward_alpha_beta(d, gy, y_min, y_max, ga, gb)
+            out.update(grad_alpha=ga, grad_beta=gb)
     torch.cuda.synchronize()
     res = {}
     for k, v in out.items():
@@ -130,3 +139,6 @@ def assert_backward_close(hip, ref, what=""):
         if ref[k] is None:
             continue
         assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+    for k in ("grad_alpha", "grad_beta"):
+        if ref.get(k) is not None and hip.get(k) is not None:
+            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)

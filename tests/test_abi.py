@@ -71,4 +71,5 @@ def test_compute_entry_points_reject_null_before_touching_the_gpu():
     assert lib.tconv_forward(ctypes.byref(cd), *([None] * 11), 0, None) == -1
     assert lib.tconv_backward_input(ctypes.byref(cd), *([None] * 7), 0, None) == -1
     assert lib.tconv_backward_weight(ctypes.byref(cd), *([None] * 8), 0, None) == -1
+    assert lib.tconv_backward_alpha_beta(ctypes.byref(cd), *([None] * 6), 0, None) == -1
     assert lib.tconv_forward(None, *([None] * 11), 0, None) == -1

@@ -132,6 +132,12 @@ def test_error_paths_return_codes():
     with pytest.raises(tb.TconvError) as e:
         tb.tconv_backward_input(d, z, None, None, zi, zi, None)
     assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:   # grad_alpha requested without y_min
+        tb.tconv_backward_alpha_beta(d, z, None, z, z, z)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:   # the combine step does not exist in max / min mode
+        tb.tconv_backward_alpha_beta(tb.Desc.from_cfg(cfg.with_(mode="max")), z, z, z, z, z)
+    assert e.value.status == -1
     with pytest.raises(tb.TconvError) as e:
         tb.tconv_backward_weight(d, z, None, None, zi, zi, z, None)
     assert e.value.status == -1
@@ -190,3 +196,23 @@ def test_resnet20_layers_one_each():
             continue
         seen.add(key)
         _check(cfg)
+
+
+def test_alpha_beta_gradient_single_outputs():
+    """Either gradient alone (the other pointer NULL) equals the pair computed together."""
+    import torch
+    cfg = RAGGED[0].with_(mode="parallel")
+    inp = make_inputs(cfg, alpha_beta="random")
+    ref = hs.run_oracle(cfg, inp)
+    hip = hs.run_hip(cfg, inp)
+    d = tb.Desc.from_cfg(cfg)
+    dev = torch.device("cuda:0")
+    gy = torch.from_numpy(inp["gy"]).to(dev)
+    ymn, ymx = torch.from_numpy(hip["y_min"]).to(dev), torch.from_numpy(hip["y_max"]).to(dev)
+    ga = torch.full((cfg.C_out,), float("nan"), device=dev)
+    gb = torch.full((cfg.C_out,), float("nan"), device=dev)
+    tb.tconv_backward_alpha_beta(d, gy, ymn, None, ga, None)
+    tb.tconv_backward_alpha_beta(d, gy, None, ymx, None, gb)
+    torch.cuda.synchronize()
+    hs.assert_grad_close(ga.cpu().numpy(), ref["grad_alpha"], ref["grad_alpha_scale"], "grad_alpha alone")
+    hs.assert_grad_close(gb.cpu().numpy(), ref["grad_beta"], ref["grad_beta_scale"], "grad_beta alone")
