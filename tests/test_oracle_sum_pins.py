@@ -172,7 +172,7 @@ def test_invariants_of_the_layer_equations(integer):
     gy = np.random.default_rng(1).standard_normal(y.shape).astype(np.float32)
     g = osum.backward(s, "parallel", x, gy, w1, w2, a, b)
     per_co = gy.astype(np.float64).sum(axis=(0, 2, 3))
-    assert np.isclose(g["grad_x"].sum(), (per_co * (a + b).astype(np.float64).sum(0)).sum(), rtol=1e-12, atol=1e-9)
+    assert np.isclose(g["grad_x"].sum(), (per_co * (a.astype(np.float64) + b.astype(np.float64)).sum(0)).sum(), rtol=1e-12, atol=1e-9)
     assert np.allclose(g["grad_w_min"].sum(axis=(2, 3)), (a.T.astype(np.float64) * per_co[:, None]), rtol=1e-12, atol=1e-9)
     assert np.allclose(g["grad_w_max"].sum(axis=(2, 3)), (b.T.astype(np.float64) * per_co[:, None]), rtol=1e-12, atol=1e-9)
 
