@@ -135,6 +135,44 @@ int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const voi
                               const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Sum-channel layers (fp32 only; TCONV_E_UNSUPPORTED for bf16).  Base operators of Sec. 3.1 for one
+ * input channel: MinPlus2d / MaxPlus2d = the minimum / maximum of x + w over the KH x KW window.
+ *   mode MIN       layer (i)  MinPlus-Sum-Conv2d:  y = sum over c_in of MinPlus2d(x, w_min)
+ *   mode MAX       layer (ii) MaxPlus-Sum-Conv2d:  y = sum over c_in of MaxPlus2d(x, w_max)
+ *   mode COMPOUND  y = sum over c_in of ( alpha[c_in, c_out]*MinPlus2d(x, W) + beta[c_in, c_out]*MaxPlus2d(x, W) )
+ *   mode PARALLEL  the same with W1 = w_min in the min-plus and W2 = w_max in the max-plus operator
+ * (the two-parameter layers of Sec. 3.5 and 3.6; a one-parameter layer is this one with
+ * beta = 1 - alpha, and its gradient is grad_alpha - grad_beta).
+ *   alpha, beta  fp32 [C_in, C_out] (element c_in*C_out + c_out) or NULL (= all ones); not used in MIN / MAX.
+ *   y        fp32 [N, C_out, H_out, W_out], overwritten.
+ * Padded taps are skipped; a channel's term is fl(fl(alpha*m) + fl(beta*M)); the terms are added in
+ * ascending c_in starting from +0, every add rounded to fp32, so the result is reproducible bit for bit.
+ */
+int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                      const float* alpha, const float* beta, void* y, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of tconv_sum_forward.  The window winners are re-computed from x and the kernels (no index
+ * tensors are kept; ties: lowest tap of the window).  With g = gy[n, c_out, oh, ow], for every
+ * (c_in, c_out, pixel) the min-plus winner (ih*, iw*, tap t*) receives
+ *   grad_x[n, c_in, ih*, iw*] += alpha*g,  grad_w_min[c_out, c_in, t*] += alpha*g,  grad_alpha[c_in, c_out] += g*m
+ * and the max-plus winner the same with beta, grad_w_max, grad_beta, M (coefficients 1 in MIN / MAX
+ * mode; COMPOUND adds both branches into ONE kernel gradient, grad_w_min if non-NULL else grad_w_max).
+ * Every gradient pointer may be NULL (not computed), not all of them; grad_alpha / grad_beta must be
+ * NULL in MIN / MAX mode.  All gradients fp32, overwritten; sums are kept in fp64 inside a
+ * workgroup and combined in fp32 in an unspecified order.
+ * TCONV_E_UNSUPPORTED: rows longer than about 5000 elements or kernel windows of more than 62 taps.
+ */
+int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                       const float* alpha, const float* beta, const float* gy, float* grad_x,
+                       float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Name of the forward kernel tconv_sum_forward selects: "sum_tiled3x3" or "sum_generic".  Host only. */
+const char* tconv_sum_forward_kernel_name(const tconv_desc* desc);
+
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */
 const char* tconv_status_string(int status);
 

@@ -150,6 +150,52 @@ int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const voi
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 
+int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                      const float* alpha, const float* beta, void* y, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!x || !y) return TCONV_E_INVAL;
+  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  SumArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, (float*)y};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
+  if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
+  const hipError_t e = launch_sum_forward(p, a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                       const float* alpha, const float* beta, const float* gy, float* grad_x,
+                       float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!x || !gy) return TCONV_E_INVAL;
+  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  const bool two = p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL;
+  if (!two && (grad_alpha || grad_beta)) return TCONV_E_INVAL;
+  if (!grad_x && !grad_w_min && !grad_w_max && !grad_alpha && !grad_beta) return TCONV_E_INVAL;
+  SumArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, nullptr};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
+  if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
+  const SumGrads g = {gy, grad_x, grad_w_min, grad_w_max, grad_alpha, grad_beta};
+  const hipError_t e = launch_sum_backward(p, a, g, (hipStream_t)hip_stream);
+  if (e == hipErrorInvalidValue) return TCONV_E_UNSUPPORTED;  // rows or kernel window too large for the LDS kernels
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+const char* tconv_sum_forward_kernel_name(const tconv_desc* desc) {
+  Params p;
+  if (make_params(desc, &p) != TCONV_OK) return nullptr;
+  return sum_forward_kernel_name(p);
+}
+
 const char* tconv_status_string(int status) {
   switch (status) {
     case TCONV_OK: return "ok";

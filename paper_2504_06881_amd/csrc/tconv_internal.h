@@ -38,6 +38,25 @@ struct BwdArgs {
   const int32_t* idx_max;
 };
 
+// Sum-channel layers (fp32): inputs of both passes, and the gradient request of the backward pass.
+struct SumArgs {
+  const float* x;
+  const float* w_min;  // W1, kernel of the min-plus branch (compound: the shared kernel)
+  const float* w_max;  // W2, kernel of the max-plus branch (compound: the shared kernel)
+  const float* alpha;  // [C_in, C_out] or NULL
+  const float* beta;
+  float* y;            // forward only
+};
+
+struct SumGrads {
+  const float* gy;
+  float* grad_x;
+  float* grad_w_min;
+  float* grad_w_max;
+  float* grad_alpha;
+  float* grad_beta;
+};
+
 // bf16 storage helpers: exact widening, round-to-nearest-even narrowing.
 typedef unsigned short bf16_t;
 
@@ -69,5 +88,9 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
 hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
                                       const void* y_max, float* grad_alpha, float* grad_beta,
                                       hipStream_t s);
+
+hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s);
+hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s);
+const char* sum_forward_kernel_name(const Params& p);
 
 }  // namespace tconv

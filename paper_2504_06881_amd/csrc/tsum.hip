@@ -1,0 +1,501 @@
+// Sum-channel tropical convolution layers on gfx950 (fp32).
+//
+// Operators.  Base operators of paper Sec. 3.1 for one input channel: MinPlus2d / MaxPlus2d = the
+// minimum / maximum of x + w over the KH x KW window.  Layers (i) MinPlus-Sum-Conv2d and (ii)
+// MaxPlus-Sum-Conv2d sum the base operator over c_in; the two-parameter compound and parallel layers
+// (Sec. 3.5, 3.6) compute
+//   y[n, c_out, oh, ow] = sum over c_in of ( alpha[c_in, c_out] * MinPlus2d(x, W1) + beta[c_in, c_out] * MaxPlus2d(x, W2) ),
+// W1 == W2 in the compound layer.  Padded taps are skipped (they hold the semiring identity), window
+// ties keep the lowest tap, every x + w is one rounded fp32 add, a channel's term is
+// fl(fl(alpha*m) + fl(beta*M)) and the channel sum adds the terms in ascending c_in starting from +0,
+// each add rounded to fp32: the result does not depend on how the work is tiled.
+//
+// Forward: a tiled kernel for 3x3 / stride 1 (lane = 8 pixels of a row x 4 output channels, kernel
+// values and coefficients wave-uniform in SGPRs, input rows in registers, NaN as padding; no
+// winner is tracked, so there is no epilogue) and a one-thread-per-output kernel for everything else.
+// Backward re-computes the window winners instead of storing C_in times larger index tensors:
+//   sum_bwd_x_kernel   one workgroup per (image, input channel[, band of rows]): the grad_x plane in LDS
+//                      as fp64, every (c_out, output pixel) adds its gradient at the winner's pixel;
+//   sum_bwd_w_kernel   one workgroup per (c_out, c_in[, slice of the batch]): 9 tap bins per branch and
+//                      the two coefficient sums in registers, reduced through LDS.
+#include <stdlib.h>
+#include <string.h>
+
+#include "tile_common.h"
+
+namespace tconv {
+namespace {
+
+using namespace tile;
+
+__device__ __forceinline__ float coef_of(const float* a, int c, int co, int C_out) {
+  return a ? a[(size_t)c * C_out + co] : 1.0f;
+}
+
+// ------------------------------------------------------------------ forward, any geometry
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const float* __restrict__ x,
+                                                              const float* __restrict__ w_min,
+                                                              const float* __restrict__ w_max,
+                                                              const float* __restrict__ alpha,
+                                                              const float* __restrict__ beta,
+                                                              float* __restrict__ y) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+  const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= total) return;
+  const int ow = (int)(o % p.Wo);
+  const int oh = (int)((o / p.Wo) % p.Ho);
+  const int co = (int)((o / ((size_t)p.Wo * p.Ho)) % p.C_out);
+  const int n = (int)(o / ((size_t)p.Wo * p.Ho * p.C_out));
+  const int KK = p.KH * p.KW;
+  const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+  float acc = 0.0f;
+  for (int c = 0; c < p.C_in; ++c) {
+    const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+    const float* wa = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * KK : nullptr;
+    const float* wb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * KK : nullptr;
+    float m = INFINITY, M = -INFINITY;
+    for (int i = 0; i < p.KH; ++i) {
+      const int ih = ih0 + i * p.dh;
+      if (ih < 0 || ih >= p.H) continue;
+      for (int j = 0; j < p.KW; ++j) {
+        const int iw = iw0 + j * p.dw;
+        if (iw < 0 || iw >= p.W) continue;
+        const float xv = xc[(size_t)ih * p.W + iw];
+        if (DO_MIN) m = fminf(m, __fadd_rn(xv, wa[i * p.KW + j]));
+        if (DO_MAX) M = fmaxf(M, __fadd_rn(xv, wb[i * p.KW + j]));
+      }
+    }
+    float term;
+    if (TWO) term = combine(coef_of(alpha, c, co, p.C_out), m, coef_of(beta, c, co, p.C_out), M);
+    else term = DO_MIN ? m : M;
+    acc = __fadd_rn(acc, term);
+  }
+  y[o] = acc;
+}
+
+// ------------------------------------------------------------------ forward, 3x3 stride 1
+// Lane = PX consecutive output pixels of a row x TN output channels; wave = 64 such segments; the
+// WAVES waves of a workgroup share the segments and differ in output-channel group.  Per input
+// channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
+// of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
+template <int MODE, int D>
+__global__ __launch_bounds__(WAVES * 64, 2) void sum_fwd_tiled3x3_kernel(
+    Params p, const float* __restrict__ x, const float* __restrict__ w_min,
+    const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
+    float* __restrict__ y, int segs, int n_units, int n_groups) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int PX = 8, TN = 4;
+  constexpr int XR = PX + 2 * D;
+
+  const int gblocks = (n_groups + WAVES - 1) / WAVES;
+  const int ublock = blockIdx.x / gblocks;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int group = (blockIdx.x - ublock * gblocks) * WAVES + wave;
+  if (group >= n_groups) return;  // whole wave leaves; the kernel has no barrier
+  const int co0 = group * TN;
+  const int lane = threadIdx.x & 63;
+  const int unit_raw = ublock * 64 + lane;
+  const bool unit_ok = unit_raw < n_units;
+  const int unit = unit_ok ? unit_raw : n_units - 1;
+  const int seg = unit % segs;
+  const int oh = (unit / segs) % p.Ho;
+  const int n = unit / (segs * p.Ho);
+  // the last segment of a row is shifted left so that every lane owns PX real pixels
+  const int ow_nom = seg * PX;
+  const int ow0 = min(ow_nom, p.Wo - PX);
+  const int first_q = unit_ok ? ow_nom - ow0 : PX;
+
+  const int iw0 = ow0 - p.pw;  // input column of register column 0
+  const size_t HW = (size_t)p.H * p.W;
+  const unsigned HWb = (unsigned)(HW * sizeof(float));
+  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
+  unsigned roff[3], mrow[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int ih = oh - p.ph + i * D;
+    mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
+    const int ihc = min(max(ih, 0), p.H - 1);
+    // byte offset of the first core column (iw0 + D >= 0 because pad_w <= D)
+    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(float));
+  }
+  int hoff[2 * D];
+  unsigned mhalo[2 * D];
+#pragma unroll
+  for (int h = 0; h < 2 * D; ++h) {
+    const int o = (h < D) ? h : h + PX;
+    const int iw = iw0 + o;
+    mhalo[h] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
+    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
+  }
+  auto load_rows = [&](float (&xs)[3][XR], int c) {
+    const unsigned soff = (unsigned)min(c, p.C_in - 1) * HWb;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+#pragma unroll
+      for (int h = 0; h < D; ++h) xs[i][h] = load_one<float>(xres, roff[i] + (unsigned)hoff[h], soff);
+      load_run<PX, float>(&xs[i][D], xres, roff[i], soff);
+#pragma unroll
+      for (int h = 0; h < D; ++h) xs[i][D + PX + h] = load_one<float>(xres, roff[i] + (unsigned)hoff[D + h], soff);
+    }
+  };
+  auto mask_rows = [&](float (&xs)[3][XR]) {
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int o = 0; o < XR; ++o) {
+        unsigned m = mrow[i];
+        if (o < D) m |= mhalo[o];
+        if (o >= D + PX) m |= mhalo[o - PX];
+        xs[i][o] = nan_or(xs[i][o], m);
+      }
+  };
+
+  float acc[TN][PX];
+#pragma unroll
+  for (int c = 0; c < TN; ++c)
+#pragma unroll
+    for (int q = 0; q < PX; ++q) acc[c][q] = 0.0f;
+
+  // one input channel: for every output channel of the lane the 9 kernel values (and the two
+  // coefficients) are wave-uniform scalars; 9 adds, 4 + 4 three-operand extrema, the rounded combine
+  auto channel = [&](const float (&xs)[3][XR], int c) {
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+      const int co = min(co0 + t, p.C_out - 1);
+      const float* wa = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * 9 : nullptr;
+      const float* wb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * 9 : nullptr;
+      float ka[9], kb[9];
+#pragma unroll
+      for (int k = 0; k < 9; ++k) {
+        if (DO_MIN) ka[k] = wa[k];
+        if (DO_MAX) kb[k] = wb[k];
+      }
+      const float ca = TWO ? coef_of(alpha, c, co, p.C_out) : 1.0f;
+      const float cb = TWO ? coef_of(beta, c, co, p.C_out) : 1.0f;
+#pragma unroll
+      for (int q = 0; q < PX; ++q) {
+        float sa[9], sb[9];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+#pragma unroll
+          for (int j = 0; j < 3; ++j) {
+            const float xv = xs[i][q + j * D];
+            if (DO_MIN) sa[i * 3 + j] = __fadd_rn(xv, ka[i * 3 + j]);
+            if (DO_MAX) sb[i * 3 + j] = (MODE == TCONV_COMPOUND) ? sa[i * 3 + j] : __fadd_rn(xv, kb[i * 3 + j]);
+          }
+        float m = 0.f, M = 0.f;
+        if (DO_MIN) {
+          m = fminf(fminf(sa[0], sa[1]), sa[2]);
+          m = fminf(fminf(m, sa[3]), sa[4]);
+          m = fminf(fminf(m, sa[5]), sa[6]);
+          m = fminf(fminf(m, sa[7]), sa[8]);
+        }
+        if (DO_MAX) {
+          M = fmaxf(fmaxf(sb[0], sb[1]), sb[2]);
+          M = fmaxf(fmaxf(M, sb[3]), sb[4]);
+          M = fmaxf(fmaxf(M, sb[5]), sb[6]);
+          M = fmaxf(fmaxf(M, sb[7]), sb[8]);
+        }
+        const float term = TWO ? combine(ca, m, cb, M) : (DO_MIN ? m : M);
+        acc[t][q] = __fadd_rn(acc[t][q], term);
+      }
+    }
+  };
+
+  float xa[3][XR], xb[3][XR];
+  load_rows(xa, 0);
+  for (int c = 0; c < p.C_in; c += 2) {
+    load_rows(xb, c + 1);  // past the last channel: a clamped, unused reload
+    mask_rows(xa);
+    channel(xa, c);
+    if (c + 1 < p.C_in) {  // wave-uniform
+      load_rows(xa, c + 2);
+      mask_rows(xb);
+      channel(xb, c + 1);
+    }
+  }
+
+  const size_t plane = (size_t)p.Ho * p.Wo;
+#pragma unroll
+  for (int t = 0; t < TN; ++t) {
+    const int co = co0 + t;
+    if (co >= p.C_out) break;  // wave-uniform
+    store_row<PX>(y + ((size_t)n * p.C_out + co) * plane + (size_t)oh * p.Wo + ow0, acc[t], first_q);
+  }
+}
+
+// ------------------------------------------------------------------ backward
+// Window of one (c_out, c_in, output pixel): the 9 (KH*KW) sums are scanned in ascending tap order with
+// strict compares, so ties keep the lowest tap.  px points at the channel's H x W plane (global or LDS,
+// row stride `rs`, first row `row0`).
+struct Winner {
+  float v;
+  int ih, iw, t;
+};
+template <bool WANT_MAX>
+__device__ __forceinline__ Winner scan_window(const Params& p, const float* px, int rs, int row0,
+                                              const float* __restrict__ w9, int oh, int ow) {
+  Winner r = {WANT_MAX ? -INFINITY : INFINITY, 0, 0, -1};
+  const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+  for (int i = 0; i < p.KH; ++i) {
+    const int ih = ih0 + i * p.dh;
+    if (ih < 0 || ih >= p.H) continue;
+    for (int j = 0; j < p.KW; ++j) {
+      const int iw = iw0 + j * p.dw;
+      if (iw < 0 || iw >= p.W) continue;
+      const float s = __fadd_rn(px[(ih - row0) * rs + iw], w9[i * p.KW + j]);
+      if (r.t < 0 || (WANT_MAX ? (s > r.v) : (s < r.v))) { r.v = s; r.ih = ih; r.iw = iw; r.t = i * p.KW + j; }
+    }
+  }
+  return r;
+}
+
+// grad_x.  Workgroup = (image n, input channel c, band of input rows [r0, r0 + TH)): the band of the
+// grad_x plane lives in LDS as fp64 next to the input rows the windows that can reach it read
+// (fp32); every (c_out, output pixel whose window can reach the band) re-computes its winners and adds
+// coef * gy at the winner's pixel if that lies in the band; the band is then written with plain stores.
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_bwd_x_kernel(Params p, const float* __restrict__ x,
+                                                        const float* __restrict__ w_min,
+                                                        const float* __restrict__ w_max,
+                                                        const float* __restrict__ alpha,
+                                                        const float* __restrict__ beta,
+                                                        const float* __restrict__ gy,
+                                                        float* __restrict__ grad_x, int TH, int n_bands) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  extern __shared__ double lds_d[];
+  const int band = blockIdx.x % n_bands;
+  const int c = (blockIdx.x / n_bands) % p.C_in;
+  const int n = blockIdx.x / (n_bands * p.C_in);
+  const int r0 = band * TH, r1 = min(r0 + TH, p.H);
+  const int eh = p.dh * (p.KH - 1);
+  // output rows whose window [oh*sh - ph, oh*sh - ph + eh] meets [r0, r1)
+  const int oh_lo = max(0, (r0 + p.ph - eh + p.sh - 1) / p.sh);
+  const int oh_hi = min(p.Ho - 1, (r1 - 1 + p.ph) / p.sh);
+  // input rows those windows read
+  const int xr0 = max(0, oh_lo * p.sh - p.ph), xr1 = min(p.H, oh_hi * p.sh - p.ph + eh + 1);
+  double* const tile = lds_d;                                   // [(r1 - r0) x W]
+  float* const xs = (float*)(lds_d + (size_t)TH * p.W);         // [(xr1 - xr0) x W]
+  for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) tile[i] = 0.0;
+  const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+  if (oh_hi >= oh_lo)
+    for (int i = threadIdx.x; i < (xr1 - xr0) * p.W; i += blockDim.x) xs[i] = xc[(size_t)xr0 * p.W + i];
+  __syncthreads();
+  const int rows = max(oh_hi - oh_lo + 1, 0);
+  const int per_co = rows * p.Wo;
+  const int KK = p.KH * p.KW;
+  for (int it = threadIdx.x; it < per_co * p.C_out; it += blockDim.x) {
+    const int co = it / per_co;
+    const int rem = it - co * per_co;
+    const int oh = oh_lo + rem / p.Wo, ow = rem % p.Wo;
+    const float g = gy[(((size_t)n * p.C_out + co) * p.Ho + oh) * p.Wo + ow];
+    if (DO_MIN) {
+      const Winner wv = scan_window<false>(p, xs, p.W, xr0, w_min + ((size_t)co * p.C_in + c) * KK, oh, ow);
+      if (wv.ih >= r0 && wv.ih < r1)
+        atomicAdd(&tile[(wv.ih - r0) * p.W + wv.iw], (double)(TWO ? coef_of(alpha, c, co, p.C_out) : 1.0f) * (double)g);
+    }
+    if (DO_MAX) {
+      const Winner wv = scan_window<true>(p, xs, p.W, xr0, w_max + ((size_t)co * p.C_in + c) * KK, oh, ow);
+      if (wv.ih >= r0 && wv.ih < r1)
+        atomicAdd(&tile[(wv.ih - r0) * p.W + wv.iw], (double)(TWO ? coef_of(beta, c, co, p.C_out) : 1.0f) * (double)g);
+    }
+  }
+  __syncthreads();
+  float* gxc = grad_x + ((size_t)n * p.C_in + c) * p.H * p.W + (size_t)r0 * p.W;
+  for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) gxc[i] = (float)tile[i];
+}
+
+// grad_w, grad_alpha, grad_beta.  Workgroup = (c_out, c_in, slice of the batch): each thread walks
+// output pixels, re-computes the winners and keeps KK tap sums per branch (in LDS, a private column per
+// thread, fp64) plus the two coefficient sums; a tree reduction over the threads, then one fp32 atomic
+// per value into the zero-filled results.
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_bwd_w_kernel(Params p, const float* __restrict__ x,
+                                                        const float* __restrict__ w_min,
+                                                        const float* __restrict__ w_max,
+                                                        const float* __restrict__ alpha,
+                                                        const float* __restrict__ beta,
+                                                        const float* __restrict__ gy,
+                                                        float* __restrict__ grad_w_min,
+                                                        float* __restrict__ grad_w_max,
+                                                        float* __restrict__ grad_alpha,
+                                                        float* __restrict__ grad_beta, int n_per_block) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
+  extern __shared__ double lds_d[];
+  const int KK = p.KH * p.KW;
+  const int NV = NBR * (KK + 1);  // per thread: KK tap sums and one coefficient sum per branch
+  const int NT = blockDim.x;                 // 256, or fewer for large kernel windows (LDS)
+  double* const mine = lds_d + threadIdx.x;  // value v of thread t at lds_d[v * NT + t]
+  for (int v = 0; v < NV; ++v) mine[v * NT] = 0.0;
+  const int co = blockIdx.x / p.C_in, c = blockIdx.x % p.C_in;
+  const int n0 = blockIdx.y * n_per_block, n1 = min(n0 + n_per_block, p.N);
+  const float* wa = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * KK : nullptr;
+  const float* wb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * KK : nullptr;
+  const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
+  const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
+  const int plane = p.Ho * p.Wo;
+  for (int n = n0; n < n1; ++n) {
+    const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+    const float* gyc = gy + ((size_t)n * p.C_out + co) * plane;
+    for (int i = threadIdx.x; i < plane; i += blockDim.x) {
+      const int oh = i / p.Wo, ow = i % p.Wo;
+      const double g = (double)gyc[i];
+      if (DO_MIN) {
+        const Winner wv = scan_window<false>(p, xc, p.W, 0, wa, oh, ow);
+        mine[wv.t * NT] += ca * g;
+        mine[KK * NT] += g * (double)wv.v;
+      }
+      if (DO_MAX) {
+        const Winner wv = scan_window<true>(p, xc, p.W, 0, wb, oh, ow);
+        const int b = (NBR - 1) * (KK + 1);
+        mine[(b + wv.t) * NT] += cb * g;
+        mine[(b + KK) * NT] += g * (double)wv.v;
+      }
+    }
+  }
+  __syncthreads();
+  for (int h = NT / 2; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h)
+      for (int v = 0; v < NV; ++v) mine[v * NT] += mine[v * NT + h];
+    __syncthreads();
+  }
+  // thread v publishes value v
+  for (int v = threadIdx.x; v < NV; v += blockDim.x) {
+    const int br = v / (KK + 1), k = v % (KK + 1);
+    const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+    const float val = (float)lds_d[v * NT];
+    if (k < KK) {
+      float* gw = is_max ? grad_w_max : grad_w_min;
+      if (gw) atomicAdd(gw + ((size_t)co * p.C_in + c) * KK + k, val);
+    } else if (TWO) {
+      float* gc = is_max ? grad_beta : grad_alpha;
+      if (gc) atomicAdd(gc + (size_t)c * p.C_out + co, val);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void sum_fill_zero_kernel(float* __restrict__ p, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+void zero_fill(float* p, size_t n, hipStream_t s) {  // a kernel, so that the call can sit in a captured graph
+  if (!p || n == 0) return;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(sum_fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+}
+
+bool tiled_ok(const Params& p) {
+  if (p.KH != 3 || p.KW != 3 || p.sh != 1 || p.sw != 1 || p.dh != p.dw) return false;
+  if (p.dh != 1 && p.dh != 2) return false;
+  if (p.pw > p.dw || p.Wo < 8) return false;
+  if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
+  return true;
+}
+
+template <int MODE>
+hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  const bool force_generic = e && strcmp(e, "generic") == 0;
+  if (tiled_ok(p) && !force_generic) {
+    const int segs = (p.Wo + 7) / 8;
+    const long long n_units = (long long)p.N * p.Ho * segs;
+    const int n_groups = (p.C_out + 3) / 4;
+    const long long blocks = ((n_units + 63) / 64) * ((n_groups + WAVES - 1) / WAVES);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (p.dh == 1)
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
+                         a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups);
+    else
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
+                         a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups);
+  } else {
+    const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+    hipLaunchKernelGGL(sum_fwd_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p,
+                       a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y);
+  }
+  return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s) {
+  const int KK = p.KH * p.KW;
+  if (g.grad_x) {
+    // band of input rows per workgroup: fp64 sums (8 B) plus the fp32 input rows its windows read
+    const size_t budget = 60 * 1024;
+    const int eh = p.dh * (p.KH - 1);
+    int TH = p.H;
+    auto bytes = [&](int th) {
+      const long long xrows = (long long)th + 2LL * eh + p.sh;  // upper bound of the rows read
+      return (size_t)th * p.W * 8 + (size_t)(xrows < p.H ? xrows : p.H) * p.W * 4;
+    };
+    while (TH > 1 && bytes(TH) > budget) TH = (TH + 1) / 2;
+    if (bytes(TH) > 64 * 1024) return hipErrorInvalidValue;  // rows too long for this kernel
+    const int n_bands = (p.H + TH - 1) / TH;
+    const long long blocks = (long long)p.N * p.C_in * n_bands;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sum_bwd_x_kernel<MODE>, dim3((unsigned)blocks), dim3(256), bytes(TH), s, p, a.x, a.w_min,
+                       a.w_max, a.alpha, a.beta, g.gy, g.grad_x, TH, n_bands);
+  }
+  float* gmin = g.grad_w_min;
+  float* gmax = g.grad_w_max;
+  if (MODE == TCONV_COMPOUND) gmin = gmax = (g.grad_w_min ? g.grad_w_min : g.grad_w_max);
+  const bool want_w = (MODE != TCONV_MAX && gmin) || (MODE != TCONV_MIN && gmax) || g.grad_alpha || g.grad_beta;
+  if (want_w) {
+    const size_t nw = (size_t)p.C_out * p.C_in * KK, nab = (size_t)p.C_in * p.C_out;
+    if (MODE != TCONV_MAX) zero_fill(gmin, nw, s);
+    if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(gmax, nw, s);
+    zero_fill(g.grad_alpha, nab, s);
+    zero_fill(g.grad_beta, nab, s);
+    const long long pairs = (long long)p.C_out * p.C_in;
+    if (pairs > 0x7fffffffLL) return hipErrorInvalidValue;
+    int slices = (int)((1024 + pairs - 1) / pairs);  // enough workgroups to fill the chip
+    if (slices > p.N) slices = p.N;
+    if (slices > 65535) slices = 65535;
+    const int n_per_block = (p.N + slices - 1) / slices;
+    const dim3 grid((unsigned)pairs, (unsigned)((p.N + n_per_block - 1) / n_per_block));
+    constexpr int NBR = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) ? 2 : 1;
+    int nt = 256;  // threads (a power of two): fewer for large kernel windows, whose sums fill the LDS
+    while (nt > 64 && (size_t)NBR * (KK + 1) * nt * sizeof(double) > 64 * 1024) nt /= 2;
+    const size_t lds = (size_t)NBR * (KK + 1) * nt * sizeof(double);
+    if (lds > 64 * 1024) return hipErrorInvalidValue;  // kernel window too large for this kernel
+    hipLaunchKernelGGL(sum_bwd_w_kernel<MODE>, grid, dim3(nt), lds, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta,
+                       g.gy, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_fwd<TCONV_MAX>(p, a, s);
+    case TCONV_MIN: return launch_fwd<TCONV_MIN>(p, a, s);
+    case TCONV_COMPOUND: return launch_fwd<TCONV_COMPOUND>(p, a, s);
+    default: return launch_fwd<TCONV_PARALLEL>(p, a, s);
+  }
+}
+
+hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_bwd<TCONV_MAX>(p, a, g, s);
+    case TCONV_MIN: return launch_bwd<TCONV_MIN>(p, a, g, s);
+    case TCONV_COMPOUND: return launch_bwd<TCONV_COMPOUND>(p, a, g, s);
+    default: return launch_bwd<TCONV_PARALLEL>(p, a, g, s);
+  }
+}
+
+const char* sum_forward_kernel_name(const Params& p) {
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  return (tiled_ok(p) && !(e && strcmp(e, "generic") == 0)) ? "sum_tiled3x3" : "sum_generic";
+}
+
+}  // namespace tconv

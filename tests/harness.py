@@ -142,3 +142,76 @@ def assert_backward_close(hip, ref, what=""):
     for k in ("grad_alpha", "grad_beta"):
         if ref.get(k) is not None and hip.get(k) is not None:
             assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+
+
+# ---------------------------------------------------------------- Sum-channel layers
+
+def sum_coefficients(cfg, inp, kind):
+    """alpha, beta [C_in, C_out] for the Sum-channel layers, drawn after everything make_inputs drew."""
+    if kind is None or cfg.mode in ("max", "min"):
+        return None, None
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 1000))
+    shape = (cfg.C_in, cfg.C_out)
+    if kind == "integer":
+        return rng.integers(-2, 3, shape).astype(np.float32), rng.integers(-2, 3, shape).astype(np.float32)
+    if kind == "one_parameter":   # beta = 1 - alpha (the one-parameter layers)
+        a = rng.uniform(0, 1, shape).astype(np.float32)
+        return a, (np.float32(1) - a).astype(np.float32)
+    return rng.uniform(-1, 1, shape).astype(np.float32), rng.uniform(-1, 1, shape).astype(np.float32)
+
+
+def run_oracle_sum(cfg, inp, alpha, beta, backward=True):
+    from oracle import tsum_oracle as osum
+    s = oracle_shape(cfg)
+    r = {"y": osum.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], alpha, beta)}
+    if backward:
+        r.update(osum.backward(s, cfg.mode, inp["x"], inp["gy"], inp["w_min"], inp["w_max"], alpha, beta))
+        ab = [None if v is None else np.abs(v) for v in (alpha, beta)]
+        sc = osum.backward(s, cfg.mode, inp["x"], np.abs(inp["gy"]), inp["w_min"], inp["w_max"], ab[0], ab[1])
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+        if r["grad_alpha"] is not None:
+            # sum of |gy * m| is at most sum|gy| * (max|x| + max|w|)
+            wmax = max(np.abs(v).max() for v in (inp["w_min"], inp["w_max"]) if v is not None)
+            bound = np.abs(inp["gy"]).astype(np.float64).sum(axis=(0, 2, 3)) * float(np.abs(inp["x"]).max() + wmax)
+            r["grad_alpha_scale"] = r["grad_beta_scale"] = np.broadcast_to(bound[None, :], r["grad_alpha"].shape)
+    return r
+
+
+def run_hip_sum(cfg, inp, alpha, beta, backward=True, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    d = tb.Desc.from_cfg(cfg)
+    ho, wo = tb.tconv_out_shape(d)
+
+    def up(a):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    x, gy, al, be = up(inp["x"]), up(inp["gy"]), up(alpha), up(beta)
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"])
+    else:
+        w_min, w_max = up(inp["w_min"]), up(inp["w_max"])
+    y = torch.full((cfg.N, cfg.C_out, ho, wo), float("nan"), device=dev)
+    tb.tconv_sum_forward(d, x, w_min, w_max, al, be, y)
+    out = dict(y=y)
+    if backward:
+        two = cfg.mode in ("compound", "parallel")
+        nan = lambda shape: torch.full(shape, float("nan"), device=dev)
+        wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+        gx = nan((cfg.N, cfg.C_in, cfg.H, cfg.W))
+        g1 = nan(wshape) if cfg.mode != "max" else None
+        g2 = nan(wshape) if cfg.mode in ("max", "parallel") else None
+        ga = nan((cfg.C_in, cfg.C_out)) if two else None
+        gb = nan((cfg.C_in, cfg.C_out)) if two else None
+        tb.tconv_sum_backward(d, x, w_min, w_max, al, be, gy, gx, g1, g2, ga, gb)
+        out.update(grad_x=gx, grad_w_min=g1, grad_w_max=g2, grad_alpha=ga, grad_beta=gb)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+def assert_sum_close(hip, ref, what=""):
+    for k in ("grad_x", "grad_w_min", "grad_w_max", "grad_alpha", "grad_beta"):
+        if ref.get(k) is None:
+            continue
+        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)

@@ -1,0 +1,85 @@
+"""GPU parity of the Sum-channel layers (tconv_sum_forward / tconv_sum_backward) against their CPU oracle:
+outputs bit for bit (the channel sum has a fixed order), gradients within 1e-5 of the size of their summands."""
+import os
+
+import numpy as np
+import pytest
+
+import harness as hs
+from paper_2504_06881_amd import binding as tb
+from paper_2504_06881_amd.inputs import CONFIGS, LayerCfg, make_inputs
+
+pytestmark = pytest.mark.gpu
+MODES = ["max", "min", "compound", "parallel"]
+
+
+def _check(cfg, coef="random", integer=False, kernel=None):
+    inp = make_inputs(cfg, integer=integer)
+    alpha, beta = hs.sum_coefficients(cfg, inp, "integer" if (integer and coef) else coef)
+    ref = hs.run_oracle_sum(cfg, inp, alpha, beta)
+    old = os.environ.pop("TCONV_FORWARD_KERNEL", None)
+    try:
+        if kernel:
+            os.environ["TCONV_FORWARD_KERNEL"] = kernel
+        hip = hs.run_hip_sum(cfg, inp, alpha, beta)
+    finally:
+        os.environ.pop("TCONV_FORWARD_KERNEL", None)
+        if old is not None:
+            os.environ["TCONV_FORWARD_KERNEL"] = old
+    what = f"[sum {cfg.name} {cfg.mode} coef={coef} int={integer} k={kernel}] "
+    hs.assert_forward_bit_exact(hip, ref, keys=("y",), what=what)
+    hs.assert_sum_close(hip, ref, what=what)
+
+
+SHAPES = [
+    LayerCfg("s_cfg1", 2, 3, 16, 16, 8, seed=40),
+    LayerCfg("s_3x3", 3, 5, 19, 23, 7, seed=41),
+    LayerCfg("s_3x3_even", 2, 6, 17, 40, 12, seed=42),
+    LayerCfg("s_3x3_d2", 2, 5, 18, 26, 5, pad=2, dil=2, seed=43),
+    LayerCfg("s_3x3_s2", 2, 4, 21, 27, 6, stride=2, seed=44),
+    LayerCfg("s_3x3_p0", 2, 3, 12, 20, 4, pad=0, seed=45),
+    LayerCfg("s_5x5", 2, 3, 14, 15, 4, KH=5, KW=5, pad=2, seed=46),
+    LayerCfg("s_1x1", 2, 9, 7, 11, 5, KH=1, KW=1, pad=0, seed=47),
+    LayerCfg("s_narrow", 4, 6, 8, 5, 8, seed=48),
+    LayerCfg("s_one3", 1, 1, 1, 1, 1, seed=49),
+    LayerCfg("s_cin33", 1, 33, 9, 16, 18, seed=50),
+    LayerCfg("s_tall", 1, 2, 300, 12, 3, seed=51),         # grad_x in several bands of rows
+]
+
+
+@pytest.mark.parametrize("cfg", SHAPES, ids=lambda c: c.name)
+def test_sum_layers(cfg):
+    for mode in MODES:
+        _check(cfg.with_(mode=mode))
+    _check(cfg.with_(mode="compound"), integer=True)
+    _check(cfg.with_(mode="parallel"), coef=None)
+    _check(cfg.with_(mode="parallel"), coef="one_parameter")
+
+
+@pytest.mark.parametrize("cfg", [SHAPES[0], SHAPES[1], SHAPES[3]], ids=lambda c: c.name)
+def test_sum_generic_forward_kernel(cfg):
+    for mode in MODES:
+        _check(cfg.with_(mode=mode), kernel="generic")
+
+
+def test_sum_layer_at_a_benchmark_size():
+    """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
+    cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
+    assert tb.tconv_sum_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "sum_tiled3x3"
+    _check(cfg)
+
+
+def test_sum_error_paths():
+    import torch
+    cfg = SHAPES[0].with_(mode="max")
+    d = tb.Desc.from_cfg(cfg)
+    z = torch.zeros(4096, device="cuda")
+    with pytest.raises(tb.TconvError) as e:     # no coefficient gradients in the single-branch layers
+        tb.tconv_sum_backward(d, z, None, z, None, None, z, z, None, z, z, None)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:     # nothing requested
+        tb.tconv_sum_backward(d, z, None, z, None, None, z, None, None, None, None, None)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:     # bf16 storage is not built for these layers
+        tb.tconv_sum_forward(tb.Desc.from_cfg(cfg.with_(dtype="bf16")), z, None, z, None, None, z)
+    assert e.value.status == -4
