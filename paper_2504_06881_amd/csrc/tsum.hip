@@ -310,6 +310,92 @@ __global__ __launch_bounds__(256) void sum_bwd_x_kernel(Params p, const float* _
   for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) gxc[i] = (float)tile[i];
 }
 
+// grad_x for 3x3 windows: the same workgroup layout, but a thread keeps the 9 input values of its output
+// pixel in registers and walks all output channels with them (the kernel values of a (c_out, c_in)
+// pair are wave-uniform scalars, gy is read coalesced), so that a (pixel, c_out) item costs about 70
+// vector instructions and one LDS atomic per branch.
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_bwd_x3x3_kernel(Params p, const float* __restrict__ x,
+                                                           const float* __restrict__ w_min,
+                                                           const float* __restrict__ w_max,
+                                                           const float* __restrict__ alpha,
+                                                           const float* __restrict__ beta,
+                                                           const float* __restrict__ gy,
+                                                           float* __restrict__ grad_x, int TH, int n_bands) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  extern __shared__ double lds_d[];
+  const int band = blockIdx.x % n_bands;
+  const int c = (blockIdx.x / n_bands) % p.C_in;
+  const int n = blockIdx.x / (n_bands * p.C_in);
+  const int r0 = band * TH, r1 = min(r0 + TH, p.H);
+  const int eh = 2 * p.dh;
+  const int oh_lo = max(0, (r0 + p.ph - eh + p.sh - 1) / p.sh);
+  const int oh_hi = min(p.Ho - 1, (r1 - 1 + p.ph) / p.sh);
+  const int xr0 = max(0, oh_lo * p.sh - p.ph), xr1 = min(p.H, oh_hi * p.sh - p.ph + eh + 1);
+  double* const tile = lds_d;                                   // [(r1 - r0) x W]
+  float* const xs = (float*)(lds_d + (size_t)TH * p.W);         // [(xr1 - xr0) x W]
+  for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) tile[i] = 0.0;
+  const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+  if (oh_hi >= oh_lo)
+    for (int i = threadIdx.x; i < (xr1 - xr0) * p.W; i += blockDim.x) xs[i] = xc[(size_t)xr0 * p.W + i];
+  __syncthreads();
+  const int rows = max(oh_hi - oh_lo + 1, 0);
+  const int n_pix = rows * p.Wo;
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  for (int pix = threadIdx.x; pix < n_pix; pix += blockDim.x) {
+    const int oh = oh_lo + pix / p.Wo, ow = pix % p.Wo;
+    const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    // the window's input values; a tap outside the image holds the identity of its branch and never wins
+    float xlo[9], xhi[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      const int ih = ih0 + (t / 3) * p.dh, iw = iw0 + (t % 3) * p.dw;
+      const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      const float v = ok ? xs[(ih - xr0) * p.W + iw] : 0.f;
+      xlo[t] = ok ? v : INFINITY;
+      xhi[t] = ok ? v : -INFINITY;
+    }
+    const float* gyp = gy + (size_t)n * p.C_out * plane + (size_t)oh * p.Wo + ow;
+    for (int co = 0; co < p.C_out; ++co) {  // uniform over the workgroup
+      const float g = gyp[(size_t)co * plane];
+      if (DO_MIN) {
+        const float* w9 = w_min + ((size_t)co * p.C_in + c) * 9;
+        float best = INFINITY;
+        int ts = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const float sm = __fadd_rn(xlo[t], w9[t]);
+          const bool b = sm < best;
+          best = b ? sm : best;
+          ts = b ? t : ts;
+        }
+        const int ih = ih0 + (ts / 3) * p.dh, iw = iw0 + (ts % 3) * p.dw;
+        if (ih >= r0 && ih < r1)
+          atomicAdd(&tile[(ih - r0) * p.W + iw], (double)(TWO ? coef_of(alpha, c, co, p.C_out) : 1.0f) * (double)g);
+      }
+      if (DO_MAX) {
+        const float* w9 = w_max + ((size_t)co * p.C_in + c) * 9;
+        float best = -INFINITY;
+        int ts = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const float sm = __fadd_rn(xhi[t], w9[t]);
+          const bool b = sm > best;
+          best = b ? sm : best;
+          ts = b ? t : ts;
+        }
+        const int ih = ih0 + (ts / 3) * p.dh, iw = iw0 + (ts % 3) * p.dw;
+        if (ih >= r0 && ih < r1)
+          atomicAdd(&tile[(ih - r0) * p.W + iw], (double)(TWO ? coef_of(beta, c, co, p.C_out) : 1.0f) * (double)g);
+      }
+    }
+  }
+  __syncthreads();
+  float* gxc = grad_x + ((size_t)n * p.C_in + c) * p.H * p.W + (size_t)r0 * p.W;
+  for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) gxc[i] = (float)tile[i];
+}
+
 // grad_w, grad_alpha, grad_beta.  Workgroup = (c_out, c_in, slice of the batch): each thread walks
 // output pixels, re-computes the winners and keeps KK tap sums per branch (in LDS, a private column per
 // thread, fp64) plus the two coefficient sums; a tree reduction over the threads, then one fp32 atomic
@@ -381,6 +467,97 @@ __global__ __launch_bounds__(256) void sum_bwd_w_kernel(Params p, const float* _
   }
 }
 
+// grad_w, grad_alpha, grad_beta for 3x3 windows: as above with the window unrolled (9 coalesced loads of
+// x per output pixel, kernel values in scalar registers).
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float* __restrict__ x,
+                                                           const float* __restrict__ w_min,
+                                                           const float* __restrict__ w_max,
+                                                           const float* __restrict__ alpha,
+                                                           const float* __restrict__ beta,
+                                                           const float* __restrict__ gy,
+                                                           float* __restrict__ grad_w_min,
+                                                           float* __restrict__ grad_w_max,
+                                                           float* __restrict__ grad_alpha,
+                                                           float* __restrict__ grad_beta, int n_per_block) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
+  constexpr int KK = 9, NV = NBR * (KK + 1);
+  extern __shared__ double lds_d[];
+  double* const mine = lds_d + threadIdx.x;  // value v of thread t at lds_d[v * 256 + t]
+#pragma unroll
+  for (int v = 0; v < NV; ++v) mine[v * 256] = 0.0;
+  const int co = blockIdx.x / p.C_in, c = blockIdx.x % p.C_in;
+  const int n0 = blockIdx.y * n_per_block, n1 = min(n0 + n_per_block, p.N);
+  float ka[9], kb[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    ka[t] = DO_MIN ? w_min[((size_t)co * p.C_in + c) * 9 + t] : 0.f;
+    kb[t] = DO_MAX ? w_max[((size_t)co * p.C_in + c) * 9 + t] : 0.f;
+  }
+  const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
+  const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
+  const int plane = p.Ho * p.Wo;
+  for (int n = n0; n < n1; ++n) {
+    const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+    const float* gyc = gy + ((size_t)n * p.C_out + co) * plane;
+    for (int i = threadIdx.x; i < plane; i += blockDim.x) {
+      const int oh = i / p.Wo, ow = i % p.Wo;
+      const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+      const double g = (double)gyc[i];
+      float bmin = INFINITY, bmax = -INFINITY;
+      int tmin = 0, tmax = 0;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int ih = ih0 + (t / 3) * p.dh, iw = iw0 + (t % 3) * p.dw;
+        const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+        const float xv = ok ? xc[(size_t)ih * p.W + iw] : 0.f;
+        if (DO_MIN) {
+          const float sm = ok ? __fadd_rn(xv, ka[t]) : INFINITY;
+          const bool b = sm < bmin;
+          bmin = b ? sm : bmin;
+          tmin = b ? t : tmin;
+        }
+        if (DO_MAX) {
+          const float sm = ok ? __fadd_rn(xv, kb[t]) : -INFINITY;
+          const bool b = sm > bmax;
+          bmax = b ? sm : bmax;
+          tmax = b ? t : tmax;
+        }
+      }
+      if (DO_MIN) {
+        mine[tmin * 256] += ca * g;
+        mine[KK * 256] += g * (double)bmin;
+      }
+      if (DO_MAX) {
+        constexpr int b0 = (NBR - 1) * (KK + 1);
+        mine[(b0 + tmax) * 256] += cb * g;
+        mine[(b0 + KK) * 256] += g * (double)bmax;
+      }
+    }
+  }
+  __syncthreads();
+  for (int h = 128; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h)
+#pragma unroll
+      for (int v = 0; v < NV; ++v) mine[v * 256] += mine[v * 256 + h];
+    __syncthreads();
+  }
+  for (int v = threadIdx.x; v < NV; v += blockDim.x) {
+    const int br = v / (KK + 1), k = v % (KK + 1);
+    const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+    const float val = (float)lds_d[v * 256];
+    if (k < KK) {
+      float* gw = is_max ? grad_w_max : grad_w_min;
+      if (gw) atomicAdd(gw + ((size_t)co * p.C_in + c) * KK + k, val);
+    } else if (TWO) {
+      float* gc = is_max ? grad_beta : grad_alpha;
+      if (gc) atomicAdd(gc + (size_t)c * p.C_out + co, val);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void sum_fill_zero_kernel(float* __restrict__ p, size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
@@ -442,8 +619,12 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
     const int n_bands = (p.H + TH - 1) / TH;
     const long long blocks = (long long)p.N * p.C_in * n_bands;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(sum_bwd_x_kernel<MODE>, dim3((unsigned)blocks), dim3(256), bytes(TH), s, p, a.x, a.w_min,
-                       a.w_max, a.alpha, a.beta, g.gy, g.grad_x, TH, n_bands);
+    if (p.KH == 3 && p.KW == 3)
+      hipLaunchKernelGGL(sum_bwd_x3x3_kernel<MODE>, dim3((unsigned)blocks), dim3(256), bytes(TH), s, p, a.x,
+                         a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, TH, n_bands);
+    else
+      hipLaunchKernelGGL(sum_bwd_x_kernel<MODE>, dim3((unsigned)blocks), dim3(256), bytes(TH), s, p, a.x, a.w_min,
+                         a.w_max, a.alpha, a.beta, g.gy, g.grad_x, TH, n_bands);
   }
   float* gmin = g.grad_w_min;
   float* gmax = g.grad_w_max;
@@ -467,7 +648,12 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
     while (nt > 64 && (size_t)NBR * (KK + 1) * nt * sizeof(double) > 64 * 1024) nt /= 2;
     const size_t lds = (size_t)NBR * (KK + 1) * nt * sizeof(double);
     if (lds > 64 * 1024) return hipErrorInvalidValue;  // kernel window too large for this kernel
-    hipLaunchKernelGGL(sum_bwd_w_kernel<MODE>, grid, dim3(nt), lds, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta,
+    if (p.KH == 3 && p.KW == 3)
+      hipLaunchKernelGGL(sum_bwd_w3x3_kernel<MODE>, grid, dim3(256), (size_t)NBR * 10 * 256 * sizeof(double), s, p,
+                         a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, gmin, gmax, g.grad_alpha, g.grad_beta,
+                         n_per_block);
+    else
+      hipLaunchKernelGGL(sum_bwd_w_kernel<MODE>, grid, dim3(nt), lds, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta,
                        g.gy, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);
   }
   return hipGetLastError();
