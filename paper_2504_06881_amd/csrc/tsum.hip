@@ -499,20 +499,35 @@ __global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float
   const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
   const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
   const int plane = p.Ho * p.Wo;
+  // x through a buffer resource and 32-bit offsets: row offset + column offset per tap, clamped into the
+  // image (a tap outside it is loaded from the clamped position and replaced by the branch's identity)
+  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * p.H * p.W * sizeof(float)));
   for (int n = n0; n < n1; ++n) {
-    const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+    const unsigned xbase = (unsigned)(((size_t)n * p.C_in + c) * p.H * p.W * sizeof(float));  // uniform
     const float* gyc = gy + ((size_t)n * p.C_out + co) * plane;
     for (int i = threadIdx.x; i < plane; i += blockDim.x) {
       const int oh = i / p.Wo, ow = i % p.Wo;
       const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
       const double g = (double)gyc[i];
+      unsigned roff[3], coff[3];
+      bool rok[3], cok[3];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int ih = ih0 + k * p.dh, iw = iw0 + k * p.dw;
+        rok[k] = ih >= 0 && ih < p.H;
+        cok[k] = iw >= 0 && iw < p.W;
+        roff[k] = (unsigned)(min(max(ih, 0), p.H - 1) * p.W) * 4u;
+        coff[k] = (unsigned)min(max(iw, 0), p.W - 1) * 4u;
+      }
+      float xv9[9];
+#pragma unroll
+      for (int t = 0; t < 9; ++t) xv9[t] = load_one<float>(xres, roff[t / 3] + coff[t % 3], xbase);
       float bmin = INFINITY, bmax = -INFINITY;
       int tmin = 0, tmax = 0;
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
-        const int ih = ih0 + (t / 3) * p.dh, iw = iw0 + (t % 3) * p.dw;
-        const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-        const float xv = ok ? xc[(size_t)ih * p.W + iw] : 0.f;
+        const bool ok = rok[t / 3] && cok[t % 3];
+        const float xv = xv9[t];
         if (DO_MIN) {
           const float sm = ok ? __fadd_rn(xv, ka[t]) : INFINITY;
           const bool b = sm < bmin;
@@ -648,7 +663,7 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
     while (nt > 64 && (size_t)NBR * (KK + 1) * nt * sizeof(double) > 64 * 1024) nt /= 2;
     const size_t lds = (size_t)NBR * (KK + 1) * nt * sizeof(double);
     if (lds > 64 * 1024) return hipErrorInvalidValue;  // kernel window too large for this kernel
-    if (p.KH == 3 && p.KW == 3)
+    if (p.KH == 3 && p.KW == 3 && (size_t)p.N * p.C_in * p.H * p.W * 4 < 0xfffff000ull)  // 32-bit byte offsets into x
       hipLaunchKernelGGL(sum_bwd_w3x3_kernel<MODE>, grid, dim3(256), (size_t)NBR * 10 * 256 * sizeof(double), s, p,
                          a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, gmin, gmax, g.grad_alpha, g.grad_beta,
                          n_per_block);
