@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_main")
+    ap.add_argument("--op", default="full", choices=["full", "sum"],
+                    help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
+                         "(tconv_sum_forward / tconv_sum_backward) on the same shapes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -79,8 +82,9 @@ def main() -> int:
     class Layer:
         """Device buffers and the three calls of one layer."""
 
-        def __init__(self, cfg):
+        def __init__(self, cfg, op):
             self.cfg = cfg
+            self.op = op
             self.inp = inp = make_inputs(cfg)
             self.d = d = tb.Desc.from_cfg(cfg)
             ho, wo = tb.tconv_out_shape(d)
@@ -110,18 +114,41 @@ def main() -> int:
             # algorithmic HBM bytes of the backward calls: gy + idx per output per branch, grad written once
             self.bytes_bi = self.n_out * (4 + 4 * cfg.branches) + inp["x"].size * 4
             self.bytes_bw = self.n_out * (4 + 4 * cfg.branches) + cfg.C_out * cfg.K * 4 * (2 if cfg.mode == "parallel" else 1)
+            if op == "sum":
+                two = cfg.mode in ("compound", "parallel")
+                g = torch.Generator(device="cpu")
+                g.manual_seed(cfg.seed + 1000)
+                cshape = (cfg.C_in, cfg.C_out)
+                self.alpha = torch.rand(cshape, generator=g).to(dev) if two else None
+                self.beta = torch.rand(cshape, generator=g).to(dev) if two else None
+                self.ga = torch.empty(cshape, device=dev) if two else None
+                self.gb = torch.empty(cshape, device=dev) if two else None
+                # the backward pass re-reads x and gy instead of index tensors
+                self.bytes_bi = (inp["x"].size + self.n_out) * 4 + inp["x"].size * 4
+                self.bytes_bw = (inp["x"].size + self.n_out) * 4
 
         def fwd(self):
+            if self.op == "sum":
+                return tb.tconv_sum_forward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.y)
             tb.tconv_forward(self.d, self.x, self.w_min, self.w_max, None, None, self.y, self.y_min, self.y_max,
                              self.idx_min, self.idx_max)
 
         def bwd_in(self):
+            if self.op == "sum":
+                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.gy,
+                                             self.gx, None, None, None, None)
             tb.tconv_backward_input(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gx)
 
         def bwd_w(self):
+            if self.op == "sum":
+                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.gy,
+                                             None, self.gw_min, self.gw_max, self.ga, self.gb)
             tb.tconv_backward_weight(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gw_min, self.gw_max)
 
-    layers = [Layer(c) for c in cfgs]
+    if args.op == "sum" and any(c.dtype != "f32" for c in cfgs):
+        print("bench.py: the Sum-channel layers are fp32 only", file=sys.stderr)
+        return 2
+    layers = [Layer(c, args.op) for c in cfgs]
 
     # HIP events on the stream the kernels are launched on (torch's current stream)
     def ev():
@@ -164,7 +191,8 @@ def main() -> int:
     dtypes = {L.cfg.dtype for L in layers}
 
     out = {
-        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step",
+        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step"
+                  + (" (Sum-channel layers)" if args.op == "sum" else ""),
         "value": round(value, 2),
         "unit": "GOPS",
         "n_gpus": 1,
@@ -177,7 +205,8 @@ def main() -> int:
         "dtype": "f32" if dtypes == {"f32"} else "bf16-storage/f32-arith",
         "data": "synthetic",
         "config": {"workload": wl_name + ", fwd+bwd_input+bwd_weight", "pairs_per_step": pairs,
-                   "forward_kernel": tb.tconv_forward_kernel_name(layers[-1].d)},
+                   "forward_kernel": (tb.tconv_sum_forward_kernel_name(layers[-1].d) if args.op == "sum"
+                                      else tb.tconv_forward_kernel_name(layers[-1].d))},
         "forward_gops": round(fwd_pairs_s / 1e9, 2),
         "ms_forward": round(t_f, 4),
         "ms_backward_input": round(t_bi, 4),
@@ -194,23 +223,34 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline([(L.cfg, L.inp) for L in layers], args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline([(L.cfg, L.inp) for L in layers], args.cpu_seconds, args.op,
+                                           [(None if L.op != "sum" or L.alpha is None else L.alpha.cpu().numpy(),
+                                             None if L.op != "sum" or L.beta is None else L.beta.cpu().numpy())
+                                            for L in layers])
     print(json.dumps(out), flush=True)
     return 0
 
 
-def cpu_baseline(layers, target_s: float):
+def cpu_baseline(layers, target_s: float, op: str = "full", coefs=None):
     """The CPU oracle, as it stands, on a batch slice sized for about target_s seconds of CPU work."""
     from oracle import tconv_oracle as orc
     threads = orc.num_threads()
+    if op == "sum":
+        from oracle import tsum_oracle as osum
+        threads = 1  # the Sum-channel oracle is a single-threaded loop nest
     n_full = layers[0][0].N
     per_image = sum(cfg.pairs for cfg, _ in layers) / n_full
 
     def run(n_img):
         t0 = time.perf_counter()
-        for cfg, inp in layers:
+        for li, (cfg, inp) in enumerate(layers):
             s = orc.Shape(n_img, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
             xs, gys = inp["x"][:n_img], inp["gy"][:n_img]
+            if op == "sum":
+                a, b = coefs[li]
+                osum.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"], a, b)
+                osum.backward(s, cfg.mode, xs, gys, inp["w_min"], inp["w_max"], a, b)
+                continue
             r = orc.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"])
             orc.backward_input(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
             orc.backward_weight(s, cfg.mode, gys, r["idx_min"], r["idx_max"])
