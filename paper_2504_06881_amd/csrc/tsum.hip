@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const fl
 // channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
 // of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
 template <int MODE, int D>
-__global__ __launch_bounds__(WAVES * 64, 2) void sum_fwd_tiled3x3_kernel(
+__global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
     float* __restrict__ y, int segs, int n_units, int n_groups) {
