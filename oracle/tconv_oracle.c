@@ -173,6 +173,60 @@ int oracle_tconv_forward(const oracle_shape* s, int mode, const float* x, const 
   return 0;
 }
 
+/*
+ * Mixed layers of Sec. 3.1: (iii) MinPlus-Max-Conv2d, y = max over c_in of MinPlus2d(X, W, h, w, c_in, c_out),
+ * and (vi) MaxPlus-Min-Conv2d, y = min over c_in of MaxPlus2d(...).  outer_max != 0 selects (iii).
+ * The window of every input channel is scanned in ascending tap order with a strict compare (ties:
+ * lowest tap, padded taps skipped), then the channels in ascending c_in with a strict compare (ties:
+ * lowest channel).  idx receives the flattened tap k = (c*KH + i)*KW + j of the winner, so the backward
+ * functions below apply unchanged (mode MIN or MAX: the whole gradient goes through idx).
+ */
+int oracle_tconv_forward_mixed(const oracle_shape* s, int outer_max, const float* x, const float* w,
+                               float* y, int32_t* idx, int out_bf16) {
+  int32_t Ho, Wo;
+  if (oracle_out_shape(s, &Ho, &Wo) != 0 || Ho < 1 || Wo < 1) return -1;
+  if (s->pad_h > s->dil_h * (s->KH - 1) || s->pad_w > s->dil_w * (s->KW - 1)) return -1;
+  if (!x || !w) return -1;
+  const int KK = s->KH * s->KW;
+  const size_t K = (size_t)s->C_in * KK;
+  const size_t x_img = (size_t)s->C_in * s->H * s->W;
+  for (int n = 0; n < s->N; ++n)
+    for (int co = 0; co < s->C_out; ++co)
+      for (int oh = 0; oh < Ho; ++oh)
+        for (int ow = 0; ow < Wo; ++ow) {
+          float best = 0.0f;
+          int32_t bk = -1;
+          for (int c = 0; c < s->C_in; ++c) {
+            /* base operator of channel c: min-plus for layer (iii), max-plus for layer (vi) */
+            float v = 0.0f;
+            int32_t t = -1;
+            for (int i = 0; i < s->KH; ++i) {
+              int ih = oh * s->stride_h - s->pad_h + i * s->dil_h;
+              if (ih < 0 || ih >= s->H) continue;
+              for (int j = 0; j < s->KW; ++j) {
+                int iw = ow * s->stride_w - s->pad_w + j * s->dil_w;
+                if (iw < 0 || iw >= s->W) continue;
+                volatile float sum = x[(size_t)n * x_img + ((size_t)c * s->H + ih) * s->W + iw] +
+                                     w[(size_t)co * K + (size_t)c * KK + i * s->KW + j];
+                float sv = sum;
+                if (t < 0 || (outer_max ? (sv < v) : (sv > v))) {
+                  v = sv;
+                  t = i * s->KW + j;
+                }
+              }
+            }
+            if (bk < 0 || (outer_max ? (v > best) : (v < best))) {
+              best = v;
+              bk = c * KK + t;
+            }
+          }
+          size_t o = (((size_t)n * s->C_out + co) * Ho + oh) * Wo + ow;
+          if (y) y[o] = out_bf16 ? round_to_bf16(best) : best;
+          if (idx) idx[o] = bk;
+        }
+  return 0;
+}
+
 /* Gradient that one output sends down one branch. */
 static double branch_grad(int mode, int is_max, const float* alpha, const float* beta, int co,
                           float gy) {

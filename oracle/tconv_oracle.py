@@ -83,6 +83,7 @@ def _load():
         lib.oracle_tconv_forward.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 10 + [ctypes.c_int]
         lib.oracle_tconv_backward_input.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 6
         lib.oracle_tconv_backward_weight.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 7
+        lib.oracle_tconv_forward_mixed.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 4 + [ctypes.c_int]
         lib.oracle_tconv_backward_alpha_beta.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 5
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
@@ -200,3 +201,20 @@ def backward_alpha_beta(s: Shape, mode: str, gy, y_min, y_max):
     if rc != 0:
         raise ValueError(f"oracle_tconv_backward_alpha_beta rejected the arguments (rc={rc})")
     return ga, gb
+
+
+def forward_mixed(s: Shape, layer: str, x, w, out_bf16: bool = False):
+    """Mixed layers of Sec. 3.1: layer "minplus_max" = (iii), "maxplus_min" = (vi).
+    Returns dict(y, idx) with idx the flattened winning tap k."""
+    ho, wo = out_shape(s)
+    x = _f32(x, (s.N, s.C_in, s.H, s.W))
+    w = _f32(w, (s.C_out, s.C_in, s.KH, s.KW))
+    y = np.empty((s.N, s.C_out, ho, wo), np.float32)
+    idx = np.empty((s.N, s.C_out, ho, wo), np.int32)
+    cs = s.c()
+    outer_max = {"minplus_max": 1, "maxplus_min": 0}[layer]
+    rc = _load().oracle_tconv_forward_mixed(ctypes.byref(cs), outer_max, _p(x), _p(w), _p(y), _p(idx),
+                                            1 if out_bf16 else 0)
+    if rc != 0:
+        raise ValueError(f"oracle_tconv_forward_mixed rejected the arguments (rc={rc})")
+    return dict(y=y, idx=idx)

@@ -72,3 +72,26 @@ def scatter_backward(xshape, wshape, idx, g, stride, pad, dil):
                     gx[n, c, oh * stride - pad + i * dil, ow * stride - pad + j * dil] += g[n, co, oh, ow]
                     gw[co, c, i, j] += g[n, co, oh, ow]
     return gx, gw
+
+
+def forward_mixed(x, w, outer_max, stride=1, pad=0, dil=1, dtype=np.float32):
+    """(y, idx) of the mixed layers of paper Sec. 3.1 by enumeration: every output's K candidate sums are
+    laid out as [C_in, KH*KW]; the inner operator reduces each row (min-plus under an outer max = layer
+    (iii), max-plus under an outer min = layer (vi)), the outer one the column of row results.  numpy's
+    argmin / argmax return the first occurrence, i.e. the lowest tap and the lowest channel."""
+    N, C, H, W = x.shape
+    CO, _, KH, KW = w.shape
+    ho, wo = out_hw(H, W, KH, KW, stride, pad, dil)
+    y = np.empty((N, CO, ho, wo), dtype)
+    idx = np.empty((N, CO, ho, wo), np.int32)
+    fill = np.inf if outer_max else -np.inf          # identity of the INNER operator
+    for n in range(N):
+        for co in range(CO):
+            for oh in range(ho):
+                for ow in range(wo):
+                    s = candidates(x, w, n, co, oh, ow, stride, pad, dil, fill, dtype).reshape(C, KH * KW)
+                    t = np.argmin(s, axis=1) if outer_max else np.argmax(s, axis=1)
+                    v = s[np.arange(C), t]
+                    c = int(np.argmax(v)) if outer_max else int(np.argmin(v))
+                    y[n, co, oh, ow], idx[n, co, oh, ow] = v[c], c * KH * KW + int(t[c])
+    return y, idx
