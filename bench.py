@@ -35,7 +35,8 @@ HBM_PEAK_GBS = 8000.0
 def alu_peak_pairs_per_s(mode: str) -> float:
     """Plain fp32 VALU roofline in pairs/s: one v_add_f32 and one v_max/min_f32 per pair,
     except compound where one add feeds both branches (3 lane-instructions per 2 pairs)."""
-    instr_per_pair = {"max": 2.0, "min": 2.0, "parallel": 2.0, "compound": 1.5}[mode]
+    instr_per_pair = {"max": 2.0, "min": 2.0, "parallel": 2.0, "compound": 1.5,
+                      "minplus_max": 2.0, "maxplus_min": 2.0}[mode]
     return LANE_OPS_PER_S / instr_per_pair
 
 
@@ -48,6 +49,9 @@ def main() -> int:
     ap.add_argument("--op", default="full", choices=["full", "sum"],
                     help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
                          "(tconv_sum_forward / tconv_sum_backward) on the same shapes")
+    ap.add_argument("--mode", default=None,
+                    choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
+                    help="run the workload's shape as another layer of the family (default: the configuration's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -74,6 +78,8 @@ def main() -> int:
         wl_name = "cfg5: the 19 parallel-mode 3x3 layers of a ResNet-20-style net on x[256,3,32,32], f32"
     else:
         cfgs = [CONFIGS[args.workload]]
+        if args.mode:
+            cfgs = [cfgs[0].with_(mode=args.mode)]
         c0 = cfgs[0]
         wl_name = (f"{c0.name}: x[{c0.N},{c0.C_in},{c0.H},{c0.W}] -> {c0.C_out}ch 3x3 s{c0.stride} p{c0.pad} "
                    f"d{c0.dil} {c0.mode} {c0.dtype}")
@@ -100,7 +106,7 @@ def main() -> int:
                 self.w_min, self.w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
             self.gy = up(inp["gy"])
             osh = (cfg.N, cfg.C_out, ho, wo)
-            do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+            do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
             self.y = torch.empty(osh, device=dev, dtype=tdt)
             self.y_min = torch.empty(osh, device=dev, dtype=tdt) if do_min else None
             self.y_max = torch.empty(osh, device=dev, dtype=tdt) if do_max else None
@@ -109,7 +115,7 @@ def main() -> int:
             self.gx = torch.empty(tuple(inp["x"].shape), device=dev)
             wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
             self.gw_min = torch.empty(wshape, device=dev) if do_min else None
-            self.gw_max = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel") else None
+            self.gw_max = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
             self.n_out = cfg.N * cfg.C_out * ho * wo
             # algorithmic HBM bytes of the backward calls: gy + idx per output per branch, grad written once
             self.bytes_bi = self.n_out * (4 + 4 * cfg.branches) + inp["x"].size * 4
@@ -250,6 +256,13 @@ def cpu_baseline(layers, target_s: float, op: str = "full", coefs=None):
                 a, b = coefs[li]
                 osum.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"], a, b)
                 osum.backward(s, cfg.mode, xs, gys, inp["w_min"], inp["w_max"], a, b)
+                continue
+            if cfg.mode in ("minplus_max", "maxplus_min"):  # single-branch layer; backward of the plain layer of its side
+                side = "min" if cfg.mode == "minplus_max" else "max"
+                f = orc.forward_mixed(s, cfg.mode, xs, inp["w_" + side])
+                kw = {"idx_" + side: f["idx"]}
+                orc.backward_input(s, side, gys, **kw)
+                orc.backward_weight(s, side, gys, **kw)
                 continue
             r = orc.forward(s, cfg.mode, xs, inp["w_min"], inp["w_max"])
             orc.backward_input(s, cfg.mode, gys, r["idx_min"], r["idx_max"])

@@ -15,7 +15,14 @@
  *     parallel:  y = alpha[c_out]*y_min + beta[c_out]*y_max,  kernel g1 = w_min, g2 = w_max
  *
  * (Sec. 3.3, Definitions "compound" and "parallel"; alpha = beta = 1 gives the
- * direct-summation variants of App. B.4).  Padding holds the semiring identity
+ * direct-summation variants of App. B.4).  The mixed layers of Sec. 3.1 reduce the
+ * window of every input channel with one operator and the channel results with the other:
+ *
+ *     minplus_max:  y = max_c ( min_{i,j} ( x + w_min ) )     layer (iii) MinPlus-Max-Conv2d
+ *     maxplus_min:  y = min_c ( max_{i,j} ( x + w_max ) )     layer (vi)  MaxPlus-Min-Conv2d
+ *
+ * with winner k = c* *KH*KW + t*: the lowest tap t* of the inner reduction inside the lowest
+ * channel c* of the outer one.  Padding holds the semiring identity
  * (-inf for max-plus, +inf for min-plus, Sec. 3.1): a padded tap never wins.
  * Ties keep the lowest k.  Every x + w is one rounded fp32 add; the combine is
  * two rounded fp32 products and one rounded fp32 sum (no fused multiply-add).
@@ -48,7 +55,16 @@
 extern "C" {
 #endif
 
-enum tconv_mode { TCONV_MAX = 0, TCONV_MIN = 1, TCONV_COMPOUND = 2, TCONV_PARALLEL = 3 };
+enum tconv_mode {
+  TCONV_MAX = 0,         /* Sec. 3.1 layer (v)  MaxPlus-Max-Conv2d                                   */
+  TCONV_MIN = 1,         /* Sec. 3.1 layer (iv) MinPlus-Min-Conv2d                                   */
+  TCONV_COMPOUND = 2,    /* Sec. 3.3 compound: one shared kernel, alpha*min + beta*max               */
+  TCONV_PARALLEL = 3,    /* Sec. 3.3 parallel: two kernels, alpha*min + beta*max                     */
+  TCONV_MINPLUS_MAX = 4, /* Sec. 3.1 layer (iii) MinPlus-Max-Conv2d: max over c_in of the min-plus operator;
+                            single branch on the MIN side (w_min, idx_min, y_min, grad_w_min)       */
+  TCONV_MAXPLUS_MIN = 5  /* Sec. 3.1 layer (vi) MaxPlus-Min-Conv2d: min over c_in of the max-plus operator;
+                            single branch on the MAX side (w_max, idx_max, y_max, grad_w_max)       */
+};
 enum tconv_dtype { TCONV_F32 = 0, TCONV_BF16 = 1 };
 enum tconv_op {
   TCONV_OP_FORWARD = 0,
@@ -81,12 +97,13 @@ int tconv_out_shape(const tconv_desc* desc, int32_t* H_out, int32_t* W_out);
 int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes);
 
 /*
- * Forward (Sec. 3.1 layers (iv), (v); Sec. 3.3 compound / parallel).
+ * Forward (Sec. 3.1 layers (iii) - (vi); Sec. 3.3 compound / parallel).
  *   x        [N, C_in, H, W], dtype.
  *   w_min    kernel of the min-plus branch, w_max of the max-plus branch, dtype.
  *            max: w_max required (w_min ignored); min: w_min required;
  *            compound: the one shared kernel through either pointer (w_min wins if both set);
- *            parallel: both required (g1 = w_min, g2 = w_max).
+ *            parallel: both required (g1 = w_min, g2 = w_max);
+ *            minplus_max: as min (w_min, idx_min, optional y_min); maxplus_min: as max.
  *   alpha, beta  fp32 [C_out] or NULL (= all ones); ignored in max / min mode.
  *   y        required; combined output (max / min: the single branch), dtype.
  *   y_min, y_max  optional branch outputs (NULL = not written), dtype.
@@ -102,7 +119,8 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
 /*
  * Backward w.r.t. the input: grad_x[n, c*, ih*, iw*] += g_b for every output and
  * live branch b, (c*, i*, j*) = unflatten(idx_b); g_min = alpha*gy, g_max = beta*gy
- * (compound / parallel), g = gy (max / min).  grad_x fp32 [N, C_in, H, W] is
+ * (compound / parallel), g = gy (max / min; minplus_max is treated as min, maxplus_min as
+ * max: one winner per output carries the whole gradient).  grad_x fp32 [N, C_in, H, W] is
  * overwritten.  The sums are accumulated in fp64 in an unspecified order and rounded
  * to fp32 once.
  */
@@ -112,7 +130,7 @@ int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* a
 
 /*
  * Backward w.r.t. the kernel(s): grad_w_b[c_out, k*] += g_b summed over (n, oh, ow).
- * max: grad_w_max; min: grad_w_min; parallel: both; compound: both branches add
+ * max, maxplus_min: grad_w_max; min, minplus_max: grad_w_min; parallel: both; compound: both branches add
  * into ONE tensor, grad_w_min if non-NULL else grad_w_max.  fp32 OIHW, overwritten.
  */
 int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* alpha,

@@ -190,8 +190,10 @@ int oracle_tconv_forward_mixed(const oracle_shape* s, int outer_max, const float
   const int KK = s->KH * s->KW;
   const size_t K = (size_t)s->C_in * KK;
   const size_t x_img = (size_t)s->C_in * s->H * s->W;
-  for (int n = 0; n < s->N; ++n)
-    for (int co = 0; co < s->C_out; ++co)
+  const long planes = (long)s->N * s->C_out; /* independent output planes; threads only share inputs */
+#pragma omp parallel for schedule(dynamic, 1)
+  for (long pl = 0; pl < planes; ++pl) {
+    const int n = (int)(pl / s->C_out), co = (int)(pl % s->C_out);
       for (int oh = 0; oh < Ho; ++oh)
         for (int ow = 0; ow < Wo; ++ow) {
           float best = 0.0f;
@@ -224,6 +226,7 @@ int oracle_tconv_forward_mixed(const oracle_shape* s, int outer_max, const float
           if (y) y[o] = out_bf16 ? round_to_bf16(best) : best;
           if (idx) idx[o] = bk;
         }
+  }
   return 0;
 }
 

@@ -14,7 +14,7 @@ from typing import Optional, Tuple
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtconv.so")
 
-MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3}
+MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3, "minplus_max": 4, "maxplus_min": 5}
 DTYPES = {"f32": 0, "bf16": 1}
 OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",

@@ -18,7 +18,7 @@ int make_params(const tconv_desc* d, Params* p) {
   if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1 || d->pad_h < 0 ||
       d->pad_w < 0)
     return TCONV_E_INVAL;
-  if (d->mode < TCONV_MAX || d->mode > TCONV_PARALLEL) return TCONV_E_INVAL;
+  if (d->mode < TCONV_MAX || d->mode > TCONV_MAXPLUS_MIN) return TCONV_E_INVAL;
   if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16) return TCONV_E_INVAL;
   const long long eh = (long long)d->dil_h * (d->KH - 1), ew = (long long)d->dil_w * (d->KW - 1);
   // a window must never lie wholly in the padding
@@ -82,7 +82,7 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
   if (!x || !y) return TCONV_E_INVAL;
   FwdArgs a = {x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max};
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (w_min ? w_min : w_max);
-  const bool do_min = p.mode != TCONV_MAX, do_max = p.mode != TCONV_MIN;
+  const bool do_min = mode_has_min(p.mode), do_max = mode_has_max(p.mode);
   if (do_min && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
   if (do_max && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
   hipStream_t s = (hipStream_t)hip_stream;
@@ -106,6 +106,7 @@ int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* a
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!gy || !grad_x) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
   if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
@@ -122,6 +123,7 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!gy) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
   if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
   switch (p.mode) {
@@ -158,6 +160,7 @@ int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, 
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!x || !y) return TCONV_E_INVAL;
+  if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
   if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
   SumArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, (float*)y};
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
@@ -176,6 +179,7 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!x || !gy) return TCONV_E_INVAL;
+  if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
   if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
   const bool two = p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL;
   if (!two && (grad_alpha || grad_beta)) return TCONV_E_INVAL;
@@ -192,7 +196,7 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
 
 const char* tconv_sum_forward_kernel_name(const tconv_desc* desc) {
   Params p;
-  if (make_params(desc, &p) != TCONV_OK) return nullptr;
+  if (make_params(desc, &p) != TCONV_OK || p.mode > TCONV_PARALLEL) return nullptr;
   return sum_forward_kernel_name(p);
 }
 

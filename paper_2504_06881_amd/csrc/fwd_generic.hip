@@ -76,6 +76,57 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, const T* __r
   }
 }
 
+// Mixed layers (paper Sec. 3.1 (iii) MinPlus-Max-Conv2d, (vi) MaxPlus-Min-Conv2d): the window of every
+// input channel is reduced on its own (strict compares, ascending taps: lowest tap), then the channel
+// results with the opposite operator (strict compares, ascending channels: lowest channel).
+template <bool OUTER_MAX, typename T>
+__global__ __launch_bounds__(256) void fwd_mixed_generic_kernel(Params p, const T* __restrict__ x,
+                                                                const T* __restrict__ w, T* __restrict__ y,
+                                                                T* __restrict__ y_branch,
+                                                                int32_t* __restrict__ idx) {
+  const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+  const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= total) return;
+  const int ow = (int)(o % p.Wo);
+  const int oh = (int)((o / p.Wo) % p.Ho);
+  const int co = (int)((o / ((size_t)p.Wo * p.Ho)) % p.C_out);
+  const int n = (int)(o / ((size_t)p.Wo * p.Ho * p.C_out));
+  const T* xn = x + (size_t)n * p.C_in * p.H * p.W;
+  const T* wr = w + (size_t)co * p.K;
+  const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+  float best = OUTER_MAX ? -INFINITY : INFINITY;
+  int ibest = 0, k = 0;
+  for (int c = 0; c < p.C_in; ++c) {
+    const T* xc = xn + (size_t)c * p.H * p.W;
+    float v = OUTER_MAX ? INFINITY : -INFINITY;  // identity of the inner operator
+    int kv = k;
+    for (int i = 0; i < p.KH; ++i) {
+      const int ih = ih0 + i * p.dh;
+      const bool rv = (ih >= 0 && ih < p.H);
+      for (int j = 0; j < p.KW; ++j, ++k) {
+        const int iw = iw0 + j * p.dw;
+        if (!rv || iw < 0 || iw >= p.W) continue;
+        const float s = __fadd_rn(ld_f32(xc, (size_t)ih * p.W + iw), ld_f32(wr, k));
+        if (OUTER_MAX ? (s < v) : (s > v)) { v = s; kv = k; }
+      }
+    }
+    if (OUTER_MAX ? (v > best) : (v < best)) { best = v; ibest = kv; }
+  }
+  st_f32(y, o, best);
+  if (y_branch) st_f32(y_branch, o, best);
+  idx[o] = ibest;
+}
+
+template <bool OUTER_MAX, typename T>
+static hipError_t launch_mixed(const Params& p, const FwdArgs& a, hipStream_t s) {
+  const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL((fwd_mixed_generic_kernel<OUTER_MAX, T>), dim3(blocks), dim3(256), 0, s, p, (const T*)a.x,
+                     (const T*)(OUTER_MAX ? a.w_min : a.w_max), (T*)a.y, (T*)(OUTER_MAX ? a.y_min : a.y_max),
+                     OUTER_MAX ? a.idx_min : a.idx_max);
+  return hipGetLastError();
+}
+
 template <int MODE, typename T>
 static hipError_t launch_t(const Params& p, const FwdArgs& a, hipStream_t s) {
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
@@ -92,7 +143,9 @@ static hipError_t launch_m(const Params& p, const FwdArgs& a, hipStream_t s) {
     case TCONV_MAX: return launch_t<TCONV_MAX, T>(p, a, s);
     case TCONV_MIN: return launch_t<TCONV_MIN, T>(p, a, s);
     case TCONV_COMPOUND: return launch_t<TCONV_COMPOUND, T>(p, a, s);
-    default: return launch_t<TCONV_PARALLEL, T>(p, a, s);
+    case TCONV_PARALLEL: return launch_t<TCONV_PARALLEL, T>(p, a, s);
+    case TCONV_MINPLUS_MAX: return launch_mixed<true, T>(p, a, s);
+    default: return launch_mixed<false, T>(p, a, s);
   }
 }
 

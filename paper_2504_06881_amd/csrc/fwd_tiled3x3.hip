@@ -2,7 +2,8 @@
 //
 // Operator: paper Sec. 3.1 layers (iv) / (v) (one min / max over all C_in*9 taps of x + w) and the
 // Sec. 3.3 compound (one shared add feeds both reductions, Sec. 3.5 closing remark) and parallel
-// combinations.  The semiring has no multiply, so the matrix cores do not apply; the kernel is
+// combinations, and the Sec. 3.1 mixed layers (iii) / (vi) (min-plus inside a channel under a max over
+// the channels, and the dual), which differ only in the inner block.  The semiring has no multiply, so the matrix cores do not apply; the kernel is
 // built for the vector ALUs:
 //
 //  * A lane owns a row segment of PX consecutive output pixels (8 at stride 1, 4 at stride 2) and 4
@@ -55,7 +56,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
     int n_units, int n_groups, int wrps, int dbg) {
-  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  // the mixed layers run as one branch: (iii) through the min-side kernel, accumulators and outputs
+  // (its operator is min-plus), (vi) through the max side; only the start value and the block differ
+  constexpr bool DO_MIN = mode_has_min(MODE), DO_MAX = mode_has_max(MODE);
   constexpr int PX = (S == 1) ? 8 : 4;          // output pixels per lane
   constexpr int NC = (PX - 1) * S + 1;          // core columns [D, D+NC): always inside the row
   constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
@@ -120,7 +123,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   for (int c = 0; c < TN; ++c)
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
-      bmax[c][q] = -INFINITY; bmin[c][q] = INFINITY;
+      bmax[c][q] = (MODE == TCONV_MAXPLUS_MIN) ? INFINITY : -INFINITY;   // identity of the fold over channels
+      bmin[c][q] = (MODE == TCONV_MINPLUS_MAX) ? -INFINITY : INFINITY;
       imax[c][q] = 0; imin[c][q] = 0;
     }
 
@@ -210,16 +214,21 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
         for (int c = 0; c < TN; ++c)
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
-            const bool is_max = (MODE == TCONV_MAX) || (MODE == TCONV_PARALLEL && b == 0);
+            const bool is_max = (MODE == TCONV_MAX) || (MODE == TCONV_MAXPLUS_MIN) || (MODE == TCONV_PARALLEL && b == 0);
             // next block in program order: other branch of the same channel, or next channel
             const int cn = (b == NB - 1) ? (c + 1) % TN : c;
-            const bool next_is_max = (MODE == TCONV_MAX) || (MODE == TCONV_PARALLEL && ((b + 1) % NB) == 0);
+            const bool next_is_max = (MODE == TCONV_MAX) || (MODE == TCONV_MAXPLUS_MIN) ||
+                                     (MODE == TCONV_PARALLEL && ((b + 1) % NB) == 0);
             float wn[18];
             load_w(wn, next_is_max ? wr_max[cn] : wr_min[cn], cA, cB);
             float wA[9], wB[9];
 #pragma unroll
             for (int t = 0; t < 9; ++t) { wA[t] = wc[t]; wB[t] = wc[9 + t]; }
-            if (is_max)
+            if (MODE == TCONV_MAXPLUS_MIN)
+              blk_maxmin2(bmax[c][q], imax[c][q], bmax[c][q + 1], imax[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
+            else if (MODE == TCONV_MINPLUS_MAX)
+              blk_minmax2(bmin[c][q], imin[c][q], bmin[c][q + 1], imin[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
+            else if (is_max)
               blk_max2(bmax[c][q], imax[c][q], bmax[c][q + 1], imax[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
             else
               blk_min2(bmin[c][q], imin[c][q], bmin[c][q + 1], imin[c][q + 1], xA0, xB0, xA1, xB1, wA, wB, tA, tB);
@@ -432,8 +441,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     }
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
-      if (MODE == TCONV_MAX) out[q] = bmax[c][q];
-      else if (MODE == TCONV_MIN) out[q] = bmin[c][q];
+      if (!DO_MIN) out[q] = bmax[c][q];
+      else if (!DO_MAX) out[q] = bmin[c][q];
       else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
     }
     store_row<PX>(y + ob, out, first_qs);
@@ -526,7 +535,9 @@ hipError_t launch_mode(const Params& p, const float* x, const float* w_min, cons
     case TCONV_MAX: return launch_geo<TCONV_MAX, TO>(p, x, w_min, w_max, a, s);
     case TCONV_MIN: return launch_geo<TCONV_MIN, TO>(p, x, w_min, w_max, a, s);
     case TCONV_COMPOUND: return launch_geo<TCONV_COMPOUND, TO>(p, x, w_min, w_max, a, s);
-    default: return launch_geo<TCONV_PARALLEL, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_PARALLEL: return launch_geo<TCONV_PARALLEL, TO>(p, x, w_min, w_max, a, s);
+    case TCONV_MINPLUS_MAX: return launch_geo<TCONV_MINPLUS_MAX, TO>(p, x, w_min, w_max, a, s);
+    default: return launch_geo<TCONV_MAXPLUS_MIN, TO>(p, x, w_min, w_max, a, s);
   }
 }
 
@@ -573,7 +584,7 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
     widen(a.w_max, wb, nw, s);
     wmin_f = wa; wmax_f = wb;
   } else {
-    widen(p.mode == TCONV_MIN ? a.w_min : a.w_max, wa, nw, s);
+    widen(mode_has_max(p.mode) ? a.w_max : a.w_min, wa, nw, s);
     wmin_f = wmax_f = wa;
   }
   return launch_mode<bf16_t>(p, xf, wmin_f, wmax_f, a, s);

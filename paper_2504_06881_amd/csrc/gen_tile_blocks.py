@@ -141,10 +141,63 @@ __device__ __forceinline__ void {name}(float& b0, int& i0, float& b1, int& i1,
 """
 
 
+def gen_mixed2(name, inner, outer, cmp):
+    """Mixed layers (paper Sec. 3.1 (iii) / (vi)): the inner operator reduces the 9 taps of ONE channel on
+    its own (v_{inner}3 over three fresh sums, then three more with two sums each), the outer operator
+    folds that channel result into the running extremum.  Same instruction count as the single-branch
+    blocks: per channel 9 adds, 4 three-operand reductions, 1 compare, 1 outer fold, 1 select."""
+    L = []
+    masks = {("0", "A"): "%[m1]", ("1", "A"): "%[m2]", ("0", "B"): "%[m3]", ("1", "B"): "vcc"}
+    for ch in "AB":
+        for p in "01":
+            L.append(f"v_add_f32 %[sa], %[w{ch}0], %[x{ch}{p}_0]")
+            L.append(f"v_add_f32 %[sb], %[w{ch}1], %[x{ch}{p}_1]")
+            L.append(f"v_add_f32 %[sc], %[w{ch}2], %[x{ch}{p}_2]")
+            L.append(f"v_{inner}3_f32 %[t{p}], %[sa], %[sb], %[sc]")
+            for a, b in [(3, 4), (5, 6), (7, 8)]:
+                L.append(f"v_add_f32 %[sa], %[w{ch}{a}], %[x{ch}{p}_{a}]")
+                L.append(f"v_add_f32 %[sb], %[w{ch}{b}], %[x{ch}{p}_{b}]")
+                L.append(f"v_{inner}3_f32 %[t{p}], %[t{p}], %[sa], %[sb]")
+        # the folds of both pixels after both chains: no instruction reads its predecessor's result
+        for p in "01":
+            L.append(f"v_cmp_{cmp}_f32 {masks[(p, ch)]}, %[t{p}], %[b{p}]")
+        for p in "01":
+            L.append(f"v_{outer}_f32 %[b{p}], %[b{p}], %[t{p}]")
+    L.append("v_cndmask_b32 %[i0], %[i0], %[tA], %[m1]")
+    L.append("v_cndmask_b32 %[i1], %[i1], %[tA], %[m2]")
+    L.append("v_cndmask_b32 %[i0], %[i0], %[tB], %[m3]")
+    L.append("v_cndmask_b32 %[i1], %[i1], %[tB], vcc")
+    ins = []
+    for ch in "AB":
+        for p in "01":
+            ins += [f'[x{ch}{p}_{i}] "v"(x{ch}{p}[{i}])' for i in range(9)]
+        ins += [f'[w{ch}{i}] "s"(w{ch}[{i}])' for i in range(9)]
+    ins += ['[tA] "v"(tA)', '[tB] "v"(tB)']
+    return f"""
+// Mixed layer: {inner}-plus inside a channel, {outer} across channels; two pixels of one output channel.
+// 64 VALU instructions for 2 x 18 candidates.
+__device__ __forceinline__ void {name}(float& b0, int& i0, float& b1, int& i1,
+                                       const float (&xA0)[9], const float (&xB0)[9],
+                                       const float (&xA1)[9], const float (&xB1)[9],
+                                       const float (&wA)[9], const float (&wB)[9], int tA, int tB) {{
+  float t0, t1, sa, sb, sc;
+  unsigned long long m1, m2, m3;
+  asm(
+{emit_asm(L)}
+      : [t0] "=&v"(t0), [t1] "=&v"(t1), [sa] "=&v"(sa), [sb] "=&v"(sb), [sc] "=&v"(sc),
+        [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+        [b0] "+v"(b0), [i0] "+v"(i0), [b1] "+v"(b1), [i1] "+v"(i1)
+      : {", ".join(ins)}
+      : "vcc");
+}}
+"""
+
+
 HEADER = """// GENERATED by gen_tile_blocks.py - do not edit by hand.
 //
 // Hand-scheduled gfx950 inner blocks of the tiled 3x3 tropical-convolution forward kernel
-// (paper Sec. 3.1 layers (iv)/(v): one max / min over all taps of x + w; Sec. 3.3 compound).
+// (paper Sec. 3.1 layers (iv)/(v): one max / min over all taps of x + w; Sec. 3.3 compound;
+// Sec. 3.1 mixed layers (iii)/(vi): min-plus per channel under a max over channels, and the dual).
 // See the generator for the scheme and for why the instruction order is fixed.
 #pragma once
 
@@ -165,5 +218,6 @@ __device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory")
 
 if __name__ == "__main__":
     out = HEADER + gen_both() + gen_one2("blk_max2", "max", "gt") + gen_one2("blk_min2", "min", "lt")
+    out += gen_mixed2("blk_minmax2", "min", "max", "gt") + gen_mixed2("blk_maxmin2", "max", "min", "lt")
     out += "\n}  // namespace tconv\n"
     print(out, end="")

@@ -17,6 +17,16 @@ struct Params {
   int mode;  // enum tconv_mode
 };
 
+// Which kernel / index / output side a mode uses.  The mixed layers are single-branch: (iii) MinPlus-Max
+// lives on the min side (its operator is min-plus), (vi) MaxPlus-Min on the max side.
+__host__ __device__ constexpr bool mode_has_min(int m) { return m != TCONV_MAX && m != TCONV_MAXPLUS_MIN; }
+__host__ __device__ constexpr bool mode_has_max(int m) { return m != TCONV_MIN && m != TCONV_MINPLUS_MAX; }
+// The backward pass of a mixed layer is the one of the plain single-branch layer on the same side: the
+// whole gradient of an output goes through its one winning tap, whatever reduction picked it.
+constexpr int backward_mode(int m) {
+  return m == TCONV_MINPLUS_MAX ? TCONV_MIN : (m == TCONV_MAXPLUS_MIN ? TCONV_MAX : m);
+}
+
 struct FwdArgs {
   const void* x;
   const void* w_min;  // kernel of the min-plus branch (compound: the shared kernel)

@@ -32,7 +32,7 @@ class LayerCfg:
     stride: int = 1
     pad: int = 1
     dil: int = 1
-    mode: str = "max"          # max | min | compound | parallel
+    mode: str = "max"          # max | min | compound | parallel | minplus_max | maxplus_min
     dtype: str = "f32"         # f32 | bf16 (storage of x, w, y)
     seed: int = 0
     w_range: float = 1.0       # kernels ~ U(-w_range, w_range)
@@ -114,7 +114,7 @@ def make_inputs(cfg: LayerCfg, alpha_beta: Optional[str] = None, integer: bool =
     alpha_beta: None -> alpha = beta = None (all ones); "random" -> U(-1, 1) per output
     channel; "half" -> 0.5 each; "contrast" -> (1, -1).
     integer: integer-valued x and w in [-4, 4] (every add exact, massive ties).
-    Weight tensors: max mode fills w_max, min mode w_min, compound one tensor returned
+    Weight tensors: max and maxplus_min mode fill w_max, min and minplus_max mode w_min, compound one tensor returned
     as both, parallel two independent tensors (W1 -> w_min, W2 -> w_max).
     """
     rng = np.random.Generator(np.random.PCG64(cfg.seed if seed is None else seed))
@@ -153,9 +153,9 @@ def make_inputs(cfg: LayerCfg, alpha_beta: Optional[str] = None, integer: bool =
         w2 = to_bf16_grid(w2) if w2 is not None else None
     x, w1 = _no_neg_zero(x), _no_neg_zero(w1)
     w2 = _no_neg_zero(w2) if w2 is not None else None
-    if cfg.mode == "max":
+    if cfg.mode in ("max", "maxplus_min"):
         w_min, w_max = None, w1
-    elif cfg.mode == "min":
+    elif cfg.mode in ("min", "minplus_max"):
         w_min, w_max = w1, None
     elif cfg.mode == "compound":
         w_min = w_max = w1

@@ -11,6 +11,9 @@ from paper_2504_06881_amd import binding as tb
 GRAD_RTOL = 1e-5  # spec tolerance for fp32 gradients
 
 
+MIXED = {"minplus_max": "min", "maxplus_min": "max"}   # mixed layer -> the side (kernel, index, output) it uses
+
+
 def oracle_shape(cfg):
     return orc.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
 
@@ -18,8 +21,16 @@ def oracle_shape(cfg):
 def run_oracle(cfg, inp, backward=True):
     s = oracle_shape(cfg)
     m = cfg.mode
-    r = orc.forward(s, m, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"],
-                    out_bf16=(cfg.dtype == "bf16"))
+    if m in MIXED:
+        # single-branch layer on the side of its operator; backward = the plain layer of that side
+        side = MIXED[m]
+        f = orc.forward_mixed(s, m, inp["x"], inp["w_" + side], out_bf16=(cfg.dtype == "bf16"))
+        r = dict(y=f["y"], y_min=None, y_max=None, idx_min=None, idx_max=None)
+        r["y_" + side], r["idx_" + side] = f["y"], f["idx"]
+        m = side
+    else:
+        r = orc.forward(s, m, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"],
+                        out_bf16=(cfg.dtype == "bf16"))
     if backward:
         kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"], alpha=inp["alpha"], beta=inp["beta"])
         r["grad_x"] = orc.backward_input(s, m, inp["gy"], **kw)
@@ -55,7 +66,7 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
         w_min, w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
     alpha, beta, gy = up(inp["alpha"]), up(inp["beta"]), up(inp["gy"])
     oshape = (cfg.N, cfg.C_out, ho, wo)
-    do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+    do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
 
     def poison(dt):  # outputs start from garbage: the library must overwrite, never accumulate
         t = torch.empty(oshape, device=dev, dtype=dt)
@@ -79,7 +90,7 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
         tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
         wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
-        gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel") else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
         tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
         if cfg.mode in ("compound", "parallel") and branch_outputs:
