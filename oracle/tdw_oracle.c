@@ -76,8 +76,9 @@ static void window(const oracle_shape* s, const float* plane, const float* w, in
   *value = best;
 }
 
+/* tap_min / tap_max (optional, int32 per output): the winning tap t = i*KW + j of each live branch. */
 int oracle_tdw_forward(const oracle_shape* s, int mode, const float* x, const float* w_min, const float* w_max,
-                       const float* alpha, const float* beta, float* y) {
+                       const float* alpha, const float* beta, float* y, int32_t* tap_min, int32_t* tap_max) {
   int32_t Ho, Wo;
   if (out_shape(s, &Ho, &Wo) != 0 || !x || !y) return -1;
   const int do_min = (mode != ORACLE_MAX), do_max = (mode != ORACLE_MIN);
@@ -92,10 +93,10 @@ int oracle_tdw_forward(const oracle_shape* s, int mode, const float* x, const fl
     for (int oh = 0; oh < Ho; ++oh)
       for (int ow = 0; ow < Wo; ++ow) {
         float m = 0.0f, M = 0.0f, out;
-        int t;
+        int t_min = 0, t_max = 0;
         long off;
-        if (do_min) window(s, plane, w_min + (long)co * KK, oh, ow, 0, &m, &t, &off);
-        if (do_max) window(s, plane, w_max + (long)co * KK, oh, ow, 1, &M, &t, &off);
+        if (do_min) window(s, plane, w_min + (long)co * KK, oh, ow, 0, &m, &t_min, &off);
+        if (do_max) window(s, plane, w_max + (long)co * KK, oh, ow, 1, &M, &t_max, &off);
         if (mode == ORACLE_MAX) out = M;
         else if (mode == ORACLE_MIN) out = m;
         else {
@@ -105,6 +106,8 @@ int oracle_tdw_forward(const oracle_shape* s, int mode, const float* x, const fl
           out = sum;
         }
         y[(pl * Ho + oh) * Wo + ow] = out;
+        if (do_min && tap_min) tap_min[(pl * Ho + oh) * Wo + ow] = t_min;
+        if (do_max && tap_max) tap_max[(pl * Ho + oh) * Wo + ow] = t_max;
       }
   }
   return 0;

@@ -39,7 +39,7 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         P = ctypes.c_void_p
-        lib.oracle_tdw_forward.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 6
+        lib.oracle_tdw_forward.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 8
         lib.oracle_tdw_backward.argtypes = [ctypes.POINTER(_Shape), ctypes.c_int] + [P] * 11
         lib.oracle_tdw_forward.restype = ctypes.c_int
         lib.oracle_tdw_backward.restype = ctypes.c_int
@@ -66,20 +66,23 @@ def out_hw(s: Shape):
     return ho, wo
 
 
-def forward(s: Shape, mode: str, x, w_min=None, w_max=None, alpha=None, beta=None):
-    """y [N, C_out, H_out, W_out] fp32.  Kernels [C_out, 1, KH, KW]; alpha, beta [C_out] or None (ones)."""
+def forward(s: Shape, mode: str, x, w_min=None, w_max=None, alpha=None, beta=None, taps: bool = False):
+    """y [N, C_out, H_out, W_out] fp32.  Kernels [C_out, 1, KH, KW]; alpha, beta [C_out] or None (ones).
+    taps=True: returns (y, tap_min, tap_max), the winning taps t = i*KW + j (int32; None for a dead branch)."""
     ho, wo = out_hw(s)
     wshape = (s.C_out, 1, s.KH, s.KW)
     x = _arr(x, (s.N, s.C_in, s.H, s.W))
     w_min, w_max = _arr(w_min, wshape), _arr(w_max, wshape)
     alpha, beta = _arr(alpha, (s.C_out,)), _arr(beta, (s.C_out,))
     y = np.empty((s.N, s.C_out, ho, wo), np.float32)
+    tmin = np.empty(y.shape, np.int32) if (taps and mode != "max") else None
+    tmax = np.empty(y.shape, np.int32) if (taps and mode != "min") else None
     cs = s.c()
     rc = _load().oracle_tdw_forward(ctypes.byref(cs), MODES[mode], _p(x), _p(w_min), _p(w_max),
-                                    _p(alpha), _p(beta), _p(y))
+                                    _p(alpha), _p(beta), _p(y), _p(tmin), _p(tmax))
     if rc != 0:
         raise ValueError(f"oracle_tdw_forward rejected the arguments (rc={rc})")
-    return y
+    return (y, tmin, tmax) if taps else y
 
 
 def backward(s: Shape, mode: str, x, gy, w_min=None, w_max=None, alpha=None, beta=None):

@@ -51,7 +51,7 @@ def test_channel_slices_are_the_full_window_layer(mode, mult, stride, pad, dil, 
     s, x, w1, w2, a, b, rng = _layer(3 + k, mult=mult, k=k, stride=stride, pad=pad, dil=dil, H=9, W=8)
     wmn, wmx = _kernels(mode, w1, w2)
     two = mode in ("compound", "parallel")
-    y = odw.forward(s, mode, x, wmn, wmx, a if two else None, b if two else None)
+    y, tmin, tmax = odw.forward(s, mode, x, wmn, wmx, a if two else None, b if two else None, taps=True)
     gy = rng.standard_normal(y.shape).astype(np.float32)
     g = odw.backward(s, mode, x, gy, wmn, wmx, a if two else None, b if two else None)
     s1 = orc.Shape(s.N, 1, s.H, s.W, 1, k, k, stride, pad, dil)
@@ -62,6 +62,10 @@ def test_channel_slices_are_the_full_window_layer(mode, mult, stride, pad, dil, 
         ab = dict(alpha=a[co:co + 1], beta=b[co:co + 1]) if two else {}
         r = orc.forward(s1, mode, x[:, c:c + 1], **kw, **ab)
         assert np.array_equal(y[:, co:co + 1], r["y"])
+        if mode != "max":   # one input channel: the flattened winner k of the full-window layer is the tap
+            assert np.array_equal(tmin[:, co:co + 1], r["idx_min"])
+        if mode != "min":
+            assert np.array_equal(tmax[:, co:co + 1], r["idx_max"])
         ikw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"], **ab)
         gx[:, c:c + 1] += orc.backward_input(s1, mode, gy[:, co:co + 1], **ikw)
         g1, g2 = orc.backward_weight(s1, mode, gy[:, co:co + 1], **ikw)
