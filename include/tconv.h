@@ -191,6 +191,43 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
 /* Name of the forward kernel tconv_sum_forward selects: "sum_tiled3x3" or "sum_generic".  Host only. */
 const char* tconv_sum_forward_kernel_name(const tconv_desc* desc);
 
+/*
+ * Depthwise layers (fp32 only; TCONV_E_UNSUPPORTED for bf16).  The MobileNetV2 variants of Sec. 5 put a
+ * tropical layer in place of every depthwise convolution: output channel co reads the single input
+ * channel co / mult, mult = C_out / C_in (TCONV_E_SHAPE unless C_out is a multiple of C_in), so the layer
+ * is the base operator of Sec. 3.1 per channel, combined as in Sec. 3.5 / 3.6:
+ *   m = min over the window of x[n, co / mult] + w_min[co],  M = max over the window of x + w_max[co]
+ *   mode MAX: y = M;  MIN: y = m;  COMPOUND (one kernel) / PARALLEL (two): y = alpha[co]*m + beta[co]*M
+ *   x [N, C_in, H, W];  w_min, w_max [C_out, 1, KH, KW] (same rules as tconv_forward for which is needed);
+ *   alpha, beta fp32 [C_out] or NULL (= ones), ignored in MAX / MIN mode;  y [N, C_out, H_out, W_out].
+ * Padded taps are skipped, ties keep the lowest tap t = i*KW + j, every x + w is one rounded fp32 add and
+ * y = fl(fl(alpha*m) + fl(beta*M)).  Modes above PARALLEL: TCONV_E_INVAL.
+ *   idx      uint8 [N, C_out, H_out, W_out], optional in forward (NULL: inference, nothing saved),
+ *            required in backward: low nibble = winning tap of the min-plus branch, high nibble = of the
+ *            max-plus branch (0 for a branch the mode does not have).  TCONV_E_UNSUPPORTED if KH*KW > 16.
+ */
+int tconv_depthwise_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                            const float* alpha, const float* beta, void* y, uint8_t* idx, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of the depthwise layer through the saved winners, with g = gy[n, co, oh, ow]:
+ *   grad_x[n, co / mult, ih*, iw*] += alpha[co]*g (min winner), += beta[co]*g (max winner); g itself in
+ *   MAX / MIN mode.  Summed in fp32 in a fixed order (a gather: no atomics), overwritten.
+ *   grad_w_min[co, t*] += alpha[co]*g, grad_w_max likewise with beta (COMPOUND: both into ONE tensor,
+ *   grad_w_min if non-NULL else grad_w_max);  grad_alpha[co] = sum g*m, grad_beta[co] = sum g*M (COMPOUND /
+ *   PARALLEL only, TCONV_E_INVAL otherwise; they need x and the kernels, which may be NULL when neither is
+ *   requested).  Partial sums in fp32 / fp64 inside a workgroup, fp32 atomics across workgroups; overwritten.
+ * Any gradient pointer may be NULL (not computed); at least one must be given.
+ */
+int tconv_depthwise_backward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                             const float* alpha, const float* beta, const float* gy, const uint8_t* idx,
+                             float* grad_x, float* grad_w_min, float* grad_w_max, float* grad_alpha,
+                             float* grad_beta, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Name of the forward kernel tconv_depthwise_forward selects: "dw_tiled3x3" or "dw_generic".  Host only. */
+const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc);
+
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */
 const char* tconv_status_string(int status);
 

@@ -19,7 +19,8 @@ DTYPES = {"f32": 0, "bf16": 1}
 OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",
            "tconv_backward_weight", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
-           "tconv_sum_forward_kernel_name", "tconv_status_string", "tconv_forward_kernel_name")
+           "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
+           "tconv_depthwise_forward_kernel_name", "tconv_status_string", "tconv_forward_kernel_name")
 
 
 class TconvError(RuntimeError):
@@ -85,13 +86,18 @@ def load() -> ctypes.CDLL:
         lib.tconv_sum_backward.argtypes = [D] + [P] * 12 + [ctypes.c_size_t, P]
         lib.tconv_sum_forward_kernel_name.argtypes = [D]
         lib.tconv_sum_forward_kernel_name.restype = ctypes.c_char_p
+        lib.tconv_depthwise_forward.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv_depthwise_backward.argtypes = [D] + [P] * 13 + [ctypes.c_size_t, P]
+        lib.tconv_depthwise_forward_kernel_name.argtypes = [D]
+        lib.tconv_depthwise_forward_kernel_name.restype = ctypes.c_char_p
         lib.tconv_status_string.argtypes = [ctypes.c_int]
         lib.tconv_status_string.restype = ctypes.c_char_p
         lib.tconv_forward_kernel_name.argtypes = [D]
         lib.tconv_forward_kernel_name.restype = ctypes.c_char_p
         for f in ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward",
                   "tconv_backward_input", "tconv_backward_weight", "tconv_backward_alpha_beta",
-                  "tconv_sum_forward", "tconv_sum_backward"):
+                  "tconv_sum_forward", "tconv_sum_backward", "tconv_depthwise_forward",
+                  "tconv_depthwise_backward"):
             getattr(lib, f).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -195,4 +201,29 @@ def tconv_sum_backward(desc: Desc, x, w_min, w_max, alpha, beta, gy, grad_x, gra
 def tconv_sum_forward_kernel_name(desc: Desc) -> str:
     cd = desc.c()
     r = load().tconv_sum_forward_kernel_name(ctypes.byref(cd))
+    return r.decode() if r else ""
+
+
+def tconv_depthwise_forward(desc: Desc, x, w_min, w_max, alpha, beta, y, idx=None, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_depthwise_forward(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha),
+                                          _ptr(beta), _ptr(y), _ptr(idx), _ptr(workspace), wsz, _stream()),
+           "tconv_depthwise_forward")
+
+
+def tconv_depthwise_backward(desc: Desc, x, w_min, w_max, alpha, beta, gy, idx, grad_x, grad_w_min, grad_w_max,
+                             grad_alpha, grad_beta, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_depthwise_backward(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha),
+                                           _ptr(beta), _ptr(gy), _ptr(idx), _ptr(grad_x), _ptr(grad_w_min),
+                                           _ptr(grad_w_max), _ptr(grad_alpha), _ptr(grad_beta), _ptr(workspace),
+                                           wsz, _stream()),
+           "tconv_depthwise_backward")
+
+
+def tconv_depthwise_forward_kernel_name(desc: Desc) -> str:
+    cd = desc.c()
+    r = load().tconv_depthwise_forward_kernel_name(ctypes.byref(cd))
     return r.decode() if r else ""

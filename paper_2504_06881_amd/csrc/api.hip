@@ -200,6 +200,65 @@ const char* tconv_sum_forward_kernel_name(const tconv_desc* desc) {
   return sum_forward_kernel_name(p);
 }
 
+// Depthwise layers: C_out a multiple of C_in, one of the four base modes, fp32 storage.
+static int depthwise_params(const tconv_desc* desc, Params* p) {
+  const int rc = make_params(desc, p);
+  if (rc != TCONV_OK) return rc;
+  if (p->mode > TCONV_PARALLEL) return TCONV_E_INVAL;
+  if (p->C_out % p->C_in != 0) return TCONV_E_SHAPE;
+  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  return TCONV_OK;
+}
+
+int tconv_depthwise_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                            const float* alpha, const float* beta, void* y, uint8_t* idx, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = depthwise_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!x || !y) return TCONV_E_INVAL;
+  if (idx && p.KH * p.KW > 16) return TCONV_E_UNSUPPORTED;  // a winning tap must fit a nibble
+  DwArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, (float*)y, idx};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
+  if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
+  const hipError_t e = launch_depthwise_forward(p, a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_depthwise_backward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                             const float* alpha, const float* beta, const float* gy, const uint8_t* idx,
+                             float* grad_x, float* grad_w_min, float* grad_w_max, float* grad_alpha,
+                             float* grad_beta, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params p;
+  const int rc = depthwise_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !idx) return TCONV_E_INVAL;
+  if (p.KH * p.KW > 16) return TCONV_E_UNSUPPORTED;
+  const bool two = p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL;
+  if (!two && (grad_alpha || grad_beta)) return TCONV_E_INVAL;
+  if (!grad_x && !grad_w_min && !grad_w_max && !grad_alpha && !grad_beta) return TCONV_E_INVAL;
+  DwArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, nullptr,
+              const_cast<uint8_t*>(idx)};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
+  if (grad_alpha || grad_beta) {  // the branch outputs are re-evaluated at the winners
+    if (!x) return TCONV_E_INVAL;
+    if ((p.mode != TCONV_MAX && !a.w_min) || (p.mode != TCONV_MIN && !a.w_max)) return TCONV_E_INVAL;
+  }
+  const DwGrads g = {gy, grad_x, grad_w_min, grad_w_max, grad_alpha, grad_beta};
+  const hipError_t e = launch_depthwise_backward(p, a, g, (hipStream_t)hip_stream);
+  if (e == hipErrorInvalidValue) return TCONV_E_UNSUPPORTED;
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc) {
+  Params p;
+  if (depthwise_params(desc, &p) != TCONV_OK) return nullptr;
+  return depthwise_forward_kernel_name(p);
+}
+
 const char* tconv_status_string(int status) {
   switch (status) {
     case TCONV_OK: return "ok";

@@ -67,6 +67,28 @@ struct SumGrads {
   float* grad_beta;
 };
 
+// Depthwise layers (fp32): C_out = mult * C_in, output channel co reads input channel co / mult; kernels
+// [C_out, 1, KH, KW], alpha / beta [C_out]; idx: one byte per output, low nibble = winning tap of the min-plus
+// branch, high nibble = of the max-plus branch.
+struct DwArgs {
+  const float* x;
+  const float* w_min;
+  const float* w_max;
+  const float* alpha;
+  const float* beta;
+  float* y;      // forward only
+  uint8_t* idx;  // written by forward (optional there), read by backward
+};
+
+struct DwGrads {
+  const float* gy;
+  float* grad_x;
+  float* grad_w_min;
+  float* grad_w_max;
+  float* grad_alpha;
+  float* grad_beta;
+};
+
 // bf16 storage helpers: exact widening, round-to-nearest-even narrowing.
 typedef unsigned short bf16_t;
 
@@ -102,5 +124,9 @@ hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* g
 hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s);
 hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s);
 const char* sum_forward_kernel_name(const Params& p);
+
+hipError_t launch_depthwise_forward(const Params& p, const DwArgs& a, hipStream_t s);
+hipError_t launch_depthwise_backward(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s);
+const char* depthwise_forward_kernel_name(const Params& p);
 
 }  // namespace tconv

@@ -1,0 +1,580 @@
+// Depthwise tropical convolution layers on gfx950: forward and backward.
+//
+// Layer: every output channel co reads ONE input channel c = co / mult (mult = C_out / C_in), so the
+// layer is the base operator of paper Sec. 3.1 applied per channel,
+//   m = min over the window of x + w_min[co],  M = max over the window of x + w_max[co],
+//   y = M | m | alpha[co]*m + beta[co]*M  (Sec. 3.5 / 3.6 combination; used in place of the depthwise
+//   convolutions of the MobileNetV2 variants, Sec. 5).
+// With 9 candidates per output and 8-9 bytes of traffic per output the layer is bound by HBM, not by the
+// vector ALUs, so the kernels are built around bytes:
+//   * forward writes, next to y, ONE byte per output that packs both winning taps (low nibble: min-plus
+//     tap, high nibble: max-plus tap); backward reads gy and that byte instead of re-deriving the winners
+//     from x (4 more bytes per output and several times the arithmetic);
+//   * forward, 3x3: a wave stages the input tile of 64 x 4 outputs in its own slice of LDS (padding as NaN,
+//     which v_min3 / v_max3 ignore), each lane then owns 4 consecutive outputs of one row; no workgroup
+//     barrier anywhere;
+//   * backward w.r.t. the input is a GATHER: the lane that owns an input pixel visits the 9 outputs whose
+//     window covers it and adds the gradient of those that picked it.  No atomics, no zero fill, a fixed
+//     summation order;
+//   * the kernel / coefficient gradients are per-channel reductions: per-thread partial sums in LDS, one
+//     float atomic per workgroup and result element.
+#include <stdlib.h>
+#include <string.h>
+
+#include "tile_common.h"
+// after tile_common.h: the blocks header relies on the HIP runtime declarations included there
+#include <tile_blocks_gfx950.h>
+
+namespace tconv {
+namespace {
+
+using namespace tile;
+
+__device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7fc00000u); }
+
+// y of one output from its branch extrema
+template <int MODE>
+__device__ __forceinline__ float dw_combine(float m, float M, float a, float b) {
+  if (MODE == TCONV_MAX) return M;
+  if (MODE == TCONV_MIN) return m;
+  return combine(a, m, b, M);
+}
+
+// ------------------------------------------------------------------------------------------ forward, generic
+
+// One thread per output, any window size, stride, padding, dilation.  Padded taps are skipped; strict
+// compares in ascending tap order keep the lowest winning tap.
+template <int MODE>
+__global__ __launch_bounds__(256) void dw_fwd_generic_kernel(Params p, int mult, const float* __restrict__ x,
+                                                             const float* __restrict__ w_min,
+                                                             const float* __restrict__ w_max,
+                                                             const float* __restrict__ alpha,
+                                                             const float* __restrict__ beta, float* __restrict__ y,
+                                                             uint8_t* __restrict__ idx) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+  const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= total) return;
+  const int ow = (int)(o % p.Wo);
+  const int oh = (int)((o / p.Wo) % p.Ho);
+  const int co = (int)((o / ((size_t)p.Wo * p.Ho)) % p.C_out);
+  const int n = (int)(o / ((size_t)p.Wo * p.Ho * p.C_out));
+  const int KK = p.KH * p.KW;
+  const float* xp = x + ((size_t)n * p.C_in + co / mult) * p.H * p.W;
+  const float* wa = DO_MIN ? w_min + (size_t)co * KK : nullptr;
+  const float* wb = DO_MAX ? w_max + (size_t)co * KK : nullptr;
+  float m = INFINITY, M = -INFINITY;
+  int tm = 0, tM = 0;
+  for (int i = 0; i < p.KH; ++i) {
+    const int ih = oh * p.sh - p.ph + i * p.dh;
+    if (ih < 0 || ih >= p.H) continue;
+    for (int j = 0; j < p.KW; ++j) {
+      const int iw = ow * p.sw - p.pw + j * p.dw;
+      if (iw < 0 || iw >= p.W) continue;
+      const float xv = xp[(size_t)ih * p.W + iw];
+      const int t = i * p.KW + j;
+      if (DO_MIN) {
+        const float s = __fadd_rn(xv, wa[t]);
+        if (s < m) { m = s; tm = t; }
+      }
+      if (DO_MAX) {
+        const float s = __fadd_rn(xv, wb[t]);
+        if (s > M) { M = s; tM = t; }
+      }
+    }
+  }
+  float a = 1.f, b = 1.f;
+  if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
+    if (alpha) a = alpha[co];
+    if (beta) b = beta[co];
+  }
+  y[o] = dw_combine<MODE>(m, M, a, b);
+  if (idx) idx[o] = (uint8_t)(tm | (tM << 4));
+}
+
+// ------------------------------------------------------------------------------------------ forward, 3x3 tiled
+
+// A wave owns TH x TW outputs of one (image, output channel) plane: LR = TW/4 lanes side by side, each with
+// 4 consecutive outputs of a row, TH = 64 / LR rows.  The last tile of a row is moved left so that it ends
+// with the row (its lanes store only the columns the unmoved tile would own), and the last 4-pixel segment
+// of a short row likewise.
+template <int MODE, int S, int TW, bool WANT_IDX>
+__global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int mult, const float* __restrict__ x,
+                                                                  const float* __restrict__ w_min,
+                                                                  const float* __restrict__ w_max,
+                                                                  const float* __restrict__ alpha,
+                                                                  const float* __restrict__ beta,
+                                                                  float* __restrict__ y, uint8_t* __restrict__ idx,
+                                                                  int tiles_w, int tiles_h, long long n_items) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr int LR = TW / 4, TH = 64 / LR;
+  constexpr int ROWS = (TH - 1) * S + 3, COLS = (TW - 1) * S + 3, PITCH = (COLS + 3) & ~3;
+  constexpr int NC = 3 * S + 3;  // input columns under a lane's 4 outputs
+  __shared__ float tile_all[WAVES][ROWS * PITCH];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const long long item = (long long)blockIdx.x * WAVES + wave;
+  if (item >= n_items) return;  // whole wave; the kernel has no workgroup barrier
+  const int tw = (int)(item % tiles_w);
+  const int th = (int)((item / tiles_w) % tiles_h);
+  const long long plane = item / ((long long)tiles_w * tiles_h);  // n * C_out + co
+  const int co = (int)(plane % p.C_out);
+  const int n = (int)(plane / p.C_out);
+  const int own_w = tw * TW;
+  const int org_w = min(own_w, max(p.Wo - TW, 0));
+  const int oh0 = th * TH;
+  const float* xp = x + ((size_t)n * p.C_in + co / mult) * p.H * p.W;
+  const int ih_base = oh0 * S - p.ph, iw_base = org_w * S - p.pw;
+  float* const t = tile_all[wave];
+  for (int e = lane; e < ROWS * COLS; e += 64) {
+    const int r = e / COLS, cc = e - r * COLS;
+    const int ih = ih_base + r, iw = iw_base + cc;
+    float v = quiet_nan();
+    if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) v = xp[(size_t)ih * p.W + iw];
+    t[r * PITCH + cc] = v;
+  }
+  wave_lds_fence();
+
+  const int r = lane / LR, seg = lane % LR;
+  const int oh = oh0 + r;
+  const int nominal = org_w + 4 * seg;
+  const int lo = max(own_w, nominal);       // first column this lane is responsible for
+  const int ow0 = min(nominal, p.Wo - 4);   // first column it computes
+  const int first_q = lo - ow0;             // >= 4: nothing to store
+  const bool act = (oh < p.Ho) && (first_q < 4);
+  const int lc = (ow0 - org_w) * S;
+
+  float xs[3][NC];
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+#pragma unroll
+    for (int k = 0; k < NC; ++k) xs[i][k] = t[(r * S + i) * PITCH + lc + k];
+
+  float wa[9], wb[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    wa[k] = DO_MIN ? w_min[(size_t)co * 9 + k] : 0.f;
+    wb[k] = DO_MAX ? w_max[(size_t)co * 9 + k] : 0.f;
+  }
+  float a = 1.f, b = 1.f;
+  if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
+    if (alpha) a = alpha[co];
+    if (beta) b = beta[co];
+  }
+  float out[4];
+  int code[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float sa[9], sb[9];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float xv = xs[i][q * S + j];
+        if (DO_MIN) sa[i * 3 + j] = __fadd_rn(xv, wa[i * 3 + j]);
+        if (DO_MAX) sb[i * 3 + j] = (MODE == TCONV_COMPOUND) ? sa[i * 3 + j] : __fadd_rn(xv, wb[i * 3 + j]);
+      }
+    float m = 0.f, M = 0.f;
+    int tm = 0, tM = 0;
+    if (DO_MIN) {
+      m = fminf(fminf(sa[0], sa[1]), sa[2]);
+      m = fminf(fminf(m, sa[3]), sa[4]);
+      m = fminf(fminf(m, sa[5]), sa[6]);
+      m = fminf(fminf(m, sa[7]), sa[8]);
+      if (WANT_IDX) {
+#pragma unroll
+        for (int k = 8; k >= 0; --k) tm = (sa[k] == m) ? k : tm;  // NaN (padding) never equals
+      }
+    }
+    if (DO_MAX) {
+      M = fmaxf(fmaxf(sb[0], sb[1]), sb[2]);
+      M = fmaxf(fmaxf(M, sb[3]), sb[4]);
+      M = fmaxf(fmaxf(M, sb[5]), sb[6]);
+      M = fmaxf(fmaxf(M, sb[7]), sb[8]);
+      if (WANT_IDX) {
+#pragma unroll
+        for (int k = 8; k >= 0; --k) tM = (sb[k] == M) ? k : tM;
+      }
+    }
+    out[q] = dw_combine<MODE>(m, M, a, b);
+    code[q] = tm | (tM << 4);
+  }
+  if (!act) return;
+  const size_t ob = ((size_t)plane * p.Ho + oh) * p.Wo + ow0;
+  store_row<4>(y + ob, out, first_q);
+  if (WANT_IDX) {
+    if (first_q == 0 && ((uintptr_t)(idx + ob) & 3) == 0) {
+      *(unsigned*)(idx + ob) = (unsigned)code[0] | ((unsigned)code[1] << 8) | ((unsigned)code[2] << 16) |
+                               ((unsigned)code[3] << 24);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (q >= first_q) idx[ob + q] = (uint8_t)code[q];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ backward w.r.t. x
+
+// Generic gather, one thread per input element: tap (i, j) of output (oh, ow) reads input
+// (oh*s - p + i*d, ow*s - p + j*d), so the input pixel looks, for every tap, at the one output (if any)
+// that would read it through that tap and takes its gradient if that tap is the output's winner.
+template <int MODE>
+__global__ __launch_bounds__(256) void dw_bwd_x_generic_kernel(Params p, int mult, const float* __restrict__ gy,
+                                                               const uint8_t* __restrict__ idx,
+                                                               const float* __restrict__ alpha,
+                                                               const float* __restrict__ beta,
+                                                               float* __restrict__ grad_x) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  const size_t total = (size_t)p.N * p.C_in * p.H * p.W;
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int iw = (int)(e % p.W);
+  const int ih = (int)((e / p.W) % p.H);
+  const int c = (int)((e / ((size_t)p.W * p.H)) % p.C_in);
+  const int n = (int)(e / ((size_t)p.W * p.H * p.C_in));
+  float acc = 0.f;
+  for (int mm = 0; mm < mult; ++mm) {
+    const int co = c * mult + mm;
+    const float a = (TWO && alpha) ? alpha[co] : 1.f, b = (TWO && beta) ? beta[co] : 1.f;
+    const size_t pb = ((size_t)n * p.C_out + co) * p.Ho * p.Wo;
+    for (int i = 0; i < p.KH; ++i) {
+      const int th = ih + p.ph - i * p.dh;
+      if (th < 0 || th % p.sh != 0 || th / p.sh >= p.Ho) continue;
+      for (int j = 0; j < p.KW; ++j) {
+        const int tw = iw + p.pw - j * p.dw;
+        if (tw < 0 || tw % p.sw != 0 || tw / p.sw >= p.Wo) continue;
+        const size_t o = pb + (size_t)(th / p.sh) * p.Wo + tw / p.sw;
+        const int code = idx[o], t = i * p.KW + j;
+        const float g = gy[o];
+        if (DO_MIN && (code & 15) == t) acc += a * g;
+        if (DO_MAX && (code >> 4) == t) acc += b * g;
+      }
+    }
+  }
+  grad_x[e] = acc;
+}
+
+// 3x3, stride 1, dilation 1: a wave owns TH x TW INPUT pixels of one (image, input channel) plane and stages
+// the gy / winner tiles of the outputs around them in LDS (gradient 0 and a code no tap matches outside
+// the output plane).
+template <int MODE, int TW>
+__global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, int mult, const float* __restrict__ gy,
+                                                                    const uint8_t* __restrict__ idx,
+                                                                    const float* __restrict__ alpha,
+                                                                    const float* __restrict__ beta,
+                                                                    float* __restrict__ grad_x, int tiles_w,
+                                                                    int tiles_h, long long n_items) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int LR = TW / 4, TH = 64 / LR;
+  constexpr int ROWS = TH + 2, COLS = TW + 2, PITCH = (COLS + 3) & ~3;
+  __shared__ float g_all[WAVES][ROWS * PITCH];
+  __shared__ int c_all[WAVES][ROWS * PITCH];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const long long item = (long long)blockIdx.x * WAVES + wave;
+  if (item >= n_items) return;  // whole wave; no workgroup barrier
+  const int tw = (int)(item % tiles_w);
+  const int th = (int)((item / tiles_w) % tiles_h);
+  const long long plane = item / ((long long)tiles_w * tiles_h);  // n * C_in + c
+  const int c = (int)(plane % p.C_in);
+  const int n = (int)(plane / p.C_in);
+  const int own_w = tw * TW;
+  const int org_w = min(own_w, max(p.W - TW, 0));
+  const int ih0 = th * TH;
+  float* const gt = g_all[wave];
+  int* const ct = c_all[wave];
+
+  const int r = lane / LR, seg = lane % LR;
+  const int ih = ih0 + r;
+  const int nominal = org_w + 4 * seg;
+  const int lo = max(own_w, nominal);
+  const int iw0 = min(nominal, p.W - 4);
+  const int first_q = lo - iw0;
+  const bool act = (ih < p.H) && (first_q < 4);
+  const int lc = iw0 - org_w;
+
+  // tile row rr holds output row ih0 + ph - 2 + rr, tile column cc output column org_w + pw - 2 + cc;
+  // input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
+  const int oh_base = ih0 + p.ph - 2, ow_base = org_w + p.pw - 2;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int mm = 0; mm < mult; ++mm) {
+    const int co = c * mult + mm;
+    const size_t pb = ((size_t)n * p.C_out + co) * p.Ho * p.Wo;
+    wave_lds_fence();  // every lane is done with the tiles of the previous output channel
+    for (int e = lane; e < ROWS * COLS; e += 64) {
+      const int rr = e / COLS, cc = e - rr * COLS;
+      const int oh = oh_base + rr, ow = ow_base + cc;
+      float g = 0.f;
+      int code = 0xff;
+      if (oh >= 0 && oh < p.Ho && ow >= 0 && ow < p.Wo) {
+        const size_t o = pb + (size_t)oh * p.Wo + ow;
+        g = gy[o];
+        code = idx[o];
+      }
+      gt[rr * PITCH + cc] = g;
+      ct[rr * PITCH + cc] = code;
+    }
+    wave_lds_fence();
+    const float a = (TWO && alpha) ? alpha[co] : 1.f, b = (TWO && beta) ? beta[co] : 1.f;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      // outputs of tile row r + 2 - i, columns lc + q + 2 - j for q = 0..3, j = 0..2: lc .. lc + 5
+      float g6[6];
+      int c6[6];
+#pragma unroll
+      for (int k = 0; k < 6; ++k) {
+        g6[k] = gt[(r + 2 - i) * PITCH + lc + k];
+        c6[k] = ct[(r + 2 - i) * PITCH + lc + k];
+      }
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int t = i * 3 + j;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float g = g6[q + 2 - j];
+          const int code = c6[q + 2 - j];
+          if (DO_MIN) acc[q] += ((code & 15) == t) ? a * g : 0.f;
+          if (DO_MAX) acc[q] += ((code >> 4) == t) ? b * g : 0.f;
+        }
+      }
+    }
+  }
+  if (!act) return;
+  store_row<4>(grad_x + ((size_t)plane * p.H + ih) * p.W + iw0, acc, first_q);
+}
+
+// ------------------------------------------------------------------------------------------ parameter gradients
+
+// Offset, inside its input plane, of the pixel that tap t of output (oh, ow) reads.  A winner written by the
+// forward pass is always inside the plane; the clamps only keep a corrupted index tensor from reading
+// out of bounds.
+__device__ __forceinline__ size_t winner_offset(const Params& p, int oh, int ow, int t) {
+  const int i = min(t / p.KW, p.KH - 1), j = t - (t / p.KW) * p.KW;
+  const int ih = min(max(oh * p.sh - p.ph + i * p.dh, 0), p.H - 1);
+  const int iw = min(max(ow * p.sw - p.pw + j * p.dw, 0), p.W - 1);
+  return (size_t)ih * p.W + iw;
+}
+
+// grad_w_b[co, t] = coef_b * sum of gy over the outputs of channel co whose branch-b winner is tap t;
+// grad_alpha[co] = sum gy * m, grad_beta[co] = sum gy * M with m, M re-evaluated at the winner.
+// Workgroup = (output channel, slice of the batch).  Every thread keeps its own column of partial sums in
+// LDS (bins[row][thread], no conflicts), rows: KK taps per branch, then one per coefficient gradient.
+template <int MODE>
+__global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, const float* __restrict__ x,
+                                                            const float* __restrict__ w_min,
+                                                            const float* __restrict__ w_max,
+                                                            const float* __restrict__ alpha,
+                                                            const float* __restrict__ beta,
+                                                            const float* __restrict__ gy,
+                                                            const uint8_t* __restrict__ idx,
+                                                            float* __restrict__ grad_w_min,
+                                                            float* __restrict__ grad_w_max,
+                                                            float* __restrict__ grad_alpha,
+                                                            float* __restrict__ grad_beta, int n_per_block) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int NBR = TWO ? 2 : 1;
+  constexpr int NT = 256, PITCH = NT + 1;
+  HIP_DYNAMIC_SHARED(float, bins)  // [NBR * (KK + 1)][PITCH]
+  const int KK = p.KH * p.KW;
+  const int rows = NBR * (KK + 1);
+  const int co = blockIdx.x, c = co / mult;
+  const int n0 = blockIdx.y * n_per_block;
+  const int n1 = min(n0 + n_per_block, p.N);
+  const int tid = threadIdx.x;
+  for (int rw = 0; rw < rows; ++rw) bins[rw * PITCH + tid] = 0.f;
+  const bool want_coef = TWO && (grad_alpha || grad_beta);
+  const int plane = p.Ho * p.Wo;
+  const long long cnt = (long long)(n1 - n0) * plane;
+  for (long long e = tid; e < cnt; e += NT) {
+    const int n = n0 + (int)(e / plane);
+    const int pix = (int)(e % plane);
+    const size_t o = ((size_t)n * p.C_out + co) * plane + pix;
+    const float g = gy[o];
+    const int code = idx[o];
+    const int oh = pix / p.Wo, ow = pix - oh * p.Wo;
+    const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * p.H * p.W : nullptr;
+    if (DO_MIN) {
+      const int t = min(code & 15, KK - 1);
+      bins[t * PITCH + tid] += g;
+      if (want_coef) {
+        const float m = __fadd_rn(xp[winner_offset(p, oh, ow, t)], w_min[(size_t)co * KK + min(t, KK - 1)]);
+        bins[KK * PITCH + tid] += g * m;
+      }
+    }
+    if (DO_MAX) {
+      const int t = min(code >> 4, KK - 1);
+      const int base = (NBR - 1) * (KK + 1);
+      bins[(base + t) * PITCH + tid] += g;
+      if (want_coef) {
+        const float M = __fadd_rn(xp[winner_offset(p, oh, ow, t)], w_max[(size_t)co * KK + min(t, KK - 1)]);
+        bins[(base + KK) * PITCH + tid] += g * M;
+      }
+    }
+  }
+  __syncthreads();
+  // one thread per row adds the 256 partial sums in double and issues the atomic
+  if (tid < rows) {
+    double s = 0.0;
+    for (int k = 0; k < NT; ++k) s += (double)bins[tid * PITCH + k];
+    const int br = tid / (KK + 1), k = tid - br * (KK + 1);
+    const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+    if (k < KK) {
+      const float coef = !TWO ? 1.f : (is_max ? (beta ? beta[co] : 1.f) : (alpha ? alpha[co] : 1.f));
+      float* gw = is_max ? grad_w_max : grad_w_min;
+      if (gw) atomicAdd(gw + (size_t)co * KK + k, (float)((double)coef * s));
+    } else if (TWO) {
+      float* gc = is_max ? grad_beta : grad_alpha;
+      if (gc) atomicAdd(gc + co, (float)s);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void dw_fill_zero_kernel(float* __restrict__ p, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+void zero_fill(float* p, size_t n, hipStream_t s) {  // a kernel, so that the call can sit in a captured graph
+  if (!p || n == 0) return;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(dw_fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+}
+
+bool force_generic() {
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  return e && strcmp(e, "generic") == 0;
+}
+
+// widest tile (a multiple of 4 columns, at most 32) that a row of `width` pixels fills reasonably
+int tile_width(int width) { return width > 16 ? 32 : (width > 8 ? 16 : 8); }
+
+bool fwd_tiled_ok(const Params& p) {
+  if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1) return false;
+  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+  return p.Wo >= 8;
+}
+
+bool bwd_x_tiled_ok(const Params& p) {
+  return p.KH == 3 && p.KW == 3 && p.dh == 1 && p.dw == 1 && p.sh == 1 && p.sw == 1 && p.W >= 8;
+}
+
+template <int MODE, int S, int TW>
+hipError_t launch_fwd_tile(const Params& p, int mult, const DwArgs& a, hipStream_t s) {
+  constexpr int TH = 64 / (TW / 4);
+  const int tiles_w = (p.Wo + TW - 1) / TW, tiles_h = (p.Ho + TH - 1) / TH;
+  const long long n_items = (long long)p.N * p.C_out * tiles_w * tiles_h;
+  const long long blocks = (n_items + WAVES - 1) / WAVES;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (a.idx)
+    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, true>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
+                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, n_items);
+  else
+    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, false>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
+                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, n_items);
+  return hipGetLastError();
+}
+
+template <int MODE, int S>
+hipError_t launch_fwd_s(const Params& p, int mult, const DwArgs& a, hipStream_t s) {
+  switch (tile_width(p.Wo)) {
+    case 32: return launch_fwd_tile<MODE, S, 32>(p, mult, a, s);
+    case 16: return launch_fwd_tile<MODE, S, 16>(p, mult, a, s);
+    default: return launch_fwd_tile<MODE, S, 8>(p, mult, a, s);
+  }
+}
+
+template <int MODE>
+hipError_t launch_fwd(const Params& p, const DwArgs& a, hipStream_t s) {
+  const int mult = p.C_out / p.C_in;
+  if (fwd_tiled_ok(p) && !force_generic())
+    return p.sh == 1 ? launch_fwd_s<MODE, 1>(p, mult, a, s) : launch_fwd_s<MODE, 2>(p, mult, a, s);
+  const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
+  hipLaunchKernelGGL(dw_fwd_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p, mult,
+                     a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx);
+  return hipGetLastError();
+}
+
+template <int MODE, int TW>
+hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const DwGrads& g, hipStream_t s) {
+  constexpr int TH = 64 / (TW / 4);
+  const int tiles_w = (p.W + TW - 1) / TW, tiles_h = (p.H + TH - 1) / TH;
+  const long long n_items = (long long)p.N * p.C_in * tiles_w * tiles_h;
+  const long long blocks = (n_items + WAVES - 1) / WAVES;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p, mult,
+                     g.gy, a.idx, a.alpha, a.beta, g.grad_x, tiles_w, tiles_h, n_items);
+  return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t launch_bwd(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s) {
+  const int mult = p.C_out / p.C_in, KK = p.KH * p.KW;
+  if (g.grad_x) {
+    hipError_t e;
+    if (bwd_x_tiled_ok(p) && !force_generic()) {
+      switch (tile_width(p.W)) {
+        case 32: e = launch_bwd_x_tile<MODE, 32>(p, mult, a, g, s); break;
+        case 16: e = launch_bwd_x_tile<MODE, 16>(p, mult, a, g, s); break;
+        default: e = launch_bwd_x_tile<MODE, 8>(p, mult, a, g, s); break;
+      }
+    } else {
+      const size_t total = (size_t)p.N * p.C_in * p.H * p.W;
+      hipLaunchKernelGGL(dw_bwd_x_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p,
+                         mult, g.gy, a.idx, a.alpha, a.beta, g.grad_x);
+      e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
+  }
+  float* gmin = g.grad_w_min;
+  float* gmax = g.grad_w_max;
+  if (MODE == TCONV_COMPOUND) gmin = gmax = (g.grad_w_min ? g.grad_w_min : g.grad_w_max);
+  const bool want = (MODE != TCONV_MAX && gmin) || (MODE != TCONV_MIN && gmax) || g.grad_alpha || g.grad_beta;
+  if (want) {
+    const size_t nw = (size_t)p.C_out * KK;
+    if (MODE != TCONV_MAX) zero_fill(gmin, nw, s);
+    if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(gmax, nw, s);
+    zero_fill(g.grad_alpha, (size_t)p.C_out, s);
+    zero_fill(g.grad_beta, (size_t)p.C_out, s);
+    int slices = (2048 + p.C_out - 1) / p.C_out;  // enough workgroups to fill the chip
+    if (slices > p.N) slices = p.N;
+    if (slices > 65535) slices = 65535;
+    const int n_per_block = (p.N + slices - 1) / slices;
+    const dim3 grid((unsigned)p.C_out, (unsigned)((p.N + n_per_block - 1) / n_per_block));
+    constexpr int NBR = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) ? 2 : 1;
+    const size_t lds = (size_t)NBR * (KK + 1) * 257 * sizeof(float);
+    hipLaunchKernelGGL(dw_bwd_params_kernel<MODE>, grid, dim3(256), lds, s, p, mult, a.x, a.w_min, a.w_max, a.alpha,
+                       a.beta, g.gy, a.idx, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_depthwise_forward(const Params& p, const DwArgs& a, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_fwd<TCONV_MAX>(p, a, s);
+    case TCONV_MIN: return launch_fwd<TCONV_MIN>(p, a, s);
+    case TCONV_COMPOUND: return launch_fwd<TCONV_COMPOUND>(p, a, s);
+    default: return launch_fwd<TCONV_PARALLEL>(p, a, s);
+  }
+}
+
+hipError_t launch_depthwise_backward(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_bwd<TCONV_MAX>(p, a, g, s);
+    case TCONV_MIN: return launch_bwd<TCONV_MIN>(p, a, g, s);
+    case TCONV_COMPOUND: return launch_bwd<TCONV_COMPOUND>(p, a, g, s);
+    default: return launch_bwd<TCONV_PARALLEL>(p, a, g, s);
+  }
+}
+
+const char* depthwise_forward_kernel_name(const Params& p) {
+  return (fwd_tiled_ok(p) && !force_generic()) ? "dw_tiled3x3" : "dw_generic";
+}
+
+}  // namespace tconv

@@ -162,3 +162,50 @@ def make_inputs(cfg: LayerCfg, alpha_beta: Optional[str] = None, integer: bool =
     else:
         w_min, w_max = w1, w2
     return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)
+
+
+# Depthwise layers: the 3x3 depthwise layers of a MobileNetV2 on 32x32 inputs (expansion 6, stride-1
+# "custom" configuration of the paper's CIFAR runs) have 96 - 960 channels on 32x32 ... 4x4 maps.
+DW_CONFIGS: Dict[str, LayerCfg] = {c.name: c for c in [
+    LayerCfg("dw_small", 2, 6, 16, 16, 6, mode="compound", seed=60, w_range=1.0),
+    LayerCfg("dw_main", 128, 192, 32, 32, 192, mode="compound", seed=61, w_range=0.1),
+    LayerCfg("dw_s2", 128, 192, 32, 32, 192, stride=2, mode="compound", seed=62, w_range=0.1),
+    LayerCfg("dw_16", 128, 384, 16, 16, 384, mode="compound", seed=63, w_range=0.1),
+    LayerCfg("dw_8", 128, 576, 8, 8, 576, mode="compound", seed=64, w_range=0.1),
+]}
+
+
+def make_depthwise_inputs(cfg: LayerCfg, coef: Optional[str] = "random", integer: bool = False):
+    """x [N, C_in, H, W], w_min / w_max [C_out, 1, KH, KW] (as make_inputs assigns them to the modes), gy,
+    alpha / beta [C_out] (coef: None -> NULL, "random" -> U(-1, 1), "integer" -> small integers) for a
+    depthwise layer with C_out = mult * C_in."""
+    assert cfg.C_out % cfg.C_in == 0
+    rng = np.random.Generator(np.random.PCG64(cfg.seed))
+    ho, wo = cfg.out_hw
+    xs, ws = (cfg.N, cfg.C_in, cfg.H, cfg.W), (cfg.C_out, 1, cfg.KH, cfg.KW)
+    if integer:
+        draw_x = lambda: rng.integers(-4, 5, size=xs).astype(np.float32)
+        draw_w = lambda: rng.integers(-4, 5, size=ws).astype(np.float32)
+    else:
+        draw_x = lambda: rng.standard_normal(size=xs, dtype=np.float32)
+        draw_w = lambda: ((rng.random(size=ws, dtype=np.float32) * 2 - 1) * np.float32(cfg.w_range)).astype(np.float32)
+    x, w1 = _no_neg_zero(draw_x()), _no_neg_zero(draw_w())
+    w2 = _no_neg_zero(draw_w()) if cfg.mode == "parallel" else None
+    gy = rng.standard_normal(size=(cfg.N, cfg.C_out, ho, wo), dtype=np.float32)
+    alpha = beta = None
+    if coef is not None and cfg.mode in ("compound", "parallel"):
+        if coef == "integer":
+            alpha = rng.integers(-2, 3, cfg.C_out).astype(np.float32)
+            beta = rng.integers(-2, 3, cfg.C_out).astype(np.float32)
+        else:
+            alpha = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+            beta = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+    if cfg.mode == "max":
+        w_min, w_max = None, w1
+    elif cfg.mode == "min":
+        w_min, w_max = w1, None
+    elif cfg.mode == "compound":
+        w_min = w_max = w1
+    else:
+        w_min, w_max = w1, w2
+    return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)

@@ -226,3 +226,72 @@ def assert_sum_close(hip, ref, what=""):
         if ref.get(k) is None:
             continue
         assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+
+
+# ---------------------------------------------------------------- depthwise layers
+
+def run_oracle_dw(cfg, inp, backward=True):
+    from oracle import tdw_oracle as odw
+    s = oracle_shape(cfg)
+    a, b = inp["alpha"], inp["beta"]
+    y, tmin, tmax = odw.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], a, b, taps=True)
+    r = dict(y=y, tap_min=tmin, tap_max=tmax)
+    if backward:
+        r.update(odw.backward(s, cfg.mode, inp["x"], inp["gy"], inp["w_min"], inp["w_max"], a, b))
+        ab = [None if v is None else np.abs(v) for v in (a, b)]
+        sc = odw.backward(s, cfg.mode, inp["x"], np.abs(inp["gy"]), inp["w_min"], inp["w_max"], ab[0], ab[1])
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+        if r["grad_alpha"] is not None:
+            wmax = max(np.abs(v).max() for v in (inp["w_min"], inp["w_max"]) if v is not None)
+            bound = np.abs(inp["gy"]).astype(np.float64).sum(axis=(0, 2, 3)) * float(np.abs(inp["x"]).max() + wmax)
+            r["grad_alpha_scale"] = r["grad_beta_scale"] = bound
+    return r
+
+
+def run_hip_dw(cfg, inp, backward=True, save_idx=True, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    d = tb.Desc.from_cfg(cfg)
+    ho, wo = tb.tconv_out_shape(d)
+
+    def up(a):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    x, gy, al, be = up(inp["x"]), up(inp["gy"]), up(inp["alpha"]), up(inp["beta"])
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"])
+    else:
+        w_min, w_max = up(inp["w_min"]), up(inp["w_max"])
+    oshape = (cfg.N, cfg.C_out, ho, wo)
+    y = torch.full(oshape, float("nan"), device=dev)
+    idx = torch.full(oshape, 0xEE, device=dev, dtype=torch.uint8) if save_idx else None
+    tb.tconv_depthwise_forward(d, x, w_min, w_max, al, be, y, idx)
+    out = dict(y=y, idx=idx)
+    if backward:
+        two = cfg.mode in ("compound", "parallel")
+        nan = lambda shape: torch.full(shape, float("nan"), device=dev)
+        wshape = (cfg.C_out, 1, cfg.KH, cfg.KW)
+        gx = nan((cfg.N, cfg.C_in, cfg.H, cfg.W))
+        g1 = nan(wshape) if cfg.mode != "max" else None
+        g2 = nan(wshape) if cfg.mode in ("max", "parallel") else None
+        ga = nan((cfg.C_out,)) if two else None
+        gb = nan((cfg.C_out,)) if two else None
+        tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, gx, g1, g2, ga, gb)
+        out.update(grad_x=gx, grad_w_min=g1, grad_w_max=g2, grad_alpha=ga, grad_beta=gb)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+def assert_dw_close(hip, ref, mode, what="", backward=True):
+    assert_forward_bit_exact(hip, ref, keys=("y",), what=what)
+    if hip.get("idx") is not None:   # both winners in one byte: low nibble min-plus tap, high nibble max-plus tap
+        if mode != "max":
+            assert np.array_equal(hip["idx"] & 15, ref["tap_min"]), what + "min-plus winners"
+        if mode != "min":
+            assert np.array_equal(hip["idx"] >> 4, ref["tap_max"]), what + "max-plus winners"
+    if backward:
+        for k in ("grad_x", "grad_w_min", "grad_w_max", "grad_alpha", "grad_beta"):
+            if ref.get(k) is None:
+                continue
+            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)

@@ -1,0 +1,120 @@
+"""GPU parity of the depthwise layers (tconv_depthwise_forward / tconv_depthwise_backward) against their CPU
+oracle: outputs and winning taps bit for bit, gradients within 1e-5 of the size of their summands."""
+import os
+
+import numpy as np
+import pytest
+
+import harness as hs
+from paper_2504_06881_amd import binding as tb
+from paper_2504_06881_amd.inputs import DW_CONFIGS, LayerCfg, make_depthwise_inputs
+
+pytestmark = pytest.mark.gpu
+MODES = ["max", "min", "compound", "parallel"]
+
+
+def _check(cfg, coef="random", integer=False, kernel=None):
+    inp = make_depthwise_inputs(cfg, coef="integer" if (integer and coef) else coef, integer=integer)
+    ref = hs.run_oracle_dw(cfg, inp)
+    old = os.environ.pop("TCONV_FORWARD_KERNEL", None)
+    try:
+        if kernel:
+            os.environ["TCONV_FORWARD_KERNEL"] = kernel
+        hip = hs.run_hip_dw(cfg, inp)
+    finally:
+        os.environ.pop("TCONV_FORWARD_KERNEL", None)
+        if old is not None:
+            os.environ["TCONV_FORWARD_KERNEL"] = old
+    hs.assert_dw_close(hip, ref, cfg.mode, what=f"[dw {cfg.name} {cfg.mode} coef={coef} int={integer} k={kernel}] ")
+
+
+# C_out = mult * C_in; widths that are not multiples of 4 or of a tile, heights that leave idle tile rows,
+# strides, paddings 0 / 1 / 2, dilation and non-3x3 windows (generic kernels), tiny maps
+SHAPES = [
+    LayerCfg("d_16", 2, 3, 16, 16, 3, seed=70),
+    LayerCfg("d_m2", 1, 2, 19, 23, 4, seed=71),
+    LayerCfg("d_w40", 2, 2, 17, 40, 2, seed=72),
+    LayerCfg("d_s2", 1, 3, 21, 27, 3, stride=2, seed=73),
+    LayerCfg("d_s2_32", 2, 2, 32, 32, 4, stride=2, seed=74),
+    LayerCfg("d_8", 3, 5, 8, 8, 5, seed=75),
+    LayerCfg("d_w33", 1, 2, 9, 33, 2, seed=76),
+    LayerCfg("d_p0", 1, 1, 12, 20, 1, pad=0, seed=77),
+    LayerCfg("d_p2", 1, 2, 10, 13, 2, pad=2, seed=78),
+    LayerCfg("d_d2", 1, 2, 18, 26, 2, pad=2, dil=2, seed=79),
+    LayerCfg("d_4x4win", 1, 2, 9, 10, 4, KH=4, KW=4, pad=1, seed=80),
+    LayerCfg("d_2x3win", 2, 2, 9, 10, 2, KH=2, KW=3, pad=1, seed=81),
+    LayerCfg("d_7", 2, 3, 7, 7, 3, seed=82),
+    LayerCfg("d_4", 2, 6, 4, 4, 6, seed=83),
+    LayerCfg("d_one", 1, 1, 1, 1, 1, seed=84),
+    LayerCfg("d_tall", 1, 2, 70, 9, 2, stride=2, seed=85),
+    LayerCfg("d_wide_s2", 1, 1, 11, 66, 1, stride=2, seed=86),
+    LayerCfg("d_h40", 1, 2, 40, 12, 2, seed=87),
+]
+
+
+@pytest.mark.parametrize("cfg", SHAPES, ids=lambda c: c.name)
+def test_depthwise_layers(cfg):
+    for mode in MODES:
+        _check(cfg.with_(mode=mode))
+        _check(cfg.with_(mode=mode), integer=True)      # ties everywhere: lowest tap
+    _check(cfg.with_(mode="parallel"), coef=None)
+
+
+@pytest.mark.parametrize("cfg", [SHAPES[0], SHAPES[1], SHAPES[3]], ids=lambda c: c.name)
+def test_generic_kernels(cfg):
+    for mode in MODES:
+        _check(cfg.with_(mode=mode), kernel="generic")
+    _check(cfg.with_(mode="compound"), integer=True, kernel="generic")
+
+
+@pytest.mark.parametrize("name", ["dw_main", "dw_s2", "dw_8"])
+def test_full_size_layers(name):
+    cfg = DW_CONFIGS[name]
+    print(f"[dw full] {name}", flush=True)
+    _check(cfg)
+
+
+def test_inference_without_indices_and_partial_gradients():
+    import torch
+    cfg = SHAPES[1].with_(mode="parallel")
+    inp = make_depthwise_inputs(cfg)
+    ref = hs.run_oracle_dw(cfg, inp)
+    hip = hs.run_hip_dw(cfg, inp, backward=False, save_idx=False)
+    hs.assert_forward_bit_exact(hip, ref, keys=("y",))
+    # grad_x alone needs neither x nor the kernels
+    full = hs.run_hip_dw(cfg, inp)
+    dev = torch.device("cuda:0")
+    d = tb.Desc.from_cfg(cfg)
+    gx = torch.full((cfg.N, cfg.C_in, cfg.H, cfg.W), float("nan"), device=dev)
+    tb.tconv_depthwise_backward(d, None, None, None, torch.from_numpy(inp["alpha"]).to(dev),
+                                torch.from_numpy(inp["beta"]).to(dev), torch.from_numpy(inp["gy"]).to(dev),
+                                torch.from_numpy(full["idx"]).to(dev), gx, None, None, None, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(gx.cpu().numpy(), full["grad_x"])
+
+
+def test_error_paths():
+    import torch
+    z = torch.zeros(64, device="cuda")
+    zb = torch.zeros(64, device="cuda", dtype=torch.uint8)
+    d = tb.Desc(1, 2, 4, 4, 3, 3, 3, pad=(1, 1), mode="max")
+    with pytest.raises(tb.TconvError) as e:   # C_out not a multiple of C_in
+        tb.tconv_depthwise_forward(d, z, None, z, None, None, z, zb)
+    assert e.value.status == -2
+    d = tb.Desc(1, 2, 4, 4, 2, 5, 5, pad=(2, 2), mode="max")
+    with pytest.raises(tb.TconvError) as e:   # 25 taps do not fit a nibble
+        tb.tconv_depthwise_forward(d, z, None, z, None, None, z, zb)
+    assert e.value.status == -4
+    tb.tconv_depthwise_forward(d, z, None, z, None, None, z, None)   # without indices it is fine
+    d = tb.Desc(1, 2, 4, 4, 2, 3, 3, pad=(1, 1), mode="compound")
+    with pytest.raises(tb.TconvError) as e:   # backward needs the indices
+        tb.tconv_depthwise_backward(d, z, z, z, None, None, z, None, z, None, None, None, None)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:   # coefficient gradients need x
+        tb.tconv_depthwise_backward(d, None, z, z, None, None, z, zb, None, None, None, z, z)
+    assert e.value.status == -1
+    with pytest.raises(tb.TconvError) as e:   # no minimax depthwise layer
+        tb.tconv_depthwise_forward(tb.Desc(1, 2, 4, 4, 2, 3, 3, pad=(1, 1), mode="minplus_max"), z, z, None, None,
+                                   None, z, zb)
+    assert e.value.status == -1
+    torch.cuda.synchronize()
