@@ -32,6 +32,26 @@ using namespace tile;
 
 __device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7fc00000u); }
 
+typedef float f4a __attribute__((ext_vector_type(4)));  // 16-byte aligned
+typedef int i4a __attribute__((ext_vector_type(4)));
+typedef unsigned u1a __attribute__((aligned(1)));       // 4 winner bytes at any address
+
+// N consecutive floats from LDS at any 4-byte aligned address (gfx950 reads unaligned vectors from LDS)
+template <int N>
+__device__ __forceinline__ void lds_run(float* dst, const float* src) {
+  if constexpr (N >= 4) {
+    const f4u v = *(const f4u*)src;
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    lds_run<N - 4>(dst + 4, src + 4);
+  } else if constexpr (N >= 2) {
+    const f2u v = *(const f2u*)src;
+    dst[0] = v.x; dst[1] = v.y;
+    lds_run<N - 2>(dst + 2, src + 2);
+  } else if constexpr (N == 1) {
+    dst[0] = src[0];
+  }
+}
+
 // y of one output from its branch extrema
 template <int MODE>
 __device__ __forceinline__ float dw_combine(float m, float M, float a, float b) {
@@ -105,33 +125,63 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
                                                                   const float* __restrict__ alpha,
                                                                   const float* __restrict__ beta,
                                                                   float* __restrict__ y, uint8_t* __restrict__ idx,
-                                                                  int tiles_w, int tiles_h, long long n_items) {
+                                                                  int tiles_w, int tiles_h, int n_items) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr int LR = TW / 4, TH = 64 / LR;
-  constexpr int ROWS = (TH - 1) * S + 3, COLS = (TW - 1) * S + 3, PITCH = (COLS + 3) & ~3;
-  constexpr int NC = 3 * S + 3;  // input columns under a lane's 4 outputs
-  __shared__ float tile_all[WAVES][ROWS * PITCH];
+  constexpr int ROWS = (TH - 1) * S + 3, COLS = (TW - 1) * S + 3;
+  constexpr int CPR = (COLS + 3 + 3) / 4, PITCH = 4 * CPR;  // 4-float chunks per tile row (any alignment of its start)
+  constexpr int NC = 3 * S + 3;                             // input columns under a lane's 4 outputs
+  __shared__ __attribute__((aligned(16))) float tile_all[WAVES][ROWS * PITCH];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const long long item = (long long)blockIdx.x * WAVES + wave;
+  const int item = blockIdx.x * WAVES + wave;
   if (item >= n_items) return;  // whole wave; the kernel has no workgroup barrier
-  const int tw = (int)(item % tiles_w);
-  const int th = (int)((item / tiles_w) % tiles_h);
-  const long long plane = item / ((long long)tiles_w * tiles_h);  // n * C_out + co
-  const int co = (int)(plane % p.C_out);
-  const int n = (int)(plane / p.C_out);
+  const int tw = item % tiles_w;
+  const int th = (item / tiles_w) % tiles_h;
+  const int plane = item / (tiles_w * tiles_h);  // n * C_out + co
+  const int co = plane % p.C_out;
+  const int n = plane / p.C_out;
   const int own_w = tw * TW;
   const int org_w = min(own_w, max(p.Wo - TW, 0));
   const int oh0 = th * TH;
   const float* xp = x + ((size_t)n * p.C_in + co / mult) * p.H * p.W;
   const int ih_base = oh0 * S - p.ph, iw_base = org_w * S - p.pw;
   float* const t = tile_all[wave];
-  for (int e = lane; e < ROWS * COLS; e += 64) {
-    const int r = e / COLS, cc = e - r * COLS;
-    const int ih = ih_base + r, iw = iw_base + cc;
-    float v = quiet_nan();
-    if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) v = xp[(size_t)ih * p.W + iw];
-    t[r * PITCH + cc] = v;
+  // The tile is fetched in 4-float chunks that start at multiples of 4 in plane columns (tile column 0 is
+  // plane column cbase), so a chunk is left of the plane, right of it, inside it, or hangs over the row end
+  // by the same dd = (4 - W % 4) % 4 columns everywhere; that last kind is loaded from W - 4 and shifted.
+  // All loads are issued before any is consumed: one memory latency per tile.
+  const int cbase = (iw_base < 0) ? -4 : (iw_base & ~3);
+  const int dd = (4 - (p.W & 3)) & 3;
+  constexpr int NCH = ROWS * CPR, NIT = (NCH + 63) / 64;
+  f4u stage[NIT];
+#pragma unroll
+  for (int k = 0; k < NIT; ++k) {
+    const int e = min(lane + 64 * k, NCH - 1);
+    const int r = e / CPR, q = e - r * CPR;
+    const int ih = min(max(ih_base + r, 0), p.H - 1);
+    const int start = min(max(cbase + 4 * q, 0), p.W - 4);
+    stage[k] = *(const f4u*)(xp + (size_t)ih * p.W + start);
+  }
+#pragma unroll
+  for (int k = 0; k < NIT; ++k) {
+    const int e = lane + 64 * k;
+    const int r = e / CPR, q = e - r * CPR;
+    const int ih = ih_base + r, c0 = cbase + 4 * q;
+    const bool row_ok = (ih >= 0 && ih < p.H);
+    f4u v = stage[k];
+    if (dd != 0 && c0 + 4 > p.W) {  // hangs over the row end (or lies beyond it: then nothing of it is kept)
+      const f4u u = v;
+      if (dd == 1) { v.x = u.y; v.y = u.z; v.z = u.w; }
+      else if (dd == 2) { v.x = u.z; v.y = u.w; }
+      else { v.x = u.w; }
+    }
+    f4a o;
+    o.x = (row_ok && c0 >= 0 && c0 < p.W) ? v.x : quiet_nan();
+    o.y = (row_ok && c0 >= 0 && c0 + 1 < p.W) ? v.y : quiet_nan();
+    o.z = (row_ok && c0 >= 0 && c0 + 2 < p.W) ? v.z : quiet_nan();
+    o.w = (row_ok && c0 >= 0 && c0 + 3 < p.W) ? v.w : quiet_nan();
+    if (e < NCH) *(f4a*)&t[r * PITCH + 4 * q] = o;
   }
   wave_lds_fence();
 
@@ -142,13 +192,11 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
   const int ow0 = min(nominal, p.Wo - 4);   // first column it computes
   const int first_q = lo - ow0;             // >= 4: nothing to store
   const bool act = (oh < p.Ho) && (first_q < 4);
-  const int lc = (ow0 - org_w) * S;
+  const int lc = ow0 * S - p.pw - cbase;  // tile column of the first input column under this lane
 
   float xs[3][NC];
 #pragma unroll
-  for (int i = 0; i < 3; ++i)
-#pragma unroll
-    for (int k = 0; k < NC; ++k) xs[i][k] = t[(r * S + i) * PITCH + lc + k];
+  for (int i = 0; i < 3; ++i) lds_run<NC>(xs[i], &t[(r * S + i) * PITCH + lc]);
 
   float wa[9], wb[9];
 #pragma unroll
@@ -265,22 +313,23 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
                                                                     const float* __restrict__ alpha,
                                                                     const float* __restrict__ beta,
                                                                     float* __restrict__ grad_x, int tiles_w,
-                                                                    int tiles_h, long long n_items) {
+                                                                    int tiles_h, int n_items) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int LR = TW / 4, TH = 64 / LR;
-  constexpr int ROWS = TH + 2, COLS = TW + 2, PITCH = (COLS + 3) & ~3;
-  __shared__ float g_all[WAVES][ROWS * PITCH];
-  __shared__ int c_all[WAVES][ROWS * PITCH];
+  constexpr int ROWS = TH + 2, COLS = TW + 2;
+  constexpr int CPR = (COLS + 3 + 3) / 4, PITCH = 4 * CPR;  // 4-element chunks per tile row, as in the forward kernel
+  __shared__ __attribute__((aligned(16))) float g_all[WAVES][ROWS * PITCH];
+  __shared__ __attribute__((aligned(16))) int c_all[WAVES][ROWS * PITCH];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const long long item = (long long)blockIdx.x * WAVES + wave;
+  const int item = blockIdx.x * WAVES + wave;
   if (item >= n_items) return;  // whole wave; no workgroup barrier
-  const int tw = (int)(item % tiles_w);
-  const int th = (int)((item / tiles_w) % tiles_h);
-  const long long plane = item / ((long long)tiles_w * tiles_h);  // n * C_in + c
-  const int c = (int)(plane % p.C_in);
-  const int n = (int)(plane / p.C_in);
+  const int tw = item % tiles_w;
+  const int th = (item / tiles_w) % tiles_h;
+  const int plane = item / (tiles_w * tiles_h);  // n * C_in + c
+  const int c = plane % p.C_in;
+  const int n = plane / p.C_in;
   const int own_w = tw * TW;
   const int org_w = min(own_w, max(p.W - TW, 0));
   const int ih0 = th * TH;
@@ -294,28 +343,60 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
   const int iw0 = min(nominal, p.W - 4);
   const int first_q = lo - iw0;
   const bool act = (ih < p.H) && (first_q < 4);
-  const int lc = iw0 - org_w;
 
-  // tile row rr holds output row ih0 + ph - 2 + rr, tile column cc output column org_w + pw - 2 + cc;
-  // input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
+  // tile row rr holds output row oh_base + rr, tile column cc output column cbase + cc (cbase a multiple of
+  // 4, or -4); input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
   const int oh_base = ih0 + p.ph - 2, ow_base = org_w + p.pw - 2;
+  const int cbase = (ow_base < 0) ? -4 : (ow_base & ~3);
+  const int dd = (4 - (p.Wo & 3)) & 3;
+  const int lc = iw0 + p.pw - 2 - cbase;  // tile column of output column iw0 + pw - 2
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int mm = 0; mm < mult; ++mm) {
     const int co = c * mult + mm;
     const size_t pb = ((size_t)n * p.C_out + co) * p.Ho * p.Wo;
     wave_lds_fence();  // every lane is done with the tiles of the previous output channel
-    for (int e = lane; e < ROWS * COLS; e += 64) {
-      const int rr = e / COLS, cc = e - rr * COLS;
-      const int oh = oh_base + rr, ow = ow_base + cc;
-      float g = 0.f;
-      int code = 0xff;
-      if (oh >= 0 && oh < p.Ho && ow >= 0 && ow < p.Wo) {
-        const size_t o = pb + (size_t)oh * p.Wo + ow;
-        g = gy[o];
-        code = idx[o];
+    // chunks of 4 outputs (16 bytes of gy, 4 bytes of winners), all in flight before the first LDS write; a
+    // chunk that hangs over the row end is loaded from Wo - 4 and shifted by dd
+    constexpr int NCH = ROWS * CPR, NIT = (NCH + 63) / 64;
+    f4u sg[NIT];
+    unsigned sc[NIT];
+#pragma unroll
+    for (int k = 0; k < NIT; ++k) {
+      const int e = min(lane + 64 * k, NCH - 1);
+      const int rr = e / CPR, q = e - rr * CPR;
+      const int oh = min(max(oh_base + rr, 0), p.Ho - 1);
+      const int start = min(max(cbase + 4 * q, 0), p.Wo - 4);
+      const size_t o = pb + (size_t)oh * p.Wo + start;
+      sg[k] = *(const f4u*)(gy + o);
+      sc[k] = *(const u1a*)(idx + o);
+    }
+#pragma unroll
+    for (int k = 0; k < NIT; ++k) {
+      const int e = lane + 64 * k;
+      const int rr = e / CPR, q = e - rr * CPR;
+      const int oh = oh_base + rr, c0 = cbase + 4 * q;
+      const bool row_ok = (oh >= 0 && oh < p.Ho);
+      f4u v = sg[k];
+      unsigned cw = sc[k];
+      if (dd != 0 && c0 + 4 > p.Wo) {
+        const f4u u = v;
+        if (dd == 1) { v.x = u.y; v.y = u.z; v.z = u.w; }
+        else if (dd == 2) { v.x = u.z; v.y = u.w; }
+        else { v.x = u.w; }
+        cw >>= 8 * dd;
       }
-      gt[rr * PITCH + cc] = g;
-      ct[rr * PITCH + cc] = code;
+      const bool k0 = row_ok && c0 >= 0 && c0 < p.Wo, k1 = row_ok && c0 >= 0 && c0 + 1 < p.Wo;
+      const bool k2 = row_ok && c0 >= 0 && c0 + 2 < p.Wo, k3 = row_ok && c0 >= 0 && c0 + 3 < p.Wo;
+      f4a go;
+      i4a co4;
+      go.x = k0 ? v.x : 0.f; co4.x = k0 ? (int)(cw & 0xffu) : 0xff;   // 0xff: a code no tap matches
+      go.y = k1 ? v.y : 0.f; co4.y = k1 ? (int)((cw >> 8) & 0xffu) : 0xff;
+      go.z = k2 ? v.z : 0.f; co4.z = k2 ? (int)((cw >> 16) & 0xffu) : 0xff;
+      go.w = k3 ? v.w : 0.f; co4.w = k3 ? (int)(cw >> 24) : 0xff;
+      if (e < NCH) {
+        *(f4a*)&gt[rr * PITCH + 4 * q] = go;
+        *(i4a*)&ct[rr * PITCH + 4 * q] = co4;
+      }
     }
     wave_lds_fence();
     const float a = (TWO && alpha) ? alpha[co] : 1.f, b = (TWO && beta) ? beta[co] : 1.f;
@@ -324,20 +405,22 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
       // outputs of tile row r + 2 - i, columns lc + q + 2 - j for q = 0..3, j = 0..2: lc .. lc + 5
       float g6[6];
       int c6[6];
+      lds_run<6>(g6, &gt[(r + 2 - i) * PITCH + lc]);
+      lds_run<6>((float*)c6, (const float*)&ct[(r + 2 - i) * PITCH + lc]);
+      float ag[6], bg[6];
+      int cmn[6], cmx[6];
 #pragma unroll
       for (int k = 0; k < 6; ++k) {
-        g6[k] = gt[(r + 2 - i) * PITCH + lc + k];
-        c6[k] = ct[(r + 2 - i) * PITCH + lc + k];
+        ag[k] = a * g6[k]; bg[k] = b * g6[k];
+        cmn[k] = c6[k] & 15; cmx[k] = c6[k] >> 4;
       }
 #pragma unroll
       for (int j = 0; j < 3; ++j) {
         const int t = i * 3 + j;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const float g = g6[q + 2 - j];
-          const int code = c6[q + 2 - j];
-          if (DO_MIN) acc[q] += ((code & 15) == t) ? a * g : 0.f;
-          if (DO_MAX) acc[q] += ((code >> 4) == t) ? b * g : 0.f;
+          if (DO_MIN) acc[q] += (cmn[q + 2 - j] == t) ? ag[q + 2 - j] : 0.f;
+          if (DO_MAX) acc[q] += (cmx[q + 2 - j] == t) ? bg[q + 2 - j] : 0.f;
         }
       }
     }
@@ -348,20 +431,14 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
 
 // ------------------------------------------------------------------------------------------ parameter gradients
 
-// Offset, inside its input plane, of the pixel that tap t of output (oh, ow) reads.  A winner written by the
-// forward pass is always inside the plane; the clamps only keep a corrupted index tensor from reading
-// out of bounds.
-__device__ __forceinline__ size_t winner_offset(const Params& p, int oh, int ow, int t) {
-  const int i = min(t / p.KW, p.KH - 1), j = t - (t / p.KW) * p.KW;
-  const int ih = min(max(oh * p.sh - p.ph + i * p.dh, 0), p.H - 1);
-  const int iw = min(max(ow * p.sw - p.pw + j * p.dw, 0), p.W - 1);
-  return (size_t)ih * p.W + iw;
-}
-
-// grad_w_b[co, t] = coef_b * sum of gy over the outputs of channel co whose branch-b winner is tap t;
-// grad_alpha[co] = sum gy * m, grad_beta[co] = sum gy * M with m, M re-evaluated at the winner.
+// grad_w_b[co, t] = coef_b * S_b[t], S_b[t] = sum of gy over the outputs of channel co whose branch-b winner is
+// tap t; grad_alpha[co] = sum gy * m and grad_beta[co] = sum gy * M, where the branch output at the winner
+// is x[winner] + w[t], so the sum splits into sum gy * x[winner] plus sum over t of w[t] * S_b[t] (the
+// second part comes from the tap sums; the split differs from the rounded x + w by one rounding per term).
 // Workgroup = (output channel, slice of the batch).  Every thread keeps its own column of partial sums in
-// LDS (bins[row][thread], no conflicts), rows: KK taps per branch, then one per coefficient gradient.
+// LDS (bins[row][thread]: no conflicts, no atomics), rows: KK taps per branch, then one for sum gy * x.
+// A thread takes 4 consecutive outputs per trip (one 16-byte and one 4-byte load) and fetches the next
+// trip's operands before it works on the current ones.
 template <int MODE>
 __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, const float* __restrict__ x,
                                                             const float* __restrict__ w_min,
@@ -378,57 +455,106 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NBR = TWO ? 2 : 1;
   constexpr int NT = 256, PITCH = NT + 1;
-  HIP_DYNAMIC_SHARED(float, bins)  // [NBR * (KK + 1)][PITCH]
+  HIP_DYNAMIC_SHARED(float, bins)  // [NBR * (KK + 1)][PITCH], then int toff[16]
   const int KK = p.KH * p.KW;
   const int rows = NBR * (KK + 1);
+  int* const toff = (int*)(bins + rows * PITCH);  // offset of tap t from the window's first input pixel
   const int co = blockIdx.x, c = co / mult;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
   const int tid = threadIdx.x;
+  if (tid < 16) {
+    const int t = min(tid, KK - 1), i = t / p.KW, j = t - i * p.KW;
+    toff[tid] = i * p.dh * p.W + j * p.dw;
+  }
   for (int rw = 0; rw < rows; ++rw) bins[rw * PITCH + tid] = 0.f;
+  __syncthreads();
   const bool want_coef = TWO && (grad_alpha || grad_beta);
-  const int plane = p.Ho * p.Wo;
-  const long long cnt = (long long)(n1 - n0) * plane;
-  for (long long e = tid; e < cnt; e += NT) {
-    const int n = n0 + (int)(e / plane);
-    const int pix = (int)(e % plane);
-    const size_t o = ((size_t)n * p.C_out + co) * plane + pix;
-    const float g = gy[o];
-    const int code = idx[o];
-    const int oh = pix / p.Wo, ow = pix - oh * p.Wo;
-    const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * p.H * p.W : nullptr;
+  const int plane = p.Ho * p.Wo, xplane = p.H * p.W;
+  const int ngrp = plane >> 2;                 // groups of 4 consecutive outputs inside a plane
+  const int base_max = (NBR - 1) * (KK + 1);   // first row of the max-plus branch
+  float sx_min = 0.f, sx_max = 0.f;            // sum gy * x[winner]
+
+  // one output: g, its winner byte, its position, its image's input plane
+  auto one = [&](float g, int code, int oh, int ow, const float* xp) {
+    const int first = (oh * p.sh - p.ph) * p.W + (ow * p.sw - p.pw);  // may lie in the padding; the winner does not
     if (DO_MIN) {
       const int t = min(code & 15, KK - 1);
       bins[t * PITCH + tid] += g;
-      if (want_coef) {
-        const float m = __fadd_rn(xp[winner_offset(p, oh, ow, t)], w_min[(size_t)co * KK + min(t, KK - 1)]);
-        bins[KK * PITCH + tid] += g * m;
-      }
+      if (want_coef) sx_min += g * xp[min(max(first + toff[t], 0), xplane - 1)];  // clamp: a corrupted index stays in bounds
     }
     if (DO_MAX) {
       const int t = min(code >> 4, KK - 1);
-      const int base = (NBR - 1) * (KK + 1);
-      bins[(base + t) * PITCH + tid] += g;
-      if (want_coef) {
-        const float M = __fadd_rn(xp[winner_offset(p, oh, ow, t)], w_max[(size_t)co * KK + min(t, KK - 1)]);
-        bins[(base + KK) * PITCH + tid] += g * M;
+      bins[(base_max + t) * PITCH + tid] += g;
+      if (want_coef) sx_max += g * xp[min(max(first + toff[t], 0), xplane - 1)];
+    }
+  };
+
+  if (ngrp > 0) {
+    const int total = (n1 - n0) * ngrp;  // trips of the slice, n-major
+    auto fetch = [&](int f, f4u& g4, unsigned& c4, int& n, int& pix) {
+      n = n0 + f / ngrp;
+      pix = (f - (n - n0) * ngrp) * 4;
+      const size_t o = ((size_t)n * p.C_out + co) * plane + pix;
+      g4 = *(const f4u*)(gy + o);
+      c4 = *(const u1a*)(idx + o);
+    };
+    int f = tid;
+    f4u g4 = {0.f, 0.f, 0.f, 0.f};
+    unsigned c4 = 0;
+    int n = n0, pix = 0;
+    if (f < total) fetch(f, g4, c4, n, pix);
+    while (f < total) {
+      const int fn = f + NT;
+      f4u g4n = g4;
+      unsigned c4n = c4;
+      int nn = n, pixn = pix;
+      if (fn < total) fetch(fn, g4n, c4n, nn, pixn);
+      const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
+      int oh = pix / p.Wo, ow = pix - oh * p.Wo;
+      const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        one(gs[u], (int)((c4 >> (8 * u)) & 0xffu), oh, ow, xp);
+        if (++ow == p.Wo) { ow = 0; ++oh; }
       }
+      g4 = g4n; c4 = c4n; n = nn; pix = pixn; f = fn;
     }
   }
+  // the last plane % 4 outputs of every plane
+  const int rem = plane - 4 * ngrp;
+  for (int e = tid; e < (n1 - n0) * rem; e += NT) {
+    const int n = n0 + e / rem, pix = 4 * ngrp + e % rem;
+    const size_t o = ((size_t)n * p.C_out + co) * plane + pix;
+    const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
+    one(gy[o], idx[o], pix / p.Wo, pix % p.Wo, xp);
+  }
+  if (want_coef) {
+    if (DO_MIN) bins[KK * PITCH + tid] = sx_min;
+    if (DO_MAX) bins[(base_max + KK) * PITCH + tid] = sx_max;
+  }
   __syncthreads();
-  // one thread per row adds the 256 partial sums in double and issues the atomic
+  // one thread per row adds the 256 partial sums in double; row KK of a branch becomes its coefficient sum
+  double* const tot = (double*)(((uintptr_t)(toff + 16) + 7) & ~(uintptr_t)7);  // [rows]
   if (tid < rows) {
-    double s = 0.0;
-    for (int k = 0; k < NT; ++k) s += (double)bins[tid * PITCH + k];
+    double sacc = 0.0;
+    for (int k = 0; k < NT; ++k) sacc += (double)bins[tid * PITCH + k];
+    tot[tid] = sacc;
+  }
+  __syncthreads();
+  if (tid < rows) {
     const int br = tid / (KK + 1), k = tid - br * (KK + 1);
     const bool is_max = DO_MAX && (NBR == 1 || br == 1);
     if (k < KK) {
       const float coef = !TWO ? 1.f : (is_max ? (beta ? beta[co] : 1.f) : (alpha ? alpha[co] : 1.f));
       float* gw = is_max ? grad_w_max : grad_w_min;
-      if (gw) atomicAdd(gw + (size_t)co * KK + k, (float)((double)coef * s));
-    } else if (TWO) {
+      if (gw) atomicAdd(gw + (size_t)co * KK + k, (float)((double)coef * tot[tid]));
+    } else if (want_coef) {
       float* gc = is_max ? grad_beta : grad_alpha;
-      if (gc) atomicAdd(gc + co, (float)s);
+      const float* wv = (is_max ? w_max : w_min) + (size_t)co * KK;
+      double sacc = tot[tid];
+      for (int t = 0; t < KK; ++t) sacc += (double)wv[t] * tot[br * (KK + 1) + t];
+      if (gc) atomicAdd(gc + co, (float)sacc);
     }
   }
 }
@@ -456,6 +582,7 @@ int tile_width(int width) { return width > 16 ? 32 : (width > 8 ? 16 : 8); }
 bool fwd_tiled_ok(const Params& p) {
   if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1) return false;
   if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+  if ((size_t)p.N * p.C_in * p.H * p.W * sizeof(float) >= 0xfffff000ull) return false;  // 32-bit buffer offsets
   return p.Wo >= 8;
 }
 
@@ -469,13 +596,13 @@ hipError_t launch_fwd_tile(const Params& p, int mult, const DwArgs& a, hipStream
   const int tiles_w = (p.Wo + TW - 1) / TW, tiles_h = (p.Ho + TH - 1) / TH;
   const long long n_items = (long long)p.N * p.C_out * tiles_w * tiles_h;
   const long long blocks = (n_items + WAVES - 1) / WAVES;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (n_items > 0x7fffffffLL - WAVES) return hipErrorInvalidValue;
   if (a.idx)
     hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, true>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, n_items);
+                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, (int)n_items);
   else
     hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, false>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, n_items);
+                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, (int)n_items);
   return hipGetLastError();
 }
 
@@ -505,9 +632,9 @@ hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const D
   const int tiles_w = (p.W + TW - 1) / TW, tiles_h = (p.H + TH - 1) / TH;
   const long long n_items = (long long)p.N * p.C_in * tiles_w * tiles_h;
   const long long blocks = (n_items + WAVES - 1) / WAVES;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (n_items > 0x7fffffffLL - WAVES) return hipErrorInvalidValue;
   hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p, mult,
-                     g.gy, a.idx, a.alpha, a.beta, g.grad_x, tiles_w, tiles_h, n_items);
+                     g.gy, a.idx, a.alpha, a.beta, g.grad_x, tiles_w, tiles_h, (int)n_items);
   return hipGetLastError();
 }
 
@@ -546,7 +673,7 @@ hipError_t launch_bwd(const Params& p, const DwArgs& a, const DwGrads& g, hipStr
     const int n_per_block = (p.N + slices - 1) / slices;
     const dim3 grid((unsigned)p.C_out, (unsigned)((p.N + n_per_block - 1) / n_per_block));
     constexpr int NBR = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) ? 2 : 1;
-    const size_t lds = (size_t)NBR * (KK + 1) * 257 * sizeof(float);
+    const size_t lds = (size_t)NBR * (KK + 1) * 257 * sizeof(float) + 16 * sizeof(int) + (size_t)NBR * (KK + 1) * sizeof(double) + 8;
     hipLaunchKernelGGL(dw_bwd_params_kernel<MODE>, grid, dim3(256), lds, s, p, mult, a.x, a.w_min, a.w_max, a.alpha,
                        a.beta, g.gy, a.idx, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);
   }
