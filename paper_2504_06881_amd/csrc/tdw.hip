@@ -125,7 +125,7 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
                                                                   const float* __restrict__ alpha,
                                                                   const float* __restrict__ beta,
                                                                   float* __restrict__ y, uint8_t* __restrict__ idx,
-                                                                  int tiles_w, int tiles_h, int n_items) {
+                                                                  int tiles_h, unsigned inv_tiles_h) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr int LR = TW / 4, TH = 64 / LR;
   constexpr int ROWS = (TH - 1) * S + 3, COLS = (TW - 1) * S + 3;
@@ -134,13 +134,15 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
   __shared__ __attribute__((aligned(16))) float tile_all[WAVES][ROWS * PITCH];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int item = blockIdx.x * WAVES + wave;
-  if (item >= n_items) return;  // whole wave; the kernel has no workgroup barrier
-  const int tw = item % tiles_w;
-  const int th = (item / tiles_w) % tiles_h;
-  const int plane = item / (tiles_w * tiles_h);  // n * C_out + co
-  const int co = plane % p.C_out;
-  const int n = plane / p.C_out;
+  // grid: x = tile column, y = groups of WAVES (output channel, tile row) pairs, z = image; the one split that
+  // is needed is a multiply-high (an integer division would run on the vector ALU even though it is uniform)
+  const int tw = blockIdx.x;
+  const unsigned u = blockIdx.y * WAVES + wave;
+  const int co = (int)((tiles_h == 1) ? u : __umulhi(u, inv_tiles_h));
+  const int th = (int)u - co * tiles_h;
+  if (co >= p.C_out) return;  // whole wave; the kernel has no workgroup barrier
+  const int n = blockIdx.z;
+  const int plane = n * p.C_out + co;
   const int own_w = tw * TW;
   const int org_w = min(own_w, max(p.Wo - TW, 0));
   const int oh0 = th * TH;
@@ -312,8 +314,8 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
                                                                     const uint8_t* __restrict__ idx,
                                                                     const float* __restrict__ alpha,
                                                                     const float* __restrict__ beta,
-                                                                    float* __restrict__ grad_x, int tiles_w,
-                                                                    int tiles_h, int n_items) {
+                                                                    float* __restrict__ grad_x, int tiles_h,
+                                                                    unsigned inv_tiles_h) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int LR = TW / 4, TH = 64 / LR;
@@ -323,13 +325,13 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
   __shared__ __attribute__((aligned(16))) int c_all[WAVES][ROWS * PITCH];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int item = blockIdx.x * WAVES + wave;
-  if (item >= n_items) return;  // whole wave; no workgroup barrier
-  const int tw = item % tiles_w;
-  const int th = (item / tiles_w) % tiles_h;
-  const int plane = item / (tiles_w * tiles_h);  // n * C_in + c
-  const int c = plane % p.C_in;
-  const int n = plane / p.C_in;
+  const int tw = blockIdx.x;
+  const unsigned u = blockIdx.y * WAVES + wave;  // (input channel, tile row)
+  const int c = (int)((tiles_h == 1) ? u : __umulhi(u, inv_tiles_h));
+  const int th = (int)u - c * tiles_h;
+  if (c >= p.C_in) return;  // whole wave; no workgroup barrier
+  const int n = blockIdx.z;
+  const int plane = n * p.C_in + c;
   const int own_w = tw * TW;
   const int org_w = min(own_w, max(p.W - TW, 0));
   const int ih0 = th * TH;
@@ -579,30 +581,51 @@ bool force_generic() {
 // widest tile (a multiple of 4 columns, at most 32) that a row of `width` pixels fills reasonably
 int tile_width(int width) { return width > 16 ? 32 : (width > 8 ? 16 : 8); }
 
+// Launch grid of the tiled kernels: x = tile column, y = ceil(channels * tiles_h / WAVES) (a workgroup's waves
+// take consecutive (channel, tile row) pairs), z = image.  inv_tiles_h = floor(2^32 / tiles_h) + 1 turns the
+// split of a pair number u into a multiply-high (exact while u * tiles_h < 2^32; u < 2^18 * tiles_h here).
+struct TileGrid {
+  dim3 grid;
+  unsigned inv_tiles_h;
+};
+
+TileGrid tile_grid(int tiles_w, int tiles_h, int channels, int images) {
+  TileGrid t;
+  const long long pairs = (long long)channels * tiles_h;
+  t.grid = dim3((unsigned)tiles_w, (unsigned)((pairs + WAVES - 1) / WAVES), (unsigned)images);
+  t.inv_tiles_h = tiles_h > 1 ? (unsigned)(0x100000000ull / (unsigned)tiles_h) + 1u : 0u;
+  return t;
+}
+
+// the tiled kernels put channel and image into grid dimensions y and z and address a plane with 32 bits
+bool tiled_dims_ok(const Params& p) {
+  // grid y = channels * tile rows / WAVES <= 65535; tile rows <= H / 8 + 1
+  const long long worst = ((long long)(p.C_out > p.C_in ? p.C_out : p.C_in) * (p.H / 8 + 1) + WAVES - 1) / WAVES;
+  return worst <= 65535 && p.N <= 65535 && (long long)p.H * p.W < (1 << 24) && (long long)p.N * p.C_out < 0x7fffffffLL;
+}
+
 bool fwd_tiled_ok(const Params& p) {
   if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1) return false;
   if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
-  if ((size_t)p.N * p.C_in * p.H * p.W * sizeof(float) >= 0xfffff000ull) return false;  // 32-bit buffer offsets
-  return p.Wo >= 8;
+  return tiled_dims_ok(p) && p.Wo >= 8;
 }
 
 bool bwd_x_tiled_ok(const Params& p) {
-  return p.KH == 3 && p.KW == 3 && p.dh == 1 && p.dw == 1 && p.sh == 1 && p.sw == 1 && p.W >= 8;
+  return p.KH == 3 && p.KW == 3 && p.dh == 1 && p.dw == 1 && p.sh == 1 && p.sw == 1 && p.W >= 8 &&
+         tiled_dims_ok(p);
 }
 
 template <int MODE, int S, int TW>
 hipError_t launch_fwd_tile(const Params& p, int mult, const DwArgs& a, hipStream_t s) {
   constexpr int TH = 64 / (TW / 4);
   const int tiles_w = (p.Wo + TW - 1) / TW, tiles_h = (p.Ho + TH - 1) / TH;
-  const long long n_items = (long long)p.N * p.C_out * tiles_w * tiles_h;
-  const long long blocks = (n_items + WAVES - 1) / WAVES;
-  if (n_items > 0x7fffffffLL - WAVES) return hipErrorInvalidValue;
+  const TileGrid tg = tile_grid(tiles_w, tiles_h, p.C_out, p.N);
   if (a.idx)
-    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, true>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, (int)n_items);
+    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, true>), tg.grid, dim3(WAVES * 64), 0, s, p, mult, a.x,
+                       a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_h, tg.inv_tiles_h);
   else
-    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, false>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                       mult, a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_w, tiles_h, (int)n_items);
+    hipLaunchKernelGGL((dw_fwd_tiled_kernel<MODE, S, TW, false>), tg.grid, dim3(WAVES * 64), 0, s, p, mult, a.x,
+                       a.w_min, a.w_max, a.alpha, a.beta, a.y, a.idx, tiles_h, tg.inv_tiles_h);
   return hipGetLastError();
 }
 
@@ -630,11 +653,9 @@ template <int MODE, int TW>
 hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const DwGrads& g, hipStream_t s) {
   constexpr int TH = 64 / (TW / 4);
   const int tiles_w = (p.W + TW - 1) / TW, tiles_h = (p.H + TH - 1) / TH;
-  const long long n_items = (long long)p.N * p.C_in * tiles_w * tiles_h;
-  const long long blocks = (n_items + WAVES - 1) / WAVES;
-  if (n_items > 0x7fffffffLL - WAVES) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p, mult,
-                     g.gy, a.idx, a.alpha, a.beta, g.grad_x, tiles_w, tiles_h, (int)n_items);
+  const TileGrid tg = tile_grid(tiles_w, tiles_h, p.C_in, p.N);
+  hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), tg.grid, dim3(WAVES * 64), 0, s, p, mult, g.gy, a.idx,
+                     a.alpha, a.beta, g.grad_x, tiles_h, tg.inv_tiles_h);
   return hipGetLastError();
 }
 
