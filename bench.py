@@ -46,9 +46,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_main")
-    ap.add_argument("--op", default="full", choices=["full", "sum"],
+    ap.add_argument("--op", default="full", choices=["full", "sum", "dw"],
                     help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
-                         "(tconv_sum_forward / tconv_sum_backward) on the same shapes")
+                         "(tconv_sum_forward / tconv_sum_backward) on the same shapes; dw: the depthwise layers "
+                         "(tconv_depthwise_forward / tconv_depthwise_backward; --workload dw_main | dw_s2 | dw_16 | dw_8)")
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
@@ -70,6 +71,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     tb.load()  # fails loudly if libtconv.so has not been built
+    if args.op == "dw":
+        return bench_depthwise(args, torch, tb)
     from paper_2504_06881_amd.inputs import resnet20_layers
     if args.workload == "cfg5":
         # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (benchmark configs[4]);
@@ -233,6 +236,109 @@ def main() -> int:
                                            [(None if L.op != "sum" or L.alpha is None else L.alpha.cpu().numpy(),
                                              None if L.op != "sum" or L.beta is None else L.beta.cpu().numpy())
                                             for L in layers])
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_depthwise(args, torch, tb) -> int:
+    """One depthwise layer: forward (writes y and the packed winner byte), backward w.r.t. the input, backward
+    w.r.t. kernel and coefficients.  These layers are HBM bound: the roofline entry is the forward kernel's
+    algorithmic bytes (x read once, y and one index byte written per output) against the HBM peak."""
+    from paper_2504_06881_amd.inputs import DW_CONFIGS, make_depthwise_inputs
+    name = args.workload if args.workload in DW_CONFIGS else "dw_main"
+    cfg = DW_CONFIGS[name]
+    if args.mode:
+        if args.mode not in ("max", "min", "compound", "parallel"):
+            print("bench.py: depthwise layers have the modes max, min, compound, parallel", file=sys.stderr)
+            return 2
+        cfg = cfg.with_(mode=args.mode)
+    dev = torch.device("cuda:0")
+    inp = make_depthwise_inputs(cfg)
+    d = tb.Desc.from_cfg(cfg)
+    ho, wo = tb.tconv_out_shape(d)
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    x, gy, al, be = up(inp["x"]), up(inp["gy"]), up(inp["alpha"]), up(inp["beta"])
+    w_min = up(inp["w_min"])
+    w_max = w_min if cfg.mode == "compound" else up(inp["w_max"])
+    two = cfg.mode in ("compound", "parallel")
+    osh = (cfg.N, cfg.C_out, ho, wo)
+    y = torch.empty(osh, device=dev)
+    idx = torch.empty(osh, device=dev, dtype=torch.uint8)
+    gx = torch.empty_like(x)
+    wshape = (cfg.C_out, 1, cfg.KH, cfg.KW)
+    g1 = torch.empty(wshape, device=dev) if cfg.mode != "max" else None
+    g2 = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel") else None
+    ga = torch.empty(cfg.C_out, device=dev) if two else None
+    gb = torch.empty(cfg.C_out, device=dev) if two else None
+    fwd = lambda: tb.tconv_depthwise_forward(d, x, w_min, w_max, al, be, y, idx)
+    bwd_x = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, gx, None, None, None, None)
+    bwd_p = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, None, g1, g2, ga, gb)
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, device=dev)
+        src.normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        fwd(); bwd_x(); bwd_p()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(); fwd(); e[1].record(); bwd_x(); e[2].record(); bwd_p(); e[3].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
+    t_bx = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
+    t_bp = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    ms_step = wall * 1e3 / args.steps
+    n_in, n_out = x.numel(), y.numel()
+    pairs = n_out * cfg.KH * cfg.KW * (2 if two else 1)
+    bytes_f = n_in * 4 + n_out * 5            # x read; y and one winner byte written
+    bytes_bx = n_out * 5 + n_in * 4           # gy and winner byte read; grad_x written
+    bytes_bp = n_out * 5 + (n_in * 4 if two else 0)   # gy, winner byte (and x for the coefficient gradients) read
+    out = {
+        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step (depthwise layer)",
+        "value": round(pairs / (ms_step * 1e-3) / 1e9, 2), "unit": "GOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: depthwise x[{cfg.N},{cfg.C_in},{cfg.H},{cfg.W}] -> {cfg.C_out}ch 3x3 "
+                               f"s{cfg.stride} p{cfg.pad} {cfg.mode} f32, fwd+bwd_input+bwd_params",
+                   "pairs_per_step": pairs, "forward_kernel": tb.tconv_depthwise_forward_kernel_name(d)},
+        "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
+        "ms_forward": round(t_f, 4), "ms_backward_input": round(t_bx, 4), "ms_backward_weight": round(t_bp, 4),
+        "backward_input_gbs": round(bytes_bx / (t_bx * 1e-3) / 1e9, 1),
+        "backward_weight_gbs": round(bytes_bp / (t_bp * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "forward", "achieved": round(bytes_f / (t_f * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_f / (t_f * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import tconv_oracle as orc
+        from oracle import tdw_oracle as odw
+
+        def run(n_img):
+            t = time.perf_counter()
+            s = orc.Shape(n_img, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+            odw.forward(s, cfg.mode, inp["x"][:n_img], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"])
+            odw.backward(s, cfg.mode, inp["x"][:n_img], inp["gy"][:n_img], inp["w_min"], inp["w_max"], inp["alpha"],
+                         inp["beta"])
+            return time.perf_counter() - t
+
+        t1 = run(1)
+        n_img = int(max(1, min(cfg.N, args.cpu_seconds / max(t1, 1e-6))))
+        reps, total = 0, 0.0
+        while reps == 0 or (total < args.cpu_seconds and reps < 50):
+            total += run(n_img)
+            reps += 1
+        out["cpu_baseline"] = {"value": round(pairs / cfg.N * n_img * reps / total / 1e9, 3), "unit": "GOPS",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {n_img} of {cfg.N} images of the same layer, forward + backward, "
+                                         f"{reps} repetitions, {total:.1f} s of wall time"}
     print(json.dumps(out), flush=True)
     return 0
 

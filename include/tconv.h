@@ -225,7 +225,7 @@ int tconv_depthwise_backward(const tconv_desc* desc, const void* x, const void* 
                              float* grad_x, float* grad_w_min, float* grad_w_max, float* grad_alpha,
                              float* grad_beta, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Name of the forward kernel tconv_depthwise_forward selects: "dw_tiled3x3" or "dw_generic".  Host only. */
+/* Name of the forward kernel tconv_depthwise_forward selects: "dw_tiled3x3", "dw_rows3x3" or "dw_generic".  Host only. */
 const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc);
 
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */

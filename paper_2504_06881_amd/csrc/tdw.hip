@@ -52,6 +52,13 @@ __device__ __forceinline__ void lds_run(float* dst, const float* src) {
   }
 }
 
+// sum over the 64 lanes of a wave, returned in every lane
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+  return v;
+}
+
 // y of one output from its branch extrema
 template <int MODE>
 __device__ __forceinline__ float dw_combine(float m, float M, float a, float b) {
@@ -59,6 +66,94 @@ __device__ __forceinline__ float dw_combine(float m, float M, float a, float b) 
   if (MODE == TCONV_MIN) return m;
   return combine(a, m, b, M);
 }
+
+// 4 consecutive outputs of one row from the 3 x (3*S + 3) input values under them (padding = NaN, which
+// v_min3 / v_max3 ignore and which never equals an extremum): y, and the packed winners if wanted.
+template <int MODE, int S, bool WANT_IDX>
+__device__ __forceinline__ void dw_px4(const float (&xs)[3][3 * S + 3], const float (&wa)[9], const float (&wb)[9],
+                                       float a, float b, float (&out)[4], int (&code)[4]) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float sa[9], sb[9];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float xv = xs[i][q * S + j];
+        if (DO_MIN) sa[i * 3 + j] = __fadd_rn(xv, wa[i * 3 + j]);
+        if (DO_MAX) sb[i * 3 + j] = (MODE == TCONV_COMPOUND) ? sa[i * 3 + j] : __fadd_rn(xv, wb[i * 3 + j]);
+      }
+    float m = 0.f, M = 0.f;
+    int tm = 0, tM = 0;
+    if (DO_MIN) {
+      m = fminf(fminf(sa[0], sa[1]), sa[2]);
+      m = fminf(fminf(m, sa[3]), sa[4]);
+      m = fminf(fminf(m, sa[5]), sa[6]);
+      m = fminf(fminf(m, sa[7]), sa[8]);
+      if (WANT_IDX) {
+#pragma unroll
+        for (int k = 8; k >= 0; --k) tm = (sa[k] == m) ? k : tm;
+      }
+    }
+    if (DO_MAX) {
+      M = fmaxf(fmaxf(sb[0], sb[1]), sb[2]);
+      M = fmaxf(fmaxf(M, sb[3]), sb[4]);
+      M = fmaxf(fmaxf(M, sb[5]), sb[6]);
+      M = fmaxf(fmaxf(M, sb[7]), sb[8]);
+      if (WANT_IDX) {
+#pragma unroll
+        for (int k = 8; k >= 0; --k) tM = (sb[k] == M) ? k : tM;
+      }
+    }
+    out[q] = dw_combine<MODE>(m, M, a, b);
+    code[q] = tm | (tM << 4);
+  }
+}
+
+// outputs q >= first_q of a lane's 4 go to y[ob + q] (and their winner bytes to idx[ob + q])
+template <bool WANT_IDX>
+__device__ __forceinline__ void dw_store4(float* __restrict__ y, uint8_t* __restrict__ idx, size_t ob,
+                                          const float (&out)[4], const int (&code)[4], int first_q) {
+  store_row<4>(y + ob, out, first_q);
+  if (WANT_IDX) {
+    if (first_q == 0 && ((uintptr_t)(idx + ob) & 3) == 0) {
+      *(unsigned*)(idx + ob) = (unsigned)code[0] | ((unsigned)code[1] << 8) | ((unsigned)code[2] << 16) |
+                               ((unsigned)code[3] << 24);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (q >= first_q) idx[ob + q] = (uint8_t)code[q];
+    }
+  }
+}
+
+// The gradient that reaches each of 4 consecutive input pixels through either branch, unscaled: g6 / c6 hold gy
+// and the winner bytes of the outputs of rows ih + ph - i (i = 0, 1, 2), columns iw0 + pw - 2 .. + 3.
+template <int MODE>
+__device__ __forceinline__ void dw_gather4(const float (&g6)[3][6], const int (&c6)[3][6], float (&am)[4],
+                                           float (&aM)[4]) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    int cmn[6], cmx[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) { cmn[k] = c6[i][k] & 15; cmx[k] = c6[i][k] >> 4; }
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int t = i * 3 + j;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (DO_MIN) am[q] += (cmn[q + 2 - j] == t) ? g6[i][q + 2 - j] : 0.f;
+        if (DO_MAX) aM[q] += (cmx[q + 2 - j] == t) ? g6[i][q + 2 - j] : 0.f;
+      }
+    }
+  }
+}
+
+// quotient of u by d through the multiply-high with inv = floor(2^32 / d) + 1 (inv = 0 stands for d = 1);
+// exact while u * d < 2^32
+__device__ __forceinline__ unsigned fast_div(unsigned u, unsigned inv) { return inv ? __umulhi(u, inv) : u; }
 
 // ------------------------------------------------------------------------------------------ forward, generic
 
@@ -213,55 +308,113 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
   }
   float out[4];
   int code[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    float sa[9], sb[9];
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const float xv = xs[i][q * S + j];
-        if (DO_MIN) sa[i * 3 + j] = __fadd_rn(xv, wa[i * 3 + j]);
-        if (DO_MAX) sb[i * 3 + j] = (MODE == TCONV_COMPOUND) ? sa[i * 3 + j] : __fadd_rn(xv, wb[i * 3 + j]);
-      }
-    float m = 0.f, M = 0.f;
-    int tm = 0, tM = 0;
-    if (DO_MIN) {
-      m = fminf(fminf(sa[0], sa[1]), sa[2]);
-      m = fminf(fminf(m, sa[3]), sa[4]);
-      m = fminf(fminf(m, sa[5]), sa[6]);
-      m = fminf(fminf(m, sa[7]), sa[8]);
-      if (WANT_IDX) {
-#pragma unroll
-        for (int k = 8; k >= 0; --k) tm = (sa[k] == m) ? k : tm;  // NaN (padding) never equals
-      }
-    }
-    if (DO_MAX) {
-      M = fmaxf(fmaxf(sb[0], sb[1]), sb[2]);
-      M = fmaxf(fmaxf(M, sb[3]), sb[4]);
-      M = fmaxf(fmaxf(M, sb[5]), sb[6]);
-      M = fmaxf(fmaxf(M, sb[7]), sb[8]);
-      if (WANT_IDX) {
-#pragma unroll
-        for (int k = 8; k >= 0; --k) tM = (sb[k] == M) ? k : tM;
-      }
-    }
-    out[q] = dw_combine<MODE>(m, M, a, b);
-    code[q] = tm | (tM << 4);
-  }
+  dw_px4<MODE, S, WANT_IDX>(xs, wa, wb, a, b, out, code);
   if (!act) return;
-  const size_t ob = ((size_t)plane * p.Ho + oh) * p.Wo + ow0;
-  store_row<4>(y + ob, out, first_q);
-  if (WANT_IDX) {
-    if (first_q == 0 && ((uintptr_t)(idx + ob) & 3) == 0) {
-      *(unsigned*)(idx + ob) = (unsigned)code[0] | ((unsigned)code[1] << 8) | ((unsigned)code[2] << 16) |
-                               ((unsigned)code[3] << 24);
-    } else {
+  dw_store4<WANT_IDX>(y, idx, ((size_t)plane * p.Ho + oh) * p.Wo + ow0, out, code, first_q);
+}
+
+// ------------------------------------------------------------------------------------------ 3x3 by rows (small planes)
+
+// One lane = 4 consecutive outputs (forward) or input pixels (backward) of one row of one plane, with the rows
+// of ALL planes numbered consecutively, so that planes much smaller than a wave's tile still fill the wave.
+// No LDS: a lane reads the values under its 4 pixels itself (clamped addresses, padding selected afterwards);
+// neighbouring lanes touch the same cache lines.  One input channel per output channel (mult == 1), so an
+// output plane and its input plane have the same number.
+template <int MODE, int S, bool WANT_IDX>
+__global__ __launch_bounds__(256) void dw_fwd_rows_kernel(Params p, const float* __restrict__ x,
+                                                          const float* __restrict__ w_min,
+                                                          const float* __restrict__ w_max,
+                                                          const float* __restrict__ alpha,
+                                                          const float* __restrict__ beta, float* __restrict__ y,
+                                                          uint8_t* __restrict__ idx, int segs, unsigned n_units,
+                                                          unsigned inv_segs, unsigned inv_rows, unsigned inv_c) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr int NC = 3 * S + 3;
+  const unsigned u = blockIdx.x * 256u + threadIdx.x;
+  if (u >= n_units) return;
+  const unsigned t = fast_div(u, inv_segs);
+  const int seg = (int)(u - t * (unsigned)segs);
+  const unsigned plane = fast_div(t, inv_rows);
+  const int oh = (int)(t - plane * (unsigned)p.Ho);
+  const int co = (int)(plane - fast_div(plane, inv_c) * (unsigned)p.C_out);
+  const int ow0 = min(seg * 4, p.Wo - 4);
+  const int first_q = seg * 4 - ow0;
+  const float* xp = x + (size_t)plane * p.H * p.W;
+  float xs[3][NC];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (q >= first_q) idx[ob + q] = (uint8_t)code[q];
+  for (int i = 0; i < 3; ++i) {
+    const int ih = oh * S - p.ph + i;
+    const bool row_ok = (ih >= 0 && ih < p.H);
+    const float* xr = xp + (size_t)min(max(ih, 0), p.H - 1) * p.W;
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+      const int iw = ow0 * S - p.pw + k;
+      const float v = xr[min(max(iw, 0), p.W - 1)];
+      xs[i][k] = (row_ok && iw >= 0 && iw < p.W) ? v : quiet_nan();
     }
   }
+  float wa[9], wb[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) {
+    wa[k] = DO_MIN ? w_min[(size_t)co * 9 + k] : 0.f;
+    wb[k] = DO_MAX ? w_max[(size_t)co * 9 + k] : 0.f;
+  }
+  float a = 1.f, b = 1.f;
+  if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
+    if (alpha) a = alpha[co];
+    if (beta) b = beta[co];
+  }
+  float out[4];
+  int code[4];
+  dw_px4<MODE, S, WANT_IDX>(xs, wa, wb, a, b, out, code);
+  dw_store4<WANT_IDX>(y, idx, ((size_t)plane * p.Ho + oh) * p.Wo + ow0, out, code, first_q);
+}
+
+// stride 1, dilation 1
+template <int MODE>
+__global__ __launch_bounds__(256) void dw_bwd_x_rows_kernel(Params p, const float* __restrict__ gy,
+                                                            const uint8_t* __restrict__ idx,
+                                                            const float* __restrict__ alpha,
+                                                            const float* __restrict__ beta,
+                                                            float* __restrict__ grad_x, int segs, unsigned n_units,
+                                                            unsigned inv_segs, unsigned inv_rows, unsigned inv_c) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  const unsigned u = blockIdx.x * 256u + threadIdx.x;
+  if (u >= n_units) return;
+  const unsigned t = fast_div(u, inv_segs);
+  const int seg = (int)(u - t * (unsigned)segs);
+  const unsigned plane = fast_div(t, inv_rows);
+  const int ih = (int)(t - plane * (unsigned)p.H);
+  const int c = (int)(plane - fast_div(plane, inv_c) * (unsigned)p.C_in);
+  const int iw0 = min(seg * 4, p.W - 4);
+  const int first_q = seg * 4 - iw0;
+  const size_t pb = (size_t)plane * p.Ho * p.Wo;
+  float g6[3][6];
+  int c6[3][6];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {  // input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
+    const int oh = ih + p.ph - i;
+    const bool row_ok = (oh >= 0 && oh < p.Ho);
+    const size_t rb = pb + (size_t)min(max(oh, 0), p.Ho - 1) * p.Wo;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+      const int ow = iw0 + p.pw - 2 + k;
+      const bool ok = row_ok && ow >= 0 && ow < p.Wo;
+      const size_t o = rb + min(max(ow, 0), p.Wo - 1);
+      const float g = gy[o];
+      const int code = idx[o];
+      g6[i][k] = ok ? g : 0.f;
+      c6[i][k] = ok ? code : 0xff;  // a code no tap matches
+    }
+  }
+  float am[4] = {0.f, 0.f, 0.f, 0.f}, aM[4] = {0.f, 0.f, 0.f, 0.f};
+  dw_gather4<MODE>(g6, c6, am, aM);
+  const float a = (TWO && alpha) ? alpha[c] : 1.f, b = (TWO && beta) ? beta[c] : 1.f;
+  float acc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) acc[q] = (DO_MIN ? a * am[q] : 0.f) + (DO_MAX ? b * aM[q] : 0.f);
+  store_row<4>(grad_x + ((size_t)plane * p.H + ih) * p.W + iw0, acc, first_q);
 }
 
 // ------------------------------------------------------------------------------------------ backward w.r.t. x
@@ -269,7 +422,8 @@ __global__ __launch_bounds__(WAVES * 64) void dw_fwd_tiled_kernel(Params p, int 
 // Generic gather, one thread per input element: tap (i, j) of output (oh, ow) reads input
 // (oh*s - p + i*d, ow*s - p + j*d), so the input pixel looks, for every tap, at the one output (if any)
 // that would read it through that tap and takes its gradient if that tap is the output's winner.
-template <int MODE>
+// SS: the stride when it is 1 or 2 on both axes (no integer division then), 0 = any stride.
+template <int MODE, int SS>
 __global__ __launch_bounds__(256) void dw_bwd_x_generic_kernel(Params p, int mult, const float* __restrict__ gy,
                                                                const uint8_t* __restrict__ idx,
                                                                const float* __restrict__ alpha,
@@ -291,11 +445,12 @@ __global__ __launch_bounds__(256) void dw_bwd_x_generic_kernel(Params p, int mul
     const size_t pb = ((size_t)n * p.C_out + co) * p.Ho * p.Wo;
     for (int i = 0; i < p.KH; ++i) {
       const int th = ih + p.ph - i * p.dh;
-      if (th < 0 || th % p.sh != 0 || th / p.sh >= p.Ho) continue;
+      const int sh = SS ? SS : p.sh, sw = SS ? SS : p.sw;
+      if (th < 0 || th % sh != 0 || th / sh >= p.Ho) continue;
       for (int j = 0; j < p.KW; ++j) {
         const int tw = iw + p.pw - j * p.dw;
-        if (tw < 0 || tw % p.sw != 0 || tw / p.sw >= p.Wo) continue;
-        const size_t o = pb + (size_t)(th / p.sh) * p.Wo + tw / p.sw;
+        if (tw < 0 || tw % sw != 0 || tw / sw >= p.Wo) continue;
+        const size_t o = pb + (size_t)(th / sh) * p.Wo + tw / sw;
         const int code = idx[o], t = i * p.KW + j;
         const float g = gy[o];
         if (DO_MIN && (code & 15) == t) acc += a * g;
@@ -314,8 +469,11 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
                                                                     const uint8_t* __restrict__ idx,
                                                                     const float* __restrict__ alpha,
                                                                     const float* __restrict__ beta,
-                                                                    float* __restrict__ grad_x, int tiles_h,
-                                                                    unsigned inv_tiles_h) {
+                                                                    const float* __restrict__ x,
+                                                                    float* __restrict__ grad_x,
+                                                                    float* __restrict__ grad_alpha,
+                                                                    float* __restrict__ grad_beta, int tiles_h,
+                                                                    unsigned inv_tiles_h, int imgs_per_wave) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int LR = TW / 4, TH = 64 / LR;
@@ -330,8 +488,6 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
   const int c = (int)((tiles_h == 1) ? u : __umulhi(u, inv_tiles_h));
   const int th = (int)u - c * tiles_h;
   if (c >= p.C_in) return;  // whole wave; no workgroup barrier
-  const int n = blockIdx.z;
-  const int plane = n * p.C_in + c;
   const int own_w = tw * TW;
   const int org_w = min(own_w, max(p.W - TW, 0));
   const int ih0 = th * TH;
@@ -352,6 +508,14 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
   const int cbase = (ow_base < 0) ? -4 : (ow_base & ~3);
   const int dd = (4 - (p.Wo & 3)) & 3;
   const int lc = iw0 + p.pw - 2 - cbase;  // tile column of output column iw0 + pw - 2
+  // The wave walks the same tile through imgs_per_wave images, so that the x part of the coefficient
+  // gradients (one value per output channel) leaves it with ONE atomic per branch instead of one per image:
+  // atomics to the same address are served one after the other.
+  const bool want_coef = TWO && x && (grad_alpha || grad_beta);
+  float sx_min = 0.f, sx_max = 0.f;
+  const int n_first = blockIdx.z * imgs_per_wave, n_last = min(n_first + imgs_per_wave, p.N);
+  for (int n = n_first; n < n_last; ++n) {
+  const int plane = n * p.C_in + c;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int mm = 0; mm < mult; ++mm) {
     const int co = c * mult + mm;
@@ -402,33 +566,43 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
     }
     wave_lds_fence();
     const float a = (TWO && alpha) ? alpha[co] : 1.f, b = (TWO && beta) ? beta[co] : 1.f;
+    float am[4] = {0.f, 0.f, 0.f, 0.f}, aM[4] = {0.f, 0.f, 0.f, 0.f};  // unscaled gradient through each branch
+    float g6[3][6];
+    int c6[3][6];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      // outputs of tile row r + 2 - i, columns lc + q + 2 - j for q = 0..3, j = 0..2: lc .. lc + 5
-      float g6[6];
-      int c6[6];
-      lds_run<6>(g6, &gt[(r + 2 - i) * PITCH + lc]);
-      lds_run<6>((float*)c6, (const float*)&ct[(r + 2 - i) * PITCH + lc]);
-      float ag[6], bg[6];
-      int cmn[6], cmx[6];
+    for (int i = 0; i < 3; ++i) {  // outputs of tile row r + 2 - i, tile columns lc .. lc + 5
+      lds_run<6>(g6[i], &gt[(r + 2 - i) * PITCH + lc]);
+      lds_run<6>((float*)c6[i], (const float*)&ct[(r + 2 - i) * PITCH + lc]);
+    }
+    dw_gather4<MODE>(g6, c6, am, aM);
 #pragma unroll
-      for (int k = 0; k < 6; ++k) {
-        ag[k] = a * g6[k]; bg[k] = b * g6[k];
-        cmn[k] = c6[k] & 15; cmx[k] = c6[k] >> 4;
+    for (int q = 0; q < 4; ++q) {
+      if (DO_MIN) acc[q] += a * am[q];
+      if (DO_MAX) acc[q] += b * aM[q];
+    }
+    // The x part of the coefficient gradients: sum over outputs of gy * x[winner] = sum over input pixels of
+    // x * (gradient that reached the pixel through that branch).  Pixels this lane computes for a neighbour
+    // (moved last segment / tile) are left to their owner.
+    if (want_coef) {
+      if (act) {
+        const f4u xv = *(const f4u*)(x + ((size_t)plane * p.H + ih) * p.W + iw0);
+        const float x4[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (q >= first_q) { sx_min += x4[q] * am[q]; sx_max += x4[q] * aM[q]; }
       }
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int t = i * 3 + j;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (DO_MIN) acc[q] += (cmn[q + 2 - j] == t) ? ag[q + 2 - j] : 0.f;
-          if (DO_MAX) acc[q] += (cmx[q + 2 - j] == t) ? bg[q + 2 - j] : 0.f;
+      if (mult > 1 || n == n_last - 1) {  // several output channels per input channel: one flush per channel and image
+        const float sa = wave_sum(sx_min), sb = wave_sum(sx_max);
+        if (lane == 0) {
+          if (grad_alpha) atomicAdd(grad_alpha + co, sa);
+          if (grad_beta) atomicAdd(grad_beta + co, sb);
         }
+        sx_min = sx_max = 0.f;
       }
     }
   }
-  if (!act) return;
-  store_row<4>(grad_x + ((size_t)plane * p.H + ih) * p.W + iw0, acc, first_q);
+  if (act && grad_x) store_row<4>(grad_x + ((size_t)plane * p.H + ih) * p.W + iw0, acc, first_q);
+  }
 }
 
 // ------------------------------------------------------------------------------------------ parameter gradients
@@ -437,6 +611,8 @@ __global__ __launch_bounds__(WAVES * 64) void dw_bwd_x_tiled_kernel(Params p, in
 // tap t; grad_alpha[co] = sum gy * m and grad_beta[co] = sum gy * M, where the branch output at the winner
 // is x[winner] + w[t], so the sum splits into sum gy * x[winner] plus sum over t of w[t] * S_b[t] (the
 // second part comes from the tap sums; the split differs from the rounded x + w by one rounding per term).
+// The tiled input-gradient kernel adds the x part itself (it has every input pixel's share of the gradient in
+// registers); this kernel then only adds the w part (gather_x == 0).
 // Workgroup = (output channel, slice of the batch).  Every thread keeps its own column of partial sums in
 // LDS (bins[row][thread]: no conflicts, no atomics), rows: KK taps per branch, then one for sum gy * x.
 // A thread takes 4 consecutive outputs per trip (one 16-byte and one 4-byte load) and fetches the next
@@ -452,7 +628,8 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
                                                             float* __restrict__ grad_w_min,
                                                             float* __restrict__ grad_w_max,
                                                             float* __restrict__ grad_alpha,
-                                                            float* __restrict__ grad_beta, int n_per_block) {
+                                                            float* __restrict__ grad_beta, int n_per_block,
+                                                            int gather_x) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NBR = TWO ? 2 : 1;
@@ -472,6 +649,7 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
   for (int rw = 0; rw < rows; ++rw) bins[rw * PITCH + tid] = 0.f;
   __syncthreads();
   const bool want_coef = TWO && (grad_alpha || grad_beta);
+  const bool want_x = want_coef && gather_x;  // else the input-gradient kernel has added the x part already
   const int plane = p.Ho * p.Wo, xplane = p.H * p.W;
   const int ngrp = plane >> 2;                 // groups of 4 consecutive outputs inside a plane
   const int base_max = (NBR - 1) * (KK + 1);   // first row of the max-plus branch
@@ -483,12 +661,12 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
     if (DO_MIN) {
       const int t = min(code & 15, KK - 1);
       bins[t * PITCH + tid] += g;
-      if (want_coef) sx_min += g * xp[min(max(first + toff[t], 0), xplane - 1)];  // clamp: a corrupted index stays in bounds
+      if (want_x) sx_min += g * xp[min(max(first + toff[t], 0), xplane - 1)];  // clamp: a corrupted index stays in bounds
     }
     if (DO_MAX) {
       const int t = min(code >> 4, KK - 1);
       bins[(base_max + t) * PITCH + tid] += g;
-      if (want_coef) sx_max += g * xp[min(max(first + toff[t], 0), xplane - 1)];
+      if (want_x) sx_max += g * xp[min(max(first + toff[t], 0), xplane - 1)];
     }
   };
 
@@ -512,7 +690,7 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
       unsigned c4n = c4;
       int nn = n, pixn = pix;
       if (fn < total) fetch(fn, g4n, c4n, nn, pixn);
-      const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
+      const float* xp = want_x ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
       int oh = pix / p.Wo, ow = pix - oh * p.Wo;
       const float gs[4] = {g4.x, g4.y, g4.z, g4.w};
 #pragma unroll
@@ -528,10 +706,10 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
   for (int e = tid; e < (n1 - n0) * rem; e += NT) {
     const int n = n0 + e / rem, pix = 4 * ngrp + e % rem;
     const size_t o = ((size_t)n * p.C_out + co) * plane + pix;
-    const float* xp = want_coef ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
+    const float* xp = want_x ? x + ((size_t)n * p.C_in + c) * xplane : nullptr;
     one(gy[o], idx[o], pix / p.Wo, pix % p.Wo, xp);
   }
-  if (want_coef) {
+  if (want_x) {
     if (DO_MIN) bins[KK * PITCH + tid] = sx_min;
     if (DO_MAX) bins[(base_max + KK) * PITCH + tid] = sx_max;
   }
@@ -554,23 +732,33 @@ __global__ __launch_bounds__(256) void dw_bwd_params_kernel(Params p, int mult, 
     } else if (want_coef) {
       float* gc = is_max ? grad_beta : grad_alpha;
       const float* wv = (is_max ? w_max : w_min) + (size_t)co * KK;
-      double sacc = tot[tid];
+      double sacc = want_x ? tot[tid] : 0.0;
       for (int t = 0; t < KK; ++t) sacc += (double)wv[t] * tot[br * (KK + 1) + t];
       if (gc) atomicAdd(gc + co, (float)sacc);
     }
   }
 }
 
-__global__ __launch_bounds__(256) void dw_fill_zero_kernel(float* __restrict__ p, size_t n) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+// Zero fill of the (small) parameter gradients before the atomics: up to four buffers in one launch, as a
+// kernel so that the call can sit in a captured graph.
+struct ZeroList {
+  float* ptr[4];
+  unsigned n[4];
+};
+
+__global__ __launch_bounds__(256) void dw_fill_zero_kernel(ZeroList z) {
+  const unsigned stride = gridDim.x * blockDim.x;
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < z.n[b]; i += stride) z.ptr[b][i] = 0.f;
 }
 
-void zero_fill(float* p, size_t n, hipStream_t s) {  // a kernel, so that the call can sit in a captured graph
-  if (!p || n == 0) return;
-  size_t blocks = (n + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(dw_fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+int resident_cus() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  return cus;
 }
 
 bool force_generic() {
@@ -615,6 +803,60 @@ bool bwd_x_tiled_ok(const Params& p) {
          tiled_dims_ok(p);
 }
 
+// The by-rows kernels: 3x3, dilation 1, one input channel per output channel, rows of at least 4 pixels, and
+// row numbers small enough for the multiply-high quotients (u * d < 2^32 for d = segments, rows, channels).
+bool rows_dims_ok(long long planes, int rows, int width, int channels) {
+  if (width < 4) return false;
+  const long long segs = (width + 3) / 4, units = planes * rows * segs;
+  const long long dmax = segs > rows ? (segs > channels ? segs : channels) : (rows > channels ? rows : channels);
+  return units * dmax < 0xffffffffLL && units + 256 < 0xffffffffLL;
+}
+
+bool fwd_rows_ok(const Params& p) {
+  if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1 || p.C_out != p.C_in) return false;
+  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+  return rows_dims_ok((long long)p.N * p.C_out, p.Ho, p.Wo, p.C_out);
+}
+
+bool bwd_x_rows_ok(const Params& p) {
+  if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1 || p.C_out != p.C_in || p.sh != 1 || p.sw != 1) return false;
+  return rows_dims_ok((long long)p.N * p.C_in, p.H, p.W, p.C_in);
+}
+
+// a plane that fills at most half of a wave's tile goes by rows
+bool small_plane(int rows, int width) { return (long long)rows * (tile_width(width) / 4) <= 32; }
+
+unsigned inv_of(int d) { return d > 1 ? (unsigned)(0x100000000ull / (unsigned)d) + 1u : 0u; }
+
+// 0: generic, 1: tiled through LDS, 2: by rows
+int fwd_kernel_choice(const Params& p) {
+  if (force_generic()) return 0;
+  const bool tiled = fwd_tiled_ok(p), rows = fwd_rows_ok(p);
+  if (rows && (!tiled || small_plane(p.Ho, p.Wo))) return 2;
+  return tiled ? 1 : 0;
+}
+
+int bwd_x_kernel_choice(const Params& p) {
+  if (force_generic()) return 0;
+  const bool tiled = bwd_x_tiled_ok(p), rows = bwd_x_rows_ok(p);
+  if (rows && (!tiled || small_plane(p.H, p.W))) return 2;
+  return tiled ? 1 : 0;
+}
+
+template <int MODE, int S>
+hipError_t launch_fwd_rows(const Params& p, const DwArgs& a, hipStream_t s) {
+  const int segs = (p.Wo + 3) / 4;
+  const unsigned n_units = (unsigned)((long long)p.N * p.C_out * p.Ho * segs);
+  const dim3 grid((n_units + 255) / 256);
+  if (a.idx)
+    hipLaunchKernelGGL((dw_fwd_rows_kernel<MODE, S, true>), grid, dim3(256), 0, s, p, a.x, a.w_min, a.w_max, a.alpha,
+                       a.beta, a.y, a.idx, segs, n_units, inv_of(segs), inv_of(p.Ho), inv_of(p.C_out));
+  else
+    hipLaunchKernelGGL((dw_fwd_rows_kernel<MODE, S, false>), grid, dim3(256), 0, s, p, a.x, a.w_min, a.w_max, a.alpha,
+                       a.beta, a.y, a.idx, segs, n_units, inv_of(segs), inv_of(p.Ho), inv_of(p.C_out));
+  return hipGetLastError();
+}
+
 template <int MODE, int S, int TW>
 hipError_t launch_fwd_tile(const Params& p, int mult, const DwArgs& a, hipStream_t s) {
   constexpr int TH = 64 / (TW / 4);
@@ -641,7 +883,9 @@ hipError_t launch_fwd_s(const Params& p, int mult, const DwArgs& a, hipStream_t 
 template <int MODE>
 hipError_t launch_fwd(const Params& p, const DwArgs& a, hipStream_t s) {
   const int mult = p.C_out / p.C_in;
-  if (fwd_tiled_ok(p) && !force_generic())
+  if (fwd_kernel_choice(p) == 2)
+    return p.sh == 1 ? launch_fwd_rows<MODE, 1>(p, a, s) : launch_fwd_rows<MODE, 2>(p, a, s);
+  if (fwd_kernel_choice(p) == 1)
     return p.sh == 1 ? launch_fwd_s<MODE, 1>(p, mult, a, s) : launch_fwd_s<MODE, 2>(p, mult, a, s);
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
   hipLaunchKernelGGL(dw_fwd_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p, mult,
@@ -650,53 +894,88 @@ hipError_t launch_fwd(const Params& p, const DwArgs& a, hipStream_t s) {
 }
 
 template <int MODE, int TW>
-hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const DwGrads& g, hipStream_t s) {
+hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const DwGrads& g, bool want_coef,
+                             hipStream_t s) {
   constexpr int TH = 64 / (TW / 4);
   const int tiles_w = (p.W + TW - 1) / TW, tiles_h = (p.H + TH - 1) / TH;
-  const TileGrid tg = tile_grid(tiles_w, tiles_h, p.C_in, p.N);
+  // images per wave: as many as still leave about four waves per SIMD slot busy, at most 16
+  const long long waves_per_image = (long long)tiles_w * tiles_h * p.C_in;
+  int ipw = 1;
+  if (want_coef) {
+    ipw = (int)((waves_per_image * p.N) / (4LL * 4 * resident_cus()));
+    ipw = ipw < 1 ? 1 : (ipw > 16 ? 16 : ipw);
+  }
+  const TileGrid tg = tile_grid(tiles_w, tiles_h, p.C_in, (p.N + ipw - 1) / ipw);
   hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), tg.grid, dim3(WAVES * 64), 0, s, p, mult, g.gy, a.idx,
-                     a.alpha, a.beta, g.grad_x, tiles_h, tg.inv_tiles_h);
+                     a.alpha, a.beta, want_coef ? a.x : nullptr, g.grad_x, g.grad_alpha, g.grad_beta, tiles_h,
+                     tg.inv_tiles_h, ipw);
   return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t launch_bwd(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s) {
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   const int mult = p.C_out / p.C_in, KK = p.KH * p.KW;
-  if (g.grad_x) {
-    hipError_t e;
-    if (bwd_x_tiled_ok(p) && !force_generic()) {
-      switch (tile_width(p.W)) {
-        case 32: e = launch_bwd_x_tile<MODE, 32>(p, mult, a, g, s); break;
-        case 16: e = launch_bwd_x_tile<MODE, 16>(p, mult, a, g, s); break;
-        default: e = launch_bwd_x_tile<MODE, 8>(p, mult, a, g, s); break;
-      }
-    } else {
-      const size_t total = (size_t)p.N * p.C_in * p.H * p.W;
-      hipLaunchKernelGGL(dw_bwd_x_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p,
-                         mult, g.gy, a.idx, a.alpha, a.beta, g.grad_x);
-      e = hipGetLastError();
-    }
-    if (e != hipSuccess) return e;
-  }
   float* gmin = g.grad_w_min;
   float* gmax = g.grad_w_max;
   if (MODE == TCONV_COMPOUND) gmin = gmax = (g.grad_w_min ? g.grad_w_min : g.grad_w_max);
-  const bool want = (MODE != TCONV_MAX && gmin) || (MODE != TCONV_MIN && gmax) || g.grad_alpha || g.grad_beta;
-  if (want) {
-    const size_t nw = (size_t)p.C_out * KK;
-    if (MODE != TCONV_MAX) zero_fill(gmin, nw, s);
-    if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(gmax, nw, s);
-    zero_fill(g.grad_alpha, (size_t)p.C_out, s);
-    zero_fill(g.grad_beta, (size_t)p.C_out, s);
+  const bool want_coef = TWO && (g.grad_alpha || g.grad_beta);
+  const bool want_params = (MODE != TCONV_MAX && gmin) || (MODE != TCONV_MIN && gmax) || want_coef;
+  if (want_params) {  // every parameter gradient is accumulated with atomics
+    const unsigned nw = (unsigned)p.C_out * KK;
+    ZeroList z = {{nullptr, nullptr, nullptr, nullptr}, {0u, 0u, 0u, 0u}};
+    int nz = 0;
+    auto add = [&](float* ptr, unsigned n) { if (ptr) { z.ptr[nz] = ptr; z.n[nz] = n; ++nz; } };
+    if (MODE != TCONV_MAX) add(gmin, nw);
+    if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) add(gmax, nw);
+    add(g.grad_alpha, (unsigned)p.C_out);
+    add(g.grad_beta, (unsigned)p.C_out);
+    unsigned zblocks = (nw + 255) / 256;
+    if (zblocks > 1024) zblocks = 1024;
+    hipLaunchKernelGGL(dw_fill_zero_kernel, dim3(zblocks), dim3(256), 0, s, z);
+  }
+  const int choice = bwd_x_kernel_choice(p);
+  const bool tiled = choice == 1;
+  if (choice == 2 && g.grad_x) {
+    const int segs = (p.W + 3) / 4;
+    const unsigned n_units = (unsigned)((long long)p.N * p.C_in * p.H * segs);
+    hipLaunchKernelGGL(dw_bwd_x_rows_kernel<MODE>, dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx, a.alpha,
+                       a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  } else if (tiled && (g.grad_x || want_coef)) {  // grad_x and the x part of the coefficient gradients
+    hipError_t e;
+    switch (tile_width(p.W)) {
+      case 32: e = launch_bwd_x_tile<MODE, 32>(p, mult, a, g, want_coef, s); break;
+      case 16: e = launch_bwd_x_tile<MODE, 16>(p, mult, a, g, want_coef, s); break;
+      default: e = launch_bwd_x_tile<MODE, 8>(p, mult, a, g, want_coef, s); break;
+    }
+    if (e != hipSuccess) return e;
+  } else if (g.grad_x) {
+    const size_t total = (size_t)p.N * p.C_in * p.H * p.W;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (p.sh == p.sw && p.sh == 1)
+      hipLaunchKernelGGL((dw_bwd_x_generic_kernel<MODE, 1>), grid, dim3(256), 0, s, p, mult, g.gy, a.idx, a.alpha, a.beta,
+                         g.grad_x);
+    else if (p.sh == p.sw && p.sh == 2)
+      hipLaunchKernelGGL((dw_bwd_x_generic_kernel<MODE, 2>), grid, dim3(256), 0, s, p, mult, g.gy, a.idx, a.alpha, a.beta,
+                         g.grad_x);
+    else
+      hipLaunchKernelGGL((dw_bwd_x_generic_kernel<MODE, 0>), grid, dim3(256), 0, s, p, mult, g.gy, a.idx, a.alpha, a.beta,
+                         g.grad_x);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (want_params) {
     int slices = (2048 + p.C_out - 1) / p.C_out;  // enough workgroups to fill the chip
     if (slices > p.N) slices = p.N;
     if (slices > 65535) slices = 65535;
     const int n_per_block = (p.N + slices - 1) / slices;
     const dim3 grid((unsigned)p.C_out, (unsigned)((p.N + n_per_block - 1) / n_per_block));
-    constexpr int NBR = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) ? 2 : 1;
+    constexpr int NBR = TWO ? 2 : 1;
     const size_t lds = (size_t)NBR * (KK + 1) * 257 * sizeof(float) + 16 * sizeof(int) + (size_t)NBR * (KK + 1) * sizeof(double) + 8;
     hipLaunchKernelGGL(dw_bwd_params_kernel<MODE>, grid, dim3(256), lds, s, p, mult, a.x, a.w_min, a.w_max, a.alpha,
-                       a.beta, g.gy, a.idx, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);
+                       a.beta, g.gy, a.idx, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block, tiled ? 0 : 1);
   }
   return hipGetLastError();
 }
@@ -722,7 +1001,8 @@ hipError_t launch_depthwise_backward(const Params& p, const DwArgs& a, const DwG
 }
 
 const char* depthwise_forward_kernel_name(const Params& p) {
-  return (fwd_tiled_ok(p) && !force_generic()) ? "dw_tiled3x3" : "dw_generic";
+  const int k = fwd_kernel_choice(p);
+  return k == 2 ? "dw_rows3x3" : (k == 1 ? "dw_tiled3x3" : "dw_generic");
 }
 
 }  // namespace tconv
