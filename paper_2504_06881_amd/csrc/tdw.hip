@@ -370,8 +370,10 @@ __global__ __launch_bounds__(256) void dw_fwd_rows_kernel(Params p, const float*
   dw_store4<WANT_IDX>(y, idx, ((size_t)plane * p.Ho + oh) * p.Wo + ow0, out, code, first_q);
 }
 
-// stride 1, dilation 1
-template <int MODE>
+// Dilation 1, stride S = 1 or 2.  At stride 2 an input pixel is read through tap (i, j) only where ih + ph - i and
+// iw + pw - j are even: per kernel row at most 4 outputs lie under a lane's 4 pixels, and which (pixel, tap)
+// pairs meet which of them depends on the parity of iw0 + pw alone.
+template <int MODE, int S>
 __global__ __launch_bounds__(256) void dw_bwd_x_rows_kernel(Params p, const float* __restrict__ gy,
                                                             const uint8_t* __restrict__ idx,
                                                             const float* __restrict__ alpha,
@@ -390,26 +392,65 @@ __global__ __launch_bounds__(256) void dw_bwd_x_rows_kernel(Params p, const floa
   const int iw0 = min(seg * 4, p.W - 4);
   const int first_q = seg * 4 - iw0;
   const size_t pb = (size_t)plane * p.Ho * p.Wo;
-  float g6[3][6];
-  int c6[3][6];
+  float am[4] = {0.f, 0.f, 0.f, 0.f}, aM[4] = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (S == 1) {
+    float g6[3][6];
+    int c6[3][6];
 #pragma unroll
-  for (int i = 0; i < 3; ++i) {  // input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
-    const int oh = ih + p.ph - i;
-    const bool row_ok = (oh >= 0 && oh < p.Ho);
-    const size_t rb = pb + (size_t)min(max(oh, 0), p.Ho - 1) * p.Wo;
+    for (int i = 0; i < 3; ++i) {  // input (ih, iw) is read through tap (i, j) by output (ih + ph - i, iw + pw - j)
+      const int oh = ih + p.ph - i;
+      const bool row_ok = (oh >= 0 && oh < p.Ho);
+      const size_t rb = pb + (size_t)min(max(oh, 0), p.Ho - 1) * p.Wo;
 #pragma unroll
-    for (int k = 0; k < 6; ++k) {
-      const int ow = iw0 + p.pw - 2 + k;
-      const bool ok = row_ok && ow >= 0 && ow < p.Wo;
-      const size_t o = rb + min(max(ow, 0), p.Wo - 1);
-      const float g = gy[o];
-      const int code = idx[o];
-      g6[i][k] = ok ? g : 0.f;
-      c6[i][k] = ok ? code : 0xff;  // a code no tap matches
+      for (int k = 0; k < 6; ++k) {
+        const int ow = iw0 + p.pw - 2 + k;
+        const bool ok = row_ok && ow >= 0 && ow < p.Wo;
+        const size_t o = rb + min(max(ow, 0), p.Wo - 1);
+        const float g = gy[o];
+        const int code = idx[o];
+        g6[i][k] = ok ? g : 0.f;
+        c6[i][k] = ok ? code : 0xff;  // a code no tap matches
+      }
+    }
+    dw_gather4<MODE>(g6, c6, am, aM);
+  } else {
+    const int B = iw0 + p.pw;               // column of tap j = 0 of pixel q = 0, doubled output coordinates
+    const bool odd = (B & 1) != 0;
+    const int ow_base = (B - 2) >> 1;       // floor; the 4 candidate outputs of a row are ow_base .. ow_base + 3
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int th = ih + p.ph - i;
+      const bool row_ok = (th >= 0) && ((th & 1) == 0) && ((th >> 1) < p.Ho);
+      const size_t rb = pb + (size_t)min(max(th >> 1, 0), p.Ho - 1) * p.Wo;
+      float g4[4];
+      int ce[4], co[4];  // winner bytes, kept only for the parity they can be met with
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int ow = ow_base + k;
+        const bool ok = row_ok && ow >= 0 && ow < p.Wo;
+        const size_t o = rb + min(max(ow, 0), p.Wo - 1);
+        const float g = gy[o];
+        const int code = idx[o];
+        g4[k] = g;
+        ce[k] = (ok && !odd) ? code : 0xff;
+        co[k] = (ok && odd) ? code : 0xff;
+      }
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int tp = i * 3 + j;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          // B + q - j even: B even and q - j even -> output ow_base + (q - j) / 2 + 1; B odd and q - j odd ->
+          // output ow_base + (q - j + 3) / 2
+          const bool even_pair = ((q - j) & 1) == 0;
+          const int k = even_pair ? (q - j) / 2 + 1 : (q - j + 3) / 2;
+          const int code = even_pair ? ce[k] : co[k];
+          if (DO_MIN) am[q] += ((code & 15) == tp) ? g4[k] : 0.f;
+          if (DO_MAX) aM[q] += ((code >> 4) == tp) ? g4[k] : 0.f;
+        }
+      }
     }
   }
-  float am[4] = {0.f, 0.f, 0.f, 0.f}, aM[4] = {0.f, 0.f, 0.f, 0.f};
-  dw_gather4<MODE>(g6, c6, am, aM);
   const float a = (TWO && alpha) ? alpha[c] : 1.f, b = (TWO && beta) ? beta[c] : 1.f;
   float acc[4];
 #pragma unroll
@@ -819,7 +860,8 @@ bool fwd_rows_ok(const Params& p) {
 }
 
 bool bwd_x_rows_ok(const Params& p) {
-  if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1 || p.C_out != p.C_in || p.sh != 1 || p.sw != 1) return false;
+  if (p.KH != 3 || p.KW != 3 || p.dh != 1 || p.dw != 1 || p.C_out != p.C_in) return false;
+  if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
   return rows_dims_ok((long long)p.N * p.C_in, p.H, p.W, p.C_in);
 }
 
@@ -939,8 +981,12 @@ hipError_t launch_bwd(const Params& p, const DwArgs& a, const DwGrads& g, hipStr
   if (choice == 2 && g.grad_x) {
     const int segs = (p.W + 3) / 4;
     const unsigned n_units = (unsigned)((long long)p.N * p.C_in * p.H * segs);
-    hipLaunchKernelGGL(dw_bwd_x_rows_kernel<MODE>, dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx, a.alpha,
-                       a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
+    if (p.sh == 1)
+      hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 1>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
+                         a.alpha, a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
+    else
+      hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 2>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
+                         a.alpha, a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   } else if (tiled && (g.grad_x || want_coef)) {  // grad_x and the x part of the coefficient gradients
