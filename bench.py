@@ -271,8 +271,8 @@ def bench_depthwise(args, torch, tb) -> int:
     ga = torch.empty(cfg.C_out, device=dev) if two else None
     gb = torch.empty(cfg.C_out, device=dev) if two else None
     fwd = lambda: tb.tconv_depthwise_forward(d, x, w_min, w_max, al, be, y, idx)
-    bwd_x = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, gx, None, None, None, None)
-    bwd_p = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, None, g1, g2, ga, gb)
+    # one backward call for every gradient, as a training step makes it
+    bwd = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, gx, g1, g2, ga, gb)
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, device=dev)
         src.normal_()
@@ -282,37 +282,36 @@ def bench_depthwise(args, torch, tb) -> int:
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        fwd(); bwd_x(); bwd_p()
+        fwd(); bwd()
     torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        e[0].record(); fwd(); e[1].record(); bwd_x(); e[2].record(); bwd_p(); e[3].record()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record(); fwd(); e[1].record(); bwd(); e[2].record()
         marks.append(e)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    t_bx = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
-    t_bp = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    t_b = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
     n_in, n_out = x.numel(), y.numel()
     pairs = n_out * cfg.KH * cfg.KW * (2 if two else 1)
     bytes_f = n_in * 4 + n_out * 5            # x read; y and one winner byte written
-    bytes_bx = n_out * 5 + n_in * 4           # gy and winner byte read; grad_x written
-    bytes_bp = n_out * 5 + (n_in * 4 if two else 0)   # gy, winner byte (and x for the coefficient gradients) read
+    # backward: gy and the winner byte read by the input-gradient and by the parameter-gradient kernel, x read for
+    # the coefficient gradients, grad_x written
+    bytes_b = 2 * n_out * 5 + n_in * 4 + (n_in * 4 if two else 0)
     out = {
         "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step (depthwise layer)",
         "value": round(pairs / (ms_step * 1e-3) / 1e9, 2), "unit": "GOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: depthwise x[{cfg.N},{cfg.C_in},{cfg.H},{cfg.W}] -> {cfg.C_out}ch 3x3 "
-                               f"s{cfg.stride} p{cfg.pad} {cfg.mode} f32, fwd+bwd_input+bwd_params",
+                               f"s{cfg.stride} p{cfg.pad} {cfg.mode} f32, forward + one backward call (all gradients)",
                    "pairs_per_step": pairs, "forward_kernel": tb.tconv_depthwise_forward_kernel_name(d)},
         "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
-        "ms_forward": round(t_f, 4), "ms_backward_input": round(t_bx, 4), "ms_backward_weight": round(t_bp, 4),
-        "backward_input_gbs": round(bytes_bx / (t_bx * 1e-3) / 1e9, 1),
-        "backward_weight_gbs": round(bytes_bp / (t_bp * 1e-3) / 1e9, 1),
+        "ms_forward": round(t_f, 4), "ms_backward": round(t_b, 4),
+        "backward_gbs": round(bytes_b / (t_b * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "kernel": "forward", "achieved": round(bytes_f / (t_f * 1e-3) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_f / (t_f * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "traffic": None},

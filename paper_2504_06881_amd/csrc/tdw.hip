@@ -940,12 +940,14 @@ hipError_t launch_bwd_x_tile(const Params& p, int mult, const DwArgs& a, const D
                              hipStream_t s) {
   constexpr int TH = 64 / (TW / 4);
   const int tiles_w = (p.W + TW - 1) / TW, tiles_h = (p.H + TH - 1) / TH;
-  // images per wave: as many as still leave about four waves per SIMD slot busy, at most 16
+  // images per wave: as many as still leave about four waves per SIMD slot busy, at most 8 (measured: 4 - 8
+  // is the flat optimum; one costs twice the time in atomics, 32 starves the chip of waves)
   const long long waves_per_image = (long long)tiles_w * tiles_h * p.C_in;
   int ipw = 1;
   if (want_coef) {
     ipw = (int)((waves_per_image * p.N) / (4LL * 4 * resident_cus()));
-    ipw = ipw < 1 ? 1 : (ipw > 16 ? 16 : ipw);
+    ipw = ipw < 1 ? 1 : (ipw > 8 ? 8 : ipw);
+    if (const char* e = getenv("TCONV_DW_IPW")) ipw = atoi(e) > 0 ? atoi(e) : ipw;  // tuning aid
   }
   const TileGrid tg = tile_grid(tiles_w, tiles_h, p.C_in, (p.N + ipw - 1) / ipw);
   hipLaunchKernelGGL((dw_bwd_x_tiled_kernel<MODE, TW>), tg.grid, dim3(WAVES * 64), 0, s, p, mult, g.gy, a.idx,
