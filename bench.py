@@ -46,10 +46,11 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_main")
-    ap.add_argument("--op", default="full", choices=["full", "sum", "dw"],
+    ap.add_argument("--op", default="full", choices=["full", "sum", "dw", "1d"],
                     help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
                          "(tconv_sum_forward / tconv_sum_backward) on the same shapes; dw: the depthwise layers "
-                         "(tconv_depthwise_forward / tconv_depthwise_backward; --workload dw_main | dw_s2 | dw_16 | dw_8)")
+                         "(tconv_depthwise_forward / tconv_depthwise_backward; --workload dw_main | dw_s2 | dw_16 | dw_8); "
+                         "1d: the one-dimensional layers (tconv1d_*; --workload c1d_main | c1d_stem)")
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
@@ -73,6 +74,8 @@ def main() -> int:
     tb.load()  # fails loudly if libtconv.so has not been built
     if args.op == "dw":
         return bench_depthwise(args, torch, tb)
+    if args.op == "1d":
+        return bench_1d(args, torch, tb)
     from paper_2504_06881_amd.inputs import resnet20_layers
     if args.workload == "cfg5":
         # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (benchmark configs[4]);
@@ -236,6 +239,90 @@ def main() -> int:
                                            [(None if L.op != "sum" or L.alpha is None else L.alpha.cpu().numpy(),
                                              None if L.op != "sum" or L.beta is None else L.beta.cpu().numpy())
                                             for L in layers])
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_1d(args, torch, tb) -> int:
+    """One one-dimensional layer: tconv1d_forward, tconv1d_backward_input, tconv1d_backward_weight per step; the
+    forward pass is judged against the plain fp32 VALU form, as for the two-dimensional layers."""
+    from paper_2504_06881_amd.inputs import CONFIGS_1D, make_1d_inputs
+    cfg = CONFIGS_1D[args.workload if args.workload in CONFIGS_1D else "c1d_main"]
+    if args.mode:
+        cfg = cfg.with_(mode=args.mode)
+    dev = torch.device("cuda:0")
+    inp = make_1d_inputs(cfg)
+    d = tb.Desc1d(cfg.N, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil, cfg.mode, cfg.dtype)
+    lo = tb.tconv1d_out_len(d)
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    x, gy = up(inp["x"]), up(inp["gy"])
+    w_min = up(inp["w_min"])
+    w_max = w_min if cfg.mode == "compound" else up(inp["w_max"])
+    do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
+    osh = (cfg.N, cfg.C_out, lo)
+    new = lambda dt=torch.float32: torch.empty(osh, device=dev, dtype=dt)
+    y, y_min, y_max = new(), (new() if do_min else None), (new() if do_max else None)
+    i_min, i_max = (new(torch.int32) if do_min else None), (new(torch.int32) if do_max else None)
+    gx = torch.empty_like(x)
+    wshape = (cfg.C_out, cfg.C_in, cfg.K)
+    g1 = torch.empty(wshape, device=dev) if do_min else None
+    g2 = torch.empty(wshape, device=dev) if (do_max and cfg.mode != "compound") else None
+    fwd = lambda: tb.tconv1d_forward(d, x, w_min, w_max, None, None, y, y_min, y_max, i_min, i_max)
+    bwd_i = lambda: tb.tconv1d_backward_input(d, gy, None, None, i_min, i_max, gx)
+    bwd_w = lambda: tb.tconv1d_backward_weight(d, gy, None, None, i_min, i_max, g1, g2)
+    for _ in range(args.warmup):
+        fwd(); bwd_i(); bwd_w()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(); fwd(); e[1].record(); bwd_i(); e[2].record(); bwd_w(); e[3].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
+    t_bi = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
+    t_bw = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    ms_step = wall * 1e3 / args.steps
+    pairs = cfg.pairs
+    achieved = pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode)) / (t_f * 1e-3)
+    out = {
+        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step (one-dimensional layer)",
+        "value": round(pairs / (ms_step * 1e-3) / 1e9, 2), "unit": "GOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: x[{cfg.N},{cfg.C_in},{cfg.L}] -> {cfg.C_out}ch k{cfg.K} s{cfg.stride} "
+                               f"p{cfg.pad} d{cfg.dil} {cfg.mode} f32, fwd+bwd_input+bwd_weight",
+                   "pairs_per_step": pairs, "forward_kernel": tb.tconv1d_forward_kernel_name(d)},
+        "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
+        "ms_forward": round(t_f, 4), "ms_backward_input": round(t_bi, 4), "ms_backward_weight": round(t_bw, 4),
+        "roofline": {"bound": "alu", "kernel": "forward", "achieved": round(achieved / 1e12, 3),
+                     "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
+                     "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import tconv1d_oracle as o1
+        from oracle import tconv_oracle as orc
+
+        def run(n_img):
+            t = time.perf_counter()
+            s = o1.Shape1d(n_img, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil)
+            r = o1.forward(s, cfg.mode, inp["x"][:n_img], inp["w_min"], inp["w_max"])
+            o1.backward(s, cfg.mode, inp["gy"][:n_img], r["idx_min"], r["idx_max"])
+            return time.perf_counter() - t
+
+        t1 = run(1)
+        n_img = int(max(1, min(cfg.N, args.cpu_seconds / max(t1, 1e-6))))
+        reps, total = 0, 0.0
+        while reps == 0 or (total < args.cpu_seconds and reps < 50):
+            total += run(n_img)
+            reps += 1
+        out["cpu_baseline"] = {"value": round(pairs / cfg.N * n_img * reps / total / 1e9, 3), "unit": "GOPS",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {n_img} of {cfg.N} signals of the same layer, forward + backward, "
+                                         f"{reps} repetitions, {total:.1f} s of wall time"}
     print(json.dumps(out), flush=True)
     return 0
 

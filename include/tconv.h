@@ -228,6 +228,41 @@ int tconv_depthwise_backward(const tconv_desc* desc, const void* x, const void* 
 /* Name of the forward kernel tconv_depthwise_forward selects: "dw_tiled3x3", "dw_rows3x3" or "dw_generic".  Host only. */
 const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc);
 
+/*
+ * One-dimensional layers (Sec. 3.2, one-dimensional base operators MinPlus1d / MaxPlus1d and layers (iii) - (vi);
+ * Sec. 3.3 compound / parallel): the same operator family on x [N, C_in, L] with kernels [C_out, C_in, K] and
+ * outputs [N, C_out, L_out], L_out = floor((L + 2*pad - dil*(K-1) - 1)/stride) + 1.  The saved winner is the
+ * flattened tap k = c*K + i.  Every argument has the meaning, the rules and the error behaviour of its
+ * two-dimensional counterpart above (tconv_out_shape, tconv_workspace_bytes, tconv_forward,
+ * tconv_backward_input, tconv_backward_weight, tconv_forward_kernel_name); the Sum-channel and depthwise entry
+ * points take a one-dimensional layer as the two-dimensional one with H = 1, KH = 1.
+ * These calls only choose a two-dimensional view of the same memory: in general the one-row image
+ * [N, C_in, 1, L] with a 1 x K kernel; for K = 3, dil = 1, stride 1 or 2, pad <= 1, C_in a multiple of 3 and a
+ * full-window mode the image [N, C_in/3, 3, L] with a 3 x 3 kernel and no vertical padding, whose three rows are
+ * three consecutive channels: same candidates, same k, and the tiled 3 x 3 kernels apply.
+ */
+typedef struct tconv1d_desc {
+  int32_t N, C_in, L;       /* input  [N, C_in, L]                    */
+  int32_t C_out, K;         /* kernel [C_out, C_in, K]                */
+  int32_t stride, pad, dil;
+  int32_t mode;             /* enum tconv_mode                        */
+  int32_t dtype;            /* enum tconv_dtype                       */
+} tconv1d_desc;
+
+int tconv1d_out_len(const tconv1d_desc* desc, int32_t* L_out);
+int tconv1d_workspace_bytes(const tconv1d_desc* desc, int32_t op, size_t* bytes);
+int tconv1d_forward(const tconv1d_desc* desc, const void* x, const void* w_min, const void* w_max,
+                    const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                    int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+int tconv1d_backward_input(const tconv1d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                           const int32_t* idx_min, const int32_t* idx_max, float* grad_x, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+int tconv1d_backward_weight(const tconv1d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                            const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                            float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream);
+const char* tconv1d_forward_kernel_name(const tconv1d_desc* desc);
+
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */
 const char* tconv_status_string(int status);
 

@@ -20,7 +20,9 @@ OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",
            "tconv_backward_weight", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
            "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
-           "tconv_depthwise_forward_kernel_name", "tconv_status_string", "tconv_forward_kernel_name")
+           "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
+           "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
+           "tconv_status_string", "tconv_forward_kernel_name")
 
 
 class TconvError(RuntimeError):
@@ -33,6 +35,28 @@ class tconv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "C_in", "H", "W", "C_out", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
         "dil_h", "dil_w", "mode", "dtype")]
+
+
+class tconv1d_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C_in", "L", "C_out", "K", "stride", "pad", "dil", "mode", "dtype")]
+
+
+@dataclass(frozen=True)
+class Desc1d:
+    N: int
+    C_in: int
+    L: int
+    C_out: int
+    K: int
+    stride: int = 1
+    pad: int = 0
+    dil: int = 1
+    mode: str = "max"
+    dtype: str = "f32"
+
+    def c(self) -> tconv1d_desc:
+        return tconv1d_desc(self.N, self.C_in, self.L, self.C_out, self.K, self.stride, self.pad, self.dil,
+                            MODES[self.mode], DTYPES[self.dtype])
 
 
 @dataclass(frozen=True)
@@ -90,6 +114,17 @@ def load() -> ctypes.CDLL:
         lib.tconv_depthwise_backward.argtypes = [D] + [P] * 13 + [ctypes.c_size_t, P]
         lib.tconv_depthwise_forward_kernel_name.argtypes = [D]
         lib.tconv_depthwise_forward_kernel_name.restype = ctypes.c_char_p
+        D1 = ctypes.POINTER(tconv1d_desc)
+        lib.tconv1d_out_len.argtypes = [D1, I32P]
+        lib.tconv1d_workspace_bytes.argtypes = [D1, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
+        lib.tconv1d_forward.argtypes = [D1] + [P] * 11 + [ctypes.c_size_t, P]
+        lib.tconv1d_backward_input.argtypes = [D1] + [P] * 7 + [ctypes.c_size_t, P]
+        lib.tconv1d_backward_weight.argtypes = [D1] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv1d_forward_kernel_name.argtypes = [D1]
+        lib.tconv1d_forward_kernel_name.restype = ctypes.c_char_p
+        for f in ("tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward", "tconv1d_backward_input",
+                  "tconv1d_backward_weight"):
+            getattr(lib, f).restype = ctypes.c_int
         lib.tconv_status_string.argtypes = [ctypes.c_int]
         lib.tconv_status_string.restype = ctypes.c_char_p
         lib.tconv_forward_kernel_name.argtypes = [D]
@@ -227,3 +262,47 @@ def tconv_depthwise_forward_kernel_name(desc: Desc) -> str:
     cd = desc.c()
     r = load().tconv_depthwise_forward_kernel_name(ctypes.byref(cd))
     return r.decode() if r else ""
+
+
+def tconv1d_out_len(desc: Desc1d) -> int:
+    lo = ctypes.c_int32()
+    cd = desc.c()
+    _check(load().tconv1d_out_len(ctypes.byref(cd), ctypes.byref(lo)), "tconv1d_out_len")
+    return int(lo.value)
+
+
+def tconv1d_workspace_bytes(desc: Desc1d, op: str) -> int:
+    n = ctypes.c_size_t()
+    cd = desc.c()
+    _check(load().tconv1d_workspace_bytes(ctypes.byref(cd), OPS[op], ctypes.byref(n)), "tconv1d_workspace_bytes")
+    return int(n.value)
+
+
+def tconv1d_forward(desc: Desc1d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max,
+                    workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv1d_forward(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha), _ptr(beta),
+                                  _ptr(y), _ptr(y_min), _ptr(y_max), _ptr(idx_min), _ptr(idx_max),
+                                  _ptr(workspace), wsz, _stream()), "tconv1d_forward")
+
+
+def tconv1d_backward_input(desc: Desc1d, gy, alpha, beta, idx_min, idx_max, grad_x) -> None:
+    cd = desc.c()
+    _check(load().tconv1d_backward_input(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
+                                         _ptr(idx_max), _ptr(grad_x), None, 0, _stream()), "tconv1d_backward_input")
+
+
+def tconv1d_backward_weight(desc: Desc1d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max) -> None:
+    cd = desc.c()
+    _check(load().tconv1d_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
+                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), None, 0, _stream()),
+           "tconv1d_backward_weight")
+
+
+def tconv1d_forward_kernel_name(desc: Desc1d) -> str:
+    cd = desc.c()
+    r = load().tconv1d_forward_kernel_name(ctypes.byref(cd))
+    if r is None:
+        raise TconvError(-1, "tconv1d_forward_kernel_name")
+    return r.decode()

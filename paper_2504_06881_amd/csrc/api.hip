@@ -259,6 +259,77 @@ const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc) {
   return depthwise_forward_kernel_name(p);
 }
 
+// The two-dimensional view of a one-dimensional layer (same memory, same flattened tap numbers).
+static int view_2d(const tconv1d_desc* d, tconv_desc* v) {
+  if (!d) return TCONV_E_INVAL;
+  if (d->N < 1 || d->C_in < 1 || d->L < 1 || d->C_out < 1 || d->K < 1 || d->stride < 1 || d->dil < 1 || d->pad < 0)
+    return TCONV_E_INVAL;
+  const bool full_window = d->mode >= TCONV_MAX && d->mode <= TCONV_PARALLEL;
+  // three consecutive channels as the three rows of an image: the 3 x 3 window of "channel" c' covers the taps
+  // of channels 3c', 3c'+1, 3c'+2, and k = ((c'*3 + i)*3 + j) = (3c' + i)*3 + j is the 1-D tap number
+  const bool rows3 = full_window && d->K == 3 && d->dil == 1 && (d->stride == 1 || d->stride == 2) && d->pad <= 1 &&
+                     d->C_in % 3 == 0;
+  if (rows3) {
+    const tconv_desc t = {d->N, d->C_in / 3, 3, d->L, d->C_out, 3, 3, d->stride, d->stride, 0, d->pad, 1, 1, d->mode,
+                          d->dtype};
+    *v = t;
+  } else {
+    const tconv_desc t = {d->N, d->C_in, 1, d->L, d->C_out, 1, d->K, 1, d->stride, 0, d->pad, 1, d->dil, d->mode,
+                          d->dtype};
+    *v = t;
+  }
+  return TCONV_OK;
+}
+
+int tconv1d_out_len(const tconv1d_desc* desc, int32_t* L_out) {
+  tconv_desc v;
+  int32_t ho = 0;
+  const int rc = view_2d(desc, &v);
+  return rc != TCONV_OK ? rc : tconv_out_shape(&v, &ho, L_out);
+}
+
+int tconv1d_workspace_bytes(const tconv1d_desc* desc, int32_t op, size_t* bytes) {
+  tconv_desc v;
+  const int rc = view_2d(desc, &v);
+  return rc != TCONV_OK ? rc : tconv_workspace_bytes(&v, op, bytes);
+}
+
+int tconv1d_forward(const tconv1d_desc* desc, const void* x, const void* w_min, const void* w_max,
+                    const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                    int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  tconv_desc v;
+  const int rc = view_2d(desc, &v);
+  if (rc != TCONV_OK) return rc;
+  return tconv_forward(&v, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int tconv1d_backward_input(const tconv1d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                           const int32_t* idx_min, const int32_t* idx_max, float* grad_x, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  tconv_desc v;
+  const int rc = view_2d(desc, &v);
+  if (rc != TCONV_OK) return rc;
+  return tconv_backward_input(&v, gy, alpha, beta, idx_min, idx_max, grad_x, workspace, workspace_bytes, hip_stream);
+}
+
+int tconv1d_backward_weight(const tconv1d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                            const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                            float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  tconv_desc v;
+  const int rc = view_2d(desc, &v);
+  if (rc != TCONV_OK) return rc;
+  return tconv_backward_weight(&v, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max, workspace,
+                               workspace_bytes, hip_stream);
+}
+
+const char* tconv1d_forward_kernel_name(const tconv1d_desc* desc) {
+  tconv_desc v;
+  if (view_2d(desc, &v) != TCONV_OK) return nullptr;
+  return tconv_forward_kernel_name(&v);
+}
+
 const char* tconv_status_string(int status) {
   switch (status) {
     case TCONV_OK: return "ok";

@@ -209,3 +209,73 @@ def make_depthwise_inputs(cfg: LayerCfg, coef: Optional[str] = "random", integer
     else:
         w_min, w_max = w1, w2
     return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)
+
+
+# One-dimensional layers: shapes of 1-D LeNet-style audio classifiers (raw waveform in, a long first kernel
+# with stride 4, then short kernels on a few thousand positions).
+@dataclass(frozen=True)
+class Layer1dCfg:
+    name: str
+    N: int
+    C_in: int
+    L: int
+    C_out: int
+    K: int = 3
+    stride: int = 1
+    pad: int = 1
+    dil: int = 1
+    mode: str = "max"
+    dtype: str = "f32"
+    seed: int = 0
+    w_range: float = 1.0
+
+    @property
+    def L_out(self) -> int:
+        return (self.L + 2 * self.pad - self.dil * (self.K - 1) - 1) // self.stride + 1
+
+    @property
+    def pairs(self) -> int:
+        return self.N * self.C_out * self.L_out * self.C_in * self.K * (2 if self.mode in ("compound", "parallel") else 1)
+
+    def with_(self, **kw) -> "Layer1dCfg":
+        return replace(self, **kw)
+
+
+CONFIGS_1D: Dict[str, Layer1dCfg] = {c.name: c for c in [
+    Layer1dCfg("c1d_small", 2, 6, 100, 8, mode="compound", seed=90),
+    Layer1dCfg("c1d_main", 64, 96, 8000, 96, mode="compound", seed=91, w_range=0.1),
+    Layer1dCfg("c1d_stem", 64, 1, 32000, 64, K=80, stride=4, pad=38, mode="compound", seed=92, w_range=0.1),
+]}
+
+
+def make_1d_inputs(cfg: Layer1dCfg, alpha_beta: Optional[str] = None, integer: bool = False):
+    """x [N, C_in, L], kernels [C_out, C_in, K] (assigned to the modes as make_inputs does), gy, alpha / beta."""
+    rng = np.random.Generator(np.random.PCG64(cfg.seed))
+    xs, ws = (cfg.N, cfg.C_in, cfg.L), (cfg.C_out, cfg.C_in, cfg.K)
+    if integer:
+        draw_x = lambda: rng.integers(-4, 5, size=xs).astype(np.float32)
+        draw_w = lambda: rng.integers(-4, 5, size=ws).astype(np.float32)
+    else:
+        draw_x = lambda: rng.standard_normal(size=xs, dtype=np.float32)
+        draw_w = lambda: ((rng.random(size=ws, dtype=np.float32) * 2 - 1) * np.float32(cfg.w_range)).astype(np.float32)
+    x, w1 = draw_x(), draw_w()
+    w2 = draw_w() if cfg.mode == "parallel" else None
+    gy = rng.standard_normal(size=(cfg.N, cfg.C_out, cfg.L_out), dtype=np.float32)
+    alpha = beta = None
+    if alpha_beta == "random" and cfg.mode in ("compound", "parallel"):
+        alpha = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+        beta = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+    if cfg.dtype == "bf16":
+        x, w1 = to_bf16_grid(x), to_bf16_grid(w1)
+        w2 = to_bf16_grid(w2) if w2 is not None else None
+    x, w1 = _no_neg_zero(x), _no_neg_zero(w1)
+    w2 = _no_neg_zero(w2) if w2 is not None else None
+    if cfg.mode in ("max", "maxplus_min"):
+        w_min, w_max = None, w1
+    elif cfg.mode in ("min", "minplus_max"):
+        w_min, w_max = w1, None
+    elif cfg.mode == "compound":
+        w_min = w_max = w1
+    else:
+        w_min, w_max = w1, w2
+    return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)

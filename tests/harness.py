@@ -295,3 +295,64 @@ def assert_dw_close(hip, ref, mode, what="", backward=True):
             if ref.get(k) is None:
                 continue
             assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+
+
+# ---------------------------------------------------------------- one-dimensional layers
+
+def run_oracle_1d(cfg, inp, backward=True):
+    from oracle import tconv1d_oracle as o1
+    s = o1.Shape1d(cfg.N, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil)
+    r = o1.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"])
+    if cfg.dtype == "bf16":   # storage rounding of the outputs, as the library stores them
+        import torch
+        for k in ("y", "y_min", "y_max"):
+            if r[k] is not None:
+                r[k] = torch.from_numpy(r[k]).to(torch.bfloat16).float().numpy()
+    if backward:
+        kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"])
+        r.update(o1.backward(s, cfg.mode, inp["gy"], alpha=inp["alpha"], beta=inp["beta"], **kw))
+        ab = {k: (None if inp[k] is None else np.abs(inp[k])) for k in ("alpha", "beta")}
+        sc = o1.backward(s, cfg.mode, np.abs(inp["gy"]), alpha=ab["alpha"], beta=ab["beta"], **kw)
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+    return r
+
+
+def run_hip_1d(cfg, inp, backward=True, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    d = tb.Desc1d(cfg.N, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil, cfg.mode, cfg.dtype)
+    lo = tb.tconv1d_out_len(d)
+    assert lo == cfg.L_out
+
+    def up(a, dt=torch.float32):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
+
+    x = up(inp["x"], tdt)
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"], tdt)
+    else:
+        w_min, w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
+    alpha, beta, gy = up(inp["alpha"]), up(inp["beta"]), up(inp["gy"])
+    oshape = (cfg.N, cfg.C_out, lo)
+    do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
+    nanf = lambda: torch.full(oshape, float("nan"), device=dev, dtype=tdt)
+    bad = lambda: torch.full(oshape, -12345, device=dev, dtype=torch.int32)
+    y, y_min, y_max = nanf(), (nanf() if do_min else None), (nanf() if do_max else None)
+    idx_min, idx_max = (bad() if do_min else None), (bad() if do_max else None)
+    wsz = tb.tconv1d_workspace_bytes(d, "forward")
+    ws = torch.empty(max(wsz, 1), device=dev, dtype=torch.uint8) if wsz else None
+    tb.tconv1d_forward(d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max, ws)
+    out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
+    if backward:
+        gx = torch.full((cfg.N, cfg.C_in, cfg.L), float("nan"), device=dev)
+        tb.tconv1d_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+        wshape = (cfg.C_out, cfg.C_in, cfg.K)
+        gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if (do_max and cfg.mode != "compound") else None
+        tb.tconv1d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else (v.float() if v.dtype == torch.bfloat16 else v).cpu().numpy())
+            for k, v in out.items()}

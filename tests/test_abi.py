@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "tconv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tconv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(tconv[0-9a-z]*_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -73,3 +73,21 @@ def test_compute_entry_points_reject_null_before_touching_the_gpu():
     assert lib.tconv_backward_weight(ctypes.byref(cd), *([None] * 8), 0, None) == -1
     assert lib.tconv_backward_alpha_beta(ctypes.byref(cd), *([None] * 6), 0, None) == -1
     assert lib.tconv_forward(None, *([None] * 11), 0, None) == -1
+
+
+def test_one_dimensional_descriptor_views():
+    """Host-only calls of the 1-D entry points: output length, validation, and which 2-D kernel a layer maps to."""
+    assert tb.tconv1d_out_len(tb.Desc1d(2, 6, 100, 8, 3, pad=1)) == 100
+    assert tb.tconv1d_out_len(tb.Desc1d(2, 1, 32000, 8, 80, stride=4, pad=38)) == 8000
+    assert tb.tconv1d_out_len(tb.Desc1d(2, 5, 50, 8, 3, stride=2, pad=1, dil=2)) == 24
+    # K = 3, C_in a multiple of 3, full-window mode: three channels become the three rows of a 3 x 3 window
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="compound")) == "tiled3x3"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, stride=2, pad=1, mode="max")) == "tiled3x3"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 95, 4000, 64, 3, pad=1, mode="compound")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="minplus_max")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=2, mode="compound")) == "generic"
+    for bad, code in [(tb.Desc1d(0, 3, 16, 8, 3), -1), (tb.Desc1d(1, 3, 16, 8, 3, stride=0), -1),
+                      (tb.Desc1d(1, 3, 2, 8, 3), -2), (tb.Desc1d(1, 3, 16, 8, 3, pad=3), -2)]:
+        with pytest.raises(tb.TconvError) as e:
+            tb.tconv1d_out_len(bad)
+        assert e.value.status == code, bad
