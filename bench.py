@@ -32,6 +32,16 @@ LANE_OPS_PER_S = N_CU * 64 * CLOCK_HZ           # one fp32 VALU lane-instruction
 HBM_PEAK_GBS = 8000.0
 
 
+# HBM-side bytes per launch of the forward kernel (fetched + written), measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this script and scaled by what a plain device copy reads on the same counters; the
+# summaries under profiles/ give the commands and the raw figures.  Keyed by (workload, mode, op).
+MEASURED_FORWARD_TRAFFIC = {
+    ("cfg2_main", "compound", "full"): 317.0e6 + 167.8e6,
+    ("cfg4a", "compound", "full"): 1547.0e6 + 335.6e6,
+    ("cfg2_main", "minplus_max", "full"): 294.9e6 + 100.7e6,
+}
+
+
 def alu_peak_pairs_per_s(mode: str) -> float:
     """Plain fp32 VALU roofline in pairs/s: one v_add_f32 and one v_max/min_f32 per pair,
     except compound where one add feeds both branches (3 lane-instructions per 2 pairs)."""
@@ -231,7 +241,8 @@ def main() -> int:
                      "achieved": round(achieved / 1e12, 3),
                      "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
                      "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
-                     "traffic": None},
+                     "traffic": (MEASURED_FORWARD_TRAFFIC.get((cfgs[0].name, cfgs[0].mode, args.op))
+                                 if len(cfgs) == 1 and cfgs[0].dtype == "f32" else None)},
     }
 
     if not args.no_cpu_baseline:
