@@ -3,7 +3,7 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input:
 tconv_forward + tconv_backward_input + tconv_backward_weight of the headline
-layer (benchmark configs[1]: x [128,64,32,32] -> 64 channels, 3x3, stride 1,
+layer (the CIFAR-scale ResNet block layer: x [128,64,32,32] -> 64 channels, 3x3, stride 1,
 pad 1, compound mode, fp32), inputs resident in HBM before the timed region.
 
 Prints ONE JSON line:
@@ -88,7 +88,7 @@ def main() -> int:
         return bench_1d(args, torch, tb)
     from paper_2504_06881_amd.inputs import resnet20_layers
     if args.workload == "cfg5":
-        # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (benchmark configs[4]);
+        # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (the end-to-end configuration);
         # the batch-norm / residual glue of the net is not part of the hot path and is not run
         cfgs = resnet20_layers(256)
         wl_name = "cfg5: the 19 parallel-mode 3x3 layers of a ResNet-20-style net on x[256,3,32,32], f32"
