@@ -263,6 +263,34 @@ int tconv1d_backward_weight(const tconv1d_desc* desc, const float* gy, const flo
                             float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream);
 const char* tconv1d_forward_kernel_name(const tconv1d_desc* desc);
 
+/*
+ * Three-dimensional layers (Sec. 3.2, three-dimensional base operators MinPlus3d / MaxPlus3d and layers (iii) - (vi);
+ * Sec. 3.3 compound / parallel), fp32 only (TCONV_E_UNSUPPORTED for bf16): x [N, C_in, D, H, W], kernels
+ * [C_out, C_in, KD, KH, KW], outputs [N, C_out, D_out, H_out, W_out]; per axis
+ * out = floor((in + 2*pad - dil*(k-1) - 1)/stride) + 1.  The saved winner is the flattened tap
+ * k = ((c*KD + a)*KH + i)*KW + j.  Arguments, rules and error behaviour as for tconv_out_shape, tconv_forward,
+ * tconv_backward_input and tconv_backward_weight; no workspace is needed.
+ */
+typedef struct tconv3d_desc {
+  int32_t N, C_in, D, H, W;      /* input  [N, C_in, D, H, W]            */
+  int32_t C_out, KD, KH, KW;     /* kernel [C_out, C_in, KD, KH, KW]     */
+  int32_t stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w;
+  int32_t mode;                  /* enum tconv_mode                      */
+  int32_t dtype;                 /* enum tconv_dtype                     */
+} tconv3d_desc;
+
+int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, int32_t* W_out);
+int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, const void* w_max,
+                    const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                    int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+int tconv3d_backward_input(const tconv3d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                           const int32_t* idx_min, const int32_t* idx_max, float* grad_x, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+int tconv3d_backward_weight(const tconv3d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                            const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                            float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, NUL-terminated description of a tconv_status value.  Host only. */
 const char* tconv_status_string(int status);
 

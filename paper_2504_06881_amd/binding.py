@@ -22,6 +22,7 @@ SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_b
            "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
+           "tconv3d_out_shape", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
            "tconv_status_string", "tconv_forward_kernel_name")
 
 
@@ -35,6 +36,34 @@ class tconv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "C_in", "H", "W", "C_out", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
         "dil_h", "dil_w", "mode", "dtype")]
+
+
+class tconv3d_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "N", "C_in", "D", "H", "W", "C_out", "KD", "KH", "KW", "stride_d", "stride_h", "stride_w",
+        "pad_d", "pad_h", "pad_w", "dil_d", "dil_h", "dil_w", "mode", "dtype")]
+
+
+@dataclass(frozen=True)
+class Desc3d:
+    N: int
+    C_in: int
+    D: int
+    H: int
+    W: int
+    C_out: int
+    KD: int
+    KH: int
+    KW: int
+    stride: Tuple[int, int, int] = (1, 1, 1)
+    pad: Tuple[int, int, int] = (0, 0, 0)
+    dil: Tuple[int, int, int] = (1, 1, 1)
+    mode: str = "max"
+    dtype: str = "f32"
+
+    def c(self) -> tconv3d_desc:
+        return tconv3d_desc(self.N, self.C_in, self.D, self.H, self.W, self.C_out, self.KD, self.KH, self.KW,
+                            *self.stride, *self.pad, *self.dil, MODES[self.mode], DTYPES[self.dtype])
 
 
 class tconv1d_desc(ctypes.Structure):
@@ -124,6 +153,13 @@ def load() -> ctypes.CDLL:
         lib.tconv1d_forward_kernel_name.restype = ctypes.c_char_p
         for f in ("tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward", "tconv1d_backward_input",
                   "tconv1d_backward_weight"):
+            getattr(lib, f).restype = ctypes.c_int
+        D3 = ctypes.POINTER(tconv3d_desc)
+        lib.tconv3d_out_shape.argtypes = [D3, I32P, I32P, I32P]
+        lib.tconv3d_forward.argtypes = [D3] + [P] * 11 + [ctypes.c_size_t, P]
+        lib.tconv3d_backward_input.argtypes = [D3] + [P] * 7 + [ctypes.c_size_t, P]
+        lib.tconv3d_backward_weight.argtypes = [D3] + [P] * 8 + [ctypes.c_size_t, P]
+        for f in ("tconv3d_out_shape", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight"):
             getattr(lib, f).restype = ctypes.c_int
         lib.tconv_status_string.argtypes = [ctypes.c_int]
         lib.tconv_status_string.restype = ctypes.c_char_p
@@ -306,3 +342,31 @@ def tconv1d_forward_kernel_name(desc: Desc1d) -> str:
     if r is None:
         raise TconvError(-1, "tconv1d_forward_kernel_name")
     return r.decode()
+
+
+def tconv3d_out_shape(desc: Desc3d) -> Tuple[int, int, int]:
+    do, ho, wo = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    cd = desc.c()
+    _check(load().tconv3d_out_shape(ctypes.byref(cd), ctypes.byref(do), ctypes.byref(ho), ctypes.byref(wo)),
+           "tconv3d_out_shape")
+    return int(do.value), int(ho.value), int(wo.value)
+
+
+def tconv3d_forward(desc: Desc3d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max) -> None:
+    cd = desc.c()
+    _check(load().tconv3d_forward(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha), _ptr(beta),
+                                  _ptr(y), _ptr(y_min), _ptr(y_max), _ptr(idx_min), _ptr(idx_max), None, 0,
+                                  _stream()), "tconv3d_forward")
+
+
+def tconv3d_backward_input(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, grad_x) -> None:
+    cd = desc.c()
+    _check(load().tconv3d_backward_input(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
+                                         _ptr(idx_max), _ptr(grad_x), None, 0, _stream()), "tconv3d_backward_input")
+
+
+def tconv3d_backward_weight(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max) -> None:
+    cd = desc.c()
+    _check(load().tconv3d_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
+                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), None, 0, _stream()),
+           "tconv3d_backward_weight")

@@ -330,6 +330,110 @@ const char* tconv1d_forward_kernel_name(const tconv1d_desc* desc) {
   return tconv_forward_kernel_name(&v);
 }
 
+// Validates a three-dimensional descriptor and fills the launch-time view.
+static int make_params3(const tconv3d_desc* d, Params3* p) {
+  if (!d) return TCONV_E_INVAL;
+  if (d->N < 1 || d->C_in < 1 || d->D < 1 || d->H < 1 || d->W < 1 || d->C_out < 1 || d->KD < 1 || d->KH < 1 || d->KW < 1)
+    return TCONV_E_INVAL;
+  if (d->stride_d < 1 || d->stride_h < 1 || d->stride_w < 1 || d->dil_d < 1 || d->dil_h < 1 || d->dil_w < 1 ||
+      d->pad_d < 0 || d->pad_h < 0 || d->pad_w < 0)
+    return TCONV_E_INVAL;
+  if (d->mode < TCONV_MAX || d->mode > TCONV_MAXPLUS_MIN) return TCONV_E_INVAL;
+  if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16) return TCONV_E_INVAL;
+  const long long in[3] = {d->D, d->H, d->W}, k[3] = {d->KD, d->KH, d->KW};
+  const long long st[3] = {d->stride_d, d->stride_h, d->stride_w}, pd[3] = {d->pad_d, d->pad_h, d->pad_w};
+  const long long dl[3] = {d->dil_d, d->dil_h, d->dil_w};
+  long long out[3];
+  for (int a = 0; a < 3; ++a) {
+    const long long ext = dl[a] * (k[a] - 1);
+    if (pd[a] > ext) return TCONV_E_SHAPE;  // a window could lie wholly in the padding
+    const long long n = in[a] + 2 * pd[a] - ext - 1;
+    if (n < 0) return TCONV_E_SHAPE;
+    out[a] = n / st[a] + 1;
+  }
+  const long long K = (long long)d->C_in * d->KD * d->KH * d->KW, lim = 0x7fffffffLL;
+  if (K > lim || (long long)d->N * d->C_in * d->D * d->H * d->W > lim ||
+      (long long)d->N * d->C_out * out[0] * out[1] * out[2] > lim || (long long)d->C_out * K > lim)
+    return TCONV_E_SHAPE;
+  if (d->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  p->N = d->N; p->C_in = d->C_in; p->D = d->D; p->H = d->H; p->W = d->W;
+  p->C_out = d->C_out; p->KD = d->KD; p->KH = d->KH; p->KW = d->KW;
+  p->sd = d->stride_d; p->sh = d->stride_h; p->sw = d->stride_w;
+  p->pd = d->pad_d; p->ph = d->pad_h; p->pw = d->pad_w;
+  p->dd = d->dil_d; p->dh = d->dil_h; p->dw = d->dil_w;
+  p->Do = (int)out[0]; p->Ho = (int)out[1]; p->Wo = (int)out[2];
+  p->K = (int)K; p->mode = d->mode;
+  return TCONV_OK;
+}
+
+int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, int32_t* W_out) {
+  Params3 p;
+  const int rc = make_params3(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!D_out || !H_out || !W_out) return TCONV_E_INVAL;
+  *D_out = p.Do; *H_out = p.Ho; *W_out = p.Wo;
+  return TCONV_OK;
+}
+
+int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, const void* w_max,
+                    const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
+                    int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params3 p;
+  const int rc = make_params3(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!x || !y) return TCONV_E_INVAL;
+  FwdArgs a = {x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max};
+  if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (w_min ? w_min : w_max);
+  if (mode_has_min(p.mode) && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
+  if (mode_has_max(p.mode) && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
+  const hipError_t e = launch_forward_3d(p, a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv3d_backward_input(const tconv3d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                           const int32_t* idx_min, const int32_t* idx_max, float* grad_x, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params3 p;
+  const int rc = make_params3(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !grad_x) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  const hipError_t e = launch_backward_input_3d(p, a, grad_x, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv3d_backward_weight(const tconv3d_desc* desc, const float* gy, const float* alpha, const float* beta,
+                            const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                            float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Params3 p3;
+  const int rc = make_params3(desc, &p3);
+  if (rc != TCONV_OK) return rc;
+  if (!gy) return TCONV_E_INVAL;
+  const int mode = backward_mode(p3.mode);
+  if (mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  switch (mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  // The kernel gradient is a histogram of the winners per output channel: it needs the number of outputs per
+  // (image, channel) and the number of taps, not the geometry, so the two-dimensional kernel takes it as is.
+  Params p = {};
+  p.N = p3.N; p.C_out = p3.C_out; p.Ho = p3.Do * p3.Ho; p.Wo = p3.Wo; p.K = p3.K; p.mode = mode;
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
 const char* tconv_status_string(int status) {
   switch (status) {
     case TCONV_OK: return "ok";

@@ -27,6 +27,16 @@ constexpr int backward_mode(int m) {
   return m == TCONV_MINPLUS_MAX ? TCONV_MIN : (m == TCONV_MAXPLUS_MIN ? TCONV_MAX : m);
 }
 
+// Launch-time view of a validated three-dimensional descriptor.
+struct Params3 {
+  int N, C_in, D, H, W;
+  int C_out, KD, KH, KW;
+  int sd, sh, sw, pd, ph, pw, dd, dh, dw;
+  int Do, Ho, Wo;
+  int K;     // C_in*KD*KH*KW
+  int mode;  // enum tconv_mode
+};
+
 struct FwdArgs {
   const void* x;
   const void* w_min;  // kernel of the min-plus branch (compound: the shared kernel)
@@ -124,6 +134,9 @@ hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* g
 hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s);
 hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s);
 const char* sum_forward_kernel_name(const Params& p);
+
+hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s);
+hipError_t launch_backward_input_3d(const Params3& p, const BwdArgs& a, float* grad_x, hipStream_t s);
 
 hipError_t launch_depthwise_forward(const Params& p, const DwArgs& a, hipStream_t s);
 hipError_t launch_depthwise_backward(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s);

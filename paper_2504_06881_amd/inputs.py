@@ -279,3 +279,71 @@ def make_1d_inputs(cfg: Layer1dCfg, alpha_beta: Optional[str] = None, integer: b
     else:
         w_min, w_max = w1, w2
     return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)
+
+
+# Three-dimensional layers: shapes of small volumetric classifiers (voxel grids of a few tens per side).
+@dataclass(frozen=True)
+class Layer3dCfg:
+    name: str
+    N: int
+    C_in: int
+    D: int
+    H: int
+    W: int
+    C_out: int
+    k: tuple = (3, 3, 3)
+    stride: tuple = (1, 1, 1)
+    pad: tuple = (1, 1, 1)
+    dil: tuple = (1, 1, 1)
+    mode: str = "max"
+    seed: int = 0
+    w_range: float = 1.0
+
+    @property
+    def out(self):
+        return tuple((n + 2 * p - d * (kk - 1) - 1) // s + 1
+                     for n, kk, s, p, d in zip((self.D, self.H, self.W), self.k, self.stride, self.pad, self.dil))
+
+    @property
+    def pairs(self) -> int:
+        do, ho, wo = self.out
+        return (self.N * self.C_out * do * ho * wo * self.C_in * self.k[0] * self.k[1] * self.k[2]
+                * (2 if self.mode in ("compound", "parallel") else 1))
+
+    def with_(self, **kw) -> "Layer3dCfg":
+        return replace(self, **kw)
+
+
+CONFIGS_3D: Dict[str, Layer3dCfg] = {c.name: c for c in [
+    Layer3dCfg("c3d_small", 2, 3, 6, 7, 8, 4, mode="compound", seed=120),
+    Layer3dCfg("c3d_main", 32, 16, 28, 28, 28, 32, mode="compound", seed=121, w_range=0.1),
+]}
+
+
+def make_3d_inputs(cfg: Layer3dCfg, alpha_beta: Optional[str] = None, integer: bool = False):
+    """x [N, C_in, D, H, W], kernels [C_out, C_in, KD, KH, KW] (assigned to the modes as make_inputs does), gy,
+    alpha / beta."""
+    rng = np.random.Generator(np.random.PCG64(cfg.seed))
+    xs, ws = (cfg.N, cfg.C_in, cfg.D, cfg.H, cfg.W), (cfg.C_out, cfg.C_in) + tuple(cfg.k)
+    if integer:
+        draw_x = lambda: rng.integers(-4, 5, size=xs).astype(np.float32)
+        draw_w = lambda: rng.integers(-4, 5, size=ws).astype(np.float32)
+    else:
+        draw_x = lambda: rng.standard_normal(size=xs, dtype=np.float32)
+        draw_w = lambda: ((rng.random(size=ws, dtype=np.float32) * 2 - 1) * np.float32(cfg.w_range)).astype(np.float32)
+    x, w1 = _no_neg_zero(draw_x()), _no_neg_zero(draw_w())
+    w2 = _no_neg_zero(draw_w()) if cfg.mode == "parallel" else None
+    gy = rng.standard_normal(size=(cfg.N, cfg.C_out) + cfg.out, dtype=np.float32)
+    alpha = beta = None
+    if alpha_beta == "random" and cfg.mode in ("compound", "parallel"):
+        alpha = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+        beta = (rng.random(cfg.C_out, dtype=np.float32) * 2 - 1).astype(np.float32)
+    if cfg.mode in ("max", "maxplus_min"):
+        w_min, w_max = None, w1
+    elif cfg.mode in ("min", "minplus_max"):
+        w_min, w_max = w1, None
+    elif cfg.mode == "compound":
+        w_min = w_max = w1
+    else:
+        w_min, w_max = w1, w2
+    return dict(x=x, w_min=w_min, w_max=w_max, gy=gy, alpha=alpha, beta=beta)

@@ -356,3 +356,53 @@ def run_hip_1d(cfg, inp, backward=True, device="cuda:0"):
     torch.cuda.synchronize()
     return {k: (None if v is None else (v.float() if v.dtype == torch.bfloat16 else v).cpu().numpy())
             for k, v in out.items()}
+
+
+# ---------------------------------------------------------------- three-dimensional layers
+
+def run_oracle_3d(cfg, inp, backward=True):
+    from oracle import tconv3d_oracle as o3
+    s = o3.Shape3d(cfg.N, cfg.C_in, cfg.D, cfg.H, cfg.W, cfg.C_out, cfg.k[0], cfg.k[1], cfg.k[2], tuple(cfg.stride),
+                   tuple(cfg.pad), tuple(cfg.dil))
+    r = o3.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"])
+    if backward:
+        kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"])
+        r.update(o3.backward(s, cfg.mode, inp["gy"], alpha=inp["alpha"], beta=inp["beta"], **kw))
+        ab = {k: (None if inp[k] is None else np.abs(inp[k])) for k in ("alpha", "beta")}
+        sc = o3.backward(s, cfg.mode, np.abs(inp["gy"]), alpha=ab["alpha"], beta=ab["beta"], **kw)
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+    return r
+
+
+def run_hip_3d(cfg, inp, backward=True, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    d = tb.Desc3d(cfg.N, cfg.C_in, cfg.D, cfg.H, cfg.W, cfg.C_out, cfg.k[0], cfg.k[1], cfg.k[2], tuple(cfg.stride),
+                  tuple(cfg.pad), tuple(cfg.dil), cfg.mode)
+    out3 = tb.tconv3d_out_shape(d)
+    assert out3 == cfg.out
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+    x, gy, alpha, beta = up(inp["x"]), up(inp["gy"]), up(inp["alpha"]), up(inp["beta"])
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"])
+    else:
+        w_min, w_max = up(inp["w_min"]), up(inp["w_max"])
+    oshape = (cfg.N, cfg.C_out) + out3
+    do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
+    nanf = lambda: torch.full(oshape, float("nan"), device=dev)
+    bad = lambda: torch.full(oshape, -12345, device=dev, dtype=torch.int32)
+    y, y_min, y_max = nanf(), (nanf() if do_min else None), (nanf() if do_max else None)
+    idx_min, idx_max = (bad() if do_min else None), (bad() if do_max else None)
+    tb.tconv3d_forward(d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max)
+    out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
+    if backward:
+        gx = torch.full(tuple(inp["x"].shape), float("nan"), device=dev)
+        tb.tconv3d_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+        wshape = (cfg.C_out, cfg.C_in) + tuple(cfg.k)
+        gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if (do_max and cfg.mode != "compound") else None
+        tb.tconv3d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
