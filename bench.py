@@ -56,11 +56,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_main")
-    ap.add_argument("--op", default="full", choices=["full", "sum", "dw", "1d"],
+    ap.add_argument("--op", default="full", choices=["full", "sum", "dw", "1d", "3d"],
                     help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
                          "(tconv_sum_forward / tconv_sum_backward) on the same shapes; dw: the depthwise layers "
                          "(tconv_depthwise_forward / tconv_depthwise_backward; --workload dw_main | dw_s2 | dw_16 | dw_8); "
-                         "1d: the one-dimensional layers (tconv1d_*; --workload c1d_main | c1d_stem)")
+                         "1d: the one-dimensional layers (tconv1d_*; --workload c1d_main | c1d_stem); "
+                         "3d: the three-dimensional layers (tconv3d_*; --workload c3d_main)")
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
@@ -86,6 +87,8 @@ def main() -> int:
         return bench_depthwise(args, torch, tb)
     if args.op == "1d":
         return bench_1d(args, torch, tb)
+    if args.op == "3d":
+        return bench_3d(args, torch, tb)
     from paper_2504_06881_amd.inputs import resnet20_layers
     if args.workload == "cfg5":
         # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (the end-to-end configuration);
@@ -333,6 +336,91 @@ def bench_1d(args, torch, tb) -> int:
         out["cpu_baseline"] = {"value": round(pairs / cfg.N * n_img * reps / total / 1e9, 3), "unit": "GOPS",
                                "cores": orc.num_threads(), "kind": "oracle",
                                "sample": f"first {n_img} of {cfg.N} signals of the same layer, forward + backward, "
+                                         f"{reps} repetitions, {total:.1f} s of wall time"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_3d(args, torch, tb) -> int:
+    """One three-dimensional layer: tconv3d_forward, tconv3d_backward_input, tconv3d_backward_weight per step."""
+    from paper_2504_06881_amd.inputs import CONFIGS_3D, make_3d_inputs
+    cfg = CONFIGS_3D[args.workload if args.workload in CONFIGS_3D else "c3d_main"]
+    if args.mode:
+        cfg = cfg.with_(mode=args.mode)
+    dev = torch.device("cuda:0")
+    inp = make_3d_inputs(cfg)
+    d = tb.Desc3d(cfg.N, cfg.C_in, cfg.D, cfg.H, cfg.W, cfg.C_out, cfg.k[0], cfg.k[1], cfg.k[2], tuple(cfg.stride),
+                  tuple(cfg.pad), tuple(cfg.dil), cfg.mode)
+    out3 = tb.tconv3d_out_shape(d)
+    up = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    x, gy = up(inp["x"]), up(inp["gy"])
+    w_min = up(inp["w_min"])
+    w_max = w_min if cfg.mode == "compound" else up(inp["w_max"])
+    do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
+    osh = (cfg.N, cfg.C_out) + out3
+    new = lambda dt=torch.float32: torch.empty(osh, device=dev, dtype=dt)
+    y, y_min, y_max = new(), (new() if do_min else None), (new() if do_max else None)
+    i_min, i_max = (new(torch.int32) if do_min else None), (new(torch.int32) if do_max else None)
+    gx = torch.empty_like(x)
+    wshape = (cfg.C_out, cfg.C_in) + tuple(cfg.k)
+    g1 = torch.empty(wshape, device=dev) if do_min else None
+    g2 = torch.empty(wshape, device=dev) if (do_max and cfg.mode != "compound") else None
+    fwd = lambda: tb.tconv3d_forward(d, x, w_min, w_max, None, None, y, y_min, y_max, i_min, i_max)
+    bwd_i = lambda: tb.tconv3d_backward_input(d, gy, None, None, i_min, i_max, gx)
+    bwd_w = lambda: tb.tconv3d_backward_weight(d, gy, None, None, i_min, i_max, g1, g2)
+    for _ in range(args.warmup):
+        fwd(); bwd_i(); bwd_w()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(); fwd(); e[1].record(); bwd_i(); e[2].record(); bwd_w(); e[3].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
+    t_bi = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
+    t_bw = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    ms_step = wall * 1e3 / args.steps
+    pairs = cfg.pairs
+    achieved = pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode)) / (t_f * 1e-3)
+    out = {
+        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step (three-dimensional layer)",
+        "value": round(pairs / (ms_step * 1e-3) / 1e9, 2), "unit": "GOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: x[{cfg.N},{cfg.C_in},{cfg.D},{cfg.H},{cfg.W}] -> {cfg.C_out}ch "
+                               f"k{cfg.k} s{cfg.stride} p{cfg.pad} d{cfg.dil} {cfg.mode} f32, fwd+bwd_input+bwd_weight",
+                   "pairs_per_step": pairs, "forward_kernel": "generic3d"},
+        "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
+        "ms_forward": round(t_f, 4), "ms_backward_input": round(t_bi, 4), "ms_backward_weight": round(t_bw, 4),
+        "roofline": {"bound": "alu", "kernel": "forward", "achieved": round(achieved / 1e12, 3),
+                     "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
+                     "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import tconv3d_oracle as o3
+        from oracle import tconv_oracle as orc
+
+        def run(n_img):
+            t = time.perf_counter()
+            s = o3.Shape3d(n_img, cfg.C_in, cfg.D, cfg.H, cfg.W, cfg.C_out, cfg.k[0], cfg.k[1], cfg.k[2],
+                           tuple(cfg.stride), tuple(cfg.pad), tuple(cfg.dil))
+            r = o3.forward(s, cfg.mode, inp["x"][:n_img], inp["w_min"], inp["w_max"])
+            o3.backward(s, cfg.mode, inp["gy"][:n_img], r["idx_min"], r["idx_max"])
+            return time.perf_counter() - t
+
+        t1 = run(1)
+        n_img = int(max(1, min(cfg.N, args.cpu_seconds / max(t1, 1e-6))))
+        reps, total = 0, 0.0
+        while reps == 0 or (total < args.cpu_seconds and reps < 50):
+            total += run(n_img)
+            reps += 1
+        out["cpu_baseline"] = {"value": round(pairs / cfg.N * n_img * reps / total / 1e9, 3), "unit": "GOPS",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"first {n_img} of {cfg.N} volumes of the same layer, forward + backward, "
                                          f"{reps} repetitions, {total:.1f} s of wall time"}
     print(json.dumps(out), flush=True)
     return 0
