@@ -6,10 +6,15 @@
 // pass (consecutive threads own consecutive ow, so reads of x and all writes are coalesced), a scatter with
 // float atomics for the input gradient.  The kernel gradient needs no geometry (it is a histogram of the
 // winners per output channel) and runs on the two-dimensional histogram kernel.  fp32 only.
-#include "tconv_internal.h"
+#include <stdlib.h>
+#include <string.h>
+
+#include "tile_common.h"
 
 namespace tconv {
 namespace {
+
+using namespace tile;
 
 // One pass over the window of every input channel for both branches.  Inside a channel strict compares in
 // ascending tap order keep the lowest tap; across channels strict compares in ascending order keep the lowest
@@ -85,6 +90,204 @@ __global__ __launch_bounds__(256) void fwd3d_kernel(Params3 p, const float* __re
   }
 }
 
+
+// ---------------------------------------------------------------------------------- 3 x 3 x 3, stride 1, dilation 1
+
+// Register-resident kernel for the common volumetric window.  A lane owns 4 consecutive outputs of one row and
+// TN3 = 4 output channels (the 4 waves of a workgroup take different channel groups of the same outputs, so
+// their input lines meet in the L1); per input channel it loads the 9 input rows under its outputs once
+// (3 depths x 3 heights x 6 columns, padding as NaN, which v_max3 / v_min3 ignore) and reuses them for 27 taps x
+// 4 outputs x 4 channels.  Kernel values are wave-uniform (scalar loads).  The loop tracks the winning ROW of
+// three taps (channel, depth tap, height tap: one v_min3 / v_max3, one compare and one select per row, output
+// and branch, strict compares in ascending order); afterwards only the three taps of that row are looked at
+// again and the first that equals the extremum is the winner.  (Tracking just the channel, as the
+// two-dimensional kernel does, costs 27 scattered loads per output and branch afterwards, which at the
+// few channels of volumetric nets outweighs the loop.)  Full-window modes, horizontal padding 0 or 1.
+constexpr int TN3 = 4;
+
+__device__ __forceinline__ unsigned fast_div3(unsigned u, unsigned inv) { return inv ? __umulhi(u, inv) : u; }
+
+template <int MODE>
+__global__ __launch_bounds__(WAVES * 64) void fwd3d_k3_kernel(Params3 p, const float* __restrict__ x,
+                                                              const float* __restrict__ w_min,
+                                                              const float* __restrict__ w_max,
+                                                              const float* __restrict__ alpha,
+                                                              const float* __restrict__ beta, float* __restrict__ y,
+                                                              float* __restrict__ y_min, float* __restrict__ y_max,
+                                                              int32_t* __restrict__ idx_min,
+                                                              int32_t* __restrict__ idx_max, int segs,
+                                                              unsigned n_units, unsigned inv_segs, unsigned inv_ho,
+                                                              unsigned inv_do) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int co0 = (blockIdx.y * WAVES + wave) * TN3;
+  if (co0 >= p.C_out) return;  // whole wave; the kernel has no barrier
+  const unsigned u_raw = blockIdx.x * 64u + lane;
+  const bool unit_ok = u_raw < n_units;
+  const unsigned u = unit_ok ? u_raw : n_units - 1;  // surplus lanes recompute the last unit and store nothing
+  const unsigned t1 = fast_div3(u, inv_segs);
+  const int seg = (int)(u - t1 * (unsigned)segs);
+  const unsigned t2 = fast_div3(t1, inv_ho);
+  const int oh = (int)(t1 - t2 * (unsigned)p.Ho);
+  const unsigned n = fast_div3(t2, inv_do);
+  const int od = (int)(t2 - n * (unsigned)p.Do);
+  const int ow0 = min(seg * 4, p.Wo - 4);
+  const int first_q = unit_ok ? seg * 4 - ow0 : 4;
+
+  // channel-independent addressing: 9 rows (depth a, height i), 6 columns
+  const size_t vol = (size_t)p.D * p.H * p.W;
+  const float* xn = x + (size_t)n * p.C_in * vol;
+  int roff[9];
+  bool rok[9];
+#pragma unroll
+  for (int a = 0; a < 3; ++a)
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int id = od - p.pd + a, ih = oh - p.ph + i;
+      rok[a * 3 + i] = (id >= 0 && id < p.D && ih >= 0 && ih < p.H);
+      roff[a * 3 + i] = (min(max(id, 0), p.D - 1) * p.H + min(max(ih, 0), p.H - 1)) * p.W;
+    }
+  int coff[6];
+  bool cok[6];
+#pragma unroll
+  for (int k = 0; k < 6; ++k) {
+    const int iw = ow0 - p.pw + k;
+    cok[k] = (iw >= 0 && iw < p.W);
+    coff[k] = min(max(iw, 0), p.W - 1);
+  }
+
+  const int core0 = ow0 - p.pw + 1;  // first of the four columns that are always in range
+
+  float bmax[TN3][4], bmin[TN3][4];
+  int cmax[TN3][4], cmin[TN3][4];  // winning row: channel * 9 + depth tap * 3 + height tap
+#pragma unroll
+  for (int c = 0; c < TN3; ++c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bmax[c][q] = -INFINITY; bmin[c][q] = INFINITY;
+      cmax[c][q] = 0; cmin[c][q] = 0;
+    }
+
+  for (int ci = 0; ci < p.C_in; ++ci) {
+    const float* xc = xn + (size_t)ci * vol;
+    float xs[9][6];
+#pragma unroll
+    for (int r = 0; r < 9; ++r) {
+      // columns 1..4 (the pixels themselves shifted by 1 - pw) always lie inside the row for pw <= 1
+      const f4u core = *(const f4u*)(xc + roff[r] + core0);
+      const float h0 = xc[roff[r] + coff[0]], h5 = xc[roff[r] + coff[5]];
+      const float nan = __uint_as_float(0x7fc00000u);
+      xs[r][0] = (rok[r] && cok[0]) ? h0 : nan;
+      xs[r][1] = rok[r] ? core.x : nan;
+      xs[r][2] = rok[r] ? core.y : nan;
+      xs[r][3] = rok[r] ? core.z : nan;
+      xs[r][4] = rok[r] ? core.w : nan;
+      xs[r][5] = (rok[r] && cok[5]) ? h5 : nan;
+    }
+#pragma unroll
+    for (int c = 0; c < TN3; ++c) {
+      const int co = min(co0 + c, p.C_out - 1);  // a surplus channel slot recomputes the last channel, stores nothing
+      const float* wa = DO_MIN ? w_min + ((size_t)co * p.C_in + ci) * 27 : nullptr;
+      const float* wb = DO_MAX ? w_max + ((size_t)co * p.C_in + ci) * 27 : nullptr;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int r = 0; r < 9; ++r) {
+          float s1[3], s2[3];
+#pragma unroll
+          for (int j = 0; j < 3; ++j) {
+            if (DO_MIN) s1[j] = __fadd_rn(xs[r][q + j], wa[r * 3 + j]);
+            if (DO_MAX) s2[j] = (MODE == TCONV_COMPOUND) ? s1[j] : __fadd_rn(xs[r][q + j], wb[r * 3 + j]);
+          }
+          const int row = ci * 9 + r;
+          if (DO_MIN) {
+            const float rm = fminf(fminf(s1[0], s1[1]), s1[2]);  // NaN (a row wholly in the padding) never wins
+            cmin[c][q] = (rm < bmin[c][q]) ? row : cmin[c][q];
+            bmin[c][q] = fminf(bmin[c][q], rm);
+          }
+          if (DO_MAX) {
+            const float rM = fmaxf(fmaxf(s2[0], s2[1]), s2[2]);
+            cmax[c][q] = (rM > bmax[c][q]) ? row : cmax[c][q];
+            bmax[c][q] = fmaxf(bmax[c][q], rM);
+          }
+        }
+      }
+    }
+  }
+
+  // exact tap: the first of the three taps of the winning row whose sum equals the extremum
+  auto refine = [&](const float* w, int co, int row, float best, int q) -> int {
+    const int cs = min(row / 9, p.C_in - 1), r = row - (row / 9) * 9, a = r / 3, i = r - a * 3;
+    const int id = min(max(od - p.pd + a, 0), p.D - 1), ih = min(max(oh - p.ph + i, 0), p.H - 1);
+    const float* xr = xn + (size_t)cs * vol + ((size_t)id * p.H + ih) * p.W;
+    const float* wr = w + ((size_t)co * p.C_in + cs) * 27 + r * 3;
+    int res = cs * 27 + r * 3;
+#pragma unroll
+    for (int j = 2; j >= 0; --j) {
+      const int iw = ow0 - p.pw + q + j;
+      const float sum = __fadd_rn(xr[min(max(iw, 0), p.W - 1)], wr[j]);
+      res = (iw >= 0 && iw < p.W && sum == best) ? cs * 27 + r * 3 + j : res;
+    }
+    return res;
+  };
+  const size_t ovol = (size_t)p.Do * p.Ho * p.Wo;
+#pragma unroll
+  for (int c = 0; c < TN3; ++c) {
+    const int co = co0 + c;
+    if (co >= p.C_out) break;  // wave-uniform
+    const size_t ob = ((size_t)n * p.C_out + co) * ovol + ((size_t)od * p.Ho + oh) * p.Wo + ow0;
+    float ca = 1.f, cb = 1.f;
+    if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
+      if (alpha) ca = alpha[co];
+      if (beta) cb = beta[co];
+    }
+    int ridx[4];
+    float out[4];
+    if (DO_MIN) {
+      for (int q = 0; q < 4; ++q) ridx[q] = refine(w_min, co, cmin[c][q], bmin[c][q], q);
+      store_row<4>(idx_min + ob, ridx, first_q);
+      if (y_min) store_row<4>(y_min + ob, bmin[c], first_q);
+    }
+    if (DO_MAX) {
+      for (int q = 0; q < 4; ++q) ridx[q] = refine(w_max, co, cmax[c][q], bmax[c][q], q);
+      store_row<4>(idx_max + ob, ridx, first_q);
+      if (y_max) store_row<4>(y_max + ob, bmax[c], first_q);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (!DO_MIN) out[q] = bmax[c][q];
+      else if (!DO_MAX) out[q] = bmin[c][q];
+      else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
+    }
+    store_row<4>(y + ob, out, first_q);
+  }
+}
+
+bool k3_ok(const Params3& p) {
+  if (p.KD != 3 || p.KH != 3 || p.KW != 3) return false;
+  if (p.sd != 1 || p.sh != 1 || p.sw != 1 || p.dd != 1 || p.dh != 1 || p.dw != 1) return false;
+  if (p.mode > TCONV_PARALLEL || p.Wo < 4 || p.pw > 1) return false;
+  const long long segs = (p.Wo + 3) / 4, units = (long long)p.N * p.Do * p.Ho * segs;
+  const long long dmax = segs > p.Ho ? (segs > p.Do ? segs : p.Do) : (p.Ho > p.Do ? p.Ho : p.Do);
+  if (units * dmax >= 0xffffffffLL) return false;                    // multiply-high quotients stay exact
+  if ((long long)p.D * p.H * p.W >= 0x7fffffffLL) return false;      // 32-bit offsets inside a channel volume
+  return ((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES <= 65535;
+}
+
+unsigned inv3(int d) { return d > 1 ? (unsigned)(0x100000000ull / (unsigned)d) + 1u : 0u; }
+
+template <int MODE>
+hipError_t launch_k3(const Params3& p, const FwdArgs& a, hipStream_t s) {
+  const int segs = (p.Wo + 3) / 4;
+  const unsigned n_units = (unsigned)((long long)p.N * p.Do * p.Ho * segs);
+  const dim3 grid((n_units + 63) / 64, (unsigned)(((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES));
+  hipLaunchKernelGGL(fwd3d_k3_kernel<MODE>, grid, dim3(WAVES * 64), 0, s, p, (const float*)a.x, (const float*)a.w_min,
+                     (const float*)a.w_max, a.alpha, a.beta, (float*)a.y, (float*)a.y_min, (float*)a.y_max, a.idx_min,
+                     a.idx_max, segs, n_units, inv3(segs), inv3(p.Ho), inv3(p.Do));
+  return hipGetLastError();
+}
+
 // grad_x[n, c*, id*, ih*, iw*] += g_b for every output and live branch (zero-filled first).  MODE is a backward
 // mode: MAX, MIN, COMPOUND or PARALLEL.
 template <int MODE>
@@ -133,6 +336,15 @@ hipError_t launch_fwd(const Params3& p, const FwdArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s) {
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  if (k3_ok(p) && !(e && strcmp(e, "generic") == 0)) {
+    switch (p.mode) {
+      case TCONV_MAX: return launch_k3<TCONV_MAX>(p, a, s);
+      case TCONV_MIN: return launch_k3<TCONV_MIN>(p, a, s);
+      case TCONV_COMPOUND: return launch_k3<TCONV_COMPOUND>(p, a, s);
+      default: return launch_k3<TCONV_PARALLEL>(p, a, s);
+    }
+  }
   switch (p.mode) {
     case TCONV_MAX: return launch_fwd<TCONV_MAX>(p, a, s);
     case TCONV_MIN: return launch_fwd<TCONV_MIN>(p, a, s);

@@ -32,6 +32,8 @@ SHAPES = [
     Layer3dCfg("v_one", 1, 1, 1, 1, 1, 1, seed=136),                       # 26 of 27 taps are padding
     Layer3dCfg("v_deep", 1, 40, 4, 5, 6, 3, seed=137),                     # K = 1080
     Layer3dCfg("v_wide", 1, 8, 4, 4, 4, 70, seed=138),
+    Layer3dCfg("v_ragged_w", 2, 3, 5, 6, 13, 6, pad=(1, 0, 1), seed=139),    # W_out = 13: moved last segment
+    Layer3dCfg("v_p2", 1, 3, 3, 4, 6, 9, pad=(2, 2, 1), seed=140),
 ]
 
 
@@ -41,6 +43,23 @@ def test_three_dimensional_layers(cfg):
         c = cfg.with_(mode=mode)
         _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
         _check(c, integer=True)
+
+
+def test_plain_kernel_on_3x3x3_shapes():
+    """The register-resident 3 x 3 x 3 kernel is the default on these shapes; the plain kernel must agree too."""
+    import os
+    old = os.environ.get("TCONV_FORWARD_KERNEL")
+    os.environ["TCONV_FORWARD_KERNEL"] = "generic"
+    try:
+        for cfg in (SHAPES[0], SHAPES[4]):
+            for mode in ("max", "compound", "parallel"):
+                _check(cfg.with_(mode=mode), alpha_beta="random" if mode != "max" else None)
+            _check(cfg.with_(mode="compound"), integer=True)
+    finally:
+        if old is None:
+            os.environ.pop("TCONV_FORWARD_KERNEL", None)
+        else:
+            os.environ["TCONV_FORWARD_KERNEL"] = old
 
 
 def test_larger_layer():
