@@ -319,6 +319,66 @@ __global__ __launch_bounds__(256) void bwd3d_input_kernel(Params3 p, BwdArgs a, 
   if (DO_MAX) deposit(a.idx_max[o], (SCALED && a.beta) ? a.beta[co] * g : g);
 }
 
+
+// Input gradient without global atomics: a workgroup owns TH rows of one depth slice of one image for a chunk of
+// CC input channels, keeps their sums in LDS as fp64 ([CC][TH][W]) and scans every output whose window can
+// reach them: the output depths od with od*sd - pd + a*dd == id for a depth tap a, the output rows around the
+// tile, all output columns and channels.  An output is taken if its winner has that depth tap and lands inside
+// the tile.  Every input element belongs to exactly one workgroup, so plain stores finish the job (no zero
+// fill).  K27: the 3 x 3 x 3 window, whose tap numbers unflatten by constants.
+template <int MODE, bool K27>
+__global__ __launch_bounds__(256) void bwd3d_input_tile_kernel(Params3 p, BwdArgs a, float* __restrict__ grad_x, int TH,
+                                                               int CC, int tiles_h, int chunks) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  HIP_DYNAMIC_SHARED(double, tile3)
+  int b = blockIdx.x;
+  const int ch = b % chunks; b /= chunks;
+  const int th = b % tiles_h; b /= tiles_h;
+  const int id = b % p.D;
+  const int n = b / p.D;
+  const int h0 = th * TH, c0 = ch * CC;
+  const int tsz = CC * TH * p.W;
+  for (int e = threadIdx.x; e < tsz; e += 256) tile3[e] = 0.0;
+  __syncthreads();
+
+  const int KH = K27 ? 3 : p.KH, KW = K27 ? 3 : p.KW, KHW = KH * KW, KK = (K27 ? 3 : p.KD) * KHW;
+  // output rows whose window can reach the tile rows
+  const int nh = h0 + p.ph - (KH - 1) * p.dh;
+  const int oh_lo = nh <= 0 ? 0 : (nh + p.sh - 1) / p.sh;
+  const int oh_hi = min(p.Ho - 1, (h0 + TH - 1 + p.ph) / p.sh);
+  const int RH = max(oh_hi - oh_lo + 1, 0);
+  const size_t ovol = (size_t)p.Do * p.Ho * p.Wo;
+  const int per_od = p.C_out * RH * p.Wo;  // items per output depth: (co, oh, ow), ow fastest
+  for (int ta = 0; ta < (K27 ? 3 : p.KD); ++ta) {
+    const int t = id + p.pd - ta * p.dd;
+    if (t < 0 || t % p.sd != 0 || t / p.sd >= p.Do) continue;  // no output depth reads this slice through tap ta
+    const int od = t / p.sd;
+    for (int it = threadIdx.x; it < per_od; it += 256) {
+      const int ow = it % p.Wo, r = it / p.Wo, oh = oh_lo + r % RH, co = r / RH;
+      const size_t o = ((size_t)n * p.C_out + co) * ovol + ((size_t)od * p.Ho + oh) * p.Wo + ow;
+      const float g = a.gy[o];
+      const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw;
+      auto deposit = [&](int k, double v) {
+        const int c = k / KK, tt = k - c * KK, ka = tt / KHW, rr = tt - ka * KHW, ki = rr / KW, kj = rr - ki * KW;
+        const int ih = bh + ki * p.dh, iw = bw + kj * p.dw, cc = c - c0;
+        if (ka == ta && (unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)p.W && (unsigned)cc < (unsigned)CC &&
+            h0 + ih < p.H)
+          atomicAdd(&tile3[(cc * TH + ih) * p.W + iw], v);
+      };
+      if (DO_MIN) deposit(a.idx_min[o], (SCALED && a.alpha) ? (double)a.alpha[co] * (double)g : (double)g);
+      if (DO_MAX) deposit(a.idx_max[o], (SCALED && a.beta) ? (double)a.beta[co] * (double)g : (double)g);
+    }
+  }
+  __syncthreads();
+  const size_t vol = (size_t)p.D * p.H * p.W;
+  float* gxn = grad_x + (size_t)n * p.C_in * vol + (size_t)id * p.H * p.W;
+  for (int e = threadIdx.x; e < tsz; e += 256) {
+    const int iw = e % p.W, ih = (e / p.W) % TH, cc = e / (p.W * TH);
+    if (h0 + ih < p.H && c0 + cc < p.C_in) gxn[(size_t)(c0 + cc) * vol + (size_t)(h0 + ih) * p.W + iw] = (float)tile3[e];
+  }
+}
+
 __global__ __launch_bounds__(256) void fill3d_zero_kernel(float* __restrict__ p, size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
@@ -357,6 +417,41 @@ hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s) 
 
 // p.mode is a backward mode here (the mixed layers arrive as MIN / MAX)
 hipError_t launch_backward_input_3d(const Params3& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
+  // LDS tile [CC][TH][W] of doubles: all channels if a few rows of them fit, else chunks of channels
+  const size_t budget = 48 * 1024;
+  const size_t row_bytes = (size_t)p.W * sizeof(double);
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  const bool plain = e && strcmp(e, "generic") == 0;
+  if (!plain && row_bytes <= budget) {
+    int CC = p.C_in;
+    while (CC > 1 && (size_t)CC * row_bytes * (p.H < 4 ? p.H : 4) > budget) CC = (CC + 1) / 2;
+    int TH = (int)(budget / ((size_t)CC * row_bytes));
+    if (TH > p.H) TH = p.H;
+    if (TH < 1) TH = 1;
+    const int tiles_h = (p.H + TH - 1) / TH, chunks = (p.C_in + CC - 1) / CC;
+    const long long blocks = (long long)p.N * p.D * tiles_h * chunks;
+    if (blocks <= 0x7fffffffLL) {
+      const size_t lds = (size_t)CC * TH * row_bytes;
+      const dim3 grid((unsigned)blocks);
+      const bool k27 = (p.KD == 3 && p.KH == 3 && p.KW == 3);
+#define TCONV_LAUNCH_BWD3(M)                                                                                      \
+  do {                                                                                                            \
+    if (k27) hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, true>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC, \
+                                tiles_h, chunks);                                                                 \
+    else hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, false>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC,    \
+                            tiles_h, chunks);                                                                     \
+  } while (0)
+      switch (p.mode) {
+        case TCONV_MAX: TCONV_LAUNCH_BWD3(TCONV_MAX); break;
+        case TCONV_MIN: TCONV_LAUNCH_BWD3(TCONV_MIN); break;
+        case TCONV_COMPOUND: TCONV_LAUNCH_BWD3(TCONV_COMPOUND); break;
+        default: TCONV_LAUNCH_BWD3(TCONV_PARALLEL); break;
+      }
+#undef TCONV_LAUNCH_BWD3
+      return hipGetLastError();
+    }
+  }
+  // rows too long for the LDS tile: zero fill and scatter with global atomics
   const size_t nx = (size_t)p.N * p.C_in * p.D * p.H * p.W;
   size_t zb = (nx + 255) / 256;
   if (zb > 8192) zb = 8192;
