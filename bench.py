@@ -392,7 +392,7 @@ def bench_3d(args, torch, tb) -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: x[{cfg.N},{cfg.C_in},{cfg.D},{cfg.H},{cfg.W}] -> {cfg.C_out}ch "
                                f"k{cfg.k} s{cfg.stride} p{cfg.pad} d{cfg.dil} {cfg.mode} f32, fwd+bwd_input+bwd_weight",
-                   "pairs_per_step": pairs, "forward_kernel": "generic3d"},
+                   "pairs_per_step": pairs, "forward_kernel": tb.tconv3d_forward_kernel_name(d)},
         "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
         "ms_forward": round(t_f, 4), "ms_backward_input": round(t_bi, 4), "ms_backward_weight": round(t_bw, 4),
         "roofline": {"bound": "alu", "kernel": "forward", "achieved": round(achieved / 1e12, 3),

@@ -280,6 +280,8 @@ typedef struct tconv3d_desc {
 } tconv3d_desc;
 
 int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, int32_t* W_out);
+/* "k3x3x3" (3 x 3 x 3 window, stride 1, dilation 1, horizontal padding <= 1, a full-window mode) or "generic3d". */
+const char* tconv3d_forward_kernel_name(const tconv3d_desc* desc);
 int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, const void* w_max,
                     const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
                     int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,

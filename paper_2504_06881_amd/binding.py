@@ -22,7 +22,7 @@ SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_b
            "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
-           "tconv3d_out_shape", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
+           "tconv3d_out_shape", "tconv3d_forward_kernel_name", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
            "tconv_status_string", "tconv_forward_kernel_name")
 
 
@@ -159,6 +159,8 @@ def load() -> ctypes.CDLL:
         lib.tconv3d_forward.argtypes = [D3] + [P] * 11 + [ctypes.c_size_t, P]
         lib.tconv3d_backward_input.argtypes = [D3] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv3d_backward_weight.argtypes = [D3] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv3d_forward_kernel_name.argtypes = [D3]
+        lib.tconv3d_forward_kernel_name.restype = ctypes.c_char_p
         for f in ("tconv3d_out_shape", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight"):
             getattr(lib, f).restype = ctypes.c_int
         lib.tconv_status_string.argtypes = [ctypes.c_int]
@@ -370,3 +372,11 @@ def tconv3d_backward_weight(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, gra
     _check(load().tconv3d_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
                                           _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), None, 0, _stream()),
            "tconv3d_backward_weight")
+
+
+def tconv3d_forward_kernel_name(desc: Desc3d) -> str:
+    cd = desc.c()
+    r = load().tconv3d_forward_kernel_name(ctypes.byref(cd))
+    if r is None:
+        raise TconvError(-1, "tconv3d_forward_kernel_name")
+    return r.decode()

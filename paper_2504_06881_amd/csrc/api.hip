@@ -375,6 +375,12 @@ int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, 
   return TCONV_OK;
 }
 
+const char* tconv3d_forward_kernel_name(const tconv3d_desc* desc) {
+  Params3 p;
+  if (make_params3(desc, &p) != TCONV_OK) return nullptr;
+  return forward_3d_kernel_name(p);
+}
+
 int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, const void* w_max,
                     const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
                     int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,

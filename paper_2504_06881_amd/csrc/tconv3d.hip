@@ -395,9 +395,15 @@ hipError_t launch_fwd(const Params3& p, const FwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s) {
+static bool use_k3(const Params3& p) {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
-  if (k3_ok(p) && !(e && strcmp(e, "generic") == 0)) {
+  return k3_ok(p) && !(e && strcmp(e, "generic") == 0);
+}
+
+const char* forward_3d_kernel_name(const Params3& p) { return use_k3(p) ? "k3x3x3" : "generic3d"; }
+
+hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s) {
+  if (use_k3(p)) {
     switch (p.mode) {
       case TCONV_MAX: return launch_k3<TCONV_MAX>(p, a, s);
       case TCONV_MIN: return launch_k3<TCONV_MIN>(p, a, s);

@@ -137,6 +137,7 @@ const char* sum_forward_kernel_name(const Params& p);
 
 hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_input_3d(const Params3& p, const BwdArgs& a, float* grad_x, hipStream_t s);
+const char* forward_3d_kernel_name(const Params3& p);
 
 hipError_t launch_depthwise_forward(const Params& p, const DwArgs& a, hipStream_t s);
 hipError_t launch_depthwise_backward(const Params& p, const DwArgs& a, const DwGrads& g, hipStream_t s);
