@@ -49,6 +49,8 @@ SHAPES = [
     LayerCfg("d_tall", 1, 2, 70, 9, 2, stride=2, seed=85),
     LayerCfg("d_wide_s2", 1, 1, 11, 66, 1, stride=2, seed=86),
     LayerCfg("d_h40", 1, 2, 40, 12, 2, seed=87),
+    LayerCfg("d_1d_k5", 2, 4, 1, 50, 4, KH=1, KW=5, pad=0, seed=88),           # a one-dimensional layer: H = 1, KH = 1
+    LayerCfg("d_1d_k16_s2", 2, 3, 1, 90, 6, KH=1, KW=16, stride=2, pad=0, seed=89),
 ]
 
 
