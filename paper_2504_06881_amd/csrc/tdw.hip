@@ -5,8 +5,10 @@
 //   m = min over the window of x + w_min[co],  M = max over the window of x + w_max[co],
 //   y = M | m | alpha[co]*m + beta[co]*M  (Sec. 3.5 / 3.6 combination; used in place of the depthwise
 //   convolutions of the MobileNetV2 variants, Sec. 5).
-// With 9 candidates per output and 8-9 bytes of traffic per output the layer is bound by HBM, not by the
-// vector ALUs, so the kernels are built around bytes:
+// With 9 candidates per output and 8-9 bytes of traffic per output the layer sits on the HBM side of the
+// roofline (20 vector instructions of arithmetic per output against 8 bytes), so the kernels are built around
+// bytes; what they measure at is about half the HBM rate, because finding the two winning taps exactly costs
+// 18 more instructions per output and branch than the arithmetic itself:
 //   * forward writes, next to y, ONE byte per output that packs both winning taps (low nibble: min-plus
 //     tap, high nibble: max-plus tap); backward reads gy and that byte instead of re-deriving the winners
 //     from x (4 more bytes per output and several times the arithmetic);
