@@ -8,7 +8,8 @@ pad 1, compound mode, fp32), inputs resident in HBM before the timed region.
 
 Prints ONE JSON line:
   metric / value : add+compare pairs per second of the step (dense pair count / step time), GOPS
-  roofline       : the forward kernel against the fp32 vector-ALU peak, measured live with HIP events
+  roofline       : the forward kernel against the fp32 vector-ALU peak, measured live with HIP events around
+                   every forward launch of the timed region
   cpu_baseline   : the CPU oracle timed on this machine's host cores on a bounded sample of the same workload
 Extra keys give the forward-only rate and the achieved HBM GB/s of the two backward calls.
 --workload takes any single-layer configuration name (cfg2_main, cfg3a, cfg4b, ...) or cfg5, the 19
@@ -65,6 +66,8 @@ def main() -> int:
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="multi-layer workloads (cfg5): launch every step eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -191,19 +194,57 @@ def main() -> int:
         for L in layers:
             L.fwd(); L.bwd_in(); L.bwd_w()
     torch.cuda.synchronize()
+    # The timed region carries HIP events around the dominant (forward) kernel only: an event costs about 10 us of
+    # stream time on this stack, and four of them per step took 9 % off the step rate.  The two backward calls
+    # are timed in a short pass of their own right after the timed region (auxiliary figures).
+    graph = None
+    if len(layers) > 1 and not args.no_graph:
+        # The multi-layer step is some 76 launches of 20 - 100 us each, which the Python launch path cannot always
+        # feed fast enough: the whole step (every layer, forward and backward) is captured once in a HIP graph
+        # and replayed.  The library records no memset (its zero fills are kernels), so it is capture-safe.
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for L in layers:
+                L.fwd(); L.bwd_in(); L.bwd_w()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for L in layers:
+                L.fwd(); L.bwd_in(); L.bwd_w()
+        graph.replay()
+        torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
+        if graph is not None:
+            graph.replay()
+            continue
         for L in layers:
-            e = [ev() for _ in range(4)]
-            e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); e[2].record(); L.bwd_w(); e[3].record()
+            e = [ev(), ev()]
+            e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); L.bwd_w()
             marks.append((L, e))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    t_f = sum(m[0].elapsed_time(m[1]) for _, m in marks) / args.steps   # ms per step, all layers
-    t_bi = sum(m[1].elapsed_time(m[2]) for _, m in marks) / args.steps
-    t_bw = sum(m[2].elapsed_time(m[3]) for _, m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
+    if graph is not None:  # events cannot sit inside a graph: the forward launches are timed in an eager pass
+        for _ in range(args.steps):
+            for L in layers:
+                e = [ev(), ev()]
+                e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); L.bwd_w()
+                marks.append((L, e))
+        torch.cuda.synchronize()
+    t_f = sum(m[0].elapsed_time(m[1]) for _, m in marks) / args.steps   # ms per step, all layers
+    aux_steps = min(args.steps, 10)
+    aux = []
+    for _ in range(aux_steps):
+        for L in layers:
+            e = [ev() for _ in range(3)]
+            L.fwd(); e[0].record(); L.bwd_in(); e[1].record(); L.bwd_w(); e[2].record()
+            aux.append(e)
+    torch.cuda.synchronize()
+    t_bi = sum(m[0].elapsed_time(m[1]) for m in aux) / aux_steps
+    t_bw = sum(m[1].elapsed_time(m[2]) for m in aux) / aux_steps
 
     pairs = sum(L.cfg.pairs for L in layers)
     value = pairs / (ms_step * 1e-3) / 1e9
@@ -229,7 +270,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32" if dtypes == {"f32"} else "bf16-storage/f32-arith",
         "data": "synthetic",
-        "config": {"workload": wl_name + ", fwd+bwd_input+bwd_weight", "pairs_per_step": pairs,
+        "config": {"workload": wl_name + ", fwd+bwd_input+bwd_weight" + (", one HIP graph per step" if graph else ""),
+                   "pairs_per_step": pairs,
                    "forward_kernel": (tb.tconv_sum_forward_kernel_name(layers[-1].d) if args.op == "sum"
                                       else tb.tconv_forward_kernel_name(layers[-1].d))},
         "forward_gops": round(fwd_pairs_s / 1e9, 2),
@@ -287,18 +329,27 @@ def bench_1d(args, torch, tb) -> int:
     for _ in range(args.warmup):
         fwd(); bwd_i(); bwd_w()
     torch.cuda.synchronize()
+    # events around the forward kernel only inside the timed region; the backward calls are timed in a short
+    # pass of their own afterwards (an event costs about 10 us of stream time)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        e[0].record(); fwd(); e[1].record(); bwd_i(); e[2].record(); bwd_w(); e[3].record()
+        e = [ev(), ev()]
+        e[0].record(); fwd(); e[1].record(); bwd_i(); bwd_w()
         marks.append(e)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    t_bi = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
-    t_bw = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
+    aux_steps, aux = min(args.steps, 10), []
+    for _ in range(aux_steps):
+        e = [ev() for _ in range(3)]
+        fwd(); e[0].record(); bwd_i(); e[1].record(); bwd_w(); e[2].record()
+        aux.append(e)
+    torch.cuda.synchronize()
+    t_bi = sum(m[0].elapsed_time(m[1]) for m in aux) / aux_steps
+    t_bw = sum(m[1].elapsed_time(m[2]) for m in aux) / aux_steps
     pairs = cfg.pairs
     achieved = pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode)) / (t_f * 1e-3)
     out = {
@@ -371,18 +422,27 @@ def bench_3d(args, torch, tb) -> int:
     for _ in range(args.warmup):
         fwd(); bwd_i(); bwd_w()
     torch.cuda.synchronize()
+    # events around the forward kernel only inside the timed region; the backward calls are timed in a short
+    # pass of their own afterwards (an event costs about 10 us of stream time)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        e[0].record(); fwd(); e[1].record(); bwd_i(); e[2].record(); bwd_w(); e[3].record()
+        e = [ev(), ev()]
+        e[0].record(); fwd(); e[1].record(); bwd_i(); bwd_w()
         marks.append(e)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    t_bi = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
-    t_bw = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
+    aux_steps, aux = min(args.steps, 10), []
+    for _ in range(aux_steps):
+        e = [ev() for _ in range(3)]
+        fwd(); e[0].record(); bwd_i(); e[1].record(); bwd_w(); e[2].record()
+        aux.append(e)
+    torch.cuda.synchronize()
+    t_bi = sum(m[0].elapsed_time(m[1]) for m in aux) / aux_steps
+    t_bw = sum(m[1].elapsed_time(m[2]) for m in aux) / aux_steps
     pairs = cfg.pairs
     achieved = pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode)) / (t_f * 1e-3)
     out = {
@@ -470,17 +530,24 @@ def bench_depthwise(args, torch, tb) -> int:
     for _ in range(args.warmup):
         fwd(); bwd()
     torch.cuda.synchronize()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        e[0].record(); fwd(); e[1].record(); bwd(); e[2].record()
+        e = [ev(), ev()]
+        e[0].record(); fwd(); e[1].record(); bwd()
         marks.append(e)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     t_f = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    t_b = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
     ms_step = wall * 1e3 / args.steps
+    aux_steps, aux = min(args.steps, 10), []   # the backward call, timed in a short pass of its own
+    for _ in range(aux_steps):
+        e = [ev(), ev()]
+        fwd(); e[0].record(); bwd(); e[1].record()
+        aux.append(e)
+    torch.cuda.synchronize()
+    t_b = sum(m[0].elapsed_time(m[1]) for m in aux) / aux_steps
     n_in, n_out = x.numel(), y.numel()
     pairs = n_out * cfg.KH * cfg.KW * (2 if two else 1)
     bytes_f = n_in * 4 + n_out * 5            # x read; y and one winner byte written
