@@ -41,10 +41,15 @@ int make_params(const tconv_desc* d, Params* p) {
 }
 
 // TCONV_FORWARD_KERNEL=generic forces the generic kernel (tuning / testing aid).
-bool use_tiled(const Params& p, int dtype) {
-  if (!forward_tiled3x3_supported(p, dtype)) return false;
+bool generic_forced() {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
-  return !(e && strcmp(e, "generic") == 0);
+  return e && strcmp(e, "generic") == 0;
+}
+
+bool use_tiled(const Params& p, int dtype) { return forward_tiled3x3_supported(p, dtype) && !generic_forced(); }
+
+bool use_row(const Params& p, int dtype) {
+  return !use_tiled(p, dtype) && forward_row_supported(p, dtype) && !generic_forced();
 }
 
 }  // namespace
@@ -92,6 +97,8 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)))
       return TCONV_E_WORKSPACE;
     e = launch_forward_tiled3x3(p, desc->dtype, a, workspace, s);
+  } else if (use_row(p, desc->dtype)) {
+    e = launch_forward_row(p, a, s);
   } else {
     e = launch_forward_generic(p, desc->dtype, a, s);
   }
@@ -455,7 +462,7 @@ const char* tconv_status_string(int status) {
 const char* tconv_forward_kernel_name(const tconv_desc* desc) {
   Params p;
   if (make_params(desc, &p) != TCONV_OK) return nullptr;
-  return use_tiled(p, desc->dtype) ? "tiled3x3" : "generic";
+  return use_tiled(p, desc->dtype) ? "tiled3x3" : (use_row(p, desc->dtype) ? "row1d" : "generic");
 }
 
 }  // extern "C"

@@ -88,11 +88,19 @@ __global__ __launch_bounds__(256) void bwd_input_scatter_kernel(Params p, BwdArg
 // element belongs to exactly one workgroup, so grad_x needs no zero fill.  The price is re-reading
 // gy / idx for the halo: (TH+e)(TW+e)/(TH*TW) times the algorithmic bytes (times the number of
 // channel chunks when C_in*TH*TW does not fit in LDS); neighbouring tiles share those lines in L2.
+// A winner k unflattens with two divisions; for the 3 x 3 window they are by constants, otherwise by
+// multiply-high with inv = floor(2^32 / d) + 1 (exact while k * d < 2^32; inv = 0: plain division, which
+// this target expands into dozens of vector instructions and which then dominates the kernel).
+__device__ __forceinline__ int unflatten_div(int u, int d, unsigned inv) {
+  return inv ? (int)__umulhi((unsigned)u, inv) : (d == 1 ? u : u / d);
+}
+
 template <int MODE, bool K3>
 __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ grad_x, int TH,
                                                               int TW, int CC, int tiles_h,
-                                                              int tiles_w, int chunks) {
+                                                              int tiles_w, int chunks, unsigned inv_kk,
+                                                              unsigned inv_kw) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
@@ -169,7 +177,8 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
         const float g = gv[u];
         if (DO_MIN) {
           const int k = kmn[u];
-          const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
+          const int c = K3 ? k / KK : unflatten_div(k, KK, inv_kk), r = k - c * KK;
+          const int i = K3 ? r / KWs : unflatten_div(r, KWs, inv_kw), j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
             atomicAdd(&tile[(cc * TH + ih) * TW + iw],
@@ -177,7 +186,8 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
         }
         if (DO_MAX) {
           const int k = kmx[u];
-          const int c = k / KK, r = k - c * KK, i = r / KWs, j = r - i * KWs;
+          const int c = K3 ? k / KK : unflatten_div(k, KK, inv_kk), r = k - c * KK;
+          const int i = K3 ? r / KWs : unflatten_div(r, KWs, inv_kw), j = r - i * KWs;
           const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
           if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
             atomicAdd(&tile[(cc * TH + ih) * TW + iw],
@@ -221,7 +231,9 @@ static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
   const int eh = (p.KH - 1) * p.dh, ew = (p.KW - 1) * p.dw;
   for (int chunks = 1; chunks <= p.C_in; chunks *= 2) {
     const int CC = (p.C_in + chunks - 1) / chunks;
-    for (int TWc = 8; TWc <= 128; TWc *= 2) {
+    // one-row inputs (sequences) have no second axis to grow the tile along: they take long rows instead
+    const int tw_max = p.H == 1 ? 4096 : 128;
+    for (int TWc = 8; TWc <= tw_max; TWc *= 2) {
       const int TW = TWc < p.W ? TWc : p.W;
       int TH = p.H < 64 ? p.H : 64;
       while (TH >= 1 && bwd_input_lds_bytes(p, CC, TH, TW) > lds_budget) --TH;
@@ -253,9 +265,14 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
     const size_t lds = bwd_input_lds_bytes(p, t.CC, t.TH, t.TW);
     const long long grid_blocks = ((blocks + 7) / 8) * 8;  // the kernel remaps blockIdx per XCD
     const bool k3 = (p.KH == 3 && p.KW == 3);
+    const long long kk = (long long)p.KH * p.KW;
+    const auto inv_of = [](long long d, long long umax) -> unsigned {  // 0: the kernel divides plainly
+      return (d > 1 && umax * d < 0x100000000LL) ? (unsigned)(0x100000000ULL / (unsigned long long)d) + 1u : 0u;
+    };
+    const unsigned inv_kk = inv_of(kk, p.K), inv_kw = inv_of(p.KW, kk);
 #define TCONV_LAUNCH_BWD_IN(M, K3)                                                              \
   hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)grid_blocks), dim3(1024), lds, s, p, a, \
-                     grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks)
+                     grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks, inv_kk, inv_kw)
     switch (p.mode) {
       case TCONV_MAX: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MAX, true); else TCONV_LAUNCH_BWD_IN(TCONV_MAX, false); break;
       case TCONV_MIN: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MIN, true); else TCONV_LAUNCH_BWD_IN(TCONV_MIN, false); break;

@@ -86,6 +86,14 @@ def test_one_dimensional_descriptor_views():
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 95, 4000, 64, 3, pad=1, mode="compound")) == "generic"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="minplus_max")) == "generic"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=2, mode="compound")) == "generic"
+    # long windows over few channels: the one-row kernel (strides 1, 2, 4, 8; full-window modes; fp32)
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=4, pad=38, mode="compound")) == "row1d"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=3, pad=38, mode="compound")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=4, pad=38, mode="maxplus_min")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=4, pad=38, dil=2, mode="max")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=4, pad=38, mode="max", dtype="bf16")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=1, pad=38, mode="max")) == "generic"   # window past the LDS row
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 64, 32000, 64, 80, stride=4, pad=38, mode="max")) == "generic"  # too many channels for LDS
     for bad, code in [(tb.Desc1d(0, 3, 16, 8, 3), -1), (tb.Desc1d(1, 3, 16, 8, 3, stride=0), -1),
                       (tb.Desc1d(1, 3, 2, 8, 3), -2), (tb.Desc1d(1, 3, 16, 8, 3, pad=3), -2)]:
         with pytest.raises(tb.TconvError) as e:

@@ -1,7 +1,7 @@
 """GPU parity of the one-dimensional layers (tconv1d_forward / tconv1d_backward_input / tconv1d_backward_weight)
 against their CPU oracle: outputs and winners bit for bit, gradients within 1e-5 of the size of their summands.
 Covers both two-dimensional views the library chooses between (three channels as the rows of a 3 x 3 window,
-and the one-row image)."""
+and the one-row image) and the long-window kernel of the one-row image."""
 import numpy as np
 import pytest
 
@@ -47,6 +47,40 @@ def test_one_dimensional_layers(cfg):
         c = cfg.with_(mode=mode)
         _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
         _check(c, integer=True)
+
+
+# shapes of the long-window kernel: every stride it takes, windows that are and are not whole chunks of 8 taps,
+# several input channels, outputs past one workgroup of 256, channel counts that are not multiples of 8
+LONG = [
+    Layer1dCfg("w_k80_s4_ragged", 2, 1, 2103, 9, K=80, stride=4, pad=38, seed=120),
+    Layer1dCfg("w_k80_s4_p0", 1, 1, 1500, 8, K=80, stride=4, pad=0, seed=121),
+    Layer1dCfg("w_k19_s2_c2", 1, 2, 733, 3, K=19, stride=2, pad=9, seed=122),
+    Layer1dCfg("w_k8_s1_c3", 2, 3, 270, 17, K=8, stride=1, pad=3, seed=123),
+    Layer1dCfg("w_k64_s1_maxpad", 1, 1, 64, 1, K=64, stride=1, pad=63, seed=124),
+    Layer1dCfg("w_k33_s8", 1, 1, 4100, 2, K=33, stride=8, pad=16, seed=125),
+    Layer1dCfg("w_k12_s4_c4", 1, 4, 90, 5, K=12, stride=4, pad=11, seed=126),
+    Layer1dCfg("w_k9_s1", 1, 1, 257, 4, K=9, stride=1, pad=0, seed=127),
+    Layer1dCfg("w_k25_s2_c8", 2, 8, 600, 24, K=25, stride=2, pad=12, seed=128),
+]
+
+
+@pytest.mark.parametrize("cfg", LONG, ids=lambda c: c.name)
+def test_long_window_kernel(cfg):
+    for mode in ("max", "min", "compound", "parallel"):
+        c = cfg.with_(mode=mode)
+        d = tb.Desc1d(c.N, c.C_in, c.L, c.C_out, c.K, c.stride, c.pad, c.dil, c.mode, c.dtype)
+        assert tb.tconv1d_forward_kernel_name(d) == "row1d"
+        _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+        _check(c, integer=True)
+
+
+def test_full_size_stem():
+    cfg = CONFIGS_1D["c1d_stem"].with_(N=4)
+    print(f"[1d stem] {cfg.name} pairs={cfg.pairs:.3e}", flush=True)
+    d = tb.Desc1d(cfg.N, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil, cfg.mode, cfg.dtype)
+    assert tb.tconv1d_forward_kernel_name(d) == "row1d"
+    _check(cfg)
+    _check(cfg.with_(mode="parallel"), alpha_beta="random")
 
 
 @pytest.mark.parametrize("mode", ["max", "compound", "parallel"])

@@ -35,8 +35,11 @@ def _replay_and_compare(step, outputs, scratch):
         for got, want in zip(outputs, ref):
             if got.dtype in (torch.int32, torch.uint8):
                 assert torch.equal(got, want), f"replay {rep}: integer output differs"
-            else:  # sums with atomics may round differently from run to run
-                assert torch.allclose(got, want, rtol=1e-5, atol=1e-5), f"replay {rep}: output differs"
+            else:
+                # sums with atomics round differently from run to run: by a few ulp of the partial sums, whose size
+                # the largest element of the tensor stands for (an element may be a small rest of large summands)
+                atol = 1e-5 * max(1.0, float(want.abs().max()))
+                assert torch.allclose(got, want, rtol=1e-5, atol=atol), f"replay {rep}: output differs"
 
 
 def test_hot_path_step_in_a_graph():
