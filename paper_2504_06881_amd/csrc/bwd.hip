@@ -105,7 +105,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   // [CC][TH][TW] fp64 sums, then one int2 per output pixel of the scanned region
-  extern __shared__ double tile[];
+  HIP_DYNAMIC_SHARED(double, tile)
   const int bd = blockDim.x;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a contiguous
   // run of tiles, so that the tiles of one image (which share halo rows of gy / idx) meet in one L2.
@@ -214,6 +214,98 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   }
 }
 
+// Input gradient of one-row inputs (sequences: H = 1, KH = 1).  Same ownership as the tiled kernel - a workgroup
+// owns CC channels x TW positions of one sequence in LDS as fp64 and scans every output that can reach them -
+// but a thread keeps ONE output position and walks the output channels.  On sequences the winners of the
+// channels of a position coincide massively (a peak of the input wins in every window that covers it and for
+// most kernels), and as LDS atomics on one address serialise, the pixel-major order of the tiled kernel is
+// bound by them.  Here a thread adds up the run of equal targets in a register and issues one atomic per run.
+template <int MODE>
+__global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a, float* __restrict__ grad_x, int TW,
+                                                             int CC, int tiles_w, int chunks, unsigned inv_kw) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX);
+  constexpr bool DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  HIP_DYNAMIC_SHARED(double, tile)  // [CC][TW]
+  const int bd = blockDim.x, tid = threadIdx.x;
+  int b = blockIdx.x;
+  const int ch = b % chunks; b /= chunks;
+  const int tw = b % tiles_w;
+  const int n = b / tiles_w;
+  const int w0 = tw * TW, c0 = ch * CC, tsz = CC * TW;
+  for (int e = tid; e < tsz; e += bd) tile[e] = 0.0;
+  __syncthreads();
+
+  // output positions whose window can reach the tile
+  const int nw = w0 + p.pw - (p.KW - 1) * p.dw;
+  const int ow_lo = nw <= 0 ? 0 : (nw + p.sw - 1) / p.sw;
+  const int ow_hi = min(p.Wo - 1, (w0 + TW - 1 + p.pw) / p.sw);
+  const int P = max(ow_hi - ow_lo + 1, 0);
+  if (P > 0) {
+    // P >= bd: a thread takes positions tid, tid + bd, ... and all channels; P < bd: bd / P groups of threads
+    // share the positions and deal the channels among them (surplus threads idle)
+    const int groups = max(bd / P, 1);
+    const int cg = tid / P;
+    if (cg < groups) {
+      for (int px = tid - cg * P; px < P; px += bd) {
+        const int ow = ow_lo + px;
+        const int bw = ow * p.sw - p.pw - w0;
+        const size_t base = (size_t)n * p.C_out * p.Wo + ow;
+        int am = -1, aM = -1;      // pending LDS element of the min / max branch, -1: none
+        double sm = 0.0, sM = 0.0;
+        auto target = [&](int k) -> int {
+          const int c = inv_kw ? (int)__umulhi((unsigned)k, inv_kw) : (p.KW == 1 ? k : k / p.KW);
+          const int j = k - c * p.KW, iw = bw + j * p.dw, cc = c - c0;
+          return ((unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC) ? cc * TW + iw : -1;
+        };
+        constexpr int UB = 4;
+        for (int co0 = cg; co0 < p.C_out; co0 += groups * UB) {
+          float gv[UB];
+          int kmn[UB], kmx[UB];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int co = min(co0 + u * groups, p.C_out - 1);
+            const size_t o = base + (size_t)co * p.Wo;
+            gv[u] = a.gy[o];
+            if (DO_MIN) kmn[u] = a.idx_min[o];
+            if (DO_MAX) kmx[u] = a.idx_max[o];
+          }
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int co = co0 + u * groups;
+            if (co >= p.C_out) break;
+            const double g = (double)gv[u];
+            if (DO_MIN) {
+              const int t = target(kmn[u]);
+              if (t != am) {
+                if (am >= 0) atomicAdd(&tile[am], sm);
+                am = t; sm = 0.0;
+              }
+              sm += (SCALED && a.alpha) ? (double)a.alpha[co] * g : g;
+            }
+            if (DO_MAX) {
+              const int t = target(kmx[u]);
+              if (t != aM) {
+                if (aM >= 0) atomicAdd(&tile[aM], sM);
+                aM = t; sM = 0.0;
+              }
+              sM += (SCALED && a.beta) ? (double)a.beta[co] * g : g;
+            }
+          }
+        }
+        if (DO_MIN && am >= 0) atomicAdd(&tile[am], sm);
+        if (DO_MAX && aM >= 0) atomicAdd(&tile[aM], sM);
+      }
+    }
+  }
+  __syncthreads();
+  float* gxn = grad_x + (size_t)n * p.C_in * p.W;
+  for (int e = tid; e < tsz; e += bd) {
+    const int iw = e % TW, cc = e / TW;
+    if (w0 + iw < p.W && c0 + cc < p.C_in) gxn[(size_t)(c0 + cc) * p.W + (w0 + iw)] = (float)tile[e];
+  }
+}
+
 // Tile shape for bwd_input_tile_kernel: minimise (channel chunks) x (halo re-read factor) under the
 // LDS budget, with a penalty for rows too short to coalesce.
 struct BwdInTile { int TH, TW, CC, tiles_h, tiles_w, chunks; };
@@ -256,7 +348,37 @@ static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
   return best;
 }
 
+// One-row inputs: positions per tile and channels per chunk, block size fitted to the scanned outputs.
+static bool launch_backward_input_row(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
+  if (p.H != 1 || p.KH != 1 || p.Ho != 1) return false;
+  if (const char* e = getenv("TCONV_BWD_ROW")) if (atoi(e) == 0) return false;
+  const int TW = p.W < 2048 ? p.W : 2048;
+  const size_t budget = 48 * 1024;
+  int CC = (int)(budget / ((size_t)TW * sizeof(double)));
+  if (CC < 1) return false;
+  if (CC > p.C_in) CC = p.C_in;
+  const int chunks = (p.C_in + CC - 1) / CC, tiles_w = (p.W + TW - 1) / TW;
+  const long long blocks = (long long)p.N * tiles_w * chunks;
+  if (blocks > 0x7fffffffLL) return false;
+  const long long pmax = ((long long)TW - 1 + (long long)(p.KW - 1) * p.dw) / p.sw + 1;  // outputs that can reach a tile
+  const int threads = pmax >= 1024 ? 1024 : (int)((pmax + 63) / 64) * 64;
+  const unsigned inv_kw =
+      (p.KW > 1 && (long long)p.K * p.KW < 0x100000000LL) ? (unsigned)(0x100000000ULL / (unsigned)p.KW) + 1u : 0u;
+  const size_t lds = (size_t)CC * TW * sizeof(double);
+#define TCONV_LAUNCH_BWD_ROW(M)                                                                                  \
+  hipLaunchKernelGGL(bwd_input_row_kernel<M>, dim3((unsigned)blocks), dim3(threads), lds, s, p, a, grad_x, TW, CC, \
+                     tiles_w, chunks, inv_kw)
+  switch (p.mode) {
+    case TCONV_MAX: TCONV_LAUNCH_BWD_ROW(TCONV_MAX); break;
+    case TCONV_MIN: TCONV_LAUNCH_BWD_ROW(TCONV_MIN); break;
+    default: TCONV_LAUNCH_BWD_ROW(TCONV_COMPOUND); break;  // compound and parallel route gradients identically
+  }
+#undef TCONV_LAUNCH_BWD_ROW
+  return true;
+}
+
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
+  if (launch_backward_input_row(p, a, grad_x, s)) return hipGetLastError();
   size_t LDS_BUDGET = 78 * 1024;  // per workgroup: two workgroups share a CU's 160 KB of LDS
   if (const char* e = getenv("TCONV_BWD_LDS_KB")) LDS_BUDGET = (size_t)atoi(e) * 1024;
   const BwdInTile t = choose_bwd_input_tile(p, LDS_BUDGET);
@@ -315,7 +437,7 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NHIST = (MODE == TCONV_PARALLEL) ? 2 : 1;
-  extern __shared__ double hist[];  // NHIST * K sums
+  HIP_DYNAMIC_SHARED(double, hist)  // NHIST * K sums
   const int co = blockIdx.x;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
