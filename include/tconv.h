@@ -239,7 +239,9 @@ const char* tconv_depthwise_forward_kernel_name(const tconv_desc* desc);
  * These calls only choose a two-dimensional view of the same memory: in general the one-row image
  * [N, C_in, 1, L] with a 1 x K kernel; for K = 3, dil = 1, stride 1 or 2, pad <= 1, C_in a multiple of 3 and a
  * full-window mode the image [N, C_in/3, 3, L] with a 3 x 3 kernel and no vertical padding, whose three rows are
- * three consecutive channels: same candidates, same k, and the tiled 3 x 3 kernels apply.
+ * three consecutive channels: same candidates, same k, and the tiled 3 x 3 kernels apply.  The one-row image has
+ * a forward kernel of its own for long windows over few channels (waveform stems: K >= 8, dil = 1, stride 1, 2,
+ * 4 or 8, full-window modes, fp32) and an input-gradient kernel of its own.
  */
 typedef struct tconv1d_desc {
   int32_t N, C_in, L;       /* input  [N, C_in, L]                    */
@@ -298,7 +300,8 @@ const char* tconv_status_string(int status);
 
 /*
  * Name of the forward kernel tconv_forward would launch for this descriptor
- * ("tiled3x3" or "generic"), for tests and benchmarks.  Host only; NULL on a bad descriptor.
+ * ("tiled3x3", "row1d" - one-row inputs with a window of 8 taps or more - or "generic"), for tests and
+ * benchmarks.  Host only; NULL on a bad descriptor.
  */
 const char* tconv_forward_kernel_name(const tconv_desc* desc);
 
