@@ -55,7 +55,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
-    int n_units, int n_groups, int wrps, int dbg) {
+    int n_units, int n_groups, int wrps, int dbg, int n_blocks) {
   // the mixed layers run as one branch: (iii) through the min-side kernel, accumulators and outputs
   // (its operator is min-plus), (vi) through the max side; only the start value and the block differ
   constexpr bool DO_MIN = mode_has_min(MODE), DO_MAX = mode_has_max(MODE);
@@ -64,10 +64,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The workgroups of one pixel
+  // block (same input lines, different output-channel groups) are numbered consecutively; give every XCD a
+  // contiguous run of numbers, so that they meet in one L2 instead of fetching the lines once per XCD.
+  const int per_xcd = (n_blocks + 7) >> 3;
+  const int bid = (dbg & 32) ? (int)blockIdx.x : (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+  if (bid >= n_blocks) return;  // padding of the grid to a multiple of 8; the kernel has no barrier
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
-  const int ublock = blockIdx.x / gblocks;
+  const int ublock = bid / gblocks;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int group = (blockIdx.x - ublock * gblocks) * WAVES + wave;
+  const int group = (bid - ublock * gblocks) * WAVES + wave;
   if (group >= n_groups) return;  // whole wave leaves; the kernel has no barrier
   const int co0 = group * TN;
   const int lane = threadIdx.x & 63;
@@ -475,7 +481,7 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
   const long long ublocks = (n_units + 63) / 64;
   const long long gblocks = (n_groups + WAVES - 1) / WAVES;
   const long long blocks = ublocks * gblocks;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (blocks > 0x7ffffff0LL) return hipErrorInvalidValue;
   const char* e = getenv("TCONV_DEBUG_FLAGS");
   const int dbg = e ? atoi(e) : 0;
   // kernel rows a wave stages in LDS for the epilogue gathers: as many (a power of two) as fit its
@@ -487,9 +493,10 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
     if ((long long)r * KS <= 3072) { wrps = r; break; }
   if (dbg & 16) wrps = 0;
   const size_t lds = (size_t)WAVES * wrps * KS * sizeof(float);
-  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, TO>), dim3((unsigned)blocks), dim3(WAVES * 64),
+  const long long grid = ((blocks + 7) / 8) * 8;  // the kernel renumbers the workgroups per XCD
+  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, TO>), dim3((unsigned)grid), dim3(WAVES * 64),
                      lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
-                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, wrps, dbg);
+                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, wrps, dbg, (int)blocks);
   return hipGetLastError();
 }
 
