@@ -37,9 +37,9 @@ HBM_PEAK_GBS = 8000.0
 # WRITE_SIZE runs of this script and scaled by what a plain device copy reads on the same counters; the
 # summaries under profiles/ give the commands and the raw figures.  Keyed by (workload, mode, op).
 MEASURED_FORWARD_TRAFFIC = {
-    ("cfg2_main", "compound", "full"): 317.0e6 + 167.8e6,
-    ("cfg4a", "compound", "full"): 1547.0e6 + 335.6e6,
-    ("cfg2_main", "minplus_max", "full"): 294.9e6 + 100.7e6,
+    ("cfg2_main", "compound", "full"): 53.7e6 + 167.8e6,
+    ("cfg4a", "compound", "full"): 143.7e6 + 335.6e6,
+    ("cfg2_main", "minplus_max", "full"): 52.4e6 + 100.7e6,
 }
 
 
