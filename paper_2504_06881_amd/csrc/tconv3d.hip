@@ -117,13 +117,23 @@ __global__ __launch_bounds__(WAVES * 64) void fwd3d_k3_kernel(Params3 p, const f
                                                               int32_t* __restrict__ idx_min,
                                                               int32_t* __restrict__ idx_max, int segs,
                                                               unsigned n_units, unsigned inv_segs, unsigned inv_ho,
-                                                              unsigned inv_do) {
+                                                              unsigned inv_do, int gblocks, unsigned inv_gblocks,
+                                                              int n_blocks, int xcd_runs) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int co0 = (blockIdx.y * WAVES + wave) * TN3;
-  if (co0 >= p.C_out) return;  // whole wave; the kernel has no barrier
-  const unsigned u_raw = blockIdx.x * 64u + lane;
+  // Workgroup number = pixel block * gblocks + output-channel block.  Workgroups are dealt round-robin to the 8
+  // XCDs, each with its own L2; with xcd_runs every XCD gets a contiguous run of numbers, so that the channel
+  // blocks of a pixel block (same input lines) run at the same time behind one L2.  The grid is padded to a
+  // multiple of 8; the kernel has no barrier.
+  const int per_xcd = (n_blocks + 7) >> 3;
+  const int bid = xcd_runs ? (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  if (bid >= n_blocks) return;
+  const unsigned ub = fast_div3((unsigned)bid, inv_gblocks);
+  const int gb = bid - (int)ub * gblocks;
+  const int co0 = (gb * WAVES + wave) * TN3;
+  if (co0 >= p.C_out) return;  // whole wave
+  const unsigned u_raw = ub * 64u + lane;
   const bool unit_ok = u_raw < n_units;
   const unsigned u = unit_ok ? u_raw : n_units - 1;  // surplus lanes recompute the last unit and store nothing
   const unsigned t1 = fast_div3(u, inv_segs);
@@ -272,7 +282,8 @@ bool k3_ok(const Params3& p) {
   const long long dmax = segs > p.Ho ? (segs > p.Do ? segs : p.Do) : (p.Ho > p.Do ? p.Ho : p.Do);
   if (units * dmax >= 0xffffffffLL) return false;                    // multiply-high quotients stay exact
   if ((long long)p.D * p.H * p.W >= 0x7fffffffLL) return false;      // 32-bit offsets inside a channel volume
-  return ((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES <= 65535;
+  const long long gblocks = ((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES;
+  return ((units + 63) / 64) * gblocks < 0x7ffffff0LL / gblocks;  // workgroup numbers fit, their quotient by gblocks stays exact
 }
 
 unsigned inv3(int d) { return d > 1 ? (unsigned)(0x100000000ull / (unsigned)d) + 1u : 0u; }
@@ -281,10 +292,16 @@ template <int MODE>
 hipError_t launch_k3(const Params3& p, const FwdArgs& a, hipStream_t s) {
   const int segs = (p.Wo + 3) / 4;
   const unsigned n_units = (unsigned)((long long)p.N * p.Do * p.Ho * segs);
-  const dim3 grid((n_units + 63) / 64, (unsigned)(((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES));
+  const int gblocks = ((p.C_out + TN3 - 1) / TN3 + WAVES - 1) / WAVES;
+  const long long n_blocks = (long long)((n_units + 63) / 64) * gblocks;
+  const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * (MODE == TCONV_PARALLEL ? 2 : 1);
+  const char* xe = getenv("TCONV_XCD_RUNS");
+  const int xcd_runs = xe ? atoi(xe) : (w_bytes <= 2LL * 1024 * 1024 ? 1 : 0);  // as for the two-dimensional kernel
+  const dim3 grid((unsigned)(((n_blocks + 7) / 8) * 8));
   hipLaunchKernelGGL(fwd3d_k3_kernel<MODE>, grid, dim3(WAVES * 64), 0, s, p, (const float*)a.x, (const float*)a.w_min,
                      (const float*)a.w_max, a.alpha, a.beta, (float*)a.y, (float*)a.y_min, (float*)a.y_max, a.idx_min,
-                     a.idx_max, segs, n_units, inv3(segs), inv3(p.Ho), inv3(p.Do));
+                     a.idx_max, segs, n_units, inv3(segs), inv3(p.Ho), inv3(p.Do), gblocks, inv3(gblocks),
+                     (int)n_blocks, xcd_runs);
   return hipGetLastError();
 }
 

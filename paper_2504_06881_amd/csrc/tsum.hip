@@ -85,16 +85,22 @@ template <int MODE, int D>
 __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
-    float* __restrict__ y, int segs, int n_units, int n_groups) {
+    float* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int PX = 8, TN = 4;
   constexpr int XR = PX + 2 * D;
 
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  xcd_runs: every XCD gets a contiguous
+  // run of workgroup numbers, so that the output-channel groups of a pixel block (consecutive numbers, same
+  // input lines) meet in one L2.  The grid is padded to a multiple of 8; the kernel has no barrier.
+  const int per_xcd = (n_blocks + 7) >> 3;
+  const int bid = xcd_runs ? (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  if (bid >= n_blocks) return;
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
-  const int ublock = blockIdx.x / gblocks;
+  const int ublock = bid / gblocks;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int group = (blockIdx.x - ublock * gblocks) * WAVES + wave;
+  const int group = (bid - ublock * gblocks) * WAVES + wave;
   if (group >= n_groups) return;  // whole wave leaves; the kernel has no barrier
   const int co0 = group * TN;
   const int lane = threadIdx.x & 63;
@@ -602,13 +608,18 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const long long n_units = (long long)p.N * p.Ho * segs;
     const int n_groups = (p.C_out + 3) / 4;
     const long long blocks = ((n_units + 63) / 64) * ((n_groups + WAVES - 1) / WAVES);
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (blocks > 0x7ffffff0LL) return hipErrorInvalidValue;
+    // contiguous runs per XCD while the kernels and coefficients are small next to an L2 (as for the full-window kernel)
+    const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * (MODE == TCONV_PARALLEL ? 2 : 1);
+    const char* xe = getenv("TCONV_XCD_RUNS");
+    const int xcd_runs = xe ? atoi(xe) : (w_bytes <= 2LL * 1024 * 1024 ? 1 : 0);
+    const unsigned grid = (unsigned)(((blocks + 7) / 8) * 8);
     if (p.dh == 1)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                         a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups);
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
+                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
     else
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2>), dim3((unsigned)blocks), dim3(WAVES * 64), 0, s, p,
-                         a.x, a.w_min, a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups);
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
+                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
   } else {
     const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
     hipLaunchKernelGGL(sum_fwd_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p,
