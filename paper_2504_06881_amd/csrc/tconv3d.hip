@@ -345,11 +345,15 @@ __global__ __launch_bounds__(256) void bwd3d_input_kernel(Params3 p, BwdArgs a, 
 // fill).  K27: the 3 x 3 x 3 window, whose tap numbers unflatten by constants.
 template <int MODE, bool K27>
 __global__ __launch_bounds__(256) void bwd3d_input_tile_kernel(Params3 p, BwdArgs a, float* __restrict__ grad_x, int TH,
-                                                               int CC, int tiles_h, int chunks) {
+                                                               int CC, int tiles_h, int chunks, int n_blocks) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   HIP_DYNAMIC_SHARED(double, tile3)
-  int b = blockIdx.x;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous run of tiles,
+  // so that neighbouring depth slices and row tiles (which scan the same gy / idx lines) share one L2.
+  const int per_xcd = (n_blocks + 7) >> 3;
+  int b = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+  if (b >= n_blocks) return;  // padding of the grid: the whole workgroup leaves before any barrier
   const int ch = b % chunks; b /= chunks;
   const int th = b % tiles_h; b /= tiles_h;
   const int id = b % p.D;
@@ -453,16 +457,16 @@ hipError_t launch_backward_input_3d(const Params3& p, const BwdArgs& a, float* g
     if (TH < 1) TH = 1;
     const int tiles_h = (p.H + TH - 1) / TH, chunks = (p.C_in + CC - 1) / CC;
     const long long blocks = (long long)p.N * p.D * tiles_h * chunks;
-    if (blocks <= 0x7fffffffLL) {
+    if (blocks <= 0x7ffffff0LL) {
       const size_t lds = (size_t)CC * TH * row_bytes;
-      const dim3 grid((unsigned)blocks);
+      const dim3 grid((unsigned)(((blocks + 7) / 8) * 8));  // the kernel renumbers the workgroups per XCD
       const bool k27 = (p.KD == 3 && p.KH == 3 && p.KW == 3);
 #define TCONV_LAUNCH_BWD3(M)                                                                                      \
   do {                                                                                                            \
     if (k27) hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, true>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC, \
-                                tiles_h, chunks);                                                                 \
+                                tiles_h, chunks, (int)blocks);                                                    \
     else hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, false>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC,    \
-                            tiles_h, chunks);                                                                     \
+                            tiles_h, chunks, (int)blocks);                                                        \
   } while (0)
       switch (p.mode) {
         case TCONV_MAX: TCONV_LAUNCH_BWD3(TCONV_MAX); break;
