@@ -337,66 +337,99 @@ __global__ __launch_bounds__(256) void bwd3d_input_kernel(Params3 p, BwdArgs a, 
 }
 
 
-// Input gradient without global atomics: a workgroup owns TH rows of one depth slice of one image for a chunk of
-// CC input channels, keeps their sums in LDS as fp64 ([CC][TH][W]) and scans every output whose window can
-// reach them: the output depths od with od*sd - pd + a*dd == id for a depth tap a, the output rows around the
-// tile, all output columns and channels.  An output is taken if its winner has that depth tap and lands inside
-// the tile.  Every input element belongs to exactly one workgroup, so plain stores finish the job (no zero
-// fill).  K27: the 3 x 3 x 3 window, whose tap numbers unflatten by constants.
+// Input gradient without global atomics: a workgroup owns a box of TD depth slices x TH rows (all columns) of one
+// image for a chunk of CC input channels, keeps their sums in LDS as fp64 ([CC][TD][TH][W]) and scans every output
+// whose window can reach the box: the output depths and rows around it, all output columns and channels.  An
+// output is taken if its winner lands inside the box.  Every input element belongs to exactly one workgroup, so
+// plain stores finish the job (no zero fill).  The box is as cubic as LDS allows: an output is visited by
+// (TD + reach) / TD x (TH + reach) / TH workgroups.  Item and element numbers unflatten by multiply-high
+// (inv = floor(2^32 / d) + 1, exact while number * d < 2^32; the host passes 0 where that cannot be shown, then
+// the kernel divides).  K27: the 3 x 3 x 3 window, whose tap numbers unflatten by constants.
+__device__ __forceinline__ unsigned divq(unsigned u, unsigned d, unsigned inv) {
+  return inv ? __umulhi(u, inv) : (d == 1 ? u : u / d);
+}
+
 template <int MODE, bool K27>
-__global__ __launch_bounds__(256) void bwd3d_input_tile_kernel(Params3 p, BwdArgs a, float* __restrict__ grad_x, int TH,
-                                                               int CC, int tiles_h, int chunks, int n_blocks) {
+__global__ __launch_bounds__(1024) void bwd3d_input_tile_kernel(Params3 p, BwdArgs a, float* __restrict__ grad_x, int TD,
+                                                                int TH, int CC, int tiles_d, int tiles_h, int chunks,
+                                                                int n_blocks, int fast, unsigned inv_wo, unsigned inv_w,
+                                                                unsigned inv_th, unsigned inv_td) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   HIP_DYNAMIC_SHARED(double, tile3)
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous run of tiles,
-  // so that neighbouring depth slices and row tiles (which scan the same gy / idx lines) share one L2.
+  const int bd = blockDim.x;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous run of boxes,
+  // so that neighbouring boxes (which scan the same gy / idx lines) share one L2.
   const int per_xcd = (n_blocks + 7) >> 3;
   int b = (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
   if (b >= n_blocks) return;  // padding of the grid: the whole workgroup leaves before any barrier
   const int ch = b % chunks; b /= chunks;
   const int th = b % tiles_h; b /= tiles_h;
-  const int id = b % p.D;
-  const int n = b / p.D;
-  const int h0 = th * TH, c0 = ch * CC;
-  const int tsz = CC * TH * p.W;
-  for (int e = threadIdx.x; e < tsz; e += 256) tile3[e] = 0.0;
+  const int td = b % tiles_d;
+  const int n = b / tiles_d;
+  const int d0 = td * TD, h0 = th * TH, c0 = ch * CC;
+  const int tsz = CC * TD * TH * p.W;
+  for (int e = threadIdx.x; e < tsz; e += bd) tile3[e] = 0.0;
   __syncthreads();
 
-  const int KH = K27 ? 3 : p.KH, KW = K27 ? 3 : p.KW, KHW = KH * KW, KK = (K27 ? 3 : p.KD) * KHW;
-  // output rows whose window can reach the tile rows
-  const int nh = h0 + p.ph - (KH - 1) * p.dh;
-  const int oh_lo = nh <= 0 ? 0 : (nh + p.sh - 1) / p.sh;
-  const int oh_hi = min(p.Ho - 1, (h0 + TH - 1 + p.ph) / p.sh);
+  const int KD = K27 ? 3 : p.KD, KH = K27 ? 3 : p.KH, KW = K27 ? 3 : p.KW, KHW = KH * KW, KK = KD * KHW;
+  // output depths and rows whose window can reach the box
+  const int nd = d0 + p.pd - (KD - 1) * p.dd, nh = h0 + p.ph - (KH - 1) * p.dh;
+  const int od_lo = nd <= 0 ? 0 : (nd + p.sd - 1) / p.sd, oh_lo = nh <= 0 ? 0 : (nh + p.sh - 1) / p.sh;
+  const int od_hi = min(p.Do - 1, (d0 + TD - 1 + p.pd) / p.sd), oh_hi = min(p.Ho - 1, (h0 + TH - 1 + p.ph) / p.sh);
   const int RH = max(oh_hi - oh_lo + 1, 0);
+  const int P = RH * p.Wo;          // pixels per output depth and channel
+  const int per_od = p.C_out * P;   // items per output depth: (co, oh, ow), ow fastest
+  const unsigned inv_p = (fast && P > 1) ? 0xffffffffu / (unsigned)P + 1u : 0u;
   const size_t ovol = (size_t)p.Do * p.Ho * p.Wo;
-  const int per_od = p.C_out * RH * p.Wo;  // items per output depth: (co, oh, ow), ow fastest
-  for (int ta = 0; ta < (K27 ? 3 : p.KD); ++ta) {
-    const int t = id + p.pd - ta * p.dd;
-    if (t < 0 || t % p.sd != 0 || t / p.sd >= p.Do) continue;  // no output depth reads this slice through tap ta
-    const int od = t / p.sd;
-    for (int it = threadIdx.x; it < per_od; it += 256) {
-      const int ow = it % p.Wo, r = it / p.Wo, oh = oh_lo + r % RH, co = r / RH;
-      const size_t o = ((size_t)n * p.C_out + co) * ovol + ((size_t)od * p.Ho + oh) * p.Wo + ow;
-      const float g = a.gy[o];
-      const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw;
-      auto deposit = [&](int k, double v) {
-        const int c = k / KK, tt = k - c * KK, ka = tt / KHW, rr = tt - ka * KHW, ki = rr / KW, kj = rr - ki * KW;
-        const int ih = bh + ki * p.dh, iw = bw + kj * p.dw, cc = c - c0;
-        if (ka == ta && (unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)p.W && (unsigned)cc < (unsigned)CC &&
-            h0 + ih < p.H)
-          atomicAdd(&tile3[(cc * TH + ih) * p.W + iw], v);
-      };
-      if (DO_MIN) deposit(a.idx_min[o], (SCALED && a.alpha) ? (double)a.alpha[co] * (double)g : (double)g);
-      if (DO_MAX) deposit(a.idx_max[o], (SCALED && a.beta) ? (double)a.beta[co] * (double)g : (double)g);
+  for (int od = od_lo; od <= od_hi && P > 0; ++od) {
+    const int bdz = od * p.sd - p.pd - d0;
+    const size_t obase = (size_t)n * p.C_out * ovol + (size_t)od * p.Ho * p.Wo;
+    constexpr int UB = 4;  // items per thread in flight
+    for (int it0 = threadIdx.x; it0 < per_od; it0 += bd * UB) {
+      float gv[UB];
+      int kmn[UB], kmx[UB], cov[UB], bhv[UB], bwv[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        const int it = min(it0 + u * bd, per_od - 1);
+        const int co = P > 1 ? (int)divq((unsigned)it, (unsigned)P, inv_p) : it;
+        const int px = it - co * P;
+        const int r = (int)divq((unsigned)px, (unsigned)p.Wo, fast ? inv_wo : 0u);
+        const int ow = px - r * p.Wo, oh = oh_lo + r;
+        const size_t o = obase + (size_t)co * ovol + (size_t)oh * p.Wo + ow;
+        gv[u] = a.gy[o];
+        if (DO_MIN) kmn[u] = a.idx_min[o];
+        if (DO_MAX) kmx[u] = a.idx_max[o];
+        cov[u] = co;
+        bhv[u] = oh * p.sh - p.ph - h0;
+        bwv[u] = ow * p.sw - p.pw;
+      }
+#pragma unroll
+      for (int u = 0; u < UB; ++u) {
+        if (it0 + u * bd >= per_od) break;
+        const int bh = bhv[u], bw = bwv[u];
+        auto deposit = [&](int k, double v) {
+          const int c = k / KK, tt = k - c * KK, ka = tt / KHW, rr = tt - ka * KHW, ki = rr / KW, kj = rr - ki * KW;
+          const int dz = bdz + ka * p.dd, ih = bh + ki * p.dh, iw = bw + kj * p.dw, cc = c - c0;
+          if ((unsigned)dz < (unsigned)TD && (unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)p.W &&
+              (unsigned)cc < (unsigned)CC && d0 + dz < p.D && h0 + ih < p.H)
+            atomicAdd(&tile3[((cc * TD + dz) * TH + ih) * p.W + iw], v);
+        };
+        const double g = (double)gv[u];
+        if (DO_MIN) deposit(kmn[u], (SCALED && a.alpha) ? (double)a.alpha[cov[u]] * g : g);
+        if (DO_MAX) deposit(kmx[u], (SCALED && a.beta) ? (double)a.beta[cov[u]] * g : g);
+      }
     }
   }
   __syncthreads();
   const size_t vol = (size_t)p.D * p.H * p.W;
-  float* gxn = grad_x + (size_t)n * p.C_in * vol + (size_t)id * p.H * p.W;
-  for (int e = threadIdx.x; e < tsz; e += 256) {
-    const int iw = e % p.W, ih = (e / p.W) % TH, cc = e / (p.W * TH);
-    if (h0 + ih < p.H && c0 + cc < p.C_in) gxn[(size_t)(c0 + cc) * vol + (size_t)(h0 + ih) * p.W + iw] = (float)tile3[e];
+  float* gxn = grad_x + (size_t)n * p.C_in * vol;
+  for (int e = threadIdx.x; e < tsz; e += bd) {
+    const unsigned t1 = divq((unsigned)e, (unsigned)p.W, inv_w), t2 = divq(t1, (unsigned)TH, inv_th);
+    const unsigned cc = divq(t2, (unsigned)TD, inv_td);
+    const int iw = e - (int)t1 * p.W, ih = (int)t1 - (int)t2 * TH, dz = (int)t2 - (int)cc * TD;
+    if (d0 + dz < p.D && h0 + ih < p.H && c0 + (int)cc < p.C_in)
+      gxn[(size_t)(c0 + cc) * vol + ((size_t)(d0 + dz) * p.H + (h0 + ih)) * p.W + iw] = (float)tile3[e];
   }
 }
 
@@ -444,29 +477,50 @@ hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s) 
 
 // p.mode is a backward mode here (the mixed layers arrive as MIN / MAX)
 hipError_t launch_backward_input_3d(const Params3& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
-  // LDS tile [CC][TH][W] of doubles: all channels if a few rows of them fit, else chunks of channels
-  const size_t budget = 48 * 1024;
+  // LDS box [CC][TD][TH][W] of doubles: all channels if a 2 x 2 box of them fits, else chunks of channels; then the
+  // depth x row shape that lets the fewest workgroups visit an output
+  size_t budget = 72 * 1024;  // two workgroups of 1024 threads per compute unit
+  if (const char* eb = getenv("TCONV_BWD3_LDS_KB")) budget = (size_t)atoi(eb) * 1024;  // testing aid: smaller boxes
   const size_t row_bytes = (size_t)p.W * sizeof(double);
   const char* e = getenv("TCONV_FORWARD_KERNEL");
   const bool plain = e && strcmp(e, "generic") == 0;
   if (!plain && row_bytes <= budget) {
+    const int min_rows = (p.D < 2 ? p.D : 2) * (p.H < 2 ? p.H : 2);
     int CC = p.C_in;
-    while (CC > 1 && (size_t)CC * row_bytes * (p.H < 4 ? p.H : 4) > budget) CC = (CC + 1) / 2;
-    int TH = (int)(budget / ((size_t)CC * row_bytes));
-    if (TH > p.H) TH = p.H;
-    if (TH < 1) TH = 1;
-    const int tiles_h = (p.H + TH - 1) / TH, chunks = (p.C_in + CC - 1) / CC;
-    const long long blocks = (long long)p.N * p.D * tiles_h * chunks;
-    if (blocks <= 0x7ffffff0LL) {
-      const size_t lds = (size_t)CC * TH * row_bytes;
+    while (CC > 1 && (size_t)CC * row_bytes * min_rows > budget) CC = (CC + 1) / 2;
+    const int rows = (int)(budget / ((size_t)CC * row_bytes));  // (depth, row) pairs that fit
+    const double ed = (double)(p.KD - 1) * p.dd, eh = (double)(p.KH - 1) * p.dh;
+    int TD = 1, TH = 1;
+    double best = 1e30;
+    for (int td = 1; td <= p.D && td <= rows; ++td) {
+      int thh = rows / td;
+      if (thh > p.H) thh = p.H;
+      const double cost = (td + ed) / td * (thh + eh) / thh;
+      if (cost < best - 1e-9) { best = cost; TD = td; TH = thh; }
+    }
+    const int tiles_d = (p.D + TD - 1) / TD, tiles_h = (p.H + TH - 1) / TH, chunks = (p.C_in + CC - 1) / CC;
+    TD = (p.D + tiles_d - 1) / tiles_d;  // even boxes
+    TH = (p.H + tiles_h - 1) / tiles_h;
+    const long long blocks = (long long)p.N * tiles_d * tiles_h * chunks;
+    const long long tsz = (long long)CC * TD * TH * p.W;
+    if (blocks <= 0x7ffffff0LL && tsz < 0x7fffffffLL) {
+      const size_t lds = (size_t)tsz * sizeof(double);
       const dim3 grid((unsigned)(((blocks + 7) / 8) * 8));  // the kernel renumbers the workgroups per XCD
       const bool k27 = (p.KD == 3 && p.KH == 3 && p.KW == 3);
-#define TCONV_LAUNCH_BWD3(M)                                                                                      \
-  do {                                                                                                            \
-    if (k27) hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, true>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC, \
-                                tiles_h, chunks, (int)blocks);                                                    \
-    else hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, false>), grid, dim3(256), lds, s, p, a, grad_x, TH, CC,    \
-                            tiles_h, chunks, (int)blocks);                                                        \
+      // multiply-high quotients: items it < C_out * P with P <= Ho * Wo pixels; elements e < tsz
+      const long long pmax = (long long)p.Ho * p.Wo;
+      const int fast = ((long long)p.C_out * pmax < 0x100000000LL / pmax) ? 1 : 0;
+      const long long dmax = p.W > TH ? (p.W > TD ? p.W : TD) : (TH > TD ? TH : TD);
+      const bool fast_e = tsz * dmax < 0x100000000LL;
+      const unsigned inv_wo = fast ? inv3(p.Wo) : 0u;
+      const unsigned inv_w = fast_e ? inv3(p.W) : 0u, inv_th = fast_e ? inv3(TH) : 0u, inv_td = fast_e ? inv3(TD) : 0u;
+      const int threads = 1024;
+#define TCONV_LAUNCH_BWD3(M)                                                                                       \
+  do {                                                                                                             \
+    if (k27) hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, true>), grid, dim3(threads), lds, s, p, a, grad_x, TD, TH, \
+                                CC, tiles_d, tiles_h, chunks, (int)blocks, fast, inv_wo, inv_w, inv_th, inv_td);   \
+    else hipLaunchKernelGGL((bwd3d_input_tile_kernel<M, false>), grid, dim3(threads), lds, s, p, a, grad_x, TD, TH,    \
+                            CC, tiles_d, tiles_h, chunks, (int)blocks, fast, inv_wo, inv_w, inv_th, inv_td);       \
   } while (0)
       switch (p.mode) {
         case TCONV_MAX: TCONV_LAUNCH_BWD3(TCONV_MAX); break;
