@@ -508,11 +508,14 @@ __global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float
   // x through a buffer resource and 32-bit offsets: row offset + column offset per tap, clamped into the
   // image (a tap outside it is loaded from the clamped position and replaced by the branch's identity)
   const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * p.H * p.W * sizeof(float)));
+  const int oh_first = (int)threadIdx.x / p.Wo, ow_first = (int)threadIdx.x % p.Wo;
+  const int d_oh = (int)blockDim.x / p.Wo, d_ow = (int)blockDim.x % p.Wo;
   for (int n = n0; n < n1; ++n) {
     const unsigned xbase = (unsigned)(((size_t)n * p.C_in + c) * p.H * p.W * sizeof(float));  // uniform
     const float* gyc = gy + ((size_t)n * p.C_out + co) * plane;
-    for (int i = threadIdx.x; i < plane; i += blockDim.x) {
-      const int oh = i / p.Wo, ow = i % p.Wo;
+    int oh = oh_first, ow = ow_first;
+    for (int i = threadIdx.x; i < plane; i += blockDim.x, oh += d_oh, ow += d_ow) {
+      if (ow >= p.Wo) { ow -= p.Wo; ++oh; }  // (oh, ow) = (i / Wo, i % Wo), kept by increments: no division per pixel
       const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
       const double g = (double)gyc[i];
       unsigned roff[3], coff[3];
@@ -532,16 +535,17 @@ __global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float
       int tmin = 0, tmax = 0;
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
-        const bool ok = rok[t / 3] && cok[t % 3];
-        const float xv = xv9[t];
+        // a tap outside the image becomes NaN once for both branches: no strict compare selects it
+        const float xv = (rok[t / 3] && cok[t % 3]) ? xv9[t] : __uint_as_float(0x7fc00000u);
+        const float s1 = __fadd_rn(xv, ka[t]);
         if (DO_MIN) {
-          const float sm = ok ? __fadd_rn(xv, ka[t]) : INFINITY;
+          const float sm = s1;
           const bool b = sm < bmin;
           bmin = b ? sm : bmin;
           tmin = b ? t : tmin;
         }
         if (DO_MAX) {
-          const float sm = ok ? __fadd_rn(xv, kb[t]) : -INFINITY;
+          const float sm = (MODE == TCONV_COMPOUND) ? s1 : __fadd_rn(xv, kb[t]);  // compound: one shared kernel
           const bool b = sm > bmax;
           bmax = b ? sm : bmax;
           tmax = b ? t : tmax;
