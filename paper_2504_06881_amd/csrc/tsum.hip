@@ -316,6 +316,25 @@ __global__ __launch_bounds__(256) void sum_bwd_x_kernel(Params p, const float* _
   for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) gxc[i] = (float)tile[i];
 }
 
+// Extremum of the 9 sums of a 3 x 3 window and its lowest tap, without a compare-and-select chain over the taps:
+// three v_min3 / v_max3 over the rows, one over the row results, then the first row and the first column of it
+// that equal the extremum (19 instructions where the chain takes 27).  NaN sums (taps outside the image) are
+// ignored by the three-operand instructions and equal nothing.
+template <bool WANT_MAX>
+__device__ __forceinline__ void window_extremum9(const float (&s)[9], float& best, int& tap) {
+  float r[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+    r[i] = WANT_MAX ? fmaxf(fmaxf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]) : fminf(fminf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]);
+  best = WANT_MAX ? fmaxf(fmaxf(r[0], r[1]), r[2]) : fminf(fminf(r[0], r[1]), r[2]);
+  const bool c0 = r[0] == best, c1 = r[1] == best;
+  const int row = c0 ? 0 : (c1 ? 1 : 2);
+  const float a0 = c0 ? s[0] : (c1 ? s[3] : s[6]);
+  const float a1 = c0 ? s[1] : (c1 ? s[4] : s[7]);
+  const int col = (a0 == best) ? 0 : ((a1 == best) ? 1 : 2);
+  tap = row * 3 + col;
+}
+
 // grad_x for 3x3 windows: the same workgroup layout, but a thread keeps the 9 input values of its output
 // pixel in registers and walks all output channels with them (the kernel values of a (c_out, c_in)
 // pair are wave-uniform scalars, gy is read coalesced), so that a (pixel, c_out) item costs about 70
@@ -367,30 +386,22 @@ __global__ __launch_bounds__(256) void sum_bwd_x3x3_kernel(Params p, const float
       const float g = gyp[(size_t)co * plane];
       if (DO_MIN) {
         const float* w9 = w_min + ((size_t)co * p.C_in + c) * 9;
-        float best = INFINITY;
-        int ts = 0;
+        float sums[9], best;
+        int ts;
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-          const float sm = __fadd_rn(xlo[t], w9[t]);
-          const bool b = sm < best;
-          best = b ? sm : best;
-          ts = b ? t : ts;
-        }
+        for (int t = 0; t < 9; ++t) sums[t] = __fadd_rn(xlo[t], w9[t]);
+        window_extremum9<false>(sums, best, ts);
         const int ih = ih0 + (ts / 3) * p.dh, iw = iw0 + (ts % 3) * p.dw;
         if (ih >= r0 && ih < r1)
           atomicAdd(&tile[(ih - r0) * p.W + iw], (double)(TWO ? coef_of(alpha, c, co, p.C_out) : 1.0f) * (double)g);
       }
       if (DO_MAX) {
         const float* w9 = w_max + ((size_t)co * p.C_in + c) * 9;
-        float best = -INFINITY;
-        int ts = 0;
+        float sums[9], best;
+        int ts;
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-          const float sm = __fadd_rn(xhi[t], w9[t]);
-          const bool b = sm > best;
-          best = b ? sm : best;
-          ts = b ? t : ts;
-        }
+        for (int t = 0; t < 9; ++t) sums[t] = __fadd_rn(xhi[t], w9[t]);
+        window_extremum9<true>(sums, best, ts);
         const int ih = ih0 + (ts / 3) * p.dh, iw = iw0 + (ts % 3) * p.dw;
         if (ih >= r0 && ih < r1)
           atomicAdd(&tile[(ih - r0) * p.W + iw], (double)(TWO ? coef_of(beta, c, co, p.C_out) : 1.0f) * (double)g);
@@ -533,24 +544,16 @@ __global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float
       for (int t = 0; t < 9; ++t) xv9[t] = load_one<float>(xres, roff[t / 3] + coff[t % 3], xbase);
       float bmin = INFINITY, bmax = -INFINITY;
       int tmin = 0, tmax = 0;
+      float s1[9], s2[9];
 #pragma unroll
       for (int t = 0; t < 9; ++t) {
-        // a tap outside the image becomes NaN once for both branches: no strict compare selects it
+        // a tap outside the image becomes NaN once for both branches: it is never the extremum
         const float xv = (rok[t / 3] && cok[t % 3]) ? xv9[t] : __uint_as_float(0x7fc00000u);
-        const float s1 = __fadd_rn(xv, ka[t]);
-        if (DO_MIN) {
-          const float sm = s1;
-          const bool b = sm < bmin;
-          bmin = b ? sm : bmin;
-          tmin = b ? t : tmin;
-        }
-        if (DO_MAX) {
-          const float sm = (MODE == TCONV_COMPOUND) ? s1 : __fadd_rn(xv, kb[t]);  // compound: one shared kernel
-          const bool b = sm > bmax;
-          bmax = b ? sm : bmax;
-          tmax = b ? t : tmax;
-        }
+        s1[t] = __fadd_rn(xv, ka[t]);
+        s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xv, kb[t]);  // compound: one shared kernel
       }
+      if (DO_MIN) window_extremum9<false>(s1, bmin, tmin);
+      if (DO_MAX) window_extremum9<true>(s2, bmax, tmax);
       if (DO_MIN) {
         mine[tmin * 256] += ca * g;
         mine[KK * 256] += g * (double)bmin;
