@@ -69,6 +69,26 @@ __device__ __forceinline__ float dw_combine(float m, float M, float a, float b) 
   return combine(a, m, b, M);
 }
 
+// Extremum of the 9 sums of a window and (if wanted) its lowest tap: one v_min3 / v_max3 per row, one over the row
+// results, then the first row and the first column of it that equal the extremum - 13 instructions for the tap
+// where a compare-and-select per tap takes 18.  NaN sums (padding) are ignored and equal nothing.
+template <bool WANT_MAX, bool WANT_TAP>
+__device__ __forceinline__ void dw_extremum9(const float (&s)[9], float& best, int& tap) {
+  float r[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+    r[i] = WANT_MAX ? fmaxf(fmaxf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]) : fminf(fminf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]);
+  best = WANT_MAX ? fmaxf(fmaxf(r[0], r[1]), r[2]) : fminf(fminf(r[0], r[1]), r[2]);
+  if (WANT_TAP) {
+    const bool c0 = r[0] == best, c1 = r[1] == best;
+    const int row = c0 ? 0 : (c1 ? 1 : 2);
+    const float a0 = c0 ? s[0] : (c1 ? s[3] : s[6]);
+    const float a1 = c0 ? s[1] : (c1 ? s[4] : s[7]);
+    const int col = (a0 == best) ? 0 : ((a1 == best) ? 1 : 2);
+    tap = row * 3 + col;
+  }
+}
+
 // 4 consecutive outputs of one row from the 3 x (3*S + 3) input values under them (padding = NaN, which
 // v_min3 / v_max3 ignore and which never equals an extremum): y, and the packed winners if wanted.
 template <int MODE, int S, bool WANT_IDX>
@@ -88,26 +108,8 @@ __device__ __forceinline__ void dw_px4(const float (&xs)[3][3 * S + 3], const fl
       }
     float m = 0.f, M = 0.f;
     int tm = 0, tM = 0;
-    if (DO_MIN) {
-      m = fminf(fminf(sa[0], sa[1]), sa[2]);
-      m = fminf(fminf(m, sa[3]), sa[4]);
-      m = fminf(fminf(m, sa[5]), sa[6]);
-      m = fminf(fminf(m, sa[7]), sa[8]);
-      if (WANT_IDX) {
-#pragma unroll
-        for (int k = 8; k >= 0; --k) tm = (sa[k] == m) ? k : tm;
-      }
-    }
-    if (DO_MAX) {
-      M = fmaxf(fmaxf(sb[0], sb[1]), sb[2]);
-      M = fmaxf(fmaxf(M, sb[3]), sb[4]);
-      M = fmaxf(fmaxf(M, sb[5]), sb[6]);
-      M = fmaxf(fmaxf(M, sb[7]), sb[8]);
-      if (WANT_IDX) {
-#pragma unroll
-        for (int k = 8; k >= 0; --k) tM = (sb[k] == M) ? k : tM;
-      }
-    }
+    if (DO_MIN) dw_extremum9<false, WANT_IDX>(sa, m, tm);
+    if (DO_MAX) dw_extremum9<true, WANT_IDX>(sb, M, tM);
     out[q] = dw_combine<MODE>(m, M, a, b);
     code[q] = tm | (tM << 4);
   }
