@@ -40,6 +40,8 @@ MEASURED_FORWARD_TRAFFIC = {
     ("cfg2_main", "compound", "full"): 53.7e6 + 167.8e6,
     ("cfg4a", "compound", "full"): 143.7e6 + 335.6e6,
     ("cfg2_main", "minplus_max", "full"): 52.4e6 + 100.7e6,
+    ("c1d_main", "compound", "1d"): 305.1e6 + 983.1e6,
+    ("c1d_stem", "compound", "1d"): 11.0e6 + 655.4e6,
 }
 
 
@@ -365,7 +367,7 @@ def bench_1d(args, torch, tb) -> int:
         "roofline": {"bound": "alu", "kernel": "forward", "achieved": round(achieved / 1e12, 3),
                      "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
                      "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
-                     "traffic": None},
+                     "traffic": MEASURED_FORWARD_TRAFFIC.get((cfg.name, cfg.mode, "1d"))},
     }
     if not args.no_cpu_baseline:
         from oracle import tconv1d_oracle as o1
