@@ -2,9 +2,12 @@
 """Benchmark of the tropical-convolution hot path on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input:
-tconv_forward + tconv_backward_input + tconv_backward_weight of the headline
-layer (the CIFAR-scale ResNet block layer: x [128,64,32,32] -> 64 channels, 3x3, stride 1,
-pad 1, compound mode, fp32), inputs resident in HBM before the timed region.
+tconv_forward + tconv_backward (input and kernel gradient) of the headline layer - the largest
+single-GPU layer of the benchmark configurations, the segmentation-encoder layer
+x [8,128,128,128] -> 128 channels, 3x3, stride 1, pad 1, compound mode, fp32 - with the inputs
+resident in HBM before the timed region.  The same run measures every other layer the forward bar
+is stated on ("layers": forward time and fraction of the fp32 vector peak, backward GB/s on
+rotating buffers).
 
 Prints ONE JSON line:
   metric / value : add+compare pairs per second of the step (dense pair count / step time), GOPS
@@ -34,15 +37,19 @@ HBM_PEAK_GBS = 8000.0
 
 
 # HBM-side bytes per launch of the forward kernel (fetched + written), measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs of this script and scaled by what a plain device copy reads on the same counters; the
-# summaries under profiles/ give the commands and the raw figures.  Keyed by (workload, mode, op).
+# WRITE_SIZE runs of this script and scaled by what a plain device copy reads on the same counters.  Every entry
+# names the summary under profiles/ that holds the command and the raw figures.  Keyed by (workload, mode, dtype, op).
 MEASURED_FORWARD_TRAFFIC = {
-    ("cfg2_main", "compound", "full"): 53.7e6 + 167.8e6,
-    ("cfg4a", "compound", "full"): 143.7e6 + 335.6e6,
-    ("cfg2_main", "minplus_max", "full"): 52.4e6 + 100.7e6,
-    ("c1d_main", "compound", "1d"): 305.1e6 + 983.1e6,
-    ("c1d_stem", "compound", "1d"): 11.0e6 + 655.4e6,
+    ("cfg2_main", "compound", "f32", "full"): (53.7e6 + 167.8e6, "profiles/bench_cfg2_main_all_kernels.md"),
+    ("cfg2_main", "minplus_max", "f32", "full"): (52.4e6 + 100.7e6, "profiles/bench_cfg2_main_minplus_max_all_kernels.md"),
+    ("c1d_main", "compound", "f32", "1d"): (305.1e6 + 983.1e6, "profiles/bench_c1d_main_all_kernels.md"),
+    ("c1d_stem", "compound", "f32", "1d"): (11.0e6 + 655.4e6, "profiles/bench_c1d_stem_all_kernels.md"),
 }
+
+# The layers the forward bar is stated on (large 3 x 3 layers), the HBM-judged stem, and the bf16-storage variant.
+BAR_LAYERS = [("cfg2_main", None), ("cfg2_stem", None), ("cfg3a", None), ("cfg3b", None), ("cfg3c", None),
+              ("cfg4a", None), ("cfg4b", None), ("cfg4a", "bf16")]
+ROTATE_BYTES = 600e6   # backward calls are timed on rotating operand sets larger than the 256 MB last-level cache
 
 
 def alu_peak_pairs_per_s(mode: str) -> float:
@@ -58,7 +65,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2_main")
+    ap.add_argument("--workload", default="cfg4a",
+                    help="headline workload: a single-layer configuration (cfg4a: the largest single-GPU layer, "
+                         "x[8,128,128,128] -> 128 channels, compound, fp32; cfg2_main, cfg3a, ...) or cfg5, the 19 "
+                         "layers of a ResNet-20-style net")
     ap.add_argument("--op", default="full", choices=["full", "sum", "dw", "1d", "3d"],
                     help="full: the full-window layers (the headline path); sum: the Sum-channel layers "
                          "(tconv_sum_forward / tconv_sum_backward) on the same shapes; dw: the depthwise layers "
@@ -68,8 +78,13 @@ def main() -> int:
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"], help="storage type of x, kernels and outputs")
     ap.add_argument("--no-graph", action="store_true",
                     help="multi-layer workloads (cfg5): launch every step eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-layers", action="store_true",
+                    help="leave out the per-layer table of the other bar layers (profiling runs)")
+    ap.add_argument("--separate-backward", action="store_true",
+                    help="a step calls tconv_backward_input and tconv_backward_weight instead of the one-call tconv_backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -104,15 +119,18 @@ def main() -> int:
         cfgs = [CONFIGS[args.workload]]
         if args.mode:
             cfgs = [cfgs[0].with_(mode=args.mode)]
+        if args.dtype:
+            cfgs = [cfgs[0].with_(dtype=args.dtype)]
         c0 = cfgs[0]
         wl_name = (f"{c0.name}: x[{c0.N},{c0.C_in},{c0.H},{c0.W}] -> {c0.C_out}ch 3x3 s{c0.stride} p{c0.pad} "
                    f"d{c0.dil} {c0.mode} {c0.dtype}")
     dev = torch.device("cuda:0")
 
     class Layer:
-        """Device buffers and the three calls of one layer."""
+        """Device buffers and the calls of one layer.  rotate: number of operand sets (gy, idx, gradients) for the
+        cold-cache timing of the backward calls."""
 
-        def __init__(self, cfg, op):
+        def __init__(self, cfg, op, rotate=1):
             self.cfg = cfg
             self.op = op
             self.inp = inp = make_inputs(cfg)
@@ -128,22 +146,33 @@ def main() -> int:
                 self.w_min = self.w_max = up(inp["w_min"], tdt)
             else:
                 self.w_min, self.w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
-            self.gy = up(inp["gy"])
             osh = (cfg.N, cfg.C_out, ho, wo)
             do_min, do_max = cfg.mode not in ("max", "maxplus_min"), cfg.mode not in ("min", "minplus_max")
             self.y = torch.empty(osh, device=dev, dtype=tdt)
             self.y_min = torch.empty(osh, device=dev, dtype=tdt) if do_min else None
             self.y_max = torch.empty(osh, device=dev, dtype=tdt) if do_max else None
-            self.idx_min = torch.empty(osh, device=dev, dtype=torch.int32) if do_min else None
-            self.idx_max = torch.empty(osh, device=dev, dtype=torch.int32) if do_max else None
-            self.gx = torch.empty(tuple(inp["x"].shape), device=dev)
             wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
-            self.gw_min = torch.empty(wshape, device=dev) if do_min else None
-            self.gw_max = torch.empty(wshape, device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
+            gy0 = up(inp["gy"])
+            self.sets = []
+            for r in range(rotate):
+                self.sets.append(dict(
+                    gy=gy0 if r == 0 else gy0.clone(),
+                    idx_min=torch.empty(osh, device=dev, dtype=torch.int32) if do_min else None,
+                    idx_max=torch.empty(osh, device=dev, dtype=torch.int32) if do_max else None,
+                    gx=torch.empty(tuple(inp["x"].shape), device=dev),
+                    gw_min=torch.empty(wshape, device=dev) if do_min else None,
+                    gw_max=(torch.empty(wshape, device=dev)
+                            if cfg.mode in ("max", "parallel", "maxplus_min") else None)))
             self.n_out = cfg.N * cfg.C_out * ho * wo
             # algorithmic HBM bytes of the backward calls: gy + idx per output per branch, grad written once
             self.bytes_bi = self.n_out * (4 + 4 * cfg.branches) + inp["x"].size * 4
             self.bytes_bw = self.n_out * (4 + 4 * cfg.branches) + cfg.C_out * cfg.K * 4 * (2 if cfg.mode == "parallel" else 1)
+            # one pass over gy / idx serving both gradients
+            self.bytes_b = self.bytes_bi + self.bytes_bw - self.n_out * (4 + 4 * cfg.branches)
+            wsz = tb.tconv_workspace_bytes(d, "forward") if op == "full" else 0
+            self.ws_f = torch.empty(max(wsz, 1), device=dev, dtype=torch.uint8) if wsz else None
+            wsz = tb.tconv_workspace_bytes(d, "backward") if op == "full" else 0
+            self.ws_b = torch.empty(max(wsz // 8, 1), device=dev, dtype=torch.float64) if wsz else None
             if op == "sum":
                 two = cfg.mode in ("compound", "parallel")
                 g = torch.Generator(device="cpu")
@@ -156,33 +185,84 @@ def main() -> int:
                 # the backward pass re-reads x and gy instead of index tensors
                 self.bytes_bi = (inp["x"].size + self.n_out) * 4 + inp["x"].size * 4
                 self.bytes_bw = (inp["x"].size + self.n_out) * 4
+                self.bytes_b = self.bytes_bi + self.bytes_bw
 
-        def fwd(self):
+        def fwd(self, r=0):
+            s = self.sets[r]
             if self.op == "sum":
                 return tb.tconv_sum_forward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.y)
             tb.tconv_forward(self.d, self.x, self.w_min, self.w_max, None, None, self.y, self.y_min, self.y_max,
-                             self.idx_min, self.idx_max)
+                             s["idx_min"], s["idx_max"], self.ws_f)
 
-        def bwd_in(self):
+        def bwd_in(self, r=0):
+            s = self.sets[r]
             if self.op == "sum":
-                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.gy,
-                                             self.gx, None, None, None, None)
-            tb.tconv_backward_input(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gx)
+                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, s["gy"],
+                                             s["gx"], None, None, None, None)
+            tb.tconv_backward_input(self.d, s["gy"], None, None, s["idx_min"], s["idx_max"], s["gx"])
 
-        def bwd_w(self):
+        def bwd_w(self, r=0):
+            s = self.sets[r]
             if self.op == "sum":
-                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, self.gy,
-                                             None, self.gw_min, self.gw_max, self.ga, self.gb)
-            tb.tconv_backward_weight(self.d, self.gy, None, None, self.idx_min, self.idx_max, self.gw_min, self.gw_max)
+                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, s["gy"],
+                                             None, s["gw_min"], s["gw_max"], self.ga, self.gb)
+            tb.tconv_backward_weight(self.d, s["gy"], None, None, s["idx_min"], s["idx_max"], s["gw_min"],
+                                     s["gw_max"], self.ws_b)
+
+        def bwd(self, r=0):
+            """Both gradients: the one-call entry point (the Sum-channel layers: one call for all five gradients)."""
+            s = self.sets[r]
+            if self.op == "sum":
+                return tb.tconv_sum_backward(self.d, self.x, self.w_min, self.w_max, self.alpha, self.beta, s["gy"],
+                                             s["gx"], s["gw_min"], s["gw_max"], self.ga, self.gb)
+            if args.separate_backward:
+                self.bwd_in(r)
+                return self.bwd_w(r)
+            tb.tconv_backward(self.d, s["gy"], None, None, s["idx_min"], s["idx_max"], s["gx"], s["gw_min"],
+                              s["gw_max"], self.ws_b)
+
+        def rotate_count(self):
+            set_bytes = self.n_out * (4 + 4 * self.cfg.branches)
+            return int(ROTATE_BYTES // set_bytes) + 2
 
     if args.op == "sum" and any(c.dtype != "f32" for c in cfgs):
         print("bench.py: the Sum-channel layers are fp32 only", file=sys.stderr)
         return 2
-    layers = [Layer(c, args.op) for c in cfgs]
 
     # HIP events on the stream the kernels are launched on (torch's current stream)
     def ev():
         return torch.cuda.Event(enable_timing=True)
+
+    def time_loop(fn, reps):
+        """Average milliseconds per call of fn(i), i = 0 .. reps - 1, one event pair around the whole loop."""
+        e0, e1 = ev(), ev()
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def cold_backward(cfg, op):
+        """Backward calls of one layer on rotating operand sets, so that neither gy nor idx of a call is still in the
+        last-level cache from the call that wrote or last read them.  Returns (ms_bwd_input, ms_bwd_weight, ms_both, layer)."""
+        probe = Layer(cfg, op)
+        R = probe.rotate_count()
+        del probe
+        L = Layer(cfg, op, rotate=R)
+        for r in range(R):
+            L.fwd(r)                       # valid winners in every set
+        torch.cuda.synchronize()
+        reps = max(2 * R, 8)
+        for r in range(R):                 # warm-up of the three call paths
+            L.bwd_in(r); L.bwd_w(r); L.bwd(r)
+        torch.cuda.synchronize()
+        t_bi = time_loop(lambda i: L.bwd_in(i % R), reps)
+        t_bw = time_loop(lambda i: L.bwd_w(i % R), reps)
+        t_b = time_loop(lambda i: L.bwd(i % R), reps)
+        return t_bi, t_bw, t_b, L
+
+    layers = [Layer(c, args.op) for c in cfgs]
 
     if args.calibrate_copy:
         src = torch.empty(64 * 1024 * 1024, device=dev)  # 256 MiB
@@ -194,26 +274,25 @@ def main() -> int:
         del src, dst
     for _ in range(args.warmup):
         for L in layers:
-            L.fwd(); L.bwd_in(); L.bwd_w()
+            L.fwd(); L.bwd()
     torch.cuda.synchronize()
     # The timed region carries HIP events around the dominant (forward) kernel only: an event costs about 10 us of
-    # stream time on this stack, and four of them per step took 9 % off the step rate.  The two backward calls
-    # are timed in a short pass of their own right after the timed region (auxiliary figures).
+    # stream time on this stack.  The backward calls are timed in a pass of their own afterwards, on rotating buffers.
     graph = None
     if len(layers) > 1 and not args.no_graph:
-        # The multi-layer step is some 76 launches of 20 - 100 us each, which the Python launch path cannot always
+        # The multi-layer step is some 60 launches of 20 - 100 us each, which the Python launch path cannot always
         # feed fast enough: the whole step (every layer, forward and backward) is captured once in a HIP graph
         # and replayed.  The library records no memset (its zero fills are kernels), so it is capture-safe.
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             for L in layers:
-                L.fwd(); L.bwd_in(); L.bwd_w()
+                L.fwd(); L.bwd()
         torch.cuda.current_stream().wait_stream(side)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for L in layers:
-                L.fwd(); L.bwd_in(); L.bwd_w()
+                L.fwd(); L.bwd()
         graph.replay()
         torch.cuda.synchronize()
     marks = []
@@ -224,19 +303,25 @@ def main() -> int:
             continue
         for L in layers:
             e = [ev(), ev()]
-            e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); L.bwd_w()
+            e[0].record(); L.fwd(); e[1].record(); L.bwd()
             marks.append((L, e))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    if graph is not None:  # events cannot sit inside a graph: the forward launches are timed in an eager pass
-        for _ in range(args.steps):
+    if graph is not None:
+        # events cannot sit inside a graph, and around eager launches of 20 - 100 us kernels they would time the launch
+        # gaps: the forward launches of all layers are captured in a graph of their own and its replays are timed
+        fgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(fgraph):
             for L in layers:
-                e = [ev(), ev()]
-                e[0].record(); L.fwd(); e[1].record(); L.bwd_in(); L.bwd_w()
-                marks.append((L, e))
+                L.fwd()
+        fgraph.replay()
         torch.cuda.synchronize()
-    t_f = sum(m[0].elapsed_time(m[1]) for _, m in marks) / args.steps   # ms per step, all layers
+        t_f = time_loop(lambda i: fgraph.replay(), args.steps)
+    else:
+        t_f = sum(m[0].elapsed_time(m[1]) for _, m in marks) / args.steps   # ms per step, all layers
+    # backward calls: on the operand sets of the step (warm: what a training step sees right after its forward
+    # pass) and, for single layers, on rotating sets (cold: every byte from HBM)
     aux_steps = min(args.steps, 10)
     aux = []
     for _ in range(aux_steps):
@@ -257,6 +342,8 @@ def main() -> int:
     bytes_bi = sum(L.bytes_bi for L in layers)
     bytes_bw = sum(L.bytes_bw for L in layers)
     dtypes = {L.cfg.dtype for L in layers}
+    traffic = (MEASURED_FORWARD_TRAFFIC.get((cfgs[0].name, cfgs[0].mode, cfgs[0].dtype, args.op))
+               if len(cfgs) == 1 else None)
 
     out = {
         "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step"
@@ -270,9 +357,12 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if dtypes == {"f32"} else "bf16-storage/f32-arith",
+        "dtype": "f32",   # the arithmetic type: every add and compare is fp32, whatever the storage type
+        "storage": "f32" if dtypes == {"f32"} else "bf16",
         "data": "synthetic",
-        "config": {"workload": wl_name + ", fwd+bwd_input+bwd_weight" + (", one HIP graph per step" if graph else ""),
+        "config": {"workload": wl_name + ", forward + backward (grad_x and grad_w, "
+                               + ("two calls" if args.separate_backward or args.op == "sum" else "one call") + ")"
+                               + (", one HIP graph per step" if graph else ""),
                    "pairs_per_step": pairs,
                    "forward_kernel": (tb.tconv_sum_forward_kernel_name(layers[-1].d) if args.op == "sum"
                                       else tb.tconv_forward_kernel_name(layers[-1].d))},
@@ -288,15 +378,84 @@ def main() -> int:
                      "achieved": round(achieved / 1e12, 3),
                      "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
                      "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
-                     "traffic": (MEASURED_FORWARD_TRAFFIC.get((cfgs[0].name, cfgs[0].mode, args.op))
-                                 if len(cfgs) == 1 and cfgs[0].dtype == "f32" else None)},
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_source": traffic[1] if traffic else None},
     }
+    if len(layers) == 1:
+        cfg0 = layers[0].cfg
+        del layers[0].sets[0]["gx"]
+        c_bi, c_bw, c_b, Lc = cold_backward(cfg0, args.op)
+        out["backward_cold"] = {
+            "note": "backward calls on rotating operand sets (> 600 MB between two uses of a set): nothing served from "
+                    "the last-level cache",
+            "ms_backward_input": round(c_bi, 4), "ms_backward_weight": round(c_bw, 4), "ms_backward_both": round(c_b, 4),
+            "backward_input_gbs": round(Lc.bytes_bi / (c_bi * 1e-3) / 1e9, 1),
+            "backward_weight_gbs": round(Lc.bytes_bw / (c_bw * 1e-3) / 1e9, 1),
+            "backward_both_gbs": round(Lc.bytes_b / (c_b * 1e-3) / 1e9, 1)}
+        del Lc
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline([(L.cfg, L.inp) for L in layers], args.cpu_seconds, args.op,
                                            [(None if L.op != "sum" or L.alpha is None else L.alpha.cpu().numpy(),
                                              None if L.op != "sum" or L.beta is None else L.beta.cpu().numpy())
                                             for L in layers])
+
+    if args.op == "full" and not args.no_layers and len(layers) == 1:
+        # the other layers the bar is stated on, each measured the same way in this run: forward with events over a loop
+        # of launches (milliseconds each), backward on rotating operand sets
+        del layers
+        torch.cuda.empty_cache()
+        table = []
+        for name, dt in BAR_LAYERS:
+            cfg = CONFIGS[name] if dt is None else CONFIGS[name].with_(dtype=dt)
+            c_bi, c_bw, c_b, L = cold_backward(cfg, "full")
+            for _ in range(3):
+                L.fwd()
+            torch.cuda.synchronize()
+            t = time_loop(lambda i: L.fwd(i % len(L.sets)), 10)
+            ops = cfg.pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode))
+            x_bytes = L.x.numel() * L.x.element_size()
+            out_bytes = L.n_out * (L.y.element_size() * (1 + cfg.branches) + 4 * cfg.branches)
+            table.append({
+                "layer": name, "mode": cfg.mode, "storage": cfg.dtype, "pairs": cfg.pairs,
+                "forward_kernel": tb.tconv_forward_kernel_name(L.d),
+                "ms_forward": round(t, 4), "forward_gops": round(cfg.pairs / (t * 1e-3) / 1e9, 1),
+                "frac": round(ops / (t * 1e-3) / LANE_OPS_PER_S, 4),
+                "forward_hbm_gbs": round((x_bytes + out_bytes) / (t * 1e-3) / 1e9, 1),
+                "ms_backward_input": round(c_bi, 4), "backward_input_gbs": round(L.bytes_bi / (c_bi * 1e-3) / 1e9, 1),
+                "ms_backward_weight": round(c_bw, 4), "backward_weight_gbs": round(L.bytes_bw / (c_bw * 1e-3) / 1e9, 1),
+                "ms_backward_both": round(c_b, 4), "backward_both_gbs": round(L.bytes_b / (c_b * 1e-3) / 1e9, 1)})
+            del L
+            torch.cuda.empty_cache()
+        # the 19-layer stack: forward launches replayed from one HIP graph (no launch gaps inside the timed region)
+        stack = [Layer(c, "full") for c in resnet20_layers(256)]
+        for _ in range(2):
+            for L in stack:
+                L.fwd(); L.bwd()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for L in stack:
+                L.fwd(); L.bwd()
+        torch.cuda.current_stream().wait_stream(side)
+        gf, gs = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gf):
+            for L in stack:
+                L.fwd()
+        with torch.cuda.graph(gs):
+            for L in stack:
+                L.fwd(); L.bwd()
+        gf.replay(); gs.replay()
+        torch.cuda.synchronize()
+        t_f5 = time_loop(lambda i: gf.replay(), 10)
+        t_s5 = time_loop(lambda i: gs.replay(), 10)
+        p5 = sum(L.cfg.pairs for L in stack)
+        table.append({"layer": "cfg5 (19 layers, batch 256, HIP graph replays)", "mode": "parallel", "storage": "f32",
+                      "pairs": p5, "ms_forward": round(t_f5, 4), "forward_gops": round(p5 / (t_f5 * 1e-3) / 1e9, 1),
+                      "frac": round(p5 * 2.0 / (t_f5 * 1e-3) / LANE_OPS_PER_S, 4),
+                      "ms_step": round(t_s5, 4), "step_gops": round(p5 / (t_s5 * 1e-3) / 1e9, 1)})
+        out["layers"] = table
     print(json.dumps(out), flush=True)
     return 0
 
@@ -367,7 +526,8 @@ def bench_1d(args, torch, tb) -> int:
         "roofline": {"bound": "alu", "kernel": "forward", "achieved": round(achieved / 1e12, 3),
                      "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
                      "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
-                     "traffic": MEASURED_FORWARD_TRAFFIC.get((cfg.name, cfg.mode, "1d"))},
+                     "traffic": (MEASURED_FORWARD_TRAFFIC.get((cfg.name, cfg.mode, "f32", "1d")) or (None, None))[0],
+                     "traffic_source": (MEASURED_FORWARD_TRAFFIC.get((cfg.name, cfg.mode, "f32", "1d")) or (None, None))[1]},
     }
     if not args.no_cpu_baseline:
         from oracle import tconv1d_oracle as o1

@@ -66,11 +66,19 @@ enum tconv_mode {
                             single branch on the MAX side (w_max, idx_max, y_max, grad_w_max)       */
 };
 enum tconv_dtype { TCONV_F32 = 0, TCONV_BF16 = 1 };
+enum tconv_pad_mode {
+  TCONV_PAD_IDENTITY = 0,  /* padding holds the semiring identity (Sec. 3.1): a padded tap never wins            */
+  TCONV_PAD_ZERO = 1       /* padding holds zeros (App. A.1.1, the unfold formulation pads the input with zeros):
+                              a padded tap is a candidate of value fl(0 + w[k]); it can win, its index is saved
+                              like any other, and in the backward pass its gradient reaches the kernel only     */
+};
 enum tconv_op {
   TCONV_OP_FORWARD = 0,
   TCONV_OP_BACKWARD_INPUT = 1,
   TCONV_OP_BACKWARD_WEIGHT = 2,
-  TCONV_OP_BACKWARD_ALPHA_BETA = 3
+  TCONV_OP_BACKWARD_ALPHA_BETA = 3,
+  TCONV_OP_BACKWARD = 4,  /* tconv_backward: both gradients in one call */
+  TCONV_OP_BACKWARD_BIAS = 5
 };
 
 enum tconv_status {
@@ -88,12 +96,16 @@ typedef struct tconv_desc {
   int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
   int32_t mode;             /* enum tconv_mode                        */
   int32_t dtype;            /* enum tconv_dtype                       */
+  int32_t pad_mode;         /* enum tconv_pad_mode; the full-window layers (modes max .. parallel of tconv_forward*,
+                               tconv_backward*) take both, the mixed modes and every other entry point
+                               TCONV_PAD_IDENTITY only (TCONV_E_UNSUPPORTED)                                    */
 } tconv_desc;
 
 /* H_out = floor((H + 2*pad_h - dil_h*(KH-1) - 1)/stride_h) + 1, W_out likewise.  Host only. */
 int tconv_out_shape(const tconv_desc* desc, int32_t* H_out, int32_t* W_out);
 
-/* Scratch bytes `op` (enum tconv_op) needs for this descriptor (may be 0).  Host only. */
+/* Scratch bytes `op` (enum tconv_op) needs (forward) or can use (the parameter gradients, where a workspace selects
+ * the deterministic summation) for this descriptor; may be 0.  Host only. */
 int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes);
 
 /*
@@ -117,6 +129,44 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
                   void* hip_stream);
 
 /*
+ * Forward with the layer's epilogue fused into the kernel that produces y.  The layers of the paper derive from the
+ * framework's convolution base class (App. A.2), which carries an optional bias, and its residual blocks (Sec. 5,
+ * "TCNN BasicBlock": tropical conv -> batch norm -> tropical conv -> batch norm -> shortcut add, no activation) follow
+ * every tropical layer with a batch norm and, at the end of the block, the shortcut.  With t the combined output of
+ * tconv_forward, the call stores
+ *     t1 = bias  ? fl(t + bias[c_out])                              : t
+ *     t2 = scale ? fl(fl(t1 * scale[c_out]) + shift[c_out])         : t1      (shift NULL = zeros)
+ *     y  = residual ? fl(t2 + residual[n, c_out, oh, ow])           : t2
+ * every operation rounded to fp32 on its own (then to the storage dtype).  scale / shift are a batch norm folded for
+ * inference, scale = gamma / sqrt(var + eps), shift = beta - mean * scale; forming them is the caller's business.
+ * y_min, y_max, idx_min, idx_max are those of the bare layer.  `epilogue` is a HOST pointer to a struct of DEVICE
+ * pointers (bias, scale, shift fp32 [C_out]; residual in the storage dtype, same shape as y; it may alias nothing the
+ * call writes); NULL, or all members NULL, makes the call identical to tconv_forward.  Everything else as there.
+ * Backward: the epilogue is affine, so the caller feeds tconv_backward* with gy scaled per channel (pass
+ * alpha * scale and beta * scale as coefficients in compound / parallel mode), adds gy to the shortcut's gradient,
+ * and gets grad_bias from tconv_backward_bias.
+ */
+typedef struct tconv_epilogue {
+  const float* bias;
+  const float* scale;
+  const float* shift;
+  const void* residual;
+} tconv_epilogue;
+
+int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                        const float* alpha, const float* beta, const tconv_epilogue* epilogue, void* y, void* y_min,
+                        void* y_max, int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+
+/*
+ * Gradient of the epilogue's bias: grad_bias[c_out] = sum over (n, oh, ow) of gy (gy as it arrives at the bias add,
+ * fp32).  fp32 [C_out], overwritten.  workspace optional, tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_BIAS): with
+ * it the batch slices are added in a fixed order in fp64 (deterministic), without it with fp32 atomics.
+ */
+int tconv_backward_bias(const tconv_desc* desc, const float* gy, float* grad_bias, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/*
  * Backward w.r.t. the input: grad_x[n, c*, ih*, iw*] += g_b for every output and
  * live branch b, (c*, i*, j*) = unflatten(idx_b); g_min = alpha*gy, g_max = beta*gy
  * (compound / parallel), g = gy (max / min; minplus_max is treated as min, maxplus_min as
@@ -132,11 +182,27 @@ int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* a
  * Backward w.r.t. the kernel(s): grad_w_b[c_out, k*] += g_b summed over (n, oh, ow).
  * max, maxplus_min: grad_w_max; min, minplus_max: grad_w_min; parallel: both; compound: both branches add
  * into ONE tensor, grad_w_min if non-NULL else grad_w_max.  fp32 OIHW, overwritten.
+ *   workspace  optional.  With a buffer of tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_WEIGHT) bytes (8-byte
+ *            aligned; TCONV_E_WORKSPACE if smaller) the sums are DETERMINISTIC: fp64 partial histograms per batch
+ *            slice, added in a fixed order and rounded to fp32 once.  With NULL (or when that size is 0: a window
+ *            too large for an on-chip histogram) the batch slices are combined with fp32 atomics in an unspecified
+ *            order, so the last bits vary from run to run.
  */
 int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* alpha,
                           const float* beta, const int32_t* idx_min, const int32_t* idx_max,
                           float* grad_w_min, float* grad_w_max, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Both gradients of the layer in one call: grad_x as tconv_backward_input writes it and the kernel gradient(s) as
+ * tconv_backward_weight writes them, from the same gy / idx (every argument as in those two calls; grad_x and the
+ * kernel gradient(s) of the mode are all required).  workspace: as for tconv_backward_weight, sized by
+ * tconv_workspace_bytes(desc, TCONV_OP_BACKWARD).  The two kernels run back to back on the stream, so the second
+ * reads gy / idx while the last-level cache still holds what fits of them.
+ */
+int tconv_backward(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                   const int32_t* idx_min, const int32_t* idx_max, float* grad_x, float* grad_w_min,
+                   float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Backward w.r.t. the combine coefficients (Sec. 3.3: y = alpha*y_min + beta*y_max with learnable
@@ -146,8 +212,9 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
  *   y_min, y_max  the branch outputs of tconv_forward, dtype; y_min is required when grad_alpha is
  *            requested, y_max when grad_beta is.
  *   grad_alpha, grad_beta  fp32 [C_out], overwritten; either may be NULL (not computed), not both.
- * Partial sums are fp64; the per-workgroup partial results are added in fp32 in an unspecified order.
- * No workspace is needed (tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_ALPHA_BETA) is 0).
+ * Partial sums are fp64.  workspace is optional: with a buffer of tconv_workspace_bytes(desc,
+ * TCONV_OP_BACKWARD_ALPHA_BETA) bytes (8-byte aligned) the per-workgroup sums are added in a fixed order in fp64 and
+ * rounded once (deterministic); with NULL they are added with fp32 atomics in an unspecified order.
  */
 int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const void* y_min,
                               const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
@@ -271,7 +338,9 @@ const char* tconv1d_forward_kernel_name(const tconv1d_desc* desc);
  * [C_out, C_in, KD, KH, KW], outputs [N, C_out, D_out, H_out, W_out]; per axis
  * out = floor((in + 2*pad - dil*(k-1) - 1)/stride) + 1.  The saved winner is the flattened tap
  * k = ((c*KD + a)*KH + i)*KW + j.  Arguments, rules and error behaviour as for tconv_out_shape, tconv_forward,
- * tconv_backward_input and tconv_backward_weight; no workspace is needed.
+ * tconv_backward_input and tconv_backward_weight.  Only tconv3d_backward_weight uses a workspace, and optionally:
+ * tconv3d_workspace_bytes(desc, TCONV_OP_BACKWARD_WEIGHT) bytes select the deterministic kernel gradient, as in two
+ * dimensions; every other op reports 0.
  */
 typedef struct tconv3d_desc {
   int32_t N, C_in, D, H, W;      /* input  [N, C_in, D, H, W]            */
@@ -282,6 +351,7 @@ typedef struct tconv3d_desc {
 } tconv3d_desc;
 
 int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, int32_t* W_out);
+int tconv3d_workspace_bytes(const tconv3d_desc* desc, int32_t op, size_t* bytes);
 /* "k3x3x3" (3 x 3 x 3 window, stride 1, dilation 1, horizontal padding <= 1, a full-window mode) or "generic3d". */
 const char* tconv3d_forward_kernel_name(const tconv3d_desc* desc);
 int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, const void* w_max,

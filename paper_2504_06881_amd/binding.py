@@ -16,13 +16,16 @@ LIB_PATH = os.path.join(_PKG, "libtconv.so")
 
 MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3, "minplus_max": 4, "maxplus_min": 5}
 DTYPES = {"f32": 0, "bf16": 1}
-OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2}
-SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_backward_input",
-           "tconv_backward_weight", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
+PAD_MODES = {"identity": 0, "zero": 1}
+OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2, "backward_alpha_beta": 3, "backward": 4,
+       "backward_bias": 5}
+SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_forward_fused", "tconv_backward_bias",
+           "tconv_backward_input",
+           "tconv_backward_weight", "tconv_backward", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
            "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
-           "tconv3d_out_shape", "tconv3d_forward_kernel_name", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
+           "tconv3d_out_shape", "tconv3d_workspace_bytes", "tconv3d_forward_kernel_name", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
            "tconv_status_string", "tconv_forward_kernel_name")
 
 
@@ -35,7 +38,11 @@ class TconvError(RuntimeError):
 class tconv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "N", "C_in", "H", "W", "C_out", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w",
-        "dil_h", "dil_w", "mode", "dtype")]
+        "dil_h", "dil_w", "mode", "dtype", "pad_mode")]
+
+
+class tconv_epilogue(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("bias", "scale", "shift", "residual")]
 
 
 class tconv3d_desc(ctypes.Structure):
@@ -102,18 +109,20 @@ class Desc:
     dil: Tuple[int, int] = (1, 1)
     mode: str = "max"
     dtype: str = "f32"
+    pad_mode: str = "identity"
 
     def c(self) -> tconv_desc:
         return tconv_desc(self.N, self.C_in, self.H, self.W, self.C_out, self.KH, self.KW,
                           self.stride[0], self.stride[1], self.pad[0], self.pad[1],
-                          self.dil[0], self.dil[1], MODES[self.mode], DTYPES[self.dtype])
+                          self.dil[0], self.dil[1], MODES[self.mode], DTYPES[self.dtype], PAD_MODES[self.pad_mode])
 
     @staticmethod
-    def from_cfg(cfg, mode: Optional[str] = None, dtype: Optional[str] = None) -> "Desc":
+    def from_cfg(cfg, mode: Optional[str] = None, dtype: Optional[str] = None,
+                 pad_mode: Optional[str] = None) -> "Desc":
         """From an inputs.LayerCfg (square stride / pad / dilation)."""
         return Desc(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW,
                     (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), (cfg.dil, cfg.dil),
-                    mode or cfg.mode, dtype or cfg.dtype)
+                    mode or cfg.mode, dtype or cfg.dtype, pad_mode or getattr(cfg, "pad_mode", "identity"))
 
 
 _lib = None
@@ -132,8 +141,11 @@ def load() -> ctypes.CDLL:
         lib.tconv_out_shape.argtypes = [D, I32P, I32P]
         lib.tconv_workspace_bytes.argtypes = [D, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
         lib.tconv_forward.argtypes = [D] + [P] * 11 + [ctypes.c_size_t, P]
+        lib.tconv_forward_fused.argtypes = [D] + [P] * 5 + [ctypes.POINTER(tconv_epilogue)] + [P] * 6 + [ctypes.c_size_t, P]
+        lib.tconv_backward_bias.argtypes = [D] + [P] * 3 + [ctypes.c_size_t, P]
         lib.tconv_backward_input.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_backward_weight.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
+        lib.tconv_backward.argtypes = [D] + [P] * 9 + [ctypes.c_size_t, P]
         lib.tconv_backward_alpha_beta.argtypes = [D] + [P] * 6 + [ctypes.c_size_t, P]
         lib.tconv_sum_forward.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_sum_backward.argtypes = [D] + [P] * 12 + [ctypes.c_size_t, P]
@@ -156,19 +168,20 @@ def load() -> ctypes.CDLL:
             getattr(lib, f).restype = ctypes.c_int
         D3 = ctypes.POINTER(tconv3d_desc)
         lib.tconv3d_out_shape.argtypes = [D3, I32P, I32P, I32P]
+        lib.tconv3d_workspace_bytes.argtypes = [D3, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)]
         lib.tconv3d_forward.argtypes = [D3] + [P] * 11 + [ctypes.c_size_t, P]
         lib.tconv3d_backward_input.argtypes = [D3] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv3d_backward_weight.argtypes = [D3] + [P] * 8 + [ctypes.c_size_t, P]
         lib.tconv3d_forward_kernel_name.argtypes = [D3]
         lib.tconv3d_forward_kernel_name.restype = ctypes.c_char_p
-        for f in ("tconv3d_out_shape", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight"):
+        for f in ("tconv3d_out_shape", "tconv3d_workspace_bytes", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight"):
             getattr(lib, f).restype = ctypes.c_int
         lib.tconv_status_string.argtypes = [ctypes.c_int]
         lib.tconv_status_string.restype = ctypes.c_char_p
         lib.tconv_forward_kernel_name.argtypes = [D]
         lib.tconv_forward_kernel_name.restype = ctypes.c_char_p
-        for f in ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward",
-                  "tconv_backward_input", "tconv_backward_weight", "tconv_backward_alpha_beta",
+        for f in ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_forward_fused",
+                  "tconv_backward_bias", "tconv_backward_input", "tconv_backward_weight", "tconv_backward", "tconv_backward_alpha_beta",
                   "tconv_sum_forward", "tconv_sum_backward", "tconv_depthwise_forward",
                   "tconv_depthwise_backward"):
             getattr(lib, f).restype = ctypes.c_int
@@ -225,6 +238,23 @@ def tconv_forward(desc: Desc, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx
                                 _ptr(idx_max), _ptr(workspace), wsz, _stream()), "tconv_forward")
 
 
+def tconv_forward_fused(desc: Desc, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max, bias=None,
+                        scale=None, shift=None, residual=None, workspace=None) -> None:
+    cd = desc.c()
+    ep = tconv_epilogue(_ptr(bias), _ptr(scale), _ptr(shift), _ptr(residual))
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_forward_fused(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(alpha), _ptr(beta),
+                                      ctypes.byref(ep), _ptr(y), _ptr(y_min), _ptr(y_max), _ptr(idx_min),
+                                      _ptr(idx_max), _ptr(workspace), wsz, _stream()), "tconv_forward_fused")
+
+
+def tconv_backward_bias(desc: Desc, gy, grad_bias, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward_bias(ctypes.byref(cd), _ptr(gy), _ptr(grad_bias), _ptr(workspace), wsz, _stream()),
+           "tconv_backward_bias")
+
+
 def tconv_backward_input(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_x, workspace=None) -> None:
     cd = desc.c()
     wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -241,6 +271,15 @@ def tconv_backward_weight(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_w_
                                         _ptr(idx_min), _ptr(idx_max), _ptr(grad_w_min),
                                         _ptr(grad_w_max), _ptr(workspace), wsz, _stream()),
            "tconv_backward_weight")
+
+
+def tconv_backward(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_x, grad_w_min, grad_w_max,
+                   workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min), _ptr(idx_max),
+                                 _ptr(grad_x), _ptr(grad_w_min), _ptr(grad_w_max), _ptr(workspace), wsz, _stream()),
+           "tconv_backward")
 
 
 def tconv_backward_alpha_beta(desc: Desc, gy, y_min, y_max, grad_alpha, grad_beta, workspace=None) -> None:
@@ -331,10 +370,13 @@ def tconv1d_backward_input(desc: Desc1d, gy, alpha, beta, idx_min, idx_max, grad
                                          _ptr(idx_max), _ptr(grad_x), None, 0, _stream()), "tconv1d_backward_input")
 
 
-def tconv1d_backward_weight(desc: Desc1d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max) -> None:
+def tconv1d_backward_weight(desc: Desc1d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max,
+                            workspace=None) -> None:
     cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().tconv1d_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
-                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), None, 0, _stream()),
+                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), _ptr(workspace), wsz,
+                                          _stream()),
            "tconv1d_backward_weight")
 
 
@@ -367,10 +409,20 @@ def tconv3d_backward_input(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, grad
                                          _ptr(idx_max), _ptr(grad_x), None, 0, _stream()), "tconv3d_backward_input")
 
 
-def tconv3d_backward_weight(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max) -> None:
+def tconv3d_workspace_bytes(desc: Desc3d, op: str) -> int:
+    n = ctypes.c_size_t()
     cd = desc.c()
+    _check(load().tconv3d_workspace_bytes(ctypes.byref(cd), OPS[op], ctypes.byref(n)), "tconv3d_workspace_bytes")
+    return int(n.value)
+
+
+def tconv3d_backward_weight(desc: Desc3d, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max,
+                            workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().tconv3d_backward_weight(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
-                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), None, 0, _stream()),
+                                          _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), _ptr(workspace), wsz,
+                                          _stream()),
            "tconv3d_backward_weight")
 
 

@@ -20,8 +20,9 @@ int make_params(const tconv_desc* d, Params* p) {
     return TCONV_E_INVAL;
   if (d->mode < TCONV_MAX || d->mode > TCONV_MAXPLUS_MIN) return TCONV_E_INVAL;
   if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16) return TCONV_E_INVAL;
+  if (d->pad_mode != TCONV_PAD_IDENTITY && d->pad_mode != TCONV_PAD_ZERO) return TCONV_E_INVAL;
   const long long eh = (long long)d->dil_h * (d->KH - 1), ew = (long long)d->dil_w * (d->KW - 1);
-  // a window must never lie wholly in the padding
+  // a window must never lie wholly in the padding (kept for zero padding too: one rule for both modes)
   if (d->pad_h > eh || d->pad_w > ew) return TCONV_E_SHAPE;
   const long long nh = (long long)d->H + 2LL * d->pad_h - eh - 1;
   const long long nw = (long long)d->W + 2LL * d->pad_w - ew - 1;
@@ -37,6 +38,7 @@ int make_params(const tconv_desc* d, Params* p) {
   p->sh = d->stride_h; p->sw = d->stride_w; p->ph = d->pad_h; p->pw = d->pad_w;
   p->dh = d->dil_h; p->dw = d->dil_w;
   p->Ho = (int)Ho; p->Wo = (int)Wo; p->K = (int)K; p->mode = d->mode;
+  p->pad_zero = d->pad_mode == TCONV_PAD_ZERO ? 1 : 0;
   return TCONV_OK;
 }
 
@@ -45,6 +47,20 @@ bool generic_forced() {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
   return e && strcmp(e, "generic") == 0;
 }
+
+// Optional scratch of the parameter gradients: NULL selects the atomic form, a buffer must hold `need` bytes and be
+// 8-byte aligned.  Returns false on a buffer that is too small or misaligned.
+bool take_partial(void* workspace, size_t workspace_bytes, size_t need, double** partial) {
+  *partial = nullptr;
+  if (!workspace || need == 0) return true;
+  if (workspace_bytes < need || ((uintptr_t)workspace & 7u)) return false;
+  *partial = (double*)workspace;
+  return true;
+}
+
+// A launcher reports hipGetLastError() after its launches.  That status is sticky per host thread: drop whatever an
+// earlier, unrelated call of the caller left behind, so that TCONV_E_LAUNCH always speaks of this call's launches.
+void own_status() { (void)hipGetLastError(); }
 
 bool use_tiled(const Params& p, int dtype) { return forward_tiled3x3_supported(p, dtype) && !generic_forced(); }
 
@@ -70,10 +86,18 @@ int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
-  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_ALPHA_BETA) return TCONV_E_INVAL;
+  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_BIAS) return TCONV_E_INVAL;
   *bytes = 0;
-  // only the tiled forward kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
+  if (op == TCONV_OP_BACKWARD_BIAS) *bytes = backward_alpha_beta_workspace(p);  // the same slices, two sums each
+  // forward: only the tiled kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
   if (op == TCONV_OP_FORWARD && use_tiled(p, desc->dtype)) *bytes = forward_tiled3x3_workspace(p, desc->dtype);
+  // the deterministic forms of the parameter gradients: fp64 partial sums per batch slice
+  if (op == TCONV_OP_BACKWARD_WEIGHT || op == TCONV_OP_BACKWARD) {
+    p.mode = backward_mode(p.mode);
+    *bytes = backward_weight_workspace(p);
+  }
+  if (op == TCONV_OP_BACKWARD_ALPHA_BETA && (p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL))
+    *bytes = backward_alpha_beta_workspace(p);
   return TCONV_OK;
 }
 
@@ -81,11 +105,24 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
                   const float* alpha, const float* beta, void* y, void* y_min, void* y_max,
                   int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
                   void* hip_stream) {
+  return tconv_forward_fused(desc, x, w_min, w_max, alpha, beta, nullptr, y, y_min, y_max, idx_min, idx_max, workspace,
+                             workspace_bytes, hip_stream);
+}
+
+int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                        const float* alpha, const float* beta, const tconv_epilogue* epilogue, void* y, void* y_min,
+                        void* y_max, int32_t* idx_min, int32_t* idx_max, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!x || !y) return TCONV_E_INVAL;
   FwdArgs a = {x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max};
+  if (p.pad_zero && p.mode > TCONV_PARALLEL) return TCONV_E_UNSUPPORTED;  // the mixed layers keep identity padding
+  if (epilogue) {
+    if (epilogue->shift && !epilogue->scale) return TCONV_E_INVAL;
+    a.bias = epilogue->bias; a.scale = epilogue->scale; a.shift = epilogue->shift; a.residual = epilogue->residual;
+  }
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (w_min ? w_min : w_max);
   const bool do_min = mode_has_min(p.mode), do_max = mode_has_max(p.mode);
   if (do_min && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
@@ -96,10 +133,13 @@ int tconv_forward(const tconv_desc* desc, const void* x, const void* w_min, cons
     const size_t need = forward_tiled3x3_workspace(p, desc->dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)))
       return TCONV_E_WORKSPACE;
+    own_status();
     e = launch_forward_tiled3x3(p, desc->dtype, a, workspace, s);
   } else if (use_row(p, desc->dtype)) {
+    own_status();
     e = launch_forward_row(p, a, s);
   } else {
+    own_status();
     e = launch_forward_generic(p, desc->dtype, a, s);
   }
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
@@ -117,6 +157,7 @@ int tconv_backward_input(const tconv_desc* desc, const float* gy, const float* a
   if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  own_status();
   const hipError_t e = launch_backward_input(p, a, grad_x, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -125,7 +166,6 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
                           const float* beta, const int32_t* idx_min, const int32_t* idx_max,
                           float* grad_w_min, float* grad_w_max, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
@@ -139,22 +179,67 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
     case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
     default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
   }
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, backward_weight_workspace(p), &partial)) return TCONV_E_WORKSPACE;
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
-  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  own_status();
+  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, partial, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                   const int32_t* idx_min, const int32_t* idx_max, float* grad_x, float* grad_w_min,
+                   float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !grad_x) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  switch (p.mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, backward_weight_workspace(p), &partial)) return TCONV_E_WORKSPACE;
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  own_status();
+  // the kernel gradient first: it reads gy / idx in the order the forward pass wrote them; the input gradient, which
+  // follows on the same stream, finds what the last-level cache still holds of them
+  hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, partial, (hipStream_t)hip_stream);
+  if (e == hipSuccess) e = launch_backward_input(p, a, grad_x, (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_bias(const tconv_desc* desc, const float* gy, float* grad_bias, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !grad_bias) return TCONV_E_INVAL;
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, backward_alpha_beta_workspace(p), &partial)) return TCONV_E_WORKSPACE;
+  own_status();
+  const hipError_t e = launch_backward_bias(p, gy, grad_bias, partial, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 
 int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const void* y_min,
                               const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
                               size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (p.mode != TCONV_COMPOUND && p.mode != TCONV_PARALLEL) return TCONV_E_INVAL;
   if (!gy || (!grad_alpha && !grad_beta)) return TCONV_E_INVAL;
   if ((grad_alpha && !y_min) || (grad_beta && !y_max)) return TCONV_E_INVAL;
-  const hipError_t e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta,
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, backward_alpha_beta_workspace(p), &partial)) return TCONV_E_WORKSPACE;
+  own_status();
+  const hipError_t e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta, partial,
                                                   (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -168,11 +253,12 @@ int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, 
   if (rc != TCONV_OK) return rc;
   if (!x || !y) return TCONV_E_INVAL;
   if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
-  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  if (desc->dtype != TCONV_F32 || p.pad_zero) return TCONV_E_UNSUPPORTED;
   SumArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, (float*)y};
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
   if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
+  own_status();
   const hipError_t e = launch_sum_forward(p, a, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -187,7 +273,7 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
   if (rc != TCONV_OK) return rc;
   if (!x || !gy) return TCONV_E_INVAL;
   if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
-  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  if (desc->dtype != TCONV_F32 || p.pad_zero) return TCONV_E_UNSUPPORTED;
   const bool two = p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL;
   if (!two && (grad_alpha || grad_beta)) return TCONV_E_INVAL;
   if (!grad_x && !grad_w_min && !grad_w_max && !grad_alpha && !grad_beta) return TCONV_E_INVAL;
@@ -196,6 +282,7 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
   if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
   const SumGrads g = {gy, grad_x, grad_w_min, grad_w_max, grad_alpha, grad_beta};
+  own_status();
   const hipError_t e = launch_sum_backward(p, a, g, (hipStream_t)hip_stream);
   if (e == hipErrorInvalidValue) return TCONV_E_UNSUPPORTED;  // rows or kernel window too large for the LDS kernels
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
@@ -213,7 +300,7 @@ static int depthwise_params(const tconv_desc* desc, Params* p) {
   if (rc != TCONV_OK) return rc;
   if (p->mode > TCONV_PARALLEL) return TCONV_E_INVAL;
   if (p->C_out % p->C_in != 0) return TCONV_E_SHAPE;
-  if (desc->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
+  if (desc->dtype != TCONV_F32 || p->pad_zero) return TCONV_E_UNSUPPORTED;
   return TCONV_OK;
 }
 
@@ -230,6 +317,7 @@ int tconv_depthwise_forward(const tconv_desc* desc, const void* x, const void* w
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
   if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
+  own_status();
   const hipError_t e = launch_depthwise_forward(p, a, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -255,6 +343,7 @@ int tconv_depthwise_backward(const tconv_desc* desc, const void* x, const void* 
     if ((p.mode != TCONV_MAX && !a.w_min) || (p.mode != TCONV_MIN && !a.w_max)) return TCONV_E_INVAL;
   }
   const DwGrads g = {gy, grad_x, grad_w_min, grad_w_max, grad_alpha, grad_beta};
+  own_status();
   const hipError_t e = launch_depthwise_backward(p, a, g, (hipStream_t)hip_stream);
   if (e == hipErrorInvalidValue) return TCONV_E_UNSUPPORTED;
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
@@ -373,6 +462,23 @@ static int make_params3(const tconv3d_desc* d, Params3* p) {
   return TCONV_OK;
 }
 
+// What the two-dimensional histogram kernel needs to know of a three-dimensional layer: outputs per (image, channel)
+// and taps per channel, not the geometry.
+static Params histogram_view(const Params3& p3, int mode) {
+  Params p = {};
+  p.N = p3.N; p.C_out = p3.C_out; p.Ho = p3.Do * p3.Ho; p.Wo = p3.Wo; p.K = p3.K; p.mode = mode;
+  return p;
+}
+
+int tconv3d_workspace_bytes(const tconv3d_desc* desc, int32_t op, size_t* bytes) {
+  Params3 p3;
+  const int rc = make_params3(desc, &p3);
+  if (rc != TCONV_OK) return rc;
+  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD) return TCONV_E_INVAL;
+  *bytes = (op == TCONV_OP_BACKWARD_WEIGHT) ? backward_weight_workspace(histogram_view(p3, backward_mode(p3.mode))) : 0;
+  return TCONV_OK;
+}
+
 int tconv3d_out_shape(const tconv3d_desc* desc, int32_t* D_out, int32_t* H_out, int32_t* W_out) {
   Params3 p;
   const int rc = make_params3(desc, &p);
@@ -401,6 +507,7 @@ int tconv3d_forward(const tconv3d_desc* desc, const void* x, const void* w_min, 
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (w_min ? w_min : w_max);
   if (mode_has_min(p.mode) && (!a.w_min || !idx_min)) return TCONV_E_INVAL;
   if (mode_has_max(p.mode) && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
+  own_status();
   const hipError_t e = launch_forward_3d(p, a, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -417,6 +524,7 @@ int tconv3d_backward_input(const tconv3d_desc* desc, const float* gy, const floa
   if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  own_status();
   const hipError_t e = launch_backward_input_3d(p, a, grad_x, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
@@ -424,7 +532,6 @@ int tconv3d_backward_input(const tconv3d_desc* desc, const float* gy, const floa
 int tconv3d_backward_weight(const tconv3d_desc* desc, const float* gy, const float* alpha, const float* beta,
                             const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
                             float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params3 p3;
   const int rc = make_params3(desc, &p3);
   if (rc != TCONV_OK) return rc;
@@ -440,10 +547,12 @@ int tconv3d_backward_weight(const tconv3d_desc* desc, const float* gy, const flo
   }
   // The kernel gradient is a histogram of the winners per output channel: it needs the number of outputs per
   // (image, channel) and the number of taps, not the geometry, so the two-dimensional kernel takes it as is.
-  Params p = {};
-  p.N = p3.N; p.C_out = p3.C_out; p.Ho = p3.Do * p3.Ho; p.Wo = p3.Wo; p.K = p3.K; p.mode = mode;
+  const Params p = histogram_view(p3, mode);
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, backward_weight_workspace(p), &partial)) return TCONV_E_WORKSPACE;
   BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
-  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  own_status();
+  const hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, partial, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 

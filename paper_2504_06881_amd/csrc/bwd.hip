@@ -3,15 +3,16 @@
 // x element and the one kernel element that produced the extremum).  Neither does
 // any arithmetic beyond adds, so both are bound by reading gy and idx from HBM.
 //
-//   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (input tile in LDS, LDS fp32 atomics, plain stores)
+//   backward_input : grad_x[n, c*, ih*, iw*] += g_b   (input tile in LDS as fp64, ds_add_f64, plain stores)
 //   backward_weight: grad_w_b[c_out, k*]    += g_b   (per-c_out LDS histogram, then flush)
 // Both accumulate in fp64 in LDS (see below).
 //
 // g_min = alpha[c_out]*gy and g_max = beta[c_out]*gy in compound / parallel mode
 // (paper Sec. 3.3 definitions), g = gy in max / min mode.
 #include <stdlib.h>
+#include <string.h>
 
-#include "tconv_internal.h"
+#include "tile_common.h"
 
 namespace tconv {
 
@@ -95,17 +96,21 @@ __device__ __forceinline__ int unflatten_div(int u, int d, unsigned inv) {
   return inv ? (int)__umulhi((unsigned)u, inv) : (d == 1 ? u : u / d);
 }
 
+// The kernel is bound by vector-instruction issue, not by LDS or memory (counters: the vector ALUs busy two thirds
+// of the time, LDS a quarter), so its index arithmetic is kept off the slow paths: no division by a run-time value
+// inside a loop (a 3 x 3 winner unflattens with full-rate 24-bit multiplies: k / 9 = (k * 58255) >> 19 while
+// k < 73700, r / 3 = (r * 11) >> 5 for r < 9; the tile is written out with incremental coordinates and one
+// multiply-high), and gy / idx are read through buffer resources of the image with 32-bit offsets.
 template <int MODE, bool K3>
 __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ grad_x, int TH,
                                                               int TW, int CC, int tiles_h,
                                                               int tiles_w, int chunks, unsigned inv_kk,
-                                                              unsigned inv_kw) {
+                                                              unsigned inv_kw, unsigned inv_tw, int k24) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  // [CC][TH][TW] fp64 sums, then one int2 per output pixel of the scanned region
-  HIP_DYNAMIC_SHARED(double, tile)
+  HIP_DYNAMIC_SHARED(double, acc)  // [CC][TH][TW] fp64 sums
   const int bd = blockDim.x;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a contiguous
   // run of tiles, so that the tiles of one image (which share halo rows of gy / idx) meet in one L2.
@@ -119,8 +124,7 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   const int n = b / tiles_h;
   const int h0 = th * TH, w0 = tw * TW, c0 = ch * CC;
   const int tsz = CC * TH * TW;
-  int2* tab = (int2*)(tile + tsz);
-  for (int e = threadIdx.x; e < tsz; e += bd) tile[e] = 0.0;
+  for (int e = threadIdx.x; e < tsz; e += bd) acc[e] = 0.0;
 
   // outputs whose window can reach the tile
   const int KHs = K3 ? 3 : p.KH, KWs = K3 ? 3 : p.KW, KK = KHs * KWs;
@@ -132,84 +136,112 @@ __global__ __launch_bounds__(1024) void bwd_input_tile_kernel(Params p, BwdArgs 
   const int RH = max(oh_hi - oh_lo + 1, 0), RW = max(ow_hi - ow_lo + 1, 0);
   const int P = RH * RW;  // output pixels scanned per output channel
   const int plane = p.Ho * p.Wo;
-  // per scanned pixel: position of its tap (0, 0) relative to the tile, and its offset in a plane
-  for (int px = threadIdx.x; px < P; px += bd) {
-    const int oh = oh_lo + px / RW, ow = ow_lo + px % RW;
-    const int bh = oh * p.sh - p.ph - h0, bw = ow * p.sw - p.pw - w0;
-    tab[px] = make_int2((bh & 0xffff) | (bw << 16), oh * p.Wo + ow);
-  }
-  __syncthreads();
 
   if (P > 0) {
-    const size_t nbase = (size_t)n * p.C_out * plane;
-    const int co_start = threadIdx.x / P, px_start = threadIdx.x - co_start * P;
-    const int dco = bd / P, dpx = bd - dco * P;
-    // items (co, px) in px-major order (consecutive threads read consecutive pixels of a
-    // plane row); four items per thread in flight (12 independent loads)
-    constexpr int UB = 4;
-    int co = co_start, px = px_start;
-    while (co < p.C_out) {
-      int cov[UB], tx[UB];
-      size_t ov[UB];
-      float gv[UB];
-      int kmn[UB], kmx[UB];
+    // the outputs of image n, [C_out][plane]: 32-bit byte offsets (the host checks that they fit)
+    const unsigned img_bytes = (unsigned)((size_t)p.C_out * plane * sizeof(float));
+    const size_t img_off = (size_t)n * p.C_out * plane;
+    const tile::rsrc_t r_gy = tile::make_rsrc(a.gy + img_off, img_bytes);
+    const tile::rsrc_t r_mn = tile::make_rsrc((DO_MIN ? a.idx_min : a.idx_max) + img_off, img_bytes);
+    const tile::rsrc_t r_mx = tile::make_rsrc((DO_MAX ? a.idx_max : a.idx_min) + img_off, img_bytes);
+    const unsigned plane_bytes = (unsigned)plane * 4u;
+    // A thread keeps ONE scanned pixel and walks output channels: with P <= bd pixels the threads form G = bd / P
+    // channel groups (group g takes channels g, g + G, ...; bd - G * P threads idle), otherwise one group whose
+    // threads loop over the pixels.  Consecutive threads read consecutive pixels of a plane row, and everything
+    // that depends on the pixel only (its offset, where its taps fall in the tile) is computed once.
+    const int G = max(bd / P, 1);
+    const int cg = (int)threadIdx.x / P;  // 0 for every thread when P > bd
+    constexpr int UB = 4;                 // items per thread in flight (12 independent loads)
+    float gv[UB];
+    int kmn[UB], kmx[UB];
+    auto issue = [&](unsigned voff, int co0) {
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
-        cov[u] = co;
-        const bool ok = co < p.C_out;
-        const int2 t = tab[px];
-        tx[u] = t.x;
-        ov[u] = nbase + (size_t)(ok ? co : 0) * plane + t.y;
-        px += dpx;
-        co += dco;
-        if (px >= P) { px -= P; ++co; }
+        const unsigned off = voff + __umul24((unsigned)min(co0 + u * G, p.C_out - 1), plane_bytes);
+        gv[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_gy, off, 0, 0));
+        if (DO_MIN) kmn[u] = (int)__builtin_amdgcn_raw_buffer_load_b32(r_mn, off, 0, 0);
+        if (DO_MAX) kmx[u] = (int)__builtin_amdgcn_raw_buffer_load_b32(r_mx, off, 0, 0);
       }
-#pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        gv[u] = a.gy[ov[u]];
-        if (DO_MIN) kmn[u] = a.idx_min[ov[u]];
-        if (DO_MAX) kmx[u] = a.idx_max[ov[u]];
-      }
-#pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        if (cov[u] >= p.C_out) continue;
-        const int bh = (int)(short)(tx[u] & 0xffff), bw = tx[u] >> 16;
-        const float g = gv[u];
-        if (DO_MIN) {
-          const int k = kmn[u];
-          const int c = K3 ? k / KK : unflatten_div(k, KK, inv_kk), r = k - c * KK;
-          const int i = K3 ? r / KWs : unflatten_div(r, KWs, inv_kw), j = r - i * KWs;
-          const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
-          if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd(&tile[(cc * TH + ih) * TW + iw],
-                      (SCALED && a.alpha) ? (double)a.alpha[cov[u]] * (double)g : (double)g);
+    };
+    auto pixel = [&](int px, int& bh, int& bw, unsigned& voff) {
+      const int prow = px / RW;
+      const int oh = oh_lo + prow, ow = ow_lo + (px - prow * RW);
+      bh = oh * p.sh - p.ph - h0; bw = ow * p.sw - p.pw - w0;  // tap (0, 0) relative to the tile
+      voff = (unsigned)(oh * p.Wo + ow) * 4u;
+    };
+    const bool active = cg < G;
+    int px = (int)threadIdx.x - cg * P, bh = 0, bw = 0;
+    unsigned voff = 0;
+    if (active) {  // the first loads go out before the tile is known to be zero: they do not touch LDS
+      pixel(px, bh, bw, voff);
+      issue(voff, cg);
+    }
+    __syncthreads();
+    if (active) {
+      // LDS element a winner lands on, -1: outside this workgroup's tile
+      auto target = [&](int k) -> int {
+        int c, i, j;
+        if (K3 && k24) {
+          c = (int)(__umul24((unsigned)k, 58255u) >> 19);
+          const int r = k - __mul24(c, 9);
+          i = (int)(__umul24((unsigned)r, 11u) >> 5);
+          j = r - __mul24(i, 3);
+        } else {
+          c = K3 ? k / KK : unflatten_div(k, KK, inv_kk);
+          const int r = k - c * KK;
+          i = K3 ? r / KWs : unflatten_div(r, KWs, inv_kw);
+          j = r - i * KWs;
         }
-        if (DO_MAX) {
-          const int k = kmx[u];
-          const int c = K3 ? k / KK : unflatten_div(k, KK, inv_kk), r = k - c * KK;
-          const int i = K3 ? r / KWs : unflatten_div(r, KWs, inv_kw), j = r - i * KWs;
-          const int ih = bh + i * p.dh, iw = bw + j * p.dw, cc = c - c0;
-          if ((unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC)
-            atomicAdd(&tile[(cc * TH + ih) * TW + iw],
-                      (SCALED && a.beta) ? (double)a.beta[cov[u]] * (double)g : (double)g);
+        const int ih = bh + __mul24(i, p.dh), iw = bw + __mul24(j, p.dw), cc = c - c0;
+        const bool in = (unsigned)ih < (unsigned)TH && (unsigned)iw < (unsigned)TW && (unsigned)cc < (unsigned)CC;
+        return in ? __mul24(__mul24(cc, TH) + ih, TW) + iw : -1;
+      };
+      for (;;) {
+        for (int co0 = cg; co0 < p.C_out; co0 += G * UB) {
+          if (co0 != cg) issue(voff, co0);
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int co = co0 + u * G;
+            if (co < p.C_out) {
+              const double g = (double)gv[u];
+              if (DO_MIN) {
+                const int t = target(kmn[u]);
+                if (t >= 0) atomicAdd(&acc[t], (SCALED && a.alpha) ? (double)a.alpha[co] * g : g);
+              }
+              if (DO_MAX) {
+                const int t = target(kmx[u]);
+                if (t >= 0) atomicAdd(&acc[t], (SCALED && a.beta) ? (double)a.beta[co] * g : g);
+              }
+            }
+          }
         }
+        px += bd;
+        if (px >= P) break;
+        pixel(px, bh, bw, voff);
+        issue(voff, cg);
       }
     }
     __syncthreads();
-    const size_t HW = (size_t)p.H * p.W;
-    float* gxn = grad_x + (size_t)n * p.C_in * HW;
+  } else {
+    __syncthreads();
+  }
+  // Write the tile (all zeros when no output reaches it).  Element e = (cc * TH + ih) * TW + iw; a thread's
+  // elements are bd apart, so (cc * TH + ih, iw) advance by a fixed step with one carry.
+  const size_t HW = (size_t)p.H * p.W;
+  float* gxn = grad_x + (size_t)n * p.C_in * HW;
+  const int d_row = bd / TW, d_col = bd - d_row * TW;  // uniform
+  int row = TW == 1 ? (int)threadIdx.x : (int)__umulhi(threadIdx.x, inv_tw);  // cc * TH + ih; exact: threadIdx.x * TW < 2^32
+  int iw = (int)threadIdx.x - row * TW;
+  {
+    // rows of the tile are numbered cc * TH + ih; split once per thread and carry from there on
+    int cc = row / TH, ih = row - cc * TH;
+    const int d_cc = d_row / TH, d_ih = d_row - d_cc * TH;
     for (int e = threadIdx.x; e < tsz; e += bd) {
-      const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
       if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
-        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = (float)tile[e];
-    }
-  } else {  // no output reaches this tile: its gradient is zero
-    const size_t HW = (size_t)p.H * p.W;
-    float* gxn = grad_x + (size_t)n * p.C_in * HW;
-    for (int e = threadIdx.x; e < tsz; e += bd) {
-      const int iw = e % TW, ih = (e / TW) % TH, cc = e / (TW * TH);
-      if (h0 + ih < p.H && w0 + iw < p.W && c0 + cc < p.C_in)
-        gxn[(size_t)(c0 + cc) * HW + (size_t)(h0 + ih) * p.W + (w0 + iw)] = 0.f;
+        gxn[(unsigned)((c0 + cc) * (int)HW + (h0 + ih) * p.W + (w0 + iw))] = (float)acc[e];
+      iw += d_col; ih += d_ih; cc += d_cc;
+      if (iw >= TW) { iw -= TW; ++ih; }
+      if (ih >= TH) { ih -= TH; ++cc; }
     }
   }
 }
@@ -226,14 +258,14 @@ __global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  HIP_DYNAMIC_SHARED(double, tile)  // [CC][TW]
+  HIP_DYNAMIC_SHARED(double, acc)  // [CC][TW]
   const int bd = blockDim.x, tid = threadIdx.x;
   int b = blockIdx.x;
   const int ch = b % chunks; b /= chunks;
   const int tw = b % tiles_w;
   const int n = b / tiles_w;
   const int w0 = tw * TW, c0 = ch * CC, tsz = CC * TW;
-  for (int e = tid; e < tsz; e += bd) tile[e] = 0.0;
+  for (int e = tid; e < tsz; e += bd) acc[e] = 0.0;
   __syncthreads();
 
   // output positions whose window can reach the tile
@@ -278,7 +310,7 @@ __global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a
             if (DO_MIN) {
               const int t = target(kmn[u]);
               if (t != am) {
-                if (am >= 0) atomicAdd(&tile[am], sm);
+                if (am >= 0) atomicAdd(&acc[am], sm);
                 am = t; sm = 0.0;
               }
               sm += (SCALED && a.alpha) ? (double)a.alpha[co] * g : g;
@@ -286,15 +318,15 @@ __global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a
             if (DO_MAX) {
               const int t = target(kmx[u]);
               if (t != aM) {
-                if (aM >= 0) atomicAdd(&tile[aM], sM);
+                if (aM >= 0) atomicAdd(&acc[aM], sM);
                 aM = t; sM = 0.0;
               }
               sM += (SCALED && a.beta) ? (double)a.beta[co] * g : g;
             }
           }
         }
-        if (DO_MIN && am >= 0) atomicAdd(&tile[am], sm);
-        if (DO_MAX && aM >= 0) atomicAdd(&tile[aM], sM);
+        if (DO_MIN && am >= 0) atomicAdd(&acc[am], sm);
+        if (DO_MAX && aM >= 0) atomicAdd(&acc[aM], sM);
       }
     }
   }
@@ -302,7 +334,7 @@ __global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a
   float* gxn = grad_x + (size_t)n * p.C_in * p.W;
   for (int e = tid; e < tsz; e += bd) {
     const int iw = e % TW, cc = e / TW;
-    if (w0 + iw < p.W && c0 + cc < p.C_in) gxn[(size_t)(c0 + cc) * p.W + (w0 + iw)] = (float)tile[e];
+    if (w0 + iw < p.W && c0 + cc < p.C_in) gxn[(size_t)(c0 + cc) * p.W + (w0 + iw)] = (float)acc[e];
   }
 }
 
@@ -310,11 +342,10 @@ __global__ __launch_bounds__(1024) void bwd_input_row_kernel(Params p, BwdArgs a
 // LDS budget, with a penalty for rows too short to coalesce.
 struct BwdInTile { int TH, TW, CC, tiles_h, tiles_w, chunks; };
 
-// LDS bytes of a candidate: the tile plus one int2 per scanned output pixel (bounded by the tile grown
-// by the kernel extent).
+// LDS bytes of a candidate: the tile.
 static size_t bwd_input_lds_bytes(const Params& p, int CC, int TH, int TW) {
-  const size_t region = (size_t)(TH + (p.KH - 1) * p.dh + p.sh) * (TW + (p.KW - 1) * p.dw + p.sw);
-  return (size_t)CC * TH * TW * sizeof(double) + region * sizeof(int2);
+  (void)p;
+  return (size_t)CC * TH * TW * sizeof(double);
 }
 
 static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
@@ -336,6 +367,12 @@ static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
         const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
         const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
         if (wgs < 512) cost *= 1.0 + (512 - wgs) / 512;  // too few workgroups to fill 256 CUs
+        {  // threads that own a scanned pixel: whole channel groups of P threads (see the kernel)
+          const long long RH = min((long long)p.Ho, (long long)(TH + eh) / p.sh + 1);
+          const long long RW = min((long long)p.Wo, (long long)(TW + ew) / p.sw + 1);
+          const long long P = RH * RW;
+          cost /= P <= 1024 ? (double)(P * (1024 / P)) / 1024.0 : (double)P / (double)(((P + 1023) / 1024) * 1024);
+        }
         if (cost < best_cost) {
           best_cost = cost;
           best = {TH, TW, CC, tiles_h, tiles_w, real_chunks};
@@ -383,7 +420,11 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
   if (const char* e = getenv("TCONV_BWD_LDS_KB")) LDS_BUDGET = (size_t)atoi(e) * 1024;
   const BwdInTile t = choose_bwd_input_tile(p, LDS_BUDGET);
   const long long blocks = (long long)p.N * t.tiles_h * t.tiles_w * t.chunks;
-  if (t.TH >= 1 && blocks <= 0x7fffffffLL) {
+  // the tile kernel addresses the outputs of one image and the elements of one input image with 32 bits
+  const bool fits32 = (size_t)p.C_out * p.Ho * p.Wo * sizeof(float) < 0xfffff000ull &&
+                      (size_t)p.C_in * p.H * p.W < 0x7fffffffull && (size_t)p.Ho * p.Wo * 4 < (1u << 24) &&
+                      p.C_out < (1 << 24);
+  if (t.TH >= 1 && blocks <= 0x7fffffffLL && fits32) {
     const size_t lds = bwd_input_lds_bytes(p, t.CC, t.TH, t.TW);
     const long long grid_blocks = ((blocks + 7) / 8) * 8;  // the kernel remaps blockIdx per XCD
     const bool k3 = (p.KH == 3 && p.KW == 3);
@@ -392,9 +433,11 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
       return (d > 1 && umax * d < 0x100000000LL) ? (unsigned)(0x100000000ULL / (unsigned long long)d) + 1u : 0u;
     };
     const unsigned inv_kk = inv_of(kk, p.K), inv_kw = inv_of(p.KW, kk);
+    const unsigned inv_tw = (unsigned)(0x100000000ULL / (unsigned long long)t.TW) + 1u;  // exact for thread numbers
+    const int k24 = p.K < 73700 ? 1 : 0;  // the 24-bit unflattening of a 3 x 3 winner is exact below that
 #define TCONV_LAUNCH_BWD_IN(M, K3)                                                              \
   hipLaunchKernelGGL((bwd_input_tile_kernel<M, K3>), dim3((unsigned)grid_blocks), dim3(1024), lds, s, p, a, \
-                     grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks, inv_kk, inv_kw)
+                     grad_x, t.TH, t.TW, t.CC, t.tiles_h, t.tiles_w, t.chunks, inv_kk, inv_kw, inv_tw, k24)
     switch (p.mode) {
       case TCONV_MAX: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MAX, true); else TCONV_LAUNCH_BWD_IN(TCONV_MAX, false); break;
       case TCONV_MIN: if (k3) TCONV_LAUNCH_BWD_IN(TCONV_MIN, true); else TCONV_LAUNCH_BWD_IN(TCONV_MIN, false); break;
@@ -432,7 +475,7 @@ template <int MODE>
 __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ gw_min,
                                                               float* __restrict__ gw_max,
-                                                              int n_per_block) {
+                                                              int n_per_block, double* __restrict__ partial) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
@@ -486,6 +529,11 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
     }
   }
   __syncthreads();
+  if (partial) {  // two-stage form: the fp64 histogram of this (batch slice, channel) as it is; a second kernel adds the slices
+    double* dst = partial + ((size_t)blockIdx.y * p.C_out + co) * (size_t)(NHIST * K);
+    for (int k = threadIdx.x; k < NHIST * K; k += bd) dst[k] = hist[k];
+    return;
+  }
   float* dmin = (MODE == TCONV_MAX) ? gw_max : gw_min;  // NHIST == 1: the single destination
   for (int k = threadIdx.x; k < K; k += bd) {
     const double v = hist[k];
@@ -493,6 +541,23 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
     if (NHIST == 2) {
       const double v2 = hmax[k];
       if (v2 != 0.0) atomicAdd(gw_max + (size_t)co * K + k, (float)v2);
+    }
+  }
+}
+
+// Second stage of the deterministic kernel gradient: grad_w[co, k] = the partial histograms of the batch slices
+// added in ascending slice order in fp64, rounded to fp32 once.  Writes every element: no zero fill, no atomics.
+__global__ __launch_bounds__(256) void bwd_weight_reduce_kernel(const double* __restrict__ partial,
+                                                                float* __restrict__ dst0, float* __restrict__ dst1,
+                                                                int nhist, int K, int C_out, int slices) {
+  const size_t total = (size_t)C_out * K, per_slice = total * nhist;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const size_t co = e / (size_t)K, k = e - co * K;
+    for (int h = 0; h < nhist; ++h) {
+      const double* src = partial + (co * nhist + h) * (size_t)K + k;
+      double v = 0.0;
+      for (int sl = 0; sl < slices; ++sl) v += src[(size_t)sl * per_slice];
+      (h == 0 ? dst0 : dst1)[e] = (float)v;
     }
   }
 }
@@ -522,38 +587,70 @@ __global__ __launch_bounds__(256) void bwd_weight_scatter_kernel(Params p, BwdAr
   }
 }
 
+// Batch slices of the histogram kernel: about two 1024-thread workgroups per compute unit in all.
+static int weight_slices(const Params& p, int* n_per_block) {
+  int slices = (512 + p.C_out - 1) / p.C_out;
+  if (slices > p.N) slices = p.N;
+  if (slices < 1) slices = 1;
+  *n_per_block = (p.N + slices - 1) / slices;
+  return (p.N + *n_per_block - 1) / *n_per_block;
+}
+
+static bool weight_hist_fits(const Params& p) {
+  const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
+  return (size_t)nhist * p.K * sizeof(double) <= 64 * 1024;
+}
+
+// Scratch of the deterministic (two-stage) kernel gradient: one fp64 histogram per (batch slice, output channel,
+// destination tensor).  0: the layer's histogram does not fit LDS and the scatter kernel (global atomics) runs.
+size_t backward_weight_workspace(const Params& p) {
+  if (!weight_hist_fits(p)) return 0;
+  int npb = 0;
+  const int slices = weight_slices(p, &npb);
+  const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
+  return (size_t)slices * p.C_out * nhist * p.K * sizeof(double);
+}
+
 hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad_w_min,
-                                  float* grad_w_max, hipStream_t s) {
+                                  float* grad_w_max, double* partial, hipStream_t s) {
   const size_t wn = (size_t)p.C_out * p.K;
   float* gmin = grad_w_min;
   float* gmax = grad_w_max;
   if (p.mode == TCONV_COMPOUND) gmin = gmax = (grad_w_min ? grad_w_min : grad_w_max);
-  if (p.mode != TCONV_MAX) fill_zero(gmin, wn, s);
-  if (p.mode == TCONV_MAX || p.mode == TCONV_PARALLEL) fill_zero(gmax, wn, s);
+  const bool hist = weight_hist_fits(p);
+  if (!hist) partial = nullptr;
+  if (!partial) {  // the atomic forms add into zero-filled tensors
+    if (p.mode != TCONV_MAX) fill_zero(gmin, wn, s);
+    if (p.mode == TCONV_MAX || p.mode == TCONV_PARALLEL) fill_zero(gmax, wn, s);
+  }
 
   const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
   const size_t lds = (size_t)nhist * p.K * sizeof(double);
-  if (lds <= 64 * 1024) {
-    // two 1024-thread workgroups per CU; few slices keep the number of flush atomics small
-    int slices = (512 + p.C_out - 1) / p.C_out;
-    if (slices > p.N) slices = p.N;
-    if (slices < 1) slices = 1;
-    const int n_per_block = (p.N + slices - 1) / slices;
-    slices = (p.N + n_per_block - 1) / n_per_block;
+  if (hist) {
+    // two 1024-thread workgroups per CU; few slices keep the second stage (or the flush atomics) small
+    int n_per_block = 0;
+    const int slices = weight_slices(p, &n_per_block);
     dim3 grid(p.C_out, slices);
     switch (p.mode) {
       case TCONV_MAX:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MAX>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MAX>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
         break;
       case TCONV_MIN:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MIN>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MIN>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
         break;
       case TCONV_COMPOUND:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_COMPOUND>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_COMPOUND>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
         break;
       default:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_PARALLEL>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block);
+        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_PARALLEL>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
         break;
+    }
+    if (partial) {
+      size_t blocks = (wn + 255) / 256;
+      if (blocks > 2048) blocks = 2048;
+      float* d0 = (p.mode == TCONV_MAX) ? gmax : gmin;
+      hipLaunchKernelGGL(bwd_weight_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, partial, d0, gmax, nhist, p.K,
+                         p.C_out, slices);
     }
   } else {
     const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
@@ -583,7 +680,8 @@ __global__ __launch_bounds__(256) void bwd_alpha_beta_kernel(Params p, const flo
                                                              const TY* __restrict__ y_min,
                                                              const TY* __restrict__ y_max,
                                                              float* __restrict__ grad_alpha,
-                                                             float* __restrict__ grad_beta, int n_per_block) {
+                                                             float* __restrict__ grad_beta, int n_per_block,
+                                                             double* __restrict__ partial) {
   const int co = blockIdx.x;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
@@ -609,28 +707,107 @@ __global__ __launch_bounds__(256) void bwd_alpha_beta_kernel(Params p, const flo
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    if (grad_alpha) atomicAdd(grad_alpha + co, (float)red[0][0]);
-    if (grad_beta) atomicAdd(grad_beta + co, (float)red[1][0]);
+    if (partial) {  // two-stage form: this slice's fp64 sums; ab_reduce_kernel adds the slices
+      partial[((size_t)blockIdx.y * p.C_out + co) * 2] = red[0][0];
+      partial[((size_t)blockIdx.y * p.C_out + co) * 2 + 1] = red[1][0];
+    } else {
+      if (grad_alpha) atomicAdd(grad_alpha + co, (float)red[0][0]);
+      if (grad_beta) atomicAdd(grad_beta + co, (float)red[1][0]);
+    }
   }
 }
 
-hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
-                                      const void* y_max, float* grad_alpha, float* grad_beta,
-                                      hipStream_t s) {
-  if (grad_alpha) fill_zero(grad_alpha, (size_t)p.C_out, s);
-  if (grad_beta) fill_zero(grad_beta, (size_t)p.C_out, s);
+// Second stage: the slices' sums in ascending slice order, in fp64, rounded to fp32 once.
+__global__ __launch_bounds__(256) void ab_reduce_kernel(const double* __restrict__ partial, float* __restrict__ grad_alpha,
+                                                        float* __restrict__ grad_beta, int C_out, int slices) {
+  const int co = blockIdx.x * blockDim.x + threadIdx.x;
+  if (co >= C_out) return;
+  double sa = 0.0, sb = 0.0;
+  for (int sl = 0; sl < slices; ++sl) {
+    sa += partial[((size_t)sl * C_out + co) * 2];
+    sb += partial[((size_t)sl * C_out + co) * 2 + 1];
+  }
+  if (grad_alpha) grad_alpha[co] = (float)sa;
+  if (grad_beta) grad_beta[co] = (float)sb;
+}
+
+static int ab_slices(const Params& p, int* n_per_block) {
   // about two workgroups per compute unit, each with at least one image
   int slices = (512 + p.C_out - 1) / p.C_out;
   if (slices > p.N) slices = p.N;
   if (slices > 65535) slices = 65535;
-  const int n_per_block = (p.N + slices - 1) / slices;
-  const dim3 grid((unsigned)p.C_out, (unsigned)((p.N + n_per_block - 1) / n_per_block));
+  *n_per_block = (p.N + slices - 1) / slices;
+  return (p.N + *n_per_block - 1) / *n_per_block;
+}
+
+// Scratch of the deterministic form: two fp64 sums per (batch slice, output channel).
+size_t backward_alpha_beta_workspace(const Params& p) {
+  int npb = 0;
+  return (size_t)ab_slices(p, &npb) * p.C_out * 2 * sizeof(double);
+}
+
+hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
+                                      const void* y_max, float* grad_alpha, float* grad_beta, double* partial,
+                                      hipStream_t s) {
+  if (!partial) {
+    if (grad_alpha) fill_zero(grad_alpha, (size_t)p.C_out, s);
+    if (grad_beta) fill_zero(grad_beta, (size_t)p.C_out, s);
+  }
+  int n_per_block = 0;
+  const int slices = ab_slices(p, &n_per_block);
+  const dim3 grid((unsigned)p.C_out, (unsigned)slices);
   if (dtype == TCONV_BF16)
     hipLaunchKernelGGL(bwd_alpha_beta_kernel<bf16_t>, grid, dim3(256), 0, s, p, gy, (const bf16_t*)y_min,
-                       (const bf16_t*)y_max, grad_alpha, grad_beta, n_per_block);
+                       (const bf16_t*)y_max, grad_alpha, grad_beta, n_per_block, partial);
   else
     hipLaunchKernelGGL(bwd_alpha_beta_kernel<float>, grid, dim3(256), 0, s, p, gy, (const float*)y_min,
-                       (const float*)y_max, grad_alpha, grad_beta, n_per_block);
+                       (const float*)y_max, grad_alpha, grad_beta, n_per_block, partial);
+  if (partial)
+    hipLaunchKernelGGL(ab_reduce_kernel, dim3((unsigned)((p.C_out + 255) / 256)), dim3(256), 0, s, partial, grad_alpha,
+                       grad_beta, p.C_out, slices);
+  return hipGetLastError();
+}
+
+// ---- gradient of the epilogue's bias: grad_bias[c] = sum over (n, oh, ow) of gy.  Same layout of workgroups and the
+// same two forms (fp32 atomic per workgroup, or fp64 partial sums added by ab_reduce_kernel) as the kernel above.
+__global__ __launch_bounds__(256) void bwd_bias_kernel(Params p, const float* __restrict__ gy,
+                                                       float* __restrict__ grad_bias, int n_per_block,
+                                                       double* __restrict__ partial) {
+  const int co = blockIdx.x;
+  const int n0 = blockIdx.y * n_per_block;
+  const int n1 = min(n0 + n_per_block, p.N);
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  double sa = 0.0;
+  for (int n = n0; n < n1; ++n) {
+    const size_t base = ((size_t)n * p.C_out + co) * plane;
+    for (size_t i = threadIdx.x; i < plane; i += blockDim.x) sa += (double)gy[base + i];
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = sa;
+  __syncthreads();
+  for (int h = 128; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (partial) {
+      partial[((size_t)blockIdx.y * p.C_out + co) * 2] = red[0];
+      partial[((size_t)blockIdx.y * p.C_out + co) * 2 + 1] = 0.0;
+    } else {
+      atomicAdd(grad_bias + co, (float)red[0]);
+    }
+  }
+}
+
+hipError_t launch_backward_bias(const Params& p, const float* gy, float* grad_bias, double* partial, hipStream_t s) {
+  if (!partial) fill_zero(grad_bias, (size_t)p.C_out, s);
+  int n_per_block = 0;
+  const int slices = ab_slices(p, &n_per_block);
+  hipLaunchKernelGGL(bwd_bias_kernel, dim3((unsigned)p.C_out, (unsigned)slices), dim3(256), 0, s, p, gy, grad_bias,
+                     n_per_block, partial);
+  if (partial)
+    hipLaunchKernelGGL(ab_reduce_kernel, dim3((unsigned)((p.C_out + 255) / 256)), dim3(256), 0, s, partial, grad_bias,
+                       (float*)nullptr, p.C_out, slices);
   return hipGetLastError();
 }
 

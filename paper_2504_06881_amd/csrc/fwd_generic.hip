@@ -6,21 +6,25 @@
 // Operator: paper Sec. 3.1 layers (iv) MinPlus-Min-Conv2d / (v) MaxPlus-Max-Conv2d
 // (one extremum over all C_in*KH*KW taps) and the Sec. 3.3 compound / parallel
 // combinations.  Padded taps are skipped (they hold the semiring identity and can
-// never win); strict compares while k ascends keep the lowest winning tap.
+// never win) or, with zero padding (App. A.1.1: the unfold formulation pads with zeros), enter with input value +0;
+// strict compares while k ascends keep the lowest winning tap.  The epilogue (bias, folded batch norm, residual;
+// App. A.2, Sec. 5 TCNN BasicBlock) is applied to the combined output only.
 #include "tconv_internal.h"
 
 namespace tconv {
 
 template <int MODE, typename T>
-__global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, const T* __restrict__ x,
-                                                          const T* __restrict__ w_min,
-                                                          const T* __restrict__ w_max,
-                                                          const float* __restrict__ alpha,
-                                                          const float* __restrict__ beta,
-                                                          T* __restrict__ y, T* __restrict__ y_min,
-                                                          T* __restrict__ y_max,
-                                                          int32_t* __restrict__ idx_min,
-                                                          int32_t* __restrict__ idx_max) {
+__global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, FwdArgs a) {
+  const T* __restrict__ x = (const T*)a.x;
+  const T* __restrict__ w_min = (const T*)a.w_min;
+  const T* __restrict__ w_max = (const T*)a.w_max;
+  const float* __restrict__ alpha = a.alpha;
+  const float* __restrict__ beta = a.beta;
+  T* __restrict__ y = (T*)a.y;
+  T* __restrict__ y_min = (T*)a.y_min;
+  T* __restrict__ y_max = (T*)a.y_max;
+  int32_t* __restrict__ idx_min = a.idx_min;
+  int32_t* __restrict__ idx_max = a.idx_max;
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
@@ -46,8 +50,9 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, const T* __r
       const bool rv = (ih >= 0 && ih < p.H);
       for (int j = 0; j < p.KW; ++j, ++k) {
         const int iw = iw0 + j * p.dw;
-        if (!rv || iw < 0 || iw >= p.W) continue;
-        const float xv = ld_f32(xc, (size_t)ih * p.W + iw);
+        const bool inside = rv && iw >= 0 && iw < p.W;
+        if (!inside && !p.pad_zero) continue;
+        const float xv = inside ? ld_f32(xc, (size_t)ih * p.W + iw) : 0.0f;
         if (MODE == TCONV_PARALLEL) {
           const float s1 = __fadd_rn(xv, ld_f32(wmn, k));
           const float s2 = __fadd_rn(xv, ld_f32(wmx, k));
@@ -65,7 +70,7 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, const T* __r
   if (MODE == TCONV_MAX) out = bmax;
   else if (MODE == TCONV_MIN) out = bmin;
   else out = combine(alpha ? alpha[co] : 1.0f, bmin, beta ? beta[co] : 1.0f, bmax);
-  st_f32(y, o, out);
+  st_f32(y, o, apply_epilogue<T>(out, a, co, o));
   if (DO_MIN) {
     if (y_min) st_f32(y_min, o, bmin);
     idx_min[o] = imin;
@@ -80,10 +85,12 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, const T* __r
 // input channel is reduced on its own (strict compares, ascending taps: lowest tap), then the channel
 // results with the opposite operator (strict compares, ascending channels: lowest channel).
 template <bool OUTER_MAX, typename T>
-__global__ __launch_bounds__(256) void fwd_mixed_generic_kernel(Params p, const T* __restrict__ x,
-                                                                const T* __restrict__ w, T* __restrict__ y,
-                                                                T* __restrict__ y_branch,
-                                                                int32_t* __restrict__ idx) {
+__global__ __launch_bounds__(256) void fwd_mixed_generic_kernel(Params p, FwdArgs a) {
+  const T* __restrict__ x = (const T*)a.x;
+  const T* __restrict__ w = (const T*)(OUTER_MAX ? a.w_min : a.w_max);
+  T* __restrict__ y = (T*)a.y;
+  T* __restrict__ y_branch = (T*)(OUTER_MAX ? a.y_min : a.y_max);
+  int32_t* __restrict__ idx = OUTER_MAX ? a.idx_min : a.idx_max;
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
   const size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= total) return;
@@ -105,14 +112,15 @@ __global__ __launch_bounds__(256) void fwd_mixed_generic_kernel(Params p, const 
       const bool rv = (ih >= 0 && ih < p.H);
       for (int j = 0; j < p.KW; ++j, ++k) {
         const int iw = iw0 + j * p.dw;
-        if (!rv || iw < 0 || iw >= p.W) continue;
-        const float s = __fadd_rn(ld_f32(xc, (size_t)ih * p.W + iw), ld_f32(wr, k));
+        const bool inside = rv && iw >= 0 && iw < p.W;
+        if (!inside && !p.pad_zero) continue;
+        const float s = __fadd_rn(inside ? ld_f32(xc, (size_t)ih * p.W + iw) : 0.0f, ld_f32(wr, k));
         if (OUTER_MAX ? (s < v) : (s > v)) { v = s; kv = k; }
       }
     }
     if (OUTER_MAX ? (v > best) : (v < best)) { best = v; ibest = kv; }
   }
-  st_f32(y, o, best);
+  st_f32(y, o, apply_epilogue<T>(best, a, co, o));
   if (y_branch) st_f32(y_branch, o, best);
   idx[o] = ibest;
 }
@@ -121,9 +129,7 @@ template <bool OUTER_MAX, typename T>
 static hipError_t launch_mixed(const Params& p, const FwdArgs& a, hipStream_t s) {
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL((fwd_mixed_generic_kernel<OUTER_MAX, T>), dim3(blocks), dim3(256), 0, s, p, (const T*)a.x,
-                     (const T*)(OUTER_MAX ? a.w_min : a.w_max), (T*)a.y, (T*)(OUTER_MAX ? a.y_min : a.y_max),
-                     OUTER_MAX ? a.idx_min : a.idx_max);
+  hipLaunchKernelGGL((fwd_mixed_generic_kernel<OUTER_MAX, T>), dim3(blocks), dim3(256), 0, s, p, a);
   return hipGetLastError();
 }
 
@@ -131,9 +137,7 @@ template <int MODE, typename T>
 static hipError_t launch_t(const Params& p, const FwdArgs& a, hipStream_t s) {
   const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  hipLaunchKernelGGL((fwd_generic_kernel<MODE, T>), dim3(blocks), dim3(256), 0, s, p,
-                     (const T*)a.x, (const T*)a.w_min, (const T*)a.w_max, a.alpha, a.beta,
-                     (T*)a.y, (T*)a.y_min, (T*)a.y_max, a.idx_min, a.idx_max);
+  hipLaunchKernelGGL((fwd_generic_kernel<MODE, T>), dim3(blocks), dim3(256), 0, s, p, a);
   return hipGetLastError();
 }
 

@@ -38,6 +38,16 @@ namespace {
 
 using namespace tile;
 
+// the epilogue's operands as a kernel argument (device pointers, NULL = step left out)
+struct Epilogue {
+  const float* bias;
+  const float* scale;
+  const float* shift;
+  const void* residual;
+};
+
+// kernel flag: keep the hardware's round-robin workgroup order instead of contiguous runs per XCD
+constexpr int FLAG_ROUND_ROBIN = 32;
 
 // 9 x values of pixel q for the 3x3 taps of one channel: rows[3*ch + i][q*S + j*D]
 template <int S, int D, int XR>
@@ -49,13 +59,15 @@ __device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][
 }
 
 // TN: output channels per lane (4; 2 for layers too small to fill the chip with 4)
-template <int MODE, int S, int D, int TN, typename TO>
+// PZ: zero padding (App. A.1.1: the unfold formulation pads with zeros): an out-of-image value is +0 instead of NaN,
+//     so its tap competes like any other; one AND per loaded value where the identity padding has one OR
+template <int MODE, int S, int D, int TN, bool PZ, typename TO>
 __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
-    TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, int segs,
-    int n_units, int n_groups, int wrps, int dbg, int n_blocks) {
+    TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, Epilogue ep, int segs,
+    int n_units, int n_groups, int wrps, int flags, int n_blocks) {
   // the mixed layers run as one branch: (iii) through the min-side kernel, accumulators and outputs
   // (its operator is min-plus), (vi) through the max side; only the start value and the block differ
   constexpr bool DO_MIN = mode_has_min(MODE), DO_MAX = mode_has_max(MODE);
@@ -68,7 +80,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   // block (same input lines, different output-channel groups) are numbered consecutively; give every XCD a
   // contiguous run of numbers, so that they meet in one L2 instead of fetching the lines once per XCD.
   const int per_xcd = (n_blocks + 7) >> 3;
-  const int bid = (dbg & 32) ? (int)blockIdx.x : (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
+  const int bid = (flags & FLAG_ROUND_ROBIN) ? (int)blockIdx.x : (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
   if (bid >= n_blocks) return;  // padding of the grid to a multiple of 8; the kernel has no barrier
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
   const int ublock = bid / gblocks;
@@ -94,22 +106,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   const size_t HW = (size_t)p.H * p.W;
   const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
   unsigned roff[3];  // byte offset of the first core column (iw0 + D >= 0) of each (clamped) row
-  unsigned mrow[3];  // all-ones where the row is padding
+  unsigned mrow[3];  // identity padding: all-ones where the row is padding; zero padding: all-ones where it is NOT
   int ihc[3];        // clamped input rows of the three kernel rows
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
     const int ih = oh * S - p.ph + i * D;
-    mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
+    mrow[i] = ((ih >= 0 && ih < p.H) != PZ) ? 0u : 0xffffffffu;
     ihc[i] = min(max(ih, 0), p.H - 1);
     roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc[i] * p.W + (size_t)(iw0 + D)) * sizeof(float));
   }
   int hoff[2 * D];         // clamped byte offsets of the halo columns relative to roff
-  unsigned mhalo[2 * D];   // all-ones where the halo column is padding
+  unsigned mhalo[2 * D];   // the same two conventions for the halo columns
 #pragma unroll
   for (int h = 0; h < 2 * D; ++h) {
     const int o = (h < D) ? h : h + NC;
     const int iw = iw0 + o;
-    mhalo[h] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
+    mhalo[h] = ((iw >= 0 && iw < p.W) != PZ) ? 0u : 0xffffffffu;
     hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
   }
 
@@ -136,7 +148,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
 
   // ---- main loop over channel pairs (cA = 2*du, cB = 2*du + 1; an odd C_in gets a virtual last
   // channel whose x is all NaN)
-  const int ndu = (dbg & 2) ? 0 : (p.C_in + 1) >> 1;
+#ifdef TCONV_TUNING
+  const int ndu = (flags & 2) ? 0 : (p.C_in + 1) >> 1;  // timing experiment: no main loop, WRONG results
+#else
+  const int ndu = (p.C_in + 1) >> 1;
+#endif
 
   auto chan_soff = [&](int c) -> unsigned {  // wave-uniform byte offset of channel c (clamped)
     return (unsigned)((size_t)min(c, p.C_in - 1) * HW * sizeof(float));
@@ -165,17 +181,19 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       }
     }
   };
-  auto mask_cols = [&](float (&xs)[6][XR], int lo, int hi, unsigned mB) {  // padding -> NaN, columns [lo, hi)
+  // padding -> NaN (identity) or +0 (zero padding), columns [lo, hi); the virtual channel of an odd C_in -> NaN always
+  auto mask_cols = [&](float (&xs)[6][XR], int lo, int hi, unsigned mB) {
 #pragma unroll
     for (int sl = 0; sl < 6; ++sl) {
-      const unsigned mr = mrow[sl % 3] | (sl >= 3 ? mB : 0u);
+      const unsigned vB = sl >= 3 ? mB : 0u;
+      const unsigned mr = PZ ? mrow[sl % 3] : (mrow[sl % 3] | vB);
 #pragma unroll
       for (int o = 0; o < XR; ++o) {
         if (o < lo || o >= hi) continue;
         unsigned m = mr;
-        if (o < D) m |= mhalo[o];
-        if (o >= D + NC) m |= mhalo[o - NC];
-        xs[sl][o] = nan_or(xs[sl][o], m);
+        if (o < D) m = PZ ? (m & mhalo[o]) : (m | mhalo[o]);
+        if (o >= D + NC) m = PZ ? (m & mhalo[o - NC]) : (m | mhalo[o - NC]);
+        xs[sl][o] = PZ ? __uint_as_float((__float_as_uint(xs[sl][o]) & m) | vB) : nan_or(xs[sl][o], m);
       }
     }
   };
@@ -394,7 +412,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
 #pragma unroll
         for (int j = 2; j >= 0; --j) {
           float xv;
-          bool ok = (mrow[i] == 0u);
+          bool ok = PZ ? (mrow[i] != 0u) : (mrow[i] == 0u);  // the row is inside the image
           if (inner) {
             xv = run[u][i][j * D];
           } else {
@@ -405,10 +423,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
             const int iw = iwq + j * D;
             ok = ok && (iw >= 0 && iw < p.W);
           }
-          const float sum = __fadd_rn(xv, wv[u][i * 3 + j]);
-          r = (ok && sum == best_row[q]) ? csv[u] * 9 + i * 3 + j : r;
+          // an out-of-image tap: no candidate (identity padding), or the candidate 0 + w (zero padding)
+          const float sum = __fadd_rn((PZ && !ok) ? 0.0f : xv, wv[u][i * 3 + j]);
+          r = ((PZ || ok) && sum == best_row[q]) ? csv[u] * 9 + i * 3 + j : r;
         }
-      res[q] = (dbg & 1) ? csv[u] * 9 : r;
+#ifdef TCONV_TUNING
+      res[q] = (flags & 1) ? csv[u] * 9 : r;  // timing experiment: no tap recovery, WRONG results
+#else
+      res[q] = r;
+#endif
     }
     __builtin_amdgcn_sched_barrier(0);  // the next batch starts after this one has retired its registers
   };
@@ -451,6 +474,23 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       else if (!DO_MAX) out[q] = bmin[c][q];
       else out[q] = combine(ca, bmin[c][q], cb, bmax[c][q]);
     }
+    // the layer's epilogue on the combined output: bias, folded batch norm, residual (wave-uniform branches)
+    if (ep.bias) {
+      const float bv = ep.bias[co];
+#pragma unroll
+      for (int q = 0; q < PX; ++q) out[q] = __fadd_rn(out[q], bv);
+    }
+    if (ep.scale) {
+      const float sc = ep.scale[co], sf = ep.shift ? ep.shift[co] : 0.0f;
+#pragma unroll
+      for (int q = 0; q < PX; ++q) out[q] = __fadd_rn(__fmul_rn(out[q], sc), sf);
+    }
+    if (ep.residual) {
+      const TO* rp = (const TO*)ep.residual + ob;
+#pragma unroll
+      for (int q = 0; q < PX; ++q)
+        if (q >= first_qs) out[q] = __fadd_rn(out[q], ld_f32(rp, (size_t)q));
+    }
     store_row<PX>(y + ob, out, first_qs);
   }
 }
@@ -471,7 +511,7 @@ void widen(const void* src, float* dst, size_t n, hipStream_t s) {
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-template <int MODE, int S, int D, int TN, typename TO>
+template <int MODE, int S, int D, int TN, bool PZ, typename TO>
 hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const float* w_max,
                      const FwdArgs& a, hipStream_t s) {
   constexpr int PX = (S == 1) ? 8 : 4;
@@ -482,8 +522,14 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
   const long long gblocks = (n_groups + WAVES - 1) / WAVES;
   const long long blocks = ublocks * gblocks;
   if (blocks > 0x7ffffff0LL) return hipErrorInvalidValue;
+#ifdef TCONV_TUNING
+  // Timing experiments only, never in the default build: bit 0 skips the tap recovery, bit 1 the main loop (both give
+  // WRONG results), bit 4 gathers kernel values from global memory, bit 5 forces the round-robin order.
   const char* e = getenv("TCONV_DEBUG_FLAGS");
   const int dbg = e ? atoi(e) : 0;
+#else
+  constexpr int dbg = 0;
+#endif
   // kernel rows a wave stages in LDS for the epilogue gathers: as many (a power of two) as fit its
   // 12 KB share (32 KB of static LDS + 4 x 12 KB leave room for two workgroups per compute unit)
   constexpr int NT = (MODE == TCONV_PARALLEL) ? 2 : 1;
@@ -499,20 +545,25 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
   // fetched) while the kernels are small next to an L2 (0.15 - 0.6 MB), -4 % to +1 % at 2.4 MB, -5 % at 4.7 MB;
   // beyond 2 MB the round-robin order stays.
   const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * NT;
-  const int flags = dbg | (w_bytes > 2LL * 1024 * 1024 ? 32 : 0);
+  const int flags = dbg | (w_bytes > 2LL * 1024 * 1024 ? FLAG_ROUND_ROBIN : 0);
   const long long grid = ((blocks + 7) / 8) * 8;
-  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, TO>), dim3((unsigned)grid), dim3(WAVES * 64),
+  const Epilogue ep = {a.bias, a.scale, a.shift, a.residual};
+  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, PZ, TO>), dim3((unsigned)grid), dim3(WAVES * 64),
                      lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
-                     a.idx_min, a.idx_max, segs, (int)n_units, n_groups, wrps, flags, (int)blocks);
+                     a.idx_min, a.idx_max, ep, segs, (int)n_units, n_groups, wrps, flags, (int)blocks);
   return hipGetLastError();
 }
 
-// workgroups the chip holds at once (two per compute unit)
+// workgroups the chip holds at once (two per compute unit); the unit count is asked for once per process
+// (every device of a node is the same part)
 long long resident_workgroups() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-    cus = 256;
+  static const int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+    return n;
+  }();
   return 2LL * cus;
 }
 
@@ -530,8 +581,11 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
   if (const char* e = getenv("TCONV_FWD_TN")) {  // tuning aid
     if (atoi(e) == 2 || atoi(e) == 4) tn = atoi(e);
   }
-  return tn == 2 ? launch_tn<MODE, S, D, 2, TO>(p, x, w_min, w_max, a, s)
-                 : launch_tn<MODE, S, D, 4, TO>(p, x, w_min, w_max, a, s);
+  if (p.pad_zero)
+    return tn == 2 ? launch_tn<MODE, S, D, 2, true, TO>(p, x, w_min, w_max, a, s)
+                   : launch_tn<MODE, S, D, 4, true, TO>(p, x, w_min, w_max, a, s);
+  return tn == 2 ? launch_tn<MODE, S, D, 2, false, TO>(p, x, w_min, w_max, a, s)
+                 : launch_tn<MODE, S, D, 4, false, TO>(p, x, w_min, w_max, a, s);
 }
 
 template <int MODE, typename TO>

@@ -15,6 +15,7 @@ struct Params {
   int Ho, Wo;
   int K;     // C_in*KH*KW
   int mode;  // enum tconv_mode
+  int pad_zero;  // 0: out-of-image taps never win (semiring identity); 1: they are candidates with input value +0
 };
 
 // Which kernel / index / output side a mode uses.  The mixed layers are single-branch: (iii) MinPlus-Max
@@ -48,6 +49,11 @@ struct FwdArgs {
   void* y_max;
   int32_t* idx_min;
   int32_t* idx_max;
+  // epilogue on the combined output y (each NULL = step left out), applied in this order:
+  const float* bias;      // [C_out]: y + bias
+  const float* scale;     // [C_out]: y * scale + shift (shift NULL = 0), a batch norm folded for inference
+  const float* shift;
+  const void* residual;   // [N, C_out, H_out, W_out] in the storage dtype: y + residual
 };
 
 struct BwdArgs {
@@ -118,6 +124,15 @@ __device__ __forceinline__ float combine(float a, float ymin, float b, float yma
   return __fadd_rn(__fmul_rn(a, ymin), __fmul_rn(b, ymax));
 }
 
+// The epilogue of one output: bias, affine, residual, every operation rounded to fp32 on its own.
+template <typename T>
+__device__ __forceinline__ float apply_epilogue(float t, const FwdArgs& a, int co, size_t o) {
+  if (a.bias) t = __fadd_rn(t, a.bias[co]);
+  if (a.scale) t = __fadd_rn(__fmul_rn(t, a.scale[co]), a.shift ? a.shift[co] : 0.0f);
+  if (a.residual) t = __fadd_rn(t, ld_f32((const T*)a.residual, o));
+  return t;
+}
+
 // Kernel launchers (each returns hipGetLastError() after its launches).
 hipError_t launch_forward_generic(const Params& p, int dtype, const FwdArgs& a, hipStream_t s);
 bool forward_tiled3x3_supported(const Params& p, int dtype);
@@ -127,10 +142,15 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
 bool forward_row_supported(const Params& p, int dtype);  // one-row inputs with a long window
 hipError_t launch_forward_row(const Params& p, const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);
+hipError_t launch_backward_bias(const Params& p, const float* gy, float* grad_bias, double* partial, hipStream_t s);
+// partial: device scratch of backward_weight_workspace(p) bytes for the deterministic two-stage form (fp64 partial
+// histograms per batch slice, added in a fixed order, one rounding), or NULL: fp32 atomics into zero-filled tensors
+size_t backward_weight_workspace(const Params& p);
 hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad_w_min,
-                                  float* grad_w_max, hipStream_t s);
+                                  float* grad_w_max, double* partial, hipStream_t s);
+size_t backward_alpha_beta_workspace(const Params& p);
 hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
-                                      const void* y_max, float* grad_alpha, float* grad_beta,
+                                      const void* y_max, float* grad_alpha, float* grad_beta, double* partial,
                                       hipStream_t s);
 
 hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s);

@@ -36,6 +36,7 @@ class LayerCfg:
     dtype: str = "f32"         # f32 | bf16 (storage of x, w, y)
     seed: int = 0
     w_range: float = 1.0       # kernels ~ U(-w_range, w_range)
+    pad_mode: str = "identity"  # identity (padding never wins) | zero (padding holds zeros)
 
     @property
     def K(self) -> int:

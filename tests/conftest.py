@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Worst relative gradient error seen on elements with |oracle| >= 1 (the strict gate of the parity tests)."""
+    try:
+        import harness
+    except Exception:
+        return
+    if harness.WORST_REL:
+        terminalreporter.write_line("worst |hip - oracle| / |oracle| where |oracle| >= 1 (gate 1e-5):")
+        for k, v in sorted(harness.WORST_REL.items(), key=lambda kv: -kv[1])[:12]:
+            terminalreporter.write_line(f"  {k}: {v:.3e}")

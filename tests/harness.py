@@ -47,8 +47,20 @@ def run_oracle(cfg, inp, backward=True):
     return r
 
 
-def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
-    """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32)."""
+def scratch(nbytes, dev):
+    """A poisoned device buffer of nbytes (None for 0): the library must not rely on what a workspace holds."""
+    import torch
+    if not nbytes:
+        return None
+    t = torch.empty((nbytes + 7) // 8, device=dev, dtype=torch.float64)
+    t.fill_(float("nan"))
+    return t
+
+
+def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deterministic=True, fused=False):
+    """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32).
+    deterministic: the parameter gradients get their workspaces (fixed-order fp64 sums); False: the atomic forms.
+    fused: grad_x and the kernel gradients through the one-call tconv_backward instead of the two separate calls."""
     import torch
     dev = torch.device(device)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -87,16 +99,22 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0"):
     out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
     if backward:
         gx = torch.full((cfg.N, cfg.C_in, cfg.H, cfg.W), float("nan"), device=dev)
-        tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
         wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
         gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
-        tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        if fused:
+            ws_b = scratch(tb.tconv_workspace_bytes(d, "backward"), dev) if deterministic else None
+            tb.tconv_backward(d, gy, alpha, beta, idx_min, idx_max, gx, gw_min, gw_max, ws_b)
+        else:
+            tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+            ws_w = scratch(tb.tconv_workspace_bytes(d, "backward_weight"), dev) if deterministic else None
+            tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max, ws_w)
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
         if cfg.mode in ("compound", "parallel") and branch_outputs:
             ga = torch.full((cfg.C_out,), float("nan"), device=dev)
             gb = torch.full((cfg.C_out,), float("nan"), device=dev)
-            tb.tconv_backward_alpha_beta(d, gy, y_min, y_max, ga, gb)
+            ws_ab = scratch(tb.tconv_workspace_bytes(d, "backward_alpha_beta"), dev) if deterministic else None
+            tb.tconv_backward_alpha_beta(d, gy, y_min, y_max, ga, gb, ws_ab)
             out.update(grad_alpha=ga, grad_beta=gb)
     torch.cuda.synchronize()
     res = {}
@@ -131,10 +149,19 @@ def assert_forward_bit_exact(hip, ref, keys=("y", "y_min", "y_max", "idx_min", "
                                  f"hip={a[first]!r} oracle={b[first]!r}")
 
 
-def assert_grad_close(a, b, scale, name, rtol=GRAD_RTOL):
-    """|a - b| <= rtol * max(1, sum of |summands|) per element, and the same bound in the max norm of b."""
+# worst observed |hip - oracle| / |oracle| over the elements with |oracle| >= 1, per gradient tensor name; the test
+# session prints the largest of them at its end (tests/conftest.py)
+WORST_REL = {}
+
+
+def assert_grad_close(a, b, scale, name, rtol=GRAD_RTOL, strict=True):
+    """Three gates: |a - b| <= rtol * max(1, sum of |summands|) per element; the same bound in the max norm of b;
+    and (strict) |a - b| <= rtol * |b| on every element with |b| >= 1, the plain relative tolerance.  The strict gate
+    is left out only for sums combined with fp32 atomics across workgroups, where an element can be a small rest of
+    large partial sums."""
     assert a.shape == b.shape, f"{name}: shape {a.shape} vs {b.shape}"
     assert np.isfinite(a).all(), f"{name}: non-finite values (output not overwritten?)"
+    b = np.asarray(b, np.float64)
     err = np.abs(a.astype(np.float64) - b)
     bound = rtol * np.maximum(1.0, scale)
     if not (err <= bound).all():
@@ -142,17 +169,27 @@ def assert_grad_close(a, b, scale, name, rtol=GRAD_RTOL):
         raise AssertionError(f"{name}: element {i} hip={a[i]!r} oracle={b[i]!r} |err|={err[i]:.3e} "
                              f"> {bound[i]:.3e}")
     assert err.max() <= rtol * max(1.0, np.abs(b).max()), f"{name}: max-norm error {err.max():.3e}"
+    big = np.abs(b) >= 1.0
+    if big.any():
+        rel = err[big] / np.abs(b[big])
+        worst = float(rel.max())
+        key = name.split("] ")[-1]
+        WORST_REL[key] = max(WORST_REL.get(key, 0.0), worst)
+        if strict:
+            assert worst <= rtol, f"{name}: relative error {worst:.3e} on an element with |oracle| >= 1"
 
 
-def assert_backward_close(hip, ref, what=""):
+def assert_backward_close(hip, ref, what="", strict_params=True):
+    """strict_params=False: the parameter gradients came from the atomic forms (fp32 atomics across workgroups), which
+    the plain relative gate does not bind."""
     assert_grad_close(hip["grad_x"], ref["grad_x"], ref["grad_x_scale"], what + "grad_x")
     for k in ("grad_w_min", "grad_w_max"):
         if ref[k] is None:
             continue
-        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k, strict=strict_params)
     for k in ("grad_alpha", "grad_beta"):
         if ref.get(k) is not None and hip.get(k) is not None:
-            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k, strict=strict_params)
 
 
 # ---------------------------------------------------------------- Sum-channel layers
@@ -225,7 +262,8 @@ def assert_sum_close(hip, ref, what=""):
     for k in ("grad_x", "grad_w_min", "grad_w_max", "grad_alpha", "grad_beta"):
         if ref.get(k) is None:
             continue
-        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+        # the parameter gradients of these layers are combined with fp32 atomics across workgroups
+        assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k, strict=(k == "grad_x"))
 
 
 # ---------------------------------------------------------------- depthwise layers
@@ -294,7 +332,8 @@ def assert_dw_close(hip, ref, mode, what="", backward=True):
         for k in ("grad_x", "grad_w_min", "grad_w_max", "grad_alpha", "grad_beta"):
             if ref.get(k) is None:
                 continue
-            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k)
+            # the parameter gradients of these layers are combined with fp32 atomics across workgroups
+            assert_grad_close(hip[k], ref[k], ref[k + "_scale"], what + k, strict=(k == "grad_x"))
 
 
 # ---------------------------------------------------------------- one-dimensional layers
@@ -351,7 +390,8 @@ def run_hip_1d(cfg, inp, backward=True, device="cuda:0"):
         wshape = (cfg.C_out, cfg.C_in, cfg.K)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
         gw_max = torch.full(wshape, float("nan"), device=dev) if (do_max and cfg.mode != "compound") else None
-        tb.tconv1d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        tb.tconv1d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max,
+                                   scratch(tb.tconv1d_workspace_bytes(d, "backward_weight"), dev))
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
     torch.cuda.synchronize()
     return {k: (None if v is None else (v.float() if v.dtype == torch.bfloat16 else v).cpu().numpy())
@@ -402,7 +442,99 @@ def run_hip_3d(cfg, inp, backward=True, device="cuda:0"):
         wshape = (cfg.C_out, cfg.C_in) + tuple(cfg.k)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
         gw_max = torch.full(wshape, float("nan"), device=dev) if (do_max and cfg.mode != "compound") else None
-        tb.tconv3d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max)
+        tb.tconv3d_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max,
+                                   scratch(tb.tconv3d_workspace_bytes(d, "backward_weight"), dev))
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
     torch.cuda.synchronize()
     return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+# ---------------------------------------------------------------- zero padding and the fused epilogue
+
+def draw_epilogue(cfg, kind, seed=0):
+    """bias / scale / shift [C_out] and residual [N, C_out, Ho, Wo] (fp32 host arrays; residual on the bf16 grid for
+    bf16 storage).  kind: a string of the letters b (bias), a (affine scale + shift), s (scale only), r (residual)."""
+    from paper_2504_06881_amd.inputs import to_bf16_grid
+    rng = np.random.Generator(np.random.PCG64(cfg.seed + 7000 + seed))
+    ho, wo = cfg.out_hw
+    ep = dict(bias=None, scale=None, shift=None, residual=None)
+    if "b" in kind:
+        ep["bias"] = rng.standard_normal(cfg.C_out).astype(np.float32)
+    if "a" in kind or "s" in kind:
+        ep["scale"] = rng.uniform(0.5, 2.0, cfg.C_out).astype(np.float32)
+    if "a" in kind:
+        ep["shift"] = rng.standard_normal(cfg.C_out).astype(np.float32)
+    if "r" in kind:
+        r = rng.standard_normal((cfg.N, cfg.C_out, ho, wo)).astype(np.float32)
+        ep["residual"] = to_bf16_grid(r) if cfg.dtype == "bf16" else r
+    return ep
+
+
+def run_oracle_ext(cfg, inp, ep=None, backward=True):
+    """The extension oracle: the layer's padding mode, the epilogue, and the backward pass through winners that may lie
+    in the padding.  bf16 storage: outputs rounded to the bf16 grid, as the library stores them."""
+    from oracle import text_oracle as ext
+    from paper_2504_06881_amd.inputs import to_bf16_grid
+    s = ext.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+    ep = ep or {}
+    r = ext.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], inp["alpha"], inp["beta"],
+                    pad_zero=(cfg.pad_mode == "zero"), bias=ep.get("bias"), scale=ep.get("scale"),
+                    shift=ep.get("shift"), residual=ep.get("residual"))
+    if cfg.dtype == "bf16":
+        for k in ("y", "y_min", "y_max"):
+            if r[k] is not None:
+                r[k] = to_bf16_grid(r[k])
+    if backward:
+        kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"])
+        r.update(ext.backward(s, cfg.mode, inp["gy"], alpha=inp["alpha"], beta=inp["beta"], **kw))
+        ab = {k: (None if inp[k] is None else np.abs(inp[k])) for k in ("alpha", "beta")}
+        sc = ext.backward(s, cfg.mode, np.abs(inp["gy"]), alpha=ab["alpha"], beta=ab["beta"], **kw)
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+        r["grad_bias"] = ext.backward_bias(s, inp["gy"])
+        r["grad_bias_scale"] = ext.backward_bias(s, np.abs(inp["gy"]))
+    return r
+
+
+def run_hip_ext(cfg, inp, ep=None, backward=True, device="cuda:0"):
+    """tconv_forward_fused (+ tconv_backward and tconv_backward_bias) through the C ABI."""
+    import torch
+    dev = torch.device(device)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    d = tb.Desc.from_cfg(cfg)
+    ho, wo = tb.tconv_out_shape(d)
+    ep = ep or {}
+
+    def up(a, dt=torch.float32):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
+
+    x = up(inp["x"], tdt)
+    if cfg.mode == "compound":
+        w_min = w_max = up(inp["w_min"], tdt)
+    else:
+        w_min, w_max = up(inp["w_min"], tdt), up(inp["w_max"], tdt)
+    alpha, beta, gy = up(inp["alpha"]), up(inp["beta"]), up(inp["gy"])
+    oshape = (cfg.N, cfg.C_out, ho, wo)
+    do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+    nanf = lambda: torch.full(oshape, float("nan"), device=dev, dtype=tdt)
+    bad = lambda: torch.full(oshape, -12345, device=dev, dtype=torch.int32)
+    y, y_min, y_max = nanf(), (nanf() if do_min else None), (nanf() if do_max else None)
+    idx_min, idx_max = (bad() if do_min else None), (bad() if do_max else None)
+    ws = scratch(tb.tconv_workspace_bytes(d, "forward"), dev)
+    tb.tconv_forward_fused(d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max,
+                           bias=up(ep.get("bias")), scale=up(ep.get("scale")), shift=up(ep.get("shift")),
+                           residual=up(ep.get("residual"), tdt), workspace=ws)
+    out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
+    if backward:
+        gx = torch.full((cfg.N, cfg.C_in, cfg.H, cfg.W), float("nan"), device=dev)
+        wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+        gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel") else None
+        tb.tconv_backward(d, gy, alpha, beta, idx_min, idx_max, gx, gw_min, gw_max,
+                          scratch(tb.tconv_workspace_bytes(d, "backward"), dev))
+        gb = torch.full((cfg.C_out,), float("nan"), device=dev)
+        tb.tconv_backward_bias(d, gy, gb, scratch(tb.tconv_workspace_bytes(d, "backward_bias"), dev))
+        out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max, grad_bias=gb)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else (v.float() if v.dtype == torch.bfloat16 else v).cpu().numpy())
+            for k, v in out.items()}

@@ -99,3 +99,13 @@ def test_one_dimensional_descriptor_views():
         with pytest.raises(tb.TconvError) as e:
             tb.tconv1d_out_len(bad)
         assert e.value.status == code, bad
+
+
+def test_default_build_has_no_result_changing_knob():
+    """The timing-experiment switches of the tiled forward kernel (TCONV_DEBUG_FLAGS: skip the tap recovery, skip the
+    main loop) produce wrong results by design; they exist only in -DTCONV_TUNING builds.  The shipped library must
+    not even contain the name it would look up."""
+    blob = open(tb.LIB_PATH, "rb").read()
+    assert b"TCONV_DEBUG_FLAGS" not in blob
+    from paper_2504_06881_amd import build as b
+    assert not any("TCONV_TUNING" in f for f in b.FLAGS)

@@ -9,7 +9,7 @@ import pytest
 import harness as hs
 from paper_2504_06881_amd import binding as tb
 from paper_2504_06881_amd.inputs import CONFIGS, make_inputs
-from test_gpu_parity import RAGGED, _check
+from test_gpu_parity import BOTH_TN, RAGGED, RAGGED_LARGE, _check
 
 pytestmark = pytest.mark.gpu
 
@@ -27,6 +27,15 @@ def test_cfg1(mode, kernel):
 
 @pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
 def test_ragged_shapes(cfg):
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tn = BOTH_TN if tiled else (None,)
+    for mode in MIXED:
+        _check(cfg.with_(mode=mode), tn=tn)
+        _check(cfg.with_(mode=mode), integer=True, tn=tn)
+
+
+@pytest.mark.parametrize("cfg", RAGGED_LARGE[:2], ids=lambda c: c.name)
+def test_ragged_shapes_that_pick_four_channels_per_lane(cfg):
     for mode in MIXED:
         _check(cfg.with_(mode=mode))
         _check(cfg.with_(mode=mode), integer=True)
@@ -43,8 +52,8 @@ def test_generic_kernel_on_ragged_shapes(cfg):
 def test_bf16_storage(mode):
     for base in (RAGGED[0], RAGGED[2], RAGGED[4], CONFIGS["cfg1"]):
         cfg = base.with_(mode=mode, dtype="bf16")
-        _check(cfg)
-        _check(cfg, integer=True)
+        _check(cfg, tn=BOTH_TN)
+        _check(cfg, integer=True, tn=BOTH_TN)
 
 
 @pytest.mark.parametrize("name", ["cfg2_main", "cfg3b"])

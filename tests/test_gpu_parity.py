@@ -17,22 +17,49 @@ pytestmark = pytest.mark.gpu
 MODES = ("max", "min", "compound", "parallel")
 
 
-def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None, seed=None):
+KNOBS = ("TCONV_FORWARD_KERNEL", "TCONV_FWD_TN")
+
+
+def tiled_blocks4(cfg):
+    """Workgroups of the tiled forward kernel at 4 output channels per lane (the library's own count)."""
+    ho, wo = cfg.out_hw
+    px = 8 if cfg.stride == 1 else 4
+    units = cfg.N * ho * ((wo + px - 1) // px)
+    return ((units + 63) // 64) * (((cfg.C_out + 3) // 4 + 3) // 4)
+
+
+def picks_tn4(cfg):
+    """True when the library runs the 4-channels-per-lane instantiation of the tiled kernel on its own."""
+    return tiled_blocks4(cfg) * (2 if cfg.stride == 1 else 4) > 512 or cfg.C_out <= 2
+
+
+def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None, seed=None, tn=(None,)):
+    """One oracle run, one HIP run per entry of tn (None: the library's own choice of output channels per lane of
+    the tiled forward kernel; 2 / 4: that instantiation forced), each compared with the oracle."""
     inp = make_inputs(cfg, alpha_beta=alpha_beta, integer=integer, seed=seed)
     ref = hs.run_oracle(cfg, inp)
-    old = os.environ.pop("TCONV_FORWARD_KERNEL", None)
+    old = {k: os.environ.pop(k, None) for k in KNOBS}
+    hip = None
     try:
         if kernel:
             os.environ["TCONV_FORWARD_KERNEL"] = kernel
-        hip = hs.run_hip(cfg, inp, branch_outputs=branch_outputs)
+        for t in tn:
+            os.environ.pop("TCONV_FWD_TN", None)
+            if t:
+                os.environ["TCONV_FWD_TN"] = str(t)
+            hip = hs.run_hip(cfg, inp, branch_outputs=branch_outputs)
+            what = f"[{cfg.name} {cfg.mode} {cfg.dtype} ab={alpha_beta} int={integer} k={kernel} tn={t}] "
+            hs.assert_forward_bit_exact(hip, ref, what=what)
+            hs.assert_backward_close(hip, ref, what=what)
     finally:
-        os.environ.pop("TCONV_FORWARD_KERNEL", None)
-        if old is not None:
-            os.environ["TCONV_FORWARD_KERNEL"] = old
-    what = f"[{cfg.name} {cfg.mode} {cfg.dtype} ab={alpha_beta} int={integer} k={kernel}] "
-    hs.assert_forward_bit_exact(hip, ref, what=what)
-    hs.assert_backward_close(hip, ref, what=what)
+        for k in KNOBS:
+            os.environ.pop(k, None)
+            if old[k] is not None:
+                os.environ[k] = old[k]
     return hip, ref
+
+
+BOTH_TN = (2, 4)   # both instantiations of the tiled 3x3 forward kernel (small layers pick 2, large ones 4)
 
 
 @pytest.mark.parametrize("kernel", [None, "generic"])
@@ -78,16 +105,41 @@ RAGGED = [
     LayerCfg("r_cin300", 1, 300, 6, 8, 5, seed=33),
     LayerCfg("r_cin350", 1, 350, 6, 8, 3, seed=34),
     LayerCfg("r_cin131_s2", 1, 131, 9, 10, 6, stride=2, seed=35),
+    LayerCfg("r_cin260_s2", 1, 260, 9, 10, 5, stride=2, seed=36),
+]
+
+# Ragged layers large enough for the library to choose 4 output channels per lane by itself: many images with an
+# odd channel count and a ragged output-channel tail, many output channels, and the same at stride 2.
+RAGGED_LARGE = [
+    LayerCfg("rl_many_images", 300, 5, 19, 23, 7, seed=41),
+    LayerCfg("rl_many_cout", 64, 5, 19, 23, 70, seed=42),
+    LayerCfg("rl_s2", 200, 7, 33, 37, 22, stride=2, seed=43),
+    LayerCfg("rl_d2", 210, 3, 21, 27, 9, pad=2, dil=2, seed=44),
 ]
 
 
 @pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
 def test_ragged_shapes(cfg):
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tn = BOTH_TN if tiled else (None,)
     for mode in MODES:
         c = cfg.with_(mode=mode)
-        _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+        _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None, tn=tn)
+    _check(cfg.with_(mode="compound"), integer=True, tn=tn)
+    _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast", tn=tn)
+    _check(cfg.with_(mode="max"), integer=True, tn=tn)
+    _check(cfg.with_(mode="min"), integer=True, tn=tn)
+
+
+@pytest.mark.parametrize("cfg", RAGGED_LARGE, ids=lambda c: c.name)
+def test_ragged_shapes_that_pick_four_channels_per_lane(cfg):
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3" and picks_tn4(cfg)
+    for mode in MODES:
+        _check(cfg.with_(mode=mode), alpha_beta="random" if mode in ("compound", "parallel") else None)
     _check(cfg.with_(mode="compound"), integer=True)
     _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
+    _check(cfg.with_(mode="compound", dtype="bf16"), integer=True)
+    _check(cfg.with_(mode="parallel", dtype="bf16"), alpha_beta="random")
 
 
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10]], ids=lambda c: c.name)
@@ -99,10 +151,10 @@ def test_generic_kernel_on_ragged_shapes(cfg):
 
 @pytest.mark.parametrize("mode", MODES)
 def test_bf16_storage(mode):
-    for base in (RAGGED[0], RAGGED[2], RAGGED[4], CONFIGS["cfg1"]):
+    for base in (RAGGED[0], RAGGED[1], RAGGED[2], RAGGED[4], RAGGED[20], CONFIGS["cfg1"]):
         cfg = base.with_(mode=mode, dtype="bf16")
-        _check(cfg, alpha_beta="random" if mode in ("compound", "parallel") else None)
-        _check(cfg, integer=True)
+        _check(cfg, alpha_beta="random" if mode in ("compound", "parallel") else None, tn=BOTH_TN)
+        _check(cfg, integer=True, tn=BOTH_TN)
 
 
 def test_forward_is_deterministic_and_stream_ordered():
@@ -158,44 +210,92 @@ def test_full_size_configs(name):
 
 
 @pytest.mark.parametrize("name,dtype", [("cfg4a", "f32"), ("cfg4a", "bf16"), ("cfg4b", "f32"), ("cfg4b", "bf16")])
-def test_segmentation_configs_sampled(name, dtype):
-    """Full-size launch; images 0 and N-1 are compared output by output with the oracle, and the
-    remaining images through properties that hold at any size (index validity, gradient mass)."""
+def test_segmentation_configs_full(name, dtype):
+    """The full-size segmentation layers, all 8 images, every output and every gradient element against the oracle
+    (a few seconds of the OpenMP oracle per layer)."""
     cfg = CONFIGS[name].with_(dtype=dtype)
-    print(f"[sampled] {name} {dtype} pairs={cfg.pairs:.3e}", flush=True)
-    inp = make_inputs(cfg)
-    hip = hs.run_hip(cfg, inp)
-    for n in (0, cfg.N - 1):
-        sub = cfg.with_(N=1)
-        sinp = dict(inp, x=inp["x"][n:n + 1], gy=inp["gy"][n:n + 1])
-        ref = hs.run_oracle(sub, sinp)
-        part = {k: (None if v is None else v[n:n + 1]) for k, v in hip.items() if not k.startswith("grad_w")}
-        hs.assert_forward_bit_exact(part, ref, what=f"[{name} {dtype} n={n}] ")
-        hs.assert_grad_close(part["grad_x"], ref["grad_x"], ref["grad_x_scale"], f"[{name} n={n}] grad_x")
+    print(f"[full] {name} {dtype} pairs={cfg.pairs:.3e}", flush=True)
+    hip, _ = _check(cfg)
     for k in ("idx_min", "idx_max"):
         assert hip[k].min() >= 0 and hip[k].max() < cfg.K
-    tot = 2.0 * inp["gy"].astype(np.float64).sum()
-    scale = 2.0 * np.abs(inp["gy"]).astype(np.float64).sum()
-    assert abs(hip["grad_x"].astype(np.float64).sum() - tot) <= 1e-5 * scale
-    assert abs(hip["grad_w_min"].astype(np.float64).sum() - tot) <= 1e-5 * scale
-
-
-def test_segmentation_weight_gradient_on_a_slice():
-    """grad_w needs every image, so it is compared on a two-image slice of the segmentation layers."""
-    for name in ("cfg4a", "cfg4b"):
-        cfg = CONFIGS[name].with_(N=2)
-        _check(cfg)
 
 
 def test_resnet20_layers_one_each():
-    """One layer of each distinct shape of the all-parallel ResNet-20-style stack, batch 32."""
+    """One layer of each distinct shape of the all-parallel ResNet-20-style stack, batch 32 (small grids: the
+    library picks 2 output channels per lane; the other instantiation is forced as well)."""
     seen = set()
     for cfg in resnet20_layers(batch=32):
         key = (cfg.C_in, cfg.H, cfg.C_out, cfg.stride)
         if key in seen:
             continue
         seen.add(key)
+        _check(cfg, tn=(None, 4))
+
+
+def test_resnet20_layers_at_the_benchmark_batch():
+    """The same distinct layer shapes at the batch of the end-to-end configuration (256), where the 16-channel
+    32 x 32 layers are large enough for 4 output channels per lane."""
+    seen = set()
+    for cfg in resnet20_layers(batch=256):
+        key = (cfg.C_in, cfg.H, cfg.C_out, cfg.stride)
+        if key in seen:
+            continue
+        seen.add(key)
+        print(f"[r20 b256] {cfg.name} tn4={picks_tn4(cfg)}", flush=True)
         _check(cfg)
+    assert picks_tn4(resnet20_layers(batch=256)[1])
+
+
+def test_debug_flags_are_not_read_by_the_default_build():
+    """TCONV_DEBUG_FLAGS belongs to tuning builds (-DTCONV_TUNING) only: the shipped library must give the same
+    bit-exact results with it set."""
+    os.environ["TCONV_DEBUG_FLAGS"] = "19"
+    try:
+        _check(RAGGED[0].with_(mode="compound"), tn=BOTH_TN)
+    finally:
+        os.environ.pop("TCONV_DEBUG_FLAGS", None)
+
+
+@pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[20], RAGGED_LARGE[0]],
+                         ids=lambda c: c.name)
+def test_fused_backward_and_atomic_forms(cfg):
+    """tconv_backward (both gradients in one call) equals the two separate calls bit for bit, with and without the
+    deterministic workspace; the atomic forms of the parameter gradients (no workspace) stay within the summand-scaled
+    tolerance."""
+    for mode in MODES:
+        c = cfg.with_(mode=mode)
+        inp = make_inputs(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+        ref = hs.run_oracle(c, inp)
+        sep = hs.run_hip(c, inp)
+        fus = hs.run_hip(c, inp, fused=True)
+        what = f"[{c.name} {mode} fused] "
+        hs.assert_backward_close(fus, ref, what=what)
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            if sep[k] is not None:
+                assert np.array_equal(hs.bits(sep[k]), hs.bits(fus[k])), what + k + ": differs from the separate calls"
+        for fused in (False, True):
+            ato = hs.run_hip(c, inp, deterministic=False, fused=fused)
+            hs.assert_backward_close(ato, ref, what=f"[{c.name} {mode} atomic fused={fused}] ", strict_params=False)
+            assert np.array_equal(hs.bits(sep["grad_x"]), hs.bits(ato["grad_x"]))
+
+
+def test_workspace_errors():
+    import torch
+    cfg = RAGGED[0].with_(mode="parallel")
+    d = tb.Desc.from_cfg(cfg)
+    need = tb.tconv_workspace_bytes(d, "backward_weight")
+    assert need > 0 and need == tb.tconv_workspace_bytes(d, "backward")
+    z = torch.zeros(cfg.N * cfg.C_out * cfg.H * cfg.W, device="cuda")
+    zi = torch.zeros(z.numel(), device="cuda", dtype=torch.int32)
+    gw = torch.zeros(cfg.C_out * cfg.K, device="cuda")
+    small = torch.zeros(need // 8 - 1, device="cuda", dtype=torch.float64)
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_backward_weight(d, z, None, None, zi, zi, gw, gw.clone(), small)
+    assert e.value.status == -3
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_backward(d, z, None, None, zi, zi, torch.zeros(cfg.N * cfg.C_in * cfg.H * cfg.W, device="cuda"), gw,
+                          gw.clone(), small)
+    assert e.value.status == -3
 
 
 def test_alpha_beta_gradient_single_outputs():
