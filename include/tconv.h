@@ -194,6 +194,20 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
                           size_t workspace_bytes, void* hip_stream);
 
 /*
+ * tconv_backward_weight for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments without the workspace pair, same deterministic
+ * result bit for bit as tconv_backward_weight with a workspace: the fp64 partial histograms go to a fixed array of
+ * 32 MiB of device memory that the library owns (each GPU the library runs on holds one until the process ends).
+ * The call allocates nothing and frees nothing.  TCONV_E_WORKSPACE: the layer needs more than 32 MiB of partial
+ * histograms (tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_WEIGHT) tells how much); nothing was enqueued.
+ * All calls on one GPU share the array: it needs no clearing between calls (every element is written before it is
+ * read), but two calls whose kernels overlap in time on one GPU (different streams, different threads) race.
+ */
+int tconv_backward_weight_noalloc(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                                  const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                                  float* grad_w_max, void* hip_stream);
+
+/*
  * Both gradients of the layer in one call: grad_x as tconv_backward_input writes it and the kernel gradient(s) as
  * tconv_backward_weight writes them, from the same gy / idx (every argument as in those two calls; grad_x and the
  * kernel gradient(s) of the mode are all required).  workspace: as for tconv_backward_weight, sized by

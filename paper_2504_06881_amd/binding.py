@@ -21,7 +21,7 @@ OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2, "backward_alpha_
        "backward_bias": 5}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_forward_fused", "tconv_backward_bias",
            "tconv_backward_input",
-           "tconv_backward_weight", "tconv_backward", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
+           "tconv_backward_weight", "tconv_backward_weight_noalloc", "tconv_backward", "tconv_backward_alpha_beta", "tconv_sum_forward", "tconv_sum_backward",
            "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
@@ -146,6 +146,8 @@ def load() -> ctypes.CDLL:
         lib.tconv_backward_input.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_backward_weight.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
         lib.tconv_backward.argtypes = [D] + [P] * 9 + [ctypes.c_size_t, P]
+        lib.tconv_backward_weight_noalloc.argtypes = [D] + [P] * 8
+        lib.tconv_backward_weight_noalloc.restype = ctypes.c_int
         lib.tconv_backward_alpha_beta.argtypes = [D] + [P] * 6 + [ctypes.c_size_t, P]
         lib.tconv_sum_forward.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_sum_backward.argtypes = [D] + [P] * 12 + [ctypes.c_size_t, P]
@@ -271,6 +273,13 @@ def tconv_backward_weight(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_w_
                                         _ptr(idx_min), _ptr(idx_max), _ptr(grad_w_min),
                                         _ptr(grad_w_max), _ptr(workspace), wsz, _stream()),
            "tconv_backward_weight")
+
+
+def tconv_backward_weight_noalloc(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_w_min, grad_w_max) -> None:
+    cd = desc.c()
+    _check(load().tconv_backward_weight_noalloc(ctypes.byref(cd), _ptr(gy), _ptr(alpha), _ptr(beta), _ptr(idx_min),
+                                                _ptr(idx_max), _ptr(grad_w_min), _ptr(grad_w_max), _stream()),
+           "tconv_backward_weight_noalloc")
 
 
 def tconv_backward(desc: Desc, gy, alpha, beta, idx_min, idx_max, grad_x, grad_w_min, grad_w_max,

@@ -187,6 +187,30 @@ int tconv_backward_weight(const tconv_desc* desc, const float* gy, const float* 
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 
+int tconv_backward_weight_noalloc(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                                  const int32_t* idx_min, const int32_t* idx_max, float* grad_w_min,
+                                  float* grad_w_max, void* hip_stream) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  switch (p.mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  if (backward_weight_workspace(p) > backward_weight_static_limit()) return TCONV_E_WORKSPACE;
+  BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  own_status();
+  const hipError_t e = launch_backward_weight_static(p, a, grad_w_min, grad_w_max, (hipStream_t)hip_stream);
+  if (e == hipErrorOutOfMemory) return TCONV_E_WORKSPACE;
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
 int tconv_backward(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
                    const int32_t* idx_min, const int32_t* idx_max, float* grad_x, float* grad_w_min,
                    float* grad_w_max, void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -12,6 +12,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "tile_common.h"
 
 namespace tconv {
@@ -668,6 +670,51 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
     }
   }
   return hipGetLastError();
+}
+
+// ---- the kernel gradient for callers that cannot hand over a workspace: the partial histograms live in a fixed
+// array in device memory that belongs to the library (each GPU the library runs on holds its own copy until the
+// process ends).  In host code the array's name is only a stand-in for that per-device copy; its device address is
+// asked for once per device and that pointer is what the kernels get.
+constexpr size_t STATIC_SCRATCH_BYTES = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+size_t backward_weight_static_limit() { return STATIC_SCRATCH_BYTES; }
+
+// The scratch array's address on the current device (NULL and an error code if the runtime refuses).
+static hipError_t static_scratch(double** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex lock;
+  static void* ptrs[MAX_DEV] = {};
+  *out = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> g(lock);
+  if (!ptrs[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    ptrs[dev] = ptr;
+  }
+  *out = (double*)ptrs[dev];
+  return hipSuccess;
+}
+
+// Deterministic kernel gradient with the library's own scratch.  hipErrorOutOfMemory: the layer needs more than the
+// array holds (nothing was enqueued).  Every partial histogram is written before it is read, so the array needs no
+// clearing between calls; two calls in flight on one GPU at the same time would share it and race.
+hipError_t launch_backward_weight_static(const Params& p, const BwdArgs& a, float* grad_w_min, float* grad_w_max,
+                                         hipStream_t s) {
+  const size_t need = backward_weight_workspace(p);
+  if (need > STATIC_SCRATCH_BYTES) return hipErrorOutOfMemory;
+  double* partial = nullptr;
+  if (need > 0) {
+    const hipError_t e = static_scratch(&partial);
+    if (e != hipSuccess) return e;
+  }
+  return launch_backward_weight(p, a, grad_w_min, grad_w_max, partial, s);
 }
 
 // ---- gradient of the combine step (paper Sec. 3.3: y = alpha*y_min + beta*y_max with learnable alpha,

@@ -148,6 +148,11 @@ hipError_t launch_backward_bias(const Params& p, const float* gy, float* grad_bi
 size_t backward_weight_workspace(const Params& p);
 hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad_w_min,
                                   float* grad_w_max, double* partial, hipStream_t s);
+// the same with the library's own fixed scratch array (no workspace argument, nothing allocated);
+// hipErrorOutOfMemory when the layer needs more than backward_weight_static_limit() bytes
+size_t backward_weight_static_limit();
+hipError_t launch_backward_weight_static(const Params& p, const BwdArgs& a, float* grad_w_min, float* grad_w_max,
+                                         hipStream_t s);
 size_t backward_alpha_beta_workspace(const Params& p);
 hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* gy, const void* y_min,
                                       const void* y_max, float* grad_alpha, float* grad_beta, double* partial,
