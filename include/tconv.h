@@ -65,7 +65,16 @@ enum tconv_mode {
   TCONV_MAXPLUS_MIN = 5  /* Sec. 3.1 layer (vi) MaxPlus-Min-Conv2d: min over c_in of the max-plus operator;
                             single branch on the MAX side (w_max, idx_max, y_max, grad_w_max)       */
 };
-enum tconv_dtype { TCONV_F32 = 0, TCONV_BF16 = 1 };
+enum tconv_dtype {
+  TCONV_F32 = 0,
+  TCONV_BF16 = 1,  /* storage only: widened exactly, all arithmetic and the index decision in fp32 */
+  TCONV_F16 = 2    /* IEEE binary16 storage AND arithmetic (the packed 16-bit path): every candidate x + w is ONE add
+                      rounded to binary16 (nearest even), the comparisons are on those binary16 sums, ties keep the
+                      lowest k; the combine is evaluated in fp32 from the binary16 extrema (two rounded products, one
+                      rounded sum) and rounded to binary16 once.  tconv_forward / tconv_backward* / the one-dimensional
+                      entry points only; no epilogue (TCONV_E_UNSUPPORTED elsewhere).  Results differ from the fp32
+                      layers by construction: it is a different numeric contract, not an approximation of theirs. */
+};
 enum tconv_pad_mode {
   TCONV_PAD_IDENTITY = 0,  /* padding holds the semiring identity (Sec. 3.1): a padded tap never wins            */
   TCONV_PAD_ZERO = 1       /* padding holds zeros (App. A.1.1, the unfold formulation pads the input with zeros):

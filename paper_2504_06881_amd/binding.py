@@ -15,7 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtconv.so")
 
 MODES = {"max": 0, "min": 1, "compound": 2, "parallel": 3, "minplus_max": 4, "maxplus_min": 5}
-DTYPES = {"f32": 0, "bf16": 1}
+DTYPES = {"f32": 0, "bf16": 1, "f16": 2}
 PAD_MODES = {"identity": 0, "zero": 1}
 OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2, "backward_alpha_beta": 3, "backward": 4,
        "backward_bias": 5}

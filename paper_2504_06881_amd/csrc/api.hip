@@ -19,7 +19,7 @@ int make_params(const tconv_desc* d, Params* p) {
       d->pad_w < 0)
     return TCONV_E_INVAL;
   if (d->mode < TCONV_MAX || d->mode > TCONV_MAXPLUS_MIN) return TCONV_E_INVAL;
-  if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16) return TCONV_E_INVAL;
+  if (d->dtype != TCONV_F32 && d->dtype != TCONV_BF16 && d->dtype != TCONV_F16) return TCONV_E_INVAL;
   if (d->pad_mode != TCONV_PAD_IDENTITY && d->pad_mode != TCONV_PAD_ZERO) return TCONV_E_INVAL;
   const long long eh = (long long)d->dil_h * (d->KH - 1), ew = (long long)d->dil_w * (d->KW - 1);
   // a window must never lie wholly in the padding (kept for zero padding too: one rule for both modes)
@@ -119,6 +119,10 @@ int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min
   if (!x || !y) return TCONV_E_INVAL;
   FwdArgs a = {x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max};
   if (p.pad_zero && p.mode > TCONV_PARALLEL) return TCONV_E_UNSUPPORTED;  // the mixed layers keep identity padding
+  if (desc->dtype == TCONV_F16 && p.mode > TCONV_PARALLEL) return TCONV_E_UNSUPPORTED;  // and fp32 / bf16 storage
+  if (epilogue && desc->dtype == TCONV_F16 &&
+      (epilogue->bias || epilogue->scale || epilogue->shift || epilogue->residual))
+    return TCONV_E_UNSUPPORTED;  // the binary16 contract has no epilogue
   if (epilogue) {
     if (epilogue->shift && !epilogue->scale) return TCONV_E_INVAL;
     a.bias = epilogue->bias; a.scale = epilogue->scale; a.shift = epilogue->shift; a.residual = epilogue->residual;
@@ -135,7 +139,7 @@ int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min
       return TCONV_E_WORKSPACE;
     own_status();
     e = launch_forward_tiled3x3(p, desc->dtype, a, workspace, s);
-  } else if (use_row(p, desc->dtype)) {
+  } else if (use_row(p, desc->dtype) && !a.bias && !a.scale && !a.residual) {  // the row kernel has no epilogue
     own_status();
     e = launch_forward_row(p, a, s);
   } else {

@@ -368,7 +368,7 @@ static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
         if (TW + ew < 16) cost *= 1.5;
         const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
         const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
-        if (wgs < 512) cost *= 1.0 + (512 - wgs) / 512;  // too few workgroups to fill 256 CUs
+        if (wgs < 256) cost *= 1.0 + (256 - wgs) / 256;  // too few workgroups to fill 256 CUs
         {  // threads that own a scanned pixel: whole channel groups of P threads (see the kernel)
           const long long RH = min((long long)p.Ho, (long long)(TH + eh) / p.sh + 1);
           const long long RW = min((long long)p.Wo, (long long)(TW + ew) / p.sw + 1);
@@ -418,7 +418,10 @@ static bool launch_backward_input_row(const Params& p, const BwdArgs& a, float* 
 
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s) {
   if (launch_backward_input_row(p, a, grad_x, s)) return hipGetLastError();
-  size_t LDS_BUDGET = 78 * 1024;  // per workgroup: two workgroups share a CU's 160 KB of LDS
+  // One workgroup per compute unit with nearly all of its 160 KB of LDS: measured faster than two half-size tiles on
+  // every benchmark layer (a larger tile re-reads less halo; 30 / 60 / 78 / 100 / 156 KB: 76 / 53 / 49 / 47 / 45 us on
+  // the cfg2 layer, 167 / 86 / 75 / 67 / 55 us on cfg4b)
+  size_t LDS_BUDGET = 156 * 1024;
   if (const char* e = getenv("TCONV_BWD_LDS_KB")) LDS_BUDGET = (size_t)atoi(e) * 1024;
   const BwdInTile t = choose_bwd_input_tile(p, LDS_BUDGET);
   const long long blocks = (long long)p.N * t.tiles_h * t.tiles_w * t.chunks;
@@ -803,7 +806,10 @@ hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* g
   int n_per_block = 0;
   const int slices = ab_slices(p, &n_per_block);
   const dim3 grid((unsigned)p.C_out, (unsigned)slices);
-  if (dtype == TCONV_BF16)
+  if (dtype == TCONV_F16)
+    hipLaunchKernelGGL(bwd_alpha_beta_kernel<f16_t>, grid, dim3(256), 0, s, p, gy, (const f16_t*)y_min,
+                       (const f16_t*)y_max, grad_alpha, grad_beta, n_per_block, partial);
+  else if (dtype == TCONV_BF16)
     hipLaunchKernelGGL(bwd_alpha_beta_kernel<bf16_t>, grid, dim3(256), 0, s, p, gy, (const bf16_t*)y_min,
                        (const bf16_t*)y_max, grad_alpha, grad_beta, n_per_block, partial);
   else

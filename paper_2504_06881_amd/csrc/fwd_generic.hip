@@ -54,12 +54,12 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Params p, FwdArgs a) {
         if (!inside && !p.pad_zero) continue;
         const float xv = inside ? ld_f32(xc, (size_t)ih * p.W + iw) : 0.0f;
         if (MODE == TCONV_PARALLEL) {
-          const float s1 = __fadd_rn(xv, ld_f32(wmn, k));
-          const float s2 = __fadd_rn(xv, ld_f32(wmx, k));
+          const float s1 = candidate<T>(xv, ld_f32(wmn, k));
+          const float s2 = candidate<T>(xv, ld_f32(wmx, k));
           if (s1 < bmin) { bmin = s1; imin = k; }
           if (s2 > bmax) { bmax = s2; imax = k; }
         } else {
-          const float s = __fadd_rn(xv, ld_f32(DO_MAX ? wmx : wmn, k));
+          const float s = candidate<T>(xv, ld_f32(DO_MAX ? wmx : wmn, k));
           if (DO_MAX && s > bmax) { bmax = s; imax = k; }
           if (DO_MIN && s < bmin) { bmin = s; imin = k; }
         }
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void fwd_mixed_generic_kernel(Params p, FwdArg
         const int iw = iw0 + j * p.dw;
         const bool inside = rv && iw >= 0 && iw < p.W;
         if (!inside && !p.pad_zero) continue;
-        const float s = __fadd_rn(inside ? ld_f32(xc, (size_t)ih * p.W + iw) : 0.0f, ld_f32(wr, k));
+        const float s = candidate<T>(inside ? ld_f32(xc, (size_t)ih * p.W + iw) : 0.0f, ld_f32(wr, k));
         if (OUTER_MAX ? (s < v) : (s > v)) { v = s; kv = k; }
       }
     }
@@ -154,6 +154,7 @@ static hipError_t launch_m(const Params& p, const FwdArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_forward_generic(const Params& p, int dtype, const FwdArgs& a, hipStream_t s) {
+  if (dtype == TCONV_F16) return launch_m<f16_t>(p, a, s);
   return dtype == TCONV_BF16 ? launch_m<bf16_t>(p, a, s) : launch_m<float>(p, a, s);
 }
 

@@ -218,7 +218,7 @@ hipError_t launch_m(const Params& p, const FwdArgs& a, hipStream_t s) {
 // One-row input, window of at least 8 taps without dilation, stride 1, 2, 4 or 8, full-window modes, fp32,
 // and few enough input channels that the input span and the kernels of a workgroup fit its LDS.
 bool forward_row_supported(const Params& p, int dtype) {
-  if (dtype != TCONV_F32 || p.mode > TCONV_PARALLEL) return false;
+  if (dtype != TCONV_F32 || p.mode > TCONV_PARALLEL || p.pad_zero) return false;
   if (p.H != 1 || p.KH != 1 || p.ph != 0 || p.dw != 1 || p.KW < RT_CH) return false;
   if (p.sw != 1 && p.sw != 2 && p.sw != 4 && p.sw != 8) return false;
   if ((chunks_of(p) * RT_CH - 1) / p.sw > RT_M - RT_BL - 1) return false;  // the last lane's window ends inside its LDS row

@@ -46,7 +46,7 @@ struct Epilogue {
   const void* residual;
 };
 
-// kernel flag: keep the hardware's round-robin workgroup order instead of contiguous runs per XCD
+// kernel flag: keep the hardware's workgroup order (tuning builds only)
 constexpr int FLAG_ROUND_ROBIN = 32;
 
 // 9 x values of pixel q for the 3x3 taps of one channel: rows[3*ch + i][q*S + j*D]
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, Epilogue ep, int segs,
-    int n_units, int n_groups, int wrps, int flags, int n_blocks) {
+    int n_units, int n_groups, int wrps, int flags, int n_ublocks, int xsplit) {
   // the mixed layers run as one branch: (iii) through the min-side kernel, accumulators and outputs
   // (its operator is min-plus), (vi) through the max side; only the start value and the block differ
   constexpr bool DO_MIN = mode_has_min(MODE), DO_MAX = mode_has_max(MODE);
@@ -76,16 +76,31 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The workgroups of one pixel
-  // block (same input lines, different output-channel groups) are numbered consecutively; give every XCD a
-  // contiguous run of numbers, so that they meet in one L2 instead of fetching the lines once per XCD.
-  const int per_xcd = (n_blocks + 7) >> 3;
-  const int bid = (flags & FLAG_ROUND_ROBIN) ? (int)blockIdx.x : (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3);
-  if (bid >= n_blocks) return;  // padding of the grid to a multiple of 8; the kernel has no barrier
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: XCD = blockIdx & 7.  A workgroup is a
+  // (pixel block, output-channel block) pair; the workgroups of one pixel block read the same input lines, those of
+  // one channel block the same kernel rows.  The XCDs split the work two ways: xsplit (1, 2, 4 or 8) parts of the
+  // channel blocks times 8 / xsplit parts of the pixel blocks, so that an XCD's share of the kernel tensors stays
+  // within reach of its L2 while every input line is fetched by xsplit XCDs instead of all eight.  Inside an XCD the
+  // channel blocks of a pixel block are numbered consecutively.
   const int gblocks = (n_groups + WAVES - 1) / WAVES;
-  const int ublock = bid / gblocks;
+  int ublock, gblock;
+  if (flags & FLAG_ROUND_ROBIN) {
+    if ((int)blockIdx.x >= n_ublocks * gblocks) return;
+    ublock = (int)blockIdx.x / gblocks;
+    gblock = (int)blockIdx.x - ublock * gblocks;
+  } else {
+    const int xcd = (int)(blockIdx.x & 7u), j = (int)(blockIdx.x >> 3);
+    const int gb_per = (gblocks + xsplit - 1) / xsplit;
+    const int pparts = 8 / xsplit;
+    const int ub_per = (n_ublocks + pparts - 1) / pparts;
+    const int lu = j / gb_per, lg = j - lu * gb_per;
+    ublock = (xcd / xsplit) * ub_per + lu;
+    gblock = (xcd & (xsplit - 1)) * gb_per + lg;
+    // padding of the grid (whole workgroups leave; the kernel has no barrier)
+    if (lu >= ub_per || ublock >= n_ublocks || gblock >= gblocks) return;
+  }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int group = (bid - ublock * gblocks) * WAVES + wave;
+  const int group = gblock * WAVES + wave;
   if (group >= n_groups) return;  // whole wave leaves; the kernel has no barrier
   const int co0 = group * TN;
   const int lane = threadIdx.x & 63;
@@ -539,18 +554,26 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
     if ((long long)r * KS <= 3072) { wrps = r; break; }
   if (dbg & 16) wrps = 0;
   const size_t lds = (size_t)WAVES * wrps * KS * sizeof(float);
-  // Renumbering the workgroups per XCD (see the kernel) trades input locality for kernel locality: an XCD then
-  // walks every output-channel group and its scalar loads touch the whole kernel tensor, where the round-robin
-  // order leaves each XCD one eighth of the groups.  Measured: +4 to +9 % (and 6 to 20 times fewer bytes
-  // fetched) while the kernels are small next to an L2 (0.15 - 0.6 MB), -4 % to +1 % at 2.4 MB, -5 % at 4.7 MB;
-  // beyond 2 MB the round-robin order stays.
+  // How the 8 XCDs split the work (see the kernel): more channel parts keep an XCD's share of the kernel tensors
+  // small (its scalar loads stay in its L2), fewer keep the input lines from being fetched by every XCD.  Measured
+  // with one part (every XCD walks all channel blocks): +4 to +9 % and 6 to 20 times fewer bytes fetched while the
+  // kernels are small next to an L2 (0.15 - 0.6 MB), -4 % to +1 % at 2.4 MB, -5 % at 4.7 MB; so the kernel tensors
+  // are cut into parts of at most 1.5 MB.  TCONV_FWD_XSPLIT=1|2|4|8 fixes the number of parts (tuning aid).
   const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * NT;
-  const int flags = dbg | (w_bytes > 2LL * 1024 * 1024 ? FLAG_ROUND_ROBIN : 0);
-  const long long grid = ((blocks + 7) / 8) * 8;
+  int xsplit = 1;
+  while (xsplit < 8 && w_bytes / xsplit > 1536LL * 1024 && 2 * xsplit <= gblocks) xsplit *= 2;
+  if (const char* ex = getenv("TCONV_FWD_XSPLIT")) {
+    const int v = atoi(ex);
+    if ((v == 1 || v == 2 || v == 4 || v == 8) && v <= gblocks) xsplit = v;
+  }
+  const int flags = dbg;
+  const long long gb_per = (gblocks + xsplit - 1) / xsplit, ub_per = (ublocks + 8 / xsplit - 1) / (8 / xsplit);
+  const long long grid = (dbg & FLAG_ROUND_ROBIN) ? blocks : 8 * gb_per * ub_per;
+  if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
   const Epilogue ep = {a.bias, a.scale, a.shift, a.residual};
   hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, PZ, TO>), dim3((unsigned)grid), dim3(WAVES * 64),
                      lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
-                     a.idx_min, a.idx_max, ep, segs, (int)n_units, n_groups, wrps, flags, (int)blocks);
+                     a.idx_min, a.idx_max, ep, segs, (int)n_units, n_groups, wrps, flags, (int)ublocks, xsplit);
   return hipGetLastError();
 }
 
@@ -615,7 +638,7 @@ hipError_t launch_mode(const Params& p, const float* x, const float* w_min, cons
 // horizontal padding at most the dilation (so that the core columns of every lane lie inside the row),
 // at least one full pixel segment per output row, tensors addressable with 32-bit byte offsets.
 bool forward_tiled3x3_supported(const Params& p, int dtype) {
-  (void)dtype;
+  if (dtype == TCONV_F16) return false;  // binary16 arithmetic has kernels of its own
   if (p.KH != 3 || p.KW != 3) return false;
   if (p.sh != p.sw || p.dh != p.dw) return false;
   const bool geo = (p.sh == 1 && (p.dh == 1 || p.dh == 2)) || (p.sh == 2 && p.dh == 1);

@@ -119,6 +119,19 @@ __device__ __forceinline__ void st_f32(bf16_t* p, size_t i, float v) {
   p[i] = (bf16_t)(u >> 16);
 }
 
+// binary16 storage: exact widening, round-to-nearest-even narrowing (v_cvt_f16_f32 under the default rounding mode).
+typedef _Float16 f16_t;
+__device__ __forceinline__ float ld_f32(const f16_t* p, size_t i) { return (float)p[i]; }
+__device__ __forceinline__ void st_f32(f16_t* p, size_t i, float v) { p[i] = (f16_t)v; }
+
+// One candidate: x + w rounded once, in the arithmetic type of the storage type - fp32 for fp32 and bf16 storage,
+// binary16 for binary16 storage (both operands are exactly representable there; the sum is one v_add_f16).
+template <typename T>
+__device__ __forceinline__ float candidate(float x, float w) {
+  if constexpr (sizeof(T) == 2 && !__is_same(T, bf16_t)) return (float)((f16_t)x + (f16_t)w);
+  else return __fadd_rn(x, w);
+}
+
 // alpha*y_min + beta*y_max with each product and the sum rounded separately (no FMA).
 __device__ __forceinline__ float combine(float a, float ymin, float b, float ymax) {
   return __fadd_rn(__fmul_rn(a, ymin), __fmul_rn(b, ymax));

@@ -538,3 +538,61 @@ def run_hip_ext(cfg, inp, ep=None, backward=True, device="cuda:0"):
     torch.cuda.synchronize()
     return {k: (None if v is None else (v.float() if v.dtype == torch.bfloat16 else v).cpu().numpy())
             for k, v in out.items()}
+
+
+# ---------------------------------------------------------------- binary16 arithmetic (dtype f16)
+
+def run_oracle_f16(cfg, inp, backward=True):
+    """The half-precision contract of the extension oracle on inputs rounded to binary16; the backward pass is the
+    fp32-gradient routing of the main oracle (or of the extension oracle under zero padding) on its winners."""
+    from oracle import text_oracle as ext
+    s = ext.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+    h = lambda a: None if a is None else np.asarray(a, np.float32).astype(np.float16)
+    r = ext.forward_f16(s, cfg.mode, h(inp["x"]), h(inp["w_min"]), h(inp["w_max"]), inp["alpha"], inp["beta"],
+                        pad_zero=(cfg.pad_mode == "zero"))
+    for k in ("y", "y_min", "y_max"):
+        if r[k] is not None:
+            r[k] = r[k].astype(np.float32)
+    if backward:
+        kw = dict(idx_min=r["idx_min"], idx_max=r["idx_max"])
+        r.update(ext.backward(s, cfg.mode, inp["gy"], alpha=inp["alpha"], beta=inp["beta"], **kw))
+        ab = {k: (None if inp[k] is None else np.abs(inp[k])) for k in ("alpha", "beta")}
+        sc = ext.backward(s, cfg.mode, np.abs(inp["gy"]), alpha=ab["alpha"], beta=ab["beta"], **kw)
+        for k in ("grad_x", "grad_w_min", "grad_w_max"):
+            r[k + "_scale"] = sc[k]
+    return r
+
+
+def run_hip_f16(cfg, inp, backward=True, device="cuda:0"):
+    import torch
+    dev = torch.device(device)
+    d = tb.Desc.from_cfg(cfg, dtype="f16")
+    ho, wo = tb.tconv_out_shape(d)
+    up16 = lambda a: None if a is None else torch.from_numpy(np.asarray(a, np.float32).astype(np.float16)).to(dev)
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+    x = up16(inp["x"])
+    if cfg.mode == "compound":
+        w_min = w_max = up16(inp["w_min"])
+    else:
+        w_min, w_max = up16(inp["w_min"]), up16(inp["w_max"])
+    alpha, beta, gy = up(inp["alpha"]), up(inp["beta"]), up(inp["gy"])
+    oshape = (cfg.N, cfg.C_out, ho, wo)
+    do_min, do_max = cfg.mode != "max", cfg.mode != "min"
+    nanf = lambda: torch.full(oshape, float("nan"), device=dev, dtype=torch.float16)
+    bad = lambda: torch.full(oshape, -12345, device=dev, dtype=torch.int32)
+    y, y_min, y_max = nanf(), (nanf() if do_min else None), (nanf() if do_max else None)
+    idx_min, idx_max = (bad() if do_min else None), (bad() if do_max else None)
+    ws = scratch(tb.tconv_workspace_bytes(d, "forward"), dev)
+    tb.tconv_forward(d, x, w_min, w_max, alpha, beta, y, y_min, y_max, idx_min, idx_max, ws)
+    out = dict(y=y, y_min=y_min, y_max=y_max, idx_min=idx_min, idx_max=idx_max)
+    if backward:
+        gx = torch.full((cfg.N, cfg.C_in, cfg.H, cfg.W), float("nan"), device=dev)
+        wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
+        gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
+        gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel") else None
+        tb.tconv_backward(d, gy, alpha, beta, idx_min, idx_max, gx, gw_min, gw_max,
+                          scratch(tb.tconv_workspace_bytes(d, "backward"), dev))
+        out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else (v.float() if v.dtype == torch.float16 else v).cpu().numpy())
+            for k, v in out.items()}

@@ -279,6 +279,20 @@ def test_fused_backward_and_atomic_forms(cfg):
             assert np.array_equal(hs.bits(sep["grad_x"]), hs.bits(ato["grad_x"]))
 
 
+@pytest.mark.parametrize("kb", ["3", "20"])
+def test_backward_input_small_lds_budgets(kb):
+    """The input-gradient tile chooser under a small LDS budget (TCONV_BWD_LDS_KB): channel chunks, many tiles per image,
+    ragged last tiles in every dimension, and tiles with more scanned pixels than threads."""
+    os.environ["TCONV_BWD_LDS_KB"] = kb
+    try:
+        for cfg in (RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[20], LayerCfg("r_wide", 1, 3, 40, 130, 4, seed=51)):
+            for mode in ("compound", "max"):
+                _check(cfg.with_(mode=mode), alpha_beta="random" if mode == "compound" else None)
+            _check(cfg.with_(mode="parallel"), integer=True)
+    finally:
+        os.environ.pop("TCONV_BWD_LDS_KB", None)
+
+
 def test_workspace_errors():
     import torch
     cfg = RAGGED[0].with_(mode="parallel")
