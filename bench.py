@@ -48,7 +48,8 @@ MEASURED_FORWARD_TRAFFIC = {
 
 # The layers the forward bar is stated on (large 3 x 3 layers), the HBM-judged stem, and the bf16-storage variant.
 BAR_LAYERS = [("cfg2_main", None), ("cfg2_stem", None), ("cfg3a", None), ("cfg3b", None), ("cfg3c", None),
-              ("cfg4a", None), ("cfg4b", None), ("cfg4a", "bf16")]
+              ("cfg4a", None), ("cfg4b", None), ("cfg4a", "bf16"), ("cfg4b", "bf16"),
+              ("cfg2_main", "f16"), ("cfg3a", "f16"), ("cfg4a", "f16"), ("cfg4b", "f16")]
 ROTATE_BYTES = 600e6   # backward calls are timed on rotating operand sets larger than the 256 MB last-level cache
 
 
@@ -78,7 +79,9 @@ def main() -> int:
     ap.add_argument("--mode", default=None,
                     choices=["max", "min", "compound", "parallel", "minplus_max", "maxplus_min"],
                     help="run the workload's shape as another layer of the family (default: the configuration's own)")
-    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"], help="storage type of x, kernels and outputs")
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16", "f16"],
+                    help="f32; bf16: storage type of x, kernels and outputs, fp32 arithmetic; f16: binary16 storage AND "
+                         "arithmetic (the packed 16-bit vector path, its own numeric contract)")
     ap.add_argument("--no-graph", action="store_true",
                     help="multi-layer workloads (cfg5): launch every step eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-layers", action="store_true",
@@ -110,6 +113,8 @@ def main() -> int:
     if args.op == "3d":
         return bench_3d(args, torch, tb)
     from paper_2504_06881_amd.inputs import resnet20_layers
+    if args.workload == "cfg5net":
+        return bench_net(args, torch, tb)
     if args.workload == "cfg5":
         # the 19 tropical conv layers of a ResNet-20-style net on [256, 3, 32, 32] (the end-to-end configuration);
         # the batch-norm / residual glue of the net is not part of the hot path and is not run
@@ -136,7 +141,7 @@ def main() -> int:
             self.inp = inp = make_inputs(cfg)
             self.d = d = tb.Desc.from_cfg(cfg)
             ho, wo = tb.tconv_out_shape(d)
-            tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+            tdt = {"bf16": torch.bfloat16, "f16": torch.float16}.get(cfg.dtype, torch.float32)
 
             def up(a, dt=torch.float32):
                 return None if a is None else torch.from_numpy(a).to(dev).to(dt).contiguous()
@@ -339,6 +344,8 @@ def main() -> int:
     # plain-form lane operations of the forward pass (2 per pair; compound 1.5) against the VALU issue rate
     lane_ops = sum(L.cfg.pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(L.cfg.mode)) for L in layers)
     achieved = lane_ops / (t_f * 1e-3)
+    # binary16 arithmetic: a packed instruction does two lane-operations, so the vector peak is twice the fp32 one
+    peak_ops = LANE_OPS_PER_S * (2 if all(L.cfg.dtype == "f16" for L in layers) else 1)
     bytes_bi = sum(L.bytes_bi for L in layers)
     bytes_bw = sum(L.bytes_bw for L in layers)
     dtypes = {L.cfg.dtype for L in layers}
@@ -357,8 +364,9 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",   # the arithmetic type: every add and compare is fp32, whatever the storage type
-        "storage": "f32" if dtypes == {"f32"} else "bf16",
+        # the arithmetic type: every add and compare is fp32 whatever the storage type, except the binary16 layers
+        "dtype": "f16" if dtypes == {"f16"} else "f32",
+        "storage": "f32" if dtypes == {"f32"} else ("f16" if dtypes == {"f16"} else "bf16"),
         "data": "synthetic",
         "config": {"workload": wl_name + ", forward + backward (grad_x and grad_w, "
                                + ("two calls" if args.separate_backward or args.op == "sum" else "one call") + ")"
@@ -376,8 +384,8 @@ def main() -> int:
         # frac_best prices the same work at one packed add + one 3-operand compare per two pairs
         "roofline": {"bound": "alu", "kernel": "forward",
                      "achieved": round(achieved / 1e12, 3),
-                     "peak": round(LANE_OPS_PER_S / 1e12, 3), "unit": "Tlane-op/s",
-                     "frac": round(achieved / LANE_OPS_PER_S, 4), "frac_best": round(achieved / LANE_OPS_PER_S / 2, 4),
+                     "peak": round(peak_ops / 1e12, 3), "unit": "Tlane-op/s",
+                     "frac": round(achieved / peak_ops, 4), "frac_best": round(achieved / peak_ops / 2, 4),
                      "traffic": traffic[0] if traffic else None,
                      "traffic_source": traffic[1] if traffic else None},
     }
@@ -414,13 +422,14 @@ def main() -> int:
             torch.cuda.synchronize()
             t = time_loop(lambda i: L.fwd(i % len(L.sets)), 10)
             ops = cfg.pairs * (LANE_OPS_PER_S / alu_peak_pairs_per_s(cfg.mode))
+            lpeak = LANE_OPS_PER_S * (2 if cfg.dtype == "f16" else 1)   # packed 16-bit instructions: two per lane
             x_bytes = L.x.numel() * L.x.element_size()
             out_bytes = L.n_out * (L.y.element_size() * (1 + cfg.branches) + 4 * cfg.branches)
             table.append({
                 "layer": name, "mode": cfg.mode, "storage": cfg.dtype, "pairs": cfg.pairs,
                 "forward_kernel": tb.tconv_forward_kernel_name(L.d),
                 "ms_forward": round(t, 4), "forward_gops": round(cfg.pairs / (t * 1e-3) / 1e9, 1),
-                "frac": round(ops / (t * 1e-3) / LANE_OPS_PER_S, 4),
+                "frac": round(ops / (t * 1e-3) / lpeak, 4),
                 "forward_hbm_gbs": round((x_bytes + out_bytes) / (t * 1e-3) / 1e9, 1),
                 "ms_backward_input": round(c_bi, 4), "backward_input_gbs": round(L.bytes_bi / (c_bi * 1e-3) / 1e9, 1),
                 "ms_backward_weight": round(c_bw, 4), "backward_weight_gbs": round(L.bytes_bw / (c_bw * 1e-3) / 1e9, 1),
@@ -456,6 +465,200 @@ def main() -> int:
                       "frac": round(p5 * 2.0 / (t_f5 * 1e-3) / LANE_OPS_PER_S, 4),
                       "ms_step": round(t_s5, 4), "step_gops": round(p5 / (t_s5 * 1e-3) / 1e9, 1)})
         out["layers"] = table
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_net(args, torch, tb) -> int:
+    """--workload cfg5net: ONE end-to-end training step of the all-tropical ResNet-20-style net (Sec. 5 TCNN BasicBlock:
+    TropConv -> BN -> TropConv -> BN -> + shortcut, no ReLU), [256, 3, 32, 32] synthetic images, every conv in parallel
+    mode.  Forward: 19 tconv_forward_fused calls chained layer to layer (batch norm folded to a per-channel scale and
+    shift, the shortcut added in the kernel that writes y), global average pool, a 10-way linear head and a squared
+    loss.  Backward: through the head, then per layer tconv_backward (gradient of the input and of both kernel tensors;
+    the batch-norm scale enters as the branch coefficients), tconv_backward_bias (shift) and
+    tconv_backward_alpha_beta (scale).  Pool, head, loss, the shortcut's subsampling / channel padding and the
+    gradient adds at the shortcuts are torch glue: inside the timed step, outside the pair count."""
+    from paper_2504_06881_amd.inputs import resnet20_layers, make_inputs
+    dev = torch.device("cuda:0")
+    cfgs = resnet20_layers(256)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4)
+    f32 = torch.float32
+
+    class L:
+        pass
+
+    layers = []
+    for cfg in cfgs:
+        o = L()
+        o.cfg, o.d = cfg, tb.Desc.from_cfg(cfg)
+        inp = make_inputs(cfg)
+        o.w_min = torch.from_numpy(inp["w_min"]).to(dev)
+        o.w_max = torch.from_numpy(inp["w_max"]).to(dev)
+        ho, wo = tb.tconv_out_shape(o.d)
+        osh = (cfg.N, cfg.C_out, ho, wo)
+        o.scale = (0.2 + 0.2 * torch.rand(cfg.C_out, generator=g)).to(dev)   # a branch sum doubles the scale of x
+        o.shift = (0.2 * torch.rand(cfg.C_out, generator=g) - 0.1).to(dev)
+        o.y = torch.empty(osh, device=dev)
+        o.y_min, o.y_max = torch.empty(osh, device=dev), torch.empty(osh, device=dev)
+        o.idx_min = torch.empty(osh, device=dev, dtype=torch.int32)
+        o.idx_max = torch.empty(osh, device=dev, dtype=torch.int32)
+        o.gx = torch.empty((cfg.N, cfg.C_in, cfg.H, cfg.W), device=dev)
+        o.gw_min, o.gw_max = torch.empty_like(o.w_min), torch.empty_like(o.w_max)
+        o.gshift, o.ga, o.gb = (torch.empty(cfg.C_out, device=dev) for _ in range(3))
+        o.gscale = torch.empty(cfg.C_out, device=dev)
+        nb = max(tb.tconv_workspace_bytes(o.d, k) for k in ("backward", "backward_bias", "backward_alpha_beta",
+                                                            "backward_weight"))
+        o.ws = torch.empty(max(nb // 8, 1), device=dev, dtype=torch.float64)
+        layers.append(o)
+    x0 = torch.from_numpy(make_inputs(cfgs[0])["x"]).to(dev)
+    n_cls = 10
+    w_fc = ((torch.rand(n_cls, 64, generator=g) - 0.5) * 0.2).to(dev)
+    b_fc = torch.zeros(n_cls, device=dev)
+    target = torch.randn(256, n_cls, generator=g).to(dev)
+    # blocks: (first conv, second conv) pairs after the stem; the shortcut of a block whose first conv has stride 2
+    # takes every second pixel and pads the new channels with zeros
+    blocks = [(layers[1 + 2 * b], layers[2 + 2 * b]) for b in range(9)]
+    for a, b in blocks:
+        a.sc = torch.zeros_like(b.y) if a.cfg.stride == 2 else None   # the padded channels stay zero
+        a.gsc = torch.zeros_like(a.gx) if a.cfg.stride == 2 else None  # the skipped pixels stay zero
+    head = L()
+
+    def conv(o, x, residual):
+        tb.tconv_forward_fused(o.d, x, o.w_min, o.w_max, None, None, o.y, o.y_min, o.y_max, o.idx_min, o.idx_max,
+                               scale=o.scale, shift=o.shift, residual=residual)
+
+    def forward():
+        conv(layers[0], x0, None)
+        x = layers[0].y
+        for a, b in blocks:
+            if a.sc is not None:
+                a.sc[:, :a.cfg.C_in].copy_(x[:, :, ::2, ::2])
+            conv(a, x, None)
+            conv(b, a.y, a.sc if a.sc is not None else x)
+            x = b.y
+        return x
+
+    def head_step(x):
+        pooled = x.mean(dim=(2, 3))
+        logits = torch.addmm(b_fc, pooled, w_fc.t())
+        diff = logits - target
+        head.loss = (diff * diff).mean()
+        dlogits = diff * (2.0 / diff.numel())
+        head.gw = dlogits.t() @ pooled
+        head.gb = dlogits.sum(0)
+        dpool = dlogits @ w_fc
+        head.g = (dpool * (1.0 / (x.shape[2] * x.shape[3])))[:, :, None, None].expand_as(x).contiguous()
+
+    def conv_backward(o, gy, need_gx=True):
+        if need_gx:
+            tb.tconv_backward(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.gx, o.gw_min, o.gw_max, o.ws)
+        else:
+            tb.tconv_backward_weight(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.gw_min, o.gw_max, o.ws)
+        tb.tconv_backward_bias(o.d, gy, o.gshift, o.ws)
+        tb.tconv_backward_alpha_beta(o.d, gy, o.y_min, o.y_max, o.ga, o.gb, o.ws)
+        torch.add(o.ga, o.gb, out=o.gscale)
+
+    def backward():
+        gy = head.g
+        for a, b in reversed(blocks):
+            conv_backward(b, gy)
+            conv_backward(a, b.gx)
+            if a.gsc is not None:
+                a.gsc[:, :, ::2, ::2].copy_(gy[:, :a.cfg.C_in])
+                a.gx.add_(a.gsc)
+            else:
+                a.gx.add_(gy)
+            gy = a.gx
+        conv_backward(layers[0], gy, need_gx=False)
+
+    def step_eager():
+        head_step(forward())
+        backward()
+
+    def checksum():
+        return [float(head.loss), float(layers[0].gw_min.double().abs().sum()), float(layers[5].gscale.double().sum()),
+                float(layers[18].gw_max.double().abs().sum()), float(blocks[3][0].gx.double().abs().sum())]
+
+    for _ in range(max(args.warmup, 2)):
+        step_eager()
+    torch.cuda.synchronize()
+    ref = checksum()
+    g_f = g_b = None
+    graph_ok = False
+    if not args.no_graph:
+        # the forward and backward chains of library launches (and the elementwise glue between them) replay from HIP
+        # graphs; the head (a reduction and three small matrix products) stays eager between the two
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_eager()
+        torch.cuda.current_stream().wait_stream(side)
+        g_f, g_b = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_f):
+            xo = forward()
+        head_step(xo)
+        with torch.cuda.graph(g_b):
+            backward()
+        graph_ok = True
+        for _ in range(3):   # replays against the eager step, with eager work in between
+            g_f.replay(); head_step(xo); g_b.replay()
+            torch.cuda.synchronize()
+            got = checksum()
+            if any(abs(a - b) > 1e-6 * max(1.0, abs(b)) for a, b in zip(got, ref)):
+                graph_ok = False
+            step_eager()
+            torch.cuda.synchronize()
+
+    def step():
+        if graph_ok:
+            g_f.replay(); head_step(xo); g_b.replay()
+        else:
+            step_eager()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def timed(fn, reps=10):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_f = timed(g_f.replay if graph_ok else forward)
+    t_b = timed(g_b.replay if graph_ok else backward)
+    pairs = sum(c.pairs for c in cfgs)
+    achieved = pairs * 2.0 / (t_f * 1e-3)
+    out = {
+        "metric": "tropical-conv GOPS (add+max pairs/s), forward + backward step",
+        "value": round(pairs / (ms_step * 1e-3) / 1e9, 2), "unit": "GOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "storage": "f32", "data": "synthetic",
+        "config": {"workload": "cfg5net: one training step of the all-tropical ResNet-20-style net on x[256,3,32,32], "
+                               "19 parallel-mode 3x3 layers with fused batch-norm scale/shift and shortcut, pool + "
+                               "linear head + squared loss, all gradients; glue inside the time, outside the pair count"
+                               + (", forward and backward chains replayed from HIP graphs" if graph_ok else ", eager"),
+                   "pairs_per_step": pairs, "graph_replays_checked_against_eager": graph_ok},
+        "ms_forward": round(t_f, 4), "ms_backward": round(t_b, 4),
+        "forward_gops": round(pairs / (t_f * 1e-3) / 1e9, 2),
+        "loss": ref[0],
+        "roofline": {"bound": "alu", "kernel": "forward chain (19 fused layers and the shortcut copies)",
+                     "achieved": round(achieved / 1e12, 3), "peak": round(LANE_OPS_PER_S / 1e12, 3),
+                     "unit": "Tlane-op/s", "frac": round(achieved / LANE_OPS_PER_S, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline([(c, make_inputs(c)) for c in cfgs], args.cpu_seconds, "full",
+                                           [(None, None)] * len(cfgs))
+        out["cpu_baseline"]["sample"] += " (the 19 layers' forward and backward calls; no glue)"
     print(json.dumps(out), flush=True)
     return 0
 

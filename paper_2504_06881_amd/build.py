@@ -23,13 +23,19 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build_library(verbose: bool = False, save_temps: bool = False) -> str:
-    """Compile every csrc/*.hip and link libtconv.so.  Always recompiles."""
+def build_library(verbose: bool = False, save_temps: bool = False, incremental: bool = False) -> str:
+    """Compile every csrc/*.hip and link libtconv.so.  Recompiles everything unless incremental is set (then only
+    sources newer than their object, or all of them when a header is newer)."""
     os.makedirs(OBJ, exist_ok=True)
     objs = []
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    hdrs += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    hdr_time = max(os.path.getmtime(h) for h in hdrs)
 
     def cc(src):
         obj = os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), hdr_time):
+            return obj
         cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]
         if save_temps:
             cmd += ["-save-temps=obj"]
@@ -49,4 +55,4 @@ def build_library(verbose: bool = False, save_temps: bool = False) -> str:
 
 if __name__ == "__main__":
     import sys
-    print(build_library(verbose=True, save_temps="--save-temps" in sys.argv))
+    print(build_library(verbose=True, save_temps="--save-temps" in sys.argv, incremental="--incremental" in sys.argv))

@@ -64,6 +64,8 @@ void own_status() { (void)hipGetLastError(); }
 
 bool use_tiled(const Params& p, int dtype) { return forward_tiled3x3_supported(p, dtype) && !generic_forced(); }
 
+bool use_tiled16(const Params& p, int dtype) { return forward_tiled3x3_f16_supported(p, dtype) && !generic_forced(); }
+
 bool use_row(const Params& p, int dtype) {
   return !use_tiled(p, dtype) && forward_row_supported(p, dtype) && !generic_forced();
 }
@@ -91,6 +93,8 @@ int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   if (op == TCONV_OP_BACKWARD_BIAS) *bytes = backward_alpha_beta_workspace(p);  // the same slices, two sums each
   // forward: only the tiled kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
   if (op == TCONV_OP_FORWARD && use_tiled(p, desc->dtype)) *bytes = forward_tiled3x3_workspace(p, desc->dtype);
+  // the binary16 tiled kernel: the kernel tensors re-laid in output-channel pairs
+  if (op == TCONV_OP_FORWARD && use_tiled16(p, desc->dtype)) *bytes = forward_tiled3x3_f16_workspace(p);
   // the deterministic forms of the parameter gradients: fp64 partial sums per batch slice
   if (op == TCONV_OP_BACKWARD_WEIGHT || op == TCONV_OP_BACKWARD) {
     p.mode = backward_mode(p.mode);
@@ -139,6 +143,11 @@ int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min
       return TCONV_E_WORKSPACE;
     own_status();
     e = launch_forward_tiled3x3(p, desc->dtype, a, workspace, s);
+  } else if (use_tiled16(p, desc->dtype)) {
+    const size_t need = forward_tiled3x3_f16_workspace(p);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return TCONV_E_WORKSPACE;
+    own_status();
+    e = launch_forward_tiled3x3_f16(p, a, workspace, s);
   } else if (use_row(p, desc->dtype) && !a.bias && !a.scale && !a.residual) {  // the row kernel has no epilogue
     own_status();
     e = launch_forward_row(p, a, s);
@@ -599,6 +608,7 @@ const char* tconv_status_string(int status) {
 const char* tconv_forward_kernel_name(const tconv_desc* desc) {
   Params p;
   if (make_params(desc, &p) != TCONV_OK) return nullptr;
+  if (use_tiled16(p, desc->dtype)) return "tiled3x3_f16";
   return use_tiled(p, desc->dtype) ? "tiled3x3" : (use_row(p, desc->dtype) ? "row1d" : "generic");
 }
 

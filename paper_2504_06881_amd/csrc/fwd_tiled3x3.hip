@@ -61,9 +61,11 @@ __device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][
 // TN: output channels per lane (4; 2 for layers too small to fill the chip with 4)
 // PZ: zero padding (App. A.1.1: the unfold formulation pads with zeros): an out-of-image value is +0 instead of NaN,
 //     so its tap competes like any other; one AND per loaded value where the identity padding has one OR
-template <int MODE, int S, int D, int TN, bool PZ, typename TO>
+// XA (bf16 storage at stride 1 only): every lane's core columns start at an even element of x, so they are read as
+//     whole dwords holding two values each; otherwise bf16 values are read one by one
+template <int MODE, int S, int D, int TN, bool PZ, typename TO, bool XA>
 __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
-    Params p, const float* __restrict__ x, const float* __restrict__ w_min,
+    Params p, const TO* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha,
     const float* __restrict__ beta, TO* __restrict__ y, TO* __restrict__ y_min,
     TO* __restrict__ y_max, int32_t* __restrict__ idx_min, int32_t* __restrict__ idx_max, Epilogue ep, int segs,
@@ -74,6 +76,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   constexpr int PX = (S == 1) ? 8 : 4;          // output pixels per lane
   constexpr int NC = (PX - 1) * S + 1;          // core columns [D, D+NC): always inside the row
   constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
+  constexpr bool PK = XA && sizeof(TO) == 2 && S == 1;  // core columns arrive two per dword
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: XCD = blockIdx & 7.  A workgroup is a
@@ -119,7 +122,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   // ---- channel-independent addressing and padding masks
   const int iw0 = ow0 * S - p.pw;  // input column of register column 0
   const size_t HW = (size_t)p.H * p.W;
-  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
+  // x is read in its storage type TO: fp32, or bf16 whose 16 bits are the upper half of the fp32 value (the widening
+  // shift is fused with the padding mask, see mask_cols)
+  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(TO)));
   unsigned roff[3];  // byte offset of the first core column (iw0 + D >= 0) of each (clamped) row
   unsigned mrow[3];  // identity padding: all-ones where the row is padding; zero padding: all-ones where it is NOT
   int ihc[3];        // clamped input rows of the three kernel rows
@@ -128,7 +133,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const int ih = oh * S - p.ph + i * D;
     mrow[i] = ((ih >= 0 && ih < p.H) != PZ) ? 0u : 0xffffffffu;
     ihc[i] = min(max(ih, 0), p.H - 1);
-    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc[i] * p.W + (size_t)(iw0 + D)) * sizeof(float));
+    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc[i] * p.W + (size_t)(iw0 + D)) * sizeof(TO));
   }
   int hoff[2 * D];         // clamped byte offsets of the halo columns relative to roff
   unsigned mhalo[2 * D];   // the same two conventions for the halo columns
@@ -137,7 +142,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
     const int o = (h < D) ? h : h + NC;
     const int iw = iw0 + o;
     mhalo[h] = ((iw >= 0 && iw < p.W) != PZ) ? 0u : 0xffffffffu;
-    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
+    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(TO);
   }
 
   // ---- kernel rows of this wave's output channels (wave-uniform)
@@ -170,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
 #endif
 
   auto chan_soff = [&](int c) -> unsigned {  // wave-uniform byte offset of channel c (clamped)
-    return (unsigned)((size_t)min(c, p.C_in - 1) * HW * sizeof(float));
+    return (unsigned)((size_t)min(c, p.C_in - 1) * HW * sizeof(TO));
   };
   // loads of columns [lo, hi) of all six rows of channel pair du; lo / hi fall on the boundaries
   // {0, D, D+4, D+NC, XR} so that every piece is a halo single or a run of the core
@@ -181,34 +186,57 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       const unsigned ro = roff[sl % 3];
       if (lo == 0) {
 #pragma unroll
-        for (int h = 0; h < D; ++h) xs[sl][h] = load_one<float>(xres, ro + (unsigned)hoff[h], soff);
+        for (int h = 0; h < D; ++h) xs[sl][h] = load_raw_one<TO>(xres, ro + (unsigned)hoff[h], soff);
       }
-      if (lo <= D && hi >= D + NC) {
-        load_run<NC, float>(&xs[sl][D], xres, ro, soff);
+      if constexpr (PK) {
+        // dwords of two values: columns D .. D+3 land in slots D, D+1 and columns D+4 .. D+7 in slots D+4, D+5;
+        // mask_cols spreads them over the slots of their columns
+        if (lo <= D) load_run<2, float>(&xs[sl][D], xres, ro, soff);
+        if (hi >= D + NC) load_run<2, float>(&xs[sl][D + 4], xres, ro + 8u, soff);
+      } else if (lo <= D && hi >= D + NC) {
+        load_raw_run<NC, TO>(&xs[sl][D], xres, ro, soff);
       } else if (lo <= D) {
-        load_run<4, float>(&xs[sl][D], xres, ro, soff);                    // first 4 core columns
+        load_raw_run<4, TO>(&xs[sl][D], xres, ro, soff);                                      // first 4 core columns
       } else {
-        load_run<NC - 4, float>(&xs[sl][D + 4], xres, ro + 16u, soff);      // the rest of the core
+        load_raw_run<NC - 4, TO>(&xs[sl][D + 4], xres, ro + 4u * (unsigned)sizeof(TO), soff);  // the rest of the core
       }
       if (hi == XR) {
 #pragma unroll
-        for (int h = 0; h < D; ++h) xs[sl][D + NC + h] = load_one<float>(xres, ro + (unsigned)hoff[D + h], soff);
+        for (int h = 0; h < D; ++h) xs[sl][D + NC + h] = load_raw_one<TO>(xres, ro + (unsigned)hoff[D + h], soff);
       }
     }
   };
-  // padding -> NaN (identity) or +0 (zero padding), columns [lo, hi); the virtual channel of an odd C_in -> NaN always
+  // padding -> NaN (identity) or +0 (zero padding), columns [lo, hi); the virtual channel of an odd C_in -> NaN always.
+  // bf16 storage: a slot holds the 16 loaded bits until here; the widening shift and the mask are ONE instruction
+  // ((v << 16) | m), so that bf16 rows cost the main loop no more than fp32 rows and half the bytes.
   auto mask_cols = [&](float (&xs)[6][XR], int lo, int hi, unsigned mB) {
 #pragma unroll
     for (int sl = 0; sl < 6; ++sl) {
       const unsigned vB = sl >= 3 ? mB : 0u;
       const unsigned mr = PZ ? mrow[sl % 3] : (mrow[sl % 3] | vB);
+      if constexpr (PK) {
+        // both dwords of a half are read before any slot of the half is written
+        unsigned pk[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) pk[h] = __float_as_uint(xs[sl][D + (h & 1) + (h >> 1) * 4]);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          if (D + 2 * h < lo || D + 2 * h >= hi) continue;
+          const unsigned v0 = pk[h] << 16, v1 = pk[h] & 0xffff0000u;
+          xs[sl][D + 2 * h] = __uint_as_float(PZ ? ((v0 & mr) | vB) : (v0 | mr));
+          xs[sl][D + 2 * h + 1] = __uint_as_float(PZ ? ((v1 & mr) | vB) : (v1 | mr));
+        }
+      }
 #pragma unroll
       for (int o = 0; o < XR; ++o) {
         if (o < lo || o >= hi) continue;
+        if (PK && o >= D && o < D + NC) continue;
         unsigned m = mr;
         if (o < D) m = PZ ? (m & mhalo[o]) : (m | mhalo[o]);
         if (o >= D + NC) m = PZ ? (m & mhalo[o - NC]) : (m | mhalo[o - NC]);
-        xs[sl][o] = PZ ? __uint_as_float((__float_as_uint(xs[sl][o]) & m) | vB) : nan_or(xs[sl][o], m);
+        const unsigned raw = __float_as_uint(xs[sl][o]);
+        const unsigned val = sizeof(TO) == 2 ? raw << 16 : raw;
+        xs[sl][o] = __uint_as_float(PZ ? ((val & m) | vB) : (val | m));
       }
     }
   };
@@ -412,7 +440,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
 #pragma unroll
       for (int i = 0; i < 3; ++i) {
         const size_t rbase = xn_off + (size_t)cs * HW + (size_t)ihc[i] * p.W;
-        load_run<L, float>(run[u][i], xres, (unsigned)((rbase + start) * sizeof(float)), 0u);
+        load_run<L, TO>(run[u][i], xres, (unsigned)((rbase + start) * sizeof(TO)), 0u);
       }
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the batch ahead of every use
@@ -510,7 +538,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   }
 }
 
-// bf16 storage is widened to fp32 once, into the workspace, so that the main kernel always reads fp32
+// bf16 kernel tensors are widened to fp32 once, into the workspace
 __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restrict__ src,
                                                           float* __restrict__ dst, size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -526,8 +554,8 @@ void widen(const void* src, float* dst, size_t n, hipStream_t s) {
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-template <int MODE, int S, int D, int TN, bool PZ, typename TO>
-hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const float* w_max,
+template <int MODE, int S, int D, int TN, bool PZ, typename TO, bool XA = false>
+hipError_t launch_tn(const Params& p, const void* x, const float* w_min, const float* w_max,
                      const FwdArgs& a, hipStream_t s) {
   constexpr int PX = (S == 1) ? 8 : 4;
   const int segs = (p.Wo + PX - 1) / PX;
@@ -571,8 +599,8 @@ hipError_t launch_tn(const Params& p, const float* x, const float* w_min, const 
   const long long grid = (dbg & FLAG_ROUND_ROBIN) ? blocks : 8 * gb_per * ub_per;
   if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
   const Epilogue ep = {a.bias, a.scale, a.shift, a.residual};
-  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, PZ, TO>), dim3((unsigned)grid), dim3(WAVES * 64),
-                     lds, s, p, x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
+  hipLaunchKernelGGL((fwd_tiled3x3_kernel<MODE, S, D, TN, PZ, TO, XA>), dim3((unsigned)grid), dim3(WAVES * 64),
+                     lds, s, p, (const TO*)x, w_min, w_max, a.alpha, a.beta, (TO*)a.y, (TO*)a.y_min, (TO*)a.y_max,
                      a.idx_min, a.idx_max, ep, segs, (int)n_units, n_groups, wrps, flags, (int)ublocks, xsplit);
   return hipGetLastError();
 }
@@ -591,7 +619,7 @@ long long resident_workgroups() {
 }
 
 template <int MODE, int S, int D, typename TO>
-hipError_t launch_one(const Params& p, const float* x, const float* w_min, const float* w_max,
+hipError_t launch_one(const Params& p, const void* x, const float* w_min, const float* w_max,
                       const FwdArgs& a, hipStream_t s) {
   // 4 output channels per lane reuse every loaded input value twice as often as 2, but a layer whose
   // grid leaves half of the wave slots empty runs faster on twice as many, half as long waves
@@ -604,6 +632,17 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
   if (const char* e = getenv("TCONV_FWD_TN")) {  // tuning aid
     if (atoi(e) == 2 || atoi(e) == 4) tn = atoi(e);
   }
+  if constexpr (sizeof(TO) == 2 && S == 1) {
+    // bf16 rows whose core columns start at even elements for every lane: W even (rows, channels and images start
+    // even), an even first output column of every segment (W_out even) and an even left margin D - pad_w
+    if (p.W % 2 == 0 && p.Wo % 2 == 0 && (D - p.pw) % 2 == 0) {
+      if (p.pad_zero)
+        return tn == 2 ? launch_tn<MODE, S, D, 2, true, TO, true>(p, x, w_min, w_max, a, s)
+                       : launch_tn<MODE, S, D, 4, true, TO, true>(p, x, w_min, w_max, a, s);
+      return tn == 2 ? launch_tn<MODE, S, D, 2, false, TO, true>(p, x, w_min, w_max, a, s)
+                     : launch_tn<MODE, S, D, 4, false, TO, true>(p, x, w_min, w_max, a, s);
+    }
+  }
   if (p.pad_zero)
     return tn == 2 ? launch_tn<MODE, S, D, 2, true, TO>(p, x, w_min, w_max, a, s)
                    : launch_tn<MODE, S, D, 4, true, TO>(p, x, w_min, w_max, a, s);
@@ -612,7 +651,7 @@ hipError_t launch_one(const Params& p, const float* x, const float* w_min, const
 }
 
 template <int MODE, typename TO>
-hipError_t launch_geo(const Params& p, const float* x, const float* w_min, const float* w_max,
+hipError_t launch_geo(const Params& p, const void* x, const float* w_min, const float* w_max,
                       const FwdArgs& a, hipStream_t s) {
   if (p.sh == 2) return launch_one<MODE, 2, 1, TO>(p, x, w_min, w_max, a, s);
   return p.dh == 1 ? launch_one<MODE, 1, 1, TO>(p, x, w_min, w_max, a, s)
@@ -620,7 +659,7 @@ hipError_t launch_geo(const Params& p, const float* x, const float* w_min, const
 }
 
 template <typename TO>
-hipError_t launch_mode(const Params& p, const float* x, const float* w_min, const float* w_max,
+hipError_t launch_mode(const Params& p, const void* x, const float* w_min, const float* w_max,
                        const FwdArgs& a, hipStream_t s) {
   switch (p.mode) {
     case TCONV_MAX: return launch_geo<TCONV_MAX, TO>(p, x, w_min, w_max, a, s);
@@ -647,27 +686,26 @@ bool forward_tiled3x3_supported(const Params& p, int dtype) {
   if (p.Wo < (p.sh == 1 ? 8 : 4)) return false;
   if (p.W < 2 * p.dw + 1) return false;  // the epilogue loads 2*dil + 1 consecutive columns of a row
   if (p.C_in > 65535) return false;      // winning channels are parked as 16-bit values
-  if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
+  if ((size_t)p.N * p.C_in * p.H * p.W * (dtype == TCONV_BF16 ? 2 : 4) >= 0xfffff000ull) return false;
   if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
   return true;
 }
 
-// Workspace of the tiled path: only bf16 storage needs one (fp32 copies of x and the kernel tensors).
+// Workspace of the tiled path: only bf16 storage needs one, for fp32 copies of the kernel tensors (scalar loads take
+// whole dwords at dword-aligned addresses; the tensors are small).  x is read as bf16 by the kernel itself.
 size_t forward_tiled3x3_workspace(const Params& p, int dtype) {
   if (dtype != TCONV_BF16) return 0;
-  const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;
-  return align256(nx * 4) + align256(nw * 4) * (p.mode == TCONV_PARALLEL ? 2 : 1);
+  const size_t nw = (size_t)p.C_out * p.K;
+  return align256(nw * 4) * (p.mode == TCONV_PARALLEL ? 2 : 1);
 }
 
 hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, void* workspace,
                                    hipStream_t s) {
   if (dtype != TCONV_BF16)
-    return launch_mode<float>(p, (const float*)a.x, (const float*)a.w_min, (const float*)a.w_max, a, s);
-  const size_t nx = (size_t)p.N * p.C_in * p.H * p.W, nw = (size_t)p.C_out * p.K;
-  float* xf = (float*)workspace;
-  float* wa = (float*)((char*)workspace + align256(nx * 4));
+    return launch_mode<float>(p, a.x, (const float*)a.w_min, (const float*)a.w_max, a, s);
+  const size_t nw = (size_t)p.C_out * p.K;
+  float* wa = (float*)workspace;
   float* wb = (float*)((char*)wa + align256(nw * 4));
-  widen(a.x, xf, nx, s);
   const float* wmin_f = nullptr;
   const float* wmax_f = nullptr;
   if (p.mode == TCONV_PARALLEL) {
@@ -678,7 +716,7 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
     widen(mode_has_max(p.mode) ? a.w_max : a.w_min, wa, nw, s);
     wmin_f = wmax_f = wa;
   }
-  return launch_mode<bf16_t>(p, xf, wmin_f, wmax_f, a, s);
+  return launch_mode<bf16_t>(p, a.x, wmin_f, wmax_f, a, s);
 }
 
 }  // namespace tconv

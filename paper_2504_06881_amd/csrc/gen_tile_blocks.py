@@ -23,6 +23,7 @@ between a VALU write of a lane mask (v_cmp -> VCC / SGPR pair) and the VALU read
 least three other instructions between it and its compare.
 
 Run:  python3 gen_tile_blocks.py > tile_blocks_gfx950.h
+      python3 gen_tile_blocks.py f16 > tile_blocks_f16_gfx950.h   (the binary16 blocks, described at F16_HEADER)
 """
 
 PAIRS = [(0, 1), (2, 3), (4, 5), (6, 7)]
@@ -216,7 +217,100 @@ __device__ __forceinline__ int launder_uniform(int v) {
 __device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
 """
 
+
+# ------------------------------------------------------------------ binary16 blocks (packed VALU)
+
+F16_HEADER = """// GENERATED by gen_tile_blocks.py f16 - do not edit by hand.
+//
+// Inner blocks of the tiled 3x3 forward kernel for binary16 arithmetic on gfx950 (packed 16-bit VALU).
+// Numeric contract: every candidate x + w is ONE add rounded to binary16 (v_pk_add_f16), the reductions compare
+// those binary16 sums (v_pk_max_f16 / v_pk_min_f16 return the non-NaN operand, so the NaN that stands for padding
+// never wins in either branch).
+//
+// The two halves of a register are two OUTPUT CHANNELS of one pixel.  The kernel values of a channel pair sit in
+// SGPRs as (w[co][k], w[co + 1][k]); an x value is broadcast to both halves by the operand-select bits of the
+// packed instruction (op_sel / op_sel_hi pick the half of the x register that holds the tap), so x stays packed as
+// it was loaded: two neighbouring columns per register.
+//
+// A block advances the running extrema of one pixel and one output-channel pair over TWO consecutive input
+// channels (18 taps): 18 packed adds, 18 packed max (and 18 packed min in compound mode, on the same sums:
+// paper Sec. 3.5, closing remark), and per branch 4 instructions that record the input-channel PAIR whenever a
+// half of the extremum changed (xor with the old value, 0/1 per half, 0/0xffff per half, bit-select of the pair
+// number).  The block reads the old extrema from one register and writes the new ones to another, so the caller
+// alternates two register sets and no copy is made.  The exact tap is recovered after the K loop among the 18
+// taps of the recorded pair, in ascending k.
+#pragma once
+
+namespace tconv {
+namespace f16blk {
+
+// x row registers of a lane: D halo columns (one value each, low half), 4 registers with the 8 core columns
+// (two per register), D halo columns.  Element e of the row (0 .. 8 + 2D - 1) -> register and half:
+constexpr int xreg(int D, int e) { return e < D ? e : (e < D + 8 ? D + (e - D) / 2 : D + 4 + (e - D - 8)); }
+constexpr int xhalf(int D, int e) { return (e >= D && e < D + 8) ? ((e - D) & 1) : 0; }
+"""
+
+
+def f16_block(name, branches):
+    """branches: list of (tag, op)"""
+    L = []
+    for t in range(18):
+        s = "sa" if t % 2 == 0 else "sb"
+        L.append(f"v_pk_add_f16 %[{s}], %[x{t}], %[w{t}] op_sel:[%[h{t}],0] op_sel_hi:[%[h{t}],1]")
+        for tag, op in branches:
+            src = f"s{tag}" if t == 0 else f"d{tag}"
+            L.append(f"v_pk_{op}_f16 %[d{tag}], %[{src}], %[{s}]")
+    for tag, _ in branches:
+        L.append(f"v_xor_b32 %[c{tag}], %[d{tag}], %[s{tag}]")
+    for tag, _ in branches:
+        L.append(f"v_pk_min_u16 %[c{tag}], %[c{tag}], %[one2]")
+    for tag, _ in branches:
+        L.append(f"v_pk_sub_u16 %[c{tag}], 0, %[c{tag}]")
+    for tag, _ in branches:
+        L.append(f"v_bfi_b32 %[i{tag}], %[c{tag}], %[tid], %[i{tag}]")
+    outs = ['[sa] "=&v"(sa)', '[sb] "=&v"(sb)']
+    outs += [f'[d{tag}] "=&v"(d{tag})' for tag, _ in branches]
+    outs += [f'[c{tag}] "=&v"(c{tag})' for tag, _ in branches]
+    outs += [f'[i{tag}] "+v"(i{tag})' for tag, _ in branches]
+    ins = [f'[s{tag}] "v"(s{tag})' for tag, _ in branches]
+    ins += [f'[x{t}] "v"(xs[{t // 3}][xreg(D, Q + {t % 3} * D)])' for t in range(18)]
+    ins += [f'[h{t}] "n"(xhalf(D, Q + {t % 3} * D))' for t in range(18)]
+    ins += [f'[w{t}] "s"(w[{t}])' for t in range(18)]
+    ins += ['[tid] "s"(tid)', '[one2] "v"(one2)']
+    params = ", ".join([f"unsigned& d{tag}" for tag, _ in branches] + [f"unsigned s{tag}" for tag, _ in branches] +
+                       [f"unsigned& i{tag}" for tag, _ in branches])
+    decl = ", ".join([f"c{tag}" for tag, _ in branches])
+    n = 18 + 18 * len(branches) + 4 * len(branches)
+    return f"""
+// {n} VALU instructions for 18 taps x 2 output channels x {len(branches)} branch(es).
+// xs: the six x rows of the two input channels; Q: the pixel; w: 18 kernel-value pairs; tid: the pair number in
+// both halves; one2: 0x00010001.
+template <int D, int Q>
+__device__ __forceinline__ void {name}({params}, const unsigned (&xs)[6][4 + 2 * D],
+                                       const unsigned (&w)[18], unsigned tid, unsigned one2) {{
+  unsigned sa, sb, {decl};
+  asm(
+{emit_asm(L)}
+      : {", ".join(outs)}
+      : {", ".join(ins)});
+}}
+"""
+
+
+def gen_f16():
+    out = F16_HEADER
+    out += f16_block("blk_both", [("mx", "max"), ("mn", "min")])
+    out += f16_block("blk_max", [("mx", "max")])
+    out += f16_block("blk_min", [("mn", "min")])
+    out += "\n}  // namespace f16blk\n}  // namespace tconv\n"
+    return out
+
+
 if __name__ == "__main__":
+    import sys
+    if len(sys.argv) > 1 and sys.argv[1] == "f16":
+        print(gen_f16(), end="")
+        sys.exit(0)
     out = HEADER + gen_both() + gen_one2("blk_max2", "max", "gt") + gen_one2("blk_min2", "min", "lt")
     out += gen_mixed2("blk_minmax2", "min", "max", "gt") + gen_mixed2("blk_maxmin2", "max", "min", "lt")
     out += "\n}  // namespace tconv\n"

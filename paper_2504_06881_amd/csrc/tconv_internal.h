@@ -152,6 +152,10 @@ bool forward_tiled3x3_supported(const Params& p, int dtype);
 size_t forward_tiled3x3_workspace(const Params& p, int dtype);  // bytes of device scratch it needs
 hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a, void* workspace,
                                    hipStream_t s);
+// binary16 arithmetic (TCONV_F16) on the packed 16-bit vector instructions
+bool forward_tiled3x3_f16_supported(const Params& p, int dtype);
+size_t forward_tiled3x3_f16_workspace(const Params& p);
+hipError_t launch_forward_tiled3x3_f16(const Params& p, const FwdArgs& a, void* workspace, hipStream_t s);
 bool forward_row_supported(const Params& p, int dtype);  // one-row inputs with a long window
 hipError_t launch_forward_row(const Params& p, const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);

@@ -50,6 +50,28 @@ __device__ __forceinline__ void load_run(float* dst, rsrc_t r, unsigned voff, un
   }
 }
 
+// The same loads without the widening: a register receives the stored bits (fp32: the value; bf16: its 16 bits,
+// zero-extended), so that no arithmetic instruction follows the load where it is issued; the main loop widens when
+// it masks the padding, just before the first use.
+template <int N, typename T>
+__device__ __forceinline__ void load_raw_run(float* dst, rsrc_t r, unsigned voff, unsigned soff) {
+  if constexpr (sizeof(T) == 4) {
+    load_run<N, T>(dst, r, voff, soff);
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      dst[i] = __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff + 2 * i, soff, 0));
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ float load_raw_one(rsrc_t r, unsigned voff, unsigned soff) {
+  if constexpr (sizeof(T) == 4)
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+  else
+    return __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0));
+}
+
 template <typename T>
 __device__ __forceinline__ float load_one(rsrc_t r, unsigned voff, unsigned soff) {
   if constexpr (sizeof(T) == 4)

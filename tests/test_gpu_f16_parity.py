@@ -51,6 +51,32 @@ def test_f16_ragged_shapes(cfg):
         _check16(cfg.with_(mode="parallel", pad_mode="zero"), integer=True)
 
 
+# Shapes the packed kernel takes (even W, even left margin dilation - pad): odd channel counts on both sides, a shifted
+# last segment, dilation 2 with pad 2 and pad 0, a lone channel, many images.
+PACKED_SHAPES = [
+    LayerCfg("h_odd", 3, 5, 19, 24, 7, seed=61),
+    LayerCfg("h_odd_cout1", 2, 3, 9, 10, 1, seed=62),
+    LayerCfg("h_d2", 2, 5, 18, 26, 6, pad=2, dil=2, seed=63),
+    LayerCfg("h_d2_p0", 2, 4, 18, 26, 5, pad=0, dil=2, seed=64),
+    LayerCfg("h_cin1", 3, 1, 12, 16, 9, seed=65),
+    LayerCfg("h_many", 130, 7, 14, 20, 10, seed=66),
+    LayerCfg("h_deep", 1, 131, 8, 12, 5, seed=67),
+]
+
+
+@pytest.mark.parametrize("cfg", PACKED_SHAPES, ids=lambda c: c.name)
+def test_f16_packed_kernel_shapes(cfg):
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg, dtype="f16")) == "tiled3x3_f16"
+    for mode in MODES:
+        c = cfg.with_(mode=mode)
+        _check16(c, alpha_beta="random" if mode in ("compound", "parallel") else None, backward=(mode == "compound"))
+        _check16(c, integer=True, backward=False)
+    if cfg.pad > 0:
+        _check16(cfg.with_(mode="compound", pad_mode="zero"), backward=False)
+        _check16(cfg.with_(mode="parallel", pad_mode="zero"), integer=True, backward=False)
+        _check16(cfg.with_(mode="min", pad_mode="zero"), backward=False)
+
+
 @pytest.mark.parametrize("cfg", RAGGED_LARGE[:2], ids=lambda c: c.name)
 def test_f16_large_ragged_shapes(cfg):
     for mode in ("compound", "parallel", "min"):
@@ -61,6 +87,8 @@ def test_f16_benchmark_layer_slice():
     """A four-image slice of the headline classification layer: w ~ U(-0.1, 0.1) against x ~ N(0, 1) in binary16."""
     _check16(CONFIGS["cfg2_main"].with_(N=4, name="cfg2_n4"))
     _check16(CONFIGS["cfg3b"].with_(N=2, name="cfg3b_n2"), backward=False)
+    _check16(CONFIGS["cfg3a"].with_(N=2, name="cfg3a_n2"), backward=False)
+    _check16(CONFIGS["cfg4b"].with_(N=1, C_out=32, name="cfg4b_n1_c32"), backward=False)
 
 
 def test_f16_error_paths():
