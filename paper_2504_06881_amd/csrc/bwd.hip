@@ -12,6 +12,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <math.h>
+
 #include <mutex>
 
 #include "tile_common.h"
@@ -350,41 +352,73 @@ static size_t bwd_input_lds_bytes(const Params& p, int CC, int TH, int TW) {
   return (size_t)CC * TH * TW * sizeof(double);
 }
 
-static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
+// Cost of a candidate: (channel chunks) x halo^0.55 / utilisation^0.15 / (how evenly the workgroups fill 256 compute
+// units, one resident workgroup each).  halo = scanned output pixels per owned input pixel (ragged last tiles scan
+// nearly as much as full ones but own less), utilisation = share of the 1024 threads that own a scanned pixel (whole
+// channel groups of P threads, see the kernel).  The exponents are fitted to measured times of two tile shapes each
+// on the 32 x 32 and the 56 x 56 benchmark layers (64 channels): a tile's fixed work - zeroing, the write-out, the
+// first load latency - does not grow with either.
+static BwdInTile search_bwd_input_tile(const Params& p, size_t lds_budget) {
   BwdInTile best = {0, 0, 0, 0, 0, 0};
   double best_cost = 1e30;
   const int eh = (p.KH - 1) * p.dh, ew = (p.KW - 1) * p.dw;
   for (int chunks = 1; chunks <= p.C_in; chunks *= 2) {
     const int CC = (p.C_in + chunks - 1) / chunks;
+    const int real_chunks = (p.C_in + CC - 1) / CC;
     // one-row inputs (sequences) have no second axis to grow the tile along: they take long rows instead
     const int tw_max = p.H == 1 ? 4096 : 128;
-    for (int TWc = 8; TWc <= tw_max; TWc *= 2) {
+    for (int TWc = 8; TWc <= tw_max; TWc += (TWc < 64 ? 4 : (TWc < 256 ? 32 : 512))) {
       const int TW = TWc < p.W ? TWc : p.W;
-      int TH = p.H < 64 ? p.H : 64;
-      while (TH >= 1 && bwd_input_lds_bytes(p, CC, TH, TW) > lds_budget) --TH;
-      if (TH >= 1) {
-        const int real_chunks = (p.C_in + CC - 1) / CC;
-        double cost = (double)real_chunks * (TH + eh) / TH * (TW + ew) / TW;
-        if (TW + ew < 16) cost *= 1.5;
+      const int th_max = p.H < 64 ? p.H : 64;
+      for (int TH = th_max; TH >= 1; --TH) {
+        if (bwd_input_lds_bytes(p, CC, TH, TW) > lds_budget) continue;
+        const long long RH = min((long long)p.Ho, (long long)(TH - 1 + eh) / p.sh + 1);
+        const long long RW = min((long long)p.Wo, (long long)(TW - 1 + ew) / p.sw + 1);
+        const long long P = RH * RW;  // output pixels an interior tile scans per output channel
         const int tiles_h = (p.H + TH - 1) / TH, tiles_w = (p.W + TW - 1) / TW;
+        const double halo = (double)P * p.sh * p.sw / ((double)TH * TW) * ((double)tiles_h * TH / p.H) *
+                            ((double)tiles_w * TW / p.W);
+        const double util =
+            P <= 1024 ? (double)(P * (1024 / P)) / 1024.0 : (double)P / (double)(((P + 1023) / 1024) * 1024);
+        double cost = (double)real_chunks * pow(halo, 0.55) / pow(util, 0.15);
+        if (RW < 16) cost *= 1.5;  // rows too short to coalesce
         const double wgs = (double)p.N * tiles_h * tiles_w * real_chunks;
-        if (wgs < 256) cost *= 1.0 + (256 - wgs) / 256;  // too few workgroups to fill 256 CUs
-        {  // threads that own a scanned pixel: whole channel groups of P threads (see the kernel)
-          const long long RH = min((long long)p.Ho, (long long)(TH + eh) / p.sh + 1);
-          const long long RW = min((long long)p.Wo, (long long)(TW + ew) / p.sw + 1);
-          const long long P = RH * RW;
-          cost /= P <= 1024 ? (double)(P * (1024 / P)) / 1024.0 : (double)P / (double)(((P + 1023) / 1024) * 1024);
-        }
-        if (cost < best_cost) {
+        const double rounds = (double)(((long long)wgs + 255) / 256);
+        cost *= rounds * 256.0 / wgs;  // idle compute units in the last round (or in the only one)
+        if (cost < best_cost - 1e-12) {
           best_cost = cost;
           best = {TH, TW, CC, tiles_h, tiles_w, real_chunks};
         }
+        if (TH * 2 < th_max && TH * 4 * (long long)TW * CC * 8 < (long long)lds_budget) break;  // far below the budget
       }
       if (TW == p.W) break;
     }
     if (CC == 1) break;
   }
   return best;
+}
+
+// The search runs once per layer shape and LDS budget (a few thousand candidates); later launches look the tile up.
+static BwdInTile choose_bwd_input_tile(const Params& p, size_t lds_budget) {
+  struct Entry { int key[14]; size_t budget; BwdInTile tile; };
+  static std::mutex mu;
+  static Entry cache[64];
+  static int n_cached = 0;
+  const int key[14] = {p.N, p.C_in, p.H, p.W, p.C_out, p.KH, p.KW, p.sh, p.sw, p.ph, p.pw, p.dh, p.dw, p.Ho * 65536 + p.Wo};
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    for (int e = 0; e < n_cached; ++e)
+      if (cache[e].budget == lds_budget && memcmp(cache[e].key, key, sizeof(key)) == 0) return cache[e].tile;
+  }
+  const BwdInTile t = search_bwd_input_tile(p, lds_budget);
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    Entry& e = cache[n_cached < 64 ? n_cached++ : (key[0] + key[1] + key[2]) & 63];
+    memcpy(e.key, key, sizeof(key));
+    e.budget = lds_budget;
+    e.tile = t;
+  }
+  return t;
 }
 
 // One-row inputs: positions per tile and channels per chunk, block size fitted to the scanned outputs.
@@ -561,6 +595,8 @@ __global__ __launch_bounds__(256) void bwd_weight_reduce_kernel(const double* __
     for (int h = 0; h < nhist; ++h) {
       const double* src = partial + (co * nhist + h) * (size_t)K + k;
       double v = 0.0;
+      // the loads of 8 slices go out together (the adds keep their order): this kernel is a chain of load latencies
+#pragma unroll 8
       for (int sl = 0; sl < slices; ++sl) v += src[(size_t)sl * per_slice];
       (h == 0 ? dst0 : dst1)[e] = (float)v;
     }
@@ -737,8 +773,32 @@ __global__ __launch_bounds__(256) void bwd_alpha_beta_kernel(Params p, const flo
   const int n1 = min(n0 + n_per_block, p.N);
   const size_t plane = (size_t)p.Ho * p.Wo;
   double sa = 0.0, sb = 0.0;
+  // fp32 planes of a multiple of four elements are read 16 bytes at a time (plane bases are then 16-byte aligned
+  // when the tensors are); a thread's terms are added in a fixed order either way
+  const bool vec4 = sizeof(TY) == 4 && (plane & 3) == 0 &&
+                    ((((uintptr_t)gy | (uintptr_t)y_min | (uintptr_t)y_max) & 15) == 0);
   for (int n = n0; n < n1; ++n) {
     const size_t base = ((size_t)n * p.C_out + co) * plane;
+    if (vec4) {
+      const float4* g4 = (const float4*)(gy + base);
+      const float4* a4 = (const float4*)((const float*)y_min + base);
+      const float4* b4 = (const float4*)((const float*)y_max + base);
+#pragma unroll 2
+      for (size_t i = threadIdx.x; i < plane / 4; i += blockDim.x) {
+        const float4 g = g4[i];
+        if (grad_alpha) {
+          const float4 v = a4[i];
+          sa += (double)g.x * (double)v.x; sa += (double)g.y * (double)v.y;
+          sa += (double)g.z * (double)v.z; sa += (double)g.w * (double)v.w;
+        }
+        if (grad_beta) {
+          const float4 v = b4[i];
+          sb += (double)g.x * (double)v.x; sb += (double)g.y * (double)v.y;
+          sb += (double)g.z * (double)v.z; sb += (double)g.w * (double)v.w;
+        }
+      }
+      continue;
+    }
     for (size_t i = threadIdx.x; i < plane; i += blockDim.x) {
       const float g = gy[base + i];
       if (grad_alpha) sa += (double)g * (double)ld_f32(y_min, base + i);
@@ -773,17 +833,20 @@ __global__ __launch_bounds__(256) void ab_reduce_kernel(const double* __restrict
   const int co = blockIdx.x * blockDim.x + threadIdx.x;
   if (co >= C_out) return;
   double sa = 0.0, sb = 0.0;
+#pragma unroll 8
   for (int sl = 0; sl < slices; ++sl) {
-    sa += partial[((size_t)sl * C_out + co) * 2];
-    sb += partial[((size_t)sl * C_out + co) * 2 + 1];
+    const double2 v = *(const double2*)(partial + ((size_t)sl * C_out + co) * 2);
+    sa += v.x;
+    sb += v.y;
   }
   if (grad_alpha) grad_alpha[co] = (float)sa;
   if (grad_beta) grad_beta[co] = (float)sb;
 }
 
 static int ab_slices(const Params& p, int* n_per_block) {
-  // about two workgroups per compute unit, each with at least one image
-  int slices = (512 + p.C_out - 1) / p.C_out;
+  // about eight 256-thread workgroups per compute unit (these kernels stream their operands once and need the
+  // loads of many waves in flight), each with at least one image
+  int slices = (2048 + p.C_out - 1) / p.C_out;
   if (slices > p.N) slices = p.N;
   if (slices > 65535) slices = 65535;
   *n_per_block = (p.N + slices - 1) / slices;
@@ -831,8 +894,18 @@ __global__ __launch_bounds__(256) void bwd_bias_kernel(Params p, const float* __
   const int n1 = min(n0 + n_per_block, p.N);
   const size_t plane = (size_t)p.Ho * p.Wo;
   double sa = 0.0;
+  const bool vec4 = (plane & 3) == 0 && (((uintptr_t)gy & 15) == 0);
   for (int n = n0; n < n1; ++n) {
     const size_t base = ((size_t)n * p.C_out + co) * plane;
+    if (vec4) {
+      const float4* g4 = (const float4*)(gy + base);
+#pragma unroll 2
+      for (size_t i = threadIdx.x; i < plane / 4; i += blockDim.x) {
+        const float4 g = g4[i];
+        sa += (double)g.x; sa += (double)g.y; sa += (double)g.z; sa += (double)g.w;
+      }
+      continue;
+    }
     for (size_t i = threadIdx.x; i < plane; i += blockDim.x) sa += (double)gy[base + i];
   }
   __shared__ double red[256];

@@ -62,6 +62,21 @@ def test_plain_kernel_on_3x3x3_shapes():
             os.environ["TCONV_FORWARD_KERNEL"] = old
 
 
+@pytest.mark.parametrize("kb", ["2", "12"])
+def test_input_gradient_boxes_under_a_small_lds_budget(kb):
+    """TCONV_BWD3_LDS_KB shrinks the LDS box of the input-gradient kernel: channel chunks (fewer channels than C_in per
+    box), several boxes per volume, ragged last boxes."""
+    import os
+    os.environ["TCONV_BWD3_LDS_KB"] = kb
+    try:
+        for cfg in (SHAPES[0], SHAPES[1], SHAPES[3], SHAPES[7], SHAPES[9]):
+            _check(cfg.with_(mode="compound"), alpha_beta="random")
+            _check(cfg.with_(mode="parallel"), integer=True)
+            _check(cfg.with_(mode="min"))
+    finally:
+        os.environ.pop("TCONV_BWD3_LDS_KB", None)
+
+
 def test_larger_layer():
     cfg = CONFIGS_3D["c3d_main"].with_(N=2)
     print(f"[3d] {cfg.name} pairs={cfg.pairs:.3e}", flush=True)

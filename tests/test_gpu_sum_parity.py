@@ -43,7 +43,9 @@ SHAPES = [
     LayerCfg("s_narrow", 4, 6, 8, 5, 8, seed=48),
     LayerCfg("s_one3", 1, 1, 1, 1, 1, seed=49),
     LayerCfg("s_cin33", 1, 33, 9, 16, 18, seed=50),
-    LayerCfg("s_tall", 1, 2, 300, 12, 3, seed=51),         # grad_x in several bands of rows
+    LayerCfg("s_tall", 1, 2, 300, 12, 3, seed=51),         # a tall, narrow plane (one band of rows)
+    LayerCfg("s_bands", 1, 2, 300, 40, 3, seed=54),        # 144 KB of plane: the input gradient in three bands of rows
+    LayerCfg("s_bands_5x5_s2", 1, 2, 260, 48, 3, KH=5, KW=5, stride=2, pad=2, seed=55),   # the same for the generic gradient kernel
     LayerCfg("s_1d_k5", 2, 5, 1, 60, 6, KH=1, KW=5, pad=0, seed=52),           # a one-dimensional layer: H = 1, KH = 1
     LayerCfg("s_1d_k9_s2", 2, 3, 1, 101, 4, KH=1, KW=9, stride=2, pad=0, seed=53),
 ]
