@@ -393,8 +393,9 @@ const char* tconv_status_string(int status);
 
 /*
  * Name of the forward kernel tconv_forward would launch for this descriptor
- * ("tiled3x3", "row1d" - one-row inputs with a window of 8 taps or more - or "generic"), for tests and
- * benchmarks.  Host only; NULL on a bad descriptor.
+ * ("tiled3x3"; "tiled3x3_f16" - binary16 arithmetic on the packed 16-bit vector instructions; "row1d" - one-row
+ * inputs with a window of 8 taps or more; "rowtile" - other windows up to 7 taps wide, fp32; or "generic"), for
+ * tests and benchmarks.  Host only; NULL on a bad descriptor.
  */
 const char* tconv_forward_kernel_name(const tconv_desc* desc);
 

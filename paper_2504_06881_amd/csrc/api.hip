@@ -70,6 +70,11 @@ bool use_row(const Params& p, int dtype) {
   return !use_tiled(p, dtype) && forward_row_supported(p, dtype) && !generic_forced();
 }
 
+bool use_rowtile(const Params& p, int dtype) {
+  return !use_tiled(p, dtype) && !use_tiled16(p, dtype) && !use_row(p, dtype) && forward_rowtile_supported(p, dtype) &&
+         !generic_forced();
+}
+
 }  // namespace
 
 extern "C" {
@@ -151,6 +156,9 @@ int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min
   } else if (use_row(p, desc->dtype) && !a.bias && !a.scale && !a.residual) {  // the row kernel has no epilogue
     own_status();
     e = launch_forward_row(p, a, s);
+  } else if (use_rowtile(p, desc->dtype) && !a.bias && !a.scale && !a.residual) {  // nor has the row-tiled kernel
+    own_status();
+    e = launch_forward_rowtile(p, a, s);
   } else {
     own_status();
     e = launch_forward_generic(p, desc->dtype, a, s);
@@ -609,7 +617,9 @@ const char* tconv_forward_kernel_name(const tconv_desc* desc) {
   Params p;
   if (make_params(desc, &p) != TCONV_OK) return nullptr;
   if (use_tiled16(p, desc->dtype)) return "tiled3x3_f16";
-  return use_tiled(p, desc->dtype) ? "tiled3x3" : (use_row(p, desc->dtype) ? "row1d" : "generic");
+  if (use_tiled(p, desc->dtype)) return "tiled3x3";
+  if (use_row(p, desc->dtype)) return "row1d";
+  return use_rowtile(p, desc->dtype) ? "rowtile" : "generic";
 }
 
 }  // extern "C"

@@ -156,6 +156,9 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
 bool forward_tiled3x3_f16_supported(const Params& p, int dtype);
 size_t forward_tiled3x3_f16_workspace(const Params& p);
 hipError_t launch_forward_tiled3x3_f16(const Params& p, const FwdArgs& a, void* workspace, hipStream_t s);
+// windows other than 3x3 (KW <= 7), fp32: kernel rows walked with the input row segment in registers
+bool forward_rowtile_supported(const Params& p, int dtype);
+hipError_t launch_forward_rowtile(const Params& p, const FwdArgs& a, hipStream_t s);
 bool forward_row_supported(const Params& p, int dtype);  // one-row inputs with a long window
 hipError_t launch_forward_row(const Params& p, const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);

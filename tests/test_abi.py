@@ -62,7 +62,9 @@ def test_workspace_status_and_kernel_name():
     for s in (-1, -2, -3, -4, -5, -99):
         assert len(tb.status_string(s)) > 3
     assert tb.tconv_forward_kernel_name(d) in ("tiled3x3", "generic")
-    assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2))) == "generic"
+    assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2))) == "rowtile"
+    assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2), dil=(1, 2))) == "generic"
+    assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 3, 3, pad=(1, 1), dtype="f16")) == "tiled3x3_f16"
 
 
 def test_compute_entry_points_reject_null_before_touching_the_gpu():
@@ -83,9 +85,11 @@ def test_one_dimensional_descriptor_views():
     # K = 3, C_in a multiple of 3, full-window mode: three channels become the three rows of a 3 x 3 window
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="compound")) == "tiled3x3"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, stride=2, pad=1, mode="max")) == "tiled3x3"
-    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 95, 4000, 64, 3, pad=1, mode="compound")) == "generic"
+    # other short windows (K <= 7, no dilation, stride 1 or 2) of the full-window modes: the row-tiled kernel
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 95, 4000, 64, 3, pad=1, mode="compound")) == "rowtile"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=2, mode="compound")) == "rowtile"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="minplus_max")) == "generic"
-    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=2, mode="compound")) == "generic"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=4, dil=2, mode="compound")) == "generic"
     # long windows over few channels: the one-row kernel (strides 1, 2, 4, 8; full-window modes; fp32)
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=4, pad=38, mode="compound")) == "row1d"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 1, 32000, 64, 80, stride=3, pad=38, mode="compound")) == "generic"

@@ -118,6 +118,33 @@ RAGGED_LARGE = [
 ]
 
 
+# Windows other than 3x3 on the row-tiled kernel: the 5x5 LeNet layers (Table 1), a 7x7 stride-2 stem, 1x1, even and
+# non-square windows, a one-row layer, vertical dilation, odd channel counts, ragged and shifted last segments, a
+# layer large enough for many workgroups per XCD.
+ROWTILE = [
+    LayerCfg("t_5x5", 3, 3, 14, 15, 6, KH=5, KW=5, pad=2, seed=71),
+    LayerCfg("t_5x5_p0", 2, 6, 16, 16, 16, KH=5, KW=5, pad=0, seed=72),
+    LayerCfg("t_7x7_s2", 2, 3, 37, 45, 9, KH=7, KW=7, stride=2, pad=3, seed=73),
+    LayerCfg("t_1x1", 2, 9, 7, 11, 5, KH=1, KW=1, pad=0, seed=74),
+    LayerCfg("t_2x3", 2, 3, 9, 10, 3, KH=2, KW=3, pad=1, seed=75),
+    LayerCfg("t_4x4_s2", 2, 5, 18, 22, 7, KH=4, KW=4, stride=2, pad=1, seed=76),
+    LayerCfg("t_6x2", 1, 4, 20, 12, 5, KH=6, KW=2, pad=1, seed=77),
+    LayerCfg("t_1x5_row", 3, 4, 1, 50, 6, KH=1, KW=5, pad=0, seed=78),
+    LayerCfg("t_5x5_many", 70, 5, 19, 23, 7, KH=5, KW=5, pad=2, seed=79),
+    LayerCfg("t_3x3_p2", 2, 4, 12, 16, 6, pad=2, seed=80),     # 3x3 with pad_w > dil: not the 3x3 kernel's
+]
+
+
+@pytest.mark.parametrize("cfg", ROWTILE, ids=lambda c: c.name)
+def test_row_tiled_kernel_shapes(cfg):
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "rowtile"
+    for mode in MODES:
+        c = cfg.with_(mode=mode)
+        _check(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+        _check(c, integer=True)
+    _check(cfg.with_(mode="compound"), kernel="generic")
+
+
 @pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
 def test_ragged_shapes(cfg):
     tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
