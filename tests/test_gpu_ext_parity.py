@@ -117,3 +117,86 @@ def test_extension_error_paths():
     with pytest.raises(tb.TconvError) as e:   # the Sum-channel layers keep identity padding
         tb.tconv_sum_forward(d, z, None, z, None, None, z)
     assert e.value.status == -4
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_residual_block_training_step(stride):
+    """One Sec. 5 TCNN BasicBlock, forward and backward, chained through the library the way bench.py's end-to-end
+    workload chains it (batch norm as a fused scale / shift, shortcut as the fused residual: the block input, or at a
+    stage boundary every second pixel with zero-filled new channels; gradient of a fused layer = tconv_backward with
+    alpha = beta = scale, tconv_backward_bias, tconv_backward_alpha_beta), against the same chain of oracle calls."""
+    import torch
+    from oracle import text_oracle as ext
+    dev = torch.device("cuda:0")
+    rng = np.random.Generator(np.random.PCG64(4242 + stride))
+    N, C, H, W = 3, 6, 12, 16
+    Co = C * stride
+    Ho, Wo = H // stride, W // stride
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = lambda co, ci: ((rng.random((2, co, ci, 3, 3), dtype=np.float32) * 2 - 1) * np.float32(0.1))
+    wa, wb = w(Co, C), w(Co, Co)
+    sa, sb = (rng.uniform(0.2, 0.4, Co).astype(np.float32) for _ in range(2))
+    ha, hb = (rng.standard_normal(Co).astype(np.float32) * np.float32(0.1) for _ in range(2))
+    gy = rng.standard_normal((N, Co, Ho, Wo)).astype(np.float32)
+    short = x if stride == 1 else np.concatenate([x[:, :, ::2, ::2], np.zeros((N, Co - C, Ho, Wo), np.float32)], 1)
+    ones = np.ones(Co, np.float32)
+    # ---- oracle chain
+    s_a = ext.Shape(N, C, H, W, Co, 3, 3, stride, 1, 1)
+    s_b = ext.Shape(N, Co, Ho, Wo, Co, 3, 3, 1, 1, 1)
+    fa = ext.forward(s_a, "parallel", x, wa[0], wa[1], ones, ones, scale=sa, shift=ha)
+    fb = ext.forward(s_b, "parallel", fa["y"], wb[0], wb[1], ones, ones, scale=sb, shift=hb, residual=short)
+    gb = ext.backward(s_b, "parallel", gy, fb["idx_min"], fb["idx_max"], alpha=sb, beta=sb)
+    g_mid = gb["grad_x"].astype(np.float32)
+    ga = ext.backward(s_a, "parallel", g_mid, fa["idx_min"], fa["idx_max"], alpha=sa, beta=sa)
+    g_short = gy if stride == 1 else None
+    g_x = ga["grad_x"].copy()
+    if stride == 1:
+        g_x += gy
+    else:
+        g_x[:, :, ::2, ::2] += gy[:, :C]
+    want = dict(y=fb["y"], g_x=g_x, gwa_min=ga["grad_w_min"], gwb_max=gb["grad_w_max"],
+                g_hb=ext.backward_bias(s_b, gy), g_ha=ext.backward_bias(s_a, g_mid),
+                g_sb=np.sum(gy.astype(np.float64) * (fb["y_min"].astype(np.float64) + fb["y_max"]), axis=(0, 2, 3)),
+                g_sa=np.sum(g_mid.astype(np.float64) * (fa["y_min"].astype(np.float64) + fa["y_max"]), axis=(0, 2, 3)))
+    # ---- the same chain through the C ABI
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    d_a = tb.Desc(N, C, H, W, Co, 3, 3, (stride, stride), (1, 1), (1, 1), "parallel")
+    d_b = tb.Desc(N, Co, Ho, Wo, Co, 3, 3, (1, 1), (1, 1), (1, 1), "parallel")
+
+    def fused(d, xin, wpair, scale, shift, residual):
+        osh = (N, Co, Ho, Wo)
+        o = {k: torch.empty(osh, device=dev) for k in ("y", "y_min", "y_max")}
+        o.update({k: torch.empty(osh, device=dev, dtype=torch.int32) for k in ("idx_min", "idx_max")})
+        tb.tconv_forward_fused(d, xin, up(wpair[0]), up(wpair[1]), None, None, o["y"], o["y_min"], o["y_max"],
+                               o["idx_min"], o["idx_max"], scale=up(scale), shift=up(shift), residual=residual)
+        return o
+
+    def backward(d, g, o, scale, xshape, wshape):
+        r = dict(gx=torch.empty(xshape, device=dev), gw_min=torch.empty(wshape, device=dev),
+                 gw_max=torch.empty(wshape, device=dev), gh=torch.empty(Co, device=dev),
+                 ga=torch.empty(Co, device=dev), gb=torch.empty(Co, device=dev))
+        sc = up(scale)
+        ws = lambda op: hs.scratch(tb.tconv_workspace_bytes(d, op), dev)
+        tb.tconv_backward(d, g, sc, sc, o["idx_min"], o["idx_max"], r["gx"], r["gw_min"], r["gw_max"], ws("backward"))
+        tb.tconv_backward_bias(d, g, r["gh"], ws("backward_bias"))
+        tb.tconv_backward_alpha_beta(d, g, o["y_min"], o["y_max"], r["ga"], r["gb"], ws("backward_alpha_beta"))
+        return r
+
+    oa = fused(d_a, up(x), wa, sa, ha, None)
+    ob = fused(d_b, oa["y"], wb, sb, hb, up(short))
+    rb = backward(d_b, up(gy), ob, sb, (N, Co, Ho, Wo), (Co, Co, 3, 3))
+    ra = backward(d_a, rb["gx"], oa, sa, (N, C, H, W), (Co, C, 3, 3))
+    gx = ra["gx"].clone()
+    if stride == 1:
+        gx += up(gy)
+    else:
+        gx[:, :, ::2, ::2] += up(gy)[:, :C]
+    torch.cuda.synchronize()
+    got = dict(y=ob["y"], g_x=gx, gwa_min=ra["gw_min"], gwb_max=rb["gw_max"], g_hb=rb["gh"], g_ha=ra["gh"],
+               g_sb=rb["ga"] + rb["gb"], g_sa=ra["ga"] + ra["gb"])
+    got = {k: v.cpu().numpy() for k, v in got.items()}
+    assert np.array_equal(hs.bits(got["y"]), hs.bits(want["y"])), "block output differs"
+    for k in ("g_x", "gwa_min", "gwb_max", "g_hb", "g_ha", "g_sb", "g_sa"):
+        a, b = got[k].astype(np.float64), np.asarray(want[k], np.float64)
+        tol = 2e-5 * max(1.0, float(np.max(np.abs(b))))
+        assert np.max(np.abs(a - b)) <= tol, (k, float(np.max(np.abs(a - b))), tol)

@@ -264,3 +264,64 @@ def test_half_duality_and_ordering():
     assert np.array_equal(mx["y"], -mn["y"]) and np.array_equal(mx["idx_max"], mn["idx_min"])
     both = ext.forward_f16(s, "compound", xh, w, None)
     assert (both["y_max"].astype(np.float32) >= both["y_min"].astype(np.float32)).all()
+
+
+# ---------------------------------------------------------------- gradient rules of a residual block
+
+def _block_loss64(x, wa, wb, sa, ha, sb, hb, gy):
+    """sum(gy * block(x)) in float64 by enumeration: block = conv_b(conv_a(x)*sa + ha)*sb + hb + x, both convs
+    parallel-mode 3x3 / pad 1 with alpha = beta = 1 (Sec. 5 TCNN BasicBlock with the batch norms folded to affines)."""
+    import brute
+
+    def conv(v, w):
+        y_min, _ = brute.forward(v, w[0], False, 1, 1, 1, dtype=np.float64)
+        y_max, _ = brute.forward(v, w[1], True, 1, 1, 1, dtype=np.float64)
+        return y_min + y_max
+
+    a = conv(x, wa) * sa[None, :, None, None] + ha[None, :, None, None]
+    b = conv(a, wb) * sb[None, :, None, None] + hb[None, :, None, None] + x
+    return float(np.sum(gy.astype(np.float64) * b))
+
+
+def test_residual_block_gradient_rules_against_finite_differences():
+    """How the fused layers compose into a training step (the rule bench.py's end-to-end workload uses): the gradient of
+    a fused layer's bare output is scale*g, passed to the backward call as alpha = beta = scale; grad_shift is the bias
+    gradient of g; grad_scale is sum g*(y_min + y_max); the shortcut adds g to the block input's gradient.  Checked on
+    the oracle's own forward / backward calls against central differences of a float64 enumeration of the block."""
+    rng = np.random.Generator(np.random.PCG64(991))
+    N, C, H, W = 2, 3, 5, 6
+    s = ext.Shape(N, C, H, W, C, 3, 3, 1, 1, 1)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    wa = (rng.random((2, C, C, 3, 3), dtype=np.float32) * 2 - 1) * np.float32(0.5)
+    wb = (rng.random((2, C, C, 3, 3), dtype=np.float32) * 2 - 1) * np.float32(0.5)
+    sa, sb = (rng.uniform(0.3, 0.9, C).astype(np.float32) for _ in range(2))
+    ha, hb = (rng.standard_normal(C).astype(np.float32) * np.float32(0.1) for _ in range(2))
+    gy = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    ones = np.ones(C, np.float32)
+    # forward through the fused layers
+    fa = ext.forward(s, "parallel", x, wa[0], wa[1], ones, ones, scale=sa, shift=ha)
+    fb = ext.forward(s, "parallel", fa["y"], wb[0], wb[1], ones, ones, scale=sb, shift=hb, residual=x)
+    # backward by the rules
+    gb = ext.backward(s, "parallel", gy, fb["idx_min"], fb["idx_max"], alpha=sb, beta=sb)
+    g_hb = ext.backward_bias(s, gy)
+    g_sb = np.sum(gy.astype(np.float64) * (fb["y_min"].astype(np.float64) + fb["y_max"]), axis=(0, 2, 3))
+    g_mid = gb["grad_x"].astype(np.float32)
+    ga = ext.backward(s, "parallel", g_mid, fa["idx_min"], fa["idx_max"], alpha=sa, beta=sa)
+    g_ha = ext.backward_bias(s, g_mid)
+    g_sa = np.sum(g_mid.astype(np.float64) * (fa["y_min"].astype(np.float64) + fa["y_max"]), axis=(0, 2, 3))
+    g_x = ga["grad_x"] + gy
+    args = dict(x=x, wa=wa, wb=wb, sa=sa, ha=ha, sb=sb, hb=hb)
+    analytic = dict(x=g_x, wa=np.stack([ga["grad_w_min"], ga["grad_w_max"]]),
+                    wb=np.stack([gb["grad_w_min"], gb["grad_w_max"]]), sa=g_sa, ha=g_ha, sb=g_sb, hb=g_hb)
+    h = 2.0 ** -20   # small: a scale or shift moves every pixel of its channel, and a change of winner inside the
+                     # interval would mix two slopes (the enumeration is float64, so the difference stays exact)
+    for name in ("x", "wa", "wb", "sa", "ha", "sb", "hb"):
+        flat = analytic[name].reshape(-1)
+        for e in rng.choice(flat.size, size=min(12, flat.size), replace=False):
+            hi = {k: v.astype(np.float64).copy() for k, v in args.items()}
+            lo = {k: v.astype(np.float64).copy() for k, v in args.items()}
+            hi[name].reshape(-1)[e] += h
+            lo[name].reshape(-1)[e] -= h
+            fd = (_block_loss64(gy=gy, **hi) - _block_loss64(gy=gy, **lo)) / (2 * h)
+            # the function is piecewise linear: away from a change of winner the central difference is exact
+            assert abs(fd - flat[e]) <= 1e-4 * max(1.0, abs(fd)), (name, int(e), fd, float(flat[e]))
