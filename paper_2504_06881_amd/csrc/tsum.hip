@@ -14,10 +14,16 @@
 // values and coefficients wave-uniform in SGPRs, input rows in registers, NaN as padding; no
 // winner is tracked, so there is no epilogue) and a one-thread-per-output kernel for everything else.
 // Backward re-computes the window winners instead of storing C_in times larger index tensors:
-//   sum_bwd_x_kernel   one workgroup per (image, input channel[, band of rows]): the grad_x plane in LDS
-//                      as fp64, every (c_out, output pixel) adds its gradient at the winner's pixel;
-//   sum_bwd_w_kernel   one workgroup per (c_out, c_in[, slice of the batch]): 9 tap bins per branch and
-//                      the two coefficient sums in registers, reduced through LDS.
+//   sum_bwd_fused3x3_kernel  3x3 windows, all gradients of a call from ONE winner search: workgroup = (image,
+//                      input channel[, band of rows]) with the grad_x plane and replicated tap bins in LDS;
+//   sum_bwd_x_kernel / sum_bwd_x3x3_kernel   grad_x alone (or other windows): the same workgroup layout, every
+//                      (c_out, output pixel) adds its gradient at the winner's pixel of the fp64 plane in LDS;
+//   sum_bwd_w3x3_blk_kernel / sum_bwd_w_kernel   the parameter gradients alone (or other windows): workgroup =
+//                      (c_in, block of c_out | one c_out[, slice of the batch]), tap bins per branch in LDS.
+// What bounds the backward pass: an item (pixel, c_out, c_in) costs about 70 vector instructions (9 adds, two winner
+// searches of 19, the fp64 products) and one ds_add_f64 per branch and gradient; an LDS fp64 atomic takes a compute
+// unit about 22 clocks per wave, as much as 5 vector instructions, so the fused kernel (4 atomics per item) is bound
+// by the LDS atomics and the separate kernels (2 each, the search done twice) by instruction issue.
 #include <stdlib.h>
 #include <string.h>
 
@@ -484,51 +490,52 @@ __global__ __launch_bounds__(256) void sum_bwd_w_kernel(Params p, const float* _
   }
 }
 
-// grad_w, grad_alpha, grad_beta for 3x3 windows: as above with the window unrolled (9 coalesced loads of
-// x per output pixel, kernel values in scalar registers).
+// grad_w, grad_alpha, grad_beta for 3x3 windows, several output channels per workgroup.  Workgroup = (input channel c,
+// block of CB output channels, slice of the batch).  A thread takes output pixels; per pixel it works out the tap
+// addresses and loads the 9 input values ONCE and then walks the CB output channels with them (kernel values and
+// coefficients are wave-uniform scalars, gy is read coalesced): the address arithmetic and the loads, more than half
+// of the one-channel kernel's instructions, are shared by CB items.  The tap sums go to LDS bins [REP][CB][branch][9]
+// of fp64 with ds_add_f64; a lane uses replica (lane mod REP), so that at most 64 / REP lanes of a wave can meet in
+// one bin.  The coefficient sums stay in fp64 registers.  At the end the replicas are added in a fixed order and each
+// value goes into the zero-filled result with one fp32 atomic.
+constexpr int SUMW_CB = 4, SUMW_REP = 16;
 template <int MODE>
-__global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float* __restrict__ x,
-                                                           const float* __restrict__ w_min,
-                                                           const float* __restrict__ w_max,
-                                                           const float* __restrict__ alpha,
-                                                           const float* __restrict__ beta,
-                                                           const float* __restrict__ gy,
-                                                           float* __restrict__ grad_w_min,
-                                                           float* __restrict__ grad_w_max,
-                                                           float* __restrict__ grad_alpha,
-                                                           float* __restrict__ grad_beta, int n_per_block) {
+__global__ __launch_bounds__(256) void sum_bwd_w3x3_blk_kernel(Params p, const float* __restrict__ x,
+                                                               const float* __restrict__ w_min,
+                                                               const float* __restrict__ w_max,
+                                                               const float* __restrict__ alpha,
+                                                               const float* __restrict__ beta,
+                                                               const float* __restrict__ gy,
+                                                               float* __restrict__ grad_w_min,
+                                                               float* __restrict__ grad_w_max,
+                                                               float* __restrict__ grad_alpha,
+                                                               float* __restrict__ grad_beta, int n_per_block,
+                                                               int n_coblocks) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
-  constexpr int KK = 9, NV = NBR * (KK + 1);
-  extern __shared__ double lds_d[];
-  double* const mine = lds_d + threadIdx.x;  // value v of thread t at lds_d[v * 256 + t]
-#pragma unroll
-  for (int v = 0; v < NV; ++v) mine[v * 256] = 0.0;
-  const int co = blockIdx.x / p.C_in, c = blockIdx.x % p.C_in;
+  constexpr int CB = SUMW_CB, REP = SUMW_REP;
+  __shared__ double bins[CB][NBR][REP][11];  // 11: an odd stride spreads the replicas over the LDS banks
+  __shared__ double csum[4][CB][2];  // per wave: coefficient sums
+  for (int e = threadIdx.x; e < CB * NBR * REP * 11; e += blockDim.x) (&bins[0][0][0][0])[e] = 0.0;
+  const int c = blockIdx.x / n_coblocks, cob = blockIdx.x - c * n_coblocks;
+  const int co0 = cob * CB;
   const int n0 = blockIdx.y * n_per_block, n1 = min(n0 + n_per_block, p.N);
-  float ka[9], kb[9];
-#pragma unroll
-  for (int t = 0; t < 9; ++t) {
-    ka[t] = DO_MIN ? w_min[((size_t)co * p.C_in + c) * 9 + t] : 0.f;
-    kb[t] = DO_MAX ? w_max[((size_t)co * p.C_in + c) * 9 + t] : 0.f;
-  }
-  const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
-  const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
   const int plane = p.Ho * p.Wo;
-  // x through a buffer resource and 32-bit offsets: row offset + column offset per tap, clamped into the
-  // image (a tap outside it is loaded from the clamped position and replaced by the branch's identity)
   const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * p.H * p.W * sizeof(float)));
   const int oh_first = (int)threadIdx.x / p.Wo, ow_first = (int)threadIdx.x % p.Wo;
   const int d_oh = (int)blockDim.x / p.Wo, d_ow = (int)blockDim.x % p.Wo;
+  const int myrep = threadIdx.x & (REP - 1);
+  double sa[CB], sb[CB];
+#pragma unroll
+  for (int b = 0; b < CB; ++b) { sa[b] = 0.0; sb[b] = 0.0; }
+  __syncthreads();
   for (int n = n0; n < n1; ++n) {
     const unsigned xbase = (unsigned)(((size_t)n * p.C_in + c) * p.H * p.W * sizeof(float));  // uniform
-    const float* gyc = gy + ((size_t)n * p.C_out + co) * plane;
     int oh = oh_first, ow = ow_first;
     for (int i = threadIdx.x; i < plane; i += blockDim.x, oh += d_oh, ow += d_ow) {
-      if (ow >= p.Wo) { ow -= p.Wo; ++oh; }  // (oh, ow) = (i / Wo, i % Wo), kept by increments: no division per pixel
+      if (ow >= p.Wo) { ow -= p.Wo; ++oh; }
       const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
-      const double g = (double)gyc[i];
       unsigned roff[3], coff[3];
       bool rok[3], cok[3];
 #pragma unroll
@@ -539,50 +546,242 @@ __global__ __launch_bounds__(256) void sum_bwd_w3x3_kernel(Params p, const float
         roff[k] = (unsigned)(min(max(ih, 0), p.H - 1) * p.W) * 4u;
         coff[k] = (unsigned)min(max(iw, 0), p.W - 1) * 4u;
       }
-      float xv9[9];
+      float xv[9];
 #pragma unroll
-      for (int t = 0; t < 9; ++t) xv9[t] = load_one<float>(xres, roff[t / 3] + coff[t % 3], xbase);
-      float bmin = INFINITY, bmax = -INFINITY;
-      int tmin = 0, tmax = 0;
-      float s1[9], s2[9];
+      for (int t = 0; t < 9; ++t) xv[t] = load_one<float>(xres, roff[t / 3] + coff[t % 3], xbase);
 #pragma unroll
-      for (int t = 0; t < 9; ++t) {
-        // a tap outside the image becomes NaN once for both branches: it is never the extremum
-        const float xv = (rok[t / 3] && cok[t % 3]) ? xv9[t] : __uint_as_float(0x7fc00000u);
-        s1[t] = __fadd_rn(xv, ka[t]);
-        s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xv, kb[t]);  // compound: one shared kernel
+      for (int t = 0; t < 9; ++t)  // a tap outside the image becomes NaN once for both branches: never the extremum
+        xv[t] = (rok[t / 3] && cok[t % 3]) ? xv[t] : __uint_as_float(0x7fc00000u);
+#pragma unroll
+      for (int b = 0; b < CB; ++b) {
+        const int co = min(co0 + b, p.C_out - 1);  // a block past C_out repeats the last channel and publishes nothing
+        const float* ka = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const float* kb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const double g = (double)gy[((size_t)n * p.C_out + co) * plane + i];
+        float s1[9], s2[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          if (DO_MIN) s1[t] = __fadd_rn(xv[t], ka[t]);
+          if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xv[t], kb[t]);
+        }
+        if (DO_MIN) {
+          float bmin; int tmin;
+          window_extremum9<false>(s1, bmin, tmin);
+          const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
+          atomicAdd(&bins[b][0][myrep][tmin], ca * g);
+          sa[b] += g * (double)bmin;
+        }
+        if (DO_MAX) {
+          float bmax; int tmax;
+          window_extremum9<true>(s2, bmax, tmax);
+          const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
+          atomicAdd(&bins[b][NBR - 1][myrep][tmax], cb * g);
+          sb[b] += g * (double)bmax;
+        }
       }
-      if (DO_MIN) window_extremum9<false>(s1, bmin, tmin);
-      if (DO_MAX) window_extremum9<true>(s2, bmax, tmax);
-      if (DO_MIN) {
-        mine[tmin * 256] += ca * g;
-        mine[KK * 256] += g * (double)bmin;
+    }
+  }
+  // coefficient sums: lanes of a wave by shuffles (fixed tree), then the four waves in order
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int b = 0; b < CB; ++b) {
+    double va = sa[b], vb = sb[b];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      va += __shfl_down(va, off, 64);
+      vb += __shfl_down(vb, off, 64);
+    }
+    if (lane == 0) { csum[wave][b][0] = va; csum[wave][b][1] = vb; }
+  }
+  __syncthreads();
+  for (int v = threadIdx.x; v < CB * NBR * 9; v += blockDim.x) {
+    const int b = v / (NBR * 9), r = v - b * (NBR * 9), br = r / 9, t = r - br * 9;
+    if (co0 + b >= p.C_out) continue;
+    double sum = 0.0;
+#pragma unroll
+    for (int q = 0; q < REP; ++q) sum += bins[b][br][q][t];
+    const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+    float* gw = is_max ? grad_w_max : grad_w_min;
+    if (gw) atomicAdd(gw + ((size_t)(co0 + b) * p.C_in + c) * 9 + t, (float)sum);
+  }
+  if (TWO && threadIdx.x < CB * 2) {
+    const int b = threadIdx.x >> 1, which = threadIdx.x & 1;
+    if (co0 + b < p.C_out) {
+      const double sum = csum[0][b][which] + csum[1][b][which] + csum[2][b][which] + csum[3][b][which];
+      float* gc = which ? grad_beta : grad_alpha;
+      if (gc) atomicAdd(gc + (size_t)c * p.C_out + (co0 + b), (float)sum);
+    }
+  }
+}
+
+// All gradients of a 3x3 layer from ONE winner search.  Workgroup = (image n, input channel c, band of input rows), as
+// in the grad_x kernel above: the band of the grad_x plane (fp64) and the input rows its windows read (fp32) live in
+// LDS.  A thread keeps the 9 input values of up to PT of its output pixels in registers and walks the output channels
+// (kernel values and coefficients are wave-uniform scalars, gy is read coalesced).  Per (pixel, c_out) item: 9 adds
+// (shared by both branches in compound mode), the two winner searches, and from their result
+//   grad_x:      one ds_add_f64 per branch at the winner's pixel of the band,
+//   grad_w:      one ds_add_f64 per branch into LDS bins [COB][branch][REP][11] (a lane uses replica lane mod REP; the
+//                odd stride of 11 doubles spreads the replicas over the LDS banks: with a stride that is a multiple
+//                of 32 doubles every replica of a tap sits in the same bank and the adds of a wave serialise),
+//   grad_alpha / grad_beta: g * extremum summed over the thread's pixels in registers, one ds_add_f64 per
+//                (thread, c_out, branch) into a tenth bin.
+// The output channels are walked in chunks of COB (the bins of one chunk fit the LDS next to the band); after a chunk
+// the replicas are added in a fixed order and every value goes into the zero-filled result with one fp32 atomic.
+// An output pixel is scanned by every band its window reaches (for grad_x) but counts for the parameter gradients only
+// in the band that holds the first row of its window that lies inside the image.
+// ONE_BAND: the band is the whole plane (the common case), so every winner lands in it and every scanned pixel counts
+// here: the per-item range checks drop out.
+constexpr int SUMF_PT = 4, SUMF_REP = 8;
+template <int MODE, bool ONE_BAND>
+__global__ __launch_bounds__(256) void sum_bwd_fused3x3_kernel(Params p, const float* __restrict__ x,
+                                                               const float* __restrict__ w_min,
+                                                               const float* __restrict__ w_max,
+                                                               const float* __restrict__ alpha,
+                                                               const float* __restrict__ beta,
+                                                               const float* __restrict__ gy,
+                                                               float* __restrict__ grad_x,
+                                                               float* __restrict__ grad_w_min,
+                                                               float* __restrict__ grad_w_max,
+                                                               float* __restrict__ grad_alpha,
+                                                               float* __restrict__ grad_beta, int TH, int n_bands,
+                                                               int COB) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
+  constexpr int PT = SUMF_PT, REP = SUMF_REP;
+  extern __shared__ double lds_d[];
+  const int band = blockIdx.x % n_bands;
+  const int c = (blockIdx.x / n_bands) % p.C_in;
+  const int n = blockIdx.x / (n_bands * p.C_in);
+  const int r0 = band * TH, r1 = min(r0 + TH, p.H);
+  const int eh = 2 * p.dh;
+  const int oh_lo = max(0, (r0 + p.ph - eh + p.sh - 1) / p.sh);
+  const int oh_hi = min(p.Ho - 1, (r1 - 1 + p.ph) / p.sh);
+  const int xr0 = max(0, oh_lo * p.sh - p.ph), xr1 = min(p.H, oh_hi * p.sh - p.ph + eh + 1);
+  double* const tile = lds_d;                                           // [(r1 - r0) x W]
+  double* const bins = lds_d + (size_t)TH * p.W;                        // [COB][NBR][REP][11]
+  float* const xs = (float*)(bins + (size_t)COB * NBR * REP * 11);      // [(xr1 - xr0) x W]
+  for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) tile[i] = 0.0;
+  const float* xc = x + ((size_t)n * p.C_in + c) * p.H * p.W;
+  if (oh_hi >= oh_lo)
+    for (int i = threadIdx.x; i < (xr1 - xr0) * p.W; i += blockDim.x) xs[i] = xc[(size_t)xr0 * p.W + i];
+  const int rows = max(oh_hi - oh_lo + 1, 0);
+  const int n_pix = rows * p.Wo;
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  double* const mybins = bins + (size_t)(threadIdx.x & (REP - 1)) * 11;
+  const int row_step8 = p.dh * p.W * 8, col_step8 = p.dw * 8;  // byte steps of a tap row / column inside the band
+  for (int cob = 0; cob < p.C_out; cob += COB) {
+    const int ncb = min(COB, p.C_out - cob);
+    __syncthreads();  // the previous chunk's bins have been published (first pass: tile and xs are written)
+    for (int e = threadIdx.x; e < COB * NBR * REP * 11; e += blockDim.x) bins[e] = 0.0;
+    __syncthreads();
+    for (int base = 0; base < n_pix; base += PT * (int)blockDim.x) {
+      // the thread's pixels of this round: window values (padding = NaN: never an extremum), where tap (0, 0) falls
+      // in the band (byte offset, may be negative), which tap rows fall inside the band, whether the pixel counts
+      // for the parameter gradients here
+      float xv[PT][9];
+      int t0off[PT], rowmask[PT];
+      bool live[PT], own[PT];
+      size_t gyoff[PT];
+#pragma unroll
+      for (int k = 0; k < PT; ++k) {
+        const int pix = base + k * (int)blockDim.x + (int)threadIdx.x;
+        live[k] = pix < n_pix;
+        const int pr = live[k] ? pix / p.Wo : 0;
+        const int oh = oh_lo + pr, ow = live[k] ? pix - pr * p.Wo : 0;
+        const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+        rowmask[k] = 0;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const int ih = ih0 + (t / 3) * p.dh, iw = iw0 + (t % 3) * p.dw;
+          const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+          xv[k][t] = ok ? xs[(ih - xr0) * p.W + iw] : __uint_as_float(0x7fc00000u);
+        }
+#pragma unroll
+        for (int ii = 0; ii < 3; ++ii) {
+          const int ih = ih0 + ii * p.dh;
+          if (ih >= r0 && ih < r1) rowmask[k] |= 1 << ii;
+        }
+        t0off[k] = ((ih0 - r0) * p.W + iw0) * 8;
+        // the first row of the window that lies inside the image (ih0 < H always): in exactly one band, and that
+        // band scans this output
+        const int ihv = ih0 >= 0 ? ih0 : (ih0 + p.dh >= 0 ? ih0 + p.dh : ih0 + 2 * p.dh);
+        own[k] = live[k] && ihv >= r0 && ihv < r1;
+        gyoff[k] = (size_t)n * p.C_out * plane + (size_t)oh * p.Wo + ow;
       }
-      if (DO_MAX) {
-        constexpr int b0 = (NBR - 1) * (KK + 1);
-        mine[(b0 + tmax) * 256] += cb * g;
-        mine[(b0 + KK) * 256] += g * (double)bmax;
+      for (int b = 0; b < ncb; ++b) {  // uniform over the workgroup
+        const int co = cob + b;
+        const float* ka = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const float* kb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
+        const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
+        double* const bn = mybins + (size_t)b * NBR * REP * 11;
+        double s_min = 0.0, s_max = 0.0;  // coefficient sums over the thread's pixels
+        bool any_own = false;
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          if (!live[k]) continue;
+          const double g = (double)gy[gyoff[k] + (size_t)co * plane];
+          float s1[9], s2[9];
+#pragma unroll
+          for (int t = 0; t < 9; ++t) {
+            if (DO_MIN) s1[t] = __fadd_rn(xv[k][t], ka[t]);
+            if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xv[k][t], kb[t]);
+          }
+          if (DO_MIN) {
+            float bmin; int t;
+            window_extremum9<false>(s1, bmin, t);
+            const double v = ca * g;
+            const int row = (t * 11) >> 5;
+            if (ONE_BAND || ((rowmask[k] >> row) & 1))
+              atomicAdd((double*)((char*)tile + (t0off[k] + row * row_step8 + (t - 3 * row) * col_step8)), v);
+            if (ONE_BAND || own[k]) {
+              atomicAdd(bn + t, v);
+              s_min += g * (double)bmin;
+            }
+          }
+          if (DO_MAX) {
+            float bmax; int t;
+            window_extremum9<true>(s2, bmax, t);
+            const double v = cb * g;
+            const int row = (t * 11) >> 5;
+            if (ONE_BAND || ((rowmask[k] >> row) & 1))
+              atomicAdd((double*)((char*)tile + (t0off[k] + row * row_step8 + (t - 3 * row) * col_step8)), v);
+            if (ONE_BAND || own[k]) {
+              atomicAdd(bn + (NBR - 1) * REP * 11 + t, v);
+              s_max += g * (double)bmax;
+            }
+          }
+          any_own = any_own || ONE_BAND || own[k];
+        }
+        if (TWO && any_own) {
+          atomicAdd(bn + 9, s_min);
+          atomicAdd(bn + REP * 11 + 9, s_max);
+        }
+      }
+    }
+    __syncthreads();
+    // publish the chunk: replicas in a fixed order, one fp32 atomic per value
+    for (int v = threadIdx.x; v < ncb * NBR * 10; v += blockDim.x) {
+      const int b = v / (NBR * 10), r = v - b * (NBR * 10), br = r / 10, t = r - br * 10;
+      double sum = 0.0;
+#pragma unroll
+      for (int q = 0; q < REP; ++q) sum += bins[((size_t)(b * NBR + br) * REP + q) * 11 + t];
+      const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+      const int co = cob + b;
+      if (t < 9) {
+        float* gw = is_max ? grad_w_max : grad_w_min;
+        if (gw) atomicAdd(gw + ((size_t)co * p.C_in + c) * 9 + t, (float)sum);
+      } else if (TWO) {
+        float* gc = is_max ? grad_beta : grad_alpha;
+        if (gc) atomicAdd(gc + (size_t)c * p.C_out + co, (float)sum);
       }
     }
   }
   __syncthreads();
-  for (int h = 128; h > 0; h >>= 1) {
-    if ((int)threadIdx.x < h)
-#pragma unroll
-      for (int v = 0; v < NV; ++v) mine[v * 256] += mine[v * 256 + h];
-    __syncthreads();
-  }
-  for (int v = threadIdx.x; v < NV; v += blockDim.x) {
-    const int br = v / (KK + 1), k = v % (KK + 1);
-    const bool is_max = DO_MAX && (NBR == 1 || br == 1);
-    const float val = (float)lds_d[v * 256];
-    if (k < KK) {
-      float* gw = is_max ? grad_w_max : grad_w_min;
-      if (gw) atomicAdd(gw + ((size_t)co * p.C_in + c) * KK + k, val);
-    } else if (TWO) {
-      float* gc = is_max ? grad_beta : grad_alpha;
-      if (gc) atomicAdd(gc + (size_t)c * p.C_out + co, val);
-    }
+  if (grad_x) {
+    float* gxc = grad_x + ((size_t)n * p.C_in + c) * p.H * p.W + (size_t)r0 * p.W;
+    for (int i = threadIdx.x; i < (r1 - r0) * p.W; i += blockDim.x) gxc[i] = (float)tile[i];
   }
 }
 
@@ -638,6 +837,45 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
 template <int MODE>
 hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s) {
   const int KK = p.KH * p.KW;
+  {
+    // 3x3 windows with the input gradient AND parameter gradients wanted: one kernel, one winner search
+    float* fmin = g.grad_w_min;
+    float* fmax = g.grad_w_max;
+    if (MODE == TCONV_COMPOUND) fmin = fmax = (g.grad_w_min ? g.grad_w_min : g.grad_w_max);
+    const bool want_par = (MODE != TCONV_MAX && fmin) || (MODE != TCONV_MIN && fmax) || g.grad_alpha || g.grad_beta;
+    const char* sep = getenv("TCONV_SUM_BWD");  // testing aid: "separate" keeps the two-kernel path
+    if (p.KH == 3 && p.KW == 3 && g.grad_x && want_par && !(sep && strcmp(sep, "separate") == 0)) {
+      constexpr int NBR = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) ? 2 : 1;
+      int COB = p.C_out < 16 ? p.C_out : 16;  // 16 channels x 16 replicas x 2 branches x 11 doubles = 45 KB
+      const size_t bins_bytes = (size_t)SUMF_REP * COB * NBR * 11 * 8;
+      const size_t budget = 60 * 1024;
+      const int eh = p.dh * 2;
+      int TH = p.H;
+      auto bytes = [&](int th) {
+        const long long xrows = (long long)th + 2LL * eh + p.sh;
+        return (size_t)th * p.W * 8 + bins_bytes + (size_t)(xrows < p.H ? xrows : p.H) * p.W * 4;
+      };
+      while (TH > 1 && bytes(TH) > budget) TH = (TH + 1) / 2;
+      const int n_bands = (p.H + TH - 1) / TH;
+      const long long blocks = (long long)p.N * p.C_in * n_bands;
+      if (bytes(TH) <= 64 * 1024 && blocks <= 0x7fffffffLL) {
+        const size_t nw = (size_t)p.C_out * p.C_in * KK, nab = (size_t)p.C_in * p.C_out;
+        if (MODE != TCONV_MAX) zero_fill(fmin, nw, s);
+        if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(fmax, nw, s);
+        zero_fill(g.grad_alpha, nab, s);
+        zero_fill(g.grad_beta, nab, s);
+        if (n_bands == 1)
+          hipLaunchKernelGGL((sum_bwd_fused3x3_kernel<MODE, true>), dim3((unsigned)blocks), dim3(256), bytes(TH), s, p,
+                             a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax, g.grad_alpha,
+                             g.grad_beta, TH, n_bands, COB);
+        else
+          hipLaunchKernelGGL((sum_bwd_fused3x3_kernel<MODE, false>), dim3((unsigned)blocks), dim3(256), bytes(TH), s, p,
+                             a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax, g.grad_alpha,
+                             g.grad_beta, TH, n_bands, COB);
+        return hipGetLastError();
+      }
+    }
+  }
   if (g.grad_x) {
     // band of input rows per workgroup: fp64 sums (8 B) plus the fp32 input rows its windows read
     const size_t budget = 60 * 1024;
@@ -681,10 +919,17 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
     while (nt > 64 && (size_t)NBR * (KK + 1) * nt * sizeof(double) > 64 * 1024) nt /= 2;
     const size_t lds = (size_t)NBR * (KK + 1) * nt * sizeof(double);
     if (lds > 64 * 1024) return hipErrorInvalidValue;  // kernel window too large for this kernel
-    if (p.KH == 3 && p.KW == 3 && (size_t)p.N * p.C_in * p.H * p.W * 4 < 0xfffff000ull)  // 32-bit byte offsets into x
-      hipLaunchKernelGGL(sum_bwd_w3x3_kernel<MODE>, grid, dim3(256), (size_t)NBR * 10 * 256 * sizeof(double), s, p,
-                         a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, gmin, gmax, g.grad_alpha, g.grad_beta,
-                         n_per_block);
+    if (p.KH == 3 && p.KW == 3 && (size_t)p.N * p.C_in * p.H * p.W * 4 < 0xfffff000ull) {  // 32-bit byte offsets into x
+      const long long n_coblocks = (p.C_out + SUMW_CB - 1) / SUMW_CB, wgs = n_coblocks * p.C_in;
+      int sl = (int)((2048 + wgs - 1) / wgs);  // enough workgroups to fill the chip several times over
+      if (sl > p.N) sl = p.N;
+      if (sl > 65535) sl = 65535;
+      const int npb = (p.N + sl - 1) / sl;
+      if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+      hipLaunchKernelGGL(sum_bwd_w3x3_blk_kernel<MODE>, dim3((unsigned)wgs, (unsigned)((p.N + npb - 1) / npb)), dim3(256),
+                         0, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, gmin, gmax, g.grad_alpha, g.grad_beta,
+                         npb, (int)n_coblocks);
+    }
     else
       hipLaunchKernelGGL(sum_bwd_w_kernel<MODE>, grid, dim3(nt), lds, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta,
                        g.gy, gmin, gmax, g.grad_alpha, g.grad_beta, n_per_block);

@@ -66,6 +66,20 @@ def test_sum_generic_forward_kernel(cfg):
         _check(cfg.with_(mode=mode), kernel="generic")
 
 
+@pytest.mark.parametrize("cfg", [SHAPES[1], SHAPES[3], SHAPES[4], SHAPES[11], SHAPES[12]], ids=lambda c: c.name)
+def test_sum_backward_in_separate_calls_and_kernels(cfg):
+    """The fused backward kernel serves calls that want the input gradient and parameter gradients together; here the
+    separate kernels run (TCONV_SUM_BWD=separate), as they do for calls that want only one of the two."""
+    import os
+    os.environ["TCONV_SUM_BWD"] = "separate"
+    try:
+        for mode in MODES:
+            _check(cfg.with_(mode=mode))
+        _check(cfg.with_(mode="compound"), integer=True)
+    finally:
+        os.environ.pop("TCONV_SUM_BWD", None)
+
+
 def test_sum_layer_at_a_benchmark_size():
     """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
     cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
