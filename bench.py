@@ -472,12 +472,40 @@ def main() -> int:
                       "pairs": p5, "ms_forward": round(t_f5, 4), "forward_gops": round(p5 / (t_f5 * 1e-3) / 1e9, 1),
                       "frac": round(p5 * 2.0 / (t_f5 * 1e-3) / LANE_OPS_PER_S, 4),
                       "ms_step": round(t_s5, 4), "step_gops": round(p5 / (t_s5 * 1e-3) / 1e9, 1)})
+        del stack, gf, gs
+        torch.cuda.empty_cache()
+        # the same net as ONE end-to-end training step (fused batch-norm / shortcut epilogues, head, all gradients)
+        import copy
+        nargs = copy.copy(args)
+        nargs.steps, nargs.warmup, nargs.no_cpu_baseline = 10, 3, True
+        net = bench_net(nargs, torch, tb, emit=False)
+        table.append({"layer": "cfg5net (end-to-end training step of the ResNet-20-style net, glue included)",
+                      "mode": "parallel", "storage": "f32", "pairs": net["config"]["pairs_per_step"],
+                      "ms_forward": net["ms_forward"], "ms_backward": net["ms_backward"],
+                      "ms_step": net["ms_per_step"], "step_gops": net["value"], "frac": net["roofline"]["frac"],
+                      "graph_replays_checked_against_eager": net["config"]["graph_replays_checked_against_eager"]})
+        torch.cuda.empty_cache()
+        # the Sum-channel compound layer on the cfg2 shape (what the paper's networks are built from)
+        Ls = Layer(CONFIGS["cfg2_main"], "sum")
+        for _ in range(3):
+            Ls.fwd(); Ls.bwd()
+        torch.cuda.synchronize()
+        t_sf = time_loop(lambda i: Ls.fwd(), 10)
+        t_sb = time_loop(lambda i: Ls.bwd(), 10)
+        ps = Ls.cfg.pairs
+        table.append({"layer": "cfg2_main as a Sum-channel layer (tconv_sum_forward / tconv_sum_backward, all five "
+                               "gradients)", "mode": "compound", "storage": "f32", "pairs": ps,
+                      "forward_kernel": tb.tconv_sum_forward_kernel_name(Ls.d),
+                      "ms_forward": round(t_sf, 4), "forward_gops": round(ps / (t_sf * 1e-3) / 1e9, 1),
+                      "frac": round(ps * 1.5 / (t_sf * 1e-3) / LANE_OPS_PER_S, 4),
+                      "ms_backward": round(t_sb, 4), "step_gops": round(ps / ((t_sf + t_sb) * 1e-3) / 1e9, 1)})
+        del Ls
         out["layers"] = table
     print(json.dumps(out), flush=True)
     return 0
 
 
-def bench_net(args, torch, tb) -> int:
+def bench_net(args, torch, tb, emit: bool = True):
     """--workload cfg5net: ONE end-to-end training step of the all-tropical ResNet-20-style net (Sec. 5 TCNN BasicBlock:
     TropConv -> BN -> TropConv -> BN -> + shortcut, no ReLU), [256, 3, 32, 32] synthetic images, every conv in parallel
     mode.  Forward: 19 tconv_forward_fused calls chained layer to layer (batch norm folded to a per-channel scale and
@@ -667,6 +695,8 @@ def bench_net(args, torch, tb) -> int:
         out["cpu_baseline"] = cpu_baseline([(c, make_inputs(c)) for c in cfgs], args.cpu_seconds, "full",
                                            [(None, None)] * len(cfgs))
         out["cpu_baseline"]["sample"] += " (the 19 layers' forward and backward calls; no glue)"
+    if not emit:
+        return out
     print(json.dumps(out), flush=True)
     return 0
 
