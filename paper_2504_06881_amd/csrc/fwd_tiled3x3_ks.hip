@@ -1,0 +1,51 @@
+// Tiled 3x3 forward, the form in which the four waves of a workgroup split the input channels of one group of four
+// output channels (four times as many, a quarter as long workgroups).  Instantiations and their choice; the kernel is
+// in fwd_tiled3x3_kernel.h.
+#include "fwd_tiled3x3_kernel.h"
+
+namespace tconv {
+namespace {
+
+template <int MODE, int S, int D>
+hipError_t launch_ks(const Params& p, const void* x, const float* w_min, const float* w_max, const FwdArgs& a,
+                     hipStream_t s) {
+  return p.pad_zero ? launch_tn<MODE, S, D, 4, true, float, false, true>(p, x, w_min, w_max, a, s)
+                    : launch_tn<MODE, S, D, 4, false, float, false, true>(p, x, w_min, w_max, a, s);
+}
+
+template <int MODE>
+hipError_t launch_ks_geo(const Params& p, const void* x, const float* w_min, const float* w_max, const FwdArgs& a,
+                         hipStream_t s) {
+  if (p.sh == 2) return launch_ks<MODE, 2, 1>(p, x, w_min, w_max, a, s);
+  return p.dh == 1 ? launch_ks<MODE, 1, 1>(p, x, w_min, w_max, a, s) : launch_ks<MODE, 1, 2>(p, x, w_min, w_max, a, s);
+}
+
+}  // namespace
+
+// Where it applies: fp32 storage, modes max / min / compound / parallel, one channel pair per wave or more (chosen by
+// itself from two pairs per wave), more than two output channels.  Where it pays: workgroups of the plain form all run equally long, so a grid of them occupies
+// the chip in whole rounds of `resident` workgroups; the split form has four times as many, a quarter as long
+// workgroups and costs a few per cent in the exchange and in set-up done four times.  It is chosen unless the plain
+// grid fills its rounds to 95 % (measured, plain -> split, ms: 3.06 rounds 0.936 -> 0.849, 1.75 rounds 0.610 -> 0.547,
+// 0.875 rounds 0.961 -> 0.853, a quarter round 0.111 -> 0.075; 2.0 rounds 0.439 -> 0.462 and 1.587 -> 1.630, 4.0 rounds
+// 1.499 -> 1.494).  TCONV_FWD_KSPLIT=1 asks for it wherever it applies, 0 never (tuning and testing aid).
+bool forward_tiled3x3_ks_wanted(const Params& p, long long plain_workgroups, long long resident) {
+  if (p.mode > TCONV_PARALLEL || p.C_in < 2 * tile::WAVES || p.C_out <= 2) return false;
+  if (const char* e = getenv("TCONV_FWD_KSPLIT")) return atoi(e) == 1;
+  if (p.C_in < 4 * tile::WAVES) return false;
+  const long long rounds = (plain_workgroups + resident - 1) / resident;
+  return plain_workgroups * 100 < rounds * resident * 95;
+}
+
+hipError_t launch_forward_tiled3x3_ks(const Params& p, const void* x, const float* w_min, const float* w_max,
+                                      const FwdArgs& a, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_ks_geo<TCONV_MAX>(p, x, w_min, w_max, a, s);
+    case TCONV_MIN: return launch_ks_geo<TCONV_MIN>(p, x, w_min, w_max, a, s);
+    case TCONV_COMPOUND: return launch_ks_geo<TCONV_COMPOUND>(p, x, w_min, w_max, a, s);
+    case TCONV_PARALLEL: return launch_ks_geo<TCONV_PARALLEL>(p, x, w_min, w_max, a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace tconv

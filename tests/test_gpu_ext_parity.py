@@ -24,7 +24,10 @@ def _check_ext(cfg, ep_kind="", alpha_beta=None, integer=False, kernel=None, tn=
             os.environ["TCONV_FORWARD_KERNEL"] = kernel
         for t in tn:
             os.environ.pop("TCONV_FWD_TN", None)
-            if t:
+            os.environ["TCONV_FWD_KSPLIT"] = "1" if t == "ks" else "0" if t else ""
+            if not t:
+                os.environ.pop("TCONV_FWD_KSPLIT")
+            elif t != "ks":
                 os.environ["TCONV_FWD_TN"] = str(t)
             hip = hs.run_hip_ext(cfg, inp, ep, backward=backward)
             what = f"[{cfg.name} {cfg.mode} {cfg.dtype} pad={cfg.pad_mode} ep={ep_kind} int={integer} k={kernel} tn={t}] "

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 MODES = ("max", "min", "compound", "parallel")
 
 
-KNOBS = ("TCONV_FORWARD_KERNEL", "TCONV_FWD_TN")
+KNOBS = ("TCONV_FORWARD_KERNEL", "TCONV_FWD_TN", "TCONV_FWD_KSPLIT")
 
 
 def tiled_blocks4(cfg):
@@ -28,14 +28,22 @@ def tiled_blocks4(cfg):
     return ((units + 63) // 64) * (((cfg.C_out + 3) // 4 + 3) // 4)
 
 
+def picks_split(cfg):
+    """True when the library splits the input channels over the waves of a workgroup on its own: at least 16 of them,
+    and the plain grid fills its rounds of 512 resident workgroups to less than 95 %."""
+    b = tiled_blocks4(cfg)
+    return cfg.C_in >= 16 and cfg.C_out > 2 and b * 100 < ((b + 511) // 512) * 512 * 95
+
+
 def picks_tn4(cfg):
     """True when the library runs the 4-channels-per-lane instantiation of the tiled kernel on its own."""
     return tiled_blocks4(cfg) * (2 if cfg.stride == 1 else 4) > 512 or cfg.C_out <= 2
 
 
 def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None, seed=None, tn=(None,)):
-    """One oracle run, one HIP run per entry of tn (None: the library's own choice of output channels per lane of
-    the tiled forward kernel; 2 / 4: that instantiation forced), each compared with the oracle."""
+    """One oracle run, one HIP run per entry of tn (None: the library's own choice of the tiled forward kernel's form;
+    2 / 4: that many output channels per lane forced, input channels not split; "ks": the form that splits the input
+    channels over the waves of a workgroup forced wherever it applies), each compared with the oracle."""
     inp = make_inputs(cfg, alpha_beta=alpha_beta, integer=integer, seed=seed)
     ref = hs.run_oracle(cfg, inp)
     old = {k: os.environ.pop(k, None) for k in KNOBS}
@@ -45,7 +53,10 @@ def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None
             os.environ["TCONV_FORWARD_KERNEL"] = kernel
         for t in tn:
             os.environ.pop("TCONV_FWD_TN", None)
-            if t:
+            os.environ["TCONV_FWD_KSPLIT"] = "1" if t == "ks" else "0" if t else ""
+            if not t:
+                os.environ.pop("TCONV_FWD_KSPLIT")
+            elif t != "ks":
                 os.environ["TCONV_FWD_TN"] = str(t)
             hip = hs.run_hip(cfg, inp, branch_outputs=branch_outputs)
             what = f"[{cfg.name} {cfg.mode} {cfg.dtype} ab={alpha_beta} int={integer} k={kernel} tn={t}] "
@@ -59,7 +70,9 @@ def _check(cfg, alpha_beta=None, integer=False, branch_outputs=True, kernel=None
     return hip, ref
 
 
-BOTH_TN = (2, 4)   # both instantiations of the tiled 3x3 forward kernel (small layers pick 2, large ones 4)
+# every form of the tiled 3x3 forward kernel: 2 or 4 output channels per lane (small layers pick 2, large ones 4),
+# and the input channels split over the waves of a workgroup (layers whose grid fills its rounds badly pick it)
+BOTH_TN = (2, 4, "ks")
 
 
 @pytest.mark.parametrize("kernel", [None, "generic"])
@@ -106,6 +119,11 @@ RAGGED = [
     LayerCfg("r_cin350", 1, 350, 6, 8, 3, seed=34),
     LayerCfg("r_cin131_s2", 1, 131, 9, 10, 6, stride=2, seed=35),
     LayerCfg("r_cin260_s2", 1, 260, 9, 10, 5, stride=2, seed=36),
+    # enough input channels for the form that splits them over four waves, with unequal and odd shares, a ragged
+    # output-channel tail (a workgroup whose last waves have no channel to finish), dilation 2 and stride 2
+    LayerCfg("r_cin9_d2", 2, 9, 18, 26, 6, pad=2, dil=2, seed=37),
+    LayerCfg("r_cin13_s2", 3, 13, 21, 27, 7, stride=2, seed=38),
+    LayerCfg("r_cin11", 3, 11, 19, 23, 10, seed=39),
 ]
 
 # Ragged layers large enough for the library to choose 4 output channels per lane by itself: many images with an
@@ -115,6 +133,13 @@ RAGGED_LARGE = [
     LayerCfg("rl_many_cout", 64, 5, 19, 23, 70, seed=42),
     LayerCfg("rl_s2", 200, 7, 33, 37, 22, stride=2, seed=43),
     LayerCfg("rl_d2", 210, 3, 21, 27, 9, pad=2, dil=2, seed=44),
+]
+
+# Ragged layers for which the library splits the input channels over the waves of a workgroup by itself: grids of
+# plain workgroups that fill a quarter of a round and 5.2 rounds of the chip's 512 resident workgroups.
+RAGGED_SPLIT = [
+    LayerCfg("rs_cin19", 150, 19, 19, 23, 13, seed=45),
+    LayerCfg("rs_cin17_s2", 1000, 17, 33, 37, 22, stride=2, seed=46),
 ]
 
 
@@ -167,6 +192,15 @@ def test_ragged_shapes_that_pick_four_channels_per_lane(cfg):
     _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
     _check(cfg.with_(mode="compound", dtype="bf16"), integer=True)
     _check(cfg.with_(mode="parallel", dtype="bf16"), alpha_beta="random")
+
+
+@pytest.mark.parametrize("cfg", RAGGED_SPLIT, ids=lambda c: c.name)
+def test_ragged_shapes_that_split_the_input_channels(cfg):
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3" and picks_split(cfg)
+    for mode in MODES:
+        _check(cfg.with_(mode=mode), alpha_beta="random" if mode in ("compound", "parallel") else None)
+    _check(cfg.with_(mode="compound"), integer=True)
+    _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
 
 
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10]], ids=lambda c: c.name)
@@ -256,7 +290,7 @@ def test_resnet20_layers_one_each():
         if key in seen:
             continue
         seen.add(key)
-        _check(cfg, tn=(None, 4))
+        _check(cfg, tn=(None, 4, "ks"))
 
 
 def test_resnet20_layers_at_the_benchmark_batch():
