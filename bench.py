@@ -510,9 +510,8 @@ def bench_net(args, torch, tb, emit: bool = True):
     TropConv -> BN -> TropConv -> BN -> + shortcut, no ReLU), [256, 3, 32, 32] synthetic images, every conv in parallel
     mode.  Forward: 19 tconv_forward_fused calls chained layer to layer (batch norm folded to a per-channel scale and
     shift, the shortcut added in the kernel that writes y), global average pool, a 10-way linear head and a squared
-    loss.  Backward: through the head, then per layer tconv_backward (gradient of the input and of both kernel tensors;
-    the batch-norm scale enters as the branch coefficients), tconv_backward_bias (shift) and
-    tconv_backward_alpha_beta (scale).  Pool, head, loss, the shortcut's subsampling / channel padding and the
+    loss.  Backward: through the head, then per layer tconv_backward_input and tconv_backward_params (both kernel
+    tensors, the shift and the scale from one pass over gy; the batch-norm scale enters as the branch coefficients).  Pool, head, loss, the shortcut's subsampling / channel padding and the
     gradient adds at the shortcuts are torch glue: inside the timed step, outside the pair count."""
     from paper_2504_06881_amd.inputs import resnet20_layers, make_inputs
     dev = torch.device("cuda:0")
@@ -543,8 +542,7 @@ def bench_net(args, torch, tb, emit: bool = True):
         o.gw_min, o.gw_max = torch.empty_like(o.w_min), torch.empty_like(o.w_max)
         o.gshift, o.ga, o.gb = (torch.empty(cfg.C_out, device=dev) for _ in range(3))
         o.gscale = torch.empty(cfg.C_out, device=dev)
-        nb = max(tb.tconv_workspace_bytes(o.d, k) for k in ("backward", "backward_bias", "backward_alpha_beta",
-                                                            "backward_weight"))
+        nb = tb.tconv_workspace_bytes(o.d, "backward_params")
         o.ws = torch.empty(max(nb // 8, 1), device=dev, dtype=torch.float64)
         layers.append(o)
     x0 = torch.from_numpy(make_inputs(cfgs[0])["x"]).to(dev)
@@ -588,11 +586,9 @@ def bench_net(args, torch, tb, emit: bool = True):
 
     def conv_backward(o, gy, need_gx=True):
         if need_gx:
-            tb.tconv_backward(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.gx, o.gw_min, o.gw_max, o.ws)
-        else:
-            tb.tconv_backward_weight(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.gw_min, o.gw_max, o.ws)
-        tb.tconv_backward_bias(o.d, gy, o.gshift, o.ws)
-        tb.tconv_backward_alpha_beta(o.d, gy, o.y_min, o.y_max, o.ga, o.gb, o.ws)
+            tb.tconv_backward_input(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.gx)
+        tb.tconv_backward_params(o.d, gy, o.scale, o.scale, o.idx_min, o.idx_max, o.y_min, o.y_max, o.gw_min, o.gw_max,
+                                 o.ga, o.gb, o.gshift, o.ws)
         torch.add(o.ga, o.gb, out=o.gscale)
 
     def backward():

@@ -87,7 +87,8 @@ enum tconv_op {
   TCONV_OP_BACKWARD_WEIGHT = 2,
   TCONV_OP_BACKWARD_ALPHA_BETA = 3,
   TCONV_OP_BACKWARD = 4,  /* tconv_backward: both gradients in one call */
-  TCONV_OP_BACKWARD_BIAS = 5
+  TCONV_OP_BACKWARD_BIAS = 5,
+  TCONV_OP_BACKWARD_PARAMS = 6  /* tconv_backward_params: every parameter gradient in one call */
 };
 
 enum tconv_status {
@@ -242,6 +243,25 @@ int tconv_backward(const tconv_desc* desc, const float* gy, const float* alpha, 
 int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const void* y_min,
                               const void* y_max, float* grad_alpha, float* grad_beta, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Every parameter gradient of a layer in one call, from one pass over gy where the layer allows it: the kernel
+ * gradient(s) of tconv_backward_weight (Sec. 3.2: the winner of every output receives its gradient), grad_alpha /
+ * grad_beta of tconv_backward_alpha_beta (Sec. 3.3: the combine is linear in its coefficients) and grad_bias of
+ * tconv_backward_bias, each argument as in those calls.  grad_alpha, grad_beta (compound and parallel mode only) and
+ * grad_bias are optional (NULL: not computed); the kernel gradient(s) of the mode are required.
+ *   workspace  optional, tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_PARAMS) bytes, 8-byte aligned
+ *            (TCONV_E_WORKSPACE if smaller).  With it every result is a sum of fp64 partial sums per batch slice added
+ *            in a fixed order and rounded to fp32 once, and for fp32 storage and windows whose histogram fits on chip
+ *            (3x3 layers up to 455 input channels, 910 with one kernel tensor) one kernel reads gy, the winner indices and the branch outputs
+ *            ONCE for all of them, followed by one reduction - three launches fewer than the separate calls, which is
+ *            what a training step of a small layer is made of.  With NULL, or for other layers, the separate kernels
+ *            run (NULL: their fp32-atomic forms).
+ */
+int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                          const int32_t* idx_min, const int32_t* idx_max, const void* y_min, const void* y_max,
+                          float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
+                          float* grad_bias, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Sum-channel layers (fp32 only; TCONV_E_UNSUPPORTED for bf16).  Base operators of Sec. 3.1 for one

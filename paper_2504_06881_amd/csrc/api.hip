@@ -89,11 +89,22 @@ int tconv_out_shape(const tconv_desc* desc, int32_t* H_out, int32_t* W_out) {
   return TCONV_OK;
 }
 
+namespace {
+// tconv_backward_params: the one-pass form wants fp32 branch outputs and a window whose histogram fits LDS; otherwise
+// the separate kernels run, the kernel gradient's scratch first and the two-sums-per-slice scratch behind it
+bool params_one_pass(const Params& p, int dtype) { return dtype == TCONV_F32 && backward_params_workspace(p) != 0; }
+size_t params_split_offset(const Params& p) { return (backward_weight_workspace(p) + 255) & ~(size_t)255; }
+size_t params_workspace(const Params& p, int dtype) {
+  if (params_one_pass(p, dtype)) return backward_params_workspace(p);
+  return params_split_offset(p) + backward_alpha_beta_workspace(p);
+}
+}  // namespace
+
 int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
-  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_BIAS) return TCONV_E_INVAL;
+  if (!bytes || op < TCONV_OP_FORWARD || op > TCONV_OP_BACKWARD_PARAMS) return TCONV_E_INVAL;
   *bytes = 0;
   if (op == TCONV_OP_BACKWARD_BIAS) *bytes = backward_alpha_beta_workspace(p);  // the same slices, two sums each
   // forward: only the tiled kernel with bf16 storage stages anything (fp32 copies of x and the kernels)
@@ -107,6 +118,10 @@ int tconv_workspace_bytes(const tconv_desc* desc, int32_t op, size_t* bytes) {
   }
   if (op == TCONV_OP_BACKWARD_ALPHA_BETA && (p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL))
     *bytes = backward_alpha_beta_workspace(p);
+  if (op == TCONV_OP_BACKWARD_PARAMS) {
+    p.mode = backward_mode(p.mode);
+    *bytes = params_workspace(p, desc->dtype);
+  }
   return TCONV_OK;
 }
 
@@ -286,6 +301,46 @@ int tconv_backward_alpha_beta(const tconv_desc* desc, const float* gy, const voi
   own_status();
   const hipError_t e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta, partial,
                                                   (hipStream_t)hip_stream);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* alpha, const float* beta,
+                          const int32_t* idx_min, const int32_t* idx_max, const void* y_min, const void* y_max,
+                          float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
+                          float* grad_bias, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy) return TCONV_E_INVAL;
+  if ((grad_alpha || grad_beta) && p.mode != TCONV_COMPOUND && p.mode != TCONV_PARALLEL) return TCONV_E_INVAL;
+  if ((grad_alpha && !y_min) || (grad_beta && !y_max)) return TCONV_E_INVAL;
+  p.mode = backward_mode(p.mode);
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  switch (p.mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, params_workspace(p, desc->dtype), &partial)) return TCONV_E_WORKSPACE;
+  const BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  hipStream_t s = (hipStream_t)hip_stream;
+  own_status();
+  if (partial && params_one_pass(p, desc->dtype)) {
+    const hipError_t e = launch_backward_params(p, a, (const float*)y_min, (const float*)y_max, grad_w_min, grad_w_max,
+                                                grad_alpha, grad_beta, grad_bias, partial, s);
+    return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+  }
+  // the separate kernels, each in its deterministic form when there is scratch; the two small reductions share theirs
+  // (they follow each other on the stream)
+  double* const part_w = (partial && backward_weight_workspace(p)) ? partial : nullptr;
+  double* const part_ab = partial ? (double*)((char*)partial + params_split_offset(p)) : nullptr;
+  hipError_t e = launch_backward_weight(p, a, grad_w_min, grad_w_max, part_w, s);
+  if (e == hipSuccess && (grad_alpha || grad_beta))
+    e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta, part_ab, s);
+  if (e == hipSuccess && grad_bias) e = launch_backward_bias(p, gy, grad_bias, part_ab, s);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 

@@ -510,16 +510,25 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
 // flushes the non-zero bins (rounded to fp32 once) with global atomics.
 // NHIST = 1: a single destination (max, min, and compound where both branches share
 // one grad_w); NHIST = 2: parallel (min branch -> grad_w_min, max branch -> grad_w_max).
-template <int MODE>
+// EXTRA (two-stage form only): the same pass also sums gy, gy * y_min and gy * y_max over the slice (the gradients
+// of a bias and of the combine coefficients, Sec. 3.3) into three more fp64 slots behind the histogram.
+struct ParamExtras {
+  const float* y_min;  // NULL: no grad_alpha
+  const float* y_max;  // NULL: no grad_beta
+};
+constexpr int N_EXTRA = 3;  // bias, alpha, beta
+
+template <int MODE, bool EXTRA>
 __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ gw_min,
                                                               float* __restrict__ gw_max,
-                                                              int n_per_block, double* __restrict__ partial) {
+                                                              int n_per_block, double* __restrict__ partial,
+                                                              ParamExtras ex) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX);
   constexpr bool DO_MAX = (MODE != TCONV_MIN);
   constexpr bool SCALED = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NHIST = (MODE == TCONV_PARALLEL) ? 2 : 1;
-  HIP_DYNAMIC_SHARED(double, hist)  // NHIST * K sums
+  HIP_DYNAMIC_SHARED(double, hist)  // NHIST * K sums; EXTRA: + 3 totals + 3 x 16 per-wave sums
   const int co = blockIdx.x;
   const int n0 = blockIdx.y * n_per_block;
   const int n1 = min(n0 + n_per_block, p.N);
@@ -534,6 +543,7 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
   const int plane = p.Ho * p.Wo;
   const int n_start = n0 + threadIdx.x / plane, q_start = threadIdx.x % plane;
   const int dn = bd / plane, dq = bd % plane;
+  double s_bias = 0.0, s_alpha = 0.0, s_beta = 0.0;
   // items (image, pixel) of this slice, pixel-major; four per thread in flight
   {
     constexpr int UB = 4;
@@ -541,7 +551,7 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
     while (n < n1) {
       size_t ov[UB];
       bool okv[UB];
-      float gv[UB];
+      float gv[UB], ymn[UB], ymx[UB];
       int kmn[UB], kmx[UB];
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -556,10 +566,18 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
         gv[u] = a.gy[ov[u]];
         if (DO_MIN) kmn[u] = a.idx_min[ov[u]];
         if (DO_MAX) kmx[u] = a.idx_max[ov[u]];
+        if (EXTRA && ex.y_min) ymn[u] = ex.y_min[ov[u]];
+        if (EXTRA && ex.y_max) ymx[u] = ex.y_max[ov[u]];
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         if (!okv[u]) continue;
+        if (EXTRA) {
+          const double g = (double)gv[u];
+          s_bias += g;
+          if (ex.y_min) s_alpha += g * (double)ymn[u];
+          if (ex.y_max) s_beta += g * (double)ymx[u];
+        }
         if (DO_MIN && (unsigned)kmn[u] < (unsigned)K)
           atomicAdd(hmin + kmn[u], SCALED ? (double)ca * (double)gv[u] : (double)gv[u]);
         if (DO_MAX && (unsigned)kmx[u] < (unsigned)K)
@@ -567,10 +585,33 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
       }
     }
   }
+  if (EXTRA) {  // a wave's three sums (butterfly), then the 16 waves' in wave order: a fixed order of additions
+    double* wsum = hist + NHIST * K + N_EXTRA;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      s_bias += __shfl_xor(s_bias, off);
+      s_alpha += __shfl_xor(s_alpha, off);
+      s_beta += __shfl_xor(s_beta, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+      const int w = threadIdx.x >> 6;
+      wsum[w] = s_bias; wsum[16 + w] = s_alpha; wsum[32 + w] = s_beta;
+    }
+  }
   __syncthreads();
+  if (EXTRA) {
+    if (threadIdx.x < N_EXTRA) {
+      const double* wsum = hist + NHIST * K + N_EXTRA + 16 * threadIdx.x;
+      double t = 0.0;
+      for (int w = 0; w < bd / 64; ++w) t += wsum[w];
+      hist[NHIST * K + threadIdx.x] = t;
+    }
+    __syncthreads();
+  }
   if (partial) {  // two-stage form: the fp64 histogram of this (batch slice, channel) as it is; a second kernel adds the slices
-    double* dst = partial + ((size_t)blockIdx.y * p.C_out + co) * (size_t)(NHIST * K);
-    for (int k = threadIdx.x; k < NHIST * K; k += bd) dst[k] = hist[k];
+    const int NH = NHIST * K + (EXTRA ? N_EXTRA : 0);
+    double* dst = partial + ((size_t)blockIdx.y * p.C_out + co) * (size_t)NH;
+    for (int k = threadIdx.x; k < NH; k += bd) dst[k] = hist[k];
     return;
   }
   float* dmin = (MODE == TCONV_MAX) ? gw_max : gw_min;  // NHIST == 1: the single destination
@@ -599,6 +640,30 @@ __global__ __launch_bounds__(256) void bwd_weight_reduce_kernel(const double* __
 #pragma unroll 8
       for (int sl = 0; sl < slices; ++sl) v += src[(size_t)sl * per_slice];
       (h == 0 ? dst0 : dst1)[e] = (float)v;
+    }
+  }
+}
+
+// The same second stage for the pass that also carries the three extra sums: a slice's record per output channel is
+// nhist * K bins followed by the sums of gy, gy * y_min, gy * y_max.
+__global__ __launch_bounds__(256) void bwd_params_reduce_kernel(const double* __restrict__ partial,
+                                                                float* __restrict__ dst0, float* __restrict__ dst1,
+                                                                float* __restrict__ grad_bias,
+                                                                float* __restrict__ grad_alpha,
+                                                                float* __restrict__ grad_beta, int nhist, int K,
+                                                                int C_out, int slices) {
+  const size_t NH = (size_t)nhist * K + N_EXTRA, total = (size_t)C_out * NH;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const size_t co = e / NH, r = e - co * NH;
+    const double* src = partial + e;
+    double v = 0.0;
+#pragma unroll 8
+    for (int sl = 0; sl < slices; ++sl) v += src[(size_t)sl * total];
+    if (r < (size_t)K) dst0[co * K + r] = (float)v;
+    else if (r < (size_t)nhist * K) dst1[co * K + (r - K)] = (float)v;
+    else {
+      float* const d = (r == (size_t)nhist * K) ? grad_bias : (r == (size_t)nhist * K + 1) ? grad_alpha : grad_beta;
+      if (d) d[co] = (float)v;
     }
   }
 }
@@ -674,16 +739,16 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
     dim3 grid(p.C_out, slices);
     switch (p.mode) {
       case TCONV_MAX:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MAX>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MAX, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       case TCONV_MIN:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_MIN>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MIN, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       case TCONV_COMPOUND:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_COMPOUND>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_COMPOUND, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       default:
-        hipLaunchKernelGGL(bwd_weight_hist_kernel<TCONV_PARALLEL>, grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial);
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
     }
     if (partial) {
@@ -708,6 +773,54 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
         break;
     }
   }
+  return hipGetLastError();
+}
+
+// ---- every parameter gradient of a layer from one pass over gy: the kernel gradient(s) as launch_backward_weight
+// writes them in its two-stage form, and from the same loads grad_bias[c] = sum gy, grad_alpha[c] = sum gy * y_min,
+// grad_beta[c] = sum gy * y_max (each optional).  One histogram kernel and one reduction instead of three kernels
+// and three reductions: a training step of a small layer is a chain of launch latencies, not of bytes.
+// 0: no fused form for this layer (window too large for an on-chip histogram); the caller runs the separate kernels.
+size_t backward_params_workspace(const Params& p) {
+  if (!weight_hist_fits(p)) return 0;
+  int npb = 0;
+  const int slices = weight_slices(p, &npb);
+  const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
+  return (size_t)slices * p.C_out * ((size_t)nhist * p.K + N_EXTRA) * sizeof(double);
+}
+
+hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float* y_min, const float* y_max,
+                                  float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
+                                  float* grad_bias, double* partial, hipStream_t s) {
+  float* gmin = grad_w_min;
+  float* gmax = grad_w_max;
+  if (p.mode == TCONV_COMPOUND) gmin = gmax = (grad_w_min ? grad_w_min : grad_w_max);
+  const int nhist = (p.mode == TCONV_PARALLEL) ? 2 : 1;
+  const size_t lds = ((size_t)nhist * p.K + N_EXTRA + 16 * N_EXTRA) * sizeof(double);
+  int n_per_block = 0;
+  const int slices = weight_slices(p, &n_per_block);
+  const dim3 grid(p.C_out, slices);
+  const ParamExtras ex = {grad_alpha ? y_min : nullptr, grad_beta ? y_max : nullptr};
+  switch (p.mode) {
+    case TCONV_MAX:
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MAX, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
+      break;
+    case TCONV_MIN:
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MIN, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
+      break;
+    case TCONV_COMPOUND:
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_COMPOUND, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
+      break;
+    default:
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
+      break;
+  }
+  const size_t total = (size_t)p.C_out * ((size_t)nhist * p.K + N_EXTRA);
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  float* d0 = (p.mode == TCONV_MAX) ? gmax : gmin;
+  hipLaunchKernelGGL(bwd_params_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, partial, d0, gmax, grad_bias,
+                     grad_alpha, grad_beta, nhist, p.K, p.C_out, slices);
   return hipGetLastError();
 }
 

@@ -60,7 +60,8 @@ def scratch(nbytes, dev):
 def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deterministic=True, fused=False):
     """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32).
     deterministic: the parameter gradients get their workspaces (fixed-order fp64 sums); False: the atomic forms.
-    fused: grad_x and the kernel gradients through the one-call tconv_backward instead of the two separate calls."""
+    fused: grad_x and the kernel gradients through the one-call tconv_backward instead of the two separate calls;
+    "params": grad_x by tconv_backward_input and every parameter gradient, grad_bias included, by tconv_backward_params."""
     import torch
     dev = torch.device(device)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -102,7 +103,18 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
         wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
         gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
-        if fused:
+        if fused == "params":
+            # grad_x by its own call, every parameter gradient (kernels, combine coefficients, bias) by the one-call form
+            tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+            ab = cfg.mode in ("compound", "parallel") and branch_outputs
+            ga = torch.full((cfg.C_out,), float("nan"), device=dev) if ab else None
+            gb = torch.full((cfg.C_out,), float("nan"), device=dev) if ab else None
+            gbias = torch.full((cfg.C_out,), float("nan"), device=dev)
+            ws_p = scratch(tb.tconv_workspace_bytes(d, "backward_params"), dev) if deterministic else None
+            tb.tconv_backward_params(d, gy, alpha, beta, idx_min, idx_max, y_min, y_max, gw_min, gw_max, ga, gb, gbias,
+                                     ws_p)
+            out.update(grad_alpha=ga, grad_beta=gb, grad_bias=gbias)
+        elif fused:
             ws_b = scratch(tb.tconv_workspace_bytes(d, "backward"), dev) if deterministic else None
             tb.tconv_backward(d, gy, alpha, beta, idx_min, idx_max, gx, gw_min, gw_max, ws_b)
         else:
@@ -110,7 +122,7 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
             ws_w = scratch(tb.tconv_workspace_bytes(d, "backward_weight"), dev) if deterministic else None
             tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max, ws_w)
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
-        if cfg.mode in ("compound", "parallel") and branch_outputs:
+        if cfg.mode in ("compound", "parallel") and branch_outputs and fused != "params":
             ga = torch.full((cfg.C_out,), float("nan"), device=dev)
             gb = torch.full((cfg.C_out,), float("nan"), device=dev)
             ws_ab = scratch(tb.tconv_workspace_bytes(d, "backward_alpha_beta"), dev) if deterministic else None

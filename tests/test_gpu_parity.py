@@ -203,6 +203,35 @@ def test_ragged_shapes_that_split_the_input_channels(cfg):
     _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
 
 
+@pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[13], RAGGED[15], RAGGED[20],
+                                 RAGGED[23], RAGGED_LARGE[0], RAGGED_LARGE[1], RAGGED_SPLIT[0]], ids=lambda c: c.name)
+def test_parameter_gradients_in_one_call(cfg):
+    """tconv_backward_params against the oracle's kernel, combine-coefficient and bias gradients: the one-pass form
+    (fp32 storage with its workspace), the separate kernels behind the same call (bf16 storage; no workspace: the
+    atomic forms), optional outputs left out, and the mixed layers (kernel gradient and bias only)."""
+    from oracle import text_oracle as ext
+    s = ext.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+    for mode in MODES + ("minplus_max", "maxplus_min"):
+        for dtype, det in (("f32", True), ("f32", False), ("bf16", True)):
+            c = cfg.with_(mode=mode, dtype=dtype)
+            inp = make_inputs(c, alpha_beta="random" if mode in ("compound", "parallel") else None)
+            ref = hs.run_oracle(c, inp)
+            ref["grad_bias"] = ext.backward_bias(s, inp["gy"])
+            ref["grad_bias_scale"] = ext.backward_bias(s, np.abs(inp["gy"]))
+            hip = hs.run_hip(c, inp, fused="params", deterministic=det)
+            what = f"[{c.name} {mode} {dtype} one-call det={det}] "
+            hs.assert_forward_bit_exact(hip, ref, what=what)
+            hs.assert_backward_close(hip, ref, what=what, strict_params=det)
+            hs.assert_grad_close(hip["grad_bias"], ref["grad_bias"], ref["grad_bias_scale"], what + "grad_bias",
+                                 strict=det)
+    # optional outputs left out (no branch outputs kept, so no combine-coefficient gradients), integer data
+    c = cfg.with_(mode="compound")
+    inp = make_inputs(c, integer=True)
+    ref = hs.run_oracle(c, inp)
+    hip = hs.run_hip(c, inp, fused="params", branch_outputs=False)
+    hs.assert_backward_close(hip, ref, what=f"[{c.name} compound one-call, no branch outputs] ")
+
+
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10]], ids=lambda c: c.name)
 def test_generic_kernel_on_ragged_shapes(cfg):
     for mode in MODES:
