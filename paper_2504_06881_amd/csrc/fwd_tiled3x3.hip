@@ -25,6 +25,7 @@ bool forward_tiled3x3_supported(const Params& p, int dtype) {
   if (p.C_in > 65535) return false;      // winning channels are parked as 16-bit values
   if ((size_t)p.N * p.C_in * p.H * p.W * (dtype == TCONV_BF16 ? 2 : 4) >= 0xfffff000ull) return false;
   if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
+  if ((size_t)p.N * p.C_out * p.Ho * p.Wo * 4 >= 0xfffff000ull) return false;  // a lane's output offset is 32 bits
   return true;
 }
 

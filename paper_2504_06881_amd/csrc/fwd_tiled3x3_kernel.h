@@ -469,18 +469,43 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   };
   // Exact taps for RB pixels of one (channel, branch) row at a time: first ALL gathers of the batch
   // are issued (9 kernel values and a 3 x (2D+1) input patch per item), only then any is consumed,
-  // so the batch pays one memory latency instead of one per item.  A pixel whose taps may leave the
-  // row loads its patch from a start clamped into the row and picks the taps with a per-lane shift.
+  // so the batch pays one memory latency instead of one per item.  Straight-line code: the pixel index is a
+  // compile-time constant, an out-of-image tap is masked exactly as in the main loop (NaN, or +0 under zero
+  // padding) and so needs no test of its own, and what depends on the lane alone (row offsets, the start column
+  // of every pixel's patch, its shift) is computed once for all items.
   constexpr int L = 2 * D + 1;           // contiguous input columns spanned by the 3 taps of a row
   constexpr int RB = (D == 1) ? 4 : 2;   // items per batch (register budget)
-  auto refine_batch = [&](const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co,
-                          const float* wl, int q0, int (&res)[PX]) {
+  // a pixel whose three tap columns are core columns (always inside the row) loads its patch where it is; the
+  // others load from a start clamped into the row and pick their taps by the shift
+  auto is_inner = [](int q) { return q * S >= D && q * S + 2 * D < D + NC; };
+  const unsigned HWb = (unsigned)(HW * sizeof(TO));
+  unsigned rowb[3];   // byte offset of column 0 of the (clamped) input row i in channel 0 of this image
+  unsigned colb[PX];  // byte offset of the first loaded column of pixel q's patch
+  int shq[PX];        // non-inner pixels: tap column minus loaded column
+#pragma unroll
+  for (int i = 0; i < 3; ++i) rowb[i] = (unsigned)((xn_off + (size_t)ihc[i] * p.W) * sizeof(TO));
+#pragma unroll
+  for (int q = 0; q < PX; ++q) {
+    const int iwq = iw0 + q * S;
+    const int start = is_inner(q) ? iwq : min(max(iwq, 0), p.W - L);
+    colb[q] = (unsigned)start * (unsigned)sizeof(TO);
+    shq[q] = iwq - start;
+  }
+  // the padding mask of the tap in register column o of row i, in the convention of the main loop
+  auto tap_mask = [&](int i, int o) -> unsigned {
+    unsigned m = mrow[i];
+    if (o < D) m = PZ ? (m & mhalo[o]) : (m | mhalo[o]);
+    if (o >= D + NC) m = PZ ? (m & mhalo[o - NC]) : (m | mhalo[o - NC]);
+    return m;
+  };
+  auto refine_batch = [&](auto q0c, const int (&cs_row)[PX], const float (&best_row)[PX], rsrc_t wres, int co,
+                          const float* wl, int (&res)[PX]) {
+    constexpr int q0 = decltype(q0c)::value;
     float wv[RB][9];
     float run[RB][3][L];
-    int csv[RB], shv[RB];
-#pragma unroll
-    for (int u = 0; u < RB; ++u) {
-      const int q = q0 + u;
+    int csv[RB];
+    static_steps<0, RB, 1>([&](auto uc) {
+      constexpr int u = decltype(uc)::value, q = q0 + u;
       const int cs = min(cs_row[q], p.C_in - 1);  // a virtual channel never wins; keep the address in range
       csv[u] = cs;
       if (wl) {  // uniform
@@ -489,56 +514,54 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       } else {
         load_run<9, float>(wv[u], wres, (unsigned)(((size_t)co * p.K + (size_t)cs * 9) * sizeof(float)), 0u);
       }
-      const int iwq = (ow0 + q) * S - p.pw;
-      // stride 1: pixels D .. PX-1-D have every tap column inside the row whatever the padding
-      const bool inner = (S == 1) && (q >= D && q <= PX - 1 - D);
-      const int start = inner ? iwq : min(max(iwq, 0), p.W - L);
-      shv[u] = iwq - start;
+      const unsigned xb = (unsigned)cs * HWb + colb[q];
 #pragma unroll
-      for (int i = 0; i < 3; ++i) {
-        const size_t rbase = xn_off + (size_t)cs * HW + (size_t)ihc[i] * p.W;
-        load_run<L, TO>(run[u][i], xres, (unsigned)((rbase + start) * sizeof(TO)), 0u);
-      }
-    }
+      for (int i = 0; i < 3; ++i) load_run<L, TO>(run[u][i], xres, xb + rowb[i], 0u);
+    });
     __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the batch ahead of every use
+    static_steps<0, RB, 1>([&](auto uc) {
+      constexpr int u = decltype(uc)::value, q = q0 + u;
+      constexpr bool inner = q * S >= D && q * S + 2 * D < D + NC;
+      int rt = 0;  // winning tap inside the channel
 #pragma unroll
-    for (int u = 0; u < RB; ++u) {
-      const int q = q0 + u;
-      const bool inner = (S == 1) && (q >= D && q <= PX - 1 - D);
-      const int iwq = (ow0 + q) * S - p.pw;
-      int r = csv[u] * 9;
-#pragma unroll
-      for (int i = 2; i >= 0; --i)
+      for (int i = 2; i >= 0; --i) {
+        // identity padding, inner pixel: only a whole row can be outside; its taps are compared with NaN
+        const float best_i = (!PZ && inner) ? nan_or(best_row[q], mrow[i]) : best_row[q];
 #pragma unroll
         for (int j = 2; j >= 0; --j) {
           float xv;
-          bool ok = PZ ? (mrow[i] != 0u) : (mrow[i] == 0u);  // the row is inside the image
-          if (inner) {
+          if constexpr (inner) {
             xv = run[u][i][j * D];
           } else {
-            const int col = j * D + shv[u];  // position of the tap inside the loaded run
+            const int col = j * D + shq[q];  // position of the tap inside the loaded run
             xv = run[u][i][0];
 #pragma unroll
             for (int t = 1; t < L; ++t) xv = (col == t) ? run[u][i][t] : xv;
-            const int iw = iwq + j * D;
-            ok = ok && (iw >= 0 && iw < p.W);
           }
-          // an out-of-image tap: no candidate (identity padding), or the candidate 0 + w (zero padding)
-          const float sum = __fadd_rn((PZ && !ok) ? 0.0f : xv, wv[u][i * 3 + j]);
-          r = ((PZ || ok) && sum == best_row[q]) ? csv[u] * 9 + i * 3 + j : r;
+          // an out-of-image tap: no candidate (identity padding: NaN), or the candidate 0 + w (zero padding)
+          if constexpr (PZ || !inner) {
+            const unsigned m = tap_mask(i, q * S + j * D);
+            xv = __uint_as_float(PZ ? (__float_as_uint(xv) & m) : (__float_as_uint(xv) | m));
+          }
+          const float sum = __fadd_rn(xv, wv[u][i * 3 + j]);
+          rt = (sum == best_i) ? i * 3 + j : rt;
         }
+      }
 #ifdef TCONV_TUNING
-      res[q] = (flags & 1) ? csv[u] * 9 : r;  // timing experiment: no tap recovery, WRONG results
+      res[q] = (flags & 1) ? csv[u] * 9 : csv[u] * 9 + rt;  // timing experiment: no tap recovery, WRONG results
 #else
-      res[q] = r;
+      res[q] = csv[u] * 9 + rt;
 #endif
-    }
+    });
     __builtin_amdgcn_sched_barrier(0);  // the next batch starts after this one has retired its registers
   };
   const size_t plane = (size_t)p.Ho * p.Wo;
+  const unsigned lane_ob = (unsigned)(((size_t)n * p.C_out) * plane + (size_t)oh * p.Wo + ow0);
   // one output channel: c is its slot among the parked winners and the staged kernel rows
   auto finish_channel = [&](int c, int co, const float (&vmin)[PX], const float (&vmax)[PX]) {
-    const size_t ob = ((size_t)n * p.C_out + co) * plane + (size_t)oh * p.Wo + ow0;
+    // outputs: a wave-uniform channel base and the lane's 32-bit element offset (tensors stay below 4 GiB)
+    const size_t cb_off = (size_t)co * plane;
+    const size_t ob = lane_ob + cb_off;
     float ca = 1.f, cb = 1.f;
     if (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL) {
       if (alpha) ca = alpha[co];
@@ -557,10 +580,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       } else {
         unstash(0, c, cids);
       }
-#pragma unroll
-      for (int q = 0; q < PX; q += RB) refine_batch(cids, vmin, wres_min, co, wl, q, ridx);
-      store_row<PX>(idx_min + ob, ridx, first_qs);
-      if (y_min) store_row<PX>(y_min + ob, vmin, first_qs);
+      static_steps<0, PX, RB>([&](auto qc) { refine_batch(qc, cids, vmin, wres_min, co, wl, ridx); });
+      store_row<PX>(idx_min + cb_off, lane_ob, ridx, first_qs);
+      if (y_min) store_row<PX>(y_min + cb_off, lane_ob, vmin, first_qs);
     }
     if (DO_MAX) {
       if (wrps > 0 && s_max % wrps == 0 && !(DO_MIN && NT == 1)) stage_rows(s_max);
@@ -571,10 +593,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       } else {
         unstash(NBR - 1, c, cids);
       }
-#pragma unroll
-      for (int q = 0; q < PX; q += RB) refine_batch(cids, vmax, wres_max, co, wl, q, ridx);
-      store_row<PX>(idx_max + ob, ridx, first_qs);
-      if (y_max) store_row<PX>(y_max + ob, vmax, first_qs);
+      static_steps<0, PX, RB>([&](auto qc) { refine_batch(qc, cids, vmax, wres_max, co, wl, ridx); });
+      store_row<PX>(idx_max + cb_off, lane_ob, ridx, first_qs);
+      if (y_max) store_row<PX>(y_max + cb_off, lane_ob, vmax, first_qs);
     }
 #pragma unroll
     for (int q = 0; q < PX; ++q) {
@@ -599,7 +620,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       for (int q = 0; q < PX; ++q)
         if (q >= first_qs) out[q] = __fadd_rn(out[q], ld_f32(rp, (size_t)q));
     }
-    store_row<PX>(y + ob, out, first_qs);
+    store_row<PX>(y + cb_off, lane_ob, out, first_qs);
   };
   if constexpr (KSP) {
     finish_channel(0, co0 + wave, fmin, fmax);

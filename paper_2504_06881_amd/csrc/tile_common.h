@@ -1,12 +1,24 @@
 // Helpers shared by the tiled 3x3 forward kernels (gfx950): lane geometry constants, raw buffer
 // loads of x, and the vectorised row stores of the epilogue.
 #pragma once
+#include <type_traits>
+
 #include "tconv_internal.h"
 
 namespace tconv {
 namespace tile {
 
 constexpr int WAVES = 4;  // waves per workgroup, each a different c_out group
+
+// f(integral_constant<int, I>) for I = FIRST, FIRST + STEP, ... below LAST: a loop whose index is a compile-time
+// constant in the body whatever the optimiser decides about unrolling
+template <int FIRST, int LAST, int STEP, typename F>
+__device__ __forceinline__ void static_steps(F&& f) {
+  if constexpr (FIRST < LAST) {
+    f(std::integral_constant<int, FIRST>{});
+    static_steps<FIRST + STEP, LAST, STEP>(f);
+  }
+}
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef float f2u __attribute__((ext_vector_type(2), aligned(4)));
@@ -82,6 +94,8 @@ __device__ __forceinline__ float load_one(rsrc_t r, unsigned voff, unsigned soff
 
 // ---- a lane's NP (4 or 8) consecutive outputs -> memory.  Pixels q < first_q belong to the
 // neighbouring lane (shifted last segment of a row): then single predicated stores, else 16-byte stores.
+// The (base, off) forms take a wave-uniform base and the lane's 32-bit element offset, which is what a store
+// instruction with a scalar base address wants: no 64-bit per-lane address arithmetic.
 typedef int i4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef unsigned u4h __attribute__((ext_vector_type(4), aligned(2)));
 typedef unsigned u2h __attribute__((ext_vector_type(2), aligned(2)));
@@ -139,6 +153,12 @@ __device__ __forceinline__ void store_row(bf16_t* p, const float (&v)[NP], int f
     for (int q = 0; q < NP; ++q)
       if (q >= first_q) p[q] = (bf16_t)bf16_bits(v[q]);
   }
+}
+
+// element offset -> byte offset in 32 bits (the caller keeps tensors below 4 GiB), added to the uniform base
+template <int NP, typename T, typename V>
+__device__ __forceinline__ void store_row(T* base, unsigned off, const V (&v)[NP], int first_q) {
+  store_row<NP>((T*)((char*)base + (size_t)(off * (unsigned)sizeof(T))), v, first_q);
 }
 
 }  // namespace tile
