@@ -29,7 +29,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_rowtile_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min, const float* __restrict__ w_max,
     const float* __restrict__ alpha, const float* __restrict__ beta, float* __restrict__ y,
     float* __restrict__ y_min, float* __restrict__ y_max, int32_t* __restrict__ idx_min,
-    int32_t* __restrict__ idx_max, int segs, int n_units, int n_groups, int n_blocks) {
+    int32_t* __restrict__ idx_max, int segs, int n_units, int n_groups, int n_blocks, int core_lo, int core_hi,
+    unsigned inv_kh) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr int PX = (S == 1) ? 8 : 4;
   constexpr int XR = (PX - 1) * S + KW;  // input columns a lane touches per row
@@ -73,13 +74,38 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_rowtile_kernel(
   }
   const int nst = p.C_in * p.KH;  // steps: (channel, kernel row) pairs in k order
 
-  // row segment of step (c, i): XR single loads from clamped positions; returns the row's padding mask
+  // Register columns [core_lo, core_hi) lie inside the row for every lane (core_lo = the left padding; the host
+  // derives both from the geometry): they are read in runs of four with 16-byte loads, the columns left and right
+  // of them one by one from clamped positions.  The run boundaries depend on core_lo, a wave-uniform run-time value,
+  // while register numbers must be constants: one statically laid out variant per left padding 0..3, chosen by a
+  // uniform branch (wider paddings: every column on its own).
+  const unsigned cb0 = (unsigned)(iw0 * 4);  // byte offset of register column 0 (may wrap; only used inside the core)
+  auto load_cols = [&](float (&xs)[XR], unsigned roff, unsigned soff, auto loc) {
+    constexpr int LO = decltype(loc)::value;
+#pragma unroll
+    for (int e = 0; e < (LO < XR ? LO : XR); ++e) xs[e] = load_one<float>(xres, roff + coff[e], soff);
+    static_steps<LO, XR, 4>([&](auto ec) {
+      constexpr int e = decltype(ec)::value;
+      if (e + 4 <= XR && e + 4 <= core_hi) {  // wave-uniform
+        if constexpr (e + 4 <= XR) load_run<4, float>(&xs[e], xres, roff + cb0 + 4u * e, soff);
+      } else {
+#pragma unroll
+        for (int t = e; t < (e + 4 < XR ? e + 4 : XR); ++t) xs[t] = load_one<float>(xres, roff + coff[t], soff);
+      }
+    });
+  };
+  // row segment of step (c, i); returns the row's padding mask
   auto load_row = [&](float (&xs)[XR], int c, int i) -> unsigned {
     const int ih = ih0 + i * p.dh;
     const unsigned roff = nbase + (unsigned)(min(max(ih, 0), p.H - 1) * p.W) * 4u;
     const unsigned soff = (unsigned)min(c, p.C_in - 1) * HWb;
-#pragma unroll
-    for (int e = 0; e < XR; ++e) xs[e] = load_one<float>(xres, roff + coff[e], soff);
+    switch (core_lo) {  // wave-uniform
+      case 0: load_cols(xs, roff, soff, std::integral_constant<int, 0>{}); break;
+      case 1: load_cols(xs, roff, soff, std::integral_constant<int, 1>{}); break;
+      case 2: load_cols(xs, roff, soff, std::integral_constant<int, 2>{}); break;
+      case 3: load_cols(xs, roff, soff, std::integral_constant<int, 3>{}); break;
+      default: load_cols(xs, roff, soff, std::integral_constant<int, XR>{}); break;
+    }
     return (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
   };
   auto mask_row = [&](float (&xs)[XR], unsigned mrow) {
@@ -163,24 +189,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_rowtile_kernel(
   const size_t plane = (size_t)p.Ho * p.Wo;
   const rsrc_t wres_min = make_rsrc(DO_MIN ? w_min : w_max, (unsigned)((size_t)p.C_out * p.K * sizeof(float)));
   const rsrc_t wres_max = make_rsrc(DO_MAX ? w_max : w_min, (unsigned)((size_t)p.C_out * p.K * sizeof(float)));
-  auto refine = [&](rsrc_t wres, int co, int q, int st, float best) -> int {
-    const int c = st / p.KH, i = st - c * p.KH;
+  // (the step unflattens with a multiply-high: inv_kh = floor(2^32 / KH) + 1 is exact for st * KH < 2^32; KH = 1: 0)
+  auto refine = [&](rsrc_t wres, unsigned cobase, auto qc, int st, float best) -> int {
+    constexpr int q = decltype(qc)::value;
+    const int c = inv_kh ? (int)__umulhi((unsigned)st, inv_kh) : st;
+    const int i = st - c * p.KH;
     const int ih = ih0 + i * p.dh;  // inside the image: the recorded step improved the extremum
     const unsigned roff = nbase + (unsigned)c * HWb + (unsigned)(min(max(ih, 0), p.H - 1) * p.W) * 4u;
-    const unsigned wbase = (unsigned)(((size_t)co * p.K + (size_t)st * KW) * sizeof(float));
     float xv[KW], wv[KW];
+    load_run<KW, float>(wv, wres, cobase + (unsigned)(st * KW) * 4u, 0u);
+    if (q * S >= core_lo && q * S + KW <= core_hi) {  // wave-uniform: the pixel's window is inside the row
+      load_run<KW, float>(xv, xres, roff + cb0 + 4u * (q * S), 0u);
+    } else {
 #pragma unroll
-    for (int j = 0; j < KW; ++j) {
-      xv[j] = load_one<float>(xres, roff + coff[q * S + j], 0u);
-      wv[j] = load_one<float>(wres, wbase + 4u * j, 0u);
+      for (int j = 0; j < KW; ++j) xv[j] = nan_or(load_one<float>(xres, roff + coff[q * S + j], 0u), mcol[q * S + j]);
     }
     int r = 0;
 #pragma unroll
-    for (int j = KW - 1; j >= 0; --j) {
-      const bool ok = mcol[q * S + j] == 0u;
-      const bool eq = __fadd_rn(xv[j], wv[j]) == best;
-      r = (ok & eq) ? j : r;
-    }
+    for (int j = KW - 1; j >= 0; --j) r = (__fadd_rn(xv[j], wv[j]) == best) ? j : r;
     return st * KW + r;
   };
 #pragma unroll
@@ -195,15 +221,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_rowtile_kernel(
     }
     int ridx[PX];
     float out[PX];
+    const unsigned cobase = (unsigned)((size_t)co * p.K * sizeof(float));
     if (DO_MIN) {
-#pragma unroll
-      for (int q = 0; q < PX; ++q) ridx[q] = refine(wres_min, co, q, imin[t][q], bmin[t][q]);
+      static_steps<0, PX, 1>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        ridx[q] = refine(wres_min, cobase, qc, imin[t][q], bmin[t][q]);
+      });
       store_row<PX>(idx_min + ob, ridx, first_q);
       if (y_min) store_row<PX>(y_min + ob, bmin[t], first_q);
     }
     if (DO_MAX) {
-#pragma unroll
-      for (int q = 0; q < PX; ++q) ridx[q] = refine(wres_max, co, q, imax[t][q], bmax[t][q]);
+      static_steps<0, PX, 1>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        ridx[q] = refine(wres_max, cobase, qc, imax[t][q], bmax[t][q]);
+      });
       store_row<PX>(idx_max + ob, ridx, first_q);
       if (y_max) store_row<PX>(y_max + ob, bmax[t], first_q);
     }
@@ -226,9 +257,17 @@ hipError_t launch_k(const Params& p, const FwdArgs& a, hipStream_t s) {
   const long long blocks = ((n_units + 63) / 64) * ((n_groups + WAVES - 1) / WAVES);
   const long long grid = ((blocks + 7) / 8) * 8;
   if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
+  // register columns inside the row for every lane: a lane's column e is input column ow0 * S - pad_w + e with
+  // 0 <= ow0 <= W_out - PX
+  constexpr int XR = (PX - 1) * S + KW;
+  const int core_lo = p.pw < XR ? p.pw : XR;
+  long long hi = (long long)p.W + p.pw - (long long)(p.Wo - PX) * S;
+  const int core_hi = (int)(hi < core_lo ? core_lo : (hi > XR ? XR : hi));
+  const unsigned inv_kh = p.KH > 1 ? (unsigned)(0x100000000ULL / (unsigned long long)p.KH) + 1u : 0u;
   hipLaunchKernelGGL((fwd_rowtile_kernel<MODE, KW, S>), dim3((unsigned)grid), dim3(WAVES * 64), 0, s, p,
                      (const float*)a.x, (const float*)a.w_min, (const float*)a.w_max, a.alpha, a.beta, (float*)a.y,
-                     (float*)a.y_min, (float*)a.y_max, a.idx_min, a.idx_max, segs, (int)n_units, n_groups, (int)blocks);
+                     (float*)a.y_min, (float*)a.y_max, a.idx_min, a.idx_max, segs, (int)n_units, n_groups, (int)blocks,
+                     core_lo, core_hi, inv_kh);
   return hipGetLastError();
 }
 
@@ -262,6 +301,7 @@ bool forward_rowtile_supported(const Params& p, int dtype) {
   if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
   if ((size_t)p.C_out * p.K * 4 >= 0xfffff000ull) return false;
   if ((long long)p.C_in * p.KH >= (1LL << 28)) return false;
+  if ((long long)p.C_in * p.KH * p.KH >= (1LL << 32)) return false;  // a step unflattens with a multiply-high
   return true;
 }
 
