@@ -413,7 +413,9 @@ const char* tconv_status_string(int status);
 
 /*
  * Name of the forward kernel tconv_forward would launch for this descriptor
- * ("tiled3x3"; "tiled3x3_f16" - binary16 arithmetic on the packed 16-bit vector instructions; "row1d" - one-row
+ * ("tiled3x3"; "tiled3x3_split" - the same kernel with the input channels split over the waves of a workgroup, chosen
+ * where whole rounds of plain workgroups would fill the chip badly; "tiled3x3_f16" - binary16 arithmetic on the packed
+ * 16-bit vector instructions; "row1d" - one-row
  * inputs with a window of 8 taps or more; "rowtile" - other windows up to 7 taps wide, fp32; or "generic"), for
  * tests and benchmarks.  Host only; NULL on a bad descriptor.
  */

@@ -672,7 +672,7 @@ const char* tconv_forward_kernel_name(const tconv_desc* desc) {
   Params p;
   if (make_params(desc, &p) != TCONV_OK) return nullptr;
   if (use_tiled16(p, desc->dtype)) return "tiled3x3_f16";
-  if (use_tiled(p, desc->dtype)) return "tiled3x3";
+  if (use_tiled(p, desc->dtype)) return forward_tiled3x3_splits(p, desc->dtype) ? "tiled3x3_split" : "tiled3x3";
   if (use_row(p, desc->dtype)) return "row1d";
   return use_rowtile(p, desc->dtype) ? "rowtile" : "generic";
 }

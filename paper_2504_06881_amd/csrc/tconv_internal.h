@@ -158,6 +158,7 @@ hipError_t launch_forward_tiled3x3_bf16(const Params& p, const FwdArgs& a, void*
 // four full-window modes; a code object of its own).  plain_workgroups: the grid of the plain form with 4 output
 // channels per lane, resident: the workgroups the chip holds at once
 bool forward_tiled3x3_ks_wanted(const Params& p, long long plain_workgroups, long long resident);
+bool forward_tiled3x3_splits(const Params& p, int dtype);  // the tiled path will take that form (host only)
 hipError_t launch_forward_tiled3x3_ks(const Params& p, const void* x, const float* w_min, const float* w_max,
                                       const FwdArgs& a, hipStream_t s);
 // binary16 arithmetic (TCONV_F16) on the packed 16-bit vector instructions

@@ -62,6 +62,10 @@ def test_workspace_status_and_kernel_name():
     for s in (-1, -2, -3, -4, -5, -99):
         assert len(tb.status_string(s)) > 3
     assert tb.tconv_forward_kernel_name(d) in ("tiled3x3", "generic")
+    # 64 input channels and a grid of a quarter of a round of plain workgroups: the input channels are split
+    assert tb.tconv_forward_kernel_name(tb.Desc(32, 64, 8, 8, 64, 3, 3, pad=(1, 1), mode="parallel")) == "tiled3x3_split"
+    assert tb.tconv_forward_kernel_name(tb.Desc(128, 64, 32, 32, 64, 3, 3, pad=(1, 1), mode="compound")) == "tiled3x3"
+    assert tb.tconv_forward_kernel_name(tb.Desc(32, 64, 8, 8, 64, 3, 3, pad=(1, 1), mode="minplus_max")) == "tiled3x3"
     assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2))) == "rowtile"
     assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 5, 5, pad=(2, 2), dil=(1, 2))) == "generic"
     assert tb.tconv_forward_kernel_name(tb.Desc(2, 3, 16, 16, 8, 3, 3, pad=(1, 1), dtype="f16")) == "tiled3x3_f16"
@@ -83,8 +87,8 @@ def test_one_dimensional_descriptor_views():
     assert tb.tconv1d_out_len(tb.Desc1d(2, 1, 32000, 8, 80, stride=4, pad=38)) == 8000
     assert tb.tconv1d_out_len(tb.Desc1d(2, 5, 50, 8, 3, stride=2, pad=1, dil=2)) == 24
     # K = 3, C_in a multiple of 3, full-window mode: three channels become the three rows of a 3 x 3 window
-    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="compound")) == "tiled3x3"
-    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, stride=2, pad=1, mode="max")) == "tiled3x3"
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, pad=1, mode="compound")) in ("tiled3x3", "tiled3x3_split")
+    assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 3, stride=2, pad=1, mode="max")) in ("tiled3x3", "tiled3x3_split")
     # other short windows (K <= 7, no dilation, stride 1 or 2) of the full-window modes: the row-tiled kernel
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 95, 4000, 64, 3, pad=1, mode="compound")) == "rowtile"
     assert tb.tconv1d_forward_kernel_name(tb.Desc1d(4, 96, 4000, 64, 5, pad=2, mode="compound")) == "rowtile"

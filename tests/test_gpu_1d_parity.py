@@ -94,7 +94,7 @@ def test_full_size_layer():
     print(f"[1d full] {cfg.name} pairs={cfg.pairs:.3e}", flush=True)
     _check(cfg)
     d = tb.Desc1d(cfg.N, cfg.C_in, cfg.L, cfg.C_out, cfg.K, cfg.stride, cfg.pad, cfg.dil, cfg.mode, cfg.dtype)
-    assert tb.tconv1d_forward_kernel_name(d) == "tiled3x3"
+    assert tb.tconv1d_forward_kernel_name(d) in ("tiled3x3", "tiled3x3_split")
 
 
 def test_error_paths():

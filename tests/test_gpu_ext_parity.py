@@ -9,7 +9,7 @@ import pytest
 import harness as hs
 from paper_2504_06881_amd import binding as tb
 from paper_2504_06881_amd.inputs import CONFIGS, LayerCfg, make_inputs
-from test_gpu_parity import BOTH_TN, KNOBS, MODES, RAGGED, RAGGED_LARGE
+from test_gpu_parity import BOTH_TN, KNOBS, MODES, RAGGED, RAGGED_LARGE, TILED
 
 pytestmark = pytest.mark.gpu
 
@@ -49,7 +49,7 @@ ZERO_SHAPES = [c for c in RAGGED if c.pad > 0 and c.name not in ("r_cin300", "r_
 @pytest.mark.parametrize("cfg", ZERO_SHAPES, ids=lambda c: c.name)
 def test_zero_padding_ragged_shapes(cfg):
     cfg = cfg.with_(pad_mode="zero")
-    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) in TILED
     tn = BOTH_TN if tiled else (None,)
     for mode in MODES:
         _check_ext(cfg.with_(mode=mode), alpha_beta="random" if mode in ("compound", "parallel") else None, tn=tn)
@@ -77,7 +77,7 @@ def test_zero_padding_bf16_storage(mode):
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[1], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[12]], ids=lambda c: c.name)
 def test_epilogue_ragged_shapes(cfg, pad_mode):
     cfg = cfg.with_(pad_mode=pad_mode)
-    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) in TILED
     tn = BOTH_TN if tiled else (None,)
     for mode in MODES:
         ab = "random" if mode in ("compound", "parallel") else None

@@ -27,7 +27,7 @@ def test_cfg1(mode, kernel):
 
 @pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
 def test_ragged_shapes(cfg):
-    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) in ("tiled3x3", "tiled3x3_split")
     tn = BOTH_TN if tiled else (None,)
     for mode in MIXED:
         _check(cfg.with_(mode=mode), tn=tn)

@@ -20,6 +20,9 @@ MODES = ("max", "min", "compound", "parallel")
 KNOBS = ("TCONV_FORWARD_KERNEL", "TCONV_FWD_TN", "TCONV_FWD_KSPLIT")
 
 
+TILED = ("tiled3x3", "tiled3x3_split")   # the tiled 3x3 kernel, plain or with the input channels split over the waves
+
+
 def tiled_blocks4(cfg):
     """Workgroups of the tiled forward kernel at 4 output channels per lane (the library's own count)."""
     ho, wo = cfg.out_hw
@@ -172,7 +175,7 @@ def test_row_tiled_kernel_shapes(cfg):
 
 @pytest.mark.parametrize("cfg", RAGGED, ids=lambda c: c.name)
 def test_ragged_shapes(cfg):
-    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3"
+    tiled = tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) in TILED
     tn = BOTH_TN if tiled else (None,)
     for mode in MODES:
         c = cfg.with_(mode=mode)
@@ -196,7 +199,7 @@ def test_ragged_shapes_that_pick_four_channels_per_lane(cfg):
 
 @pytest.mark.parametrize("cfg", RAGGED_SPLIT, ids=lambda c: c.name)
 def test_ragged_shapes_that_split_the_input_channels(cfg):
-    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3" and picks_split(cfg)
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "tiled3x3_split" and picks_split(cfg)
     for mode in MODES:
         _check(cfg.with_(mode=mode), alpha_beta="random" if mode in ("compound", "parallel") else None)
     _check(cfg.with_(mode="compound"), integer=True)
