@@ -39,7 +39,7 @@ size_t forward_tiled3x3_workspace(const Params& p, int dtype) {
 
 // whether launch_forward_tiled3x3 will run the form that splits the input channels over the waves (host only)
 bool forward_tiled3x3_splits(const Params& p, int dtype) {
-  if (dtype != TCONV_F32) return false;
+  if (dtype != TCONV_F32 && dtype != TCONV_BF16) return false;
   const int px = p.sh == 1 ? 8 : 4;
   const long long n_units = (long long)p.N * p.Ho * ((p.Wo + px - 1) / px);
   const long long blocks4 = ((n_units + 63) / 64) * ((((long long)p.C_out + 3) / 4 + WAVES - 1) / WAVES);

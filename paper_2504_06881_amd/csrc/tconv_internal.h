@@ -154,13 +154,13 @@ hipError_t launch_forward_tiled3x3(const Params& p, int dtype, const FwdArgs& a,
                                    hipStream_t s);
 // its bf16-storage instantiations (a translation unit of their own); workspace as forward_tiled3x3_workspace says
 hipError_t launch_forward_tiled3x3_bf16(const Params& p, const FwdArgs& a, void* workspace, hipStream_t s);
-// the form of the tiled 3x3 kernel that splits the input channels over the waves of a workgroup (fp32 storage, the
-// four full-window modes; a code object of its own).  plain_workgroups: the grid of the plain form with 4 output
+// the form of the tiled 3x3 kernel that splits the input channels over the waves of a workgroup (fp32 and bf16 storage,
+// the four full-window modes; a code object of its own; xa: bf16 rows read as dword pairs).  plain_workgroups: the grid of the plain form with 4 output
 // channels per lane, resident: the workgroups the chip holds at once
 bool forward_tiled3x3_ks_wanted(const Params& p, long long plain_workgroups, long long resident);
 bool forward_tiled3x3_splits(const Params& p, int dtype);  // the tiled path will take that form (host only)
-hipError_t launch_forward_tiled3x3_ks(const Params& p, const void* x, const float* w_min, const float* w_max,
-                                      const FwdArgs& a, hipStream_t s);
+hipError_t launch_forward_tiled3x3_ks(const Params& p, bool bf16, bool xa, const void* x, const float* w_min,
+                                      const float* w_max, const FwdArgs& a, hipStream_t s);
 // binary16 arithmetic (TCONV_F16) on the packed 16-bit vector instructions
 bool forward_tiled3x3_f16_supported(const Params& p, int dtype);
 size_t forward_tiled3x3_f16_workspace(const Params& p);
