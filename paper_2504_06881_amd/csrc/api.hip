@@ -157,7 +157,11 @@ int tconv_forward_fused(const tconv_desc* desc, const void* x, const void* w_min
   if (do_max && (!a.w_max || !idx_max)) return TCONV_E_INVAL;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e;
-  if (use_tiled(p, desc->dtype)) {
+  // the tiled kernel reads bf16 rows as whole dwords: x dword-aligned, and an even element count so that no dword
+  // reaches past the tensor; anything else goes to the kernels that read value by value
+  const bool bf16_dwords = desc->dtype != TCONV_BF16 ||
+                           (((uintptr_t)x & 3u) == 0 && (((size_t)p.N * p.C_in * p.H * p.W) & 1u) == 0);
+  if (use_tiled(p, desc->dtype) && bf16_dwords) {
     const size_t need = forward_tiled3x3_workspace(p, desc->dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)))
       return TCONV_E_WORKSPACE;

@@ -475,6 +475,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   // of every pixel's patch, its shift) is computed once for all items.
   constexpr int L = 2 * D + 1;           // contiguous input columns spanned by the 3 taps of a row
   constexpr int RB = (D == 1) ? 4 : 2;   // items per batch (register budget)
+  constexpr int ND16 = (L + 2) / 2;      // 16-bit storage: aligned dwords that cover L values from any halfword
   // a pixel whose three tap columns are core columns (always inside the row) loads its patch where it is; the
   // others load from a start clamped into the row and pick their taps by the shift
   auto is_inner = [](int q) { return q * S >= D && q * S + 2 * D < D + NC; };
@@ -516,13 +517,39 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       }
       const unsigned xb = (unsigned)cs * HWb + colb[q];
 #pragma unroll
-      for (int i = 0; i < 3; ++i) load_run<L, TO>(run[u][i], xres, xb + rowb[i], 0u);
+      for (int i = 0; i < 3; ++i) {
+        if constexpr (sizeof(TO) == 2) {
+          // 16-bit storage: the aligned dwords that cover the L values (one load; unpacked below, after the batch's
+          // loads are all out).  The host takes this kernel only for a dword-aligned x with an even element count,
+          // so the last dword of a run never reaches past the tensor.
+          load_run<ND16, float>(run[u][i], xres, (xb + rowb[i]) & ~3u, 0u);
+        } else {
+          load_run<L, TO>(run[u][i], xres, xb + rowb[i], 0u);
+        }
+      }
     });
     __builtin_amdgcn_sched_barrier(0);  // keep the gathers of the batch ahead of every use
     static_steps<0, RB, 1>([&](auto uc) {
       constexpr int u = decltype(uc)::value, q = q0 + u;
       constexpr bool inner = q * S >= D && q * S + 2 * D < D + NC;
       int rt = 0;  // winning tap inside the channel
+      if constexpr (sizeof(TO) == 2) {
+        // shift the dword run right by the halfword the values start at, then widen value t from half t of the run
+        const unsigned xb = (unsigned)csv[u] * HWb + colb[q];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+          const unsigned sh = ((xb + rowb[i]) & 2u) << 3;
+          unsigned r[ND16];
+#pragma unroll
+          for (int k = 0; k < ND16; ++k) {
+            const unsigned lo = __float_as_uint(run[u][i][k]);
+            r[k] = k + 1 < ND16 ? __builtin_amdgcn_alignbit(__float_as_uint(run[u][i][k + 1]), lo, sh) : lo >> sh;
+          }
+#pragma unroll
+          for (int t = 0; t < L; ++t)
+            run[u][i][t] = __uint_as_float((t & 1) ? (r[t >> 1] & 0xffff0000u) : (r[t >> 1] << 16));
+        }
+      }
 #pragma unroll
       for (int i = 2; i >= 0; --i) {
         // identity padding, inner pixel: only a whole row can be outside; its taps are compared with NaN
