@@ -57,7 +57,8 @@ def scratch(nbytes, dev):
     return t
 
 
-def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deterministic=True, fused=False):
+def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deterministic=True, fused=False,
+            x_halfword_offset=False):
     """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32).
     deterministic: the parameter gradients get their workspaces (fixed-order fp64 sums); False: the atomic forms.
     fused: grad_x and the kernel gradients through the one-call tconv_backward instead of the two separate calls;
@@ -73,6 +74,11 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt).contiguous()
 
     x = up(inp["x"], tdt)
+    if x_halfword_offset:  # 16-bit storage: the same values one element into a larger buffer (address = 2 mod 4)
+        big = torch.empty(x.numel() + 1, device=dev, dtype=tdt)
+        big[1:].copy_(x.reshape(-1))
+        x = big[1:].view(x.shape)
+        assert x.data_ptr() % 4 == 2
     if cfg.mode == "compound":
         w_min = w_max = up(inp["w_min"], tdt)
     else:

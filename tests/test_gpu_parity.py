@@ -250,6 +250,18 @@ def test_bf16_storage(mode):
         _check(cfg, integer=True, tn=BOTH_TN)
 
 
+def test_bf16_input_not_dword_aligned_or_of_odd_size():
+    """The tiled kernel reads bf16 rows as whole dwords; an input at an address that is 2 mod 4, or with an odd
+    element count, must take the value-by-value kernels and give the same bit-exact result."""
+    for base in (RAGGED[1], RAGGED[4], RAGGED[0]):   # even, even (dilation 2), odd element count
+        cfg = base.with_(mode="compound", dtype="bf16")
+        inp = make_inputs(cfg, alpha_beta="random")
+        ref = hs.run_oracle(cfg, inp, backward=False)
+        for off in (False, True):
+            hip = hs.run_hip(cfg, inp, backward=False, x_halfword_offset=off)
+            hs.assert_forward_bit_exact(hip, ref, what=f"[{cfg.name} bf16 x offset={off}] ")
+
+
 def test_forward_is_deterministic_and_stream_ordered():
     import torch
     cfg = RAGGED[1].with_(mode="compound")
