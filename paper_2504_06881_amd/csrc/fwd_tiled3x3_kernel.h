@@ -67,8 +67,9 @@ __device__ __forceinline__ void taps_of(float (&out)[9], const float (&rows)[6][
 // TN: output channels per lane (4; 2 for layers too small to fill the chip with 4)
 // PZ: zero padding (App. A.1.1: the unfold formulation pads with zeros): an out-of-image value is +0 instead of NaN,
 //     so its tap competes like any other; one AND per loaded value where the identity padding has one OR
-// XA (bf16 storage at stride 1 only): every lane's core columns start at an even element of x, so they are read as
-//     whole dwords holding two values each; otherwise bf16 values are read one by one
+// XA: bf16 storage at stride 1: every lane's core columns start at an even element of x, so they are read as
+//     whole dwords holding two values each (otherwise bf16 values are read one by one); fp32 storage at stride 2: the
+//     right halo column is inside the row for every lane and is read in one run with the core columns
 // KSP: the four waves of a workgroup share ONE group of TN output channels and split the input channels between
 //     them (a quarter of the channel pairs each, in ascending order); their running extrema and winning channels
 //     meet in LDS, wave w keeps output channel w of the group and finishes it.  Four times as many, a quarter as
@@ -88,6 +89,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   constexpr int NC = (PX - 1) * S + 1;          // core columns [D, D+NC): always inside the row
   constexpr int XR = NC + 2 * D;                // input columns a lane touches per row
   constexpr bool PK = XA && sizeof(TO) == 2 && S == 1;  // core columns arrive two per dword
+  // stride 2, fp32 storage, XA: the right halo column lies inside the row for every lane (the host has checked), so
+  // the 7 core columns and it are one run of 8 values (two 16-byte loads instead of a 16-, an 8-, a 4-byte load and a
+  // single value: at stride 2 the texture addresser is the busiest unit)
+  constexpr bool WIDE2 = XA && sizeof(TO) == 4 && S == 2;
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: XCD = blockIdx & 7.  A workgroup is a
@@ -210,6 +215,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
         // mask_cols spreads them over the slots of their columns
         if (lo <= D) load_run<2, float>(&xs[sl][D], xres, ro, soff);
         if (hi >= D + NC) load_run<2, float>(&xs[sl][D + 4], xres, ro + 8u, soff);
+      } else if constexpr (WIDE2) {
+        load_raw_run<NC + D, TO>(&xs[sl][D], xres, ro, soff);  // always called for whole rows at stride 2
       } else if (lo <= D && hi >= D + NC) {
         load_raw_run<NC, TO>(&xs[sl][D], xres, ro, soff);
       } else if (lo <= D) {
@@ -217,7 +224,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       } else {
         load_raw_run<NC - 4, TO>(&xs[sl][D + 4], xres, ro + 4u * (unsigned)sizeof(TO), soff);  // the rest of the core
       }
-      if (hi == XR) {
+      if (hi == XR && !WIDE2) {
 #pragma unroll
         for (int h = 0; h < D; ++h) xs[sl][D + NC + h] = load_raw_one<TO>(xres, ro + (unsigned)hoff[D + h], soff);
       }

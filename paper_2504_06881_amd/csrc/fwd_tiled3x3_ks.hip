@@ -13,11 +13,17 @@ hipError_t launch_ks(const Params& p, const void* x, const float* w_min, const f
                     : launch_tn<MODE, S, D, 4, false, TO, XA, true>(p, x, w_min, w_max, a, s);
 }
 
-// xa: bf16 rows whose core columns start at even elements for every lane (stride 1 only; the caller has checked)
+// xa: bf16 rows whose core columns start at even elements for every lane (stride 1), fp32 rows whose right halo
+// column is inside the row for every lane (stride 2); the caller has checked
 template <int MODE, typename TO>
 hipError_t launch_ks_geo(const Params& p, bool xa, const void* x, const float* w_min, const float* w_max,
                          const FwdArgs& a, hipStream_t s) {
-  if (p.sh == 2) return launch_ks<MODE, 2, 1, TO, false>(p, x, w_min, w_max, a, s);
+  if (p.sh == 2) {
+    if constexpr (sizeof(TO) == 4) {
+      if (xa) return launch_ks<MODE, 2, 1, TO, true>(p, x, w_min, w_max, a, s);
+    }
+    return launch_ks<MODE, 2, 1, TO, false>(p, x, w_min, w_max, a, s);
+  }
   if constexpr (sizeof(TO) == 2) {
     if (xa)
       return p.dh == 1 ? launch_ks<MODE, 1, 1, TO, true>(p, x, w_min, w_max, a, s)
@@ -59,7 +65,7 @@ bool forward_tiled3x3_ks_wanted(const Params& p, long long plain_workgroups, lon
 hipError_t launch_forward_tiled3x3_ks(const Params& p, bool bf16, bool xa, const void* x, const float* w_min,
                                       const float* w_max, const FwdArgs& a, hipStream_t s) {
   return bf16 ? launch_ks_mode<bf16_t>(p, xa, x, w_min, w_max, a, s)
-              : launch_ks_mode<float>(p, false, x, w_min, w_max, a, s);
+              : launch_ks_mode<float>(p, xa, x, w_min, w_max, a, s);
 }
 
 }  // namespace tconv
