@@ -93,6 +93,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
   // the 7 core columns and it are one run of 8 values (two 16-byte loads instead of a 16-, an 8-, a 4-byte load and a
   // single value: at stride 2 the texture addresser is the busiest unit)
   constexpr bool WIDE2 = XA && sizeof(TO) == 4 && S == 2;
+  // the same at stride 2 in 16-bit storage, where the run also starts at an even element: four dwords of two values
+  constexpr bool PK2 = XA && sizeof(TO) == 2 && S == 2;
 
   // ---- which c_out group (wave-uniform) and which pixel segment (per lane)
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: XCD = blockIdx & 7.  A workgroup is a
@@ -215,6 +217,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
         // mask_cols spreads them over the slots of their columns
         if (lo <= D) load_run<2, float>(&xs[sl][D], xres, ro, soff);
         if (hi >= D + NC) load_run<2, float>(&xs[sl][D + 4], xres, ro + 8u, soff);
+      } else if constexpr (PK2) {
+        load_run<4, float>(&xs[sl][D], xres, ro, soff);  // 8 values in slots D .. D+3; mask_cols spreads them
       } else if constexpr (WIDE2) {
         load_raw_run<NC + D, TO>(&xs[sl][D], xres, ro, soff);  // always called for whole rows at stride 2
       } else if (lo <= D && hi >= D + NC) {
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
       } else {
         load_raw_run<NC - 4, TO>(&xs[sl][D + 4], xres, ro + 4u * (unsigned)sizeof(TO), soff);  // the rest of the core
       }
-      if (hi == XR && !WIDE2) {
+      if (hi == XR && !WIDE2 && !PK2) {
 #pragma unroll
         for (int h = 0; h < D; ++h) xs[sl][D + NC + h] = load_raw_one<TO>(xres, ro + (unsigned)hoff[D + h], soff);
       }
@@ -251,10 +255,26 @@ __global__ __launch_bounds__(WAVES * 64, 2) void fwd_tiled3x3_kernel(
           xs[sl][D + 2 * h + 1] = __uint_as_float(PZ ? ((v1 & mr) | vB) : (v1 | mr));
         }
       }
+      if constexpr (PK2) {
+        // columns D .. D+7 (the core and the right halo column) from the four dwords, all read before any is written
+        unsigned pk[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) pk[h] = __float_as_uint(xs[sl][D + h]);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          const unsigned v0 = pk[h] << 16, v1 = pk[h] & 0xffff0000u;
+          const int o1 = D + 2 * h + 1;
+          unsigned m1 = mr;
+          if (o1 >= D + NC) m1 = PZ ? (m1 & mhalo[o1 - NC]) : (m1 | mhalo[o1 - NC]);
+          xs[sl][D + 2 * h] = __uint_as_float(PZ ? ((v0 & mr) | vB) : (v0 | mr));
+          xs[sl][o1] = __uint_as_float(PZ ? ((v1 & m1) | vB) : (v1 | m1));
+        }
+      }
 #pragma unroll
       for (int o = 0; o < XR; ++o) {
         if (o < lo || o >= hi) continue;
         if (PK && o >= D && o < D + NC) continue;
+        if (PK2 && o >= D) continue;
         unsigned m = mr;
         if (o < D) m = PZ ? (m & mhalo[o]) : (m | mhalo[o]);
         if (o >= D + NC) m = PZ ? (m & mhalo[o - NC]) : (m | mhalo[o - NC]);

@@ -18,12 +18,9 @@ hipError_t launch_ks(const Params& p, const void* x, const float* w_min, const f
 template <int MODE, typename TO>
 hipError_t launch_ks_geo(const Params& p, bool xa, const void* x, const float* w_min, const float* w_max,
                          const FwdArgs& a, hipStream_t s) {
-  if (p.sh == 2) {
-    if constexpr (sizeof(TO) == 4) {
-      if (xa) return launch_ks<MODE, 2, 1, TO, true>(p, x, w_min, w_max, a, s);
-    }
-    return launch_ks<MODE, 2, 1, TO, false>(p, x, w_min, w_max, a, s);
-  }
+  if (p.sh == 2)
+    return xa ? launch_ks<MODE, 2, 1, TO, true>(p, x, w_min, w_max, a, s)
+              : launch_ks<MODE, 2, 1, TO, false>(p, x, w_min, w_max, a, s);
   if constexpr (sizeof(TO) == 2) {
     if (xa)
       return p.dh == 1 ? launch_ks<MODE, 1, 1, TO, true>(p, x, w_min, w_max, a, s)

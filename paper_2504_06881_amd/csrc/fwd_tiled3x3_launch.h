@@ -38,12 +38,14 @@ hipError_t launch_one(const Params& p, const void* x, const float* w_min, const 
   // even), an even first output column of every segment (W_out even) and an even left margin D - pad_w
   // fp32 rows at stride 2 whose right halo column (register column 8 of the widest-placed segment, input column
   // 2 * (W_out - 4) - pad_w + 8) is inside the row: read in one run with the core columns
+  // (bf16 rows at stride 2: both: the run of 8 then starts at an even element and is four dwords)
+  const bool wide2 = S == 2 && 2 * p.Wo - p.pw <= p.W - 1 && !getenv("TCONV_FWD_NARROW2");
   const bool xa = (sizeof(TO) == 2 && S == 1 && p.W % 2 == 0 && p.Wo % 2 == 0 && (D - p.pw) % 2 == 0) ||
-                  (sizeof(TO) == 4 && S == 2 && 2 * p.Wo - p.pw <= p.W - 1 && !getenv("TCONV_FWD_NARROW2"));
+                  (sizeof(TO) == 4 && wide2) || (sizeof(TO) == 2 && wide2 && p.W % 2 == 0 && (D - p.pw) % 2 == 0);
   // the form that splits the input channels over the waves of a workgroup lives in a code object of its own
   if (forward_tiled3x3_ks_wanted(p, blocks4, resident_workgroups()))
     return launch_forward_tiled3x3_ks(p, sizeof(TO) == 2, xa, x, w_min, w_max, a, s);
-  if constexpr (sizeof(TO) == 2 && S == 1) {
+  if constexpr (sizeof(TO) == 2) {
     if (xa) {
       if (p.pad_zero)
         return tn == 2 ? launch_tn<MODE, S, D, 2, true, TO, true>(p, x, w_min, w_max, a, s)

@@ -244,7 +244,10 @@ def test_generic_kernel_on_ragged_shapes(cfg):
 
 @pytest.mark.parametrize("mode", MODES)
 def test_bf16_storage(mode):
-    for base in (RAGGED[0], RAGGED[1], RAGGED[2], RAGGED[4], RAGGED[20], CONFIGS["cfg1"]):
+    # the last two: stride 2 on even-width rows (a row's core and right halo columns read as four dwords), the second
+    # with enough input channels for the form that splits them over the waves
+    for base in (RAGGED[0], RAGGED[1], RAGGED[2], RAGGED[4], RAGGED[20], CONFIGS["cfg1"], RAGGED[3],
+                 LayerCfg("r_cin18_s2_even", 3, 18, 16, 24, 10, stride=2, seed=47)):
         cfg = base.with_(mode=mode, dtype="bf16")
         _check(cfg, alpha_beta="random" if mode in ("compound", "parallel") else None, tn=BOTH_TN)
         _check(cfg, integer=True, tn=BOTH_TN)
