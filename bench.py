@@ -41,12 +41,12 @@ HBM_PEAK_GBS = 8000.0
 # names the summary under profiles/ that holds the command and the raw figures.  Keyed by (workload, mode, dtype, op).
 MEASURED_FORWARD_TRAFFIC = {
     ("cfg4a", "compound", "f32", "full"): (142.4e6 + 335.5e6, "profiles/bench_cfg4a_all_kernels.md"),
-    ("cfg4a", "compound", "bf16", "full"): (84.1e6 + 234.9e6, "profiles/bench_cfg4a_bf16_all_kernels.md"),
+    ("cfg4a", "compound", "bf16", "full"): (84.6e6 + 234.9e6, "profiles/bench_cfg4a_bf16_all_kernels.md"),
     ("cfg4a", "compound", "f16", "full"): (58.1e6 + 234.9e6, "profiles/bench_cfg4a_f16_all_kernels.md"),
-    ("cfg4b", "compound", "f32", "full"): (156.8e6 + 176.2e6, "profiles/bench_cfg4b_all_kernels.md"),
+    ("cfg4b", "compound", "f32", "full"): (156.7e6 + 176.2e6, "profiles/bench_cfg4b_all_kernels.md"),
     ("cfg2_main", "compound", "f32", "full"): (53.4e6 + 167.8e6, "profiles/bench_cfg2_main_all_kernels.md"),
     ("cfg3a", "parallel", "f32", "full"): (56.6e6 + 256.9e6, "profiles/bench_cfg3a_all_kernels.md"),
-    ("cfg3b", "parallel", "f32", "full"): (70.7e6 + 70.7e6, "profiles/bench_cfg3b_all_kernels.md"),
+    ("cfg3b", "parallel", "f32", "full"): (70.7e6 + 70.6e6, "profiles/bench_cfg3b_all_kernels.md"),
     ("cfg3c", "parallel", "f32", "full"): (73.6e6 + 66.1e6, "profiles/bench_cfg3c_all_kernels.md"),
     ("cfg2_main", "minplus_max", "f32", "full"): (52.4e6 + 100.7e6, "profiles/bench_cfg2_main_minplus_max_all_kernels.md"),
     ("cfg2_main", "compound", "f32", "sum"): (37.7e6 + 34.6e6, "profiles/bench_sum_cfg2_main_all_kernels.md"),
