@@ -785,6 +785,171 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_kernel(Params p, const f
   }
 }
 
+// The same for planes of at most 1024 outputs with stride 1, dilation 1 and an output width that is a multiple of 4
+// (the 32 x 32, 16 x 16 and 8 x 8 maps of the paper's CIFAR networks): workgroup = (input channel c, G images whose
+// planes together have at most 1024 outputs), a thread owns FOUR ADJACENT output pixels of a row of one image.
+// Their windows overlap, so the thread keeps 3 x 6 input values instead of 4 x 9, reads gy with one 16-byte load per
+// output channel, and -- the point -- adds a winner's gradient into one of 18 fp64 slots of its own in LDS
+// ([slot][thread]: no other thread touches them, so a plain read-add-write serves: 8 LDS clocks where the atomic
+// into the shared plane costs 13 and, with the winners of neighbouring pixels falling on the same element, 20 on
+// average; fp32 slots would halve that again but miss the 1e-5 relative gate at 64 output channels).  After the
+// last output channel an input element is the sum of the at most six slots that cover it, read in a fixed order: no
+// plane in LDS, no atomics, and grad_x is the same on every run.  The parameter gradients are formed as in the
+// kernel above, in chunks of SUMQ_COB output channels.
+// Bins of one (output channel, branch, replica): 9 taps, the coefficient sum, one pad (an odd stride spreads the
+// replicas over the LDS banks).  With the slots 48 KB of LDS: three workgroups per compute unit.  Measured on the
+// 32 x 32, 64 -> 64 layer: 8 channels x 8 replicas 1.27 ms, 4 x 16 1.28, 2 x 8 (four workgroups) 1.28, 8 x 4 1.48,
+// 2 x 32 1.46, 16 x 8 (two workgroups) 1.46, 1 x 8 1.38; four slots for the coefficient sum (fewer adds to one
+// address) at a stride of 13: 1.32.
+constexpr int SUMQ_COB = 8, SUMQ_REP = 8, SUMQ_BS = 11;
+constexpr int SUMQ_PRIV_BYTES = 18 * 256 * 8;
+template <int MODE>
+__global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, const float* __restrict__ x,
+                                                                    const float* __restrict__ w_min,
+                                                                    const float* __restrict__ w_max,
+                                                                    const float* __restrict__ alpha,
+                                                                    const float* __restrict__ beta,
+                                                                    const float* __restrict__ gy,
+                                                                    float* __restrict__ grad_x,
+                                                                    float* __restrict__ grad_w_min,
+                                                                    float* __restrict__ grad_w_max,
+                                                                    float* __restrict__ grad_alpha,
+                                                                    float* __restrict__ grad_beta, int COB, int G) {
+  constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
+  constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
+  constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
+  constexpr int REP = SUMQ_REP;
+  constexpr int BS = SUMQ_BS;
+  const int NBINS = COB * NBR * REP * BS;
+  extern __shared__ double lds_d[];
+  const int c = blockIdx.x % p.C_in;
+  const int n0 = (blockIdx.x / p.C_in) * G;        // first image of the group
+  double* const priv = lds_d;                      // [18][256]
+  float* const xs = (float*)lds_d;                 // [G][H x W], before the slots are cleared
+  double* const bins = lds_d + 18 * 256;           // [COB][NBR][REP][BS]
+  const int HW = p.H * p.W;
+  for (int i = threadIdx.x; i < G * HW; i += blockDim.x) {
+    const int img = i / HW;
+    xs[i] = n0 + img < p.N ? x[((size_t)(n0 + img) * p.C_in + c) * HW + (i - img * HW)] : 0.f;
+  }
+  for (int e = threadIdx.x; e < NBINS; e += blockDim.x) bins[e] = 0.0;
+  __syncthreads();
+  const size_t plane = (size_t)p.Ho * p.Wo;
+  const int quads = (int)(plane >> 2);  // per image
+  const int img = min((int)threadIdx.x / quads, G - 1);
+  const bool live = (int)threadIdx.x < G * quads && n0 + img < p.N;
+  const int pix0 = live ? 4 * ((int)threadIdx.x - img * quads) : 0;
+  const int oh = pix0 / p.Wo, ow0 = pix0 - oh * p.Wo;
+  const int ih0 = oh - p.ph, iw0 = ow0 - p.pw;
+  float xw[3][6];  // padding = NaN: never an extremum
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+      const int ih = ih0 + r, iw = iw0 + q;
+      const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      xw[r][q] = ok ? xs[img * HW + ih * p.W + iw] : __uint_as_float(0x7fc00000u);
+    }
+  __syncthreads();  // every window is in registers: the slots take the place of the plane
+  double* const mine = priv + threadIdx.x;
+#pragma unroll
+  for (int sl = 0; sl < 18; ++sl) mine[sl * 256] = 0.0;
+  double* const mybins = bins + (size_t)(threadIdx.x & (REP - 1)) * BS;
+  const float* gyq = gy + (size_t)(live ? n0 + img : 0) * p.C_out * plane + pix0;
+  for (int cob = 0; cob < p.C_out; cob += COB) {
+    const int ncb = min(COB, p.C_out - cob);
+    if (live) {
+      for (int b = 0; b < ncb; ++b) {  // uniform over the workgroup
+        const int co = cob + b;
+        const float* ka = DO_MIN ? w_min + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const float* kb = DO_MAX ? w_max + ((size_t)co * p.C_in + c) * 9 : nullptr;
+        const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
+        const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
+        double* const bn = mybins + (size_t)b * NBR * REP * BS;
+        const float4 g4 = *(const float4*)(gyq + (size_t)co * plane);
+        const float gk[4] = {g4.x, g4.y, g4.z, g4.w};
+        double s_min = 0.0, s_max = 0.0;  // coefficient sums over the thread's pixels
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const double g = (double)gk[k];
+          float s1[9], s2[9];
+#pragma unroll
+          for (int t = 0; t < 9; ++t) {
+            if (DO_MIN) s1[t] = __fadd_rn(xw[t / 3][k + t % 3], ka[t]);
+            if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xw[t / 3][k + t % 3], kb[t]);
+          }
+          if (DO_MIN) {
+            float bmin; int t;
+            window_extremum9<false>(s1, bmin, t);
+            const double v = ca * g;
+            const int row = (t * 11) >> 5;
+            mine[(t + 3 * row + k) * 256] += v;  // slot (row, k + column)
+            atomicAdd(bn + t, v);
+            s_min += g * (double)bmin;
+          }
+          if (DO_MAX) {
+            float bmax; int t;
+            window_extremum9<true>(s2, bmax, t);
+            const double v = cb * g;
+            const int row = (t * 11) >> 5;
+            mine[(t + 3 * row + k) * 256] += v;
+            atomicAdd(bn + (NBR - 1) * REP * BS + t, v);
+            s_max += g * (double)bmax;
+          }
+        }
+        if (TWO) {
+          atomicAdd(bn + 9, s_min);
+          atomicAdd(bn + REP * BS + 9, s_max);
+        }
+      }
+    }
+    __syncthreads();
+    // publish the chunk (replicas in a fixed order, one fp32 atomic per value) and clear what was read
+    for (int v = threadIdx.x; v < COB * NBR * 10; v += blockDim.x) {
+      const int b = v / (NBR * 10), r = v - b * (NBR * 10), br = r / 10, t = r - br * 10;
+      double sum = 0.0;
+#pragma unroll
+      for (int q = 0; q < REP; ++q) {
+        double* const e = bins + ((size_t)(b * NBR + br) * REP + q) * BS + t;
+        sum += *e;
+        *e = 0.0;
+      }
+      const bool is_max = DO_MAX && (NBR == 1 || br == 1);
+      const int co = cob + b;
+      if (b < ncb) {
+        if (t < 9) {
+          float* gw = is_max ? grad_w_max : grad_w_min;
+          if (gw) atomicAdd(gw + ((size_t)co * p.C_in + c) * 9 + t, (float)sum);
+        } else if (TWO) {
+          float* gc = is_max ? grad_beta : grad_alpha;
+          if (gc) atomicAdd(gc + (size_t)c * p.C_out + co, (float)sum);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // An input element (ih, iw) lies in slot (r, q) of the thread whose outputs start at (ih + ph - r, iw + pw - q); that
+  // column is a multiple of 4 for one or two q in 0..5.  Slots outside the image never received anything.
+  for (int i = threadIdx.x; i < G * HW; i += blockDim.x) {
+    const int im = i / HW, pos = i - im * HW;
+    if (n0 + im >= p.N) break;
+    const int ih = pos / p.W, iw = pos - ih * p.W;
+    const int q0 = (iw + p.pw) & 3;
+    double sum = 0.0;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+      const int oh2 = ih + p.ph - r;
+      if (oh2 < 0 || oh2 >= p.Ho) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int q = q0 + 4 * j, oc = iw + p.pw - q;
+        if (q <= 5 && oc >= 0 && oc < p.Wo) sum += priv[(r * 6 + q) * 256 + im * quads + ((oh2 * p.Wo + oc) >> 2)];
+      }
+    }
+    grad_x[((size_t)(n0 + im) * p.C_in + c) * HW + pos] = (float)sum;
+  }
+}
+
 __global__ __launch_bounds__(256) void sum_fill_zero_kernel(float* __restrict__ p, size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
@@ -864,6 +1029,22 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
         if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(fmax, nw, s);
         zero_fill(g.grad_alpha, nab, s);
         zero_fill(g.grad_beta, nab, s);
+        // planes of at most 1024 outputs, stride 1, dilation 1, rows of a multiple of 4 outputs, gy readable in
+        // 16-byte pieces: a thread owns four adjacent outputs and its own gradient slots
+        const long long plane = (long long)p.Ho * p.Wo;
+        const int G = plane > 0 && plane <= 1024 ? (int)std::min<long long>(1024 / plane, p.N) : 0;
+        const bool quad = p.sh == 1 && p.sw == 1 && p.dh == 1 && p.dw == 1 && p.Wo % 4 == 0 && G >= 1 &&
+                          G * plane > 512 && (size_t)G * p.H * p.W * 4 <= (size_t)SUMQ_PRIV_BYTES &&
+                          ((uintptr_t)g.gy & 15) == 0 && !(sep && strcmp(sep, "spread") == 0);
+        if (quad) {
+          const int cobq = SUMQ_COB;
+          const size_t qbytes = (size_t)SUMQ_PRIV_BYTES + (size_t)SUMQ_REP * cobq * NBR * SUMQ_BS * 8;
+          const long long groups = ((long long)p.N + G - 1) / G;
+          hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE>), dim3((unsigned)(groups * p.C_in)), dim3(256),
+                             qbytes, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax,
+                             g.grad_alpha, g.grad_beta, cobq, G);
+          return hipGetLastError();
+        }
         if (n_bands == 1)
           hipLaunchKernelGGL((sum_bwd_fused3x3_kernel<MODE, true>), dim3((unsigned)blocks), dim3(256), bytes(TH), s, p,
                              a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax, g.grad_alpha,

@@ -48,6 +48,14 @@ SHAPES = [
     LayerCfg("s_bands_5x5_s2", 1, 2, 260, 48, 3, KH=5, KW=5, stride=2, pad=2, seed=55),   # the same for the generic gradient kernel
     LayerCfg("s_1d_k5", 2, 5, 1, 60, 6, KH=1, KW=5, pad=0, seed=52),           # a one-dimensional layer: H = 1, KH = 1
     LayerCfg("s_1d_k9_s2", 2, 3, 1, 101, 4, KH=1, KW=9, stride=2, pad=0, seed=53),
+    # planes of at most 1024 outputs in rows of a multiple of 4, alone or several images to a workgroup (the last
+    # group short): the backward kernel whose threads own four adjacent outputs
+    LayerCfg("s_quad", 2, 5, 32, 32, 11, seed=56),
+    LayerCfg("s_quad_p0", 2, 3, 26, 34, 5, pad=0, seed=57),
+    LayerCfg("s_quad_wide", 1, 4, 20, 44, 9, seed=58),
+    LayerCfg("s_quad_g4", 9, 3, 16, 16, 6, seed=59),
+    LayerCfg("s_quad_g16", 20, 2, 8, 8, 5, seed=60),
+    LayerCfg("s_quad_g2", 5, 3, 16, 24, 10, seed=61),
 ]
 
 
@@ -72,6 +80,20 @@ def test_sum_backward_in_separate_calls_and_kernels(cfg):
     separate kernels run (TCONV_SUM_BWD=separate), as they do for calls that want only one of the two."""
     import os
     os.environ["TCONV_SUM_BWD"] = "separate"
+    try:
+        for mode in MODES:
+            _check(cfg.with_(mode=mode))
+        _check(cfg.with_(mode="compound"), integer=True)
+    finally:
+        os.environ.pop("TCONV_SUM_BWD", None)
+
+
+@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name.startswith("s_quad")], ids=lambda c: c.name)
+def test_sum_backward_of_mid_size_planes_by_the_kernel_for_any_plane(cfg):
+    """TCONV_SUM_BWD=spread keeps the fused kernel that serves every plane size on the shapes the four-adjacent-outputs
+    kernel takes by default (the default runs in test_sum_layers)."""
+    import os
+    os.environ["TCONV_SUM_BWD"] = "spread"
     try:
         for mode in MODES:
             _check(cfg.with_(mode=mode))
