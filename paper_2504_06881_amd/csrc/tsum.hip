@@ -87,15 +87,18 @@ __global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const fl
 // WAVES waves of a workgroup share the segments and differ in output-channel group.  Per input
 // channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
 // of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
-template <int MODE, int D>
+template <int MODE, int D, int S>
 __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
     Params p, const float* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
     float* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  constexpr int PX = 8, TN = 4;
-  constexpr int XR = PX + 2 * D;
+  constexpr int PX = S == 1 ? 8 : 4, TN = 4;
+  constexpr int CORE = 8;                       // columns of the 32-byte run every row is loaded with
+  constexpr int NHR = (PX - 1) * S + D + 1 - CORE;  // halo columns right of the run: D at stride 1, none at stride 2
+  constexpr int XR = D + CORE + NHR;
+  static_assert(NHR >= 0 && (S == 1 || D == 1), "geometries: stride 1 with dilation 1 or 2, stride 2 with dilation 1");
 
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  xcd_runs: every XCD gets a contiguous
   // run of workgroup numbers, so that the output-channel groups of a pixel block (consecutive numbers, same
@@ -121,27 +124,32 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
   const int ow0 = min(ow_nom, p.Wo - PX);
   const int first_q = unit_ok ? ow_nom - ow0 : PX;
 
-  const int iw0 = ow0 - p.pw;  // input column of register column 0
+  const int iw0 = ow0 * S - p.pw;  // input column of register column 0
   const size_t HW = (size_t)p.H * p.W;
   const unsigned HWb = (unsigned)(HW * sizeof(float));
   const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
   unsigned roff[3], mrow[3];
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
-    const int ih = oh - p.ph + i * D;
+    const int ih = oh * S - p.ph + i * D;
     mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
     const int ihc = min(max(ih, 0), p.H - 1);
     // byte offset of the first core column (iw0 + D >= 0 because pad_w <= D)
     roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(float));
   }
-  int hoff[2 * D];
-  unsigned mhalo[2 * D];
+  // halo columns: D left of the run, NHR right of it; at stride 2 the run's last column can lie past the row end
+  // (the load then takes the next row's first value, or 0 past the tensor), so every column has a mask
+  int hoff[D + NHR];
+  unsigned mcol[XR];
 #pragma unroll
-  for (int h = 0; h < 2 * D; ++h) {
-    const int o = (h < D) ? h : h + PX;
+  for (int o = 0; o < XR; ++o) {
     const int iw = iw0 + o;
-    mhalo[h] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
-    hoff[h] = (min(max(iw, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
+    mcol[o] = (iw >= 0 && iw < p.W) ? 0u : 0xffffffffu;
+  }
+#pragma unroll
+  for (int h = 0; h < D + NHR; ++h) {
+    const int o = (h < D) ? h : h + CORE;
+    hoff[h] = (min(max(iw0 + o, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
   }
   auto load_rows = [&](float (&xs)[3][XR], int c) {
     const unsigned soff = (unsigned)min(c, p.C_in - 1) * HWb;
@@ -149,9 +157,9 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
     for (int i = 0; i < 3; ++i) {
 #pragma unroll
       for (int h = 0; h < D; ++h) xs[i][h] = load_one<float>(xres, roff[i] + (unsigned)hoff[h], soff);
-      load_run<PX, float>(&xs[i][D], xres, roff[i], soff);
+      load_run<CORE, float>(&xs[i][D], xres, roff[i], soff);
 #pragma unroll
-      for (int h = 0; h < D; ++h) xs[i][D + PX + h] = load_one<float>(xres, roff[i] + (unsigned)hoff[D + h], soff);
+      for (int h = 0; h < NHR; ++h) xs[i][D + CORE + h] = load_one<float>(xres, roff[i] + (unsigned)hoff[D + h], soff);
     }
   };
   auto mask_rows = [&](float (&xs)[3][XR]) {
@@ -159,10 +167,8 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
     for (int i = 0; i < 3; ++i)
 #pragma unroll
       for (int o = 0; o < XR; ++o) {
-        unsigned m = mrow[i];
-        if (o < D) m |= mhalo[o];
-        if (o >= D + PX) m |= mhalo[o - PX];
-        xs[i][o] = nan_or(xs[i][o], m);
+        const bool inside = S == 1 && o >= D && o < D + CORE;  // stride 1: the run lies inside the row
+        xs[i][o] = nan_or(xs[i][o], inside ? mrow[i] : (mrow[i] | mcol[o]));
       }
   };
 
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
         for (int i = 0; i < 3; ++i)
 #pragma unroll
           for (int j = 0; j < 3; ++j) {
-            const float xv = xs[i][q + j * D];
+            const float xv = xs[i][q * S + j * D];
             if (DO_MIN) sa[i * 3 + j] = __fadd_rn(xv, ka[i * 3 + j]);
             if (DO_MAX) sb[i * 3 + j] = (MODE == TCONV_COMPOUND) ? sa[i * 3 + j] : __fadd_rn(xv, kb[i * 3 + j]);
           }
@@ -963,9 +969,11 @@ void zero_fill(float* p, size_t n, hipStream_t s) {  // a kernel, so that the ca
 }
 
 bool tiled_ok(const Params& p) {
-  if (p.KH != 3 || p.KW != 3 || p.sh != 1 || p.sw != 1 || p.dh != p.dw) return false;
-  if (p.dh != 1 && p.dh != 2) return false;
-  if (p.pw > p.dw || p.Wo < 8) return false;
+  if (p.KH != 3 || p.KW != 3 || p.sh != p.sw || p.dh != p.dw) return false;
+  const bool geo = (p.sh == 1 && (p.dh == 1 || p.dh == 2)) || (p.sh == 2 && p.dh == 1);
+  if (!geo) return false;
+  if (p.pw > p.dw || p.Wo < (p.sh == 1 ? 8 : 4)) return false;
+  if (p.W < 8) return false;  // a row is loaded as a run of 8 columns
   if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
   return true;
 }
@@ -975,7 +983,8 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
   const bool force_generic = e && strcmp(e, "generic") == 0;
   if (tiled_ok(p) && !force_generic) {
-    const int segs = (p.Wo + 7) / 8;
+    const int px = p.sh == 1 ? 8 : 4;
+    const int segs = (p.Wo + px - 1) / px;
     const long long n_units = (long long)p.N * p.Ho * segs;
     const int n_groups = (p.C_out + 3) / 4;
     const long long blocks = ((n_units + 63) / 64) * ((n_groups + WAVES - 1) / WAVES);
@@ -985,11 +994,14 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const char* xe = getenv("TCONV_XCD_RUNS");
     const int xcd_runs = xe ? atoi(xe) : (w_bytes <= 2LL * 1024 * 1024 ? 1 : 0);
     const unsigned grid = (unsigned)(((blocks + 7) / 8) * 8);
-    if (p.dh == 1)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
+    if (p.sh == 2)
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 2>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
+                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+    else if (p.dh == 1)
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
                          a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
     else
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
                          a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
   } else {
     const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;

@@ -56,6 +56,9 @@ SHAPES = [
     LayerCfg("s_quad_g4", 9, 3, 16, 16, 6, seed=59),
     LayerCfg("s_quad_g16", 20, 2, 8, 8, 5, seed=60),
     LayerCfg("s_quad_g2", 5, 3, 16, 24, 10, seed=61),
+    # stride 2 in the tiled forward kernel
+    LayerCfg("s_3x3_s2_even", 2, 5, 16, 32, 9, stride=2, seed=62),       # the run of 8 columns ends past the row
+    LayerCfg("s_3x3_s2_p0", 2, 3, 15, 21, 4, stride=2, pad=0, seed=63),  # last segment shifted, no padding
 ]
 
 
@@ -100,6 +103,12 @@ def test_sum_backward_of_mid_size_planes_by_the_kernel_for_any_plane(cfg):
         _check(cfg.with_(mode="compound"), integer=True)
     finally:
         os.environ.pop("TCONV_SUM_BWD", None)
+
+
+def test_sum_tiled_forward_takes_stride_two():
+    for name in ("s_3x3_s2", "s_3x3_s2_even", "s_3x3_s2_p0"):
+        cfg = next(c for c in SHAPES if c.name == name)
+        assert tb.tconv_sum_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "sum_tiled3x3"
 
 
 def test_sum_layer_at_a_benchmark_size():
