@@ -333,6 +333,19 @@ __global__ __launch_bounds__(256) void sum_bwd_x_kernel(Params p, const float* _
 // that equal the extremum (19 instructions where the chain takes 27).  NaN sums (taps outside the image) are
 // ignored by the three-operand instructions and equal nothing.
 template <bool WANT_MAX>
+__device__ __forceinline__ void window_extremum9_rc(const float (&s)[9], float& best, int& row, int& col) {
+  float r[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+    r[i] = WANT_MAX ? fmaxf(fmaxf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]) : fminf(fminf(s[3 * i], s[3 * i + 1]), s[3 * i + 2]);
+  best = WANT_MAX ? fmaxf(fmaxf(r[0], r[1]), r[2]) : fminf(fminf(r[0], r[1]), r[2]);
+  const bool c0 = r[0] == best, c1 = r[1] == best;
+  row = c0 ? 0 : (c1 ? 1 : 2);
+  const float a0 = c0 ? s[0] : (c1 ? s[3] : s[6]);
+  const float a1 = c0 ? s[1] : (c1 ? s[4] : s[7]);
+  col = (a0 == best) ? 0 : ((a1 == best) ? 1 : 2);
+}
+template <bool WANT_MAX>
 __device__ __forceinline__ void window_extremum9(const float (&s)[9], float& best, int& tap) {
   float r[3];
 #pragma unroll
@@ -874,7 +887,7 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
         double* const bn = mybins + (size_t)b * NBR * REP * BS;
         const float4 g4 = *(const float4*)(gyq + (size_t)co * plane);
         const float gk[4] = {g4.x, g4.y, g4.z, g4.w};
-        double s_min = 0.0, s_max = 0.0;  // coefficient sums over the thread's pixels
+        float s_min = 0.f, s_max = 0.f;  // coefficient sums over the thread's four pixels
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const double g = (double)gk[k];
@@ -885,27 +898,25 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
             if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xw[t / 3][k + t % 3], kb[t]);
           }
           if (DO_MIN) {
-            float bmin; int t;
-            window_extremum9<false>(s1, bmin, t);
+            float bmin; int row, col;
+            window_extremum9_rc<false>(s1, bmin, row, col);
             const double v = ca * g;
-            const int row = (t * 11) >> 5;
-            mine[(t + 3 * row + k) * 256] += v;  // slot (row, k + column)
-            atomicAdd(bn + t, v);
-            s_min += g * (double)bmin;
+            mine[(row * 6 + col + k) * 256] += v;  // slot (row, k + column)
+            atomicAdd(bn + (row * 3 + col), v);
+            s_min = fmaf(gk[k], bmin, s_min);
           }
           if (DO_MAX) {
-            float bmax; int t;
-            window_extremum9<true>(s2, bmax, t);
+            float bmax; int row, col;
+            window_extremum9_rc<true>(s2, bmax, row, col);
             const double v = cb * g;
-            const int row = (t * 11) >> 5;
-            mine[(t + 3 * row + k) * 256] += v;
-            atomicAdd(bn + (NBR - 1) * REP * BS + t, v);
-            s_max += g * (double)bmax;
+            mine[(row * 6 + col + k) * 256] += v;
+            atomicAdd(bn + (NBR - 1) * REP * BS + (row * 3 + col), v);
+            s_max = fmaf(gk[k], bmax, s_max);
           }
         }
         if (TWO) {
-          atomicAdd(bn + 9, s_min);
-          atomicAdd(bn + REP * BS + 9, s_max);
+          atomicAdd(bn + 9, (double)s_min);
+          atomicAdd(bn + REP * BS + 9, (double)s_max);
         }
       }
     }
