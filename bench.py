@@ -61,6 +61,18 @@ BAR_LAYERS = [("cfg2_main", None), ("cfg2_stem", None), ("cfg3a", None), ("cfg3b
 ROTATE_BYTES = 600e6   # backward calls are timed on rotating operand sets larger than the 256 MB last-level cache
 
 
+def calibrate_copy(torch, dev) -> None:
+    """--calibrate-copy: a plain 256 MiB device copy, three times; what FETCH_SIZE / WRITE_SIZE read for it fixes the
+    unit of those counters in the same profiler run."""
+    src = torch.empty(64 * 1024 * 1024, device=dev)  # 256 MiB
+    src.normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def alu_peak_pairs_per_s(mode: str) -> float:
     """Plain fp32 VALU roofline in pairs/s: one v_add_f32 and one v_max/min_f32 per pair,
     except compound where one add feeds both branches (3 lane-instructions per 2 pairs)."""
@@ -278,13 +290,7 @@ def main() -> int:
     layers = [Layer(c, args.op) for c in cfgs]
 
     if args.calibrate_copy:
-        src = torch.empty(64 * 1024 * 1024, device=dev)  # 256 MiB
-        src.normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dev)
     for _ in range(args.warmup):
         for L in layers:
             L.fwd(); L.bwd()
@@ -648,6 +654,8 @@ def bench_net(args, torch, tb, emit: bool = True):
         else:
             step_eager()
 
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -919,13 +927,7 @@ def bench_depthwise(args, torch, tb) -> int:
     # one backward call for every gradient, as a training step makes it
     bwd = lambda: tb.tconv_depthwise_backward(d, x, w_min, w_max, al, be, gy, idx, gx, g1, g2, ga, gb)
     if args.calibrate_copy:
-        src = torch.empty(64 * 1024 * 1024, device=dev)
-        src.normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch, dev)
     for _ in range(args.warmup):
         fwd(); bwd()
     torch.cuda.synchronize()
