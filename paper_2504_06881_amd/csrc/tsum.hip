@@ -804,9 +804,12 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_kernel(Params p, const f
   }
 }
 
-// The same for planes of at most 1024 outputs with stride 1, dilation 1 and an output width that is a multiple of 4
-// (the 32 x 32, 16 x 16 and 8 x 8 maps of the paper's CIFAR networks): workgroup = (input channel c, G images whose
-// planes together have at most 1024 outputs), a thread owns FOUR ADJACENT output pixels of a row of one image.
+// The same for stride 1, dilation 1 and an output width that is a multiple of 4.  Planes of at most 1024 outputs (the
+// 32 x 32, 16 x 16 and 8 x 8 maps of the paper's CIFAR networks): workgroup = (input channel c, G images whose planes
+// together have at most 1024 outputs).  Larger planes: workgroup = (image, input channel, band of RB input rows); it
+// scans the RB + 2 output rows whose windows reach the band (at most 1024 outputs) and an output counts for the
+// parameter gradients in the band that owns the first row of its window.  A thread owns FOUR ADJACENT output pixels
+// of a row of one image.
 // Their windows overlap, so the thread keeps 3 x 6 input values instead of 4 x 9, reads gy with one 16-byte load per
 // output channel, and -- the point -- adds a winner's gradient into one of 18 fp64 slots of its own in LDS
 // ([slot][thread]: no other thread touches them, so a plain read-add-write serves: 8 LDS clocks where the atomic
@@ -833,7 +836,8 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
                                                                     float* __restrict__ grad_w_min,
                                                                     float* __restrict__ grad_w_max,
                                                                     float* __restrict__ grad_alpha,
-                                                                    float* __restrict__ grad_beta, int COB, int G) {
+                                                                    float* __restrict__ grad_beta, int COB, int G, int RB,
+                                                                    int n_bands) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
@@ -841,25 +845,36 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   constexpr int BS = SUMQ_BS;
   const int NBINS = COB * NBR * REP * BS;
   extern __shared__ double lds_d[];
-  const int c = blockIdx.x % p.C_in;
-  const int n0 = (blockIdx.x / p.C_in) * G;        // first image of the group
+  const int band = blockIdx.x % n_bands;
+  const int c = (blockIdx.x / n_bands) % p.C_in;
+  const int n0 = (blockIdx.x / (n_bands * p.C_in)) * G;  // first image of the group
+  // the band owns the input rows [r0, r1); the output rows whose windows reach them are scanned
+  const int r0 = band * RB, r1 = min(r0 + RB, p.H);
+  const int oh_lo = max(0, r0 + p.ph - 2), oh_hi = min(p.Ho - 1, r1 - 1 + p.ph);
+  const int srows = max(oh_hi - oh_lo + 1, 0);
+  const int xr0 = max(0, oh_lo - p.ph), xr1 = srows > 0 ? min(p.H, oh_hi - p.ph + 3) : xr0;  // input rows read
   double* const priv = lds_d;                      // [18][256]
-  float* const xs = (float*)lds_d;                 // [G][H x W], before the slots are cleared
+  float* const xs = (float*)lds_d;                 // [G][(xr1 - xr0) x W], before the slots are cleared
   double* const bins = lds_d + 18 * 256;           // [COB][NBR][REP][BS]
   const int HW = p.H * p.W;
-  for (int i = threadIdx.x; i < G * HW; i += blockDim.x) {
-    const int img = i / HW;
-    xs[i] = n0 + img < p.N ? x[((size_t)(n0 + img) * p.C_in + c) * HW + (i - img * HW)] : 0.f;
+  const int XW = (xr1 - xr0) * p.W;
+  for (int i = threadIdx.x; i < G * XW; i += blockDim.x) {
+    const int img = i / XW;
+    xs[i] = n0 + img < p.N ? x[((size_t)(n0 + img) * p.C_in + c) * HW + (size_t)xr0 * p.W + (i - img * XW)] : 0.f;
   }
   for (int e = threadIdx.x; e < NBINS; e += blockDim.x) bins[e] = 0.0;
   __syncthreads();
   const size_t plane = (size_t)p.Ho * p.Wo;
-  const int quads = (int)(plane >> 2);  // per image
-  const int img = min((int)threadIdx.x / quads, G - 1);
+  const int qrow = p.Wo >> 2;             // quads per output row
+  const int quads = srows * qrow;         // per image
+  const int img = quads > 0 ? min((int)threadIdx.x / quads, G - 1) : 0;
   const bool live = (int)threadIdx.x < G * quads && n0 + img < p.N;
-  const int pix0 = live ? 4 * ((int)threadIdx.x - img * quads) : 0;
-  const int oh = pix0 / p.Wo, ow0 = pix0 - oh * p.Wo;
+  const int lq = live ? (int)threadIdx.x - img * quads : 0;
+  const int srow = lq / qrow;
+  const int oh = oh_lo + srow, ow0 = 4 * (lq - srow * qrow);
   const int ih0 = oh - p.ph, iw0 = ow0 - p.pw;
+  // an output counts for the parameter gradients in the band that owns the first row of its window inside the image
+  const bool own = live && max(ih0, 0) >= r0 && max(ih0, 0) < r1;
   float xw[3][6];  // padding = NaN: never an extremum
 #pragma unroll
   for (int r = 0; r < 3; ++r)
@@ -867,14 +882,14 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
     for (int q = 0; q < 6; ++q) {
       const int ih = ih0 + r, iw = iw0 + q;
       const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-      xw[r][q] = ok ? xs[img * HW + ih * p.W + iw] : __uint_as_float(0x7fc00000u);
+      xw[r][q] = ok ? xs[img * XW + (ih - xr0) * p.W + iw] : __uint_as_float(0x7fc00000u);
     }
   __syncthreads();  // every window is in registers: the slots take the place of the plane
   double* const mine = priv + threadIdx.x;
 #pragma unroll
   for (int sl = 0; sl < 18; ++sl) mine[sl * 256] = 0.0;
   double* const mybins = bins + (size_t)(threadIdx.x & (REP - 1)) * BS;
-  const float* gyq = gy + (size_t)(live ? n0 + img : 0) * p.C_out * plane + pix0;
+  const float* gyq = gy + (size_t)(live ? n0 + img : 0) * p.C_out * plane + (size_t)oh * p.Wo + ow0;
   for (int cob = 0; cob < p.C_out; cob += COB) {
     const int ncb = min(COB, p.C_out - cob);
     if (live) {
@@ -902,7 +917,7 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
             window_extremum9_rc<false>(s1, bmin, row, col);
             const double v = ca * g;
             mine[(row * 6 + col + k) * 256] += v;  // slot (row, k + column)
-            atomicAdd(bn + (row * 3 + col), v);
+            if (own) atomicAdd(bn + (row * 3 + col), v);
             s_min = fmaf(gk[k], bmin, s_min);
           }
           if (DO_MAX) {
@@ -910,11 +925,11 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
             window_extremum9_rc<true>(s2, bmax, row, col);
             const double v = cb * g;
             mine[(row * 6 + col + k) * 256] += v;
-            atomicAdd(bn + (NBR - 1) * REP * BS + (row * 3 + col), v);
+            if (own) atomicAdd(bn + (NBR - 1) * REP * BS + (row * 3 + col), v);
             s_max = fmaf(gk[k], bmax, s_max);
           }
         }
-        if (TWO) {
+        if (TWO && own) {
           atomicAdd(bn + 9, (double)s_min);
           atomicAdd(bn + REP * BS + 9, (double)s_max);
         }
@@ -947,23 +962,25 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   }
   // An input element (ih, iw) lies in slot (r, q) of the thread whose outputs start at (ih + ph - r, iw + pw - q); that
   // column is a multiple of 4 for one or two q in 0..5.  Slots outside the image never received anything.
-  for (int i = threadIdx.x; i < G * HW; i += blockDim.x) {
-    const int im = i / HW, pos = i - im * HW;
+  const int BW = (r1 - r0) * p.W;
+  for (int i = threadIdx.x; i < G * BW; i += blockDim.x) {
+    const int im = i / BW, pos = i - im * BW;
     if (n0 + im >= p.N) break;
-    const int ih = pos / p.W, iw = pos - ih * p.W;
+    const int br = pos / p.W, iw = pos - br * p.W, ih = r0 + br;
     const int q0 = (iw + p.pw) & 3;
     double sum = 0.0;
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
       const int oh2 = ih + p.ph - r;
-      if (oh2 < 0 || oh2 >= p.Ho) continue;
+      if (oh2 < oh_lo || oh2 > oh_hi) continue;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int q = q0 + 4 * j, oc = iw + p.pw - q;
-        if (q <= 5 && oc >= 0 && oc < p.Wo) sum += priv[(r * 6 + q) * 256 + im * quads + ((oh2 * p.Wo + oc) >> 2)];
+        if (q <= 5 && oc >= 0 && oc < p.Wo)
+          sum += priv[(r * 6 + q) * 256 + im * quads + (oh2 - oh_lo) * qrow + (oc >> 2)];
       }
     }
-    grad_x[((size_t)(n0 + im) * p.C_in + c) * HW + pos] = (float)sum;
+    grad_x[((size_t)(n0 + im) * p.C_in + c) * HW + (size_t)ih * p.W + iw] = (float)sum;
   }
 }
 
@@ -1052,20 +1069,33 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
         if (MODE == TCONV_MAX || MODE == TCONV_PARALLEL) zero_fill(fmax, nw, s);
         zero_fill(g.grad_alpha, nab, s);
         zero_fill(g.grad_beta, nab, s);
-        // planes of at most 1024 outputs, stride 1, dilation 1, rows of a multiple of 4 outputs, gy readable in
-        // 16-byte pieces: a thread owns four adjacent outputs and its own gradient slots
+        // stride 1, dilation 1, rows of a multiple of 4 outputs, gy readable in 16-byte pieces: a thread owns four
+        // adjacent outputs and its own gradient slots.  Planes of at most 1024 outputs: one band, as many images to a
+        // workgroup as fill its threads.  Larger planes: one image, bands of RB input rows whose RB + 2 scanned
+        // output rows fill the threads (at least 4 rows to a band: at most 1.5 x the outputs are scanned).
         const long long plane = (long long)p.Ho * p.Wo;
-        const int G = plane > 0 && plane <= 1024 ? (int)std::min<long long>(1024 / plane, p.N) : 0;
+        const int qrow = p.Wo / 4;
+        int G = 0, RB = p.H, nb = 1;
+        if (plane > 0 && plane <= 1024) {
+          G = (int)std::min<long long>(1024 / plane, p.N);
+          if (G * plane <= 512) G = 0;  // too few outputs for the threads
+        } else if (qrow >= 1 && qrow <= 42) {
+          G = 1;
+          RB = 256 / qrow - 2;
+          nb = (p.H + RB - 1) / RB;
+        }
+        const long long xrows = std::min<long long>((long long)RB + 4, p.H);
         const bool quad = p.sh == 1 && p.sw == 1 && p.dh == 1 && p.dw == 1 && p.Wo % 4 == 0 && G >= 1 &&
-                          G * plane > 512 && (size_t)G * p.H * p.W * 4 <= (size_t)SUMQ_PRIV_BYTES &&
+                          (size_t)G * xrows * p.W * 4 <= (size_t)SUMQ_PRIV_BYTES &&
+                          (long long)((p.N + G - 1) / G) * p.C_in * nb <= 0x7fffffffLL &&
                           ((uintptr_t)g.gy & 15) == 0 && !(sep && strcmp(sep, "spread") == 0);
         if (quad) {
           const int cobq = SUMQ_COB;
           const size_t qbytes = (size_t)SUMQ_PRIV_BYTES + (size_t)SUMQ_REP * cobq * NBR * SUMQ_BS * 8;
           const long long groups = ((long long)p.N + G - 1) / G;
-          hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE>), dim3((unsigned)(groups * p.C_in)), dim3(256),
+          hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE>), dim3((unsigned)(groups * p.C_in * nb)), dim3(256),
                              qbytes, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax,
-                             g.grad_alpha, g.grad_beta, cobq, G);
+                             g.grad_alpha, g.grad_beta, cobq, G, RB, nb);
           return hipGetLastError();
         }
         if (n_bands == 1)

@@ -56,6 +56,7 @@ SHAPES = [
     LayerCfg("s_quad_g4", 9, 3, 16, 16, 6, seed=59),
     LayerCfg("s_quad_g16", 20, 2, 8, 8, 5, seed=60),
     LayerCfg("s_quad_g2", 5, 3, 16, 24, 10, seed=61),
+    LayerCfg("s_quad_bands_p0", 1, 2, 70, 30, 3, pad=0, seed=64),   # more than 1024 outputs: bands of rows, no padding
     # stride 2 in the tiled forward kernel
     LayerCfg("s_3x3_s2_even", 2, 5, 16, 32, 9, stride=2, seed=62),       # the run of 8 columns ends past the row
     LayerCfg("s_3x3_s2_p0", 2, 3, 15, 21, 4, stride=2, pad=0, seed=63),  # last segment shifted, no padding
@@ -91,7 +92,8 @@ def test_sum_backward_in_separate_calls_and_kernels(cfg):
         os.environ.pop("TCONV_SUM_BWD", None)
 
 
-@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name.startswith("s_quad")], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name.startswith("s_quad") or c.name in ("s_tall", "s_bands")],
+                         ids=lambda c: c.name)
 def test_sum_backward_of_mid_size_planes_by_the_kernel_for_any_plane(cfg):
     """TCONV_SUM_BWD=spread keeps the fused kernel that serves every plane size on the shapes the four-adjacent-outputs
     kernel takes by default (the default runs in test_sum_layers)."""
