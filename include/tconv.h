@@ -264,7 +264,7 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
                           float* grad_bias, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Sum-channel layers (fp32 only; TCONV_E_UNSUPPORTED for bf16).  Base operators of Sec. 3.1 for one
+ * Sum-channel layers.  Base operators of Sec. 3.1 for one
  * input channel: MinPlus2d / MaxPlus2d = the minimum / maximum of x + w over the KH x KW window.
  *   mode MIN       layer (i)  MinPlus-Sum-Conv2d:  y = sum over c_in of MinPlus2d(x, w_min)
  *   mode MAX       layer (ii) MaxPlus-Sum-Conv2d:  y = sum over c_in of MaxPlus2d(x, w_max)
@@ -273,10 +273,17 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
  * (the two-parameter layers of Sec. 3.5 and 3.6; a one-parameter layer is this one with
  * beta = 1 - alpha, and its gradient is grad_alpha - grad_beta).
  *   alpha, beta  fp32 [C_in, C_out] (element c_in*C_out + c_out) or NULL (= all ones); not used in MIN / MAX.
- *   y        fp32 [N, C_out, H_out, W_out], overwritten.
+ *   y        [N, C_out, H_out, W_out] in the storage type, overwritten.
  * Padded taps are skipped; a channel's term is fl(fl(alpha*m) + fl(beta*M)); the terms are added in
  * ascending c_in starting from +0, every add rounded to fp32, so the result is reproducible bit for bit.
+ * dtype TCONV_BF16 (storage of x, the kernels and y, as in the conventions above: widened exactly, fp32
+ * arithmetic, y rounded to nearest-even once, after the channel sum): forward for the geometries of the
+ * "sum_tiled3x3" kernel (else TCONV_E_UNSUPPORTED), backward for every geometry; both need a workspace
+ * (device, 256-byte aligned) of tconv_sum_workspace_bytes bytes, else TCONV_E_WORKSPACE.  fp32 needs none.
  */
+/* Workspace of tconv_sum_forward (backward == 0) or tconv_sum_backward (backward != 0), in *bytes (host). */
+int tconv_sum_workspace_bytes(const tconv_desc* desc, int backward, size_t* bytes);
+
 int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
                       const float* alpha, const float* beta, void* y, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
@@ -289,8 +296,8 @@ int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, 
  * and the max-plus winner the same with beta, grad_w_max, grad_beta, M (coefficients 1 in MIN / MAX
  * mode; COMPOUND adds both branches into ONE kernel gradient, grad_w_min if non-NULL else grad_w_max).
  * Every gradient pointer may be NULL (not computed), not all of them; grad_alpha / grad_beta must be
- * NULL in MIN / MAX mode.  All gradients fp32, overwritten; sums are kept in fp64 inside a
- * workgroup and combined in fp32 in an unspecified order.
+ * NULL in MIN / MAX mode.  gy and all gradients fp32 (also with bf16 storage of x and the kernels),
+ * overwritten; sums are kept in fp64 inside a workgroup and combined in fp32 in an unspecified order.
  * TCONV_E_UNSUPPORTED: rows longer than about 5000 elements or kernel windows of more than 62 taps.
  */
 int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,

@@ -22,7 +22,7 @@ OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2, "backward_alpha_
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_forward_fused", "tconv_backward_bias",
            "tconv_backward_input",
            "tconv_backward_weight", "tconv_backward_weight_noalloc", "tconv_backward", "tconv_backward_alpha_beta", "tconv_backward_params", "tconv_sum_forward", "tconv_sum_backward",
-           "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
+           "tconv_sum_workspace_bytes", "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
            "tconv3d_out_shape", "tconv3d_workspace_bytes", "tconv3d_forward_kernel_name", "tconv3d_forward", "tconv3d_backward_input", "tconv3d_backward_weight",
@@ -153,6 +153,8 @@ def load() -> ctypes.CDLL:
         lib.tconv_backward_params.restype = ctypes.c_int
         lib.tconv_sum_forward.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_sum_backward.argtypes = [D] + [P] * 12 + [ctypes.c_size_t, P]
+        lib.tconv_sum_workspace_bytes.argtypes = [D, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+        lib.tconv_sum_workspace_bytes.restype = ctypes.c_int
         lib.tconv_sum_forward_kernel_name.argtypes = [D]
         lib.tconv_sum_forward_kernel_name.restype = ctypes.c_char_p
         lib.tconv_depthwise_forward.argtypes = [D] + [P] * 8 + [ctypes.c_size_t, P]
@@ -329,6 +331,14 @@ def tconv_sum_backward(desc: Desc, x, w_min, w_max, alpha, beta, gy, grad_x, gra
                                      _ptr(grad_w_max), _ptr(grad_alpha), _ptr(grad_beta),
                                      _ptr(workspace), wsz, _stream()),
            "tconv_sum_backward")
+
+
+def tconv_sum_workspace_bytes(desc: Desc, backward: bool) -> int:
+    n = ctypes.c_size_t()
+    cd = desc.c()
+    _check(load().tconv_sum_workspace_bytes(ctypes.byref(cd), 1 if backward else 0, ctypes.byref(n)),
+           "tconv_sum_workspace_bytes")
+    return int(n.value)
 
 
 def tconv_sum_forward_kernel_name(desc: Desc) -> str:

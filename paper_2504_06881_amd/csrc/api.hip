@@ -348,22 +348,34 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 
+int tconv_sum_workspace_bytes(const tconv_desc* desc, int backward, size_t* bytes) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!bytes || p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;
+  if (desc->dtype != TCONV_F32 && desc->dtype != TCONV_BF16) return TCONV_E_UNSUPPORTED;
+  *bytes = sum_workspace(p, desc->dtype, backward != 0);
+  return TCONV_OK;
+}
+
 int tconv_sum_forward(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
                       const float* alpha, const float* beta, void* y, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!x || !y) return TCONV_E_INVAL;
   if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
-  if (desc->dtype != TCONV_F32 || p.pad_zero) return TCONV_E_UNSUPPORTED;
+  if ((desc->dtype != TCONV_F32 && desc->dtype != TCONV_BF16) || p.pad_zero) return TCONV_E_UNSUPPORTED;
+  if (!sum_forward_supported(p, desc->dtype)) return TCONV_E_UNSUPPORTED;
+  const size_t need = sum_workspace(p, desc->dtype, false);
+  if (need && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return TCONV_E_WORKSPACE;
   SumArgs a = {(const float*)x, (const float*)w_min, (const float*)w_max, alpha, beta, (float*)y};
   if (p.mode == TCONV_COMPOUND) a.w_min = a.w_max = (const float*)(w_min ? w_min : w_max);
   if (p.mode != TCONV_MAX && !a.w_min) return TCONV_E_INVAL;
   if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
   own_status();
-  const hipError_t e = launch_sum_forward(p, a, (hipStream_t)hip_stream);
+  const hipError_t e = launch_sum_forward(p, desc->dtype, a, workspace, (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 
@@ -371,13 +383,14 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
                        const float* alpha, const float* beta, const float* gy, float* grad_x,
                        float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   Params p;
   const int rc = make_params(desc, &p);
   if (rc != TCONV_OK) return rc;
   if (!x || !gy) return TCONV_E_INVAL;
   if (p.mode > TCONV_PARALLEL) return TCONV_E_INVAL;  // the mixed layers have no channel sum
-  if (desc->dtype != TCONV_F32 || p.pad_zero) return TCONV_E_UNSUPPORTED;
+  if ((desc->dtype != TCONV_F32 && desc->dtype != TCONV_BF16) || p.pad_zero) return TCONV_E_UNSUPPORTED;
+  const size_t need = sum_workspace(p, desc->dtype, true);
+  if (need && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return TCONV_E_WORKSPACE;
   const bool two = p.mode == TCONV_COMPOUND || p.mode == TCONV_PARALLEL;
   if (!two && (grad_alpha || grad_beta)) return TCONV_E_INVAL;
   if (!grad_x && !grad_w_min && !grad_w_max && !grad_alpha && !grad_beta) return TCONV_E_INVAL;
@@ -387,7 +400,7 @@ int tconv_sum_backward(const tconv_desc* desc, const void* x, const void* w_min,
   if (p.mode != TCONV_MIN && !a.w_max) return TCONV_E_INVAL;
   const SumGrads g = {gy, grad_x, grad_w_min, grad_w_max, grad_alpha, grad_beta};
   own_status();
-  const hipError_t e = launch_sum_backward(p, a, g, (hipStream_t)hip_stream);
+  const hipError_t e = launch_sum_backward(p, desc->dtype, a, g, workspace, (hipStream_t)hip_stream);
   if (e == hipErrorInvalidValue) return TCONV_E_UNSUPPORTED;  // rows or kernel window too large for the LDS kernels
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }

@@ -192,8 +192,13 @@ hipError_t launch_backward_alpha_beta(const Params& p, int dtype, const float* g
                                       const void* y_max, float* grad_alpha, float* grad_beta, double* partial,
                                       hipStream_t s);
 
-hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s);
-hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s);
+// Sum-channel layers.  dtype TCONV_BF16: x, the kernels and y are bf16 behind the float pointers of SumArgs, workspace
+// holds sum_workspace(p, dtype, backward) bytes; forward then only where sum_forward_supported says so.
+size_t sum_workspace(const Params& p, int dtype, bool backward);
+bool sum_forward_supported(const Params& p, int dtype);
+hipError_t launch_sum_forward(const Params& p, int dtype, const SumArgs& a, void* workspace, hipStream_t s);
+hipError_t launch_sum_backward(const Params& p, int dtype, const SumArgs& a, const SumGrads& g, void* workspace,
+                               hipStream_t s);
 const char* sum_forward_kernel_name(const Params& p);
 
 hipError_t launch_forward_3d(const Params3& p, const FwdArgs& a, hipStream_t s);

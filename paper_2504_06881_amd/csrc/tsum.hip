@@ -87,11 +87,11 @@ __global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const fl
 // WAVES waves of a workgroup share the segments and differ in output-channel group.  Per input
 // channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
 // of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
-template <int MODE, int D, int S>
+template <int MODE, int D, int S, typename TO>
 __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
-    Params p, const float* __restrict__ x, const float* __restrict__ w_min,
+    Params p, const TO* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
-    float* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs) {
+    TO* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
   constexpr int PX = S == 1 ? 8 : 4, TN = 4;
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
 
   const int iw0 = ow0 * S - p.pw;  // input column of register column 0
   const size_t HW = (size_t)p.H * p.W;
-  const unsigned HWb = (unsigned)(HW * sizeof(float));
-  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(float)));
+  const unsigned HWb = (unsigned)(HW * sizeof(TO));
+  const rsrc_t xres = make_rsrc(x, (unsigned)((size_t)p.N * p.C_in * HW * sizeof(TO)));
   unsigned roff[3], mrow[3];
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
     mrow[i] = (ih >= 0 && ih < p.H) ? 0u : 0xffffffffu;
     const int ihc = min(max(ih, 0), p.H - 1);
     // byte offset of the first core column (iw0 + D >= 0 because pad_w <= D)
-    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(float));
+    roff[i] = (unsigned)(((size_t)n * p.C_in * HW + (size_t)ihc * p.W + (size_t)(iw0 + D)) * sizeof(TO));
   }
   // halo columns: D left of the run, NHR right of it; at stride 2 the run's last column can lie past the row end
   // (the load then takes the next row's first value, or 0 past the tensor), so every column has a mask
@@ -149,17 +149,17 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
 #pragma unroll
   for (int h = 0; h < D + NHR; ++h) {
     const int o = (h < D) ? h : h + CORE;
-    hoff[h] = (min(max(iw0 + o, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(float);
+    hoff[h] = (min(max(iw0 + o, 0), p.W - 1) - (iw0 + D)) * (int)sizeof(TO);
   }
   auto load_rows = [&](float (&xs)[3][XR], int c) {
     const unsigned soff = (unsigned)min(c, p.C_in - 1) * HWb;
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
 #pragma unroll
-      for (int h = 0; h < D; ++h) xs[i][h] = load_one<float>(xres, roff[i] + (unsigned)hoff[h], soff);
-      load_run<CORE, float>(&xs[i][D], xres, roff[i], soff);
+      for (int h = 0; h < D; ++h) xs[i][h] = load_one<TO>(xres, roff[i] + (unsigned)hoff[h], soff);
+      load_run<CORE, TO>(&xs[i][D], xres, roff[i], soff);
 #pragma unroll
-      for (int h = 0; h < NHR; ++h) xs[i][D + CORE + h] = load_one<float>(xres, roff[i] + (unsigned)hoff[D + h], soff);
+      for (int h = 0; h < NHR; ++h) xs[i][D + CORE + h] = load_one<TO>(xres, roff[i] + (unsigned)hoff[D + h], soff);
     }
   };
   auto mask_rows = [&](float (&xs)[3][XR]) {
@@ -1006,7 +1006,7 @@ bool tiled_ok(const Params& p) {
   return true;
 }
 
-template <int MODE>
+template <int MODE, typename TO>
 hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
   const bool force_generic = e && strcmp(e, "generic") == 0;
@@ -1022,15 +1022,19 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const char* xe = getenv("TCONV_XCD_RUNS");
     const int xcd_runs = xe ? atoi(xe) : (w_bytes <= 2LL * 1024 * 1024 ? 1 : 0);
     const unsigned grid = (unsigned)(((blocks + 7) / 8) * 8);
+    const TO* x = (const TO*)a.x;
+    TO* y = (TO*)a.y;
     if (p.sh == 2)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 2>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
-                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 2, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
+                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
     else if (p.dh == 1)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
-                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 1, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
+                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
     else
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2, 1>), dim3(grid), dim3(WAVES * 64), 0, s, p, a.x, a.w_min,
-                         a.w_max, a.alpha, a.beta, a.y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2, 1, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
+                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+  } else if (sizeof(TO) != 4) {
+    return hipErrorInvalidValue;  // bf16 storage: the tiled kernel only
   } else {
     const size_t total = (size_t)p.N * p.C_out * p.Ho * p.Wo;
     hipLaunchKernelGGL(sum_fwd_generic_kernel<MODE>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p,
@@ -1173,16 +1177,90 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
 
 }  // namespace
 
-hipError_t launch_sum_forward(const Params& p, const SumArgs& a, hipStream_t s) {
-  switch (p.mode) {
-    case TCONV_MAX: return launch_fwd<TCONV_MAX>(p, a, s);
-    case TCONV_MIN: return launch_fwd<TCONV_MIN>(p, a, s);
-    case TCONV_COMPOUND: return launch_fwd<TCONV_COMPOUND>(p, a, s);
-    default: return launch_fwd<TCONV_PARALLEL>(p, a, s);
+namespace {
+
+__global__ __launch_bounds__(256) void sum_widen_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    dst[i] = __uint_as_float((unsigned)src[i] << 16);
+}
+
+void widen(const void* src, float* dst, size_t n, hipStream_t s) {
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(sum_widen_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)src, dst, n);
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// bf16 storage: fp32 copies of the kernel tensors (they are read as scalars, in whole dwords) and, for the backward
+// pass, of x; returns the copies' pointers in a
+void widen_operands(const Params& p, SumArgs& a, bool with_x, void* workspace, hipStream_t s) {
+  char* ws = (char*)workspace;
+  const size_t nw = (size_t)p.C_out * p.K;
+  const bool use_min = p.mode != TCONV_MAX, use_max = p.mode != TCONV_MIN;
+  const bool shared = p.mode == TCONV_COMPOUND;  // one kernel tensor behind both pointers
+  const float* wmin_f = nullptr;
+  if (use_min) {
+    widen(a.w_min, (float*)ws, nw, s);
+    wmin_f = (const float*)ws;
+    ws += align256(nw * 4);
+  }
+  const float* wmax_f = wmin_f;
+  if (use_max && !shared) {
+    widen(a.w_max, (float*)ws, nw, s);
+    wmax_f = (const float*)ws;
+    ws += align256(nw * 4);
+  }
+  a.w_min = use_min ? wmin_f : nullptr;
+  a.w_max = use_max ? wmax_f : nullptr;
+  if (with_x) {
+    const size_t nx = (size_t)p.N * p.C_in * p.H * p.W;
+    widen(a.x, (float*)ws, nx, s);
+    a.x = (const float*)ws;
   }
 }
 
-hipError_t launch_sum_backward(const Params& p, const SumArgs& a, const SumGrads& g, hipStream_t s) {
+}  // namespace
+
+size_t sum_workspace(const Params& p, int dtype, bool backward) {
+  if (dtype != TCONV_BF16) return 0;
+  const size_t nw = (size_t)p.C_out * p.K;
+  size_t b = align256(nw * 4) * (p.mode == TCONV_PARALLEL ? 2 : 1);
+  if (backward) b += align256((size_t)p.N * p.C_in * p.H * p.W * 4);
+  return b;
+}
+
+bool sum_forward_supported(const Params& p, int dtype) {
+  if (dtype == TCONV_F32) return true;
+  const char* e = getenv("TCONV_FORWARD_KERNEL");
+  return dtype == TCONV_BF16 && tiled_ok(p) && !(e && strcmp(e, "generic") == 0);
+}
+
+template <typename TO>
+static hipError_t launch_sum_forward_t(const Params& p, const SumArgs& a, hipStream_t s) {
+  switch (p.mode) {
+    case TCONV_MAX: return launch_fwd<TCONV_MAX, TO>(p, a, s);
+    case TCONV_MIN: return launch_fwd<TCONV_MIN, TO>(p, a, s);
+    case TCONV_COMPOUND: return launch_fwd<TCONV_COMPOUND, TO>(p, a, s);
+    default: return launch_fwd<TCONV_PARALLEL, TO>(p, a, s);
+  }
+}
+
+// bf16 storage (x, kernels, y; workspace of sum_workspace bytes): x is read as bf16 by the kernel, y rounded on store
+hipError_t launch_sum_forward(const Params& p, int dtype, const SumArgs& a0, void* workspace, hipStream_t s) {
+  if (dtype != TCONV_BF16) return launch_sum_forward_t<float>(p, a0, s);
+  SumArgs a = a0;
+  widen_operands(p, a, false, workspace, s);
+  return launch_sum_forward_t<bf16_t>(p, a, s);
+}
+
+// bf16 storage of x and the kernels: the gradient kernels run on fp32 copies (the layer is bound by arithmetic, the
+// copies are a few per cent of its traffic)
+hipError_t launch_sum_backward(const Params& p, int dtype, const SumArgs& a0, const SumGrads& g, void* workspace,
+                               hipStream_t s) {
+  SumArgs a = a0;
+  if (dtype == TCONV_BF16) widen_operands(p, a, true, workspace, s);
   switch (p.mode) {
     case TCONV_MAX: return launch_bwd<TCONV_MAX>(p, a, g, s);
     case TCONV_MIN: return launch_bwd<TCONV_MIN>(p, a, g, s);

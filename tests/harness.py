@@ -230,6 +230,9 @@ def run_oracle_sum(cfg, inp, alpha, beta, backward=True):
     from oracle import tsum_oracle as osum
     s = oracle_shape(cfg)
     r = {"y": osum.forward(s, cfg.mode, inp["x"], inp["w_min"], inp["w_max"], alpha, beta)}
+    if cfg.dtype == "bf16":   # storage rounding of the output, as the library stores it (torch's cast)
+        import torch
+        r["y"] = torch.from_numpy(r["y"]).to(torch.bfloat16).float().numpy()
     if backward:
         r.update(osum.backward(s, cfg.mode, inp["x"], inp["gy"], inp["w_min"], inp["w_max"], alpha, beta))
         ab = [None if v is None else np.abs(v) for v in (alpha, beta)]
@@ -253,14 +256,23 @@ def run_hip_sum(cfg, inp, alpha, beta, backward=True, device="cuda:0"):
     def up(a):
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
 
-    x, gy, al, be = up(inp["x"]), up(inp["gy"]), up(alpha), up(beta)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32   # storage of x, the kernels and y
+
+    def ups(a):
+        return None if a is None else up(a).to(tdt)
+
+    def ws(backward_):
+        n = tb.tconv_sum_workspace_bytes(d, backward_)
+        return torch.empty(n, dtype=torch.uint8, device=dev) if n else None
+
+    x, gy, al, be = ups(inp["x"]), up(inp["gy"]), up(alpha), up(beta)
     if cfg.mode == "compound":
-        w_min = w_max = up(inp["w_min"])
+        w_min = w_max = ups(inp["w_min"])
     else:
-        w_min, w_max = up(inp["w_min"]), up(inp["w_max"])
-    y = torch.full((cfg.N, cfg.C_out, ho, wo), float("nan"), device=dev)
-    tb.tconv_sum_forward(d, x, w_min, w_max, al, be, y)
-    out = dict(y=y)
+        w_min, w_max = ups(inp["w_min"]), ups(inp["w_max"])
+    y = torch.full((cfg.N, cfg.C_out, ho, wo), float("nan"), device=dev, dtype=tdt)
+    tb.tconv_sum_forward(d, x, w_min, w_max, al, be, y, ws(False))
+    out = dict(y=y.float())
     if backward:
         two = cfg.mode in ("compound", "parallel")
         nan = lambda shape: torch.full(shape, float("nan"), device=dev)
@@ -270,7 +282,7 @@ def run_hip_sum(cfg, inp, alpha, beta, backward=True, device="cuda:0"):
         g2 = nan(wshape) if cfg.mode in ("max", "parallel") else None
         ga = nan((cfg.C_in, cfg.C_out)) if two else None
         gb = nan((cfg.C_in, cfg.C_out)) if two else None
-        tb.tconv_sum_backward(d, x, w_min, w_max, al, be, gy, gx, g1, g2, ga, gb)
+        tb.tconv_sum_backward(d, x, w_min, w_max, al, be, gy, gx, g1, g2, ga, gb, ws(True))
         out.update(grad_x=gx, grad_w_min=g1, grad_w_max=g2, grad_alpha=ga, grad_beta=gb)
     torch.cuda.synchronize()
     return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}

@@ -113,6 +113,45 @@ def test_sum_tiled_forward_takes_stride_two():
         assert tb.tconv_sum_forward_kernel_name(tb.Desc.from_cfg(cfg)) == "sum_tiled3x3"
 
 
+BF16_SHAPES = ("s_cfg1", "s_3x3", "s_3x3_even", "s_3x3_d2", "s_3x3_s2", "s_3x3_s2_even", "s_quad", "s_quad_g4", "s_bands")
+
+
+@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name in BF16_SHAPES], ids=lambda c: c.name)
+def test_sum_layers_in_bf16_storage(cfg):
+    """x, the kernels and y stored as bf16 (inputs on the bf16 grid, so the fp32 oracle sees the widened values; its
+    output rounded by torch's cast): y bit for bit, gradients (fp32) to the usual gate."""
+    for mode in MODES:
+        _check(cfg.with_(mode=mode, dtype="bf16"))
+    _check(cfg.with_(mode="compound", dtype="bf16"), integer=True)
+
+
+def test_sum_bf16_needs_its_workspace_and_the_tiled_forward():
+    import torch
+    cfg = SHAPES[1].with_(mode="compound", dtype="bf16")
+    d = tb.Desc.from_cfg(cfg)
+    assert tb.tconv_sum_workspace_bytes(d, False) > 0
+    assert tb.tconv_sum_workspace_bytes(d, True) > tb.tconv_sum_workspace_bytes(d, False)
+    assert tb.tconv_sum_workspace_bytes(tb.Desc.from_cfg(cfg.with_(dtype="f32")), True) == 0
+    dev = torch.device("cuda:0")
+    ho, wo = tb.tconv_out_shape(d)
+    x = torch.zeros(cfg.N, cfg.C_in, cfg.H, cfg.W, device=dev, dtype=torch.bfloat16)
+    w = torch.zeros(cfg.C_out, cfg.C_in, 3, 3, device=dev, dtype=torch.bfloat16)
+    y = torch.zeros(cfg.N, cfg.C_out, ho, wo, device=dev, dtype=torch.bfloat16)
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_sum_forward(d, x, w, w, None, None, y)            # no workspace
+    assert e.value.status == -3
+    c5 = next(c for c in SHAPES if c.name == "s_5x5").with_(mode="compound", dtype="bf16")   # no tiled kernel for 5x5
+    d5 = tb.Desc.from_cfg(c5)
+    h5, w5 = tb.tconv_out_shape(d5)
+    x5 = torch.zeros(c5.N, c5.C_in, c5.H, c5.W, device=dev, dtype=torch.bfloat16)
+    k5 = torch.zeros(c5.C_out, c5.C_in, 5, 5, device=dev, dtype=torch.bfloat16)
+    y5 = torch.zeros(c5.N, c5.C_out, h5, w5, device=dev, dtype=torch.bfloat16)
+    wsb = torch.empty(max(tb.tconv_sum_workspace_bytes(d5, False), 256), dtype=torch.uint8, device=dev)
+    with pytest.raises(tb.TconvError) as e:
+        tb.tconv_sum_forward(d5, x5, k5, k5, None, None, y5, wsb)
+    assert e.value.status == -4
+
+
 def test_sum_layer_at_a_benchmark_size():
     """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
     cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
@@ -131,6 +170,6 @@ def test_sum_error_paths():
     with pytest.raises(tb.TconvError) as e:     # nothing requested
         tb.tconv_sum_backward(d, z, None, z, None, None, z, None, None, None, None, None)
     assert e.value.status == -1
-    with pytest.raises(tb.TconvError) as e:     # bf16 storage is not built for these layers
-        tb.tconv_sum_forward(tb.Desc.from_cfg(cfg.with_(dtype="bf16")), z, None, z, None, None, z)
+    with pytest.raises(tb.TconvError) as e:     # binary16 arithmetic is not built for these layers
+        tb.tconv_sum_forward(tb.Desc.from_cfg(cfg.with_(dtype="f16")), z, None, z, None, None, z)
     assert e.value.status == -4
