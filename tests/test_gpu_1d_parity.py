@@ -108,3 +108,28 @@ def test_error_paths():
     with pytest.raises(tb.TconvError) as e:
         tb.tconv1d_backward_input(d, z, None, None, zi, None, z)
     assert e.value.status == -1
+
+
+def _random_1d_layers(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        k = int(rng.choice([1, 2, 3, 3, 3, 4, 5, 7, 9, 15]))
+        s_, d = int(rng.choice([1, 1, 2, 3, 4])), int(rng.integers(1, 3))
+        pad = int(rng.integers(0, d * (k - 1) + 1))
+        cin, cout = int(rng.choice([1, 2, 3, 5, 6, 9, 12, 13])), int(rng.integers(1, 12))
+        L = int(rng.integers(1, 300))
+        cfg = Layer1dCfg(f"lrnd{len(out)}_k{k}s{s_}d{d}p{pad}_{cin}x{L}_{cout}", int(rng.integers(1, 4)), cin, L, cout,
+                         K=k, stride=s_, pad=pad, dil=d, seed=5000 + len(out))
+        if cfg.L_out < 1:
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_1d_layers(40, 20250614), ids=lambda c: c.name)
+def test_random_sequences(cfg):
+    mode = MODES[cfg.seed % 6]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)

@@ -1,5 +1,6 @@
 """GPU parity of the three-dimensional layers (tconv3d_forward / tconv3d_backward_input / tconv3d_backward_weight)
 against their CPU oracle: outputs and winners bit for bit, gradients within 1e-5 of the size of their summands."""
+import numpy as np
 import pytest
 
 import harness as hs
@@ -98,3 +99,29 @@ def test_error_paths():
     with pytest.raises(tb.TconvError) as e:   # fp32 only
         tb.tconv3d_out_shape(tb.Desc3d(1, 2, 4, 4, 4, 2, 3, 3, 3, pad=(1, 1, 1), dtype="bf16"))
     assert e.value.status == -4
+
+
+def _random_3d_layers(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        k = tuple(int(v) for v in rng.choice([1, 2, 3, 3], size=3))
+        st = tuple(int(v) for v in rng.choice([1, 1, 2], size=3))
+        dl = tuple(int(v) for v in rng.choice([1, 1, 2], size=3))
+        pad = tuple(int(rng.integers(0, d * (kk - 1) + 1)) for kk, d in zip(k, dl))
+        dims = tuple(int(v) for v in rng.integers(1, 14, size=3))
+        cin, cout = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        cfg = Layer3dCfg(f"vrnd{len(out)}", int(rng.integers(1, 3)), cin, dims[0], dims[1], dims[2], cout, k=k,
+                         stride=st, pad=pad, dil=dl, seed=6000 + len(out))
+        if min(cfg.out) < 1:
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_3d_layers(40, 20250615), ids=lambda c: c.name)
+def test_random_volumes(cfg):
+    mode = MODES[cfg.seed % 6]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)

@@ -120,3 +120,28 @@ def test_error_paths():
                                    None, z, zb)
     assert e.value.status == -1
     torch.cuda.synchronize()
+
+
+def _random_dw_layers(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        s_ = int(rng.integers(1, 3))
+        pad = int(rng.integers(0, 2))
+        cin, mult = int(rng.integers(1, 20)), int(rng.choice([1, 1, 1, 2, 3]))
+        h, w = int(rng.integers(3, 40)), int(rng.integers(3, 48))
+        nimg = int(rng.integers(1, 6))
+        cfg = LayerCfg(f"drnd{len(out)}_s{s_}p{pad}_{nimg}x{cin}x{h}x{w}_m{mult}", nimg, cin, h, w, cin * mult, stride=s_,
+                       pad=pad, seed=4000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1:
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_dw_layers(40, 20250613), ids=lambda c: c.name)
+def test_random_depthwise_layers(cfg):
+    mode = MODES[cfg.seed % 4]
+    _check(cfg.with_(mode=mode))
+    _check(cfg.with_(mode=mode), integer=True)

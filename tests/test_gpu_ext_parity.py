@@ -9,7 +9,7 @@ import pytest
 import harness as hs
 from paper_2504_06881_amd import binding as tb
 from paper_2504_06881_amd.inputs import CONFIGS, LayerCfg, make_inputs
-from test_gpu_parity import BOTH_TN, KNOBS, MODES, RAGGED, RAGGED_LARGE, TILED
+from test_gpu_parity import BOTH_TN, KNOBS, MODES, RAGGED, RAGGED_LARGE, TILED, _random_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -203,3 +203,16 @@ def test_residual_block_training_step(stride):
         a, b = got[k].astype(np.float64), np.asarray(want[k], np.float64)
         tol = 2e-5 * max(1.0, float(np.max(np.abs(b))))
         assert np.max(np.abs(a - b)) <= tol, (k, float(np.max(np.abs(a - b))), tol)
+
+
+@pytest.mark.parametrize("cfg", _random_layers(30, 20250611), ids=lambda c: c.name)
+def test_random_layers_with_zero_padding_and_epilogue(cfg):
+    """Random shapes in every form of the tiled kernel: zero padding, and the fused epilogue (bias, scale / shift,
+    shortcut) with either padding, fp32 and bf16 storage."""
+    mode = MODES[cfg.seed % 4]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check_ext(cfg.with_(mode=mode, pad_mode="zero"), alpha_beta=ab, tn=BOTH_TN)
+    _check_ext(cfg.with_(mode=mode, pad_mode="zero"), integer=True, alpha_beta=ab, tn=BOTH_TN)
+    pm = ("identity", "zero")[cfg.seed // 4 % 2]
+    _check_ext(cfg.with_(mode=mode, pad_mode=pm), ep_kind="bar", alpha_beta=ab, tn=BOTH_TN)
+    _check_ext(cfg.with_(mode=MODES[(cfg.seed + 1) % 4], pad_mode=pm, dtype="bf16"), ep_kind="bar", tn=BOTH_TN, backward=False)

@@ -9,7 +9,7 @@ import pytest
 import harness as hs
 from paper_2504_06881_amd import binding as tb
 from paper_2504_06881_amd.inputs import CONFIGS, LayerCfg, make_inputs
-from test_gpu_parity import MODES, RAGGED, RAGGED_LARGE
+from test_gpu_parity import MODES, RAGGED, RAGGED_LARGE, _random_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -103,3 +103,13 @@ def test_f16_error_paths():
     with pytest.raises(tb.TconvError) as e:   # no epilogue in the binary16 contract
         tb.tconv_forward_fused(d, z, None, z, None, None, z, None, None, None, zi, bias=torch.zeros(8, device="cuda"))
     assert e.value.status == -4
+
+
+@pytest.mark.parametrize("cfg", _random_layers(30, 20250612), ids=lambda c: c.name)
+def test_random_layers(cfg):
+    """Random shapes in binary16: the packed kernel where it applies (stride 1, core columns at an even element),
+    else the generic kernel; real and integer data."""
+    mode = MODES[cfg.seed % 4]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check16(cfg.with_(mode=mode, dtype="f16"), alpha_beta=ab)
+    _check16(cfg.with_(mode=mode, dtype="f16"), alpha_beta=ab, integer=True)

@@ -9,7 +9,7 @@ import pytest
 import harness as hs
 from paper_2504_06881_amd import binding as tb
 from paper_2504_06881_amd.inputs import CONFIGS, make_inputs
-from test_gpu_parity import BOTH_TN, RAGGED, RAGGED_LARGE, _check
+from test_gpu_parity import BOTH_TN, RAGGED, RAGGED_LARGE, _check, _random_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -85,3 +85,11 @@ def test_kernel_selection_and_error_paths():
     with pytest.raises(tb.TconvError) as e:   # no Sum-channel variant of a mixed layer
         tb.tconv_sum_forward(d, z, z, z, None, None, z)
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("cfg", _random_layers(30, 20250610), ids=lambda c: c.name)
+def test_random_layers_in_every_form(cfg):
+    mode = MIXED[cfg.seed % 2]
+    _check(cfg.with_(mode=mode), tn=BOTH_TN)
+    _check(cfg.with_(mode=mode), integer=True, tn=BOTH_TN)
+    _check(cfg.with_(mode=MIXED[1 - cfg.seed % 2], dtype="bf16"), integer=True, tn=BOTH_TN)

@@ -206,6 +206,74 @@ def test_ragged_shapes_that_split_the_input_channels(cfg):
     _check(cfg.with_(mode="parallel"), integer=True, alpha_beta="contrast")
 
 
+def _random_layers(n, seed):
+    """Seeded random 3x3 layers inside the tiled kernel's domain: stride / dilation in {(1,1), (1,2), (2,1)}, padding
+    0 .. dilation, odd and even widths, channel counts around the multiples of 2, 4, 8 and 16 the kernel forms cut at."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        s, d = [(1, 1), (1, 2), (2, 1)][len(out) % 3]
+        rng.integers(3)
+        pad = int(rng.integers(0, d + 1))
+        cin = int(rng.choice([1, 2, 3, 5, 8, 9, 15, 16, 17, 23, 32, 33]))
+        cout = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 19]))
+        h, w = int(rng.integers(5, 30)), int(rng.integers(12, 48))
+        nimg = int(rng.integers(1, 5))
+        cfg = LayerCfg(f"rnd{len(out)}_s{s}d{d}p{pad}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w, cout, stride=s,
+                       pad=pad, dil=d, seed=1000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < (8 if s == 1 else 4):
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_layers(60, 20250607), ids=lambda c: c.name)
+def test_random_layers_in_every_form_and_storage(cfg):
+    """Random shapes, every form of the tiled kernel forced in turn (2 / 4 output channels per lane, input channels
+    split), a random mode each, fp32 and bf16 storage, real and integer (all ties) data."""
+    assert tb.tconv_forward_kernel_name(tb.Desc.from_cfg(cfg)) in TILED
+    rng = np.random.default_rng(cfg.seed)
+    mode = MODES[int(rng.integers(4))]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab, tn=BOTH_TN)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True, tn=BOTH_TN)
+    _check(cfg.with_(mode=mode, dtype="bf16"), alpha_beta=ab, tn=BOTH_TN)
+    other = MODES[(MODES.index(mode) + 2) % 4]
+    _check(cfg.with_(mode=other, dtype="bf16"), alpha_beta="random" if other in ("compound", "parallel") else None,
+           integer=True, tn=BOTH_TN)
+
+
+def _random_windows(n, seed):
+    """Seeded random layers with any window from 1x1 to 7x7, strides 1-3, dilations 1-2: whatever kernel the library
+    picks for them (row-tiled, tiled 3x3, generic)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        kh, kw = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        s, d = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        pad = int(rng.integers(0, d * (min(kh, kw) - 1) + 1))
+        cin, cout = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        h, w = int(rng.integers(1, 30)), int(rng.integers(1, 40))
+        nimg = int(rng.integers(1, 4))
+        cfg = LayerCfg(f"wrnd{len(out)}_{kh}x{kw}s{s}d{d}p{pad}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w, cout,
+                       KH=kh, KW=kw, stride=s, pad=pad, dil=d, seed=3000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1:
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_windows(60, 20250609), ids=lambda c: c.name)
+def test_random_windows(cfg):
+    rng = np.random.default_rng(cfg.seed)
+    mode = MODES[int(rng.integers(4))]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)
+
+
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[13], RAGGED[15], RAGGED[20],
                                  RAGGED[23], RAGGED_LARGE[0], RAGGED_LARGE[1], RAGGED_SPLIT[0]], ids=lambda c: c.name)
 def test_parameter_gradients_in_one_call(cfg):

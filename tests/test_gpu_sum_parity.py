@@ -152,6 +152,37 @@ def test_sum_bf16_needs_its_workspace_and_the_tiled_forward():
     assert e.value.status == -4
 
 
+def _random_sum_layers(n, seed):
+    """Seeded random 3x3 Sum-channel layers around the cuts of the kernels: stride 1 / 2, dilation 1 / 2, output widths
+    that are and are not multiples of 4, planes below and above 512 and 1024 outputs, one to many images."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        s, d = [(1, 1), (1, 1), (1, 2), (2, 1)][len(out) % 4]
+        pad = int(rng.integers(0, d + 1))
+        cin, cout = int(rng.integers(1, 7)), int(rng.integers(1, 19))
+        h = int(rng.choice([6, 8, 9, 16, 17, 24, 32, 33, 40, 70]))
+        w = int(rng.choice([8, 10, 12, 16, 18, 20, 24, 32, 34, 44]))
+        nimg = int(rng.choice([1, 2, 3, 5, 9, 17]))
+        if nimg * cin * h * w * cout > 600000:
+            continue
+        cfg = LayerCfg(f"srnd{len(out)}_s{s}d{d}p{pad}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w, cout, stride=s,
+                       pad=pad, dil=d, seed=2000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1:
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_sum_layers(40, 20250608), ids=lambda c: c.name)
+def test_random_sum_layers(cfg):
+    rng = np.random.default_rng(cfg.seed)
+    mode = MODES[int(rng.integers(len(MODES)))]
+    _check(cfg.with_(mode=mode))
+    _check(cfg.with_(mode="compound"), integer=True)
+
+
 def test_sum_layer_at_a_benchmark_size():
     """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
     cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
