@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256) void dw_fwd_rows_kernel(Params p, const float*
 // Dilation 1, stride S = 1 or 2.  At stride 2 an input pixel is read through tap (i, j) only where ih + ph - i and
 // iw + pw - j are even: per kernel row at most 4 outputs lie under a lane's 4 pixels, and which (pixel, tap)
 // pairs meet which of them depends on the parity of iw0 + pw alone.
-template <int MODE, int S>
+template <int MODE, int S, int PAR = -1>
 __global__ __launch_bounds__(256) void dw_bwd_x_rows_kernel(Params p, const float* __restrict__ gy,
                                                             const uint8_t* __restrict__ idx,
                                                             const float* __restrict__ alpha,
@@ -417,6 +417,51 @@ __global__ __launch_bounds__(256) void dw_bwd_x_rows_kernel(Params p, const floa
       }
     }
     dw_gather4<MODE>(g6, c6, am, aM);
+  } else if constexpr (PAR >= 0) {
+    // Stride 2 with W a multiple of 4: iw0 = 4 * seg, so B = iw0 + pw has the parity PAR of pw for every lane, and
+    // which taps can reach a pixel is known at compile time: a pixel q with B + q even is read through taps j = 0
+    // and j = 2 of two neighbouring outputs, one with B + q odd through tap j = 1 of one output.  Likewise a row
+    // ih is read through tap rows i0 = (ih + ph) & 1 and i0 + 2 only: 2 rows x 6 (tap, pixel) pairs instead of
+    // 3 x 12.  Outputs ob .. ob + 2 of a row serve the lane's four pixels.
+    const int B = iw0 + p.pw;
+    const int ob = ((B - 2) >> 1) + PAR;
+    const int i0 = (ih + p.ph) & 1;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int i = i0 + 2 * r;
+      const int th = ih + p.ph - i;         // even by construction
+      const bool row_ok = i < 3 && th >= 0 && (th >> 1) < p.Ho;
+      const size_t rb = pb + (size_t)min(max(th >> 1, 0), p.Ho - 1) * p.Wo;
+      float g3[3];
+      int c3[3];
+#pragma unroll
+      for (int m = 0; m < 3; ++m) {
+        const int ow = ob + m;
+        const bool ok = row_ok && ow >= 0 && ow < p.Wo;
+        const size_t o = rb + min(max(ow, 0), p.Wo - 1);
+        g3[m] = gy[o];
+        c3[m] = ok ? (int)idx[o] : 0xff;  // a code no tap matches
+      }
+      const int t0 = i * 3;  // tap (i, 0)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (((q + PAR) & 1) == 0) {  // B + q even: taps j = 0 (output m = (q + PAR) / 2 + 1 - PAR) and j = 2 (one less)
+          const int m0 = (q + PAR) / 2 + 1 - PAR, m2 = m0 - 1;
+          if (DO_MIN) {
+            am[q] += ((c3[m0] & 15) == t0) ? g3[m0] : 0.f;
+            am[q] += ((c3[m2] & 15) == t0 + 2) ? g3[m2] : 0.f;
+          }
+          if (DO_MAX) {
+            aM[q] += ((c3[m0] >> 4) == t0) ? g3[m0] : 0.f;
+            aM[q] += ((c3[m2] >> 4) == t0 + 2) ? g3[m2] : 0.f;
+          }
+        } else {                     // B + q odd: tap j = 1 of output m = (q + PAR + 1) / 2 - PAR
+          const int m1 = (q + PAR + 1) / 2 - PAR;
+          if (DO_MIN) am[q] += ((c3[m1] & 15) == t0 + 1) ? g3[m1] : 0.f;
+          if (DO_MAX) aM[q] += ((c3[m1] >> 4) == t0 + 1) ? g3[m1] : 0.f;
+        }
+      }
+    }
   } else {
     const int B = iw0 + p.pw;               // column of tap j = 0 of pixel q = 0, doubled output coordinates
     const bool odd = (B & 1) != 0;
@@ -989,6 +1034,12 @@ hipError_t launch_bwd(const Params& p, const DwArgs& a, const DwGrads& g, hipStr
     const unsigned n_units = (unsigned)((long long)p.N * p.C_in * p.H * segs);
     if (p.sh == 1)
       hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 1>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
+                         a.alpha, a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
+    else if (p.W % 4 == 0 && (p.pw & 1) == 0)  // every lane's first column has the parity of pad_w
+      hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 2, 0>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
+                         a.alpha, a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
+    else if (p.W % 4 == 0)
+      hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 2, 1>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
                          a.alpha, a.beta, g.grad_x, segs, n_units, inv_of(segs), inv_of(p.H), inv_of(p.C_in));
     else
       hipLaunchKernelGGL((dw_bwd_x_rows_kernel<MODE, 2>), dim3((n_units + 255) / 256), dim3(256), 0, s, p, g.gy, a.idx,
