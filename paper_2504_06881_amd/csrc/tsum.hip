@@ -804,7 +804,8 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_kernel(Params p, const f
   }
 }
 
-// The same for stride 1, dilation 1 and an output width that is a multiple of 4.  Planes of at most 1024 outputs (the
+// The same for dilation 1, stride 1 (below) or 2 (two adjacent outputs per thread, 3 x 5 input values, 15 slots) and
+// an output width that is a multiple of the outputs per thread.  Planes of at most 1024 outputs (the
 // 32 x 32, 16 x 16 and 8 x 8 maps of the paper's CIFAR networks): workgroup = (input channel c, G images whose planes
 // together have at most 1024 outputs).  Larger planes: workgroup = (image, input channel, band of RB input rows); it
 // scans the RB + 2 output rows whose windows reach the band (at most 1024 outputs) and an output counts for the
@@ -825,7 +826,7 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_kernel(Params p, const f
 // address) at a stride of 13: 1.32.
 constexpr int SUMQ_COB = 8, SUMQ_REP = 8, SUMQ_BS = 11;
 constexpr int SUMQ_PRIV_BYTES = 18 * 256 * 8;
-template <int MODE>
+template <int MODE, int S>
 __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, const float* __restrict__ x,
                                                                     const float* __restrict__ w_min,
                                                                     const float* __restrict__ w_max,
@@ -843,6 +844,8 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   constexpr int NBR = (DO_MIN && DO_MAX) ? 2 : 1;
   constexpr int REP = SUMQ_REP;
   constexpr int BS = SUMQ_BS;
+  constexpr int PXT = 4 / S;               // adjacent outputs of a thread: 4 at stride 1, 2 at stride 2
+  constexpr int NQ = S * (PXT - 1) + 3;    // input columns their windows span: 6 / 5
   const int NBINS = COB * NBR * REP * BS;
   extern __shared__ double lds_d[];
   const int band = blockIdx.x % n_bands;
@@ -850,9 +853,10 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   const int n0 = (blockIdx.x / (n_bands * p.C_in)) * G;  // first image of the group
   // the band owns the input rows [r0, r1); the output rows whose windows reach them are scanned
   const int r0 = band * RB, r1 = min(r0 + RB, p.H);
-  const int oh_lo = max(0, r0 + p.ph - 2), oh_hi = min(p.Ho - 1, r1 - 1 + p.ph);
+  const int lo_num = r0 + p.ph - 2;  // first output row whose window (rows S * oh - ph .. + 2) reaches row r0
+  const int oh_lo = lo_num <= 0 ? 0 : (lo_num + S - 1) / S, oh_hi = min(p.Ho - 1, (r1 - 1 + p.ph) / S);
   const int srows = max(oh_hi - oh_lo + 1, 0);
-  const int xr0 = max(0, oh_lo - p.ph), xr1 = srows > 0 ? min(p.H, oh_hi - p.ph + 3) : xr0;  // input rows read
+  const int xr0 = max(0, S * oh_lo - p.ph), xr1 = srows > 0 ? min(p.H, S * oh_hi - p.ph + 3) : xr0;  // input rows read
   double* const priv = lds_d;                      // [18][256]
   float* const xs = (float*)lds_d;                 // [G][(xr1 - xr0) x W], before the slots are cleared
   double* const bins = lds_d + 18 * 256;           // [COB][NBR][REP][BS]
@@ -865,21 +869,21 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   for (int e = threadIdx.x; e < NBINS; e += blockDim.x) bins[e] = 0.0;
   __syncthreads();
   const size_t plane = (size_t)p.Ho * p.Wo;
-  const int qrow = p.Wo >> 2;             // quads per output row
+  const int qrow = p.Wo / PXT;            // threads per output row
   const int quads = srows * qrow;         // per image
   const int img = quads > 0 ? min((int)threadIdx.x / quads, G - 1) : 0;
   const bool live = (int)threadIdx.x < G * quads && n0 + img < p.N;
   const int lq = live ? (int)threadIdx.x - img * quads : 0;
   const int srow = lq / qrow;
-  const int oh = oh_lo + srow, ow0 = 4 * (lq - srow * qrow);
-  const int ih0 = oh - p.ph, iw0 = ow0 - p.pw;
+  const int oh = oh_lo + srow, ow0 = PXT * (lq - srow * qrow);
+  const int ih0 = S * oh - p.ph, iw0 = S * ow0 - p.pw;
   // an output counts for the parameter gradients in the band that owns the first row of its window inside the image
   const bool own = live && max(ih0, 0) >= r0 && max(ih0, 0) < r1;
-  float xw[3][6];  // padding = NaN: never an extremum
+  float xw[3][NQ];  // padding = NaN: never an extremum
 #pragma unroll
   for (int r = 0; r < 3; ++r)
 #pragma unroll
-    for (int q = 0; q < 6; ++q) {
+    for (int q = 0; q < NQ; ++q) {
       const int ih = ih0 + r, iw = iw0 + q;
       const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
       xw[r][q] = ok ? xs[img * XW + (ih - xr0) * p.W + iw] : __uint_as_float(0x7fc00000u);
@@ -887,7 +891,7 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
   __syncthreads();  // every window is in registers: the slots take the place of the plane
   double* const mine = priv + threadIdx.x;
 #pragma unroll
-  for (int sl = 0; sl < 18; ++sl) mine[sl * 256] = 0.0;
+  for (int sl = 0; sl < 3 * NQ; ++sl) mine[sl * 256] = 0.0;
   double* const mybins = bins + (size_t)(threadIdx.x & (REP - 1)) * BS;
   const float* gyq = gy + (size_t)(live ? n0 + img : 0) * p.C_out * plane + (size_t)oh * p.Wo + ow0;
   for (int cob = 0; cob < p.C_out; cob += COB) {
@@ -900,23 +904,29 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
         const double ca = TWO ? (double)coef_of(alpha, c, co, p.C_out) : 1.0;
         const double cb = TWO ? (double)coef_of(beta, c, co, p.C_out) : 1.0;
         double* const bn = mybins + (size_t)b * NBR * REP * BS;
-        const float4 g4 = *(const float4*)(gyq + (size_t)co * plane);
-        const float gk[4] = {g4.x, g4.y, g4.z, g4.w};
-        float s_min = 0.f, s_max = 0.f;  // coefficient sums over the thread's four pixels
+        float gk[PXT];
+        if constexpr (S == 1) {
+          const float4 g4 = *(const float4*)(gyq + (size_t)co * plane);
+          gk[0] = g4.x; gk[1] = g4.y; gk[2] = g4.z; gk[3] = g4.w;
+        } else {
+          const float2 g2 = *(const float2*)(gyq + (size_t)co * plane);
+          gk[0] = g2.x; gk[1] = g2.y;
+        }
+        float s_min = 0.f, s_max = 0.f;  // coefficient sums over the thread's pixels
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < PXT; ++k) {
           const double g = (double)gk[k];
           float s1[9], s2[9];
 #pragma unroll
           for (int t = 0; t < 9; ++t) {
-            if (DO_MIN) s1[t] = __fadd_rn(xw[t / 3][k + t % 3], ka[t]);
-            if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xw[t / 3][k + t % 3], kb[t]);
+            if (DO_MIN) s1[t] = __fadd_rn(xw[t / 3][S * k + t % 3], ka[t]);
+            if (DO_MAX) s2[t] = (MODE == TCONV_COMPOUND) ? s1[t] : __fadd_rn(xw[t / 3][S * k + t % 3], kb[t]);
           }
           if (DO_MIN) {
             float bmin; int row, col;
             window_extremum9_rc<false>(s1, bmin, row, col);
             const double v = ca * g;
-            mine[(row * 6 + col + k) * 256] += v;  // slot (row, k + column)
+            mine[(row * NQ + col + S * k) * 256] += v;  // slot (row, S * k + column)
             if (own) atomicAdd(bn + (row * 3 + col), v);
             s_min = fmaf(gk[k], bmin, s_min);
           }
@@ -924,7 +934,7 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
             float bmax; int row, col;
             window_extremum9_rc<true>(s2, bmax, row, col);
             const double v = cb * g;
-            mine[(row * 6 + col + k) * 256] += v;
+            mine[(row * NQ + col + S * k) * 256] += v;
             if (own) atomicAdd(bn + (NBR - 1) * REP * BS + (row * 3 + col), v);
             s_max = fmaf(gk[k], bmax, s_max);
           }
@@ -960,8 +970,10 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
     }
     __syncthreads();
   }
-  // An input element (ih, iw) lies in slot (r, q) of the thread whose outputs start at (ih + ph - r, iw + pw - q); that
-  // column is a multiple of 4 for one or two q in 0..5.  Slots outside the image never received anything.
+  // An input element (ih, iw) lies in slot (r, q) of the thread whose outputs start at row (ih + ph - r) / S and column
+  // (iw + pw - q) / S; that column is a multiple of PXT, i.e. iw + pw - q a multiple of 4, for one or two q in
+  // 0 .. NQ - 1, and at stride 2 the row exists for the r of one parity only.  Slots outside the image never received
+  // anything.
   const int BW = (r1 - r0) * p.W;
   for (int i = threadIdx.x; i < G * BW; i += blockDim.x) {
     const int im = i / BW, pos = i - im * BW;
@@ -971,13 +983,15 @@ __global__ __launch_bounds__(256) void sum_bwd_fused3x3_quad_kernel(Params p, co
     double sum = 0.0;
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
-      const int oh2 = ih + p.ph - r;
+      const int on = ih + p.ph - r;
+      if (on < 0 || (S == 2 && (on & 1))) continue;
+      const int oh2 = on / S;
       if (oh2 < oh_lo || oh2 > oh_hi) continue;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int q = q0 + 4 * j, oc = iw + p.pw - q;
-        if (q <= 5 && oc >= 0 && oc < p.Wo)
-          sum += priv[(r * 6 + q) * 256 + im * quads + (oh2 - oh_lo) * qrow + (oc >> 2)];
+        const int q = q0 + 4 * j, oc = (iw + p.pw - q) / S;  // iw + pw - q is a multiple of 4 (or negative: skipped)
+        if (q < NQ && iw + p.pw - q >= 0 && oc < p.Wo)
+          sum += priv[(r * NQ + q) * 256 + im * quads + (oh2 - oh_lo) * qrow + oc / PXT];
       }
     }
     grad_x[((size_t)(n0 + im) * p.C_in + c) * HW + (size_t)ih * p.W + iw] = (float)sum;
@@ -1078,18 +1092,19 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
         // workgroup as fill its threads.  Larger planes: one image, bands of RB input rows whose RB + 2 scanned
         // output rows fill the threads (at least 4 rows to a band: at most 1.5 x the outputs are scanned).
         const long long plane = (long long)p.Ho * p.Wo;
-        const int qrow = p.Wo / 4;
+        const int S = p.sh, pxt = S == 2 ? 2 : 4;  // adjacent outputs of a thread
+        const int qrow = p.Wo / pxt;
         int G = 0, RB = p.H, nb = 1;
-        if (plane > 0 && plane <= 1024) {
-          G = (int)std::min<long long>(1024 / plane, p.N);
-          if (G * plane <= 512) G = 0;  // too few outputs for the threads
+        if (plane > 0 && plane <= 256 * pxt) {
+          G = (int)std::min<long long>(256 * pxt / plane, p.N);
+          if (G * plane <= 128 * pxt) G = 0;  // too few outputs for the threads
         } else if (qrow >= 1 && qrow <= 42) {
           G = 1;
-          RB = 256 / qrow - 2;
+          RB = S * (256 / qrow - 2);
           nb = (p.H + RB - 1) / RB;
         }
-        const long long xrows = std::min<long long>((long long)RB + 4, p.H);
-        const bool quad = p.sh == 1 && p.sw == 1 && p.dh == 1 && p.dw == 1 && p.Wo % 4 == 0 && G >= 1 &&
+        const long long xrows = std::min<long long>((long long)RB + 6, p.H);  // input rows a band's scanned outputs read, at most
+        const bool quad = p.sh == p.sw && (S == 1 || S == 2) && p.dh == 1 && p.dw == 1 && p.Wo % pxt == 0 && G >= 1 &&
                           (size_t)G * xrows * p.W * 4 <= (size_t)SUMQ_PRIV_BYTES &&
                           (long long)((p.N + G - 1) / G) * p.C_in * nb <= 0x7fffffffLL &&
                           ((uintptr_t)g.gy & 15) == 0 && !(sep && strcmp(sep, "spread") == 0);
@@ -1097,9 +1112,15 @@ hipError_t launch_bwd(const Params& p, const SumArgs& a, const SumGrads& g, hipS
           const int cobq = SUMQ_COB;
           const size_t qbytes = (size_t)SUMQ_PRIV_BYTES + (size_t)SUMQ_REP * cobq * NBR * SUMQ_BS * 8;
           const long long groups = ((long long)p.N + G - 1) / G;
-          hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE>), dim3((unsigned)(groups * p.C_in * nb)), dim3(256),
-                             qbytes, s, p, a.x, a.w_min, a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax,
-                             g.grad_alpha, g.grad_beta, cobq, G, RB, nb);
+          const dim3 qgrid((unsigned)(groups * p.C_in * nb));
+          if (S == 1)
+            hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE, 1>), qgrid, dim3(256), qbytes, s, p, a.x, a.w_min,
+                               a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax, g.grad_alpha, g.grad_beta, cobq, G,
+                               RB, nb);
+          else
+            hipLaunchKernelGGL((sum_bwd_fused3x3_quad_kernel<MODE, 2>), qgrid, dim3(256), qbytes, s, p, a.x, a.w_min,
+                               a.w_max, a.alpha, a.beta, g.gy, g.grad_x, fmin, fmax, g.grad_alpha, g.grad_beta, cobq, G,
+                               RB, nb);
           return hipGetLastError();
         }
         if (n_bands == 1)

@@ -57,6 +57,11 @@ SHAPES = [
     LayerCfg("s_quad_g16", 20, 2, 8, 8, 5, seed=60),
     LayerCfg("s_quad_g2", 5, 3, 16, 24, 10, seed=61),
     LayerCfg("s_quad_bands_p0", 1, 2, 70, 30, 3, pad=0, seed=64),   # more than 1024 outputs: bands of rows, no padding
+    # stride 2: the backward kernel's threads own two adjacent outputs; groups of images, bands of rows
+    LayerCfg("s_pair_g2", 5, 3, 32, 32, 6, stride=2, seed=65),
+    LayerCfg("s_pair_g8", 11, 2, 16, 16, 5, stride=2, seed=66),
+    LayerCfg("s_pair_bands", 1, 2, 90, 44, 3, stride=2, seed=67),
+    LayerCfg("s_pair_bands_p0", 1, 2, 91, 45, 3, stride=2, pad=0, seed=68),
     # stride 2 in the tiled forward kernel
     LayerCfg("s_3x3_s2_even", 2, 5, 16, 32, 9, stride=2, seed=62),       # the run of 8 columns ends past the row
     LayerCfg("s_3x3_s2_p0", 2, 3, 15, 21, 4, stride=2, pad=0, seed=63),  # last segment shifted, no padding
@@ -92,7 +97,7 @@ def test_sum_backward_in_separate_calls_and_kernels(cfg):
         os.environ.pop("TCONV_SUM_BWD", None)
 
 
-@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name.startswith("s_quad") or c.name in ("s_tall", "s_bands")],
+@pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name.startswith(("s_quad", "s_pair")) or c.name in ("s_tall", "s_bands", "s_3x3_s2")],
                          ids=lambda c: c.name)
 def test_sum_backward_of_mid_size_planes_by_the_kernel_for_any_plane(cfg):
     """TCONV_SUM_BWD=spread keeps the fused kernel that serves every plane size on the shapes the four-adjacent-outputs
