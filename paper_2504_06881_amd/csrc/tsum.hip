@@ -87,14 +87,14 @@ __global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const fl
 // WAVES waves of a workgroup share the segments and differ in output-channel group.  Per input
 // channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
 // of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
-template <int MODE, int D, int S, typename TO>
+template <int MODE, int D, int S, typename TO, int TN>
 __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
     Params p, const TO* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
-    TO* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs) {
+    TO* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs, int wpb) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  constexpr int PX = S == 1 ? 8 : 4, TN = 4;
+  constexpr int PX = S == 1 ? 8 : 4;
   constexpr int CORE = 8;                       // columns of the 32-byte run every row is loaded with
   constexpr int NHR = (PX - 1) * S + D + 1 - CORE;  // halo columns right of the run: D at stride 1, none at stride 2
   constexpr int XR = D + CORE + NHR;
@@ -106,10 +106,10 @@ __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 
   const int per_xcd = (n_blocks + 7) >> 3;
   const int bid = xcd_runs ? (int)(blockIdx.x & 7u) * per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
   if (bid >= n_blocks) return;
-  const int gblocks = (n_groups + WAVES - 1) / WAVES;
+  const int gblocks = (n_groups + wpb - 1) / wpb;  // wpb waves per workgroup, each a different c_out group
   const int ublock = bid / gblocks;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int group = (bid - ublock * gblocks) * WAVES + wave;
+  const int group = (bid - ublock * gblocks) * wpb + wave;
   if (group >= n_groups) return;  // whole wave leaves; the kernel has no barrier
   const int co0 = group * TN;
   const int lane = threadIdx.x & 63;
@@ -1028,8 +1028,20 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const int px = p.sh == 1 ? 8 : 4;
     const int segs = (p.Wo + px - 1) / px;
     const long long n_units = (long long)p.N * p.Ho * segs;
-    const int n_groups = (p.C_out + 3) / 4;
-    const long long blocks = ((n_units + 63) / 64) * ((n_groups + WAVES - 1) / WAVES);
+    const long long ublocks = (n_units + 63) / 64;
+    // Small layers (the 16 x 16 and 8 x 8 maps of a CIFAR network) have too few waves at 4 output channels per lane:
+    // 2 channels per lane when 4 leave fewer than one wave per SIMD ([128, 32, 16, 16] -> 32: 54 -> 32 us, [128, 64, 8, 8]
+    // -> 64: 99 -> 55 us; 1 channel per lane gains nothing more, nor do fewer waves per workgroup at the same number
+    // of waves).
+    const char* te = getenv("TCONV_SUM_FWD_TN");  // testing aid: 2 or 4 output channels per lane
+    const int wpb = WAVES;
+    auto nblocks = [&](int tn_, int wpb_) { return ublocks * ((((long long)p.C_out + tn_ - 1) / tn_ + wpb_ - 1) / wpb_); };
+    auto nwaves = [&](int tn_) { return ublocks * (((long long)p.C_out + tn_ - 1) / tn_); };
+    int tn = 4;
+    if (te && (te[0] == '2' || te[0] == '4') && te[1] == 0) tn = te[0] - '0';
+    else if (nwaves(4) < 1024) tn = 2;
+    const int n_groups = (p.C_out + tn - 1) / tn;
+    const long long blocks = nblocks(tn, wpb);
     if (blocks > 0x7ffffff0LL) return hipErrorInvalidValue;
     // contiguous runs per XCD while the kernels and coefficients are small next to an L2 (as for the full-window kernel)
     const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * (MODE == TCONV_PARALLEL ? 2 : 1);
@@ -1038,15 +1050,16 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const unsigned grid = (unsigned)(((blocks + 7) / 8) * 8);
     const TO* x = (const TO*)a.x;
     TO* y = (TO*)a.y;
-    if (p.sh == 2)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 2, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
-                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
-    else if (p.dh == 1)
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 1, 1, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
-                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
-    else
-      hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, 2, 1, TO>), dim3(grid), dim3(WAVES * 64), 0, s, p, x, a.w_min,
-                         a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs);
+#define TCONV_SUM_FWD(D_, S_, TN_)                                                                                     \
+  hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, D_, S_, TO, TN_>), dim3(grid), dim3(wpb * 64), 0, s, p, x, a.w_min, \
+                     a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs, wpb)
+#define TCONV_SUM_FWD_TN(D_, S_) \
+  do { if (tn == 4) TCONV_SUM_FWD(D_, S_, 4); else TCONV_SUM_FWD(D_, S_, 2); } while (0)
+    if (p.sh == 2) TCONV_SUM_FWD_TN(1, 2);
+    else if (p.dh == 1) TCONV_SUM_FWD_TN(1, 1);
+    else TCONV_SUM_FWD_TN(2, 1);
+#undef TCONV_SUM_FWD_TN
+#undef TCONV_SUM_FWD
   } else if (sizeof(TO) != 4) {
     return hipErrorInvalidValue;  // bf16 storage: the tiled kernel only
   } else {
