@@ -382,8 +382,9 @@ def main() -> int:
         "dtype": "f16" if dtypes == {"f16"} else "f32",
         "storage": "f32" if dtypes == {"f32"} else ("f16" if dtypes == {"f16"} else "bf16"),
         "data": "synthetic",
-        "config": {"workload": wl_name + ", forward + backward (grad_x and grad_w, "
-                               + ("two calls" if args.separate_backward or args.op == "sum" else "one call") + ")"
+        "config": {"workload": wl_name + (", forward + backward (all five gradients, one call)" if args.op == "sum" else
+                                          ", forward + backward (grad_x and grad_w, "
+                                          + ("two calls" if args.separate_backward else "one call") + ")")
                                + (", one HIP graph per step" if graph else ""),
                    "pairs_per_step": pairs,
                    "forward_kernel": (tb.tconv_sum_forward_kernel_name(layers[-1].d) if args.op == "sum"
