@@ -264,6 +264,22 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
                           float* grad_bias, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * tconv_backward_params without stored branch outputs, for a forward pass that was given y_min = y_max = NULL (12
+ * instead of 20 bytes written per output, which is what layers with few input channels wait for): an output's
+ * y_min / y_max is formed again from its winner, fl(x[winner] + w[winner]), the very add the forward pass made
+ * (Sec. 3.1: the output of a branch IS its winning candidate), so every gradient equals tconv_backward_params' bit
+ * for bit.  x, w_min, w_max as in tconv_forward (COMPOUND: the one kernel tensor in either pointer); the other
+ * arguments as in tconv_backward_params.  fp32 storage, windows whose histogram fits LDS (else
+ * TCONV_E_UNSUPPORTED), and the workspace is required: tconv_workspace_bytes(desc, TCONV_OP_BACKWARD_PARAMS)
+ * bytes (else TCONV_E_WORKSPACE).
+ */
+int tconv_backward_params_recompute(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                                    const float* gy, const float* alpha, const float* beta, const int32_t* idx_min,
+                                    const int32_t* idx_max, float* grad_w_min, float* grad_w_max, float* grad_alpha,
+                                    float* grad_beta, float* grad_bias, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream);
+
+/*
  * Sum-channel layers.  Base operators of Sec. 3.1 for one
  * input channel: MinPlus2d / MaxPlus2d = the minimum / maximum of x + w over the KH x KW window.
  *   mode MIN       layer (i)  MinPlus-Sum-Conv2d:  y = sum over c_in of MinPlus2d(x, w_min)

@@ -21,7 +21,7 @@ OPS = {"forward": 0, "backward_input": 1, "backward_weight": 2, "backward_alpha_
        "backward_bias": 5, "backward_params": 6}
 SYMBOLS = ("tconv_out_shape", "tconv_workspace_bytes", "tconv_forward", "tconv_forward_fused", "tconv_backward_bias",
            "tconv_backward_input",
-           "tconv_backward_weight", "tconv_backward_weight_noalloc", "tconv_backward", "tconv_backward_alpha_beta", "tconv_backward_params", "tconv_sum_forward", "tconv_sum_backward",
+           "tconv_backward_weight", "tconv_backward_weight_noalloc", "tconv_backward", "tconv_backward_alpha_beta", "tconv_backward_params", "tconv_backward_params_recompute", "tconv_sum_forward", "tconv_sum_backward",
            "tconv_sum_workspace_bytes", "tconv_sum_forward_kernel_name", "tconv_depthwise_forward", "tconv_depthwise_backward",
            "tconv_depthwise_forward_kernel_name", "tconv1d_out_len", "tconv1d_workspace_bytes", "tconv1d_forward",
            "tconv1d_backward_input", "tconv1d_backward_weight", "tconv1d_forward_kernel_name",
@@ -151,6 +151,8 @@ def load() -> ctypes.CDLL:
         lib.tconv_backward_alpha_beta.argtypes = [D] + [P] * 6 + [ctypes.c_size_t, P]
         lib.tconv_backward_params.argtypes = [D] + [P] * 13 + [ctypes.c_size_t, P]
         lib.tconv_backward_params.restype = ctypes.c_int
+        lib.tconv_backward_params_recompute.argtypes = [D] + [P] * 14 + [ctypes.c_size_t, P]
+        lib.tconv_backward_params_recompute.restype = ctypes.c_int
         lib.tconv_sum_forward.argtypes = [D] + [P] * 7 + [ctypes.c_size_t, P]
         lib.tconv_sum_backward.argtypes = [D] + [P] * 12 + [ctypes.c_size_t, P]
         lib.tconv_sum_workspace_bytes.argtypes = [D, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
@@ -303,6 +305,17 @@ def tconv_backward_params(desc: Desc, gy, alpha, beta, idx_min, idx_max, y_min, 
                                         _ptr(idx_max), _ptr(y_min), _ptr(y_max), _ptr(grad_w_min), _ptr(grad_w_max),
                                         _ptr(grad_alpha), _ptr(grad_beta), _ptr(grad_bias), _ptr(workspace), wsz,
                                         _stream()), "tconv_backward_params")
+
+
+def tconv_backward_params_recompute(desc: Desc, x, w_min, w_max, gy, alpha, beta, idx_min, idx_max, grad_w_min,
+                                    grad_w_max, grad_alpha=None, grad_beta=None, grad_bias=None, workspace=None) -> None:
+    cd = desc.c()
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tconv_backward_params_recompute(ctypes.byref(cd), _ptr(x), _ptr(w_min), _ptr(w_max), _ptr(gy),
+                                                  _ptr(alpha), _ptr(beta), _ptr(idx_min), _ptr(idx_max),
+                                                  _ptr(grad_w_min), _ptr(grad_w_max), _ptr(grad_alpha),
+                                                  _ptr(grad_beta), _ptr(grad_bias), _ptr(workspace), wsz, _stream()),
+           "tconv_backward_params_recompute")
 
 
 def tconv_backward_alpha_beta(desc: Desc, gy, y_min, y_max, grad_alpha, grad_beta, workspace=None) -> None:

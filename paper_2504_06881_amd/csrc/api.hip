@@ -333,8 +333,8 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
   hipStream_t s = (hipStream_t)hip_stream;
   own_status();
   if (partial && params_one_pass(p, desc->dtype)) {
-    const hipError_t e = launch_backward_params(p, a, (const float*)y_min, (const float*)y_max, grad_w_min, grad_w_max,
-                                                grad_alpha, grad_beta, grad_bias, partial, s);
+    const hipError_t e = launch_backward_params(p, a, (const float*)y_min, (const float*)y_max, nullptr, nullptr, nullptr,
+                                                grad_w_min, grad_w_max, grad_alpha, grad_beta, grad_bias, partial, s);
     return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
   }
   // the separate kernels, each in its deterministic form when there is scratch; the two small reductions share theirs
@@ -345,6 +345,44 @@ int tconv_backward_params(const tconv_desc* desc, const float* gy, const float* 
   if (e == hipSuccess && (grad_alpha || grad_beta))
     e = launch_backward_alpha_beta(p, desc->dtype, gy, y_min, y_max, grad_alpha, grad_beta, part_ab, s);
   if (e == hipSuccess && grad_bias) e = launch_backward_bias(p, gy, grad_bias, part_ab, s);
+  return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
+}
+
+int tconv_backward_params_recompute(const tconv_desc* desc, const void* x, const void* w_min, const void* w_max,
+                                    const float* gy, const float* alpha, const float* beta, const int32_t* idx_min,
+                                    const int32_t* idx_max, float* grad_w_min, float* grad_w_max, float* grad_alpha,
+                                    float* grad_beta, float* grad_bias, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+  Params p;
+  const int rc = make_params(desc, &p);
+  if (rc != TCONV_OK) return rc;
+  if (!gy || !x) return TCONV_E_INVAL;
+  if ((grad_alpha || grad_beta) && p.mode != TCONV_COMPOUND && p.mode != TCONV_PARALLEL) return TCONV_E_INVAL;
+  const int fwd_mode = p.mode;
+  p.mode = backward_mode(p.mode);
+  if (p.mode != TCONV_MAX && !idx_min) return TCONV_E_INVAL;
+  if (p.mode != TCONV_MIN && !idx_max) return TCONV_E_INVAL;
+  const void* wa = w_min;
+  const void* wb = w_max;
+  if (fwd_mode == TCONV_COMPOUND) wa = wb = (w_min ? w_min : w_max);
+  if (grad_alpha && !wa) return TCONV_E_INVAL;
+  if (grad_beta && !wb) return TCONV_E_INVAL;
+  switch (p.mode) {
+    case TCONV_MAX: if (!grad_w_max) return TCONV_E_INVAL; break;
+    case TCONV_MIN: if (!grad_w_min) return TCONV_E_INVAL; break;
+    case TCONV_COMPOUND: if (!grad_w_min && !grad_w_max) return TCONV_E_INVAL; break;
+    default: if (!grad_w_min || !grad_w_max) return TCONV_E_INVAL; break;
+  }
+  // fp32 storage, a window whose histogram fits LDS, and the scratch of the one-pass form
+  if (desc->dtype != TCONV_F32 || !params_one_pass(p, desc->dtype)) return TCONV_E_UNSUPPORTED;
+  double* partial = nullptr;
+  if (!take_partial(workspace, workspace_bytes, params_workspace(p, desc->dtype), &partial) || !partial)
+    return TCONV_E_WORKSPACE;
+  const BwdArgs a = {gy, alpha, beta, idx_min, idx_max};
+  own_status();
+  const hipError_t e = launch_backward_params(p, a, nullptr, nullptr, (const float*)x, (const float*)wa, (const float*)wb,
+                                              grad_w_min, grad_w_max, grad_alpha, grad_beta, grad_bias, partial,
+                                              (hipStream_t)hip_stream);
   return e == hipSuccess ? TCONV_OK : TCONV_E_LAUNCH;
 }
 

@@ -513,12 +513,19 @@ hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_
 // EXTRA (two-stage form only): the same pass also sums gy, gy * y_min and gy * y_max over the slice (the gradients
 // of a bias and of the combine coefficients, Sec. 3.3) into three more fp64 slots behind the histogram.
 struct ParamExtras {
-  const float* y_min;  // NULL: no grad_alpha
-  const float* y_max;  // NULL: no grad_beta
+  const float* y_min;  // EXTRA == 1: the branch outputs as the forward pass stored them; NULL: no grad_alpha
+  const float* y_max;  //             NULL: no grad_beta
+  // EXTRA == 2: no stored branch outputs; an output's y_min / y_max is formed again from its winner,
+  // fl(x[winner] + w[winner]), the very add the forward pass made (a padded winner, possible under zero padding only,
+  // reads x as +0)
+  const float* x;
+  const float* w_min;
+  const float* w_max;
+  int want_alpha, want_beta;
 };
 constexpr int N_EXTRA = 3;  // bias, alpha, beta
 
-template <int MODE, bool EXTRA>
+template <int MODE, int EXTRA>
 __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs a,
                                                               float* __restrict__ gw_min,
                                                               float* __restrict__ gw_max,
@@ -552,10 +559,12 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
       size_t ov[UB];
       bool okv[UB];
       float gv[UB], ymn[UB], ymx[UB];
-      int kmn[UB], kmx[UB];
+      int kmn[UB], kmx[UB], nv[UB], qv[UB];
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
         okv[u] = n < n1;
+        nv[u] = okv[u] ? n : n0;
+        qv[u] = q;
         ov[u] = ((size_t)(okv[u] ? n : n0) * p.C_out + co) * plane + q;
         q += dq;
         n += dn;
@@ -566,8 +575,25 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
         gv[u] = a.gy[ov[u]];
         if (DO_MIN) kmn[u] = a.idx_min[ov[u]];
         if (DO_MAX) kmx[u] = a.idx_max[ov[u]];
-        if (EXTRA && ex.y_min) ymn[u] = ex.y_min[ov[u]];
-        if (EXTRA && ex.y_max) ymx[u] = ex.y_max[ov[u]];
+        if (EXTRA == 1 && ex.y_min) ymn[u] = ex.y_min[ov[u]];
+        if (EXTRA == 1 && ex.y_max) ymx[u] = ex.y_max[ov[u]];
+      }
+      if (EXTRA == 2) {
+        const int KK = p.KH * p.KW;
+        auto branch_output = [&](int nn, int qq, int k, const float* w) -> float {
+          if ((unsigned)k >= (unsigned)K) return 0.f;  // a corrupted index stays in bounds (and adds nothing below)
+          const int c = k / KK, r = k - c * KK, i = r / p.KW, j = r - i * p.KW;
+          const int oh = qq / p.Wo, ow = qq - oh * p.Wo;
+          const int ih = oh * p.sh - p.ph + i * p.dh, iw = ow * p.sw - p.pw + j * p.dw;
+          const bool inside = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+          const float xv = inside ? ex.x[((size_t)nn * p.C_in + c) * ((size_t)p.H * p.W) + (size_t)ih * p.W + iw] : 0.f;
+          return __fadd_rn(xv, w[(size_t)co * K + k]);
+        };
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          if (DO_MIN && ex.want_alpha) ymn[u] = branch_output(nv[u], qv[u], kmn[u], ex.w_min);
+          if (DO_MAX && ex.want_beta) ymx[u] = branch_output(nv[u], qv[u], kmx[u], ex.w_max);
+        }
       }
 #pragma unroll
       for (int u = 0; u < UB; ++u) {
@@ -575,8 +601,8 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
         if (EXTRA) {
           const double g = (double)gv[u];
           s_bias += g;
-          if (ex.y_min) s_alpha += g * (double)ymn[u];
-          if (ex.y_max) s_beta += g * (double)ymx[u];
+          if (EXTRA == 1 ? ex.y_min != nullptr : (DO_MIN && ex.want_alpha)) s_alpha += g * (double)ymn[u];
+          if (EXTRA == 1 ? ex.y_max != nullptr : (DO_MAX && ex.want_beta)) s_beta += g * (double)ymx[u];
         }
         if (DO_MIN && (unsigned)kmn[u] < (unsigned)K)
           atomicAdd(hmin + kmn[u], SCALED ? (double)ca * (double)gv[u] : (double)gv[u]);
@@ -739,16 +765,16 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
     dim3 grid(p.C_out, slices);
     switch (p.mode) {
       case TCONV_MAX:
-        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MAX, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MAX, 0>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       case TCONV_MIN:
-        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MIN, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MIN, 0>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       case TCONV_COMPOUND:
-        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_COMPOUND, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_COMPOUND, 0>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
       default:
-        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, false>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
+        hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, 0>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
     }
     if (partial) {
@@ -790,8 +816,9 @@ size_t backward_params_workspace(const Params& p) {
 }
 
 hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float* y_min, const float* y_max,
-                                  float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
-                                  float* grad_bias, double* partial, hipStream_t s) {
+                                  const float* x, const float* w_min, const float* w_max, float* grad_w_min,
+                                  float* grad_w_max, float* grad_alpha, float* grad_beta, float* grad_bias,
+                                  double* partial, hipStream_t s) {
   float* gmin = grad_w_min;
   float* gmax = grad_w_max;
   if (p.mode == TCONV_COMPOUND) gmin = gmax = (grad_w_min ? grad_w_min : grad_w_max);
@@ -800,21 +827,25 @@ hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float
   int n_per_block = 0;
   const int slices = weight_slices(p, &n_per_block);
   const dim3 grid(p.C_out, slices);
-  const ParamExtras ex = {grad_alpha ? y_min : nullptr, grad_beta ? y_max : nullptr};
+  const bool recompute = x != nullptr;  // the branch outputs again from the winners instead of stored tensors
+  const ParamExtras ex = {(!recompute && grad_alpha) ? y_min : nullptr, (!recompute && grad_beta) ? y_max : nullptr,
+                          x, w_min, w_max, (recompute && grad_alpha) ? 1 : 0, (recompute && grad_beta) ? 1 : 0};
+#define TCONV_LAUNCH_PARAMS(M)                                                                                       \
+  do {                                                                                                               \
+    if (recompute)                                                                                                   \
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<M, 2>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block,    \
+                         partial, ex);                                                                               \
+    else                                                                                                             \
+      hipLaunchKernelGGL((bwd_weight_hist_kernel<M, 1>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block,    \
+                         partial, ex);                                                                               \
+  } while (0)
   switch (p.mode) {
-    case TCONV_MAX:
-      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MAX, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
-      break;
-    case TCONV_MIN:
-      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_MIN, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
-      break;
-    case TCONV_COMPOUND:
-      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_COMPOUND, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
-      break;
-    default:
-      hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, true>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ex);
-      break;
+    case TCONV_MAX: TCONV_LAUNCH_PARAMS(TCONV_MAX); break;
+    case TCONV_MIN: TCONV_LAUNCH_PARAMS(TCONV_MIN); break;
+    case TCONV_COMPOUND: TCONV_LAUNCH_PARAMS(TCONV_COMPOUND); break;
+    default: TCONV_LAUNCH_PARAMS(TCONV_PARALLEL); break;
   }
+#undef TCONV_LAUNCH_PARAMS
   const size_t total = (size_t)p.C_out * ((size_t)nhist * p.K + N_EXTRA);
   size_t blocks = (total + 255) / 256;
   if (blocks > 2048) blocks = 2048;

@@ -172,11 +172,14 @@ bool forward_row_supported(const Params& p, int dtype);  // one-row inputs with 
 hipError_t launch_forward_row(const Params& p, const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_input(const Params& p, const BwdArgs& a, float* grad_x, hipStream_t s);
 hipError_t launch_backward_bias(const Params& p, const float* gy, float* grad_bias, double* partial, hipStream_t s);
-// every parameter gradient from one pass (fp32 branch outputs; partial: backward_params_workspace(p) bytes, not 0)
+// every parameter gradient from one pass (fp32 branch outputs; partial: backward_params_workspace(p) bytes, not 0).
+// x != NULL: the branch outputs are not read but formed again from the winners, fl(x[winner] + w[winner]) (fp32 x and
+// kernels; y_min / y_max ignored).
 size_t backward_params_workspace(const Params& p);
 hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float* y_min, const float* y_max,
-                                  float* grad_w_min, float* grad_w_max, float* grad_alpha, float* grad_beta,
-                                  float* grad_bias, double* partial, hipStream_t s);
+                                  const float* x, const float* w_min, const float* w_max, float* grad_w_min,
+                                  float* grad_w_max, float* grad_alpha, float* grad_beta, float* grad_bias,
+                                  double* partial, hipStream_t s);
 // partial: device scratch of backward_weight_workspace(p) bytes for the deterministic two-stage form (fp64 partial
 // histograms per batch slice, added in a fixed order, one rounding), or NULL: fp32 atomics into zero-filled tensors
 size_t backward_weight_workspace(const Params& p);

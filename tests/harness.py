@@ -62,7 +62,8 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
     """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32).
     deterministic: the parameter gradients get their workspaces (fixed-order fp64 sums); False: the atomic forms.
     fused: grad_x and the kernel gradients through the one-call tconv_backward instead of the two separate calls;
-    "params": grad_x by tconv_backward_input and every parameter gradient, grad_bias included, by tconv_backward_params."""
+    "params": grad_x by tconv_backward_input and every parameter gradient, grad_bias included, by tconv_backward_params;
+    "recompute": the same by tconv_backward_params_recompute after a forward pass without branch outputs."""
     import torch
     dev = torch.device(device)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -109,7 +110,19 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
         wshape = (cfg.C_out, cfg.C_in, cfg.KH, cfg.KW)
         gw_min = torch.full(wshape, float("nan"), device=dev) if do_min else None
         gw_max = torch.full(wshape, float("nan"), device=dev) if cfg.mode in ("max", "parallel", "maxplus_min") else None
-        if fused == "params":
+        if fused == "recompute":
+            # the forward pass above kept no branch outputs; the combine-coefficient gradients come from the winners
+            assert y_min is None and y_max is None
+            tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
+            ab = cfg.mode in ("compound", "parallel")
+            ga = torch.full((cfg.C_out,), float("nan"), device=dev) if ab else None
+            gb = torch.full((cfg.C_out,), float("nan"), device=dev) if ab else None
+            gbias = torch.full((cfg.C_out,), float("nan"), device=dev)
+            ws_p = scratch(tb.tconv_workspace_bytes(d, "backward_params"), dev)
+            tb.tconv_backward_params_recompute(d, x, w_min, w_max, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max,
+                                               ga, gb, gbias, ws_p)
+            out.update(grad_alpha=ga, grad_beta=gb, grad_bias=gbias)
+        elif fused == "params":
             # grad_x by its own call, every parameter gradient (kernels, combine coefficients, bias) by the one-call form
             tb.tconv_backward_input(d, gy, alpha, beta, idx_min, idx_max, gx)
             ab = cfg.mode in ("compound", "parallel") and branch_outputs
@@ -128,7 +141,7 @@ def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deter
             ws_w = scratch(tb.tconv_workspace_bytes(d, "backward_weight"), dev) if deterministic else None
             tb.tconv_backward_weight(d, gy, alpha, beta, idx_min, idx_max, gw_min, gw_max, ws_w)
         out.update(grad_x=gx, grad_w_min=gw_min, grad_w_max=gw_max)
-        if cfg.mode in ("compound", "parallel") and branch_outputs and fused != "params":
+        if cfg.mode in ("compound", "parallel") and branch_outputs and fused not in ("params", "recompute"):
             ga = torch.full((cfg.C_out,), float("nan"), device=dev)
             gb = torch.full((cfg.C_out,), float("nan"), device=dev)
             ws_ab = scratch(tb.tconv_workspace_bytes(d, "backward_alpha_beta"), dev) if deterministic else None

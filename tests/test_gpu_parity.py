@@ -303,6 +303,44 @@ def test_parameter_gradients_in_one_call(cfg):
     hs.assert_backward_close(hip, ref, what=f"[{c.name} compound one-call, no branch outputs] ")
 
 
+@pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[13], RAGGED[15], RAGGED[20],
+                                 RAGGED[23], RAGGED_LARGE[0], RAGGED_SPLIT[0]], ids=lambda c: c.name)
+def test_parameter_gradients_without_stored_branch_outputs(cfg):
+    """tconv_backward_params_recompute after a forward pass that kept no y_min / y_max: every parameter gradient
+    against the oracle (the combine-coefficient gradients need the branch outputs, which the kernel forms again from
+    the winners), and bit for bit against tconv_backward_params on stored branch outputs."""
+    from oracle import text_oracle as ext
+    s = ext.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+    for mode in MODES + ("minplus_max", "maxplus_min"):
+        for integer in (False, True):
+            c = cfg.with_(mode=mode)
+            inp = make_inputs(c, alpha_beta="random" if mode in ("compound", "parallel") else None, integer=integer)
+            ref = hs.run_oracle(c, inp)
+            ref["grad_bias"] = ext.backward_bias(s, inp["gy"])
+            ref["grad_bias_scale"] = ext.backward_bias(s, np.abs(inp["gy"]))
+            hip = hs.run_hip(c, inp, fused="recompute", branch_outputs=False)
+            what = f"[{c.name} {mode} int={integer} recompute] "
+            hs.assert_backward_close(hip, ref, what=what)
+            hs.assert_grad_close(hip["grad_bias"], ref["grad_bias"], ref["grad_bias_scale"], what + "grad_bias")
+            stored = hs.run_hip(c, inp, fused="params")
+            for k in ("grad_w_min", "grad_w_max", "grad_alpha", "grad_beta", "grad_bias"):
+                if stored.get(k) is not None:
+                    assert np.array_equal(hs.bits(hip[k]), hs.bits(stored[k])), what + k + " differs from the stored form"
+    # zero padding: a winner may lie in the padding, where the recomputed branch output is fl(0 + w)
+    for mode in ("compound", "parallel"):
+        c = cfg.with_(mode=mode, pad_mode="zero")
+        inp = make_inputs(c, alpha_beta="random", integer=(mode == "parallel"))
+        ref = hs.run_oracle_ext(c, inp)
+        gy64 = inp["gy"].astype(np.float64)
+        for k, yk in (("grad_alpha", "y_min"), ("grad_beta", "y_max")):
+            ref[k] = (gy64 * ref[yk]).sum(axis=(0, 2, 3))
+            ref[k + "_scale"] = (np.abs(gy64) * np.abs(ref[yk])).sum(axis=(0, 2, 3))
+        hip = hs.run_hip(c, inp, fused="recompute", branch_outputs=False)
+        what = f"[{c.name} {mode} zero padding, recompute] "
+        hs.assert_backward_close(hip, ref, what=what)
+        hs.assert_grad_close(hip["grad_bias"], ref["grad_bias"], ref["grad_bias_scale"], what + "grad_bias")
+
+
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10]], ids=lambda c: c.name)
 def test_generic_kernel_on_ragged_shapes(cfg):
     for mode in MODES:
