@@ -107,7 +107,7 @@ def main() -> int:
     ap.add_argument("--recompute-branch-outputs", action="store_true",
                     help="cfg5net: the forward pass stores no y_min / y_max (12 instead of 20 bytes per output) and "
                          "tconv_backward_params_recompute forms them again from the winners; default: stored and read "
-                         "by tconv_backward_params (the faster step: 2.29 against 2.50 ms)")
+                         "by tconv_backward_params (the faster step: 2.29 against 2.48 ms)")
     ap.add_argument("--no-layers", action="store_true",
                     help="leave out the per-layer table of the other bar layers (profiling runs)")
     ap.add_argument("--separate-backward", action="store_true",

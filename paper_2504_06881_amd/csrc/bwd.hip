@@ -522,6 +522,8 @@ struct ParamExtras {
   const float* w_min;
   const float* w_max;
   int want_alpha, want_beta;
+  int k3;            // 3 x 3 window with K < 73700
+  unsigned inv_wo;   // 2^32 / W_out + 1 where that divides every pixel number of a plane exactly, else 0
 };
 constexpr int N_EXTRA = 3;  // bias, alpha, beta
 
@@ -582,8 +584,19 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
         const int KK = p.KH * p.KW;
         auto branch_output = [&](int nn, int qq, int k, const float* w) -> float {
           if ((unsigned)k >= (unsigned)K) return 0.f;  // a corrupted index stays in bounds (and adds nothing below)
-          const int c = k / KK, r = k - c * KK, i = r / p.KW, j = r - i * p.KW;
-          const int oh = qq / p.Wo, ow = qq - oh * p.Wo;
+          int c, i, j;
+          if (ex.k3) {  // 3 x 3 windows, K < 73700: the winner unflattens with 24-bit multiplies (exact in that range)
+            c = (int)(__umul24((unsigned)k, 58255u) >> 19);
+            const int r = k - __mul24(c, 9);
+            i = (int)(__umul24((unsigned)r, 11u) >> 5);
+            j = r - __mul24(i, 3);
+          } else {
+            c = k / KK;
+            const int r = k - c * KK;
+            i = r / p.KW;
+            j = r - i * p.KW;
+          }
+          const int oh = ex.inv_wo ? (int)__umulhi((unsigned)qq, ex.inv_wo) : qq / p.Wo, ow = qq - oh * p.Wo;
           const int ih = oh * p.sh - p.ph + i * p.dh, iw = ow * p.sw - p.pw + j * p.dw;
           const bool inside = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
           const float xv = inside ? ex.x[((size_t)nn * p.C_in + c) * ((size_t)p.H * p.W) + (size_t)ih * p.W + iw] : 0.f;
@@ -828,8 +841,11 @@ hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float
   const int slices = weight_slices(p, &n_per_block);
   const dim3 grid(p.C_out, slices);
   const bool recompute = x != nullptr;  // the branch outputs again from the winners instead of stored tensors
+  const long long plane = (long long)p.Ho * p.Wo;
+  const unsigned inv_wo = (p.Wo > 1 && plane * p.Wo < 0x100000000LL) ? (unsigned)(0x100000000ULL / (unsigned)p.Wo) + 1u : 0u;
   const ParamExtras ex = {(!recompute && grad_alpha) ? y_min : nullptr, (!recompute && grad_beta) ? y_max : nullptr,
-                          x, w_min, w_max, (recompute && grad_alpha) ? 1 : 0, (recompute && grad_beta) ? 1 : 0};
+                          x, w_min, w_max, (recompute && grad_alpha) ? 1 : 0, (recompute && grad_beta) ? 1 : 0,
+                          (p.KH == 3 && p.KW == 3 && p.K < 73700) ? 1 : 0, inv_wo};
 #define TCONV_LAUNCH_PARAMS(M)                                                                                       \
   do {                                                                                                               \
     if (recompute)                                                                                                   \
