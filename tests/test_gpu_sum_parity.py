@@ -56,6 +56,8 @@ SHAPES = [
     LayerCfg("s_quad_g4", 9, 3, 16, 16, 6, seed=59),
     LayerCfg("s_quad_g16", 20, 2, 8, 8, 5, seed=60),
     LayerCfg("s_quad_g2", 5, 3, 16, 24, 10, seed=61),
+    LayerCfg("s_quad_p2", 2, 3, 30, 30, 5, pad=2, seed=69),            # padding 2: windows that start two rows above the image
+    LayerCfg("s_quad_bands_p2", 1, 2, 66, 30, 3, pad=2, seed=70),
     LayerCfg("s_quad_bands_p0", 1, 2, 70, 30, 3, pad=0, seed=64),   # more than 1024 outputs: bands of rows, no padding
     # stride 2: the backward kernel's threads own two adjacent outputs; groups of images, bands of rows
     LayerCfg("s_pair_g2", 5, 3, 32, 32, 6, stride=2, seed=65),
