@@ -208,6 +208,17 @@ def test_random_sum_layers(cfg):
     _check(cfg.with_(mode="compound"), integer=True)
 
 
+def test_sum_input_gradient_is_the_same_on_every_run():
+    """The adjacent-outputs backward kernel adds into slots no other thread touches and gathers them in a fixed order:
+    grad_x must repeat bit for bit (the parameter gradients, combined by fp32 atomics, need not)."""
+    cfg = CONFIGS["cfg2_main"].with_(N=8, name="s_cfg2_n8")
+    inp = make_inputs(cfg)
+    alpha, beta = hs.sum_coefficients(cfg, inp, "random")
+    runs = [hs.run_hip_sum(cfg, inp, alpha, beta)["grad_x"] for _ in range(3)]
+    for r in runs[1:]:
+        assert np.array_equal(hs.bits(r), hs.bits(runs[0]))
+
+
 def test_sum_layer_at_a_benchmark_size():
     """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
     cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
