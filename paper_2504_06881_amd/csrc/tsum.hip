@@ -87,18 +87,19 @@ __global__ __launch_bounds__(256) void sum_fwd_generic_kernel(Params p, const fl
 // WAVES waves of a workgroup share the segments and differ in output-channel group.  Per input
 // channel a lane holds 3 rows x (PX + 2*D) input values (loaded one channel ahead into a second set
 // of registers), padding replaced by NaN, which v_max3 / v_min3 ignore.
-template <int MODE, int D, int S, typename TO, int TN>
+template <int MODE, int D, int S, typename TO, int TN, int PX>
 __global__ __launch_bounds__(WAVES * 64, (D == 1 && MODE != TCONV_PARALLEL) ? 4 : 2) void sum_fwd_tiled3x3_kernel(
     Params p, const TO* __restrict__ x, const float* __restrict__ w_min,
     const float* __restrict__ w_max, const float* __restrict__ alpha, const float* __restrict__ beta,
     TO* __restrict__ y, int segs, int n_units, int n_groups, int n_blocks, int xcd_runs, int wpb) {
   constexpr bool DO_MIN = (MODE != TCONV_MAX), DO_MAX = (MODE != TCONV_MIN);
   constexpr bool TWO = (MODE == TCONV_COMPOUND || MODE == TCONV_PARALLEL);
-  constexpr int PX = S == 1 ? 8 : 4;
-  constexpr int CORE = 8;                       // columns of the 32-byte run every row is loaded with
+  // PX outputs per lane: 8 at stride 1 (4 on layers with too few lanes otherwise), 4 at stride 2
+  constexpr int CORE = PX * S;                  // columns of the run every row is loaded with (32 or 16 bytes)
   constexpr int NHR = (PX - 1) * S + D + 1 - CORE;  // halo columns right of the run: D at stride 1, none at stride 2
   constexpr int XR = D + CORE + NHR;
-  static_assert(NHR >= 0 && (S == 1 || D == 1), "geometries: stride 1 with dilation 1 or 2, stride 2 with dilation 1");
+  static_assert(NHR >= 0 && (S == 1 || (D == 1 && PX == 4)) && (PX == 4 || PX == 8),
+                "geometries: stride 1 with dilation 1 or 2, stride 2 with dilation 1 and 4 outputs per lane");
 
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  xcd_runs: every XCD gets a contiguous
   // run of workgroup numbers, so that the output-channel groups of a pixel block (consecutive numbers, same
@@ -1014,8 +1015,8 @@ bool tiled_ok(const Params& p) {
   if (p.KH != 3 || p.KW != 3 || p.sh != p.sw || p.dh != p.dw) return false;
   const bool geo = (p.sh == 1 && (p.dh == 1 || p.dh == 2)) || (p.sh == 2 && p.dh == 1);
   if (!geo) return false;
-  if (p.pw > p.dw || p.Wo < (p.sh == 1 ? 8 : 4)) return false;
-  if (p.W < 8) return false;  // a row is loaded as a run of 8 columns
+  if (p.pw > p.dw || p.Wo < 4) return false;
+  if (p.W < 8) return false;  // a row is loaded as a run of 8 (or 4) columns
   if ((size_t)p.N * p.C_in * p.H * p.W * 4 >= 0xfffff000ull) return false;
   return true;
 }
@@ -1025,23 +1026,38 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
   const char* e = getenv("TCONV_FORWARD_KERNEL");
   const bool force_generic = e && strcmp(e, "generic") == 0;
   if (tiled_ok(p) && !force_generic) {
-    const int px = p.sh == 1 ? 8 : 4;
+    // Small layers (the maps of a CIFAR network) have too few waves at 8 outputs x 4 output channels per lane: fewer
+    // outputs (stride 1) or channels per lane then.  1 channel per lane gains nothing more, nor do fewer waves per
+    // workgroup at the same number of waves.
+    const char* te = getenv("TCONV_SUM_FWD_TN");  // testing aid: 2 or 4 output channels per lane
+    const char* pe = getenv("TCONV_SUM_FWD_PX");  // testing aid: 4 or 8 outputs per lane at stride 1
+    const int wpb = WAVES;
+    auto nwaves = [&](int tn_, int px_) {
+      const long long units = (long long)p.N * p.Ho * ((p.Wo + px_ - 1) / px_);
+      return ((units + 63) / 64) * (((long long)p.C_out + tn_ - 1) / tn_);
+    };
+    int tn = 4, px = p.sh == 1 ? 8 : 4;
+    if (p.sh == 1) {
+      // the first of (4 channels, 8 outputs), (4, 4), (2, 8), (2, 4) per lane that gives two waves per SIMD, else the last.
+      // Measured (us, the four forms in that order): [128, 16, 32, 32] -> 16: 33.2 / 28.8 / 34.9 / 35.4,
+      // [128, 32, 16, 16] -> 32: 55.5 / 35.6 / 32.3 / 33.0, [128, 64, 8, 8] -> 64: 100.8 / 63.5 / 55.7 / 38.7.
+      static const int forms[4][2] = {{4, 8}, {4, 4}, {2, 8}, {2, 4}};
+      int pick = 3;
+      for (int f = 0; f < 4; ++f)
+        if (nwaves(forms[f][0], forms[f][1]) >= 2048) { pick = f; break; }
+      tn = forms[pick][0];
+      px = forms[pick][1];
+    } else if (nwaves(4, px) < 1024) {
+      tn = 2;
+    }
+    if (te && (te[0] == '2' || te[0] == '4') && te[1] == 0) tn = te[0] - '0';
+    if (p.sh == 1 && pe && (pe[0] == '4' || pe[0] == '8') && pe[1] == 0) px = pe[0] - '0';
+    if (p.Wo < px) px = 4;  // Wo >= 4 here
     const int segs = (p.Wo + px - 1) / px;
     const long long n_units = (long long)p.N * p.Ho * segs;
     const long long ublocks = (n_units + 63) / 64;
-    // Small layers (the 16 x 16 and 8 x 8 maps of a CIFAR network) have too few waves at 4 output channels per lane:
-    // 2 channels per lane when 4 leave fewer than one wave per SIMD ([128, 32, 16, 16] -> 32: 54 -> 32 us, [128, 64, 8, 8]
-    // -> 64: 99 -> 55 us; 1 channel per lane gains nothing more, nor do fewer waves per workgroup at the same number
-    // of waves).
-    const char* te = getenv("TCONV_SUM_FWD_TN");  // testing aid: 2 or 4 output channels per lane
-    const int wpb = WAVES;
-    auto nblocks = [&](int tn_, int wpb_) { return ublocks * ((((long long)p.C_out + tn_ - 1) / tn_ + wpb_ - 1) / wpb_); };
-    auto nwaves = [&](int tn_) { return ublocks * (((long long)p.C_out + tn_ - 1) / tn_); };
-    int tn = 4;
-    if (te && (te[0] == '2' || te[0] == '4') && te[1] == 0) tn = te[0] - '0';
-    else if (nwaves(4) < 1024) tn = 2;
     const int n_groups = (p.C_out + tn - 1) / tn;
-    const long long blocks = nblocks(tn, wpb);
+    const long long blocks = ublocks * ((n_groups + wpb - 1) / wpb);
     if (blocks > 0x7ffffff0LL) return hipErrorInvalidValue;
     // contiguous runs per XCD while the kernels and coefficients are small next to an L2 (as for the full-window kernel)
     const long long w_bytes = (long long)p.C_out * p.K * (long long)sizeof(float) * (MODE == TCONV_PARALLEL ? 2 : 1);
@@ -1050,14 +1066,14 @@ hipError_t launch_fwd(const Params& p, const SumArgs& a, hipStream_t s) {
     const unsigned grid = (unsigned)(((blocks + 7) / 8) * 8);
     const TO* x = (const TO*)a.x;
     TO* y = (TO*)a.y;
-#define TCONV_SUM_FWD(D_, S_, TN_)                                                                                     \
-  hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, D_, S_, TO, TN_>), dim3(grid), dim3(wpb * 64), 0, s, p, x, a.w_min, \
+#define TCONV_SUM_FWD(D_, S_, TN_, PX_)                                                                                     \
+  hipLaunchKernelGGL((sum_fwd_tiled3x3_kernel<MODE, D_, S_, TO, TN_, PX_>), dim3(grid), dim3(wpb * 64), 0, s, p, x, a.w_min, \
                      a.w_max, a.alpha, a.beta, y, segs, (int)n_units, n_groups, (int)blocks, xcd_runs, wpb)
-#define TCONV_SUM_FWD_TN(D_, S_) \
-  do { if (tn == 4) TCONV_SUM_FWD(D_, S_, 4); else TCONV_SUM_FWD(D_, S_, 2); } while (0)
-    if (p.sh == 2) TCONV_SUM_FWD_TN(1, 2);
-    else if (p.dh == 1) TCONV_SUM_FWD_TN(1, 1);
-    else TCONV_SUM_FWD_TN(2, 1);
+#define TCONV_SUM_FWD_TN(D_, S_, PX_) \
+  do { if (tn == 4) TCONV_SUM_FWD(D_, S_, 4, PX_); else TCONV_SUM_FWD(D_, S_, 2, PX_); } while (0)
+    if (p.sh == 2) TCONV_SUM_FWD_TN(1, 2, 4);
+    else if (p.dh == 1) { if (px == 8) TCONV_SUM_FWD_TN(1, 1, 8); else TCONV_SUM_FWD_TN(1, 1, 4); }
+    else { if (px == 8) TCONV_SUM_FWD_TN(2, 1, 8); else TCONV_SUM_FWD_TN(2, 1, 4); }
 #undef TCONV_SUM_FWD_TN
 #undef TCONV_SUM_FWD
   } else if (sizeof(TO) != 4) {

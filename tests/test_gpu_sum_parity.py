@@ -114,15 +114,18 @@ def test_sum_backward_of_mid_size_planes_by_the_kernel_for_any_plane(cfg):
         os.environ.pop("TCONV_SUM_BWD", None)
 
 
+@pytest.mark.parametrize("px", ["4", "8"])
 @pytest.mark.parametrize("tn", ["2", "4"])
 @pytest.mark.parametrize("cfg", [c for c in SHAPES if c.name in ("s_cfg1", "s_3x3", "s_3x3_even", "s_3x3_d2", "s_3x3_s2",
-                                                               "s_cin33", "s_3x3_s2_p0", "s_quad")],
+                                                               "s_cin33", "s_3x3_s2_p0", "s_quad", "s_3x3_p0")],
                          ids=lambda c: c.name)
-def test_sum_forward_channels_per_lane(cfg, tn):
-    """Both instantiations of the tiled forward kernel (small layers pick 2 output channels per lane, large ones 4) on
-    the ragged shapes: odd channel counts, tails of 1 to 3 channels, shifted last segments."""
+def test_sum_forward_channels_and_outputs_per_lane(cfg, tn, px):
+    """Every instantiation of the tiled forward kernel (small layers pick 2 output channels and, at stride 1, 4 outputs
+    per lane, large ones 4 and 8) on the ragged shapes: odd channel counts, tails of 1 to 3 channels, shifted last
+    segments."""
     import os
     os.environ["TCONV_SUM_FWD_TN"] = tn
+    os.environ["TCONV_SUM_FWD_PX"] = px
     try:
         for mode in MODES:
             _check(cfg.with_(mode=mode))
@@ -130,6 +133,7 @@ def test_sum_forward_channels_per_lane(cfg, tn):
         _check(cfg.with_(mode="parallel", dtype="bf16"))
     finally:
         os.environ.pop("TCONV_SUM_FWD_TN", None)
+        os.environ.pop("TCONV_SUM_FWD_PX", None)
 
 
 def test_sum_tiled_forward_takes_stride_two():
