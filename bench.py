@@ -511,6 +511,31 @@ def main() -> int:
                       "frac": round(ps * 1.5 / (t_sf * 1e-3) / LANE_OPS_PER_S, 4),
                       "ms_backward": round(t_sb, 4), "step_gops": round(ps / ((t_sf + t_sb) * 1e-3) / 1e9, 1)})
         del Ls
+        torch.cuda.empty_cache()
+        # the 19 layers of the ResNet-20 stack as Sum-channel layers (batch 256), back to back
+        sstack = [Layer(c, "sum") for c in resnet20_layers(256)]
+        for _ in range(2):
+            for L in sstack:
+                L.fwd(); L.bwd()
+        torch.cuda.synchronize()
+
+        def sum_fwd_all(i):
+            for L in sstack:
+                L.fwd()
+
+        def sum_bwd_all(i):
+            for L in sstack:
+                L.bwd()
+
+        t_ssf = time_loop(sum_fwd_all, 5)
+        t_ssb = time_loop(sum_bwd_all, 5)
+        pss = sum(L.cfg.pairs for L in sstack)
+        table.append({"layer": "cfg5 as Sum-channel layers (19 layers, batch 256, launches back to back)",
+                      "mode": "parallel", "storage": "f32", "pairs": pss, "ms_forward": round(t_ssf, 4),
+                      "forward_gops": round(pss / (t_ssf * 1e-3) / 1e9, 1),
+                      "frac": round(pss * 2.0 / (t_ssf * 1e-3) / LANE_OPS_PER_S, 4), "ms_backward": round(t_ssb, 4),
+                      "step_gops": round(pss / ((t_ssf + t_ssb) * 1e-3) / 1e9, 1)})
+        del sstack
         out["layers"] = table
     print(json.dumps(out), flush=True)
     return 0
