@@ -223,6 +223,33 @@ def test_sum_input_gradient_is_the_same_on_every_run():
         assert np.array_equal(hs.bits(r), hs.bits(runs[0]))
 
 
+def test_sum_backward_with_gy_at_an_address_that_is_4_mod_16():
+    """The adjacent-outputs kernel reads gy in 16-byte pieces; a gy that is only 4-byte aligned takes the kernel for
+    any plane and gives the same gradients."""
+    import torch
+    cfg = next(c for c in SHAPES if c.name == "s_quad").with_(mode="compound")
+    inp = make_inputs(cfg)
+    alpha, beta = hs.sum_coefficients(cfg, inp, "random")
+    dev = torch.device("cuda:0")
+    d = tb.Desc.from_cfg(cfg)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+    x, w, al, be, gy = up(inp["x"]), up(inp["w_min"]), up(alpha), up(beta), up(inp["gy"])
+    big = torch.empty(gy.numel() + 1, device=dev)
+    big[1:].copy_(gy.reshape(-1))
+    gy_off = big[1:].view(gy.shape)
+    assert gy_off.data_ptr() % 16 == 4
+    outs = []
+    for g in (gy, gy_off):
+        gx, gw = torch.full_like(x, float("nan")), torch.full_like(w, float("nan"))
+        ga, gb = torch.full_like(al, float("nan")), torch.full_like(be, float("nan"))
+        tb.tconv_sum_backward(d, x, w, w, al, be, g, gx, gw, None, ga, gb)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().astype(np.float64) for t in (gx, gw, ga, gb)])
+    for a, b in zip(*outs):
+        assert np.isfinite(b).all()
+        assert np.abs(a - b).max() <= 1e-5 * max(1.0, np.abs(a).max())
+
+
 def test_sum_layer_at_a_benchmark_size():
     """[32, 64, 32, 32] -> 64, compound: a quarter of the headline layer's batch (the oracle stays in seconds)."""
     cfg = CONFIGS["cfg2_main"].with_(N=32, name="s_cfg2_n32")
