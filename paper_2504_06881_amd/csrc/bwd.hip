@@ -524,6 +524,10 @@ struct ParamExtras {
   int want_alpha, want_beta;
   int k3;            // 3 x 3 window with K < 73700
   unsigned inv_wo;   // 2^32 / W_out + 1 where that divides every pixel number of a plane exactly, else 0
+  // where the three extra sums go when the batch is not sliced (one workgroup per output channel writes its results)
+  float* grad_bias;
+  float* grad_alpha;
+  float* grad_beta;
 };
 constexpr int N_EXTRA = 3;  // bias, alpha, beta
 
@@ -646,6 +650,20 @@ __global__ __launch_bounds__(1024) void bwd_weight_hist_kernel(Params p, BwdArgs
       hist[NHIST * K + threadIdx.x] = t;
     }
     __syncthreads();
+  }
+  if (partial && gridDim.y == 1) {
+    // the batch is not sliced (at least 512 output channels): this workgroup's sums are the result, rounded once as the
+    // second stage would round them; no partial histograms, no second kernel
+    float* d0 = (MODE == TCONV_MAX) ? gw_max : gw_min;
+    for (int k = threadIdx.x; k < K; k += bd) {
+      d0[(size_t)co * K + k] = (float)hist[k];
+      if (NHIST == 2) gw_max[(size_t)co * K + k] = (float)hmax[k];
+    }
+    if (EXTRA && threadIdx.x < N_EXTRA) {
+      float* const d = threadIdx.x == 0 ? ex.grad_bias : (threadIdx.x == 1 ? ex.grad_alpha : ex.grad_beta);
+      if (d) d[co] = (float)hist[NHIST * K + threadIdx.x];
+    }
+    return;
   }
   if (partial) {  // two-stage form: the fp64 histogram of this (batch slice, channel) as it is; a second kernel adds the slices
     const int NH = NHIST * K + (EXTRA ? N_EXTRA : 0);
@@ -790,7 +808,7 @@ hipError_t launch_backward_weight(const Params& p, const BwdArgs& a, float* grad
         hipLaunchKernelGGL((bwd_weight_hist_kernel<TCONV_PARALLEL, 0>), grid, dim3(1024), lds, s, p, a, gmin, gmax, n_per_block, partial, ParamExtras{});
         break;
     }
-    if (partial) {
+    if (partial && slices > 1) {  // one slice: the histogram kernel has written the result itself
       size_t blocks = (wn + 255) / 256;
       if (blocks > 2048) blocks = 2048;
       float* d0 = (p.mode == TCONV_MAX) ? gmax : gmin;
@@ -845,7 +863,7 @@ hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float
   const unsigned inv_wo = (p.Wo > 1 && plane * p.Wo < 0x100000000LL) ? (unsigned)(0x100000000ULL / (unsigned)p.Wo) + 1u : 0u;
   const ParamExtras ex = {(!recompute && grad_alpha) ? y_min : nullptr, (!recompute && grad_beta) ? y_max : nullptr,
                           x, w_min, w_max, (recompute && grad_alpha) ? 1 : 0, (recompute && grad_beta) ? 1 : 0,
-                          (p.KH == 3 && p.KW == 3 && p.K < 73700) ? 1 : 0, inv_wo};
+                          (p.KH == 3 && p.KW == 3 && p.K < 73700) ? 1 : 0, inv_wo, grad_bias, grad_alpha, grad_beta};
 #define TCONV_LAUNCH_PARAMS(M)                                                                                       \
   do {                                                                                                               \
     if (recompute)                                                                                                   \
@@ -862,6 +880,7 @@ hipError_t launch_backward_params(const Params& p, const BwdArgs& a, const float
     default: TCONV_LAUNCH_PARAMS(TCONV_PARALLEL); break;
   }
 #undef TCONV_LAUNCH_PARAMS
+  if (slices == 1) return hipGetLastError();  // one slice: the histogram kernel has written the results itself
   const size_t total = (size_t)p.C_out * ((size_t)nhist * p.K + N_EXTRA);
   size_t blocks = (total + 255) / 256;
   if (blocks > 2048) blocks = 2048;
