@@ -94,7 +94,7 @@ enum tconv_op {
 enum tconv_status {
   TCONV_OK = 0,
   TCONV_E_INVAL = -1,       /* NULL required pointer, non-positive dim, stride < 1, dil < 1, pad < 0, bad mode / dtype / op */
-  TCONV_E_SHAPE = -2,       /* H_out or W_out < 1, pad > dil*(k-1) (a window could be all padding), a tensor with >= 2^31 elements */
+  TCONV_E_SHAPE = -2,       /* H_out or W_out < 1, a window with no tap inside the input (pad > dil*(k-1), or dilated taps that straddle an input shorter than the dilation), a tensor with >= 2^31 elements */
   TCONV_E_WORKSPACE = -3,   /* workspace NULL or smaller than tconv_workspace_bytes() reports */
   TCONV_E_UNSUPPORTED = -4, /* valid request this build has no kernel for */
   TCONV_E_LAUNCH = -5       /* the HIP runtime refused a launch (hipGetLastError) */

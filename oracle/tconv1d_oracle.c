@@ -30,13 +30,27 @@ typedef struct oracle1d_shape {
 
 enum { O_MAX = 0, O_MIN = 1, O_COMPOUND = 2, O_PARALLEL = 3, O_MINPLUS_MAX = 4, O_MAXPLUS_MIN = 5 };
 
+/* 1 if some window of one axis has no tap inside the input (written out: every output position, every tap).  The
+ * extremum of Sec. 3.1 over an empty set of taps is not defined, so such a layer is rejected. */
+static int axis_has_empty_window(long in, long k, long stride, long pad, long dil, long out) {
+  for (long o = 0; o < out; ++o) {
+    int hit = 0;
+    for (long t = 0; t < k; ++t) {
+      long i = o * stride - pad + t * dil;
+      if (i >= 0 && i < in) hit = 1;
+    }
+    if (!hit) return 1;
+  }
+  return 0;
+}
+
 static int out_len(const oracle1d_shape* s, int32_t* L_out) {
   long ext = (long)s->dil * (s->K - 1);
   long n = (long)s->L + 2L * s->pad - ext - 1;
   if (s->N < 1 || s->C_in < 1 || s->L < 1 || s->C_out < 1 || s->K < 1 || s->stride < 1 || s->dil < 1 || s->pad < 0) return -1;
   if (n < 0 || s->pad > ext) return -1;
   *L_out = (int32_t)(n / s->stride + 1);
-  return 0;
+  return axis_has_empty_window(s->L, s->K, s->stride, s->pad, s->dil, *L_out) ? -1 : 0;
 }
 
 /* Base operator of one channel at output position l: extremum over the valid taps and its lowest tap. */
@@ -141,8 +155,10 @@ int oracle_tconv1d_backward(const oracle1d_shape* s, int mode, const float* gy, 
           if (b == 0 ? !do_min : !do_max) continue;
           const int32_t k = b == 0 ? idx_min[o] : idx_max[o];
           const double coef = !two ? 1.0 : (b == 0 ? (alpha ? (double)alpha[co] : 1.0) : (beta ? (double)beta[co] : 1.0));
+          if (k < 0 || k >= KW) return -2; /* not a winner index of this layer */
           const int c = k / s->K, i = k % s->K;
           const long pos = (long)l * s->stride - s->pad + (long)i * s->dil;
+          if (pos < 0 || pos >= s->L) return -2; /* a padded tap */
           if (grad_x) grad_x[((long)n * s->C_in + c) * s->L + pos] += coef * g;
           double* gw = b == 0 ? grad_w_min : grad_w_max;
           if (gw) gw[(long)co * KW + k] += coef * g;

@@ -29,11 +29,25 @@ typedef struct oracle3d_shape {
 
 enum { O_MAX = 0, O_MIN = 1, O_COMPOUND = 2, O_PARALLEL = 3, O_MINPLUS_MAX = 4, O_MAXPLUS_MIN = 5 };
 
+/* 1 if some window of one axis has no tap inside the input (written out: every output position, every tap).  The
+ * extremum of Sec. 3.1 over an empty set of taps is not defined, so such a layer is rejected. */
+static int axis_has_empty_window(long in, long k, long stride, long pad, long dil, long out) {
+  for (long o = 0; o < out; ++o) {
+    int hit = 0;
+    for (long t = 0; t < k; ++t) {
+      long i = o * stride - pad + t * dil;
+      if (i >= 0 && i < in) hit = 1;
+    }
+    if (!hit) return 1;
+  }
+  return 0;
+}
+
 static int out_dim(long in, long k, long stride, long pad, long dil, int32_t* out) {
   long ext = dil * (k - 1), n = in + 2 * pad - ext - 1;
   if (in < 1 || k < 1 || stride < 1 || dil < 1 || pad < 0 || n < 0 || pad > ext) return -1;
   *out = (int32_t)(n / stride + 1);
-  return 0;
+  return axis_has_empty_window(in, k, stride, pad, dil, *out) ? -1 : 0;
 }
 
 static int out_shape(const oracle3d_shape* s, int32_t* Do, int32_t* Ho, int32_t* Wo) {
@@ -160,11 +174,13 @@ int oracle_tconv3d_backward(const oracle3d_shape* s, int mode, const float* gy, 
               if (b == 0 ? !do_min : !do_max) continue;
               const int32_t k = b == 0 ? idx_min[o] : idx_max[o];
               const double coef = !two ? 1.0 : (b == 0 ? (alpha ? (double)alpha[co] : 1.0) : (beta ? (double)beta[co] : 1.0));
+              if (k < 0 || k >= K) return -2; /* not a winner index of this layer */
               const int c = k / KK, t = k % KK;
               const int a = t / (s->KH * s->KW), i = (t / s->KW) % s->KH, j = t % s->KW;
               const long id = (long)od * s->stride[0] - s->pad[0] + (long)a * s->dil[0];
               const long ih = (long)oh * s->stride[1] - s->pad[1] + (long)i * s->dil[1];
               const long iw = (long)ow * s->stride[2] - s->pad[2] + (long)j * s->dil[2];
+              if (id < 0 || id >= s->D || ih < 0 || ih >= s->H || iw < 0 || iw >= s->W) return -2; /* a padded tap */
               if (grad_x) grad_x[((long)n * s->C_in + c) * vol + (id * s->H + ih) * s->W + iw] += coef * g;
               double* gw = b == 0 ? grad_w_min : grad_w_max;
               if (gw) gw[co * K + k] += coef * g;

@@ -65,6 +65,20 @@ void oracle_set_threads(int n) {
 #endif
 }
 
+/* 1 if some window of one axis has no tap inside the input (written out: every output position, every tap).  The
+ * extremum of Sec. 3.1 over an empty set of taps is not defined, so such a layer is rejected. */
+static int axis_has_empty_window(long in, long k, long stride, long pad, long dil, long out) {
+  for (long o = 0; o < out; ++o) {
+    int hit = 0;
+    for (long t = 0; t < k; ++t) {
+      long i = o * stride - pad + t * dil;
+      if (i >= 0 && i < in) hit = 1;
+    }
+    if (!hit) return 1;
+  }
+  return 0;
+}
+
 int oracle_out_shape(const oracle_shape* s, int32_t* H_out, int32_t* W_out) {
   long eh = (long)s->dil_h * (s->KH - 1) + 1, ew = (long)s->dil_w * (s->KW - 1) + 1;
   long nh = (long)s->H + 2L * s->pad_h - eh, nw = (long)s->W + 2L * s->pad_w - ew;
@@ -127,6 +141,9 @@ int oracle_tconv_forward(const oracle_shape* s, int mode, const float* x, const 
   int32_t Ho, Wo;
   if (oracle_out_shape(s, &Ho, &Wo) != 0 || Ho < 1 || Wo < 1) return -1;
   if (s->pad_h > s->dil_h * (s->KH - 1) || s->pad_w > s->dil_w * (s->KW - 1)) return -1;
+  if (axis_has_empty_window(s->H, s->KH, s->stride_h, s->pad_h, s->dil_h, Ho) ||
+      axis_has_empty_window(s->W, s->KW, s->stride_w, s->pad_w, s->dil_w, Wo))
+    return -1;
   const int do_min = (mode != ORACLE_MAX), do_max = (mode != ORACLE_MIN);
   const float* wmn = w_min;
   const float* wmx = w_max;
@@ -186,6 +203,9 @@ int oracle_tconv_forward_mixed(const oracle_shape* s, int outer_max, const float
   int32_t Ho, Wo;
   if (oracle_out_shape(s, &Ho, &Wo) != 0 || Ho < 1 || Wo < 1) return -1;
   if (s->pad_h > s->dil_h * (s->KH - 1) || s->pad_w > s->dil_w * (s->KW - 1)) return -1;
+  if (axis_has_empty_window(s->H, s->KH, s->stride_h, s->pad_h, s->dil_h, Ho) ||
+      axis_has_empty_window(s->W, s->KW, s->stride_w, s->pad_w, s->dil_w, Wo))
+    return -1;
   if (!x || !w) return -1;
   const int KK = s->KH * s->KW;
   const size_t K = (size_t)s->C_in * KK;

@@ -40,6 +40,20 @@ typedef struct oracle_shape {
 
 enum { ORACLE_MAX = 0, ORACLE_MIN = 1, ORACLE_COMPOUND = 2, ORACLE_PARALLEL = 3 };
 
+/* 1 if some window of one axis has no tap inside the input (written out: every output position, every tap).  The
+ * extremum of Sec. 3.1 over an empty set of taps is not defined, so such a layer is rejected. */
+static int axis_has_empty_window(long in, long k, long stride, long pad, long dil, long out) {
+  for (long o = 0; o < out; ++o) {
+    int hit = 0;
+    for (long t = 0; t < k; ++t) {
+      long i = o * stride - pad + t * dil;
+      if (i >= 0 && i < in) hit = 1;
+    }
+    if (!hit) return 1;
+  }
+  return 0;
+}
+
 static int out_shape(const oracle_shape* s, int32_t* H_out, int32_t* W_out) {
   long eh = (long)s->dil_h * (s->KH - 1) + 1, ew = (long)s->dil_w * (s->KW - 1) + 1;
   long nh = (long)s->H + 2L * s->pad_h - eh, nw = (long)s->W + 2L * s->pad_w - ew;
@@ -48,6 +62,9 @@ static int out_shape(const oracle_shape* s, int32_t* H_out, int32_t* W_out) {
   if (s->C_in < 1 || s->C_out < s->C_in || s->C_out % s->C_in != 0) return -1;
   *H_out = (int32_t)(nh / s->stride_h + 1);
   *W_out = (int32_t)(nw / s->stride_w + 1);
+  if (axis_has_empty_window(s->H, s->KH, s->stride_h, s->pad_h, s->dil_h, *H_out) ||
+      axis_has_empty_window(s->W, s->KW, s->stride_w, s->pad_w, s->dil_w, *W_out))
+    return -1;
   return 0;
 }
 

@@ -44,6 +44,20 @@ typedef struct text_shape {
 
 enum { TEXT_MAX = 0, TEXT_MIN = 1, TEXT_COMPOUND = 2, TEXT_PARALLEL = 3 };
 
+/* 1 if some window of one axis has no tap inside the input (written out: every output position, every tap).  Under
+ * identity padding the extremum of Sec. 3.1 over an empty set of taps is not defined, so such a layer is rejected. */
+static int axis_has_empty_window(long in, long k, long stride, long pad, long dil, long out) {
+  for (long o = 0; o < out; ++o) {
+    int hit = 0;
+    for (long t = 0; t < k; ++t) {
+      long i = o * stride - pad + t * dil;
+      if (i >= 0 && i < in) hit = 1;
+    }
+    if (!hit) return 1;
+  }
+  return 0;
+}
+
 static int out_hw(const text_shape* s, int32_t* Ho, int32_t* Wo) {
   long nh = (long)s->H + 2L * s->pad_h - (long)s->dil_h * (s->KH - 1) - 1;
   long nw = (long)s->W + 2L * s->pad_w - (long)s->dil_w * (s->KW - 1) - 1;
@@ -137,6 +151,9 @@ int text_forward(const text_shape* s, int mode, int pad_zero, const float* x, co
   int32_t Ho, Wo;
   if (out_hw(s, &Ho, &Wo) != 0 || Ho < 1 || Wo < 1) return -1;
   if (!pad_zero && (s->pad_h > s->dil_h * (s->KH - 1) || s->pad_w > s->dil_w * (s->KW - 1))) return -1;
+  if (!pad_zero && (axis_has_empty_window(s->H, s->KH, s->stride_h, s->pad_h, s->dil_h, Ho) ||
+                    axis_has_empty_window(s->W, s->KW, s->stride_w, s->pad_w, s->dil_w, Wo)))
+    return -1;
   const int do_min = (mode != TEXT_MAX), do_max = (mode != TEXT_MIN);
   const float* wmn = w_min;
   const float* wmx = w_max;
@@ -246,6 +263,9 @@ int text_forward_f16(const text_shape* s, int mode, int pad_zero, const uint16_t
   int32_t Ho, Wo;
   if (out_hw(s, &Ho, &Wo) != 0 || Ho < 1 || Wo < 1) return -1;
   if (!pad_zero && (s->pad_h > s->dil_h * (s->KH - 1) || s->pad_w > s->dil_w * (s->KW - 1))) return -1;
+  if (!pad_zero && (axis_has_empty_window(s->H, s->KH, s->stride_h, s->pad_h, s->dil_h, Ho) ||
+                    axis_has_empty_window(s->W, s->KW, s->stride_w, s->pad_w, s->dil_w, Wo)))
+    return -1;
   const int do_min = (mode != TEXT_MAX), do_max = (mode != TEXT_MIN);
   const uint16_t* wk[2] = {w_min, w_max};
   if (mode == TEXT_COMPOUND) wk[0] = wk[1] = (w_min ? w_min : w_max);

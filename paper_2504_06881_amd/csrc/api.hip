@@ -10,6 +10,20 @@ using namespace tconv;
 
 namespace {
 
+// True if some window of one axis has no tap inside the input.  With pad <= dil * (k - 1) and a non-empty output
+// every window's span overlaps the input, and where the input is at least as long as the dilation one of the
+// window's taps then lies inside it.  A shorter input can be straddled: at most one tap of a window can be inside,
+// the one at the window start's residue modulo the dilation, and the residues repeat with period dil / gcd(stride, dil).
+bool axis_has_empty_window(long long in, long long k, long long st, long long pd, long long dl, long long out) {
+  if (k == 1 || in >= dl) return false;
+  long long a = st, b = dl;
+  while (b) { const long long t = a % b; a = b; b = t; }
+  const long long period = dl / a, n = out < period ? out : period;
+  for (long long o = 0; o < n; ++o)
+    if (((o * st - pd) % dl + dl) % dl >= in) return true;
+  return false;
+}
+
 // Validates the descriptor and fills the launch-time view.
 int make_params(const tconv_desc* d, Params* p) {
   if (!d) return TCONV_E_INVAL;
@@ -32,6 +46,10 @@ int make_params(const tconv_desc* d, Params* p) {
   const long long lim = 0x7fffffffLL;
   if (K > lim || (long long)d->N * d->C_in * d->H * d->W > lim ||
       (long long)d->N * d->C_out * Ho * Wo > lim || (long long)d->C_out * K > lim)
+    return TCONV_E_SHAPE;
+  // ... nor may its taps straddle an input shorter than the dilation
+  if (axis_has_empty_window(d->H, d->KH, d->stride_h, d->pad_h, d->dil_h, Ho) ||
+      axis_has_empty_window(d->W, d->KW, d->stride_w, d->pad_w, d->dil_w, Wo))
     return TCONV_E_SHAPE;
   p->N = d->N; p->C_in = d->C_in; p->H = d->H; p->W = d->W;
   p->C_out = d->C_out; p->KH = d->KH; p->KW = d->KW;
@@ -606,6 +624,8 @@ static int make_params3(const tconv3d_desc* d, Params3* p) {
   if (K > lim || (long long)d->N * d->C_in * d->D * d->H * d->W > lim ||
       (long long)d->N * d->C_out * out[0] * out[1] * out[2] > lim || (long long)d->C_out * K > lim)
     return TCONV_E_SHAPE;
+  for (int a = 0; a < 3; ++a)  // the taps of a window must not straddle an input shorter than the dilation either
+    if (axis_has_empty_window(in[a], k[a], st[a], pd[a], dl[a], out[a])) return TCONV_E_SHAPE;
   if (d->dtype != TCONV_F32) return TCONV_E_UNSUPPORTED;
   p->N = d->N; p->C_in = d->C_in; p->D = d->D; p->H = d->H; p->W = d->W;
   p->C_out = d->C_out; p->KD = d->KD; p->KH = d->KH; p->KW = d->KW;
@@ -715,7 +735,7 @@ const char* tconv_status_string(int status) {
   switch (status) {
     case TCONV_OK: return "ok";
     case TCONV_E_INVAL: return "invalid argument (NULL required pointer, non-positive size, bad mode, dtype or op)";
-    case TCONV_E_SHAPE: return "unsupported shape (empty output, padding larger than the dilated kernel extent, or a tensor of 2^31 or more elements)";
+    case TCONV_E_SHAPE: return "unsupported shape (empty output, a window with no tap inside the input, or a tensor of 2^31 or more elements)";
     case TCONV_E_WORKSPACE: return "workspace missing or too small";
     case TCONV_E_UNSUPPORTED: return "no kernel for this request in this build";
     case TCONV_E_LAUNCH: return "HIP kernel launch failed";

@@ -57,6 +57,15 @@ def scratch(nbytes, dev):
     return t
 
 
+def every_window_has_a_tap(size, k, stride, pad, dil):
+    """One axis, written out: every output position has a tap inside the input.  A dilated window can straddle an
+    input shorter than the dilation; such layers have no defined output and the library and the oracles reject them, so
+    the random sweeps leave them out."""
+    n = size + 2 * pad - dil * (k - 1) - 1
+    return n >= 0 and all(any(0 <= o * stride - pad + t * dil < size for t in range(k))
+                          for o in range(n // stride + 1))
+
+
 def run_hip(cfg, inp, backward=True, branch_outputs=True, device="cuda:0", deterministic=True, fused=False,
             x_halfword_offset=False):
     """Forward (+ backward) through the C ABI; returns numpy arrays (bf16 outputs widened to fp32).

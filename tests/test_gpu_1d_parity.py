@@ -121,7 +121,7 @@ def _random_1d_layers(n, seed):
         L = int(rng.integers(1, 300))
         cfg = Layer1dCfg(f"lrnd{len(out)}_k{k}s{s_}d{d}p{pad}_{cin}x{L}_{cout}", int(rng.integers(1, 4)), cin, L, cout,
                          K=k, stride=s_, pad=pad, dil=d, seed=5000 + len(out))
-        if cfg.L_out < 1:
+        if cfg.L_out < 1 or not hs.every_window_has_a_tap(L, k, s_, pad, d):
             continue
         out.append(cfg)
     return out

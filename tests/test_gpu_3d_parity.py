@@ -113,7 +113,7 @@ def _random_3d_layers(n, seed):
         cin, cout = int(rng.integers(1, 8)), int(rng.integers(1, 8))
         cfg = Layer3dCfg(f"vrnd{len(out)}", int(rng.integers(1, 3)), cin, dims[0], dims[1], dims[2], cout, k=k,
                          stride=st, pad=pad, dil=dl, seed=6000 + len(out))
-        if min(cfg.out) < 1:
+        if min(cfg.out) < 1 or not all(hs.every_window_has_a_tap(*a) for a in zip(dims, k, st, pad, dl)):
             continue
         out.append(cfg)
     return out

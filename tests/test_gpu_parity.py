@@ -261,6 +261,8 @@ def _random_windows(n, seed):
         ho, wo = cfg.out_hw
         if ho < 1 or wo < 1:
             continue
+        if not (hs.every_window_has_a_tap(h, kh, s, pad, d) and hs.every_window_has_a_tap(w, kw, s, pad, d)):
+            continue
         out.append(cfg)
     return out
 
