@@ -3,6 +3,8 @@
 The HIP side and the oracle side only meet here, on numpy arrays; both consume the
 same seeded host buffers from ``paper_2504_06881_amd.inputs``.
 """
+import os
+
 import numpy as np
 
 from oracle import tconv_oracle as orc
@@ -55,6 +57,11 @@ def scratch(nbytes, dev):
     t = torch.empty((nbytes + 7) // 8, device=dev, dtype=torch.float64)
     t.fill_(float("nan"))
     return t
+
+
+# The random parity sweeps draw their layers from fixed seeds; TCONV_TEST_SEED_SHIFT=n (an integer) moves every one of
+# them by n, for runs over other layers than the committed ones (pytest -m gpu -k random).
+SEED_SHIFT = int(os.environ.get("TCONV_TEST_SEED_SHIFT", "0"))
 
 
 def every_window_has_a_tap(size, k, stride, pad, dil):

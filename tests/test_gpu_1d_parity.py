@@ -127,7 +127,7 @@ def _random_1d_layers(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_1d_layers(40, 20250614), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_1d_layers(40, 20250614 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_sequences(cfg):
     mode = MODES[cfg.seed % 6]
     ab = "random" if mode in ("compound", "parallel") else None

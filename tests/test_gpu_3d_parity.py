@@ -119,7 +119,7 @@ def _random_3d_layers(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_3d_layers(40, 20250615), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_3d_layers(40, 20250615 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_volumes(cfg):
     mode = MODES[cfg.seed % 6]
     ab = "random" if mode in ("compound", "parallel") else None

@@ -140,7 +140,7 @@ def _random_dw_layers(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_dw_layers(40, 20250613), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_dw_layers(40, 20250613 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_depthwise_layers(cfg):
     mode = MODES[cfg.seed % 4]
     _check(cfg.with_(mode=mode))

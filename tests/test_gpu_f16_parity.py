@@ -105,7 +105,7 @@ def test_f16_error_paths():
     assert e.value.status == -4
 
 
-@pytest.mark.parametrize("cfg", _random_layers(30, 20250612), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_layers(30, 20250612 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_layers(cfg):
     """Random shapes in binary16: the packed kernel where it applies (stride 1, core columns at an even element),
     else the generic kernel; real and integer data."""

@@ -87,7 +87,7 @@ def test_kernel_selection_and_error_paths():
     assert e.value.status == -1
 
 
-@pytest.mark.parametrize("cfg", _random_layers(30, 20250610), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_layers(30, 20250610 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_layers_in_every_form(cfg):
     mode = MIXED[cfg.seed % 2]
     _check(cfg.with_(mode=mode), tn=BOTH_TN)

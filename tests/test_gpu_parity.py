@@ -228,7 +228,7 @@ def _random_layers(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_layers(60, 20250607), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_layers(60, 20250607 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_layers_in_every_form_and_storage(cfg):
     """Random shapes, every form of the tiled kernel forced in turn (2 / 4 output channels per lane, input channels
     split), a random mode each, fp32 and bf16 storage, real and integer (all ties) data."""
@@ -267,7 +267,7 @@ def _random_windows(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_windows(60, 20250609), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_windows(60, 20250609 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_windows(cfg):
     rng = np.random.default_rng(cfg.seed)
     mode = MODES[int(rng.integers(4))]

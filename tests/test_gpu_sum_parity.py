@@ -204,7 +204,7 @@ def _random_sum_layers(n, seed):
     return out
 
 
-@pytest.mark.parametrize("cfg", _random_sum_layers(40, 20250608), ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", _random_sum_layers(40, 20250608 + hs.SEED_SHIFT), ids=lambda c: c.name)
 def test_random_sum_layers(cfg):
     rng = np.random.default_rng(cfg.seed)
     mode = MODES[int(rng.integers(len(MODES)))]
