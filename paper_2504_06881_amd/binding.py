@@ -119,9 +119,9 @@ class Desc:
     @staticmethod
     def from_cfg(cfg, mode: Optional[str] = None, dtype: Optional[str] = None,
                  pad_mode: Optional[str] = None) -> "Desc":
-        """From an inputs.LayerCfg (square stride / pad / dilation)."""
+        """From an inputs.LayerCfg."""
         return Desc(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW,
-                    (cfg.stride, cfg.stride), (cfg.pad, cfg.pad), (cfg.dil, cfg.dil),
+                    tuple(cfg.stride_hw), tuple(cfg.pad_hw), tuple(cfg.dil_hw),
                     mode or cfg.mode, dtype or cfg.dtype, pad_mode or getattr(cfg, "pad_mode", "identity"))
 
 

@@ -37,6 +37,21 @@ class LayerCfg:
     seed: int = 0
     w_range: float = 1.0       # kernels ~ U(-w_range, w_range)
     pad_mode: str = "identity"  # identity (padding never wins) | zero (padding holds zeros)
+    stride_w: Optional[int] = None  # width parameters where they differ from the height's (None: the same)
+    pad_w: Optional[int] = None
+    dil_w: Optional[int] = None
+
+    @property
+    def stride_hw(self):
+        return self.stride, self.stride if self.stride_w is None else self.stride_w
+
+    @property
+    def pad_hw(self):
+        return self.pad, self.pad if self.pad_w is None else self.pad_w
+
+    @property
+    def dil_hw(self):
+        return self.dil, self.dil if self.dil_w is None else self.dil_w
 
     @property
     def K(self) -> int:
@@ -44,8 +59,9 @@ class LayerCfg:
 
     @property
     def out_hw(self):
-        ho = (self.H + 2 * self.pad - self.dil * (self.KH - 1) - 1) // self.stride + 1
-        wo = (self.W + 2 * self.pad - self.dil * (self.KW - 1) - 1) // self.stride + 1
+        (sh, sw), (ph, pw), (dh, dw) = self.stride_hw, self.pad_hw, self.dil_hw
+        ho = (self.H + 2 * ph - dh * (self.KH - 1) - 1) // sh + 1
+        wo = (self.W + 2 * pw - dw * (self.KW - 1) - 1) // sw + 1
         return ho, wo
 
     @property

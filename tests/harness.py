@@ -17,7 +17,8 @@ MIXED = {"minplus_max": "min", "maxplus_min": "max"}   # mixed layer -> the side
 
 
 def oracle_shape(cfg):
-    return orc.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil)
+    return orc.Shape(cfg.N, cfg.C_in, cfg.H, cfg.W, cfg.C_out, cfg.KH, cfg.KW, cfg.stride, cfg.pad, cfg.dil,
+                     stride_w=cfg.stride_hw[1], pad_w=cfg.pad_hw[1], dil_w=cfg.dil_hw[1])
 
 
 def run_oracle(cfg, inp, backward=True):

@@ -276,6 +276,42 @@ def test_random_windows(cfg):
     _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)
 
 
+def _random_axes(n, seed):
+    """Seeded random layers whose height and width parameters differ: window, stride, padding and dilation are drawn
+    per axis (the descriptor carries them per axis; the named shapes and the other sweeps are all square)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, dh * (kh - 1) + 1)), int(rng.integers(0, dw * (kw - 1) + 1))
+        cin, cout = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        h, w = int(rng.integers(1, 30)), int(rng.integers(1, 40))
+        nimg = int(rng.integers(1, 4))
+        cfg = LayerCfg(f"arnd{len(out)}_{kh}x{kw}s{sh}{sw}d{dh}{dw}p{ph}{pw}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w,
+                       cout, KH=kh, KW=kw, stride=sh, pad=ph, dil=dh, stride_w=sw, pad_w=pw, dil_w=dw,
+                       seed=7000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1:
+            continue
+        if not (hs.every_window_has_a_tap(h, kh, sh, ph, dh) and hs.every_window_has_a_tap(w, kw, sw, pw, dw)):
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_axes(60, 20250616 + hs.SEED_SHIFT), ids=lambda c: c.name)
+def test_random_layers_with_their_own_parameters_per_axis(cfg):
+    rng = np.random.default_rng(cfg.seed)
+    mode = MODES[int(rng.integers(len(MODES)))]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)
+    if cfg.seed % 3 == 0:
+        _check(cfg.with_(mode=mode, dtype="bf16"), alpha_beta=ab)
+
+
 @pytest.mark.parametrize("cfg", [RAGGED[0], RAGGED[2], RAGGED[4], RAGGED[10], RAGGED[13], RAGGED[15], RAGGED[20],
                                  RAGGED[23], RAGGED_LARGE[0], RAGGED_LARGE[1], RAGGED_SPLIT[0]], ids=lambda c: c.name)
 def test_parameter_gradients_in_one_call(cfg):
