@@ -211,6 +211,39 @@ def test_random_sum_layers(cfg):
     _check(cfg.with_(mode=mode))
     _check(cfg.with_(mode="compound"), integer=True)
 
+def _random_sum_axes(n, seed):
+    """Seeded random Sum-channel layers whose window, stride, padding and dilation are drawn per axis (every other shape of
+    this file has the same parameters along height and width)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        kh, kw = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        if len(out) % 2:
+            kh = kw = 3  # the 3x3 kernels of this family, with parameters that differ per axis
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, dh * (kh - 1) + 1)), int(rng.integers(0, dw * (kw - 1) + 1))
+        cin, cout = int(rng.integers(1, 7)), int(rng.integers(1, 19))
+        h, w = int(rng.integers(1, 40)), int(rng.integers(1, 48))
+        nimg = int(rng.integers(1, 6))
+        cfg = LayerCfg(f"sarnd{len(out)}_{kh}x{kw}s{sh}{sw}d{dh}{dw}p{ph}{pw}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w,
+                       cout, KH=kh, KW=kw, stride=sh, pad=ph, dil=dh, stride_w=sw, pad_w=pw, dil_w=dw,
+                       seed=8000 + len(out))
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1:
+            continue
+        if not (hs.every_window_has_a_tap(h, kh, sh, ph, dh) and hs.every_window_has_a_tap(w, kw, sw, pw, dw)):
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_sum_axes(40, 20250617 + hs.SEED_SHIFT), ids=lambda c: c.name)
+def test_random_sum_layers_with_their_own_parameters_per_axis(cfg):
+    mode = MODES[cfg.seed % 4]
+    _check(cfg.with_(mode=mode))
+    _check(cfg.with_(mode=mode), integer=True)
+
 
 def test_sum_input_gradient_is_the_same_on_every_run():
     """The adjacent-outputs backward kernel adds into slots no other thread touches and gathers them in a fixed order:
