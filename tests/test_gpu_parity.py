@@ -276,6 +276,38 @@ def test_random_windows(cfg):
     _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)
 
 
+def _random_medium(n, seed):
+    """Seeded random layers of middle size (up to 3e8 candidates, a second of oracle time): many workgroups, batches
+    that the backward kernels slice, channel counts up to 200, windows 1x1 to 5x5."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        k = int(rng.choice([3, 3, 3, 1, 5, 2]))
+        s, d = int(rng.choice([1, 1, 2])), int(rng.choice([1, 1, 2]))
+        pad = int(rng.integers(0, d * (k - 1) + 1)) if k > 1 else 0
+        cin = int(rng.choice([3, 16, 32, 48, 64, 96, 128, 200]))
+        cout = int(rng.choice([8, 16, 32, 64, 100, 128]))
+        h, w = int(rng.integers(8, 72)), int(rng.integers(8, 72))
+        nimg = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        cfg = LayerCfg(f"mrnd{len(out)}_{k}x{k}s{s}d{d}p{pad}_{nimg}x{cin}x{h}x{w}_{cout}", nimg, cin, h, w, cout, KH=k, KW=k,
+                       stride=s, pad=pad, dil=d, seed=7500 + len(out), w_range=0.2)
+        ho, wo = cfg.out_hw
+        if ho < 1 or wo < 1 or cfg.candidates > 3e8:
+            continue
+        if not (hs.every_window_has_a_tap(h, k, s, pad, d) and hs.every_window_has_a_tap(w, k, s, pad, d)):
+            continue
+        out.append(cfg)
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_medium(12, 20250619 + hs.SEED_SHIFT), ids=lambda c: c.name)
+def test_random_layers_of_middle_size(cfg):
+    mode = MODES[cfg.seed % 4]
+    ab = "random" if mode in ("compound", "parallel") else None
+    _check(cfg.with_(mode=mode), alpha_beta=ab)
+    _check(cfg.with_(mode=mode), alpha_beta=ab, integer=True)
+
+
 def _random_axes(n, seed):
     """Seeded random layers whose height and width parameters differ: window, stride, padding and dilation are drawn
     per axis (the descriptor carries them per axis; the named shapes and the other sweeps are all square)."""
